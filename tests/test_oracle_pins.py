@@ -1,0 +1,383 @@
+"""Pins for the CPU oracle: closed forms, brute force, invariants, library routines.
+
+None of these touch the GPU.  The brute-force functions below are literal Python
+transcriptions of the definitions, written separately from the oracle's C++ loops.
+"""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import oracle
+from paper_1912_04050_amd import workloads as wl
+
+DTYPES = [np.int32, np.int64, np.float64]
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ---------------------------------------------------------------------------
+# brute force (pure Python, curves of at most 64 points)
+# ---------------------------------------------------------------------------
+
+def bf_conv(f, g):
+    n = len(f)
+    return [min(f[s] + g[t - s] for s in range(t + 1)) for t in range(n)]
+
+
+def bf_deconv(f, g):
+    n = len(f)
+    return [max(f[t + u] - g[u] for u in range(n - t)) for t in range(n)]
+
+
+def bf_pinv_lower(f, x):
+    ks = [k for k in range(len(f)) if f[k] >= x]
+    return min(ks) if ks else len(f)
+
+
+def bf_pinv_upper(f, x):
+    ks = [k for k in range(len(f)) if f[k] <= x]
+    return max(ks) if ks else -1
+
+
+def _curve(rng, n, dtype, lo=0, hi=9, start_hi=5):
+    if np.dtype(dtype) == np.float64:
+        inc = rng.random(n) * hi
+        inc[0] = rng.random() * start_hi
+        return np.cumsum(inc)
+    inc = rng.integers(lo, hi + 1, n)
+    inc[0] = rng.integers(0, start_hi + 1)
+    return np.cumsum(inc).astype(dtype)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_conv_deconv_brute_force_all_sizes_to_64(dtype):
+    rng = np.random.default_rng(11)
+    for n in range(1, 65):
+        f = _curve(rng, n, dtype)
+        g = _curve(rng, n, dtype)
+        want_c = np.array(bf_conv(f.tolist(), g.tolist()), dtype)
+        want_d = np.array(bf_deconv(f.tolist(), g.tolist()), dtype)
+        assert np.array_equal(oracle.minplus_conv(f, g)[0], want_c), n
+        assert np.array_equal(oracle.maxplus_deconv(f, g)[0], want_d), n
+
+
+@pytest.mark.parametrize("dtype", [np.int32, np.int64])
+def test_conv_deconv_brute_force_not_monotone_and_negative(dtype):
+    rng = np.random.default_rng(12)
+    for n in (1, 2, 3, 17, 40, 64):
+        f = rng.integers(-1000, 1000, n).astype(dtype)
+        g = rng.integers(-1000, 1000, n).astype(dtype)
+        assert oracle.minplus_conv(f, g)[0].tolist() == bf_conv(f.tolist(), g.tolist())
+        assert oracle.maxplus_deconv(f, g)[0].tolist() == bf_deconv(f.tolist(), g.tolist())
+
+
+def test_conv_near_overflow_limit():
+    n = 33
+    top = np.iinfo(np.int32).max
+    f = (np.arange(n) * 3 + (top // 2 - 3 * n)).astype(np.int32)
+    g = (np.arange(n) * 5 + (top // 2 - 5 * n)).astype(np.int32)
+    assert int(f[-1]) + int(g[-1]) <= top
+    assert oracle.minplus_conv(f, g)[0].tolist() == bf_conv(f.tolist(), g.tolist())
+    top = np.iinfo(np.int64).max
+    f = (np.arange(n) * 3 + (top // 2 - 3 * n)).astype(np.int64)
+    g = (np.arange(n) * 5 + (top // 2 - 5 * n)).astype(np.int64)
+    assert oracle.minplus_conv(f, g)[0].tolist() == bf_conv(f.tolist(), g.tolist())
+
+
+def test_constant_and_plateau_curves():
+    f = np.full(20, 7, np.int32)
+    g = np.array([0] * 5 + [4] * 10 + [9] * 5, np.int32)
+    assert oracle.minplus_conv(f, g)[0].tolist() == bf_conv(f.tolist(), g.tolist())
+    assert oracle.maxplus_deconv(g, f)[0].tolist() == bf_deconv(g.tolist(), f.tolist())
+
+
+def test_batched_and_broadcast_rows():
+    rng = np.random.default_rng(13)
+    f = np.stack([_curve(rng, 30, np.int64) for _ in range(4)])
+    g = _curve(rng, 30, np.int64)
+    got = oracle.minplus_conv(f, g)
+    for b in range(4):
+        assert got[b].tolist() == bf_conv(f[b].tolist(), g.tolist())
+    got = oracle.maxplus_deconv(g, f)
+    for b in range(4):
+        assert got[b].tolist() == bf_deconv(g.tolist(), f[b].tolist())
+
+
+# ---------------------------------------------------------------------------
+# hand-worked example stored as a fixture
+# ---------------------------------------------------------------------------
+
+def _read_golden(name):
+    rows = {}
+    with open(os.path.join(GOLDEN, name)) as fh:
+        for line in fh:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            key, vals = line.split(":")
+            rows[key.strip()] = [int(v) for v in vals.split()]
+    return rows
+
+
+def test_hand_worked_example():
+    ex = _read_golden("hand_worked_small.txt")
+    f = np.array(ex["f"], np.int32)
+    g = np.array(ex["g"], np.int32)
+    assert oracle.minplus_conv(f, g)[0].tolist() == ex["conv"]
+    assert oracle.maxplus_deconv(f, g)[0].tolist() == ex["deconv"]
+    x = np.array(ex["x"], np.int32)
+    assert oracle.pseudo_inverse(f, x, 0)[0].tolist() == ex["pinv_lower_f"]
+    assert oracle.pseudo_inverse(f, x, 1)[0].tolist() == ex["pinv_upper_f"]
+
+
+# ---------------------------------------------------------------------------
+# closed forms: token bucket alpha = b + r*D against rate latency beta = R*(D-T)^+
+# ---------------------------------------------------------------------------
+
+PARAMS = [(5, 2, 3, 10), (0, 1, 1, 0), (17, 3, 3, 25), (9, 1, 4, 7)]
+
+
+@pytest.mark.parametrize("b,r,R,T", PARAMS)
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_closed_form_conv(b, r, R, T, dtype):
+    n = 200
+    t = np.arange(n)
+    alpha = wl.token_bucket(n, b, r, dtype)
+    beta = wl.rate_latency(n, R, T, dtype)
+    want = (b + r * np.maximum(0, t - T)).astype(dtype)
+    assert np.array_equal(oracle.minplus_conv(alpha, beta)[0], want)
+    # left-continuous convention alpha[0] = 0
+    alpha0 = wl.token_bucket(n, b, r, dtype, at_zero=False)
+    want0 = np.minimum(want, beta)
+    assert np.array_equal(oracle.minplus_conv(alpha0, beta)[0], want0)
+
+
+@pytest.mark.parametrize("b,r,R,T", PARAMS)
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_closed_form_deconv_backlog_delay(b, r, R, T, dtype):
+    n = 200
+    t = np.arange(n)
+    alpha = wl.token_bucket(n, b, r, dtype)
+    beta = wl.rate_latency(n, R, T, dtype)
+    got = oracle.maxplus_deconv(alpha, beta)[0]
+    head = t <= n - 1 - T
+    assert np.array_equal(got[head], (b + r * (t + T)).astype(dtype)[head])
+    assert np.all(got[~head] == alpha[-1])
+    # backlog bound = vertical deviation = (alpha (/) beta)[0] = b + r*T
+    assert oracle.max_vdev(alpha, beta)[0] == b + r * T == got[0]
+    # delay bound = horizontal deviation = T + ceil(b / R)
+    h, flags = oracle.max_hdev(alpha, beta)
+    if r < R:
+        assert flags == 0
+        assert h[0] == T + -(-b // R)
+    else:
+        # equal rates: the curves never meet again inside a finite horizon for b > 0
+        assert (flags == 0) == (b == 0)
+
+
+def test_hdev_unbounded_flag_and_value():
+    n = 50
+    alpha = np.full(n, 100, np.int32)
+    beta = np.arange(n, dtype=np.int32)
+    h, flags = oracle.max_hdev(alpha, beta)
+    assert flags == 4 and h[0] == n  # term at D = 0 is n - 0
+
+
+# ---------------------------------------------------------------------------
+# invariants
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", [np.int32, np.int64])
+def test_conv_commutative_associative_monotone(dtype):
+    rng = np.random.default_rng(21)
+    for n in (1, 7, 64, 150):
+        f, g, h = (_curve(rng, n, dtype) for _ in range(3))
+        fg = oracle.minplus_conv(f, g)[0]
+        assert np.array_equal(fg, oracle.minplus_conv(g, f)[0])
+        assert np.all(np.diff(fg) >= 0)
+        left = oracle.minplus_conv(fg, h)[0]
+        right = oracle.minplus_conv(f, oracle.minplus_conv(g, h)[0])[0]
+        assert np.array_equal(left, right)
+
+
+def test_conv_commutative_float_exact():
+    rng = np.random.default_rng(22)
+    f = _curve(rng, 120, np.float64)
+    g = _curve(rng, 120, np.float64)
+    assert np.array_equal(oracle.minplus_conv(f, g)[0], oracle.minplus_conv(g, f)[0])
+
+
+@pytest.mark.parametrize("dtype", [np.int32, np.int64])
+def test_conv_identity_and_zero_curve(dtype):
+    rng = np.random.default_rng(23)
+    n = 90
+    f = _curve(rng, n, dtype)
+    big = np.iinfo(dtype).max - int(f[-1])
+    delta = np.full(n, big, dtype)
+    delta[0] = 0
+    assert np.array_equal(oracle.minplus_conv(f, delta)[0], f)
+    assert np.array_equal(oracle.minplus_conv(delta, f)[0], f)
+    zero = np.zeros(n, dtype)
+    # with the all-zero curve the result is the running minimum, i.e. f[0] for nondecreasing f
+    assert np.all(oracle.minplus_conv(f, zero)[0] == f[0])
+    wild = rng.integers(-50, 50, n).astype(dtype)
+    assert np.array_equal(oracle.minplus_conv(wild, zero)[0], np.minimum.accumulate(wild))
+
+
+@pytest.mark.parametrize("dtype", [np.int32, np.int64])
+def test_deconv_duality(dtype):
+    rng = np.random.default_rng(24)
+    n = 100
+    f = _curve(rng, n, dtype)
+    g = _curve(rng, n, dtype)
+    d = oracle.maxplus_deconv(f, g)[0]
+    assert d[0] >= f[0] - g[0]
+    assert d[0] == np.max(f - g)
+    back = oracle.minplus_conv(d, g)[0]
+    assert np.all(f <= back)
+
+
+def test_conv_of_convex_curves_merges_sorted_increments():
+    rng = np.random.default_rng(25)
+    n = 300
+    fi = np.sort(rng.integers(0, 40, n - 1))
+    gi = np.sort(rng.integers(0, 40, n - 1))
+    f = np.concatenate([[3], 3 + np.cumsum(fi)]).astype(np.int64)
+    g = np.concatenate([[5], 5 + np.cumsum(gi)]).astype(np.int64)
+    merged = np.sort(np.concatenate([fi, gi]))[: n - 1]
+    want = np.concatenate([[8], 8 + np.cumsum(merged)])
+    assert np.array_equal(oracle.minplus_conv(f, g)[0], want)
+
+
+def test_conv_of_concave_curves_through_origin_is_pointwise_min():
+    rng = np.random.default_rng(26)
+    n = 300
+    fi = np.sort(rng.integers(0, 40, n - 1))[::-1]
+    gi = np.sort(rng.integers(0, 40, n - 1))[::-1]
+    f = np.concatenate([[0], np.cumsum(fi)]).astype(np.int32)
+    g = np.concatenate([[0], np.cumsum(gi)]).astype(np.int32)
+    assert np.array_equal(oracle.minplus_conv(f, g)[0], np.minimum(f, g))
+
+
+# ---------------------------------------------------------------------------
+# pseudo-inverse
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_pinv_matches_searchsorted_and_brute_force(dtype):
+    rng = np.random.default_rng(31)
+    for n in (1, 2, 5, 64, 333):
+        f = _curve(rng, n, dtype, hi=3)  # many plateaus for the integer types
+        if np.dtype(dtype) == np.float64:
+            x = np.concatenate([f, f + 0.25, [-1.0, f[-1] + 10]])
+        else:
+            x = np.arange(int(f[0]) - 2, int(f[-1]) + 3).astype(dtype)
+        lo = oracle.pseudo_inverse(f, x, 0)[0]
+        up = oracle.pseudo_inverse(f, x, 1)[0]
+        assert np.array_equal(lo, np.searchsorted(f, x, side="left"))
+        assert np.array_equal(up, np.searchsorted(f, x, side="right") - 1)
+        if n <= 64:
+            assert lo.tolist() == [bf_pinv_lower(f.tolist(), v) for v in x.tolist()]
+            assert up.tolist() == [bf_pinv_upper(f.tolist(), v) for v in x.tolist()]
+
+
+def test_pinv_inequalities():
+    rng = np.random.default_rng(32)
+    n = 400
+    f = _curve(rng, n, np.int64, hi=4)
+    x = np.arange(int(f[0]), int(f[-1]) + 1).astype(np.int64)
+    lo = oracle.pseudo_inverse(f, x, 0)[0]
+    up = oracle.pseudo_inverse(f, x, 1)[0]
+    assert np.all(f[lo] >= x)        # gamma(gamma^-1(x)) >= x, lower inverse
+    assert np.all(f[up] <= x)        # and <= x for the upper inverse
+    k = np.arange(n)
+    assert np.all(oracle.pseudo_inverse(f, f, 0)[0] <= k)
+    assert np.all(oracle.pseudo_inverse(f, f, 1)[0] >= k)
+    # plateau: lower returns its first index, upper its last
+    p = np.array([0, 2, 2, 2, 5], np.int32)
+    assert oracle.pseudo_inverse(p, np.array([2], np.int32), 0)[0, 0] == 1
+    assert oracle.pseudo_inverse(p, np.array([2], np.int32), 1)[0, 0] == 3
+    assert oracle.pseudo_inverse(p, np.array([6], np.int32), 0)[0, 0] == 5
+    assert oracle.pseudo_inverse(p, np.array([-1], np.int32), 1)[0, 0] == -1
+
+
+# ---------------------------------------------------------------------------
+# composition
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_compose_identities_and_clamp(dtype):
+    rng = np.random.default_rng(41)
+    n = 77
+    gamma = _curve(rng, n, dtype)
+    ramp = np.arange(n, dtype=np.int32)
+    out, fl = oracle.compose(gamma, ramp)
+    assert fl == 0 and np.array_equal(out[0], gamma)
+    inner = rng.integers(0, n, 200).astype(np.int32)
+    out, fl = oracle.compose(np.arange(n).astype(dtype), inner)
+    assert fl == 0 and np.array_equal(out[0], inner.astype(dtype))
+    out, fl = oracle.compose(gamma, inner)
+    assert np.array_equal(out[0], gamma[inner])
+    bad = np.array([-3, 0, n - 1, n, n + 5], np.int32)
+    out, fl = oracle.compose(gamma, bad)
+    assert fl == 2 and np.array_equal(out[0], gamma[[0, 0, n - 1, n - 1, n - 1]])
+
+
+# ---------------------------------------------------------------------------
+# greedy processing component
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("b,r,R,T", [(5, 2, 3, 10), (17, 3, 3, 25), (9, 1, 4, 7)])
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_gpc_closed_forms(b, r, R, T, dtype):
+    n = 200
+    d = np.arange(n)
+    head = d <= n - 1 - T
+    alpha = wl.token_bucket(n, b, r, dtype)
+    beta_l = wl.rate_latency(n, R, T, dtype)
+    want_bl = np.maximum(0, (R - r) * d - R * T - b).astype(dtype)
+    # pure-rate upper service curve
+    Ru = R + 2
+    beta_u = (Ru * d).astype(dtype)
+    au, bl = oracle.gpc_step(alpha, beta_u, beta_l)
+    assert np.array_equal(au[0][head], np.minimum(b + r * (d + T), Ru * d).astype(dtype)[head])
+    assert np.array_equal(bl[0], want_bl)
+    # upper service curve equal to the lower one
+    au, bl = oracle.gpc_step(alpha, beta_l, beta_l)
+    assert np.array_equal(au[0][head], np.minimum(b + r * d, beta_l)[head])
+    assert np.array_equal(bl[0], want_bl)
+
+
+def test_gpc_from_parts_and_invariants():
+    rng = np.random.default_rng(51)
+    n = 180
+    for _ in range(4):
+        a = _curve(rng, n, np.int64, hi=6)
+        bu = _curve(rng, n, np.int64, hi=12, start_hi=0)
+        bl = np.minimum(bu, _curve(rng, n, np.int64, hi=8, start_hi=0))
+        au, blo = oracle.gpc_step(a, bu, bl)
+        c = np.array(bf_conv(a.tolist(), bu.tolist())) if n <= 64 else oracle.minplus_conv(a, bu)[0]
+        dd = oracle.maxplus_deconv(c, bl)[0]
+        assert np.array_equal(au[0], np.minimum(dd, bu))
+        assert np.array_equal(blo[0], np.maximum(0, np.maximum.accumulate(bl - a)))
+        assert np.all(au[0] <= bu)
+        assert np.all(np.diff(blo[0]) >= 0) and np.all(blo[0] >= 0)
+        assert np.all(blo[0] <= bl)
+
+
+def test_gpc_brute_force_small():
+    rng = np.random.default_rng(52)
+    for n in (1, 2, 9, 48):
+        a = _curve(rng, n, np.int32)
+        bu = _curve(rng, n, np.int32, hi=12)
+        bl = _curve(rng, n, np.int32, hi=8)
+        au, blo = oracle.gpc_step(a, bu, bl)
+        c = bf_conv(a.tolist(), bu.tolist())
+        dd = bf_deconv(c, bl.tolist())
+        assert au[0].tolist() == [min(x, y) for x, y in zip(dd, bu.tolist())]
+        run, want = None, []
+        for k in range(n):
+            v = int(bl[k]) - int(a[k])
+            run = v if run is None else max(run, v)
+            want.append(max(run, 0))
+        assert blo[0].tolist() == want
