@@ -1,0 +1,151 @@
+/* librtc -- (min,+) curve algebra of real-time calculus on AMD MI355X (gfx950).
+ *
+ * Curves are the sampled nondecreasing functions over Delta = 0..n-1 that the paper's
+ * notation preamble names: arrival curves alpha^u / alpha^l, service curves beta^u /
+ * beta^l, workload curves gamma^u / gamma^l and their pseudo-inverses (the curve macros
+ * of the preamble).  The paper only supplies the symbols; each entry point below states
+ * the textbook definition it evaluates.
+ *
+ * Conventions common to every call
+ *   - All data pointers are DEVICE pointers (HBM).  The caller owns every buffer; the
+ *     library never allocates, frees or retains device memory.
+ *   - A batch is `batch` independent rows; a row is `n` contiguous samples.  Where a
+ *     stride is given it is in ELEMENTS and is either 0 (one curve shared by all rows)
+ *     or >= n.  Outputs are always dense [batch][n].
+ *   - `hip_stream` is a hipStream_t passed as void*.  Every call only enqueues work on
+ *     that stream and returns; there is no internal synchronisation.
+ *   - Outputs must not alias inputs or the workspace.
+ *   - Return value: RTC_OK, or a negative rtc_status.  On a negative status nothing was
+ *     launched.  Data-dependent conditions are not errors: they set bits in the optional
+ *     caller-provided device word `dev_flags` (never cleared by the library).
+ *   - Integer arithmetic must not overflow: the caller guarantees that every candidate
+ *     f[s]+g[t-s] (convolution) or f[t+u]-g[u] (deconvolution) fits the element type.
+ *     With `dev_flags` non-NULL the library checks max+max / min-min style bounds of
+ *     the two rows and sets RTC_FLAG_OVERFLOW when they do not prove it.
+ *   - fp64 inputs must be finite and must not contain -0.0; results are then bit-exact
+ *     (each candidate is a single rounded add or subtract, selection is exact).
+ */
+#ifndef RTC_H
+#define RTC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { RTC_I32 = 0, RTC_I64 = 1, RTC_F64 = 2 } rtc_dtype;
+typedef enum { RTC_INV_LOWER = 0, RTC_INV_UPPER = 1 } rtc_inv_mode;
+typedef enum { RTC_OP_CONV = 0, RTC_OP_DECONV = 1, RTC_OP_GPC = 2 } rtc_op;
+
+typedef enum {
+  RTC_OK = 0,
+  RTC_ERR_NULL = -1,      /* a required pointer is NULL */
+  RTC_ERR_SHAPE = -2,     /* batch < 1, n < 1, n > RTC_MAX_N, or the launch would exceed grid limits */
+  RTC_ERR_DTYPE = -3,     /* unknown rtc_dtype */
+  RTC_ERR_ALIGN = -4,     /* a pointer is not aligned to its element size */
+  RTC_ERR_STRIDE = -5,    /* a stride is neither 0 nor >= n */
+  RTC_ERR_WORKSPACE = -6, /* workspace missing or smaller than rtc_workspace_bytes() */
+  RTC_ERR_HIP = -7,       /* the HIP runtime reported an error while enqueueing */
+  RTC_ERR_MODE = -8       /* unknown rtc_inv_mode / rtc_op */
+} rtc_status;
+
+#define RTC_MAX_N (1 << 24)
+
+#define RTC_FLAG_OVERFLOW 1  /* integer range precondition not provable from the rows' min/max */
+#define RTC_FLAG_DOMAIN 2    /* rtc_compose: an index was outside [0, n_outer-1] and was clamped */
+#define RTC_FLAG_UNBOUNDED 4 /* rtc_max_hdev: some alpha[D] is never reached by beta within the horizon */
+
+/* Min-plus convolution, out[b][t] = min_{0<=s<=t} f[b][s] + g[b][t-s], t = 0..n-1.
+ * Truncated horizon: samples beyond n-1 do not exist, the output has n samples.
+ * f, g: [batch] rows with element strides stride_f / stride_g.  out: [batch][n].
+ * ws / ws_bytes: device scratch of at least rtc_workspace_bytes(RTC_OP_CONV, ...) bytes.
+ *   RTC_I32 / RTC_F64 need it only when dev_flags != NULL (range probe); RTC_I64 always
+ *   (the rows are probed and, when every value lies in [-2^30, 2^30), convolved in 32-bit
+ *   arithmetic on narrowed copies -- exact, because every candidate then fits -- and widened
+ *   on store; other rows take the 64-bit kernel).
+ * Exact: there is one correct bit pattern per output (values only, no argmin). */
+int rtc_minplus_conv(const void* f, const void* g, void* out, int64_t batch, int64_t n,
+                     int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* ws, size_t ws_bytes,
+                     int32_t* dev_flags, void* hip_stream);
+
+/* Max-plus deconvolution on the finite horizon,
+ * out[b][t] = max_{0<=u<=n-1-t} f[b][t+u] - g[b][u]: only pairs whose two samples exist.
+ * (This under-approximates the infinite-horizon supremum near the end of the horizon.)
+ * Arguments as for rtc_minplus_conv; results may be negative. */
+int rtc_maxplus_deconv(const void* f, const void* g, void* out, int64_t batch, int64_t n,
+                       int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* ws, size_t ws_bytes,
+                       int32_t* dev_flags, void* hip_stream);
+
+/* Pseudo-inverse of a nondecreasing sampled curve (e.g. gamma^{u-1}), per query x[b][j]:
+ *   RTC_INV_LOWER: min{k in [0,n) : f[b][k] >= x}, or n when there is none; a plateau
+ *                  returns its first index; f[inv(x)] >= x holds whenever inv(x) < n.
+ *   RTC_INV_UPPER: max{k in [0,n) : f[b][k] <= x}, or -1 when there is none; a plateau
+ *                  returns its last index; f[inv(x)] <= x holds whenever inv(x) >= 0.
+ * f: [batch][n] (must be nondecreasing, unchecked), x: [batch][m] of the same dtype,
+ * out_idx: int32 [batch][m]. */
+int rtc_pseudo_inverse(const void* f, int64_t n, const void* x, int64_t m, int32_t* out_idx,
+                       int64_t batch, rtc_inv_mode mode, rtc_dtype dt, void* hip_stream);
+
+/* Composition of a workload curve with an event-count curve,
+ * out[b][D] = outer[b][ clamp(inner[b][D], 0, n_outer-1) ]  (e.g. gamma^u o alpha-bar^u).
+ * outer: [batch][n_outer] of dtype dt, inner: int32 [batch][n], out: [batch][n] of dtype dt.
+ * A clamped index sets RTC_FLAG_DOMAIN in dev_flags (optional). */
+int rtc_compose(const void* outer, int64_t n_outer, const int32_t* inner, int64_t n, void* out,
+                int64_t batch, rtc_dtype dt, int32_t* dev_flags, void* hip_stream);
+
+/* One greedy processing component, upper-arrival / lower-service outputs, per row:
+ *   alpha_u_out = min( (alpha_u (x) beta_u) (/) beta_l , beta_u )
+ *   beta_l_out[D] = max(0, max_{l<=D} beta_l[l] - alpha_u[l])
+ * and, when gamma_u is given, the event-domain images of beta_l_out,
+ *   events_lower / events_upper = lower / upper pseudo-inverse of gamma_u at beta_l_out.
+ * All curve pointers are dense [batch][n] of dtype dt (gamma_u: [batch][n_gamma]).
+ * Optional members may be NULL.  ws needs rtc_workspace_bytes(RTC_OP_GPC, ...). */
+typedef struct rtc_gpc_args {
+  const void* alpha_u;
+  const void* beta_u;
+  const void* beta_l;
+  void* alpha_u_out;
+  void* beta_l_out;
+  const void* gamma_u;    /* optional */
+  int64_t n_gamma;
+  int32_t* events_lower;  /* optional, int32 [batch][n], needs gamma_u */
+  int32_t* events_upper;  /* optional, int32 [batch][n], needs gamma_u */
+  int64_t batch;
+  int64_t n;
+  rtc_dtype dt;
+  void* ws;
+  size_t ws_bytes;
+  int32_t* dev_flags;     /* optional */
+} rtc_gpc_args;
+
+int rtc_gpc_step(const rtc_gpc_args* a, void* hip_stream);
+
+/* Delay bound: maximal horizontal deviation per row,
+ *   out[b] = max_D max(0, min{k : beta[b][k] >= alpha[b][D]} - D);
+ * an alpha[D] that beta never reaches inside the horizon contributes n - D and sets
+ * RTC_FLAG_UNBOUNDED.  alpha, beta: [batch][n] nondecreasing; out: int32 [batch]. */
+int rtc_max_hdev(const void* alpha, const void* beta, int32_t* out, int64_t batch, int64_t n,
+                 rtc_dtype dt, int32_t* dev_flags, void* hip_stream);
+
+/* Backlog bound: maximal vertical deviation per row, out[b] = max_D alpha[b][D] - beta[b][D]
+ * (equal to (alpha (/) beta)[0]).  out: [batch] of dtype dt. */
+int rtc_max_vdev(const void* alpha, const void* beta, void* out, int64_t batch, int64_t n,
+                 rtc_dtype dt, void* hip_stream);
+
+/* Bytes of device workspace an operator needs for the given shape (0 on invalid input). */
+size_t rtc_workspace_bytes(int op, int64_t batch, int64_t n, rtc_dtype dt);
+
+/* Static description of a status code. */
+const char* rtc_strerror(int status);
+
+/* Properties of the current HIP device that the VALU roofline is derived from:
+ * compute-unit count, nominal engine clock in kHz, LDS bytes per workgroup.
+ * Any pointer may be NULL.  Host pointers. */
+int rtc_device_info(int* cu_count, int* clock_khz, int* lds_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RTC_H */

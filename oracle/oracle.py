@@ -79,6 +79,19 @@ def maxplus_deconv(f, g):
     return _binary("oracle_maxplus_deconv", f, g)
 
 
+def product_at(f, g, t_idx, deconv: bool):
+    """Selected outputs of f (x) g (deconv=False) or f (/) g (deconv=True) for one row pair."""
+    f = np.ascontiguousarray(f).reshape(-1)
+    g = np.ascontiguousarray(g).reshape(-1)
+    assert f.dtype == g.dtype and f.shape == g.shape
+    t_idx = np.ascontiguousarray(t_idx, dtype=np.int64)
+    out = np.empty(t_idx.shape, f.dtype)
+    rc = lib().oracle_product_at(_p(f), _p(g), ctypes.c_int64(f.size), _p(t_idx), ctypes.c_int64(t_idx.size),
+                                 _p(out), ctypes.c_int(1 if deconv else 0), ctypes.c_int(_DT[f.dtype]))
+    assert rc == 0, rc
+    return out
+
+
 def pseudo_inverse(f, x, mode: int = 0):
     f = _rows(f)
     x = _rows(np.asarray(x, dtype=f.dtype))

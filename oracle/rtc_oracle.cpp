@@ -62,6 +62,31 @@ void deconv_one(const T* f, const T* g, T* out, int64_t n) {
   }
 }
 
+// Single outputs of the two products, for spot checks of large problems: the same loop
+// as one iteration of conv_one / deconv_one.
+template <typename T>
+void product_at(const T* f, const T* g, int64_t n, const int64_t* t_idx, int64_t m, T* out, bool deconv) {
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t j = 0; j < m; ++j) {
+    const int64_t t = t_idx[j];
+    T r;
+    if (!deconv) {
+      r = f[0] + g[t];
+      for (int64_t s = 1; s <= t; ++s) {
+        T v = f[s] + g[t - s];
+        if (v < r) r = v;
+      }
+    } else {
+      r = f[t] - g[0];
+      for (int64_t u = 1; u <= n - 1 - t; ++u) {
+        T v = f[t + u] - g[u];
+        if (v > r) r = v;
+      }
+    }
+    out[j] = r;
+  }
+}
+
 template <typename T>
 int32_t pinv_lower_one(const T* f, int64_t n, T x) {
   for (int64_t k = 0; k < n; ++k)
@@ -188,6 +213,18 @@ int oracle_maxplus_deconv(const void* f, const void* g, void* out, int64_t batch
   if (dt == 0) conv_rows<int32_t>(f, g, out, batch, n, stride_f, stride_g, true);
   else if (dt == 1) conv_rows<int64_t>(f, g, out, batch, n, stride_f, stride_g, true);
   else if (dt == 2) conv_rows<double>(f, g, out, batch, n, stride_f, stride_g, true);
+  else return -3;
+  return 0;
+}
+
+// Outputs t_idx[0..m) of one row pair (f, g of n samples); deconv = 0 convolution, 1 deconvolution.
+int oracle_product_at(const void* f, const void* g, int64_t n, const int64_t* t_idx, int64_t m,
+                      void* out, int deconv, int dt) {
+  for (int64_t j = 0; j < m; ++j)
+    if (t_idx[j] < 0 || t_idx[j] >= n) return -2;
+  if (dt == 0) product_at((const int32_t*)f, (const int32_t*)g, n, t_idx, m, (int32_t*)out, deconv != 0);
+  else if (dt == 1) product_at((const int64_t*)f, (const int64_t*)g, n, t_idx, m, (int64_t*)out, deconv != 0);
+  else if (dt == 2) product_at((const double*)f, (const double*)g, n, t_idx, m, (double*)out, deconv != 0);
   else return -3;
   return 0;
 }

@@ -1,0 +1,267 @@
+// HBM-bound curve kernels: pseudo-inverse (search), composition (gather), residual
+// service (subtract + prefix-max scan + clamp), horizontal / vertical deviation (search or
+// subtract + max-reduce).  One pass over the data each; none of them is arithmetic-bound.
+#include <hip/hip_runtime.h>
+
+#include <limits>
+
+#include "rtc_internal.h"
+
+namespace rtc {
+namespace {
+
+template <typename T> __device__ __forceinline__ T vmax(T a, T b) { return b > a ? b : a; }
+
+template <typename T> __device__ __forceinline__ T lowest() {
+  if constexpr (std::numeric_limits<T>::has_infinity) return -__builtin_huge_val();
+  else return std::numeric_limits<T>::lowest();
+}
+
+// Lower pseudo-inverse: first index with f[k] >= x (n if none).  f nondecreasing.
+template <typename T>
+__device__ __forceinline__ int lower_index(const T* __restrict__ f, int n, T x) {
+  int lo = 0, hi = n;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (f[mid] >= x) hi = mid; else lo = mid + 1;
+  }
+  return lo;
+}
+
+// Upper pseudo-inverse: last index with f[k] <= x (-1 if none).
+template <typename T>
+__device__ __forceinline__ int upper_index(const T* __restrict__ f, int n, T x) {
+  int lo = 0, hi = n;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (f[mid] <= x) lo = mid + 1; else hi = mid;
+  }
+  return lo - 1;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void pinv_kernel(const T* __restrict__ f, int n,
+                                                   const T* __restrict__ x, int m,
+                                                   int32_t* __restrict__ out, int blocks_per_row,
+                                                   int mode) {
+  const int row = blockIdx.x / blocks_per_row;
+  const int j = (blockIdx.x % blocks_per_row) * 256 + threadIdx.x;
+  if (j >= m) return;
+  const T* fr = f + (int64_t)row * n;
+  const T xv = x[(int64_t)row * m + j];
+  out[(int64_t)row * m + j] = mode == RTC_INV_LOWER ? lower_index(fr, n, xv) : upper_index(fr, n, xv);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void compose_kernel(const T* __restrict__ outer, int n_outer,
+                                                      const int32_t* __restrict__ inner, int n,
+                                                      T* __restrict__ out, int blocks_per_row,
+                                                      int32_t* __restrict__ dev_flags) {
+  const int row = blockIdx.x / blocks_per_row;
+  const int d = (blockIdx.x % blocks_per_row) * 256 + threadIdx.x;
+  bool clamped = false;
+  if (d < n) {
+    int k = inner[(int64_t)row * n + d];
+    if (k < 0) { k = 0; clamped = true; }
+    if (k > n_outer - 1) { k = n_outer - 1; clamped = true; }
+    out[(int64_t)row * n + d] = outer[(int64_t)row * n_outer + k];
+  }
+  if (dev_flags != nullptr && __any(clamped)) {
+    if ((threadIdx.x & 63) == 0) atomicOr(dev_flags, RTC_FLAG_DOMAIN);
+  }
+}
+
+// ---- wave-level inclusive max-scan with DPP row shifts and row broadcasts ----------------
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int32_t dpp_move(int32_t identity, int32_t v) {
+  return __builtin_amdgcn_update_dpp(identity, v, CTRL, ROW_MASK, 0xf, false);
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int64_t dpp_move(int64_t identity, int64_t v) {
+  const int32_t lo = __builtin_amdgcn_update_dpp((int32_t)identity, (int32_t)v, CTRL, ROW_MASK, 0xf, false);
+  const int32_t hi = __builtin_amdgcn_update_dpp((int32_t)(identity >> 32), (int32_t)(v >> 32), CTRL, ROW_MASK, 0xf, false);
+  return ((int64_t)hi << 32) | (uint32_t)lo;
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_move(double identity, double v) {
+  return __longlong_as_double(dpp_move<CTRL, ROW_MASK>((int64_t)__double_as_longlong(identity),
+                                                       (int64_t)__double_as_longlong(v)));
+}
+
+template <typename T>
+__device__ __forceinline__ T wave_scan_max(T v) {
+  const T id = lowest<T>();
+  v = vmax(v, dpp_move<0x111, 0xf>(id, v));  // row_shr:1
+  v = vmax(v, dpp_move<0x112, 0xf>(id, v));  // row_shr:2
+  v = vmax(v, dpp_move<0x114, 0xf>(id, v));  // row_shr:4
+  v = vmax(v, dpp_move<0x118, 0xf>(id, v));  // row_shr:8
+  v = vmax(v, dpp_move<0x142, 0xa>(id, v));  // row_bcast:15 into rows 1 and 3
+  v = vmax(v, dpp_move<0x143, 0xc>(id, v));  // row_bcast:31 into rows 2 and 3
+  return v;
+}
+
+// Remaining lower service of a greedy processing component:
+//   out[D] = max(0, max_{l<=D} beta_l[l] - alpha_u[l]).  One workgroup per row.
+template <typename T>
+__global__ __launch_bounds__(1024) void residual_service_kernel(const T* __restrict__ beta_l,
+                                                                const T* __restrict__ alpha_u,
+                                                                T* __restrict__ out, int n) {
+  constexpr int kPer = 4;
+  __shared__ T wave_tot[16];
+  __shared__ T carry_s;
+  const int row = blockIdx.x;
+  const T* bl = beta_l + (int64_t)row * n;
+  const T* au = alpha_u + (int64_t)row * n;
+  T* o = out + (int64_t)row * n;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  T carry = lowest<T>();
+  for (int base = 0; base < n; base += 1024 * kPer) {
+    const int i0 = base + threadIdx.x * kPer;
+    T v[kPer];
+    T run = lowest<T>();
+#pragma unroll
+    for (int e = 0; e < kPer; ++e) {
+      const int i = i0 + e;
+      // the difference may be negative; inputs obey the no-overflow precondition
+      const T d = i < n ? (T)(bl[i] - au[i]) : lowest<T>();
+      run = vmax(run, d);
+      v[e] = run;
+    }
+    const T incl = wave_scan_max(run);
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    T before = carry;
+    for (int w = 0; w < wave; ++w) before = vmax(before, wave_tot[w]);
+    // exclusive prefix inside the wave = inclusive value of the previous lane
+    T prev = __shfl_up(incl, 1);
+    if (lane == 0) prev = lowest<T>();
+    before = vmax(before, prev);
+#pragma unroll
+    for (int e = 0; e < kPer; ++e) {
+      const int i = i0 + e;
+      if (i < n) {
+        const T r = vmax(before, v[e]);
+        o[i] = r > (T)0 ? r : (T)0;
+      }
+    }
+    if (threadIdx.x == 1023) carry_s = vmax(before, run);
+    __syncthreads();
+    carry = carry_s;
+  }
+}
+
+// Maximal horizontal deviation of one row: each thread searches beta for some alpha[D].
+template <typename T>
+__global__ __launch_bounds__(256) void hdev_kernel(const T* __restrict__ alpha,
+                                                   const T* __restrict__ beta, int32_t* __restrict__ out,
+                                                   int n, int32_t* __restrict__ dev_flags) {
+  __shared__ int32_t red[4];
+  __shared__ int32_t unb[4];
+  const int row = blockIdx.x;
+  const T* a = alpha + (int64_t)row * n;
+  const T* b = beta + (int64_t)row * n;
+  int32_t h = 0;
+  bool unbounded = false;
+  for (int d = threadIdx.x; d < n; d += 256) {
+    const int k = lower_index(b, n, a[d]);
+    unbounded |= (k == n);
+    h = max(h, k - d);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) h = max(h, __shfl_xor(h, off));
+  const bool any_unb = __any(unbounded);
+  if ((threadIdx.x & 63) == 0) { red[threadIdx.x >> 6] = h; unb[threadIdx.x >> 6] = any_unb; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    out[row] = max(max(red[0], red[1]), max(red[2], red[3]));
+    if (dev_flags != nullptr && (unb[0] | unb[1] | unb[2] | unb[3])) atomicOr(dev_flags, RTC_FLAG_UNBOUNDED);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void vdev_kernel(const T* __restrict__ alpha,
+                                                   const T* __restrict__ beta, T* __restrict__ out, int n) {
+  __shared__ T red[4];
+  const int row = blockIdx.x;
+  const T* a = alpha + (int64_t)row * n;
+  const T* b = beta + (int64_t)row * n;
+  T m = lowest<T>();
+  for (int d = threadIdx.x; d < n; d += 256) m = vmax(m, (T)(a[d] - b[d]));
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m = vmax(m, __shfl_xor(m, off));
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) out[row] = vmax(vmax(red[0], red[1]), vmax(red[2], red[3]));
+}
+
+template <typename T>
+int pinv_typed(const void* f, int64_t n, const void* x, int64_t m, int32_t* out, int64_t batch, int mode,
+               hipStream_t stream) {
+  const int64_t bpr = (m + 255) / 256;
+  if (bpr * batch > 0x7fffffffLL) return RTC_ERR_SHAPE;
+  hipLaunchKernelGGL(pinv_kernel<T>, dim3((uint32_t)(bpr * batch)), dim3(256), 0, stream,
+                     static_cast<const T*>(f), (int)n, static_cast<const T*>(x), (int)m, out, (int)bpr, mode);
+  return hip_ok();
+}
+
+template <typename T>
+int compose_typed(const void* outer, int64_t n_outer, const int32_t* inner, int64_t n, void* out,
+                  int64_t batch, int32_t* dev_flags, hipStream_t stream) {
+  const int64_t bpr = (n + 255) / 256;
+  if (bpr * batch > 0x7fffffffLL) return RTC_ERR_SHAPE;
+  hipLaunchKernelGGL(compose_kernel<T>, dim3((uint32_t)(bpr * batch)), dim3(256), 0, stream,
+                     static_cast<const T*>(outer), (int)n_outer, inner, (int)n, static_cast<T*>(out),
+                     (int)bpr, dev_flags);
+  return hip_ok();
+}
+
+}  // namespace
+
+#define RTC_DISPATCH(dt, CALL)                    \
+  switch (dt) {                                   \
+    case RTC_I32: { using T = int32_t; CALL; }    \
+    case RTC_I64: { using T = int64_t; CALL; }    \
+    case RTC_F64: { using T = double; CALL; }     \
+    default: return RTC_ERR_DTYPE;                \
+  }
+
+int launch_pseudo_inverse(const void* f, int64_t n, const void* x, int64_t m, int32_t* out,
+                          int64_t batch, int mode, int dt, hipStream_t stream) {
+  RTC_DISPATCH(dt, return pinv_typed<T>(f, n, x, m, out, batch, mode, stream));
+}
+
+int launch_compose(const void* outer, int64_t n_outer, const int32_t* inner, int64_t n, void* out,
+                   int64_t batch, int dt, int32_t* dev_flags, hipStream_t stream) {
+  RTC_DISPATCH(dt, return compose_typed<T>(outer, n_outer, inner, n, out, batch, dev_flags, stream));
+}
+
+int launch_residual_service(const void* beta_l, const void* alpha_u, void* out, int64_t batch,
+                            int64_t n, int dt, hipStream_t stream) {
+  RTC_DISPATCH(dt, {
+    hipLaunchKernelGGL(residual_service_kernel<T>, dim3((uint32_t)batch), dim3(1024), 0, stream,
+                       static_cast<const T*>(beta_l), static_cast<const T*>(alpha_u),
+                       static_cast<T*>(out), (int)n);
+    return hip_ok();
+  });
+}
+
+int launch_max_hdev(const void* alpha, const void* beta, int32_t* out, int64_t batch, int64_t n,
+                    int dt, int32_t* dev_flags, hipStream_t stream) {
+  RTC_DISPATCH(dt, {
+    hipLaunchKernelGGL(hdev_kernel<T>, dim3((uint32_t)batch), dim3(256), 0, stream,
+                       static_cast<const T*>(alpha), static_cast<const T*>(beta), out, (int)n, dev_flags);
+    return hip_ok();
+  });
+}
+
+int launch_max_vdev(const void* alpha, const void* beta, void* out, int64_t batch, int64_t n, int dt,
+                    hipStream_t stream) {
+  RTC_DISPATCH(dt, {
+    hipLaunchKernelGGL(vdev_kernel<T>, dim3((uint32_t)batch), dim3(256), 0, stream,
+                       static_cast<const T*>(alpha), static_cast<const T*>(beta), static_cast<T*>(out),
+                       (int)n);
+    return hip_ok();
+  });
+}
+
+}  // namespace rtc

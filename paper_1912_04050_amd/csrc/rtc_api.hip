@@ -1,0 +1,192 @@
+// C-ABI entry points of librtc: argument validation and launch sequencing only.
+#include <hip/hip_runtime.h>
+
+#include "rtc_internal.h"
+
+using namespace rtc;
+
+namespace {
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+int check_shape(int64_t batch, int64_t n) {
+  if (batch < 1 || n < 1 || n > RTC_MAX_N || batch > 0x7fffffffLL) return RTC_ERR_SHAPE;
+  return RTC_OK;
+}
+
+int check_product(const void* f, const void* g, const void* out, int64_t batch, int64_t n,
+                  int64_t stride_f, int64_t stride_g, int dt, const void* ws, size_t ws_bytes,
+                  const int32_t* dev_flags) {
+  if (f == nullptr || g == nullptr || out == nullptr) return RTC_ERR_NULL;
+  const size_t es = elem_size(dt);
+  if (es == 0) return RTC_ERR_DTYPE;
+  if (int rc = check_shape(batch, n)) return rc;
+  if ((stride_f != 0 && stride_f < n) || (stride_g != 0 && stride_g < n)) return RTC_ERR_STRIDE;
+  if (!aligned(f, es) || !aligned(g, es) || !aligned(out, es) || !aligned(dev_flags, 4) ||
+      !aligned(ws, 16))
+    return RTC_ERR_ALIGN;
+  const size_t need = tropical_workspace_bytes(batch, n, dt);
+  if (need > 0 && (ws == nullptr || ws_bytes < need)) return RTC_ERR_WORKSPACE;
+  return RTC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int rtc_minplus_conv(const void* f, const void* g, void* out, int64_t batch, int64_t n,
+                     int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* ws, size_t ws_bytes,
+                     int32_t* dev_flags, void* hip_stream) {
+  if (int rc = check_product(f, g, out, batch, n, stride_f, stride_g, dt, ws, ws_bytes, dev_flags)) return rc;
+  return launch_tropical(false, f, g, out, batch, n, stride_f, stride_g, dt, nullptr, ws, ws_bytes,
+                         dev_flags, static_cast<hipStream_t>(hip_stream));
+}
+
+int rtc_maxplus_deconv(const void* f, const void* g, void* out, int64_t batch, int64_t n,
+                       int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* ws, size_t ws_bytes,
+                       int32_t* dev_flags, void* hip_stream) {
+  if (int rc = check_product(f, g, out, batch, n, stride_f, stride_g, dt, ws, ws_bytes, dev_flags)) return rc;
+  return launch_tropical(true, f, g, out, batch, n, stride_f, stride_g, dt, nullptr, ws, ws_bytes,
+                         dev_flags, static_cast<hipStream_t>(hip_stream));
+}
+
+int rtc_pseudo_inverse(const void* f, int64_t n, const void* x, int64_t m, int32_t* out_idx,
+                       int64_t batch, rtc_inv_mode mode, rtc_dtype dt, void* hip_stream) {
+  if (f == nullptr || x == nullptr || out_idx == nullptr) return RTC_ERR_NULL;
+  const size_t es = elem_size(dt);
+  if (es == 0) return RTC_ERR_DTYPE;
+  if (mode != RTC_INV_LOWER && mode != RTC_INV_UPPER) return RTC_ERR_MODE;
+  if (int rc = check_shape(batch, n)) return rc;
+  if (m < 1 || m > RTC_MAX_N) return RTC_ERR_SHAPE;
+  if (!aligned(f, es) || !aligned(x, es) || !aligned(out_idx, 4)) return RTC_ERR_ALIGN;
+  return launch_pseudo_inverse(f, n, x, m, out_idx, batch, mode, dt, static_cast<hipStream_t>(hip_stream));
+}
+
+int rtc_compose(const void* outer, int64_t n_outer, const int32_t* inner, int64_t n, void* out,
+                int64_t batch, rtc_dtype dt, int32_t* dev_flags, void* hip_stream) {
+  if (outer == nullptr || inner == nullptr || out == nullptr) return RTC_ERR_NULL;
+  const size_t es = elem_size(dt);
+  if (es == 0) return RTC_ERR_DTYPE;
+  if (int rc = check_shape(batch, n)) return rc;
+  if (n_outer < 1 || n_outer > RTC_MAX_N) return RTC_ERR_SHAPE;
+  if (!aligned(outer, es) || !aligned(out, es) || !aligned(inner, 4) || !aligned(dev_flags, 4))
+    return RTC_ERR_ALIGN;
+  return launch_compose(outer, n_outer, inner, n, out, batch, dt, dev_flags,
+                        static_cast<hipStream_t>(hip_stream));
+}
+
+int rtc_gpc_step(const rtc_gpc_args* a, void* hip_stream) {
+  if (a == nullptr || a->alpha_u == nullptr || a->beta_u == nullptr || a->beta_l == nullptr ||
+      a->alpha_u_out == nullptr || a->beta_l_out == nullptr)
+    return RTC_ERR_NULL;
+  const size_t es = elem_size(a->dt);
+  if (es == 0) return RTC_ERR_DTYPE;
+  if (int rc = check_shape(a->batch, a->n)) return rc;
+  if ((a->events_lower != nullptr || a->events_upper != nullptr) && a->gamma_u == nullptr) return RTC_ERR_NULL;
+  if (a->gamma_u != nullptr && (a->n_gamma < 1 || a->n_gamma > RTC_MAX_N)) return RTC_ERR_SHAPE;
+  if (!aligned(a->alpha_u, es) || !aligned(a->beta_u, es) || !aligned(a->beta_l, es) ||
+      !aligned(a->alpha_u_out, es) || !aligned(a->beta_l_out, es) || !aligned(a->gamma_u, es) ||
+      !aligned(a->events_lower, 4) || !aligned(a->events_upper, 4) || !aligned(a->dev_flags, 4) ||
+      !aligned(a->ws, 16))
+    return RTC_ERR_ALIGN;
+  const size_t need = rtc_workspace_bytes(RTC_OP_GPC, a->batch, a->n, a->dt);
+  if (a->ws == nullptr || a->ws_bytes < need) return RTC_ERR_WORKSPACE;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const int64_t batch = a->batch, n = a->n;
+  // workspace: [c = alpha_u (x) beta_u : batch*n elements][scratch of the products]
+  char* c = static_cast<char*>(a->ws);
+  const size_t c_bytes = ((size_t)batch * n * es + 255) / 256 * 256;
+  void* sub_ws = c + c_bytes;
+  const size_t sub_bytes = a->ws_bytes - c_bytes;
+  int rc = launch_tropical(false, a->alpha_u, a->beta_u, c, batch, n, n, n, a->dt, nullptr, sub_ws,
+                           sub_bytes, a->dev_flags, stream);
+  if (rc != RTC_OK) return rc;
+  rc = launch_tropical(true, c, a->beta_l, a->alpha_u_out, batch, n, n, n, a->dt, a->beta_u, sub_ws,
+                       sub_bytes, a->dev_flags, stream);
+  if (rc != RTC_OK) return rc;
+  rc = launch_residual_service(a->beta_l, a->alpha_u, a->beta_l_out, batch, n, a->dt, stream);
+  if (rc != RTC_OK) return rc;
+  if (a->events_lower != nullptr) {
+    rc = launch_pseudo_inverse(a->gamma_u, a->n_gamma, a->beta_l_out, n, a->events_lower, batch,
+                               RTC_INV_LOWER, a->dt, stream);
+    if (rc != RTC_OK) return rc;
+  }
+  if (a->events_upper != nullptr) {
+    rc = launch_pseudo_inverse(a->gamma_u, a->n_gamma, a->beta_l_out, n, a->events_upper, batch,
+                               RTC_INV_UPPER, a->dt, stream);
+    if (rc != RTC_OK) return rc;
+  }
+  return RTC_OK;
+}
+
+int rtc_max_hdev(const void* alpha, const void* beta, int32_t* out, int64_t batch, int64_t n,
+                 rtc_dtype dt, int32_t* dev_flags, void* hip_stream) {
+  if (alpha == nullptr || beta == nullptr || out == nullptr) return RTC_ERR_NULL;
+  const size_t es = elem_size(dt);
+  if (es == 0) return RTC_ERR_DTYPE;
+  if (int rc = check_shape(batch, n)) return rc;
+  if (!aligned(alpha, es) || !aligned(beta, es) || !aligned(out, 4) || !aligned(dev_flags, 4))
+    return RTC_ERR_ALIGN;
+  return launch_max_hdev(alpha, beta, out, batch, n, dt, dev_flags, static_cast<hipStream_t>(hip_stream));
+}
+
+int rtc_max_vdev(const void* alpha, const void* beta, void* out, int64_t batch, int64_t n,
+                 rtc_dtype dt, void* hip_stream) {
+  if (alpha == nullptr || beta == nullptr || out == nullptr) return RTC_ERR_NULL;
+  const size_t es = elem_size(dt);
+  if (es == 0) return RTC_ERR_DTYPE;
+  if (int rc = check_shape(batch, n)) return rc;
+  if (!aligned(alpha, es) || !aligned(beta, es) || !aligned(out, es)) return RTC_ERR_ALIGN;
+  return launch_max_vdev(alpha, beta, out, batch, n, dt, static_cast<hipStream_t>(hip_stream));
+}
+
+size_t rtc_workspace_bytes(int op, int64_t batch, int64_t n, rtc_dtype dt) {
+  const size_t es = elem_size(dt);
+  if (es == 0 || check_shape(batch, n) != RTC_OK) return 0;
+  const size_t prod = tropical_workspace_bytes(batch, n, dt);
+  switch (op) {
+    case RTC_OP_CONV:
+    case RTC_OP_DECONV:
+      return prod;
+    case RTC_OP_GPC:
+      return ((size_t)batch * n * es + 255) / 256 * 256 + prod;
+    default:
+      return 0;
+  }
+}
+
+const char* rtc_strerror(int status) {
+  switch (status) {
+    case RTC_OK: return "ok";
+    case RTC_ERR_NULL: return "required pointer is NULL";
+    case RTC_ERR_SHAPE: return "batch or n out of range";
+    case RTC_ERR_DTYPE: return "unknown dtype";
+    case RTC_ERR_ALIGN: return "pointer not aligned to its element size";
+    case RTC_ERR_STRIDE: return "stride must be 0 or >= n";
+    case RTC_ERR_WORKSPACE: return "workspace missing or too small";
+    case RTC_ERR_HIP: return "HIP runtime error while enqueueing";
+    case RTC_ERR_MODE: return "unknown mode";
+    default: return "unknown status";
+  }
+}
+
+int rtc_device_info(int* cu_count, int* clock_khz, int* lds_bytes) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return RTC_ERR_HIP;
+  int v = 0;
+  if (cu_count) {
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return RTC_ERR_HIP;
+    *cu_count = v;
+  }
+  if (clock_khz) {
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeClockRate, dev) != hipSuccess) return RTC_ERR_HIP;
+    *clock_khz = v;
+  }
+  if (lds_bytes) {
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) return RTC_ERR_HIP;
+    *lds_bytes = v;
+  }
+  return RTC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,39 @@
+// Internal declarations shared by the HIP translation units of librtc.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "rtc.h"
+
+namespace rtc {
+
+// Element size of a dtype, 0 when unknown.
+inline size_t elem_size(int dt) {
+  return dt == RTC_I32 ? 4 : (dt == RTC_I64 || dt == RTC_F64) ? 8 : 0;
+}
+
+// Tropical product launchers (tropical.hip).  `deconv` selects max-plus deconvolution.
+// `cap` (optional, dense [batch][n]) fuses out = min(out, cap) into the store, which is how
+// the greedy-processing-component step applies its final min with beta^u.
+int launch_tropical(bool deconv, const void* f, const void* g, void* out, int64_t batch, int64_t n,
+                    int64_t stride_f, int64_t stride_g, int dt, const void* cap, void* ws,
+                    size_t ws_bytes, int32_t* dev_flags, hipStream_t stream);
+size_t tropical_workspace_bytes(int64_t batch, int64_t n, int dt);
+
+// HBM-bound curve kernels (curve_ops.hip).
+int launch_pseudo_inverse(const void* f, int64_t n, const void* x, int64_t m, int32_t* out,
+                          int64_t batch, int mode, int dt, hipStream_t stream);
+int launch_compose(const void* outer, int64_t n_outer, const int32_t* inner, int64_t n, void* out,
+                   int64_t batch, int dt, int32_t* dev_flags, hipStream_t stream);
+int launch_residual_service(const void* beta_l, const void* alpha_u, void* out, int64_t batch,
+                            int64_t n, int dt, hipStream_t stream);
+int launch_max_hdev(const void* alpha, const void* beta, int32_t* out, int64_t batch, int64_t n,
+                    int dt, int32_t* dev_flags, hipStream_t stream);
+int launch_max_vdev(const void* alpha, const void* beta, void* out, int64_t batch, int64_t n, int dt,
+                    hipStream_t stream);
+
+inline int hip_ok() { return hipGetLastError() == hipSuccess ? RTC_OK : RTC_ERR_HIP; }
+
+}  // namespace rtc

@@ -1,0 +1,222 @@
+"""Thin Python binding of librtc (include/rtc.h): argument marshalling only.
+
+Every function has the name of the C entry point it calls, takes torch tensors that
+already live in HBM, and enqueues on torch's current HIP stream.  No step of the
+curve algebra runs in Python or in torch ops; torch only supplies device memory
+and the stream.  Importing this module without a built librtc.so raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librtc.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `python -m paper_1912_04050_amd._build` "
+        "(there is no CPU fallback)")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+RTC_I32, RTC_I64, RTC_F64 = 0, 1, 2
+RTC_INV_LOWER, RTC_INV_UPPER = 0, 1
+RTC_OP_CONV, RTC_OP_DECONV, RTC_OP_GPC = 0, 1, 2
+RTC_FLAG_OVERFLOW, RTC_FLAG_DOMAIN, RTC_FLAG_UNBOUNDED = 1, 2, 4
+
+_DT = {torch.int32: RTC_I32, torch.int64: RTC_I64, torch.float64: RTC_F64}
+
+_i64, _vp, _sz, _int = ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+
+
+class rtc_gpc_args(ctypes.Structure):
+    _fields_ = [("alpha_u", _vp), ("beta_u", _vp), ("beta_l", _vp), ("alpha_u_out", _vp),
+                ("beta_l_out", _vp), ("gamma_u", _vp), ("n_gamma", _i64), ("events_lower", _vp),
+                ("events_upper", _vp), ("batch", _i64), ("n", _i64), ("dt", _int), ("ws", _vp),
+                ("ws_bytes", _sz), ("dev_flags", _vp)]
+
+
+_product_sig = [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _int, _vp, _sz, _vp, _vp]
+_lib.rtc_minplus_conv.argtypes = _product_sig
+_lib.rtc_maxplus_deconv.argtypes = _product_sig
+_lib.rtc_pseudo_inverse.argtypes = [_vp, _i64, _vp, _i64, _vp, _i64, _int, _int, _vp]
+_lib.rtc_compose.argtypes = [_vp, _i64, _vp, _i64, _vp, _i64, _int, _vp, _vp]
+_lib.rtc_gpc_step.argtypes = [ctypes.POINTER(rtc_gpc_args), _vp]
+_lib.rtc_max_hdev.argtypes = [_vp, _vp, _vp, _i64, _i64, _int, _vp, _vp]
+_lib.rtc_max_vdev.argtypes = [_vp, _vp, _vp, _i64, _i64, _int, _vp]
+_lib.rtc_workspace_bytes.argtypes = [_int, _i64, _i64, _int]
+_lib.rtc_workspace_bytes.restype = _sz
+_lib.rtc_strerror.argtypes = [_int]
+_lib.rtc_strerror.restype = ctypes.c_char_p
+_lib.rtc_device_info.argtypes = [ctypes.POINTER(_int)] * 3
+for _name in ("rtc_minplus_conv", "rtc_maxplus_deconv", "rtc_pseudo_inverse", "rtc_compose",
+              "rtc_gpc_step", "rtc_max_hdev", "rtc_max_vdev", "rtc_device_info"):
+    getattr(_lib, _name).restype = _int
+
+
+class RtcError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"librtc status {status}: {_lib.rtc_strerror(status).decode()}")
+
+
+def _check(status: int):
+    if status != 0:
+        raise RtcError(status)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _rows(t: torch.Tensor):
+    """(tensor, rows, n, element stride) of a [n] or [rows][n] device tensor."""
+    if not t.is_cuda:
+        raise ValueError("librtc takes device tensors")
+    if t.dim() == 1:
+        t = t.unsqueeze(0)
+    if t.dim() != 2 or t.stride(1) != 1:
+        raise ValueError("curves must be [n] or [batch][n] with contiguous samples")
+    return t, t.shape[0], t.shape[1], (t.stride(0) if t.shape[0] > 1 else 0)
+
+
+def _row_stride(t, rows, batch, n):
+    if batch == 1:
+        return n
+    return 0 if rows == 1 else t.stride(0)
+
+
+def _dense(t: torch.Tensor):
+    """A [n] or [batch][n] device tensor that must already be dense (no copies are made here)."""
+    t, rows, n, _ = _rows(t)
+    if not t.is_contiguous():
+        raise ValueError("this argument must be a dense [batch][n] tensor")
+    return t, rows, n
+
+
+def rtc_workspace_bytes(op: int, batch: int, n: int, dtype: torch.dtype) -> int:
+    return int(_lib.rtc_workspace_bytes(op, batch, n, _DT[dtype]))
+
+
+def rtc_strerror(status: int) -> str:
+    return _lib.rtc_strerror(status).decode()
+
+
+def rtc_device_info():
+    cu, khz, lds = _int(), _int(), _int()
+    _check(_lib.rtc_device_info(ctypes.byref(cu), ctypes.byref(khz), ctypes.byref(lds)))
+    return {"cu_count": cu.value, "clock_khz": khz.value, "lds_bytes": lds.value}
+
+
+def _workspace(op, batch, n, dtype, device, ws):
+    need = rtc_workspace_bytes(op, batch, n, dtype)
+    if ws is None and need > 0:
+        ws = torch.empty(need, dtype=torch.uint8, device=device)
+    return ws, (0 if ws is None else ws.numel() * ws.element_size())
+
+
+def _product(fn, op, f, g, out, ws, dev_flags):
+    f, bf, n, sf = _rows(f)
+    g, bg, ng, sg = _rows(g)
+    if ng != n or f.dtype != g.dtype or (bf != bg and 1 not in (bf, bg)):
+        raise ValueError("operands must have the same length and dtype, batch equal or 1")
+    batch = max(bf, bg)
+    sf = _row_stride(f, bf, batch, n)
+    sg = _row_stride(g, bg, batch, n)
+    if out is None:
+        out = torch.empty((batch, n), dtype=f.dtype, device=f.device)
+    ws, ws_bytes = _workspace(op, batch, n, f.dtype, f.device, ws)
+    _check(fn(_ptr(f), _ptr(g), _ptr(out), batch, n, sf, sg, _DT[f.dtype], _ptr(ws), ws_bytes,
+              _ptr(dev_flags), _stream()))
+    return out
+
+
+def rtc_minplus_conv(f, g, out=None, ws=None, dev_flags=None):
+    """out[b][t] = min_{0<=s<=t} f[b][s] + g[b][t-s]."""
+    return _product(_lib.rtc_minplus_conv, RTC_OP_CONV, f, g, out, ws, dev_flags)
+
+
+def rtc_maxplus_deconv(f, g, out=None, ws=None, dev_flags=None):
+    """out[b][t] = max_{0<=u<=n-1-t} f[b][t+u] - g[b][u]."""
+    return _product(_lib.rtc_maxplus_deconv, RTC_OP_DECONV, f, g, out, ws, dev_flags)
+
+
+def rtc_pseudo_inverse(f, x, mode: int = RTC_INV_LOWER, out=None):
+    f, batch, n = _dense(f)
+    x, bx, m = _dense(x)
+    if bx != batch or x.dtype != f.dtype:
+        raise ValueError("x must have f's batch and dtype")
+    if out is None:
+        out = torch.empty((batch, m), dtype=torch.int32, device=f.device)
+    _check(_lib.rtc_pseudo_inverse(_ptr(f), n, _ptr(x), m, _ptr(out), batch, mode, _DT[f.dtype], _stream()))
+    return out
+
+
+def rtc_compose(outer, inner, out=None, dev_flags=None):
+    outer, batch, n_outer = _dense(outer)
+    inner, bi, n = _dense(inner)
+    if bi != batch or inner.dtype != torch.int32:
+        raise ValueError("inner must be int32 with outer's batch")
+    if out is None:
+        out = torch.empty((batch, n), dtype=outer.dtype, device=outer.device)
+    _check(_lib.rtc_compose(_ptr(outer), n_outer, _ptr(inner), n, _ptr(out), batch, _DT[outer.dtype],
+                            _ptr(dev_flags), _stream()))
+    return out
+
+
+def rtc_gpc_step(alpha_u, beta_u, beta_l, alpha_u_out=None, beta_l_out=None, gamma_u=None,
+                 events_lower=None, events_upper=None, ws=None, dev_flags=None):
+    """One greedy processing component; returns (alpha'^u, beta'^l)."""
+    alpha_u, batch, n = _dense(alpha_u)
+    beta_u = _dense(beta_u)[0]
+    beta_l = _dense(beta_l)[0]
+    if beta_u.shape != alpha_u.shape or beta_l.shape != alpha_u.shape:
+        raise ValueError("alpha_u, beta_u, beta_l must have one shape")
+    if alpha_u_out is None:
+        alpha_u_out = torch.empty_like(alpha_u)
+    if beta_l_out is None:
+        beta_l_out = torch.empty_like(alpha_u)
+    ws, ws_bytes = _workspace(RTC_OP_GPC, batch, n, alpha_u.dtype, alpha_u.device, ws)
+    a = rtc_gpc_args()
+    a.alpha_u, a.beta_u, a.beta_l = alpha_u.data_ptr(), beta_u.data_ptr(), beta_l.data_ptr()
+    a.alpha_u_out, a.beta_l_out = alpha_u_out.data_ptr(), beta_l_out.data_ptr()
+    if gamma_u is not None:
+        gamma_u = _dense(gamma_u)[0]
+        a.gamma_u, a.n_gamma = gamma_u.data_ptr(), gamma_u.shape[1]
+    a.events_lower = None if events_lower is None else events_lower.data_ptr()
+    a.events_upper = None if events_upper is None else events_upper.data_ptr()
+    a.batch, a.n, a.dt = batch, n, _DT[alpha_u.dtype]
+    a.ws, a.ws_bytes = (None if ws is None else ws.data_ptr()), ws_bytes
+    a.dev_flags = None if dev_flags is None else dev_flags.data_ptr()
+    _check(_lib.rtc_gpc_step(ctypes.byref(a), _stream()))
+    return alpha_u_out, beta_l_out
+
+
+def rtc_max_hdev(alpha, beta, out=None, dev_flags=None):
+    alpha, batch, n = _dense(alpha)
+    beta = _dense(beta)[0]
+    if beta.shape != alpha.shape or beta.dtype != alpha.dtype:
+        raise ValueError("alpha and beta must have one shape and dtype")
+    if out is None:
+        out = torch.empty(batch, dtype=torch.int32, device=alpha.device)
+    _check(_lib.rtc_max_hdev(_ptr(alpha), _ptr(beta), _ptr(out), batch, n, _DT[alpha.dtype],
+                             _ptr(dev_flags), _stream()))
+    return out
+
+
+def rtc_max_vdev(alpha, beta, out=None):
+    alpha, batch, n = _dense(alpha)
+    beta = _dense(beta)[0]
+    if beta.shape != alpha.shape or beta.dtype != alpha.dtype:
+        raise ValueError("alpha and beta must have one shape and dtype")
+    if out is None:
+        out = torch.empty(batch, dtype=alpha.dtype, device=alpha.device)
+    _check(_lib.rtc_max_vdev(_ptr(alpha), _ptr(beta), _ptr(out), batch, n, _DT[alpha.dtype], _stream()))
+    return out

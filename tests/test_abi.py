@@ -1,0 +1,87 @@
+"""The C-ABI library loads, exports every declared entry point, and rejects bad arguments
+on the host before anything is launched (no GPU needed: no call here reaches a kernel)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_1912_04050_amd", "librtc.so")
+HEADER = os.path.join(ROOT, "include", "rtc.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_1912_04050_amd import _build
+        _build.build()
+    return ctypes.CDLL(LIB)
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rtc_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert {"rtc_minplus_conv", "rtc_maxplus_deconv", "rtc_pseudo_inverse", "rtc_compose",
+            "rtc_gpc_step", "rtc_max_hdev", "rtc_max_vdev", "rtc_workspace_bytes",
+            "rtc_strerror"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_workspace_sizes_and_messages(lib):
+    lib.rtc_workspace_bytes.restype = ctypes.c_size_t
+    lib.rtc_workspace_bytes.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int]
+    assert lib.rtc_workspace_bytes(0, 4, 1000, 0) == 0
+    assert lib.rtc_workspace_bytes(0, 4, 1000, 2) == 0
+    assert lib.rtc_workspace_bytes(1, 4, 1000, 1) >= 2 * 4 * 1000 * 4 + 16
+    assert lib.rtc_workspace_bytes(2, 4, 1000, 0) >= 4 * 1000 * 4
+    assert lib.rtc_workspace_bytes(0, 0, 1000, 0) == 0 and lib.rtc_workspace_bytes(0, 1, 1 << 25, 0) == 0
+    lib.rtc_strerror.restype = ctypes.c_char_p
+    seen = {lib.rtc_strerror(s) for s in range(0, -9, -1)}
+    assert len(seen) == 9 and b"ok" in seen
+
+
+def test_products_reject_bad_arguments(lib):
+    sig = [ctypes.c_void_p] * 3 + [ctypes.c_int64] * 4 + [ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t,
+                                                         ctypes.c_void_p, ctypes.c_void_p]
+    p = ctypes.c_void_p(0x1000)  # never dereferenced: every call below fails validation first
+    for fn in (lib.rtc_minplus_conv, lib.rtc_maxplus_deconv):
+        fn.argtypes = sig
+        assert fn(None, p, p, 1, 8, 8, 8, 0, None, 0, None, None) == -1
+        assert fn(p, p, p, 0, 8, 8, 8, 0, None, 0, None, None) == -2
+        assert fn(p, p, p, 1, 0, 8, 8, 0, None, 0, None, None) == -2
+        assert fn(p, p, p, 1, (1 << 24) + 1, 1 << 25, 1 << 25, 0, None, 0, None, None) == -2
+        assert fn(p, p, p, 1, 8, 8, 8, 7, None, 0, None, None) == -3
+        assert fn(ctypes.c_void_p(0x1002), p, p, 1, 8, 8, 8, 0, None, 0, None, None) == -4
+        assert fn(p, p, p, 2, 8, 4, 8, 0, None, 0, None, None) == -5
+        assert fn(p, p, p, 1, 8, 8, 8, 1, None, 0, None, None) == -6   # int64 needs a workspace
+        assert fn(p, p, p, 1, 8, 8, 8, 1, p, 8, None, None) == -6
+
+
+def test_other_entry_points_reject_bad_arguments(lib):
+    p = ctypes.c_void_p(0x1000)
+    lib.rtc_pseudo_inverse.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
+                                       ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+                                       ctypes.c_void_p]
+    assert lib.rtc_pseudo_inverse(None, 8, p, 8, p, 1, 0, 0, None) == -1
+    assert lib.rtc_pseudo_inverse(p, 8, p, 8, p, 1, 2, 0, None) == -8
+    assert lib.rtc_pseudo_inverse(p, 8, p, 0, p, 1, 0, 0, None) == -2
+    lib.rtc_compose.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
+                                ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p,
+                                ctypes.c_void_p]
+    assert lib.rtc_compose(p, 0, p, 8, p, 1, 0, None, None) == -2
+    assert lib.rtc_compose(p, 8, None, 8, p, 1, 0, None, None) == -1
+    lib.rtc_max_hdev.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
+                                 ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    assert lib.rtc_max_hdev(p, p, None, 1, 8, 0, None, None) == -1
+    lib.rtc_max_vdev.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
+                                 ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]
+    assert lib.rtc_max_vdev(p, p, p, 1, 8, 5, None) == -3
+    lib.rtc_gpc_step.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    assert lib.rtc_gpc_step(None, None) == -1

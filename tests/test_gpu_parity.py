@@ -1,0 +1,216 @@
+"""Parity of the HIP path (through the C-ABI binding) against the CPU oracle.
+
+Bit-exact for every dtype: integer results have one correct bit pattern, and for fp64
+each candidate is a single rounded add/subtract and the selection is exact, so the
+tolerance is 0 (np.array_equal on the raw values).
+"""
+import sys
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import oracle
+from paper_1912_04050_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+NP2T = {np.dtype(np.int32): torch.int32, np.dtype(np.int64): torch.int64, np.dtype(np.float64): torch.float64}
+DTYPES = [np.int32, np.int64, np.float64]
+
+
+@pytest.fixture(scope="module")
+def rtc():
+    from paper_1912_04050_amd import rtc as mod
+    return mod
+
+
+def say(*a):
+    print("[case]", *a, flush=True)
+    sys.stdout.flush()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda")
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def check_products(rtc, f, g, tag):
+    say(tag, "conv/deconv", f.dtype, f.shape, g.shape)
+    got_c = host(rtc.rtc_minplus_conv(dev(f), dev(g)))
+    got_d = host(rtc.rtc_maxplus_deconv(dev(f), dev(g)))
+    assert np.array_equal(got_c, oracle.minplus_conv(f, g)), tag
+    assert np.array_equal(got_d, oracle.maxplus_deconv(f, g)), tag
+
+
+# sizes: below one block, around the 16-step block, around the 1024-output tile, several tiles
+SIZES = [1, 2, 15, 16, 17, 31, 33, 64, 100, 1023, 1024, 1025, 1040, 2049, 3000, 4133]
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_products_ragged_sizes(rtc, dtype):
+    for n in SIZES:
+        f = wl.random_monotone(7, 2 * n, 2, n, dtype)
+        g = wl.random_monotone(7, 2 * n + 1, 2, n, dtype)
+        check_products(rtc, f, g, f"ragged n={n}")
+
+
+@pytest.mark.parametrize("dtype", [np.int32, np.int64])
+def test_products_arbitrary_signed_values(rtc, dtype):
+    rng = np.random.default_rng(5)
+    for n in (1, 17, 700, 2500):
+        f = rng.integers(-10**6, 10**6, (3, n)).astype(dtype)
+        g = rng.integers(-10**6, 10**6, (3, n)).astype(dtype)
+        check_products(rtc, f, g, f"signed n={n}")
+
+
+def test_products_float_not_monotone(rtc):
+    rng = np.random.default_rng(6)
+    for n in (5, 1200):
+        f = rng.normal(size=(2, n)) * 100 + 1000
+        g = rng.normal(size=(2, n)) * 100 + 1000
+        check_products(rtc, f, g, f"float wild n={n}")
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_products_broadcast_rows(rtc, dtype):
+    n = 1500
+    f = wl.random_monotone(8, 1, 4, n, dtype)
+    g = wl.random_monotone(8, 2, 1, n, dtype)
+    say("broadcast g", dtype)
+    assert np.array_equal(host(rtc.rtc_minplus_conv(dev(f), dev(g))), oracle.minplus_conv(f, g))
+    assert np.array_equal(host(rtc.rtc_maxplus_deconv(dev(f), dev(g))), oracle.maxplus_deconv(f, g))
+    say("broadcast f", dtype)
+    assert np.array_equal(host(rtc.rtc_minplus_conv(dev(g), dev(f))), oracle.minplus_conv(g, f))
+    assert np.array_equal(host(rtc.rtc_maxplus_deconv(dev(g), dev(f))), oracle.maxplus_deconv(g, f))
+
+
+def test_int64_wide_and_mixed_rows(rtc):
+    """Rows beyond the 32-bit range take the 64-bit kernel; rows inside take the narrowed one."""
+    n = 1300
+    f = wl.random_monotone(9, 1, 4, n, np.int64)
+    g = wl.random_monotone(9, 2, 4, n, np.int64)
+    f[1] += 2**40
+    g[2] -= 2**35
+    f[3] = f[3] * 2**20
+    check_products(rtc, f, g, "int64 mixed")
+    top = np.iinfo(np.int64).max
+    f = (np.arange(n) * 3 + (top // 2 - 3 * n)).astype(np.int64)[None, :]
+    g = (np.arange(n) * 5 + (top // 2 - 5 * n)).astype(np.int64)[None, :]
+    check_products(rtc, f, g, "int64 near limit")
+
+
+def test_int32_near_limit(rtc):
+    n = 1100
+    top = np.iinfo(np.int32).max
+    f = (np.arange(n) * 3 + (top // 2 - 3 * n)).astype(np.int32)
+    g = (np.arange(n) * 5 + (top // 2 - 5 * n)).astype(np.int32)
+    check_products(rtc, f[None, :], g[None, :], "int32 near limit")
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_closed_form_on_gpu(rtc, dtype):
+    n, b, r, R, T = 3000, 17, 2, 3, 250
+    t = np.arange(n)
+    alpha = wl.token_bucket(n, b, r, dtype)
+    beta = wl.rate_latency(n, R, T, dtype)
+    say("closed form", dtype)
+    c = host(rtc.rtc_minplus_conv(dev(alpha), dev(beta)))[0]
+    d = host(rtc.rtc_maxplus_deconv(dev(alpha), dev(beta)))[0]
+    assert np.array_equal(c, (b + r * np.maximum(0, t - T)).astype(dtype))
+    head = t <= n - 1 - T
+    assert np.array_equal(d[head], (b + r * (t + T)).astype(dtype)[head])
+    assert host(rtc.rtc_max_vdev(dev(alpha), dev(beta)))[0] == b + r * T
+    assert host(rtc.rtc_max_hdev(dev(alpha), dev(beta)))[0] == T + -(-b // R)
+
+
+def test_overflow_flag(rtc):
+    n = 600
+    flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+    f = np.arange(n, dtype=np.int32)[None, :]
+    say("overflow flag clean")
+    rtc.rtc_minplus_conv(dev(f), dev(f), dev_flags=flags)
+    assert int(host(flags)[0]) == 0
+    big = (f + (2**31 - 1 - n)).astype(np.int32)
+    say("overflow flag raised")
+    rtc.rtc_minplus_conv(dev(big), dev(big), dev_flags=flags)
+    assert int(host(flags)[0]) & rtc.RTC_FLAG_OVERFLOW
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_pseudo_inverse(rtc, dtype):
+    for n, m in ((1, 5), (7, 40), (1000, 3000), (20000, 5000)):
+        f = wl.random_monotone(11, n, 3, n, dtype, max_inc=3)
+        if np.dtype(dtype) == np.float64:
+            x = np.sort(np.random.default_rng(n).random((3, m)) * (f[:, -1:] + 4) - 2, axis=1)
+            x[:, : min(m, n)] = f[:, : min(m, n)]  # exact hits exercise the ties
+        else:
+            x = np.random.default_rng(n).integers(-2, int(f.max()) + 3, (3, m)).astype(dtype)
+        for mode in (0, 1):
+            say("pinv", dtype, n, m, mode)
+            got = host(rtc.rtc_pseudo_inverse(dev(f), dev(x), mode))
+            assert np.array_equal(got, oracle.pseudo_inverse(f, x, mode))
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_compose(rtc, dtype):
+    rng = np.random.default_rng(12)
+    for k, n in ((1, 9), (300, 1000), (5000, 70000)):
+        outer = wl.random_monotone(12, k, 2, k, dtype)
+        inner = rng.integers(0, k, (2, n)).astype(np.int32)
+        flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+        say("compose", dtype, k, n)
+        got = host(rtc.rtc_compose(dev(outer), dev(inner), dev_flags=flags))
+        want, fl = oracle.compose(outer, inner)
+        assert np.array_equal(got, want) and int(host(flags)[0]) == fl == 0
+        inner[1, n // 2] = k + 3
+        inner[0, 0] = -1
+        got = host(rtc.rtc_compose(dev(outer), dev(inner), dev_flags=flags))
+        want, fl = oracle.compose(outer, inner)
+        assert np.array_equal(got, want) and int(host(flags)[0]) == fl == rtc.RTC_FLAG_DOMAIN
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_gpc_step(rtc, dtype):
+    for n in (1, 50, 1024, 4500, 9000):
+        a = wl.random_monotone(13, 3 * n, 3, n, dtype, max_inc=6)
+        bu = wl.random_monotone(13, 3 * n + 1, 3, n, dtype, max_inc=12, start_max=0)
+        bl = np.minimum(bu, wl.random_monotone(13, 3 * n + 2, 3, n, dtype, max_inc=8, start_max=0))
+        gam = wl.random_monotone(13, 3 * n + 3, 3, n + 5, dtype, max_inc=10, start_max=0)
+        ev_lo = torch.empty((3, n), dtype=torch.int32, device="cuda")
+        ev_up = torch.empty((3, n), dtype=torch.int32, device="cuda")
+        say("gpc", dtype, n)
+        ao, blo = rtc.rtc_gpc_step(dev(a), dev(bu), dev(bl), gamma_u=dev(gam), events_lower=ev_lo,
+                                   events_upper=ev_up)
+        want_a, want_b = oracle.gpc_step(a, bu, bl)
+        assert np.array_equal(host(ao), want_a)
+        assert np.array_equal(host(blo), want_b)
+        assert np.array_equal(host(ev_lo), oracle.pseudo_inverse(gam, want_b, 0))
+        assert np.array_equal(host(ev_up), oracle.pseudo_inverse(gam, want_b, 1))
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_deviations(rtc, dtype):
+    for n in (1, 77, 5000):
+        alpha = wl.random_monotone(14, n, 4, n, dtype, max_inc=5)
+        beta = wl.random_monotone(14, n + 1, 4, n, dtype, max_inc=9, start_max=0)
+        beta[3] = beta[3] // 3 if np.dtype(dtype) != np.float64 else beta[3] / 3  # row 3: unbounded
+        flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+        say("deviations", dtype, n)
+        h = host(rtc.rtc_max_hdev(dev(alpha), dev(beta), dev_flags=flags))
+        v = host(rtc.rtc_max_vdev(dev(alpha), dev(beta)))
+        want_h, fl = oracle.max_hdev(alpha, beta)
+        assert np.array_equal(h, want_h) and int(host(flags)[0]) == fl
+        assert np.array_equal(v, oracle.max_vdev(alpha, beta))
+
+
+def test_host_validation_on_device_pointers(rtc):
+    f = torch.zeros((2, 64), dtype=torch.int32, device="cuda")
+    with pytest.raises(rtc.RtcError) as e:
+        rtc.rtc_minplus_conv(f.to(torch.int64), f.to(torch.int64), ws=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == -6

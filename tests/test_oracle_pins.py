@@ -381,3 +381,16 @@ def test_gpc_brute_force_small():
             run = v if run is None else max(run, v)
             want.append(max(run, 0))
         assert blo[0].tolist() == want
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_sampled_outputs_agree_with_brute_force(dtype):
+    rng = np.random.default_rng(61)
+    n = 60
+    f = _curve(rng, n, dtype)
+    g = _curve(rng, n, dtype)
+    idx = np.array([0, 1, 7, 33, n - 2, n - 1])
+    want_c = np.array(bf_conv(f.tolist(), g.tolist()), dtype)[idx]
+    want_d = np.array(bf_deconv(f.tolist(), g.tolist()), dtype)[idx]
+    assert np.array_equal(oracle.product_at(f, g, idx, False), want_c)
+    assert np.array_equal(oracle.product_at(f, g, idx, True), want_d)
