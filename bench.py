@@ -34,7 +34,152 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="approximate CPU time to spend on the oracle baseline (0 disables it)")
     ap.add_argument("--no-parity", action="store_true", help="skip the sampled parity check")
+    ap.add_argument("--all-configs", action="store_true",
+                    help="also time every operator on each of the five configurations (adds per_config)")
+    ap.add_argument("--only", default="", help="profiling aid: restrict the step to a comma list of "
+                    "conv,deconv,pinv,compose,gpc,dev (the JSON line then describes that subset)")
+    ap.add_argument("--copy-mib", type=int, default=0, help="profiling aid: also run one plain device copy "
+                    "of this many MiB, the known-size kernel that FETCH_SIZE / WRITE_SIZE are scaled by")
     return ap.parse_args()
+
+
+def gpu_ms(fn, warm=3, reps=10):
+    """Median and minimum HIP-event time of fn() on torch's current stream."""
+    import torch
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1))
+    ts.sort()
+    return ts[len(ts) // 2], ts[0]
+
+
+def per_config_table(seed, peak_ops, with_cpu):
+    """GPU time of every exported operator on the five configurations, oracle time beside it."""
+    import numpy as np
+    import torch
+
+    from paper_1912_04050_amd import rtc, workloads as wl
+    if with_cpu:
+        from oracle import oracle
+        threads = oracle.num_threads()
+    rows = []
+
+    def dev(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    def cpu_s(fn):
+        if not with_cpu:
+            return None
+        ts = time.perf_counter()
+        fn()
+        return round(time.perf_counter() - ts, 4)
+
+    def product_rows(cfg, f_h, g_h, cpu_rows, storage):
+        B, N = f_h.shape
+        f, g = dev(f_h), dev(g_h)
+        out = torch.empty_like(f)
+        ws = torch.empty(max(16, rtc.rtc_workspace_bytes(rtc.RTC_OP_CONV, B, N, f.dtype)), dtype=torch.uint8,
+                         device="cuda")
+        po = B * N * (N + 1) // 2
+        for name, fn, ofn in (("minplus_conv", rtc.rtc_minplus_conv, "minplus_conv"),
+                              ("maxplus_deconv", rtc.rtc_maxplus_deconv, "maxplus_deconv")):
+            med, mn = gpu_ms(lambda: fn(f, g, out=out, ws=ws))
+            r = {"config": cfg, "op": name, "dtype": storage, "batch": B, "n": N, "gpu_ms": round(med, 4),
+                 "gpu_ms_min": round(mn, 4), "pair_ops": po, "gpair_ops_per_s": round(po / med / 1e6, 1),
+                 "pct_valu_peak_2ops": round(100 * 2 * po / (med * 1e-3) / peak_ops, 1)}
+            if with_cpu:
+                sub = slice(0, cpu_rows)
+                sec = cpu_s(lambda: getattr(oracle, ofn)(f_h[sub], g_h[sub]))
+                r.update({"oracle_s": sec, "oracle_rows": min(cpu_rows, B), "oracle_threads": threads,
+                          "oracle_gpair_ops_per_s": round(min(cpu_rows, B) * N * (N + 1) / 2 / sec / 1e9, 2)})
+            rows.append(r)
+        return f, g
+
+    def hbm_row(cfg, name, fn, nbytes, storage, B, N, extra=None):
+        med, mn = gpu_ms(fn)
+        r = {"config": cfg, "op": name, "dtype": storage, "batch": B, "n": N, "gpu_ms": round(med, 4),
+             "gpu_ms_min": round(mn, 4), "algorithmic_bytes": nbytes,
+             "gb_per_s": round(nbytes / (med * 1e-3) / 1e9, 1)}
+        if extra:
+            r.update(extra)
+        rows.append(r)
+
+    # config 1
+    c = wl.config1(seed)
+    product_rows(1, c["f"], c["g"], 1, "int32")
+    # config 2
+    c = wl.config2(seed, 1024, 4096)
+    a, b = product_rows(2, c["alpha_u"], c["beta_l"], 1024, "int32")
+    hd = torch.empty(1024, dtype=torch.int32, device="cuda")
+    vd = torch.empty(1024, dtype=torch.int32, device="cuda")
+    hbm_row(2, "max_hdev", lambda: rtc.rtc_max_hdev(a, b, out=hd), 2 * 1024 * 4096 * 4 + 4096, "int32", 1024, 4096)
+    hbm_row(2, "max_vdev", lambda: rtc.rtc_max_vdev(a, b, out=vd), 2 * 1024 * 4096 * 4 + 4096, "int32", 1024, 4096)
+    # config 3: int64 storage (range-probed 32-bit arithmetic), native int32, and forced 64-bit arithmetic
+    c = wl.config3(seed, 64, 65536)
+    product_rows(3, c["f"], c["g"], 8, "int64 storage, int32 arithmetic")
+    product_rows(3, c["f"].astype(np.int32), c["g"].astype(np.int32), 8, "int32")
+    product_rows(3, c["f"][:16] + (1 << 40), c["g"][:16], 4, "int64 arithmetic (values beyond 2^30)")
+    # config 4: one component of all 256 chains, then the whole 16-component chain
+    c = wl.config4(seed, 256, 16, 16384)
+    gam, abar = dev(c["gamma_u"]), dev(c["alpha_bar_u"])
+    bu, bl = dev(c["beta_u"]), dev(c["beta_l"])
+    a0 = torch.empty((256, 16384), dtype=torch.int32, device="cuda")
+    B4, N4 = 256, 16384
+    hbm_row(4, "compose", lambda: rtc.rtc_compose(gam, abar, out=a0), B4 * N4 * 12, "int32", B4, N4)
+    au, blo = torch.empty_like(a0), torch.empty_like(a0)
+    au2 = torch.empty_like(a0)
+    evl, evu = torch.empty_like(a0), torch.empty_like(a0)
+    ws = torch.empty(rtc.rtc_workspace_bytes(rtc.RTC_OP_GPC, B4, N4, torch.int32), dtype=torch.uint8, device="cuda")
+    po4 = 2 * B4 * N4 * (N4 + 1) // 2
+
+    def one_component():
+        rtc.rtc_gpc_step(a0, bu[0], bl[0], alpha_u_out=au, beta_l_out=blo, gamma_u=gam, events_lower=evl,
+                         events_upper=evu, ws=ws)
+
+    def whole_chain():
+        src = a0
+        for i in range(16):
+            dst = au if i % 2 == 0 else au2
+            rtc.rtc_gpc_step(src, bu[i], bl[i], alpha_u_out=dst, beta_l_out=blo, gamma_u=gam,
+                             events_lower=evl, events_upper=evu, ws=ws)
+            src = dst
+
+    med, mn = gpu_ms(one_component)
+    r = {"config": 4, "op": "gpc_step (1 component, 256 chains)", "dtype": "int32", "batch": B4, "n": N4,
+         "gpu_ms": round(med, 4), "gpu_ms_min": round(mn, 4), "pair_ops": po4,
+         "gpair_ops_per_s": round(po4 / med / 1e6, 1),
+         "pct_valu_peak_2ops": round(100 * 2 * po4 / (med * 1e-3) / peak_ops, 1)}
+    if with_cpu:
+        a0_h = oracle.compose(c["gamma_u"][:16], c["alpha_bar_u"][:16])[0]
+        sec = cpu_s(lambda: oracle.gpc_step(a0_h, c["beta_u"][0][:16], c["beta_l"][0][:16]))
+        r.update({"oracle_s": sec, "oracle_rows": 16, "oracle_threads": threads,
+                  "oracle_gpair_ops_per_s": round(2 * 16 * N4 * (N4 + 1) / 2 / sec / 1e9, 2),
+                  "oracle_note": "first 16 of 256 chains, one component; the full configuration is 256 x 16 of these"})
+    rows.append(r)
+    med, mn = gpu_ms(whole_chain, warm=1, reps=5)
+    rows.append({"config": 4, "op": "16-component chain, 256 chains", "dtype": "int32", "batch": B4, "n": N4,
+                 "gpu_ms": round(med, 3), "gpu_ms_min": round(mn, 3), "pair_ops": 16 * po4,
+                 "gpair_ops_per_s": round(16 * po4 / med / 1e6, 1),
+                 "pct_valu_peak_2ops": round(100 * 2 * 16 * po4 / (med * 1e-3) / peak_ops, 1)})
+    hbm_row(4, "pseudo_inverse lower (gamma_u at beta'_l)", lambda: rtc.rtc_pseudo_inverse(gam, blo, 0, out=evl),
+            B4 * N4 * 12, "int32", B4, N4)
+    # config 5
+    c = wl.config5(seed, 262144)
+    f, g = product_rows(5, c["f"], c["g"], 1, "float64")
+    x = dev(c["x"])
+    inv = torch.empty((1, 262144), dtype=torch.int32, device="cuda")
+    for mode, nm in ((0, "lower"), (1, "upper")):
+        hbm_row(5, f"pseudo_inverse {nm}", lambda: rtc.rtc_pseudo_inverse(f, x, mode, out=inv), 262144 * 20,
+                "float64", 1, 262144)
+    return rows
 
 
 def main():
@@ -56,7 +201,6 @@ def main():
     seed = wl.DEFAULT_SEED if args.seed is None else args.seed
     B, N = args.batch, args.n
     pair_ops_one = N * (N + 1) // 2          # per product and pair
-    products_per_step = 4                     # conv, deconv, and the two inside the GPC step
 
     # ---- synthetic inputs (seeded, resident in HBM before any timing) ----------------------
     c3 = wl.config3(seed, B, N)
@@ -84,22 +228,36 @@ def main():
 
     conv_events = []
 
+    only = set(x for x in args.only.split(",") if x) or {"conv", "deconv", "pinv", "compose", "gpc", "dev"}
+    products_per_step = ("conv" in only) + ("deconv" in only) + 2 * ("gpc" in only)
+    if args.copy_mib > 0:
+        src = torch.zeros(args.copy_mib << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+
     def step(record):
-        if record:
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-        rtc.rtc_minplus_conv(f, g, out=out_c, ws=ws, dev_flags=flags)
-        if record:
-            e1.record()
-            conv_events.append((e0, e1))
-        rtc.rtc_maxplus_deconv(f, g, out=out_d, ws=ws, dev_flags=flags)
-        rtc.rtc_pseudo_inverse(f, g, rtc.RTC_INV_LOWER, out=inv_lo)
-        rtc.rtc_pseudo_inverse(f, g, rtc.RTC_INV_UPPER, out=inv_up)
-        rtc.rtc_compose(g, inner, out=comp, dev_flags=flags)
-        rtc.rtc_gpc_step(f, beta_u, beta_l, alpha_u_out=au_out, beta_l_out=bl_out, gamma_u=g,
-                         events_lower=ev_lo, events_upper=ev_up, ws=ws, dev_flags=flags)
-        rtc.rtc_max_hdev(f, g, out=hdev, dev_flags=flags)
-        rtc.rtc_max_vdev(f, g, out=vdev)
+        if "conv" in only:
+            if record:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+            rtc.rtc_minplus_conv(f, g, out=out_c, ws=ws, dev_flags=flags)
+            if record:
+                e1.record()
+                conv_events.append((e0, e1))
+        if "deconv" in only:
+            rtc.rtc_maxplus_deconv(f, g, out=out_d, ws=ws, dev_flags=flags)
+        if "pinv" in only:
+            rtc.rtc_pseudo_inverse(f, g, rtc.RTC_INV_LOWER, out=inv_lo)
+            rtc.rtc_pseudo_inverse(f, g, rtc.RTC_INV_UPPER, out=inv_up)
+        if "compose" in only:
+            rtc.rtc_compose(g, inner, out=comp, dev_flags=flags)
+        if "gpc" in only:
+            rtc.rtc_gpc_step(f, beta_u, beta_l, alpha_u_out=au_out, beta_l_out=bl_out, gamma_u=g,
+                             events_lower=ev_lo, events_upper=ev_up, ws=ws, dev_flags=flags)
+        if "dev" in only:
+            rtc.rtc_max_hdev(f, g, out=hdev, dev_flags=flags)
+            rtc.rtc_max_vdev(f, g, out=vdev)
 
     for _ in range(args.warmup):
         step(False)
@@ -114,6 +272,14 @@ def main():
     value = total_pair_ops / (ms_per_step * 1e-3) / 1e9
 
     # ---- roofline of the dominant kernel (the int32 tropical product of rtc_minplus_conv) ---
+    if not conv_events:   # profiling subset without the convolution: time it once on its own
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            rtc.rtc_minplus_conv(f, g, out=out_c, ws=ws, dev_flags=flags)
+            e1.record()
+            conv_events.append((e0, e1))
+        torch.cuda.synchronize()
     conv_ms = sum(a.elapsed_time(b) for a, b in conv_events) / len(conv_events)
     info = rtc.rtc_device_info()
     peak_ops = info["cu_count"] * 64 * info["clock_khz"] * 1e3   # int32 VALU lane-ops per second
@@ -134,7 +300,7 @@ def main():
     cpu_baseline = None
     if not args.no_parity or args.cpu_seconds > 0:
         from oracle import oracle
-    if not args.no_parity:
+    if not args.no_parity and {"conv", "deconv"} <= only:
         rng = np.random.default_rng(seed)
         got_c, got_d = out_c.cpu().numpy(), out_d.cpu().numpy()
         ok = (int(flags.item()) & rtc.RTC_FLAG_OVERFLOW) == 0
@@ -165,10 +331,13 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
         "config": {"workload": f"config 3: {B} pairs, N={N}, int64 storage, range-probed int32 arithmetic; "
                                "step = conv + deconv + pseudo-inverses + compose + GPC step + deviations",
-                   "batch": B, "n": N, "seed": seed, "products_per_step": products_per_step},
+                   "batch": B, "n": N, "seed": seed, "products_per_step": products_per_step,
+                   "ops": sorted(only)},
         "pct_valu_peak": round(100.0 * achieved / peak_ops, 2),
         "roofline": roofline, "cpu_baseline": cpu_baseline, "parity": parity,
     }
+    if args.all_configs:
+        line["per_config"] = per_config_table(seed, peak_ops, args.cpu_seconds > 0)
     print(json.dumps(line))
     if parity == "MISMATCH":
         sys.exit(1)

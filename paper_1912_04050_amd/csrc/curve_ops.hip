@@ -150,22 +150,43 @@ __global__ __launch_bounds__(1024) void residual_service_kernel(const T* __restr
   }
 }
 
-// Maximal horizontal deviation of one row: each thread searches beta for some alpha[D].
+__device__ __forceinline__ void atomic_max_any(int32_t* p, int32_t v) { atomicMax(p, v); }
+__device__ __forceinline__ void atomic_max_any(int64_t* p, int64_t v) { atomicMax((long long*)p, (long long)v); }
+__device__ __forceinline__ void atomic_max_any(double* p, double v) { atomicMax(p, v); }
+
+template <typename T>
+__global__ __launch_bounds__(256) void init_kernel(T* __restrict__ dst, int count, T value) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < count) dst[i] = value;
+}
+
+constexpr int kDevPerThread = 4;   // alpha samples per thread in the deviation kernels
+constexpr int kDevPerBlock = 256 * kDevPerThread;
+
+// Maximal horizontal deviation: each thread searches beta for a few alpha[D]; a workgroup
+// covers kDevPerBlock consecutive D of one row and merges into out[row] (pre-set to 0) with
+// an atomic max.
 template <typename T>
 __global__ __launch_bounds__(256) void hdev_kernel(const T* __restrict__ alpha,
                                                    const T* __restrict__ beta, int32_t* __restrict__ out,
-                                                   int n, int32_t* __restrict__ dev_flags) {
+                                                   int n, int blocks_per_row,
+                                                   int32_t* __restrict__ dev_flags) {
   __shared__ int32_t red[4];
   __shared__ int32_t unb[4];
-  const int row = blockIdx.x;
+  const int row = blockIdx.x / blocks_per_row;
+  const int base = (blockIdx.x % blocks_per_row) * kDevPerBlock;
   const T* a = alpha + (int64_t)row * n;
   const T* b = beta + (int64_t)row * n;
   int32_t h = 0;
   bool unbounded = false;
-  for (int d = threadIdx.x; d < n; d += 256) {
-    const int k = lower_index(b, n, a[d]);
-    unbounded |= (k == n);
-    h = max(h, k - d);
+#pragma unroll
+  for (int e = 0; e < kDevPerThread; ++e) {
+    const int d = base + e * 256 + threadIdx.x;
+    if (d < n) {
+      const int k = lower_index(b, n, a[d]);
+      unbounded |= (k == n);
+      h = max(h, k - d);
+    }
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) h = max(h, __shfl_xor(h, off));
@@ -173,25 +194,33 @@ __global__ __launch_bounds__(256) void hdev_kernel(const T* __restrict__ alpha,
   if ((threadIdx.x & 63) == 0) { red[threadIdx.x >> 6] = h; unb[threadIdx.x >> 6] = any_unb; }
   __syncthreads();
   if (threadIdx.x == 0) {
-    out[row] = max(max(red[0], red[1]), max(red[2], red[3]));
+    const int32_t m = max(max(red[0], red[1]), max(red[2], red[3]));
+    if (m > 0) atomicMax(&out[row], m);
     if (dev_flags != nullptr && (unb[0] | unb[1] | unb[2] | unb[3])) atomicOr(dev_flags, RTC_FLAG_UNBOUNDED);
   }
 }
 
+// Maximal vertical deviation; same decomposition, out[row] pre-set to the lowest value.
 template <typename T>
 __global__ __launch_bounds__(256) void vdev_kernel(const T* __restrict__ alpha,
-                                                   const T* __restrict__ beta, T* __restrict__ out, int n) {
+                                                   const T* __restrict__ beta, T* __restrict__ out, int n,
+                                                   int blocks_per_row) {
   __shared__ T red[4];
-  const int row = blockIdx.x;
+  const int row = blockIdx.x / blocks_per_row;
+  const int base = (blockIdx.x % blocks_per_row) * kDevPerBlock;
   const T* a = alpha + (int64_t)row * n;
   const T* b = beta + (int64_t)row * n;
   T m = lowest<T>();
-  for (int d = threadIdx.x; d < n; d += 256) m = vmax(m, (T)(a[d] - b[d]));
+#pragma unroll
+  for (int e = 0; e < kDevPerThread; ++e) {
+    const int d = base + e * 256 + threadIdx.x;
+    if (d < n) m = vmax(m, (T)(a[d] - b[d]));
+  }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) m = vmax(m, __shfl_xor(m, off));
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
   __syncthreads();
-  if (threadIdx.x == 0) out[row] = vmax(vmax(red[0], red[1]), vmax(red[2], red[3]));
+  if (threadIdx.x == 0) atomic_max_any(&out[row], vmax(vmax(red[0], red[1]), vmax(red[2], red[3])));
 }
 
 template <typename T>
@@ -247,19 +276,29 @@ int launch_residual_service(const void* beta_l, const void* alpha_u, void* out, 
 
 int launch_max_hdev(const void* alpha, const void* beta, int32_t* out, int64_t batch, int64_t n,
                     int dt, int32_t* dev_flags, hipStream_t stream) {
+  const int64_t bpr = (n + kDevPerBlock - 1) / kDevPerBlock;
+  if (bpr * batch > 0x7fffffffLL) return RTC_ERR_SHAPE;
+  hipLaunchKernelGGL(init_kernel<int32_t>, dim3((uint32_t)((batch + 255) / 256)), dim3(256), 0, stream, out,
+                     (int)batch, 0);
   RTC_DISPATCH(dt, {
-    hipLaunchKernelGGL(hdev_kernel<T>, dim3((uint32_t)batch), dim3(256), 0, stream,
-                       static_cast<const T*>(alpha), static_cast<const T*>(beta), out, (int)n, dev_flags);
+    hipLaunchKernelGGL(hdev_kernel<T>, dim3((uint32_t)(bpr * batch)), dim3(256), 0, stream,
+                       static_cast<const T*>(alpha), static_cast<const T*>(beta), out, (int)n, (int)bpr,
+                       dev_flags);
     return hip_ok();
   });
 }
 
 int launch_max_vdev(const void* alpha, const void* beta, void* out, int64_t batch, int64_t n, int dt,
                     hipStream_t stream) {
+  const int64_t bpr = (n + kDevPerBlock - 1) / kDevPerBlock;
+  if (bpr * batch > 0x7fffffffLL) return RTC_ERR_SHAPE;
   RTC_DISPATCH(dt, {
-    hipLaunchKernelGGL(vdev_kernel<T>, dim3((uint32_t)batch), dim3(256), 0, stream,
+    hipLaunchKernelGGL(init_kernel<T>, dim3((uint32_t)((batch + 255) / 256)), dim3(256), 0, stream,
+                       static_cast<T*>(out), (int)batch, std::numeric_limits<T>::has_infinity
+                           ? (T)-std::numeric_limits<T>::infinity() : std::numeric_limits<T>::lowest());
+    hipLaunchKernelGGL(vdev_kernel<T>, dim3((uint32_t)(bpr * batch)), dim3(256), 0, stream,
                        static_cast<const T*>(alpha), static_cast<const T*>(beta), static_cast<T*>(out),
-                       (int)n);
+                       (int)n, (int)bpr);
     return hip_ok();
   });
 }

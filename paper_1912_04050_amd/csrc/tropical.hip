@@ -86,13 +86,20 @@ struct TropicalArgs {
   int32_t n;
   int32_t batch;
   int32_t n_tiles;
-  int32_t n_seg;        // segments launched per tile (tiles with fewer exit early)
+  int32_t fold_width;   // work items launched per folded tile pair (see item decode)
   int32_t seg;          // steps of s per segment, a multiple of the chunk length
 };
 
+#ifndef RTC_CHUNK_BLOCKS
+#define RTC_CHUNK_BLOCKS 64
+#endif
+#ifndef RTC_TARGET_ITEMS
+#define RTC_TARGET_ITEMS 65536
+#endif
+
 template <typename T, int R> struct Tile {
   static constexpr int kW = 64 * R;                          // outputs per wave
-  static constexpr int kChunk = 32 * R;                      // steps of s per staged window
+  static constexpr int kChunk = RTC_CHUNK_BLOCKS * R;        // steps of s per staged window
   static constexpr int kSlotBytes = R * (int)sizeof(T) + 16; // one group of R values + skew
   static constexpr int kSlots = 64 + kChunk / R;
   static constexpr int kVec = 16 / (int)sizeof(T);           // elements per 16-byte LDS read
@@ -133,12 +140,23 @@ __global__ __launch_bounds__(64) void tropical_kernel(const TropicalArgs p) {
 
   const int lane = threadIdx.x;
   const int n = p.n;
-  // work item = (tile, segment, row); rows vary fastest, heaviest tiles are launched first
+  // Work item = (tile, segment, row), rows fastest.  Tile k has ceil(s_end(k) / seg) segments,
+  // which grows linearly with k; tile k is therefore folded with tile n_tiles-1-k so that
+  // every folded pair owns about the same number of items and few launched workgroups are idle.
   uint32_t item = blockIdx.x;
   const int row = item % (uint32_t)p.batch;
   item /= (uint32_t)p.batch;
-  const int seg = item % (uint32_t)p.n_seg;
-  const int tile = p.n_tiles - 1 - (int)(item / (uint32_t)p.n_seg);
+  const int j = item % (uint32_t)p.fold_width;
+  const int k_lo = item / (uint32_t)p.fold_width;
+  const int k_hi = p.n_tiles - 1 - k_lo;
+  const int nseg_hi = (min((k_hi + 1) * TL::kW, n) + p.seg - 1) / p.seg;
+  int tile, seg;
+  if (j < nseg_hi) {
+    tile = k_hi; seg = j;
+  } else {
+    if (k_lo == k_hi) return;
+    tile = k_lo; seg = j - nseg_hi;
+  }
   const int t0 = tile * TL::kW;
   const int s_end = min(t0 + TL::kW, n);
   const int sa = seg * p.seg;
@@ -302,12 +320,12 @@ template <typename T, bool DECONV> T host_identity() {
 }
 
 struct Plan {
-  int n_tiles, n_seg, seg;
+  int n_tiles, fold_width, seg;
   bool atomic;
   int64_t items;
 };
 
-// Cut the triangular iteration space into about 16K work items of equal length.
+// Cut the triangular iteration space into about RTC_TARGET_ITEMS work items of equal length.
 template <typename T>
 Plan make_plan(int64_t batch, int64_t n) {
   constexpr int R = RFor<T>::value;
@@ -315,15 +333,23 @@ Plan make_plan(int64_t batch, int64_t n) {
   Plan pl;
   pl.n_tiles = (int)((n + TL::kW - 1) / TL::kW);
   const double total_steps = (double)batch * (double)n * (pl.n_tiles + 1) * 0.5;
-  int64_t seg = (int64_t)(total_steps / 16384.0);
+  // Measured on MI355X: items shorter than two chunks pay noticeably for their fixed cost
+  // (staging, atomics), items much longer than that leave a ragged tail at the end of the launch.
+  int64_t seg = (int64_t)(total_steps / (double)RTC_TARGET_ITEMS);
   seg = seg / TL::kChunk * TL::kChunk;
-  if (seg < TL::kChunk) seg = TL::kChunk;
+  if (seg < 2 * TL::kChunk) seg = total_steps / (2.0 * TL::kChunk) >= 8192.0 ? 2 * TL::kChunk : TL::kChunk;
   const int64_t span = (int64_t)pl.n_tiles * TL::kW;  // longest s range, rounded up
-  if (seg >= span) { seg = span; }
+  if (seg >= span) seg = span;
   pl.seg = (int)seg;
-  pl.n_seg = (int)((span + seg - 1) / seg);
-  pl.atomic = pl.n_seg > 1;
-  pl.items = batch * (int64_t)pl.n_tiles * pl.n_seg;
+  auto nseg = [&](int k) { const int64_t e = (int64_t)(k + 1) * TL::kW; return (int)(((e < n ? e : n) + seg - 1) / seg); };
+  pl.fold_width = 0;
+  for (int k_lo = 0; k_lo <= pl.n_tiles - 1 - k_lo; ++k_lo) {
+    const int k_hi = pl.n_tiles - 1 - k_lo;
+    const int w = nseg(k_hi) + (k_lo != k_hi ? nseg(k_lo) : 0);
+    if (w > pl.fold_width) pl.fold_width = w;
+  }
+  pl.atomic = nseg(pl.n_tiles - 1) > 1;
+  pl.items = batch * (int64_t)((pl.n_tiles + 1) / 2) * pl.fold_width;
   return pl;
 }
 
@@ -338,7 +364,7 @@ int run_product(const T* a, int64_t stride_a, const T* b, int64_t stride_b, OutT
   args.a = a; args.b = b; args.out = out; args.cap = cap; args.sel = sel;
   args.stride_a = stride_a; args.stride_b = stride_b; args.sel_want = sel_want;
   args.n = (int32_t)n; args.batch = (int32_t)batch;
-  args.n_tiles = pl.n_tiles; args.n_seg = pl.n_seg; args.seg = pl.seg;
+  args.n_tiles = pl.n_tiles; args.fold_width = pl.fold_width; args.seg = pl.seg;
   if (pl.atomic) {
     if (!prefilled) {
       const int64_t count = batch * n;
