@@ -25,8 +25,9 @@ int check_product(const void* f, const void* g, const void* out, int64_t batch, 
   if (!aligned(f, es) || !aligned(g, es) || !aligned(out, es) || !aligned(dev_flags, 4) ||
       !aligned(ws, 16))
     return RTC_ERR_ALIGN;
-  const size_t need = tropical_workspace_bytes(batch, n, dt);
-  if (need > 0 && (ws == nullptr || ws_bytes < need)) return RTC_ERR_WORKSPACE;
+  // int64 rows need the workspace; for int32 it is optional (it enables the packed fast path)
+  if (dt == RTC_I64 && (ws == nullptr || ws_bytes < tropical_workspace_bytes(batch, n, dt)))
+    return RTC_ERR_WORKSPACE;
   return RTC_OK;
 }
 

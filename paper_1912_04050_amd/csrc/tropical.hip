@@ -23,14 +23,34 @@
 // items; partial results of one tile are merged with atomic min/max (exact and order-free).
 // On the diagonal (s-block overlapping the tile) block j only concerns lanes > j, which run
 // under an exec mask; each lane's own R x R triangle is finished by a short epilogue.
+//
+// Packed 16-bit path (int32 convolution only).  A common slope rho is removed from both
+// operands (fd[s] = f[s] - rho*s, gd[i] = g[i] - rho*i, so f[s]+g[t-s] = fd[s]+gd[t-s] + rho*t).
+// Per chunk of 1024 steps the detrended values are re-based to the chunk / window minimum;
+// when range(fd chunk) + range(gd window) <= 65534 every candidate of that (tile, chunk) fits
+// an unsigned 16-bit lane, and two output halves of a 2048-wide tile are computed at once with
+// v_pk_add_u16 (saturating) + v_pk_min_u16: one VALU instruction per pair-op instead of 1.5.
+// Positions that do not exist (window index < 0, s >= n) are staged as 0xFFFF, which saturates
+// and never wins, so the packed kernel needs neither exec masks nor a triangle epilogue.
+// The decision is made per (row, tile, chunk) from precomputed block minima / maxima; chunks
+// that do not qualify are done by the 32-bit kernel, which evaluates the same predicate and
+// skips exactly the chunks the packed kernel owns.  Results are exact in both cases.
 #include <hip/hip_runtime.h>
 
 #include <limits>
+#include <type_traits>
 
 #include "rtc_internal.h"
 
 namespace rtc {
 namespace {
+
+#ifndef RTC_CHUNK_BLOCKS
+#define RTC_CHUNK_BLOCKS 64
+#endif
+#ifndef RTC_TARGET_ITEMS
+#define RTC_TARGET_ITEMS 65536
+#endif
 
 template <typename T> struct Lim;
 template <> struct Lim<int32_t> {
@@ -74,6 +94,58 @@ __device__ __forceinline__ void atomic_max(int64_t* p, int64_t v) { atomicMax((l
 __device__ __forceinline__ void atomic_min(double* p, double v) { atomicMin(p, v); }
 __device__ __forceinline__ void atomic_max(double* p, double v) { atomicMax(p, v); }
 
+template <typename T, int R> struct Tile {
+  static constexpr int kW = 64 * R;                          // outputs per wave
+  static constexpr int kChunk = RTC_CHUNK_BLOCKS * R;        // steps of s per staged window
+  static constexpr int kSlotBytes = R * (int)sizeof(T) + 16; // one group of R values + skew
+  static constexpr int kSlots = 64 + kChunk / R;
+  static constexpr int kVec = 16 / (int)sizeof(T);           // elements per 16-byte LDS read
+};
+
+// Geometry of the packed path: groups of 16 dwords like the int32 tile, two halves of 1024 outputs.
+constexpr int kPkR = 16;
+constexpr int kPkHalf = 64 * kPkR;
+constexpr int kPkW = 2 * kPkHalf;
+constexpr int kPkChunk = Tile<int32_t, kPkR>::kChunk;
+constexpr int kPkBlock = 256;          // granularity of the window minima / maxima
+constexpr uint32_t kPkPoison = 0xFFFFu;
+
+// Per-row auxiliary arrays of the packed path (all in the caller's workspace).
+struct PackAux {
+  const uint32_t* fpk;     // [B][npad]   re-based detrended f, both halves, 0xFFFFFFFF beyond n
+  const int32_t* fd;       // [B][npad]   detrended f
+  const int32_t* gd;       // [B][n]      detrended g
+  const int32_t* fb;       // [B][nchunk] chunk minimum of fd
+  const int32_t* fr;       // [B][nchunk] chunk range of fd
+  const int32_t* gmn;      // [B][nblk]   minimum of gd per block of kPkBlock
+  const int32_t* gmx;      // [B][nblk]   maximum
+  const int32_t* rho;      // [B]         slope removed from both operands
+  const int32_t* pack_ok;  // [B]         row is eligible for the packed path
+  int32_t npad, nchunk, nblk;
+};
+
+// Does the packed kernel own chunk c of the 2048-wide tile T2 of this row?  Evaluated
+// identically (wave-uniform) by both kernels.  *gb receives the window base.
+__device__ __forceinline__ bool chunk_packable(const PackAux& x, int row, int T2, int c, int n, int32_t* gb) {
+  if (x.pack_ok[row] == 0) return false;
+  const int sc = c * kPkChunk;
+  int lo = T2 * kPkW - sc - kPkChunk;
+  int hi = T2 * kPkW + kPkW - sc;
+  lo = max(lo, 0);
+  hi = min(hi, n);
+  const int b0 = lo / kPkBlock, b1 = (hi - 1) / kPkBlock;
+  const int32_t* mnp = x.gmn + (int64_t)row * x.nblk;
+  const int32_t* mxp = x.gmx + (int64_t)row * x.nblk;
+  int32_t mn = INT32_MAX, mx = INT32_MIN;
+  for (int b = b0; b <= b1; ++b) {
+    mn = min(mn, mnp[b]);
+    mx = max(mx, mxp[b]);
+  }
+  *gb = mn;
+  const int64_t range = (int64_t)x.fr[(int64_t)row * x.nchunk + c] + ((int64_t)mx - (int64_t)mn);
+  return range <= 65534;
+}
+
 struct TropicalArgs {
   const void* a;        // operand indexed by s (wave-uniform), rows of stride_a elements
   const void* b;        // operand indexed by t-s (window), rows of stride_b elements
@@ -86,24 +158,41 @@ struct TropicalArgs {
   int32_t n;
   int32_t batch;
   int32_t n_tiles;
-  int32_t fold_width;   // work items launched per folded tile pair (see item decode)
+  int32_t fold_width;   // work items launched per folded tile pair (see decode_item)
   int32_t seg;          // steps of s per segment, a multiple of the chunk length
+  int32_t use_aux;      // 1: operands are aux.fd / aux.gd, packed chunks are skipped, rho*t is added back
+  PackAux aux;
 };
 
-#ifndef RTC_CHUNK_BLOCKS
-#define RTC_CHUNK_BLOCKS 64
-#endif
-#ifndef RTC_TARGET_ITEMS
-#define RTC_TARGET_ITEMS 65536
-#endif
-
-template <typename T, int R> struct Tile {
-  static constexpr int kW = 64 * R;                          // outputs per wave
-  static constexpr int kChunk = RTC_CHUNK_BLOCKS * R;        // steps of s per staged window
-  static constexpr int kSlotBytes = R * (int)sizeof(T) + 16; // one group of R values + skew
-  static constexpr int kSlots = 64 + kChunk / R;
-  static constexpr int kVec = 16 / (int)sizeof(T);           // elements per 16-byte LDS read
-};
+// Work item = (tile, segment, row), rows fastest.  Tile k has ceil(s_end(k) / seg) segments,
+// which grows linearly with k; tile k is therefore folded with tile n_tiles-1-k so that
+// every folded pair owns about the same number of items and few launched workgroups are idle.
+// Returns false when this workgroup has nothing to do.
+template <int W>
+__device__ __forceinline__ bool decode_item(const TropicalArgs& p, int* row, int* t0, int* sa, int* sb) {
+  const int n = p.n;
+  uint32_t item = blockIdx.x;
+  *row = item % (uint32_t)p.batch;
+  item /= (uint32_t)p.batch;
+  const int j = item % (uint32_t)p.fold_width;
+  const int k_lo = item / (uint32_t)p.fold_width;
+  const int k_hi = p.n_tiles - 1 - k_lo;
+  const int nseg_hi = (min((k_hi + 1) * W, n) + p.seg - 1) / p.seg;
+  int tile, seg;
+  if (j < nseg_hi) {
+    tile = k_hi; seg = j;
+  } else {
+    if (k_lo == k_hi) return false;
+    tile = k_lo; seg = j - nseg_hi;
+  }
+  *t0 = tile * W;
+  const int s_end = min(*t0 + W, n);
+  *sa = seg * p.seg;
+  if (*sa >= s_end) return false;
+  if (p.sel != nullptr && p.sel[*row] != p.sel_want) return false;
+  *sb = min(*sa + p.seg, s_end);
+  return true;
+}
 
 template <typename T, int R>
 __device__ __forceinline__ void load_group(T (&dst)[R], const unsigned char* lds, int slot) {
@@ -140,29 +229,10 @@ __global__ __launch_bounds__(64) void tropical_kernel(const TropicalArgs p) {
 
   const int lane = threadIdx.x;
   const int n = p.n;
-  // Work item = (tile, segment, row), rows fastest.  Tile k has ceil(s_end(k) / seg) segments,
-  // which grows linearly with k; tile k is therefore folded with tile n_tiles-1-k so that
-  // every folded pair owns about the same number of items and few launched workgroups are idle.
-  uint32_t item = blockIdx.x;
-  const int row = item % (uint32_t)p.batch;
-  item /= (uint32_t)p.batch;
-  const int j = item % (uint32_t)p.fold_width;
-  const int k_lo = item / (uint32_t)p.fold_width;
-  const int k_hi = p.n_tiles - 1 - k_lo;
-  const int nseg_hi = (min((k_hi + 1) * TL::kW, n) + p.seg - 1) / p.seg;
-  int tile, seg;
-  if (j < nseg_hi) {
-    tile = k_hi; seg = j;
-  } else {
-    if (k_lo == k_hi) return;
-    tile = k_lo; seg = j - nseg_hi;
-  }
-  const int t0 = tile * TL::kW;
-  const int s_end = min(t0 + TL::kW, n);
-  const int sa = seg * p.seg;
-  if (sa >= s_end) return;
-  if (p.sel != nullptr && p.sel[row] != p.sel_want) return;
-  const int sb = min(sa + p.seg, s_end);
+  int row, t0, sa, sb;
+  if (!decode_item<TL::kW>(p, &row, &t0, &sa, &sb)) return;
+  // the packed path exists for the int32 convolution only
+  const bool aux = std::is_same<T, int32_t>::value && !DECONV && p.use_aux != 0;
 
   const T* __restrict__ arow = static_cast<const T*>(p.a) + (int64_t)row * p.stride_a;
   const T* __restrict__ brow = static_cast<const T*>(p.b) + (int64_t)row * p.stride_b;
@@ -172,6 +242,10 @@ __global__ __launch_bounds__(64) void tropical_kernel(const TropicalArgs p) {
   for (int r = 0; r < R; ++r) acc[r] = SR::identity();
 
   for (int sc = sa; sc < sb; sc += TL::kChunk) {
+    if (aux) {
+      int32_t gb;
+      if (chunk_packable(p.aux, row, t0 / kPkW, sc / kPkChunk, n, &gb)) continue;
+    }
     const int ce = min(sc + TL::kChunk, sb);
     const int nblk = (ce - sc + R - 1) / R;
     // LDS slot q holds window elements [gbase + q*R, gbase + q*R + R)
@@ -216,7 +290,12 @@ __global__ __launch_bounds__(64) void tropical_kernel(const TropicalArgs p) {
 
   const int tl = t0 + lane * R;
   // the lane's own triangle: steps s = tl+k against outputs tl+r, r >= k, window index r-k
-  if (sa <= t0 && t0 < sb) {
+  bool triangle = sa <= t0 && t0 < sb;
+  if (aux && triangle) {
+    int32_t gb;
+    if (chunk_packable(p.aux, row, t0 / kPkW, t0 / kPkChunk, n, &gb)) triangle = false;
+  }
+  if (triangle) {
     T b0[R];
 #pragma unroll
     for (int q = 0; q < R; ++q) {
@@ -234,18 +313,148 @@ __global__ __launch_bounds__(64) void tropical_kernel(const TropicalArgs p) {
   OutT* __restrict__ orow = static_cast<OutT*>(p.out) + (int64_t)row * n;
   const OutT* __restrict__ crow =
       p.cap ? static_cast<const OutT*>(p.cap) + (int64_t)row * n : nullptr;
+  const int32_t rho = aux ? p.aux.rho[row] : 0;
+  // Transpose the accumulators through LDS (lane-major [lane][R+1] -> output-major) so that
+  // the 64 lanes of one store / atomic instruction touch 64 consecutive outputs.
+  static_assert(64 * (R + 1) * sizeof(T) <= sizeof(lds), "transpose buffer must fit the window buffer");
+  T* xp = reinterpret_cast<T*>(lds);
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < R; ++r) xp[lane * (R + 1) + r] = acc[r];
+  __syncthreads();
 #pragma unroll
   for (int r = 0; r < R; ++r) {
-    const int t = tl + r;
+    const int x = r * 64 + lane;          // output offset inside the tile
+    const int t = t0 + x;
     if (t < n) {
       const int ot = DECONV ? n - 1 - t : t;
-      OutT v = (OutT)acc[r];
+      T av = xp[x + x / R];
+      if (aux) {
+        // detrended domain: an untouched accumulator must not be shifted into a valid value
+        if (av == SR::identity()) continue;
+        av = wrap_add(av, (T)(rho * t));
+      }
+      OutT v = (OutT)av;
       if (crow) v = sel_min(v, crow[ot]);
       if (ATOMIC) {
         if (DECONV) atomic_max(&orow[ot], v); else atomic_min(&orow[ot], v);
       } else {
         orow[ot] = v;
       }
+    }
+  }
+}
+
+// ---- packed 16-bit convolution kernel ------------------------------------------------------
+
+typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t pk_min_addsat(uint32_t acc, uint32_t w, uint32_t u) {
+  const us2 s = __builtin_elementwise_add_sat(__builtin_bit_cast(us2, w), __builtin_bit_cast(us2, u));
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(us2, acc), s));
+}
+
+__device__ __forceinline__ void block_steps_packed(uint32_t (&acc)[kPkR], const uint32_t (&u)[kPkR],
+                                                   const uint32_t (&lo)[kPkR], const uint32_t (&hi)[kPkR]) {
+#pragma unroll
+  for (int k = 0; k < kPkR; ++k) {
+#pragma unroll
+    for (int r = 0; r < kPkR; ++r) {
+      const uint32_t w = (r >= k) ? hi[r - k] : lo[kPkR + r - k];
+      acc[r] = pk_min_addsat(acc[r], w, u[k]);
+    }
+  }
+}
+
+// One wave owns 2048 outputs: the low 16 bits of every packed register belong to output
+// t0 + 16*lane + r, the high 16 bits to output t0 + 1024 + 16*lane + r.  Only chunks for
+// which chunk_packable() holds are processed; all results merge into out with atomic min.
+template <typename OutT>
+__global__ __launch_bounds__(64) void packed_conv_kernel(const TropicalArgs p) {
+  using TL = Tile<int32_t, kPkR>;
+  __shared__ __align__(16) unsigned char lds[TL::kSlots * TL::kSlotBytes];
+  const int lane = threadIdx.x;
+  const int n = p.n;
+  int row, t0, sa, sb;
+  if (!decode_item<kPkW>(p, &row, &t0, &sa, &sb)) return;
+  const PackAux& x = p.aux;
+  if (x.pack_ok[row] == 0) return;
+  const uint32_t* __restrict__ fpk = x.fpk + (int64_t)row * x.npad;
+  const int32_t* __restrict__ gd = x.gd + (int64_t)row * n;
+  const int32_t* __restrict__ fb = x.fb + (int64_t)row * x.nchunk;
+
+  int32_t acc_lo[kPkR], acc_hi[kPkR];
+#pragma unroll
+  for (int r = 0; r < kPkR; ++r) { acc_lo[r] = INT32_MAX; acc_hi[r] = INT32_MAX; }
+
+  for (int sc = sa; sc < sb; sc += kPkChunk) {
+    int32_t gb;
+    const int c = sc / kPkChunk;
+    if (!chunk_packable(x, row, t0 / kPkW, c, n, &gb)) continue;
+    const int ce = min(sc + kPkChunk, sb);
+    const int nblk = (ce - sc + kPkR - 1) / kPkR;
+    const int gbase = t0 - (sc + nblk * kPkR);
+    const int count = (64 + nblk) * kPkR;
+    __syncthreads();
+    for (int e = lane; e < count; e += 64) {
+      const int il = gbase + e, ih = il + kPkHalf;
+      uint32_t vl = kPkPoison, vh = kPkPoison;
+      if (il >= 0 && il < n) vl = min((uint32_t)gd[il] - (uint32_t)gb, kPkPoison);
+      if (ih >= 0 && ih < n) vh = min((uint32_t)gd[ih] - (uint32_t)gb, kPkPoison);
+      *reinterpret_cast<uint32_t*>(lds + (e / kPkR) * TL::kSlotBytes + (e % kPkR) * 4) = vl | (vh << 16);
+    }
+    __syncthreads();
+
+    uint32_t acc[kPkR];
+#pragma unroll
+    for (int r = 0; r < kPkR; ++r) acc[r] = 0xFFFFFFFFu;
+    uint32_t w0[kPkR], w1[kPkR];
+    load_group<uint32_t, kPkR>(w0, lds, lane + nblk);
+    for (int i = 0; i < nblk; i += 2) {
+      {
+        const int s0 = sc + i * kPkR;
+        load_group<uint32_t, kPkR>(w1, lds, lane + nblk - i - 1);
+        uint32_t u[kPkR];
+#pragma unroll
+        for (int k = 0; k < kPkR; ++k) u[k] = fpk[s0 + k];
+        block_steps_packed(acc, u, w1, w0);
+      }
+      if (i + 1 < nblk) {
+        const int s0 = sc + (i + 1) * kPkR;
+        load_group<uint32_t, kPkR>(w0, lds, lane + nblk - i - 2);
+        uint32_t u[kPkR];
+#pragma unroll
+        for (int k = 0; k < kPkR; ++k) u[k] = fpk[s0 + k];
+        block_steps_packed(acc, u, w0, w1);
+      }
+    }
+    // fold the chunk: a 16-bit lane that still holds 0xFFFF saw no existing candidate
+    const uint32_t cb = (uint32_t)fb[c] + (uint32_t)gb;
+#pragma unroll
+    for (int r = 0; r < kPkR; ++r) {
+      const uint32_t vl = acc[r] & 0xFFFFu, vh = acc[r] >> 16;
+      const int32_t cl = vl != kPkPoison ? (int32_t)(cb + vl) : INT32_MAX;
+      const int32_t ch = vh != kPkPoison ? (int32_t)(cb + vh) : INT32_MAX;
+      acc_lo[r] = min(acc_lo[r], cl);
+      acc_hi[r] = min(acc_hi[r], ch);
+    }
+  }
+
+  OutT* __restrict__ orow = static_cast<OutT*>(p.out) + (int64_t)row * n;
+  const int32_t rho = x.rho[row];
+  int32_t* xp = reinterpret_cast<int32_t*>(lds);
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < kPkR; ++r) xp[lane * (kPkR + 1) + r] = half == 0 ? acc_lo[r] : acc_hi[r];
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < kPkR; ++r) {
+      const int xo = r * 64 + lane;
+      const int t = t0 + half * kPkHalf + xo;
+      const int32_t av = xp[xo + xo / kPkR];
+      if (t < n && av != INT32_MAX) atomic_min(&orow[t], (OutT)wrap_add(av, rho * t));
     }
   }
 }
@@ -258,14 +467,17 @@ __global__ __launch_bounds__(256) void fill_kernel(T* __restrict__ dst, int64_t 
 }
 
 // Range probe of one row pair.  Finds min/max of both rows, raises the overflow flag when
-// the bounds do not prove that every candidate fits, and (int64 only) writes 32-bit copies
-// of both rows plus a selector saying whether the 32-bit kernel may be used for this row.
+// the bounds do not prove that every candidate fits, (int64 only) writes 32-bit copies
+// of both rows plus a selector saying whether the 32-bit kernel may be used for this row, and
+// (optionally) decides eligibility for the packed path and the slope to remove.
 template <typename T>
 __global__ __launch_bounds__(1024) void probe_kernel(const T* __restrict__ f, int64_t stride_f,
                                                      const T* __restrict__ g, int64_t stride_g, int n,
                                                      bool deconv, int32_t* __restrict__ f32,
                                                      int32_t* __restrict__ g32,
                                                      int32_t* __restrict__ narrow_ok,
+                                                     int32_t* __restrict__ pack_ok,
+                                                     int32_t* __restrict__ rho,
                                                      int32_t* __restrict__ dev_flags) {
   __shared__ T red[4][16];
   const int row = blockIdx.x;
@@ -306,6 +518,72 @@ __global__ __launch_bounds__(1024) void probe_kernel(const T* __restrict__ f, in
         const T lim = (T)1 << 30;
         narrow_ok[row] = (fmin >= -lim && fmax < lim && gmin >= -lim && gmax < lim) ? 1 : 0;
       }
+      if (pack_ok) {
+        // |values| < 2^29 keeps the detrended rows inside int32 (rho*i <= g[n-1]-g[0] < 2^30)
+        const T lim = (T)1 << 29;
+        const bool ok = fmin >= -lim && fmax < lim && gmin >= -lim && gmax < lim;
+        pack_ok[row] = ok ? 1 : 0;
+        const T g0 = gr[0], g1 = gr[n - 1];
+        rho[row] = (ok && n > 1 && g1 > g0) ? (int32_t)((g1 - g0) / (T)(n - 1)) : 0;
+      }
+    }
+  }
+}
+
+__device__ __forceinline__ int32_t wave_min(int32_t v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = min(v, __shfl_xor(v, off));
+  return v;
+}
+__device__ __forceinline__ int32_t wave_max(int32_t v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = max(v, __shfl_xor(v, off));
+  return v;
+}
+
+// Prepares the packed path for one (row, chunk of 1024 indices): detrends both operands,
+// re-bases the chunk of f to its minimum and packs it into both halves, and records the chunk
+// range of f and the minima / maxima of g per block of 256.
+__global__ __launch_bounds__(1024) void prep_kernel(const int32_t* __restrict__ f, int64_t stride_f,
+                                                    const int32_t* __restrict__ g, int64_t stride_g, int n,
+                                                    int npad, int nchunk, int nblk,
+                                                    const int32_t* __restrict__ rho,
+                                                    uint32_t* __restrict__ fpk, int32_t* __restrict__ fd,
+                                                    int32_t* __restrict__ gd, int32_t* __restrict__ fb,
+                                                    int32_t* __restrict__ fr, int32_t* __restrict__ gmn,
+                                                    int32_t* __restrict__ gmx) {
+  __shared__ int32_t s_fmn[16], s_fmx[16], s_gmn[16], s_gmx[16];
+  const int row = blockIdx.x / nchunk;
+  const int c = blockIdx.x % nchunk;
+  const int i = c * kPkChunk + threadIdx.x;
+  const int32_t r = rho[row];
+  const bool valid = i < n;
+  const int32_t fdv = valid ? wrap_sub(f[(int64_t)row * stride_f + i], r * i) : 0;
+  const int32_t gdv = valid ? wrap_sub(g[(int64_t)row * stride_g + i], r * i) : 0;
+  const int32_t fmn = wave_min(valid ? fdv : INT32_MAX), fmx = wave_max(valid ? fdv : INT32_MIN);
+  const int32_t gmn_w = wave_min(valid ? gdv : INT32_MAX), gmx_w = wave_max(valid ? gdv : INT32_MIN);
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) { s_fmn[wave] = fmn; s_fmx[wave] = fmx; s_gmn[wave] = gmn_w; s_gmx[wave] = gmx_w; }
+  __syncthreads();
+  int32_t cmn = INT32_MAX, cmx = INT32_MIN;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) { cmn = min(cmn, s_fmn[w]); cmx = max(cmx, s_fmx[w]); }
+  fpk[(int64_t)row * npad + i] = valid ? min((uint32_t)fdv - (uint32_t)cmn, kPkPoison) * 0x10001u : 0xFFFFFFFFu;
+  fd[(int64_t)row * npad + i] = fdv;
+  if (valid) gd[(int64_t)row * n + i] = gdv;
+  if (threadIdx.x == 0) {
+    fb[(int64_t)row * nchunk + c] = cmn;
+    const int64_t range = (int64_t)cmx - (int64_t)cmn;
+    fr[(int64_t)row * nchunk + c] = (int32_t)(range < 0x7fffffffLL ? range : 0x7fffffffLL);
+  }
+  if ((threadIdx.x & (kPkBlock - 1)) == 0) {
+    const int j = c * (kPkChunk / kPkBlock) + threadIdx.x / kPkBlock;
+    if (j < nblk) {
+      int32_t mn = INT32_MAX, mx = INT32_MIN;
+#pragma unroll
+      for (int w = 0; w < kPkBlock / 64; ++w) { mn = min(mn, s_gmn[wave + w]); mx = max(mx, s_gmx[wave + w]); }
+      gmn[(int64_t)row * nblk + j] = mn;
+      gmx[(int64_t)row * nblk + j] = mx;
     }
   }
 }
@@ -325,23 +603,21 @@ struct Plan {
   int64_t items;
 };
 
-// Cut the triangular iteration space into about RTC_TARGET_ITEMS work items of equal length.
-template <typename T>
-Plan make_plan(int64_t batch, int64_t n) {
-  constexpr int R = RFor<T>::value;
-  using TL = Tile<T, R>;
+// Cut the triangular iteration space (tiles of `width` outputs, chunks of `chunk` steps) into
+// about RTC_TARGET_ITEMS work items of equal length.
+Plan make_plan(int64_t batch, int64_t n, int width, int chunk) {
   Plan pl;
-  pl.n_tiles = (int)((n + TL::kW - 1) / TL::kW);
+  pl.n_tiles = (int)((n + width - 1) / width);
   const double total_steps = (double)batch * (double)n * (pl.n_tiles + 1) * 0.5;
   // Measured on MI355X: items shorter than two chunks pay noticeably for their fixed cost
   // (staging, atomics), items much longer than that leave a ragged tail at the end of the launch.
   int64_t seg = (int64_t)(total_steps / (double)RTC_TARGET_ITEMS);
-  seg = seg / TL::kChunk * TL::kChunk;
-  if (seg < 2 * TL::kChunk) seg = total_steps / (2.0 * TL::kChunk) >= 8192.0 ? 2 * TL::kChunk : TL::kChunk;
-  const int64_t span = (int64_t)pl.n_tiles * TL::kW;  // longest s range, rounded up
+  seg = seg / chunk * chunk;
+  if (seg < 2 * chunk) seg = total_steps / (2.0 * chunk) >= 8192.0 ? 2 * chunk : chunk;
+  const int64_t span = ((int64_t)pl.n_tiles * width + chunk - 1) / chunk * chunk;  // longest s range, rounded up
   if (seg >= span) seg = span;
   pl.seg = (int)seg;
-  auto nseg = [&](int k) { const int64_t e = (int64_t)(k + 1) * TL::kW; return (int)(((e < n ? e : n) + seg - 1) / seg); };
+  auto nseg = [&](int k) { const int64_t e = (int64_t)(k + 1) * width; return (int)(((e < n ? e : n) + seg - 1) / seg); };
   pl.fold_width = 0;
   for (int k_lo = 0; k_lo <= pl.n_tiles - 1 - k_lo; ++k_lo) {
     const int k_hi = pl.n_tiles - 1 - k_lo;
@@ -353,26 +629,36 @@ Plan make_plan(int64_t batch, int64_t n) {
   return pl;
 }
 
+template <typename T> Plan make_plan(int64_t batch, int64_t n) {
+  using TL = Tile<T, RFor<T>::value>;
+  return make_plan(batch, n, TL::kW, TL::kChunk);
+}
+
+template <typename OutT, bool DECONV>
+void launch_fill(OutT* out, int64_t count, hipStream_t stream) {
+  const int64_t want = (count + 2047) / 2048;
+  const int blocks = (int)(want < 65535 ? want : 65535);
+  hipLaunchKernelGGL(fill_kernel<OutT>, dim3(blocks), dim3(256), 0, stream, out, count,
+                     host_identity<OutT, DECONV>());
+}
+
+// One launch of the generic kernel.  `force_atomic` is set when several kernels contribute to
+// one output (the output is then already filled with the identity).
 template <typename T, typename OutT, bool DECONV>
 int run_product(const T* a, int64_t stride_a, const T* b, int64_t stride_b, OutT* out, const OutT* cap,
                 const int32_t* sel, int sel_want, int64_t batch, int64_t n, hipStream_t stream,
-                bool prefilled) {
+                bool prefilled, bool force_atomic, const PackAux* aux) {
   constexpr int R = RFor<T>::value;
   const Plan pl = make_plan<T>(batch, n);
   if (pl.items > 0x7fffffffLL) return RTC_ERR_SHAPE;
-  TropicalArgs args;
+  TropicalArgs args = {};
   args.a = a; args.b = b; args.out = out; args.cap = cap; args.sel = sel;
   args.stride_a = stride_a; args.stride_b = stride_b; args.sel_want = sel_want;
   args.n = (int32_t)n; args.batch = (int32_t)batch;
   args.n_tiles = pl.n_tiles; args.fold_width = pl.fold_width; args.seg = pl.seg;
-  if (pl.atomic) {
-    if (!prefilled) {
-      const int64_t count = batch * n;
-      const int64_t want = (count + 2047) / 2048;
-      const int blocks = (int)(want < 65535 ? want : 65535);
-      hipLaunchKernelGGL(fill_kernel<OutT>, dim3(blocks), dim3(256), 0, stream, out, count,
-                         host_identity<OutT, DECONV>());
-    }
+  if (aux != nullptr) { args.use_aux = 1; args.aux = *aux; }
+  if (pl.atomic || force_atomic) {
+    if (!prefilled) launch_fill<OutT, DECONV>(out, batch * n, stream);
     hipLaunchKernelGGL((tropical_kernel<T, OutT, DECONV, R, true>), dim3((uint32_t)pl.items), dim3(64), 0,
                        stream, args);
   } else {
@@ -382,79 +668,163 @@ int run_product(const T* a, int64_t stride_a, const T* b, int64_t stride_b, OutT
   return hip_ok();
 }
 
+// Layout of the packed path's arrays inside the workspace.
+struct PackLayout {
+  int64_t npad, nchunk, nblk;
+  size_t off_fpk, off_fd, off_gd, off_fb, off_fr, off_gmn, off_gmx, off_rho, off_ok, bytes;
+};
+
+PackLayout pack_layout(int64_t batch, int64_t n) {
+  PackLayout L;
+  L.nchunk = (n + kPkChunk - 1) / kPkChunk;
+  L.npad = L.nchunk * kPkChunk;
+  L.nblk = (n + kPkBlock - 1) / kPkBlock;
+  size_t o = 0;
+  auto take = [&](size_t elems) { const size_t at = o; o += (elems * 4 + 255) / 256 * 256; return at; };
+  L.off_fpk = take((size_t)batch * L.npad);
+  L.off_fd = take((size_t)batch * L.npad);
+  L.off_gd = take((size_t)batch * n);
+  L.off_fb = take((size_t)batch * L.nchunk);
+  L.off_fr = take((size_t)batch * L.nchunk);
+  L.off_gmn = take((size_t)batch * L.nblk);
+  L.off_gmx = take((size_t)batch * L.nblk);
+  L.off_rho = take((size_t)batch);
+  L.off_ok = take((size_t)batch);
+  L.bytes = o;
+  return L;
+}
+
+// int32 convolution with the packed fast path.  f32 / g32 are int32 rows (the caller's own,
+// or the narrowed copies of int64 rows); pack_ok / rho were written by the probe.  `sel`
+// (optional) restricts both kernels to rows with sel[row] == 1.
+template <typename OutT>
+int run_conv_packed(const int32_t* f32, int64_t stride_f, const int32_t* g32, int64_t stride_g, OutT* out,
+                    const int32_t* sel, int64_t batch, int64_t n, char* wsp, const PackLayout& L,
+                    hipStream_t stream) {
+  PackAux aux;
+  aux.fpk = reinterpret_cast<uint32_t*>(wsp + L.off_fpk);
+  aux.fd = reinterpret_cast<int32_t*>(wsp + L.off_fd);
+  aux.gd = reinterpret_cast<int32_t*>(wsp + L.off_gd);
+  aux.fb = reinterpret_cast<int32_t*>(wsp + L.off_fb);
+  aux.fr = reinterpret_cast<int32_t*>(wsp + L.off_fr);
+  aux.gmn = reinterpret_cast<int32_t*>(wsp + L.off_gmn);
+  aux.gmx = reinterpret_cast<int32_t*>(wsp + L.off_gmx);
+  aux.rho = reinterpret_cast<int32_t*>(wsp + L.off_rho);
+  aux.pack_ok = reinterpret_cast<int32_t*>(wsp + L.off_ok);
+  aux.npad = (int32_t)L.npad; aux.nchunk = (int32_t)L.nchunk; aux.nblk = (int32_t)L.nblk;
+  if (batch * L.nchunk > 0x7fffffffLL) return RTC_ERR_SHAPE;
+  hipLaunchKernelGGL(prep_kernel, dim3((uint32_t)(batch * L.nchunk)), dim3(1024), 0, stream, f32, stride_f, g32,
+                     stride_g, (int)n, (int)L.npad, (int)L.nchunk, (int)L.nblk, aux.rho,
+                     const_cast<uint32_t*>(aux.fpk), const_cast<int32_t*>(aux.fd), const_cast<int32_t*>(aux.gd),
+                     const_cast<int32_t*>(aux.fb), const_cast<int32_t*>(aux.fr), const_cast<int32_t*>(aux.gmn),
+                     const_cast<int32_t*>(aux.gmx));
+  const Plan pl = make_plan(batch, n, kPkW, kPkChunk);
+  if (pl.items > 0x7fffffffLL) return RTC_ERR_SHAPE;
+  TropicalArgs args = {};
+  args.out = out; args.sel = sel; args.sel_want = 1;
+  args.n = (int32_t)n; args.batch = (int32_t)batch;
+  args.n_tiles = pl.n_tiles; args.fold_width = pl.fold_width; args.seg = pl.seg;
+  args.use_aux = 1; args.aux = aux;
+  hipLaunchKernelGGL(packed_conv_kernel<OutT>, dim3((uint32_t)pl.items), dim3(64), 0, stream, args);
+  if (hip_ok() != RTC_OK) return RTC_ERR_HIP;
+  // the 32-bit kernel works on the detrended rows and skips the chunks done above
+  return run_product<int32_t, OutT, false>(aux.fd, L.npad, aux.gd, n, out, nullptr, sel, 1, batch, n, stream,
+                                           true, true, &aux);
+}
+
 template <typename T, bool DECONV>
 int run_typed(const void* f, const void* g, void* out, int64_t batch, int64_t n, int64_t stride_f,
-              int64_t stride_g, const void* cap, void* ws, int32_t* dev_flags, hipStream_t stream) {
+              int64_t stride_g, const void* cap, void* ws, size_t ws_bytes, int32_t* dev_flags,
+              hipStream_t stream) {
   // convolution: uniform operand f, window g.  deconvolution: uniform g, window f (reversed).
   const T* a = static_cast<const T*>(DECONV ? g : f);
   const T* b = static_cast<const T*>(DECONV ? f : g);
   const int64_t sa = DECONV ? stride_g : stride_f;
   const int64_t sb = DECONV ? stride_f : stride_g;
+  if constexpr (std::is_same<T, int32_t>::value && !DECONV) {
+    const PackLayout L = pack_layout(batch, n);
+    if (ws != nullptr && ws_bytes >= L.bytes && cap == nullptr) {
+      char* wsp = static_cast<char*>(ws);
+      hipLaunchKernelGGL(probe_kernel<int32_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,
+                         static_cast<const int32_t*>(f), stride_f, static_cast<const int32_t*>(g), stride_g,
+                         (int)n, false, (int32_t*)nullptr, (int32_t*)nullptr, (int32_t*)nullptr,
+                         reinterpret_cast<int32_t*>(wsp + L.off_ok), reinterpret_cast<int32_t*>(wsp + L.off_rho),
+                         dev_flags);
+      launch_fill<int32_t, false>(static_cast<int32_t*>(out), batch * n, stream);
+      return run_conv_packed<int32_t>(static_cast<const int32_t*>(f), stride_f, static_cast<const int32_t*>(g),
+                                      stride_g, static_cast<int32_t*>(out), nullptr, batch, n, wsp, L, stream);
+    }
+  }
   if (dev_flags != nullptr && std::numeric_limits<T>::is_integer) {
     hipLaunchKernelGGL(probe_kernel<T>, dim3((uint32_t)batch), dim3(1024), 0, stream,
                        static_cast<const T*>(f), stride_f, static_cast<const T*>(g), stride_g, (int)n,
-                       DECONV, (int32_t*)nullptr, (int32_t*)nullptr, (int32_t*)nullptr, dev_flags);
+                       DECONV, (int32_t*)nullptr, (int32_t*)nullptr, (int32_t*)nullptr, (int32_t*)nullptr,
+                       (int32_t*)nullptr, dev_flags);
   }
-  (void)ws;
   return run_product<T, T, DECONV>(a, sa, b, sb, static_cast<T*>(out), static_cast<const T*>(cap),
-                                   nullptr, 0, batch, n, stream, false);
+                                   nullptr, 0, batch, n, stream, false, false, nullptr);
+}
+
+// Bytes of the narrowed copies + selector that precede the packed-path arrays for int64 rows.
+size_t narrow_bytes(int64_t batch, int64_t n) {
+  return ((size_t)(2 * batch * n + batch) * sizeof(int32_t) + 255) / 256 * 256;
 }
 
 template <bool DECONV>
 int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, int64_t stride_f,
             int64_t stride_g, const void* cap, void* ws, int32_t* dev_flags, hipStream_t stream) {
-  // workspace: [f32: batch*n][g32: batch*n][narrow_ok: batch]
+  // workspace: [f32: batch*n][g32: batch*n][narrow_ok: batch][packed-path arrays]
   int32_t* f32 = static_cast<int32_t*>(ws);
   int32_t* g32 = f32 + batch * n;
   int32_t* ok = g32 + batch * n;
+  char* wsp = static_cast<char*>(ws) + narrow_bytes(batch, n);
+  const PackLayout L = pack_layout(batch, n);
+  const bool packed = !DECONV && cap == nullptr;
   hipLaunchKernelGGL(probe_kernel<int64_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,
                      static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g,
-                     (int)n, DECONV, f32, g32, ok, dev_flags);
-  // Both kernels see every row; the selector makes each row run in exactly one of them.
-  // When segments are merged with atomics the output is filled once, before both.
-  const Plan p32 = make_plan<int32_t>(batch, n);
-  const Plan p64 = make_plan<int64_t>(batch, n);
-  bool prefilled = false;
-  if (p32.atomic || p64.atomic) {
-    const int64_t count = batch * n;
-    const int64_t want = (count + 2047) / 2048;
-    const int blocks = (int)(want < 65535 ? want : 65535);
-    hipLaunchKernelGGL(fill_kernel<int64_t>, dim3(blocks), dim3(256), 0, stream,
-                       static_cast<int64_t*>(out), count, host_identity<int64_t, DECONV>());
-    prefilled = true;
+                     (int)n, DECONV, f32, g32, ok,
+                     packed ? reinterpret_cast<int32_t*>(wsp + L.off_ok) : (int32_t*)nullptr,
+                     packed ? reinterpret_cast<int32_t*>(wsp + L.off_rho) : (int32_t*)nullptr, dev_flags);
+  // Several kernels see every row; the selector makes each row run in exactly one family.
+  // The output is filled once with the identity, before all of them.
+  launch_fill<int64_t, DECONV>(static_cast<int64_t*>(out), batch * n, stream);
+  int rc;
+  if (packed) {
+    rc = run_conv_packed<int64_t>(f32, n, g32, n, static_cast<int64_t*>(out), ok, batch, n, wsp, L, stream);
+  } else {
+    rc = run_product<int32_t, int64_t, DECONV>(DECONV ? g32 : f32, n, DECONV ? f32 : g32, n,
+                                               static_cast<int64_t*>(out), static_cast<const int64_t*>(cap), ok,
+                                               1, batch, n, stream, true, true, nullptr);
   }
-  int rc = run_product<int32_t, int64_t, DECONV>(DECONV ? g32 : f32, n, DECONV ? f32 : g32, n,
-                                                 static_cast<int64_t*>(out),
-                                                 static_cast<const int64_t*>(cap), ok, 1, batch, n,
-                                                 stream, prefilled);
   if (rc != RTC_OK) return rc;
   const int64_t* a = static_cast<const int64_t*>(DECONV ? g : f);
   const int64_t* b = static_cast<const int64_t*>(DECONV ? f : g);
   return run_product<int64_t, int64_t, DECONV>(a, DECONV ? stride_g : stride_f, b,
                                                DECONV ? stride_f : stride_g, static_cast<int64_t*>(out),
                                                static_cast<const int64_t*>(cap), ok, 0, batch, n, stream,
-                                               prefilled);
+                                               true, true, nullptr);
 }
 
 }  // namespace
 
 size_t tropical_workspace_bytes(int64_t batch, int64_t n, int dt) {
-  if (dt == RTC_I64) return (size_t)(2 * batch * n + batch) * sizeof(int32_t) + 256;
+  if (dt == RTC_I64) return narrow_bytes(batch, n) + pack_layout(batch, n).bytes;
+  if (dt == RTC_I32) return pack_layout(batch, n).bytes;
   return 0;
 }
 
 int launch_tropical(bool deconv, const void* f, const void* g, void* out, int64_t batch, int64_t n,
                     int64_t stride_f, int64_t stride_g, int dt, const void* cap, void* ws,
                     size_t ws_bytes, int32_t* dev_flags, hipStream_t stream) {
-  if (ws_bytes < tropical_workspace_bytes(batch, n, dt) || (dt == RTC_I64 && ws == nullptr))
+  if (dt == RTC_I64 && (ws == nullptr || ws_bytes < tropical_workspace_bytes(batch, n, dt)))
     return RTC_ERR_WORKSPACE;
   switch (dt) {
     case RTC_I32:
-      return deconv ? run_typed<int32_t, true>(f, g, out, batch, n, stride_f, stride_g, cap, ws, dev_flags, stream)
-                    : run_typed<int32_t, false>(f, g, out, batch, n, stride_f, stride_g, cap, ws, dev_flags, stream);
+      return deconv ? run_typed<int32_t, true>(f, g, out, batch, n, stride_f, stride_g, cap, ws, ws_bytes, dev_flags, stream)
+                    : run_typed<int32_t, false>(f, g, out, batch, n, stride_f, stride_g, cap, ws, ws_bytes, dev_flags, stream);
     case RTC_F64:
-      return deconv ? run_typed<double, true>(f, g, out, batch, n, stride_f, stride_g, cap, ws, dev_flags, stream)
-                    : run_typed<double, false>(f, g, out, batch, n, stride_f, stride_g, cap, ws, dev_flags, stream);
+      return deconv ? run_typed<double, true>(f, g, out, batch, n, stride_f, stride_g, cap, ws, ws_bytes, dev_flags, stream)
+                    : run_typed<double, false>(f, g, out, batch, n, stride_f, stride_g, cap, ws, ws_bytes, dev_flags, stream);
     case RTC_I64:
       return deconv ? run_i64<true>(f, g, out, batch, n, stride_f, stride_g, cap, ws, dev_flags, stream)
                     : run_i64<false>(f, g, out, batch, n, stride_f, stride_g, cap, ws, dev_flags, stream);
