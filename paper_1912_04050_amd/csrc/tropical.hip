@@ -24,14 +24,17 @@
 // On the diagonal (s-block overlapping the tile) block j only concerns lanes > j, which run
 // under an exec mask; each lane's own R x R triangle is finished by a short epilogue.
 //
-// Packed 16-bit path (int32 convolution only).  A common slope rho is removed from both
-// operands (fd[s] = f[s] - rho*s, gd[i] = g[i] - rho*i, so f[s]+g[t-s] = fd[s]+gd[t-s] + rho*t).
+// Packed 16-bit path (int32 arithmetic only).  A common slope rho is removed from both
+// operands: with ad[s] = a[s] - rho*s and bd[i] = b'[i] -/+ rho*i (minus for the convolution,
+// plus for the deconvolution, whose window operand is the reversed, hence falling, f) every
+// candidate equals COMBINE(bd[t-s], ad[s]) +/- rho*t, so the trend is put back once per output.
 // Per chunk of 1024 steps the detrended values are re-based to the chunk / window minimum;
-// when range(fd chunk) + range(gd window) <= 65534 every candidate of that (tile, chunk) fits
+// when range(ad chunk) + range(bd window) <= 65534 every candidate of that (tile, chunk) fits
 // an unsigned 16-bit lane, and two output halves of a 2048-wide tile are computed at once with
-// v_pk_add_u16 (saturating) + v_pk_min_u16: one VALU instruction per pair-op instead of 1.5.
-// Positions that do not exist (window index < 0, s >= n) are staged as 0xFFFF, which saturates
-// and never wins, so the packed kernel needs neither exec masks nor a triangle epilogue.
+// v_pk_add_u16 + v_pk_min_u16 (v_pk_sub_u16 + v_pk_max_u16 for the deconvolution), both
+// saturating: one VALU instruction per pair-op instead of 1.5.
+// Positions that do not exist (window index < 0, s >= n) are staged as a poison value that
+// saturates and never wins, so the packed kernel needs neither exec masks nor a triangle epilogue.
 // The decision is made per (row, tile, chunk) from precomputed block minima / maxima; chunks
 // that do not qualify are done by the 32-bit kernel, which evaluates the same predicate and
 // skips exactly the chunks the packed kernel owns.  Results are exact in both cases.
@@ -112,13 +115,13 @@ constexpr uint32_t kPkPoison = 0xFFFFu;
 
 // Per-row auxiliary arrays of the packed path (all in the caller's workspace).
 struct PackAux {
-  const uint32_t* fpk;     // [B][npad]   re-based detrended f, both halves, 0xFFFFFFFF beyond n
-  const int32_t* fd;       // [B][npad]   detrended f
-  const int32_t* gd;       // [B][n]      detrended g
-  const int32_t* fb;       // [B][nchunk] chunk minimum of fd
-  const int32_t* fr;       // [B][nchunk] chunk range of fd
-  const int32_t* gmn;      // [B][nblk]   minimum of gd per block of kPkBlock
-  const int32_t* gmx;      // [B][nblk]   maximum
+  const uint32_t* apk;     // [B][npad]   re-based detrended uniform operand, both halves, 0xFFFFFFFF beyond n
+  const int32_t* ad;       // [B][npad]   detrended uniform operand
+  const int32_t* bd;       // [B][n]      detrended window operand, in window-index order
+  const int32_t* ab;       // [B][nchunk] chunk minimum of ad
+  const int32_t* ar;       // [B][nchunk] chunk range of ad
+  const int32_t* bmn;      // [B][nblk]   minimum of bd per block of kPkBlock
+  const int32_t* bmx;      // [B][nblk]   maximum
   const int32_t* rho;      // [B]         slope removed from both operands
   const int32_t* pack_ok;  // [B]         row is eligible for the packed path
   int32_t npad, nchunk, nblk;
@@ -134,15 +137,15 @@ __device__ __forceinline__ bool chunk_packable(const PackAux& x, int row, int T2
   lo = max(lo, 0);
   hi = min(hi, n);
   const int b0 = lo / kPkBlock, b1 = (hi - 1) / kPkBlock;
-  const int32_t* mnp = x.gmn + (int64_t)row * x.nblk;
-  const int32_t* mxp = x.gmx + (int64_t)row * x.nblk;
+  const int32_t* mnp = x.bmn + (int64_t)row * x.nblk;
+  const int32_t* mxp = x.bmx + (int64_t)row * x.nblk;
   int32_t mn = INT32_MAX, mx = INT32_MIN;
   for (int b = b0; b <= b1; ++b) {
     mn = min(mn, mnp[b]);
     mx = max(mx, mxp[b]);
   }
   *gb = mn;
-  const int64_t range = (int64_t)x.fr[(int64_t)row * x.nchunk + c] + ((int64_t)mx - (int64_t)mn);
+  const int64_t range = (int64_t)x.ar[(int64_t)row * x.nchunk + c] + ((int64_t)mx - (int64_t)mn);
   return range <= 65534;
 }
 
@@ -160,7 +163,7 @@ struct TropicalArgs {
   int32_t n_tiles;
   int32_t fold_width;   // work items launched per folded tile pair (see decode_item)
   int32_t seg;          // steps of s per segment, a multiple of the chunk length
-  int32_t use_aux;      // 1: operands are aux.fd / aux.gd, packed chunks are skipped, rho*t is added back
+  int32_t use_aux;      // 1: operands are aux.ad / aux.bd, packed chunks are skipped, rho*t is added back
   PackAux aux;
 };
 
@@ -231,8 +234,10 @@ __global__ __launch_bounds__(64) void tropical_kernel(const TropicalArgs p) {
   const int n = p.n;
   int row, t0, sa, sb;
   if (!decode_item<TL::kW>(p, &row, &t0, &sa, &sb)) return;
-  // the packed path exists for the int32 convolution only
-  const bool aux = std::is_same<T, int32_t>::value && !DECONV && p.use_aux != 0;
+  // aux mode (int32 only): the operands are the detrended rows prepared for the packed path;
+  // the window row is already stored in window-index order, so it is not reversed again
+  const bool aux = std::is_same<T, int32_t>::value && p.use_aux != 0;
+  const bool rev = DECONV && !aux;
 
   const T* __restrict__ arow = static_cast<const T*>(p.a) + (int64_t)row * p.stride_a;
   const T* __restrict__ brow = static_cast<const T*>(p.b) + (int64_t)row * p.stride_b;
@@ -255,7 +260,7 @@ __global__ __launch_bounds__(64) void tropical_kernel(const TropicalArgs p) {
     for (int e = lane; e < count; e += 64) {
       const int idx = gbase + e;
       T v = T(0);
-      if (idx >= 0 && idx < n) v = brow[DECONV ? n - 1 - idx : idx];
+      if (idx >= 0 && idx < n) v = brow[rev ? n - 1 - idx : idx];
       *reinterpret_cast<T*>(lds + (e / R) * TL::kSlotBytes + (e % R) * (int)sizeof(T)) = v;
     }
     __syncthreads();
@@ -300,7 +305,7 @@ __global__ __launch_bounds__(64) void tropical_kernel(const TropicalArgs p) {
 #pragma unroll
     for (int q = 0; q < R; ++q) {
       const int idx = min(q, n - 1);
-      b0[q] = brow[DECONV ? n - 1 - idx : idx];
+      b0[q] = brow[rev ? n - 1 - idx : idx];
     }
 #pragma unroll
     for (int k = 0; k < R; ++k) {
@@ -332,7 +337,7 @@ __global__ __launch_bounds__(64) void tropical_kernel(const TropicalArgs p) {
       if (aux) {
         // detrended domain: an untouched accumulator must not be shifted into a valid value
         if (av == SR::identity()) continue;
-        av = wrap_add(av, (T)(rho * t));
+        av = DECONV ? wrap_sub(av, (T)(rho * t)) : wrap_add(av, (T)(rho * t));
       }
       OutT v = (OutT)av;
       if (crow) v = sel_min(v, crow[ot]);
@@ -345,32 +350,44 @@ __global__ __launch_bounds__(64) void tropical_kernel(const TropicalArgs p) {
   }
 }
 
-// ---- packed 16-bit convolution kernel ------------------------------------------------------
+// ---- packed 16-bit kernel -----------------------------------------------------------------
 
 typedef unsigned short us2 __attribute__((ext_vector_type(2)));
 
-__device__ __forceinline__ uint32_t pk_min_addsat(uint32_t acc, uint32_t w, uint32_t u) {
-  const us2 s = __builtin_elementwise_add_sat(__builtin_bit_cast(us2, w), __builtin_bit_cast(us2, u));
-  return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(us2, acc), s));
-}
-
+// 16 steps against the 16 packed accumulators of a lane (window groups as in block_steps).
+// The combined values of a whole step are formed before the reductions so that no instruction
+// reads the result of its immediate predecessor (the compiler otherwise pads each pair with a
+// wait state).
+template <bool DECONV>
 __device__ __forceinline__ void block_steps_packed(uint32_t (&acc)[kPkR], const uint32_t (&u)[kPkR],
                                                    const uint32_t (&lo)[kPkR], const uint32_t (&hi)[kPkR]) {
 #pragma unroll
   for (int k = 0; k < kPkR; ++k) {
+    us2 s[kPkR];
 #pragma unroll
     for (int r = 0; r < kPkR; ++r) {
-      const uint32_t w = (r >= k) ? hi[r - k] : lo[kPkR + r - k];
-      acc[r] = pk_min_addsat(acc[r], w, u[k]);
+      const us2 w = __builtin_bit_cast(us2, (r >= k) ? hi[r - k] : lo[kPkR + r - k]);
+      const us2 uu = __builtin_bit_cast(us2, u[k]);
+      s[r] = DECONV ? __builtin_elementwise_sub_sat(w, uu) : __builtin_elementwise_add_sat(w, uu);
+    }
+#pragma unroll
+    for (int r = 0; r < kPkR; ++r) {
+      const us2 av = __builtin_bit_cast(us2, acc[r]);
+      acc[r] = __builtin_bit_cast(uint32_t, DECONV ? __builtin_elementwise_max(av, s[r])
+                                                   : __builtin_elementwise_min(av, s[r]));
     }
   }
 }
 
-// One wave owns 2048 outputs: the low 16 bits of every packed register belong to output
-// t0 + 16*lane + r, the high 16 bits to output t0 + 1024 + 16*lane + r.  Only chunks for
-// which chunk_packable() holds are processed; all results merge into out with atomic min.
-template <typename OutT>
-__global__ __launch_bounds__(64) void packed_conv_kernel(const TropicalArgs p) {
+// One wave owns 2048 outputs of the triangular product: the low 16 bits of every packed
+// register belong to output t0 + 16*lane + r, the high 16 bits to output t0 + 1024 + 16*lane + r.
+// Only chunks for which chunk_packable() holds are processed; results merge into out with
+// atomic min / max.
+//   convolution:   lane value = (bd - gb) + (ad - ab); poison 0xFFFF (saturating add, min)
+//   deconvolution: lane value = (bd - gb) + ar + 1 - (ad - ab) >= 1; poison 0 for the window,
+//                  0xFFFF for the uniform operand (saturating subtract gives 0, max ignores it)
+template <typename OutT, bool DECONV>
+__global__ __launch_bounds__(64) void packed_kernel(const TropicalArgs p) {
   using TL = Tile<int32_t, kPkR>;
   __shared__ __align__(16) unsigned char lds[TL::kSlots * TL::kSlotBytes];
   const int lane = threadIdx.x;
@@ -379,13 +396,17 @@ __global__ __launch_bounds__(64) void packed_conv_kernel(const TropicalArgs p) {
   if (!decode_item<kPkW>(p, &row, &t0, &sa, &sb)) return;
   const PackAux& x = p.aux;
   if (x.pack_ok[row] == 0) return;
-  const uint32_t* __restrict__ fpk = x.fpk + (int64_t)row * x.npad;
-  const int32_t* __restrict__ gd = x.gd + (int64_t)row * n;
-  const int32_t* __restrict__ fb = x.fb + (int64_t)row * x.nchunk;
+  const uint32_t* __restrict__ apk = x.apk + (int64_t)row * x.npad;
+  const int32_t* __restrict__ bd = x.bd + (int64_t)row * n;
+  const int32_t* __restrict__ ab = x.ab + (int64_t)row * x.nchunk;
+  const int32_t* __restrict__ ar = x.ar + (int64_t)row * x.nchunk;
+  constexpr int32_t kIdent = DECONV ? INT32_MIN : INT32_MAX;
+  constexpr uint32_t kWinPoison = DECONV ? 0u : kPkPoison;   // staged for window positions that do not exist
+  constexpr uint32_t kAccPoison = DECONV ? 0u : kPkPoison;   // a 16-bit lane that saw no existing candidate
 
   int32_t acc_lo[kPkR], acc_hi[kPkR];
 #pragma unroll
-  for (int r = 0; r < kPkR; ++r) { acc_lo[r] = INT32_MAX; acc_hi[r] = INT32_MAX; }
+  for (int r = 0; r < kPkR; ++r) { acc_lo[r] = kIdent; acc_hi[r] = kIdent; }
 
   for (int sc = sa; sc < sb; sc += kPkChunk) {
     int32_t gb;
@@ -395,19 +416,20 @@ __global__ __launch_bounds__(64) void packed_conv_kernel(const TropicalArgs p) {
     const int nblk = (ce - sc + kPkR - 1) / kPkR;
     const int gbase = t0 - (sc + nblk * kPkR);
     const int count = (64 + nblk) * kPkR;
+    const uint32_t lift = DECONV ? (uint32_t)ar[c] + 1u : 0u;
     __syncthreads();
     for (int e = lane; e < count; e += 64) {
       const int il = gbase + e, ih = il + kPkHalf;
-      uint32_t vl = kPkPoison, vh = kPkPoison;
-      if (il >= 0 && il < n) vl = min((uint32_t)gd[il] - (uint32_t)gb, kPkPoison);
-      if (ih >= 0 && ih < n) vh = min((uint32_t)gd[ih] - (uint32_t)gb, kPkPoison);
+      uint32_t vl = kWinPoison, vh = kWinPoison;
+      if (il >= 0 && il < n) vl = min((uint32_t)bd[il] - (uint32_t)gb + lift, kPkPoison);
+      if (ih >= 0 && ih < n) vh = min((uint32_t)bd[ih] - (uint32_t)gb + lift, kPkPoison);
       *reinterpret_cast<uint32_t*>(lds + (e / kPkR) * TL::kSlotBytes + (e % kPkR) * 4) = vl | (vh << 16);
     }
     __syncthreads();
 
     uint32_t acc[kPkR];
 #pragma unroll
-    for (int r = 0; r < kPkR; ++r) acc[r] = 0xFFFFFFFFu;
+    for (int r = 0; r < kPkR; ++r) acc[r] = kAccPoison * 0x10001u;
     uint32_t w0[kPkR], w1[kPkR];
     load_group<uint32_t, kPkR>(w0, lds, lane + nblk);
     for (int i = 0; i < nblk; i += 2) {
@@ -416,31 +438,34 @@ __global__ __launch_bounds__(64) void packed_conv_kernel(const TropicalArgs p) {
         load_group<uint32_t, kPkR>(w1, lds, lane + nblk - i - 1);
         uint32_t u[kPkR];
 #pragma unroll
-        for (int k = 0; k < kPkR; ++k) u[k] = fpk[s0 + k];
-        block_steps_packed(acc, u, w1, w0);
+        for (int k = 0; k < kPkR; ++k) u[k] = apk[s0 + k];
+        block_steps_packed<DECONV>(acc, u, w1, w0);
       }
       if (i + 1 < nblk) {
         const int s0 = sc + (i + 1) * kPkR;
         load_group<uint32_t, kPkR>(w0, lds, lane + nblk - i - 2);
         uint32_t u[kPkR];
 #pragma unroll
-        for (int k = 0; k < kPkR; ++k) u[k] = fpk[s0 + k];
-        block_steps_packed(acc, u, w0, w1);
+        for (int k = 0; k < kPkR; ++k) u[k] = apk[s0 + k];
+        block_steps_packed<DECONV>(acc, u, w0, w1);
       }
     }
-    // fold the chunk: a 16-bit lane that still holds 0xFFFF saw no existing candidate
-    const uint32_t cb = (uint32_t)fb[c] + (uint32_t)gb;
+    // fold the chunk into the 32-bit accumulators (detrended domain, wrap-around arithmetic:
+    // every folded value is a true candidate, which fits)
+    const uint32_t cb = DECONV ? (uint32_t)gb - (uint32_t)ab[c] - lift : (uint32_t)ab[c] + (uint32_t)gb;
 #pragma unroll
     for (int r = 0; r < kPkR; ++r) {
       const uint32_t vl = acc[r] & 0xFFFFu, vh = acc[r] >> 16;
-      const int32_t cl = vl != kPkPoison ? (int32_t)(cb + vl) : INT32_MAX;
-      const int32_t ch = vh != kPkPoison ? (int32_t)(cb + vh) : INT32_MAX;
-      acc_lo[r] = min(acc_lo[r], cl);
-      acc_hi[r] = min(acc_hi[r], ch);
+      const int32_t cl = vl != kAccPoison ? (int32_t)(cb + vl) : kIdent;
+      const int32_t ch = vh != kAccPoison ? (int32_t)(cb + vh) : kIdent;
+      acc_lo[r] = DECONV ? max(acc_lo[r], cl) : min(acc_lo[r], cl);
+      acc_hi[r] = DECONV ? max(acc_hi[r], ch) : min(acc_hi[r], ch);
     }
   }
 
   OutT* __restrict__ orow = static_cast<OutT*>(p.out) + (int64_t)row * n;
+  const OutT* __restrict__ crow =
+      p.cap ? static_cast<const OutT*>(p.cap) + (int64_t)row * n : nullptr;
   const int32_t rho = x.rho[row];
   int32_t* xp = reinterpret_cast<int32_t*>(lds);
 #pragma unroll
@@ -454,7 +479,12 @@ __global__ __launch_bounds__(64) void packed_conv_kernel(const TropicalArgs p) {
       const int xo = r * 64 + lane;
       const int t = t0 + half * kPkHalf + xo;
       const int32_t av = xp[xo + xo / kPkR];
-      if (t < n && av != INT32_MAX) atomic_min(&orow[t], (OutT)wrap_add(av, rho * t));
+      if (t < n && av != kIdent) {
+        const int ot = DECONV ? n - 1 - t : t;
+        OutT v = (OutT)(DECONV ? wrap_sub(av, rho * t) : wrap_add(av, rho * t));
+        if (crow) v = sel_min(v, crow[ot]);
+        if (DECONV) atomic_max(&orow[ot], v); else atomic_min(&orow[ot], v);
+      }
     }
   }
 }
@@ -523,8 +553,9 @@ __global__ __launch_bounds__(1024) void probe_kernel(const T* __restrict__ f, in
         const T lim = (T)1 << 29;
         const bool ok = fmin >= -lim && fmax < lim && gmin >= -lim && gmax < lim;
         pack_ok[row] = ok ? 1 : 0;
-        const T g0 = gr[0], g1 = gr[n - 1];
-        rho[row] = (ok && n > 1 && g1 > g0) ? (int32_t)((g1 - g0) / (T)(n - 1)) : 0;
+        // slope of the window operand: g for the convolution, f for the deconvolution
+        const T w0 = deconv ? fr[0] : gr[0], w1 = deconv ? fr[n - 1] : gr[n - 1];
+        rho[row] = (ok && n > 1 && w1 > w0) ? (int32_t)((w1 - w0) / (T)(n - 1)) : 0;
       }
     }
   }
@@ -541,49 +572,52 @@ __device__ __forceinline__ int32_t wave_max(int32_t v) {
   return v;
 }
 
-// Prepares the packed path for one (row, chunk of 1024 indices): detrends both operands,
-// re-bases the chunk of f to its minimum and packs it into both halves, and records the chunk
-// range of f and the minima / maxima of g per block of 256.
-__global__ __launch_bounds__(1024) void prep_kernel(const int32_t* __restrict__ f, int64_t stride_f,
-                                                    const int32_t* __restrict__ g, int64_t stride_g, int n,
-                                                    int npad, int nchunk, int nblk,
+// Prepares the packed path for one (row, chunk of 1024 indices): detrends both operands
+// (a = uniform operand, b = window operand, stored in window-index order, i.e. reversed for the
+// deconvolution), re-bases the chunk of a to its minimum and packs it into both halves, and
+// records the chunk range of a and the minima / maxima of b per block of 256.
+__global__ __launch_bounds__(1024) void prep_kernel(const int32_t* __restrict__ a, int64_t stride_a,
+                                                    const int32_t* __restrict__ b, int64_t stride_b, int n,
+                                                    bool deconv, int npad, int nchunk, int nblk,
                                                     const int32_t* __restrict__ rho,
-                                                    uint32_t* __restrict__ fpk, int32_t* __restrict__ fd,
-                                                    int32_t* __restrict__ gd, int32_t* __restrict__ fb,
-                                                    int32_t* __restrict__ fr, int32_t* __restrict__ gmn,
-                                                    int32_t* __restrict__ gmx) {
-  __shared__ int32_t s_fmn[16], s_fmx[16], s_gmn[16], s_gmx[16];
+                                                    uint32_t* __restrict__ apk, int32_t* __restrict__ ad,
+                                                    int32_t* __restrict__ bd, int32_t* __restrict__ ab,
+                                                    int32_t* __restrict__ ar, int32_t* __restrict__ bmn,
+                                                    int32_t* __restrict__ bmx) {
+  __shared__ int32_t s_amn[16], s_amx[16], s_bmn[16], s_bmx[16];
   const int row = blockIdx.x / nchunk;
   const int c = blockIdx.x % nchunk;
   const int i = c * kPkChunk + threadIdx.x;
   const int32_t r = rho[row];
   const bool valid = i < n;
-  const int32_t fdv = valid ? wrap_sub(f[(int64_t)row * stride_f + i], r * i) : 0;
-  const int32_t gdv = valid ? wrap_sub(g[(int64_t)row * stride_g + i], r * i) : 0;
-  const int32_t fmn = wave_min(valid ? fdv : INT32_MAX), fmx = wave_max(valid ? fdv : INT32_MIN);
-  const int32_t gmn_w = wave_min(valid ? gdv : INT32_MAX), gmx_w = wave_max(valid ? gdv : INT32_MIN);
+  const int32_t adv = valid ? wrap_sub(a[(int64_t)row * stride_a + i], r * i) : 0;
+  int32_t bdv = 0;
+  if (valid) bdv = deconv ? wrap_add(b[(int64_t)row * stride_b + (n - 1 - i)], r * i)
+                          : wrap_sub(b[(int64_t)row * stride_b + i], r * i);
+  const int32_t amn = wave_min(valid ? adv : INT32_MAX), amx = wave_max(valid ? adv : INT32_MIN);
+  const int32_t bmn_w = wave_min(valid ? bdv : INT32_MAX), bmx_w = wave_max(valid ? bdv : INT32_MIN);
   const int wave = threadIdx.x >> 6;
-  if ((threadIdx.x & 63) == 0) { s_fmn[wave] = fmn; s_fmx[wave] = fmx; s_gmn[wave] = gmn_w; s_gmx[wave] = gmx_w; }
+  if ((threadIdx.x & 63) == 0) { s_amn[wave] = amn; s_amx[wave] = amx; s_bmn[wave] = bmn_w; s_bmx[wave] = bmx_w; }
   __syncthreads();
   int32_t cmn = INT32_MAX, cmx = INT32_MIN;
 #pragma unroll
-  for (int w = 0; w < 16; ++w) { cmn = min(cmn, s_fmn[w]); cmx = max(cmx, s_fmx[w]); }
-  fpk[(int64_t)row * npad + i] = valid ? min((uint32_t)fdv - (uint32_t)cmn, kPkPoison) * 0x10001u : 0xFFFFFFFFu;
-  fd[(int64_t)row * npad + i] = fdv;
-  if (valid) gd[(int64_t)row * n + i] = gdv;
+  for (int w = 0; w < 16; ++w) { cmn = min(cmn, s_amn[w]); cmx = max(cmx, s_amx[w]); }
+  apk[(int64_t)row * npad + i] = valid ? min((uint32_t)adv - (uint32_t)cmn, kPkPoison) * 0x10001u : 0xFFFFFFFFu;
+  ad[(int64_t)row * npad + i] = adv;
+  if (valid) bd[(int64_t)row * n + i] = bdv;
   if (threadIdx.x == 0) {
-    fb[(int64_t)row * nchunk + c] = cmn;
+    ab[(int64_t)row * nchunk + c] = cmn;
     const int64_t range = (int64_t)cmx - (int64_t)cmn;
-    fr[(int64_t)row * nchunk + c] = (int32_t)(range < 0x7fffffffLL ? range : 0x7fffffffLL);
+    ar[(int64_t)row * nchunk + c] = (int32_t)(range < 0x7fffffffLL ? range : 0x7fffffffLL);
   }
   if ((threadIdx.x & (kPkBlock - 1)) == 0) {
     const int j = c * (kPkChunk / kPkBlock) + threadIdx.x / kPkBlock;
     if (j < nblk) {
       int32_t mn = INT32_MAX, mx = INT32_MIN;
 #pragma unroll
-      for (int w = 0; w < kPkBlock / 64; ++w) { mn = min(mn, s_gmn[wave + w]); mx = max(mx, s_gmx[wave + w]); }
-      gmn[(int64_t)row * nblk + j] = mn;
-      gmx[(int64_t)row * nblk + j] = mx;
+      for (int w = 0; w < kPkBlock / 64; ++w) { mn = min(mn, s_bmn[wave + w]); mx = max(mx, s_bmx[wave + w]); }
+      bmn[(int64_t)row * nblk + j] = mn;
+      bmx[(int64_t)row * nblk + j] = mx;
     }
   }
 }
@@ -671,7 +705,7 @@ int run_product(const T* a, int64_t stride_a, const T* b, int64_t stride_b, OutT
 // Layout of the packed path's arrays inside the workspace.
 struct PackLayout {
   int64_t npad, nchunk, nblk;
-  size_t off_fpk, off_fd, off_gd, off_fb, off_fr, off_gmn, off_gmx, off_rho, off_ok, bytes;
+  size_t off_apk, off_ad, off_bd, off_ab, off_ar, off_bmn, off_bmx, off_rho, off_ok, bytes;
 };
 
 PackLayout pack_layout(int64_t batch, int64_t n) {
@@ -681,55 +715,58 @@ PackLayout pack_layout(int64_t batch, int64_t n) {
   L.nblk = (n + kPkBlock - 1) / kPkBlock;
   size_t o = 0;
   auto take = [&](size_t elems) { const size_t at = o; o += (elems * 4 + 255) / 256 * 256; return at; };
-  L.off_fpk = take((size_t)batch * L.npad);
-  L.off_fd = take((size_t)batch * L.npad);
-  L.off_gd = take((size_t)batch * n);
-  L.off_fb = take((size_t)batch * L.nchunk);
-  L.off_fr = take((size_t)batch * L.nchunk);
-  L.off_gmn = take((size_t)batch * L.nblk);
-  L.off_gmx = take((size_t)batch * L.nblk);
+  L.off_apk = take((size_t)batch * L.npad);
+  L.off_ad = take((size_t)batch * L.npad);
+  L.off_bd = take((size_t)batch * n);
+  L.off_ab = take((size_t)batch * L.nchunk);
+  L.off_ar = take((size_t)batch * L.nchunk);
+  L.off_bmn = take((size_t)batch * L.nblk);
+  L.off_bmx = take((size_t)batch * L.nblk);
   L.off_rho = take((size_t)batch);
   L.off_ok = take((size_t)batch);
   L.bytes = o;
   return L;
 }
 
-// int32 convolution with the packed fast path.  f32 / g32 are int32 rows (the caller's own,
-// or the narrowed copies of int64 rows); pack_ok / rho were written by the probe.  `sel`
-// (optional) restricts both kernels to rows with sel[row] == 1.
-template <typename OutT>
-int run_conv_packed(const int32_t* f32, int64_t stride_f, const int32_t* g32, int64_t stride_g, OutT* out,
-                    const int32_t* sel, int64_t batch, int64_t n, char* wsp, const PackLayout& L,
-                    hipStream_t stream) {
+// int32 product with the packed fast path.  f32 / g32 are int32 rows (the caller's own,
+// or the narrowed copies of int64 rows); pack_ok / rho were written by the probe and the output
+// is already filled with the identity.  `sel` (optional) restricts both kernels to rows with
+// sel[row] == 1.
+template <typename OutT, bool DECONV>
+int run_packed(const int32_t* f32, int64_t stride_f, const int32_t* g32, int64_t stride_g, OutT* out,
+               const OutT* cap, const int32_t* sel, int64_t batch, int64_t n, char* wsp, const PackLayout& L,
+               hipStream_t stream) {
   PackAux aux;
-  aux.fpk = reinterpret_cast<uint32_t*>(wsp + L.off_fpk);
-  aux.fd = reinterpret_cast<int32_t*>(wsp + L.off_fd);
-  aux.gd = reinterpret_cast<int32_t*>(wsp + L.off_gd);
-  aux.fb = reinterpret_cast<int32_t*>(wsp + L.off_fb);
-  aux.fr = reinterpret_cast<int32_t*>(wsp + L.off_fr);
-  aux.gmn = reinterpret_cast<int32_t*>(wsp + L.off_gmn);
-  aux.gmx = reinterpret_cast<int32_t*>(wsp + L.off_gmx);
+  aux.apk = reinterpret_cast<uint32_t*>(wsp + L.off_apk);
+  aux.ad = reinterpret_cast<int32_t*>(wsp + L.off_ad);
+  aux.bd = reinterpret_cast<int32_t*>(wsp + L.off_bd);
+  aux.ab = reinterpret_cast<int32_t*>(wsp + L.off_ab);
+  aux.ar = reinterpret_cast<int32_t*>(wsp + L.off_ar);
+  aux.bmn = reinterpret_cast<int32_t*>(wsp + L.off_bmn);
+  aux.bmx = reinterpret_cast<int32_t*>(wsp + L.off_bmx);
   aux.rho = reinterpret_cast<int32_t*>(wsp + L.off_rho);
   aux.pack_ok = reinterpret_cast<int32_t*>(wsp + L.off_ok);
   aux.npad = (int32_t)L.npad; aux.nchunk = (int32_t)L.nchunk; aux.nblk = (int32_t)L.nblk;
   if (batch * L.nchunk > 0x7fffffffLL) return RTC_ERR_SHAPE;
-  hipLaunchKernelGGL(prep_kernel, dim3((uint32_t)(batch * L.nchunk)), dim3(1024), 0, stream, f32, stride_f, g32,
-                     stride_g, (int)n, (int)L.npad, (int)L.nchunk, (int)L.nblk, aux.rho,
-                     const_cast<uint32_t*>(aux.fpk), const_cast<int32_t*>(aux.fd), const_cast<int32_t*>(aux.gd),
-                     const_cast<int32_t*>(aux.fb), const_cast<int32_t*>(aux.fr), const_cast<int32_t*>(aux.gmn),
-                     const_cast<int32_t*>(aux.gmx));
+  // uniform operand: f for the convolution, g for the deconvolution; window operand: the other
+  hipLaunchKernelGGL(prep_kernel, dim3((uint32_t)(batch * L.nchunk)), dim3(1024), 0, stream,
+                     DECONV ? g32 : f32, DECONV ? stride_g : stride_f, DECONV ? f32 : g32,
+                     DECONV ? stride_f : stride_g, (int)n, DECONV, (int)L.npad, (int)L.nchunk, (int)L.nblk,
+                     aux.rho, const_cast<uint32_t*>(aux.apk), const_cast<int32_t*>(aux.ad),
+                     const_cast<int32_t*>(aux.bd), const_cast<int32_t*>(aux.ab), const_cast<int32_t*>(aux.ar),
+                     const_cast<int32_t*>(aux.bmn), const_cast<int32_t*>(aux.bmx));
   const Plan pl = make_plan(batch, n, kPkW, kPkChunk);
   if (pl.items > 0x7fffffffLL) return RTC_ERR_SHAPE;
   TropicalArgs args = {};
-  args.out = out; args.sel = sel; args.sel_want = 1;
+  args.out = out; args.cap = cap; args.sel = sel; args.sel_want = 1;
   args.n = (int32_t)n; args.batch = (int32_t)batch;
   args.n_tiles = pl.n_tiles; args.fold_width = pl.fold_width; args.seg = pl.seg;
   args.use_aux = 1; args.aux = aux;
-  hipLaunchKernelGGL(packed_conv_kernel<OutT>, dim3((uint32_t)pl.items), dim3(64), 0, stream, args);
+  hipLaunchKernelGGL((packed_kernel<OutT, DECONV>), dim3((uint32_t)pl.items), dim3(64), 0, stream, args);
   if (hip_ok() != RTC_OK) return RTC_ERR_HIP;
   // the 32-bit kernel works on the detrended rows and skips the chunks done above
-  return run_product<int32_t, OutT, false>(aux.fd, L.npad, aux.gd, n, out, nullptr, sel, 1, batch, n, stream,
-                                           true, true, &aux);
+  return run_product<int32_t, OutT, DECONV>(aux.ad, L.npad, aux.bd, n, out, cap, sel, 1, batch, n, stream,
+                                            true, true, &aux);
 }
 
 template <typename T, bool DECONV>
@@ -741,18 +778,19 @@ int run_typed(const void* f, const void* g, void* out, int64_t batch, int64_t n,
   const T* b = static_cast<const T*>(DECONV ? f : g);
   const int64_t sa = DECONV ? stride_g : stride_f;
   const int64_t sb = DECONV ? stride_f : stride_g;
-  if constexpr (std::is_same<T, int32_t>::value && !DECONV) {
+  if constexpr (std::is_same<T, int32_t>::value) {
     const PackLayout L = pack_layout(batch, n);
-    if (ws != nullptr && ws_bytes >= L.bytes && cap == nullptr) {
+    if (ws != nullptr && ws_bytes >= L.bytes) {
       char* wsp = static_cast<char*>(ws);
       hipLaunchKernelGGL(probe_kernel<int32_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,
                          static_cast<const int32_t*>(f), stride_f, static_cast<const int32_t*>(g), stride_g,
-                         (int)n, false, (int32_t*)nullptr, (int32_t*)nullptr, (int32_t*)nullptr,
+                         (int)n, DECONV, (int32_t*)nullptr, (int32_t*)nullptr, (int32_t*)nullptr,
                          reinterpret_cast<int32_t*>(wsp + L.off_ok), reinterpret_cast<int32_t*>(wsp + L.off_rho),
                          dev_flags);
-      launch_fill<int32_t, false>(static_cast<int32_t*>(out), batch * n, stream);
-      return run_conv_packed<int32_t>(static_cast<const int32_t*>(f), stride_f, static_cast<const int32_t*>(g),
-                                      stride_g, static_cast<int32_t*>(out), nullptr, batch, n, wsp, L, stream);
+      launch_fill<int32_t, DECONV>(static_cast<int32_t*>(out), batch * n, stream);
+      return run_packed<int32_t, DECONV>(static_cast<const int32_t*>(f), stride_f,
+                                         static_cast<const int32_t*>(g), stride_g, static_cast<int32_t*>(out),
+                                         static_cast<const int32_t*>(cap), nullptr, batch, n, wsp, L, stream);
     }
   }
   if (dev_flags != nullptr && std::numeric_limits<T>::is_integer) {
@@ -779,23 +817,15 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
   int32_t* ok = g32 + batch * n;
   char* wsp = static_cast<char*>(ws) + narrow_bytes(batch, n);
   const PackLayout L = pack_layout(batch, n);
-  const bool packed = !DECONV && cap == nullptr;
   hipLaunchKernelGGL(probe_kernel<int64_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,
                      static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g,
-                     (int)n, DECONV, f32, g32, ok,
-                     packed ? reinterpret_cast<int32_t*>(wsp + L.off_ok) : (int32_t*)nullptr,
-                     packed ? reinterpret_cast<int32_t*>(wsp + L.off_rho) : (int32_t*)nullptr, dev_flags);
+                     (int)n, DECONV, f32, g32, ok, reinterpret_cast<int32_t*>(wsp + L.off_ok),
+                     reinterpret_cast<int32_t*>(wsp + L.off_rho), dev_flags);
   // Several kernels see every row; the selector makes each row run in exactly one family.
   // The output is filled once with the identity, before all of them.
   launch_fill<int64_t, DECONV>(static_cast<int64_t*>(out), batch * n, stream);
-  int rc;
-  if (packed) {
-    rc = run_conv_packed<int64_t>(f32, n, g32, n, static_cast<int64_t*>(out), ok, batch, n, wsp, L, stream);
-  } else {
-    rc = run_product<int32_t, int64_t, DECONV>(DECONV ? g32 : f32, n, DECONV ? f32 : g32, n,
-                                               static_cast<int64_t*>(out), static_cast<const int64_t*>(cap), ok,
-                                               1, batch, n, stream, true, true, nullptr);
-  }
+  int rc = run_packed<int64_t, DECONV>(f32, n, g32, n, static_cast<int64_t*>(out),
+                                       static_cast<const int64_t*>(cap), ok, batch, n, wsp, L, stream);
   if (rc != RTC_OK) return rc;
   const int64_t* a = static_cast<const int64_t*>(DECONV ? g : f);
   const int64_t* b = static_cast<const int64_t*>(DECONV ? f : g);

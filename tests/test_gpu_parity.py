@@ -90,6 +90,58 @@ def test_products_broadcast_rows(rtc, dtype):
     assert np.array_equal(host(rtc.rtc_maxplus_deconv(dev(g), dev(f))), oracle.maxplus_deconv(g, f))
 
 
+def _both_paths(rtc, f, g, tag):
+    """int32 products with the workspace (packed 16-bit chunks where they qualify) and with a
+    token workspace (32-bit kernel only): both must equal the oracle."""
+    say(tag, f.dtype, f.shape)
+    want_c, want_d = oracle.minplus_conv(f, g), oracle.maxplus_deconv(f, g)
+    tiny = torch.empty(16, dtype=torch.uint8, device="cuda")
+    for ws in (None, tiny):
+        assert np.array_equal(host(rtc.rtc_minplus_conv(dev(f), dev(g), ws=ws)), want_c), (tag, ws is None)
+        assert np.array_equal(host(rtc.rtc_maxplus_deconv(dev(f), dev(g), ws=ws)), want_d), (tag, ws is None)
+
+
+def test_packed_path_mixed_chunks(rtc):
+    """Rows whose chunks partly qualify for the packed kernel and partly fall back."""
+    rng = np.random.default_rng(21)
+    n = 7000
+    # slow rows (every chunk packs), steep rows (none packs), rows with jumps (some chunks pack)
+    slow = np.cumsum(rng.integers(0, 5, (2, n)), axis=1)
+    steep = np.cumsum(rng.integers(0, 3000, (2, n)), axis=1)
+    jumpy = np.cumsum(rng.integers(0, 5, (2, n)), axis=1)
+    jumpy[:, 1500:] += 200000
+    jumpy[:, 4100:] += 90000
+    wild = np.concatenate([rng.integers(-40000, 40000, (1, n)), rng.integers(-9000, 9000, (1, n))])
+    for dt in (np.int32, np.int64):
+        f = np.concatenate([slow, steep, jumpy, wild]).astype(dt)
+        g = np.concatenate([slow[::-1], slow, jumpy[::-1], wild[::-1]]).astype(dt)
+        if dt == np.int32:
+            _both_paths(rtc, f, g, "packed mixed")
+            _both_paths(rtc, g, f, "packed mixed swapped")
+        else:
+            check_products(rtc, f, g, "packed mixed int64")
+
+
+def test_packed_path_value_limits(rtc):
+    """Values at the edge of the packed path's eligibility (|v| < 2^29) and beyond it."""
+    n = 3000
+    base = np.cumsum(np.random.default_rng(22).integers(0, 7, (4, n)), axis=1)
+    f = base.copy()
+    g = base[::-1].copy()
+    f[0] += 2**29 - 1 - f[0].max()      # just inside
+    f[1] += 2**29                       # just outside: 32-bit kernel only
+    g[2] -= 2**29                       # negative, inside
+    g[3] = -g[3] - 5                    # falling rows: slope estimate clamps to 0
+    _both_paths(rtc, f.astype(np.int32), g.astype(np.int32), "packed limits")
+
+
+def test_packed_path_ragged_sizes(rtc):
+    for n in (1, 17, 255, 256, 257, 1023, 1024, 1025, 2047, 2048, 2049, 3071, 3073, 5121):
+        f = wl.random_monotone(23, 2 * n, 2, n, np.int32, max_inc=40)
+        g = wl.random_monotone(23, 2 * n + 1, 2, n, np.int32, max_inc=25)
+        _both_paths(rtc, f, g, f"packed ragged n={n}")
+
+
 def test_int64_wide_and_mixed_rows(rtc):
     """Rows beyond the 32-bit range take the 64-bit kernel; rows inside take the narrowed one."""
     n = 1300
