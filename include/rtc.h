@@ -60,11 +60,14 @@ typedef enum {
 /* Min-plus convolution, out[b][t] = min_{0<=s<=t} f[b][s] + g[b][t-s], t = 0..n-1.
  * Truncated horizon: samples beyond n-1 do not exist, the output has n samples.
  * f, g: [batch] rows with element strides stride_f / stride_g.  out: [batch][n].
- * ws / ws_bytes: device scratch of at least rtc_workspace_bytes(RTC_OP_CONV, ...) bytes.
- *   RTC_I32 / RTC_F64 need it only when dev_flags != NULL (range probe); RTC_I64 always
- *   (the rows are probed and, when every value lies in [-2^30, 2^30), convolved in 32-bit
- *   arithmetic on narrowed copies -- exact, because every candidate then fits -- and widened
- *   on store; other rows take the 64-bit kernel).
+ * ws / ws_bytes: device scratch, rtc_workspace_bytes(RTC_OP_CONV, ...) bytes.
+ *   RTC_F64 needs none.  RTC_I64 requires it: the rows are probed and, when every value lies
+ *   in [-2^30, 2^30), convolved in 32-bit arithmetic on narrowed copies -- exact, because every
+ *   candidate then fits -- and widened on store; other rows take the 64-bit kernel.
+ *   For RTC_I32 it is optional: with a workspace of the full size the library also uses its
+ *   packed 16-bit kernel on every (tile, chunk of 1024 steps) whose detrended value ranges fit
+ *   16 bits (same exact results, up to 1.5x faster); with ws == NULL or a smaller size only the
+ *   32-bit kernel runs.  The packed kernel applies to int64 rows narrowed as above, too.
  * Exact: there is one correct bit pattern per output (values only, no argmin). */
 int rtc_minplus_conv(const void* f, const void* g, void* out, int64_t batch, int64_t n,
                      int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* ws, size_t ws_bytes,
@@ -144,6 +147,18 @@ const char* rtc_strerror(int status);
  * compute-unit count, nominal engine clock in kHz, LDS bytes per workgroup.
  * Any pointer may be NULL.  Host pointers. */
 int rtc_device_info(int* cu_count, int* clock_khz, int* lds_bytes);
+
+/* Measurement aid (not part of the curve algebra).  While enabled, every product kernel that
+ * rtc_minplus_conv / rtc_maxplus_deconv / rtc_gpc_step launch is bracketed by a HIP event pair
+ * on the call's stream (up to 1024 kernels; helper kernels such as probes and fills are not
+ * recorded).  rtc_profile_enable(1) clears the record and starts, rtc_profile_enable(0) stops.
+ * rtc_profile_read waits for the recorded kernels and writes up to max_entries (kind, duration
+ * in milliseconds) pairs to the HOST arrays kinds / ms; it returns the number written or a
+ * negative status.  kind = RTC_PROFILE_KIND(dtype of the arithmetic, packed 16-bit kernel?,
+ * deconvolution?).  Not thread-safe. */
+#define RTC_PROFILE_KIND(dtype, packed, deconv) ((dtype) * 4 + (packed) * 2 + (deconv))
+int rtc_profile_enable(int on);
+int rtc_profile_read(int max_entries, int* kinds, float* ms);
 
 #ifdef __cplusplus
 }

@@ -34,6 +34,10 @@ int launch_max_hdev(const void* alpha, const void* beta, int32_t* out, int64_t b
 int launch_max_vdev(const void* alpha, const void* beta, void* out, int64_t batch, int64_t n, int dt,
                     hipStream_t stream);
 
+// Optional kernel timing (profile.hip).  kind = RTC_PROFILE_KIND(dtype, packed, deconv).
+void prof_begin(int kind, hipStream_t stream);
+void prof_end(hipStream_t stream);
+
 inline int hip_ok() { return hipGetLastError() == hipSuccess ? RTC_OK : RTC_ERR_HIP; }
 
 }  // namespace rtc

@@ -116,7 +116,6 @@ constexpr uint32_t kPkPoison = 0xFFFFu;
 // Per-row auxiliary arrays of the packed path (all in the caller's workspace).
 struct PackAux {
   const uint32_t* apk;     // [B][npad]   re-based detrended uniform operand, both halves, 0xFFFFFFFF beyond n
-  const int32_t* ad;       // [B][npad]   detrended uniform operand
   const int32_t* bd;       // [B][n]      detrended window operand, in window-index order
   const int32_t* ab;       // [B][nchunk] chunk minimum of ad
   const int32_t* ar;       // [B][nchunk] chunk range of ad
@@ -163,7 +162,7 @@ struct TropicalArgs {
   int32_t n_tiles;
   int32_t fold_width;   // work items launched per folded tile pair (see decode_item)
   int32_t seg;          // steps of s per segment, a multiple of the chunk length
-  int32_t use_aux;      // 1: operands are aux.ad / aux.bd, packed chunks are skipped, rho*t is added back
+  int32_t use_aux;      // 1: skip the chunks that the packed items of the same launch own (see aux)
   PackAux aux;
 };
 
@@ -172,9 +171,9 @@ struct TropicalArgs {
 // every folded pair owns about the same number of items and few launched workgroups are idle.
 // Returns false when this workgroup has nothing to do.
 template <int W>
-__device__ __forceinline__ bool decode_item(const TropicalArgs& p, int* row, int* t0, int* sa, int* sb) {
+__device__ __forceinline__ bool decode_item(const TropicalArgs& p, uint32_t item, int* row, int* t0, int* sa,
+                                            int* sb) {
   const int n = p.n;
-  uint32_t item = blockIdx.x;
   *row = item % (uint32_t)p.batch;
   item /= (uint32_t)p.batch;
   const int j = item % (uint32_t)p.fold_width;
@@ -224,20 +223,22 @@ __device__ __forceinline__ void block_steps(T (&acc)[R], const T (&u)[R], const 
   }
 }
 
+template <typename T, int R> constexpr int lds_bytes() { return Tile<T, R>::kSlots * Tile<T, R>::kSlotBytes; }
+
+// Body of one work item of the generic (32-bit / 64-bit / fp64) product.  `lds` is the
+// workgroup's window buffer of lds_bytes<T, R>() bytes.
 template <typename T, typename OutT, bool DECONV, int R, bool ATOMIC>
-__global__ __launch_bounds__(64) void tropical_kernel(const TropicalArgs p) {
+__device__ __forceinline__ void tropical_body(const TropicalArgs& p, unsigned char* lds, uint32_t item) {
   using SR = Semiring<T, DECONV>;
   using TL = Tile<T, R>;
-  __shared__ __align__(16) unsigned char lds[TL::kSlots * TL::kSlotBytes];
 
   const int lane = threadIdx.x;
   const int n = p.n;
   int row, t0, sa, sb;
-  if (!decode_item<TL::kW>(p, &row, &t0, &sa, &sb)) return;
-  // aux mode (int32 only): the operands are the detrended rows prepared for the packed path;
-  // the window row is already stored in window-index order, so it is not reversed again
+  if (!decode_item<TL::kW>(p, item, &row, &t0, &sa, &sb)) return;
+  // with the packed path active (int32 only) the chunks owned by packed items are skipped
   const bool aux = std::is_same<T, int32_t>::value && p.use_aux != 0;
-  const bool rev = DECONV && !aux;
+  constexpr bool rev = DECONV;
 
   const T* __restrict__ arow = static_cast<const T*>(p.a) + (int64_t)row * p.stride_a;
   const T* __restrict__ brow = static_cast<const T*>(p.b) + (int64_t)row * p.stride_b;
@@ -318,10 +319,9 @@ __global__ __launch_bounds__(64) void tropical_kernel(const TropicalArgs p) {
   OutT* __restrict__ orow = static_cast<OutT*>(p.out) + (int64_t)row * n;
   const OutT* __restrict__ crow =
       p.cap ? static_cast<const OutT*>(p.cap) + (int64_t)row * n : nullptr;
-  const int32_t rho = aux ? p.aux.rho[row] : 0;
   // Transpose the accumulators through LDS (lane-major [lane][R+1] -> output-major) so that
   // the 64 lanes of one store / atomic instruction touch 64 consecutive outputs.
-  static_assert(64 * (R + 1) * sizeof(T) <= sizeof(lds), "transpose buffer must fit the window buffer");
+  static_assert(64 * (R + 1) * sizeof(T) <= lds_bytes<T, R>(), "transpose buffer must fit the window buffer");
   T* xp = reinterpret_cast<T*>(lds);
   __syncthreads();
 #pragma unroll
@@ -333,12 +333,8 @@ __global__ __launch_bounds__(64) void tropical_kernel(const TropicalArgs p) {
     const int t = t0 + x;
     if (t < n) {
       const int ot = DECONV ? n - 1 - t : t;
-      T av = xp[x + x / R];
-      if (aux) {
-        // detrended domain: an untouched accumulator must not be shifted into a valid value
-        if (av == SR::identity()) continue;
-        av = DECONV ? wrap_sub(av, (T)(rho * t)) : wrap_add(av, (T)(rho * t));
-      }
+      const T av = xp[x + x / R];
+      if (ATOMIC && av == SR::identity()) continue;   // this item saw no candidate of that output
       OutT v = (OutT)av;
       if (crow) v = sel_min(v, crow[ot]);
       if (ATOMIC) {
@@ -387,13 +383,12 @@ __device__ __forceinline__ void block_steps_packed(uint32_t (&acc)[kPkR], const 
 //   deconvolution: lane value = (bd - gb) + ar + 1 - (ad - ab) >= 1; poison 0 for the window,
 //                  0xFFFF for the uniform operand (saturating subtract gives 0, max ignores it)
 template <typename OutT, bool DECONV>
-__global__ __launch_bounds__(64) void packed_kernel(const TropicalArgs p) {
+__device__ __forceinline__ void packed_body(const TropicalArgs& p, unsigned char* lds, uint32_t item) {
   using TL = Tile<int32_t, kPkR>;
-  __shared__ __align__(16) unsigned char lds[TL::kSlots * TL::kSlotBytes];
   const int lane = threadIdx.x;
   const int n = p.n;
   int row, t0, sa, sb;
-  if (!decode_item<kPkW>(p, &row, &t0, &sa, &sb)) return;
+  if (!decode_item<kPkW>(p, item, &row, &t0, &sa, &sb)) return;
   const PackAux& x = p.aux;
   if (x.pack_ok[row] == 0) return;
   const uint32_t* __restrict__ apk = x.apk + (int64_t)row * x.npad;
@@ -489,6 +484,24 @@ __global__ __launch_bounds__(64) void packed_kernel(const TropicalArgs p) {
   }
 }
 
+template <typename T, typename OutT, bool DECONV, int R, bool ATOMIC>
+__global__ __launch_bounds__(64) void tropical_kernel(const TropicalArgs p) {
+  __shared__ __align__(16) unsigned char lds[lds_bytes<T, R>()];
+  tropical_body<T, OutT, DECONV, R, ATOMIC>(p, lds, blockIdx.x);
+}
+
+// One launch for an int32 product with the packed path: the first n_packed workgroups are
+// items of the packed kernel, the rest are items of the 32-bit kernel (which skip the chunks
+// the packed items own).  Issuing both kinds together keeps the machine full whatever share of
+// the chunks qualifies for 16 bits.
+template <typename OutT, bool DECONV>
+__global__ __launch_bounds__(64) void fused_kernel(const TropicalArgs pk, const TropicalArgs pg,
+                                                   uint32_t n_packed) {
+  __shared__ __align__(16) unsigned char lds[lds_bytes<int32_t, kPkR>()];
+  if (blockIdx.x < n_packed) packed_body<OutT, DECONV>(pk, lds, blockIdx.x);
+  else tropical_body<int32_t, OutT, DECONV, kPkR, true>(pg, lds, blockIdx.x - n_packed);
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void fill_kernel(T* __restrict__ dst, int64_t count, T value) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -555,7 +568,17 @@ __global__ __launch_bounds__(1024) void probe_kernel(const T* __restrict__ f, in
         pack_ok[row] = ok ? 1 : 0;
         // slope of the window operand: g for the convolution, f for the deconvolution
         const T w0 = deconv ? fr[0] : gr[0], w1 = deconv ? fr[n - 1] : gr[n - 1];
-        rho[row] = (ok && n > 1 && w1 > w0) ? (int32_t)((w1 - w0) / (T)(n - 1)) : 0;
+        const T u0 = deconv ? gr[0] : fr[0], u1 = deconv ? gr[n - 1] : fr[n - 1];
+        int32_t r = 0;
+        if (ok && n > 1) {
+          r = w1 > w0 ? (int32_t)((w1 - w0) / (T)(n - 1)) : 0;
+          // performance heuristic: when the two average slopes differ so much that a chunk of the
+          // uniform operand cannot stay inside 16 bits after detrending, do not prepare the row
+          const int64_t ru = (int64_t)((u1 - u0) / (T)(n - 1));
+          const int64_t diff = ru > r ? ru - r : r - ru;
+          if (diff * kPkChunk > 50000) pack_ok[row] = 0;
+        }
+        rho[row] = r;
       }
     }
   }
@@ -580,12 +603,13 @@ __global__ __launch_bounds__(1024) void prep_kernel(const int32_t* __restrict__ 
                                                     const int32_t* __restrict__ b, int64_t stride_b, int n,
                                                     bool deconv, int npad, int nchunk, int nblk,
                                                     const int32_t* __restrict__ rho,
-                                                    uint32_t* __restrict__ apk, int32_t* __restrict__ ad,
-                                                    int32_t* __restrict__ bd, int32_t* __restrict__ ab,
+                                                    const int32_t* __restrict__ pack_ok,
+                                                    uint32_t* __restrict__ apk, int32_t* __restrict__ bd, int32_t* __restrict__ ab,
                                                     int32_t* __restrict__ ar, int32_t* __restrict__ bmn,
                                                     int32_t* __restrict__ bmx) {
   __shared__ int32_t s_amn[16], s_amx[16], s_bmn[16], s_bmx[16];
   const int row = blockIdx.x / nchunk;
+  if (pack_ok[row] == 0) return;   // nothing of this row will be read
   const int c = blockIdx.x % nchunk;
   const int i = c * kPkChunk + threadIdx.x;
   const int32_t r = rho[row];
@@ -603,7 +627,6 @@ __global__ __launch_bounds__(1024) void prep_kernel(const int32_t* __restrict__ 
 #pragma unroll
   for (int w = 0; w < 16; ++w) { cmn = min(cmn, s_amn[w]); cmx = max(cmx, s_amx[w]); }
   apk[(int64_t)row * npad + i] = valid ? min((uint32_t)adv - (uint32_t)cmn, kPkPoison) * 0x10001u : 0xFFFFFFFFu;
-  ad[(int64_t)row * npad + i] = adv;
   if (valid) bd[(int64_t)row * n + i] = bdv;
   if (threadIdx.x == 0) {
     ab[(int64_t)row * nchunk + c] = cmn;
@@ -619,6 +642,42 @@ __global__ __launch_bounds__(1024) void prep_kernel(const int32_t* __restrict__ 
       bmn[(int64_t)row * nblk + j] = mn;
       bmx[(int64_t)row * nblk + j] = mx;
     }
+  }
+}
+
+// Performance heuristic only (results are exact either way): samples up to 64 x 64
+// (tile, chunk) pairs of a row, weighted by the number of chunks they stand for, and switches the
+// packed path off for the row when less than half of its chunk-tiles would qualify -- a mostly
+// unpackable row is better left to the 32-bit kernel alone.
+__global__ __launch_bounds__(256) void decide_kernel(PackAux x, int n, int32_t* __restrict__ pack_ok) {
+  __shared__ float s_yes[4], s_all[4];
+  const int row = blockIdx.x;
+  const int n_t2 = (n + kPkW - 1) / kPkW;
+  float yes = 0.f, all = 0.f;
+  if (pack_ok[row] != 0) {
+    for (int j = threadIdx.x; j < 64 * 64; j += 256) {
+      const int it = j / 64, ic = j % 64;
+      const int nt = min(n_t2, 64);
+      if (it >= nt) continue;
+      const int T2 = (int)((int64_t)it * n_t2 / nt);
+      const int nc = (min((T2 + 1) * kPkW, n) + kPkChunk - 1) / kPkChunk;   // chunks of this tile
+      const int ns = min(nc, 64);
+      if (ic >= ns) continue;
+      const int c = (int)((int64_t)ic * nc / ns);
+      const float weight = (float)nc / (float)ns * ((float)n_t2 / (float)nt);
+      int32_t gb;
+      all += weight;
+      if (chunk_packable(x, row, T2, c, n, &gb)) yes += weight;
+    }
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) { yes += __shfl_xor(yes, off); all += __shfl_xor(all, off); }
+  if ((threadIdx.x & 63) == 0) { s_yes[threadIdx.x >> 6] = yes; s_all[threadIdx.x >> 6] = all; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    yes = s_yes[0] + s_yes[1] + s_yes[2] + s_yes[3];
+    all = s_all[0] + s_all[1] + s_all[2] + s_all[3];
+    if (2.f * yes < all) pack_ok[row] = 0;
   }
 }
 
@@ -691,21 +750,25 @@ int run_product(const T* a, int64_t stride_a, const T* b, int64_t stride_b, OutT
   args.n = (int32_t)n; args.batch = (int32_t)batch;
   args.n_tiles = pl.n_tiles; args.fold_width = pl.fold_width; args.seg = pl.seg;
   if (aux != nullptr) { args.use_aux = 1; args.aux = *aux; }
+  constexpr int dtype_code = std::is_same<T, int32_t>::value ? RTC_I32 : std::is_same<T, int64_t>::value ? RTC_I64 : RTC_F64;
   if (pl.atomic || force_atomic) {
     if (!prefilled) launch_fill<OutT, DECONV>(out, batch * n, stream);
+    prof_begin(RTC_PROFILE_KIND(dtype_code, 0, DECONV ? 1 : 0), stream);
     hipLaunchKernelGGL((tropical_kernel<T, OutT, DECONV, R, true>), dim3((uint32_t)pl.items), dim3(64), 0,
                        stream, args);
   } else {
+    prof_begin(RTC_PROFILE_KIND(dtype_code, 0, DECONV ? 1 : 0), stream);
     hipLaunchKernelGGL((tropical_kernel<T, OutT, DECONV, R, false>), dim3((uint32_t)pl.items), dim3(64), 0,
                        stream, args);
   }
+  prof_end(stream);
   return hip_ok();
 }
 
 // Layout of the packed path's arrays inside the workspace.
 struct PackLayout {
   int64_t npad, nchunk, nblk;
-  size_t off_apk, off_ad, off_bd, off_ab, off_ar, off_bmn, off_bmx, off_rho, off_ok, bytes;
+  size_t off_apk, off_bd, off_ab, off_ar, off_bmn, off_bmx, off_rho, off_ok, bytes;
 };
 
 PackLayout pack_layout(int64_t batch, int64_t n) {
@@ -716,7 +779,6 @@ PackLayout pack_layout(int64_t batch, int64_t n) {
   size_t o = 0;
   auto take = [&](size_t elems) { const size_t at = o; o += (elems * 4 + 255) / 256 * 256; return at; };
   L.off_apk = take((size_t)batch * L.npad);
-  L.off_ad = take((size_t)batch * L.npad);
   L.off_bd = take((size_t)batch * n);
   L.off_ab = take((size_t)batch * L.nchunk);
   L.off_ar = take((size_t)batch * L.nchunk);
@@ -738,7 +800,6 @@ int run_packed(const int32_t* f32, int64_t stride_f, const int32_t* g32, int64_t
                hipStream_t stream) {
   PackAux aux;
   aux.apk = reinterpret_cast<uint32_t*>(wsp + L.off_apk);
-  aux.ad = reinterpret_cast<int32_t*>(wsp + L.off_ad);
   aux.bd = reinterpret_cast<int32_t*>(wsp + L.off_bd);
   aux.ab = reinterpret_cast<int32_t*>(wsp + L.off_ab);
   aux.ar = reinterpret_cast<int32_t*>(wsp + L.off_ar);
@@ -752,21 +813,28 @@ int run_packed(const int32_t* f32, int64_t stride_f, const int32_t* g32, int64_t
   hipLaunchKernelGGL(prep_kernel, dim3((uint32_t)(batch * L.nchunk)), dim3(1024), 0, stream,
                      DECONV ? g32 : f32, DECONV ? stride_g : stride_f, DECONV ? f32 : g32,
                      DECONV ? stride_f : stride_g, (int)n, DECONV, (int)L.npad, (int)L.nchunk, (int)L.nblk,
-                     aux.rho, const_cast<uint32_t*>(aux.apk), const_cast<int32_t*>(aux.ad),
-                     const_cast<int32_t*>(aux.bd), const_cast<int32_t*>(aux.ab), const_cast<int32_t*>(aux.ar),
+                     aux.rho, aux.pack_ok, const_cast<uint32_t*>(aux.apk), const_cast<int32_t*>(aux.bd), const_cast<int32_t*>(aux.ab), const_cast<int32_t*>(aux.ar),
                      const_cast<int32_t*>(aux.bmn), const_cast<int32_t*>(aux.bmx));
-  const Plan pl = make_plan(batch, n, kPkW, kPkChunk);
-  if (pl.items > 0x7fffffffLL) return RTC_ERR_SHAPE;
-  TropicalArgs args = {};
-  args.out = out; args.cap = cap; args.sel = sel; args.sel_want = 1;
-  args.n = (int32_t)n; args.batch = (int32_t)batch;
-  args.n_tiles = pl.n_tiles; args.fold_width = pl.fold_width; args.seg = pl.seg;
-  args.use_aux = 1; args.aux = aux;
-  hipLaunchKernelGGL((packed_kernel<OutT, DECONV>), dim3((uint32_t)pl.items), dim3(64), 0, stream, args);
-  if (hip_ok() != RTC_OK) return RTC_ERR_HIP;
-  // the 32-bit kernel works on the detrended rows and skips the chunks done above
-  return run_product<int32_t, OutT, DECONV>(aux.ad, L.npad, aux.bd, n, out, cap, sel, 1, batch, n, stream,
-                                            true, true, &aux);
+  hipLaunchKernelGGL(decide_kernel, dim3((uint32_t)batch), dim3(256), 0, stream, aux, (int)n,
+                     const_cast<int32_t*>(aux.pack_ok));
+  const Plan pk = make_plan(batch, n, kPkW, kPkChunk);
+  const Plan pg = make_plan<int32_t>(batch, n);
+  if (pk.items + pg.items > 0x7fffffffLL) return RTC_ERR_SHAPE;
+  TropicalArgs ak = {};
+  ak.out = out; ak.cap = cap; ak.sel = sel; ak.sel_want = 1;
+  ak.n = (int32_t)n; ak.batch = (int32_t)batch;
+  ak.n_tiles = pk.n_tiles; ak.fold_width = pk.fold_width; ak.seg = pk.seg;
+  ak.use_aux = 1; ak.aux = aux;
+  // the 32-bit items work on the caller's rows and skip the chunks owned by the packed items
+  TropicalArgs ag = ak;
+  ag.a = DECONV ? g32 : f32; ag.stride_a = DECONV ? stride_g : stride_f;
+  ag.b = DECONV ? f32 : g32; ag.stride_b = DECONV ? stride_f : stride_g;
+  ag.n_tiles = pg.n_tiles; ag.fold_width = pg.fold_width; ag.seg = pg.seg;
+  prof_begin(RTC_PROFILE_KIND(RTC_I32, 1, DECONV ? 1 : 0), stream);
+  hipLaunchKernelGGL((fused_kernel<OutT, DECONV>), dim3((uint32_t)(pk.items + pg.items)), dim3(64), 0, stream,
+                     ak, ag, (uint32_t)pk.items);
+  prof_end(stream);
+  return hip_ok();
 }
 
 template <typename T, bool DECONV>
@@ -780,7 +848,8 @@ int run_typed(const void* f, const void* g, void* out, int64_t batch, int64_t n,
   const int64_t sb = DECONV ? stride_f : stride_g;
   if constexpr (std::is_same<T, int32_t>::value) {
     const PackLayout L = pack_layout(batch, n);
-    if (ws != nullptr && ws_bytes >= L.bytes) {
+    // tiny problems are launch-bound: the extra kernels of the packed path would only cost
+    if (ws != nullptr && ws_bytes >= L.bytes && (double)batch * (double)n * (double)n >= 1073741824.0) {
       char* wsp = static_cast<char*>(ws);
       hipLaunchKernelGGL(probe_kernel<int32_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,
                          static_cast<const int32_t*>(f), stride_f, static_cast<const int32_t*>(g), stride_g,

@@ -115,6 +115,30 @@ def rtc_device_info():
     return {"cu_count": cu.value, "clock_khz": khz.value, "lds_bytes": lds.value}
 
 
+_lib.rtc_profile_enable.argtypes = [_int]
+_lib.rtc_profile_enable.restype = _int
+_lib.rtc_profile_read.argtypes = [_int, ctypes.POINTER(_int), ctypes.POINTER(ctypes.c_float)]
+_lib.rtc_profile_read.restype = _int
+
+
+def RTC_PROFILE_KIND(dtype_code: int, packed: int, deconv: int) -> int:
+    return dtype_code * 4 + packed * 2 + deconv
+
+
+def rtc_profile_enable(on: bool):
+    _check(_lib.rtc_profile_enable(1 if on else 0))
+
+
+def rtc_profile_read(max_entries: int = 1024):
+    """[(kind, milliseconds)] of the product kernels recorded since rtc_profile_enable(True)."""
+    kinds = (_int * max_entries)()
+    ms = (ctypes.c_float * max_entries)()
+    got = _lib.rtc_profile_read(max_entries, kinds, ms)
+    if got < 0:
+        raise RtcError(got)
+    return [(kinds[i], ms[i]) for i in range(got)]
+
+
 def _workspace(op, batch, n, dtype, device, ws):
     need = rtc_workspace_bytes(op, batch, n, dtype)
     if ws is None and need > 0:

@@ -37,7 +37,7 @@ def test_every_declared_symbol_is_exported(lib):
 def test_workspace_sizes_and_messages(lib):
     lib.rtc_workspace_bytes.restype = ctypes.c_size_t
     lib.rtc_workspace_bytes.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int]
-    assert lib.rtc_workspace_bytes(0, 4, 1000, 0) >= 3 * 4 * 1000 * 4   # packed-path arrays (optional)
+    assert lib.rtc_workspace_bytes(0, 4, 1000, 0) >= 2 * 4 * 1000 * 4   # packed-path arrays (optional)
     assert lib.rtc_workspace_bytes(0, 4, 1000, 2) == 0
     assert lib.rtc_workspace_bytes(1, 4, 1000, 1) >= 2 * 4 * 1000 * 4 + 16
     assert lib.rtc_workspace_bytes(2, 4, 1000, 0) >= 4 * 1000 * 4
