@@ -46,7 +46,7 @@ def parse():
 # HBM traffic of one launch of the dominant kernel on the headline workload, from two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by what the same counters read for a
 # plain 1 GiB device copy; see profiles/.  None for any other workload.
-HEADLINE_TRAFFIC_BYTES = None
+HEADLINE_TRAFFIC_BYTES = 593862317   # 38.4 MiB fetched + 528 MiB of atomic-merge writes (profiles/fused_kernel_headline_pmc.md)
 
 
 def headline_traffic(batch, n):
@@ -299,8 +299,8 @@ def main():
         kernel_times = rtc.rtc_profile_read()
         rtc.rtc_profile_enable(False)
     conv_call_ms = sum(a.elapsed_time(b) for a, b in conv_events) / len(conv_events)
-    kind_names = {rtc.RTC_PROFILE_KIND(0, 1, 0): "packed_kernel<min-plus>",
-                  rtc.RTC_PROFILE_KIND(0, 1, 1): "packed_kernel<max-plus>",
+    kind_names = {rtc.RTC_PROFILE_KIND(0, 1, 0): "fused_kernel<min-plus>",
+                  rtc.RTC_PROFILE_KIND(0, 1, 1): "fused_kernel<max-plus>",
                   rtc.RTC_PROFILE_KIND(0, 0, 0): "tropical_kernel<int32, min-plus>",
                   rtc.RTC_PROFILE_KIND(0, 0, 1): "tropical_kernel<int32, max-plus>",
                   rtc.RTC_PROFILE_KIND(1, 0, 0): "tropical_kernel<int64, min-plus>",
@@ -309,14 +309,14 @@ def main():
     for kind, ms in kernel_times:
         per_kind.setdefault(kind_names.get(kind, str(kind)), []).append(ms)
     kernels = {k: {"launches": len(v), "avg_ms": round(sum(v) / len(v), 4)} for k, v in per_kind.items()}
-    dom = per_kind.get("packed_kernel<min-plus>")
+    dom = per_kind.get("fused_kernel<min-plus>")
     conv_ms = sum(dom) / len(dom) if dom else conv_call_ms
     info = rtc.rtc_device_info()
     peak_ops = info["cu_count"] * 64 * info["clock_khz"] * 1e3   # int32 VALU lane-ops per second
     alg_ops = 2.0 * B * pair_ops_one                              # one add + one min per pair-op
     achieved = alg_ops / (conv_ms * 1e-3)
     roofline = {
-        "bound": "alu", "kernel": "packed_kernel<out int64, min-plus> (16-bit lanes, int32-exact)",
+        "bound": "alu", "kernel": "fused_kernel<out int64, min-plus> (packed 16-bit items + 32-bit items)",
         "achieved": round(achieved / 1e12, 4), "peak": round(peak_ops / 1e12, 4), "unit": "TOP/s",
         "frac": round(achieved / peak_ops, 4), "traffic": headline_traffic(B, N),
         "launch_ms": round(conv_ms, 4), "call_ms": round(conv_call_ms, 4),
@@ -326,8 +326,8 @@ def main():
         "note": "achieved counts 2 lane-ops (add + min) per pair-op by definition, over the kernel's own "
                 "HIP-event duration; peak = CUs x 64 lanes x clock. The kernel issues 1 VALU instruction per "
                 "pair-op (v_pk_add_u16 + v_pk_min_u16 serve two pair-ops), which is how frac exceeds 1; "
-                "call_ms is the whole rtc_minplus_conv call (probe, fill, prepare, packed kernel, 32-bit and "
-                "64-bit kernels that find nothing left to do)",
+                "call_ms is the whole rtc_minplus_conv call (probe, fill, prepare, decide, fused kernel, and the "
+                "64-bit kernel that finds nothing left to do)",
     }
 
     # ---- sampled parity + CPU baseline (the oracle as it stands, on this machine's host cores) --
