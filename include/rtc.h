@@ -137,6 +137,12 @@ int rtc_max_hdev(const void* alpha, const void* beta, int32_t* out, int64_t batc
 int rtc_max_vdev(const void* alpha, const void* beta, void* out, int64_t batch, int64_t n,
                  rtc_dtype dt, void* hip_stream);
 
+/* Planner knob: the packed 16-bit path of the int32 / narrowed-int64 products is used when a
+ * workspace is present and batch * n^2 >= this value (default 2^30; smaller problems are
+ * launch-bound and take the 32-bit kernel alone).  0 uses it for every size.  Results do not
+ * depend on it.  Process-wide, not thread-safe. */
+int rtc_set_packed_min_work(double batch_times_n_squared);
+
 /* Bytes of device workspace an operator needs for the given shape (0 on invalid input). */
 size_t rtc_workspace_bytes(int op, int64_t batch, int64_t n, rtc_dtype dt);
 

@@ -156,6 +156,12 @@ size_t rtc_workspace_bytes(int op, int64_t batch, int64_t n, rtc_dtype dt) {
   }
 }
 
+int rtc_set_packed_min_work(double batch_times_n_squared) {
+  if (!(batch_times_n_squared >= 0.0)) return RTC_ERR_SHAPE;
+  rtc::g_packed_min_work = batch_times_n_squared;
+  return RTC_OK;
+}
+
 const char* rtc_strerror(int status) {
   switch (status) {
     case RTC_OK: return "ok";

@@ -21,6 +21,7 @@ int launch_tropical(bool deconv, const void* f, const void* g, void* out, int64_
                     int64_t stride_f, int64_t stride_g, int dt, const void* cap, void* ws,
                     size_t ws_bytes, int32_t* dev_flags, hipStream_t stream);
 size_t tropical_workspace_bytes(int64_t batch, int64_t n, int dt);
+extern double g_packed_min_work;  // planner knob, see rtc_set_packed_min_work
 
 // HBM-bound curve kernels (curve_ops.hip).
 int launch_pseudo_inverse(const void* f, int64_t n, const void* x, int64_t m, int32_t* out,

@@ -837,6 +837,16 @@ int run_packed(const int32_t* f32, int64_t stride_f, const int32_t* g32, int64_t
   return hip_ok();
 }
 
+}  // namespace
+
+double g_packed_min_work = 1073741824.0;   // batch * n^2 from which the packed path is used
+
+namespace {
+
+bool packed_worthwhile(int64_t batch, int64_t n) {
+  return (double)batch * (double)n * (double)n >= g_packed_min_work;
+}
+
 template <typename T, bool DECONV>
 int run_typed(const void* f, const void* g, void* out, int64_t batch, int64_t n, int64_t stride_f,
               int64_t stride_g, const void* cap, void* ws, size_t ws_bytes, int32_t* dev_flags,
@@ -849,7 +859,7 @@ int run_typed(const void* f, const void* g, void* out, int64_t batch, int64_t n,
   if constexpr (std::is_same<T, int32_t>::value) {
     const PackLayout L = pack_layout(batch, n);
     // tiny problems are launch-bound: the extra kernels of the packed path would only cost
-    if (ws != nullptr && ws_bytes >= L.bytes && (double)batch * (double)n * (double)n >= 1073741824.0) {
+    if (ws != nullptr && ws_bytes >= L.bytes && packed_worthwhile(batch, n)) {
       char* wsp = static_cast<char*>(ws);
       hipLaunchKernelGGL(probe_kernel<int32_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,
                          static_cast<const int32_t*>(f), stride_f, static_cast<const int32_t*>(g), stride_g,
@@ -893,8 +903,15 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
   // Several kernels see every row; the selector makes each row run in exactly one family.
   // The output is filled once with the identity, before all of them.
   launch_fill<int64_t, DECONV>(static_cast<int64_t*>(out), batch * n, stream);
-  int rc = run_packed<int64_t, DECONV>(f32, n, g32, n, static_cast<int64_t*>(out),
-                                       static_cast<const int64_t*>(cap), ok, batch, n, wsp, L, stream);
+  int rc;
+  if (packed_worthwhile(batch, n)) {
+    rc = run_packed<int64_t, DECONV>(f32, n, g32, n, static_cast<int64_t*>(out),
+                                     static_cast<const int64_t*>(cap), ok, batch, n, wsp, L, stream);
+  } else {
+    rc = run_product<int32_t, int64_t, DECONV>(DECONV ? g32 : f32, n, DECONV ? f32 : g32, n,
+                                               static_cast<int64_t*>(out), static_cast<const int64_t*>(cap), ok,
+                                               1, batch, n, stream, true, true, nullptr);
+  }
   if (rc != RTC_OK) return rc;
   const int64_t* a = static_cast<const int64_t*>(DECONV ? g : f);
   const int64_t* b = static_cast<const int64_t*>(DECONV ? f : g);

@@ -125,6 +125,14 @@ def RTC_PROFILE_KIND(dtype_code: int, packed: int, deconv: int) -> int:
     return dtype_code * 4 + packed * 2 + deconv
 
 
+_lib.rtc_set_packed_min_work.argtypes = [ctypes.c_double]
+_lib.rtc_set_packed_min_work.restype = _int
+
+
+def rtc_set_packed_min_work(batch_times_n_squared: float):
+    _check(_lib.rtc_set_packed_min_work(float(batch_times_n_squared)))
+
+
 def rtc_profile_enable(on: bool):
     _check(_lib.rtc_profile_enable(1 if on else 0))
 

@@ -20,10 +20,14 @@ NP2T = {np.dtype(np.int32): torch.int32, np.dtype(np.int64): torch.int64, np.dty
 DTYPES = [np.int32, np.int64, np.float64]
 
 
-@pytest.fixture(scope="module")
-def rtc():
+@pytest.fixture(scope="module", params=["default-planner", "packed-at-every-size"])
+def rtc(request):
+    """Every test runs twice: with the default planner (small problems take the 32-bit kernel
+    alone) and with the packed 16-bit path forced on for every size that brings a workspace."""
     from paper_1912_04050_amd import rtc as mod
-    return mod
+    mod.rtc_set_packed_min_work(0.0 if request.param == "packed-at-every-size" else 2.0 ** 30)
+    yield mod
+    mod.rtc_set_packed_min_work(2.0 ** 30)
 
 
 def say(*a):
