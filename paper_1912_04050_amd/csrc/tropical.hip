@@ -51,6 +51,9 @@ namespace {
 #ifndef RTC_CHUNK_BLOCKS
 #define RTC_CHUNK_BLOCKS 64
 #endif
+#ifndef RTC_CHUNK_BLOCKS_WIDE
+#define RTC_CHUNK_BLOCKS_WIDE 32
+#endif
 #ifndef RTC_TARGET_ITEMS
 #define RTC_TARGET_ITEMS 65536
 #endif
@@ -99,7 +102,7 @@ __device__ __forceinline__ void atomic_max(double* p, double v) { atomicMax(p, v
 
 template <typename T, int R> struct Tile {
   static constexpr int kW = 64 * R;                          // outputs per wave
-  static constexpr int kChunk = RTC_CHUNK_BLOCKS * R;        // steps of s per staged window
+  static constexpr int kChunk = (sizeof(T) == 8 ? RTC_CHUNK_BLOCKS_WIDE : RTC_CHUNK_BLOCKS) * R;  // steps of s per staged window
   static constexpr int kSlotBytes = R * (int)sizeof(T) + 16; // one group of R values + skew
   static constexpr int kSlots = 64 + kChunk / R;
   static constexpr int kVec = 16 / (int)sizeof(T);           // elements per 16-byte LDS read
