@@ -37,7 +37,7 @@ extern "C" {
 
 typedef enum { RTC_I32 = 0, RTC_I64 = 1, RTC_F64 = 2 } rtc_dtype;
 typedef enum { RTC_INV_LOWER = 0, RTC_INV_UPPER = 1 } rtc_inv_mode;
-typedef enum { RTC_OP_CONV = 0, RTC_OP_DECONV = 1, RTC_OP_GPC = 2 } rtc_op;
+typedef enum { RTC_OP_CONV = 0, RTC_OP_DECONV = 1, RTC_OP_GPC = 2, RTC_OP_MAXCONV = 3, RTC_OP_MINDECONV = 4 } rtc_op;
 
 typedef enum {
   RTC_OK = 0,
@@ -78,6 +78,19 @@ int rtc_minplus_conv(const void* f, const void* g, void* out, int64_t batch, int
  * (This under-approximates the infinite-horizon supremum near the end of the horizon.)
  * Arguments as for rtc_minplus_conv; results may be negative. */
 int rtc_maxplus_deconv(const void* f, const void* g, void* out, int64_t batch, int64_t n,
+                       int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* ws, size_t ws_bytes,
+                       int32_t* dev_flags, void* hip_stream);
+
+/* The two dual products (max-plus algebra), same arguments, workspace rules and exactness:
+ *   rtc_maxplus_conv     out[b][t] = max_{0<=s<=t}     f[b][s]   + g[b][t-s]
+ *   rtc_minplus_deconv   out[b][t] = min_{0<=u<=n-1-t} f[b][t+u] - g[b][u]
+ * They are what the upper-service / lower-arrival side of a greedy processing component is
+ * written with ((beta^u - alpha^l) max-plus-deconvolved by 0, and so on); with g = 0 they
+ * reduce to a running maximum and a suffix minimum. */
+int rtc_maxplus_conv(const void* f, const void* g, void* out, int64_t batch, int64_t n,
+                     int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* ws, size_t ws_bytes,
+                     int32_t* dev_flags, void* hip_stream);
+int rtc_minplus_deconv(const void* f, const void* g, void* out, int64_t batch, int64_t n,
                        int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* ws, size_t ws_bytes,
                        int32_t* dev_flags, void* hip_stream);
 
@@ -161,8 +174,9 @@ int rtc_device_info(int* cu_count, int* clock_khz, int* lds_bytes);
  * rtc_profile_read waits for the recorded kernels and writes up to max_entries (kind, duration
  * in milliseconds) pairs to the HOST arrays kinds / ms; it returns the number written or a
  * negative status.  kind = RTC_PROFILE_KIND(dtype of the arithmetic, packed 16-bit kernel?,
- * deconvolution?).  Not thread-safe. */
-#define RTC_PROFILE_KIND(dtype, packed, deconv) ((dtype) * 4 + (packed) * 2 + (deconv))
+ * product), product = 0 min-plus convolution, 1 max-plus deconvolution, 2 max-plus convolution,
+ * 3 min-plus deconvolution.  Not thread-safe. */
+#define RTC_PROFILE_KIND(dtype, packed, product) ((dtype) * 8 + (packed) * 4 + (product))
 int rtc_profile_enable(int on);
 int rtc_profile_read(int max_entries, int* kinds, float* ms);
 

@@ -79,6 +79,14 @@ def maxplus_deconv(f, g):
     return _binary("oracle_maxplus_deconv", f, g)
 
 
+def maxplus_conv(f, g):
+    return _binary("oracle_maxplus_conv", f, g)
+
+
+def minplus_deconv(f, g):
+    return _binary("oracle_minplus_deconv", f, g)
+
+
 def product_at(f, g, t_idx, deconv: bool):
     """Selected outputs of f (x) g (deconv=False) or f (/) g (deconv=True) for one row pair."""
     f = np.ascontiguousarray(f).reshape(-1)

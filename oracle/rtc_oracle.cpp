@@ -14,6 +14,8 @@
 //   min-plus convolution     (f (x) g)[t] = min_{0<=s<=t} f[s] + g[t-s]
 //   max-plus deconvolution   (f (/) g)[t] = max_{0<=u<=n-1-t} f[t+u] - g[u]
 //                            (finite horizon: only pairs whose samples both exist)
+//   max-plus convolution     max_{0<=s<=t} f[s] + g[t-s]          (the two dual products)
+//   min-plus deconvolution   min_{0<=u<=n-1-t} f[t+u] - g[u]
 //   lower pseudo-inverse     min{k : f[k] >= x}, n if there is none
 //   upper pseudo-inverse     max{k : f[k] <= x}, -1 if there is none
 //   composition              out[D] = outer[clamp(inner[D], 0, n_outer-1)]
@@ -57,6 +59,32 @@ void deconv_one(const T* f, const T* g, T* out, int64_t n) {
     for (int64_t u = 1; u <= n - 1 - t; ++u) {
       T v = f[t + u] - g[u];
       if (v > m) m = v;
+    }
+    out[t] = m;
+  }
+}
+
+template <typename T>
+void maxconv_one(const T* f, const T* g, T* out, int64_t n) {
+#pragma omp parallel for schedule(dynamic, 64)
+  for (int64_t t = 0; t < n; ++t) {
+    T m = f[0] + g[t];
+    for (int64_t s = 1; s <= t; ++s) {
+      T v = f[s] + g[t - s];
+      if (v > m) m = v;
+    }
+    out[t] = m;
+  }
+}
+
+template <typename T>
+void mindeconv_one(const T* f, const T* g, T* out, int64_t n) {
+#pragma omp parallel for schedule(dynamic, 64)
+  for (int64_t t = 0; t < n; ++t) {
+    T m = f[t] - g[0];
+    for (int64_t u = 1; u <= n - 1 - t; ++u) {
+      T v = f[t + u] - g[u];
+      if (v < m) m = v;
     }
     out[t] = m;
   }
@@ -191,6 +219,17 @@ void conv_rows(const void* f, const void* g, void* out, int64_t batch, int64_t n
   }
 }
 
+template <typename T>
+void dual_rows(const void* f, const void* g, void* out, int64_t batch, int64_t n, int64_t sf,
+               int64_t sg, bool deconv) {
+  for (int64_t b = 0; b < batch; ++b) {
+    const T* fr = (const T*)f + b * sf;
+    const T* gr = (const T*)g + b * sg;
+    T* o = (T*)out + b * n;
+    if (deconv) mindeconv_one(fr, gr, o, n); else maxconv_one(fr, gr, o, n);
+  }
+}
+
 }  // namespace
 
 // dt: 0 = int32, 1 = int64, 2 = float64.  All pointers are host pointers; rows are
@@ -213,6 +252,24 @@ int oracle_maxplus_deconv(const void* f, const void* g, void* out, int64_t batch
   if (dt == 0) conv_rows<int32_t>(f, g, out, batch, n, stride_f, stride_g, true);
   else if (dt == 1) conv_rows<int64_t>(f, g, out, batch, n, stride_f, stride_g, true);
   else if (dt == 2) conv_rows<double>(f, g, out, batch, n, stride_f, stride_g, true);
+  else return -3;
+  return 0;
+}
+
+int oracle_maxplus_conv(const void* f, const void* g, void* out, int64_t batch, int64_t n,
+                        int64_t stride_f, int64_t stride_g, int dt) {
+  if (dt == 0) dual_rows<int32_t>(f, g, out, batch, n, stride_f, stride_g, false);
+  else if (dt == 1) dual_rows<int64_t>(f, g, out, batch, n, stride_f, stride_g, false);
+  else if (dt == 2) dual_rows<double>(f, g, out, batch, n, stride_f, stride_g, false);
+  else return -3;
+  return 0;
+}
+
+int oracle_minplus_deconv(const void* f, const void* g, void* out, int64_t batch, int64_t n,
+                          int64_t stride_f, int64_t stride_g, int dt) {
+  if (dt == 0) dual_rows<int32_t>(f, g, out, batch, n, stride_f, stride_g, true);
+  else if (dt == 1) dual_rows<int64_t>(f, g, out, batch, n, stride_f, stride_g, true);
+  else if (dt == 2) dual_rows<double>(f, g, out, batch, n, stride_f, stride_g, true);
   else return -3;
   return 0;
 }

@@ -39,7 +39,23 @@ int rtc_minplus_conv(const void* f, const void* g, void* out, int64_t batch, int
                      int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* ws, size_t ws_bytes,
                      int32_t* dev_flags, void* hip_stream) {
   if (int rc = check_product(f, g, out, batch, n, stride_f, stride_g, dt, ws, ws_bytes, dev_flags)) return rc;
-  return launch_tropical(false, f, g, out, batch, n, stride_f, stride_g, dt, nullptr, ws, ws_bytes,
+  return launch_tropical(RTC_OP_CONV, f, g, out, batch, n, stride_f, stride_g, dt, nullptr, ws, ws_bytes,
+                         dev_flags, static_cast<hipStream_t>(hip_stream));
+}
+
+int rtc_maxplus_conv(const void* f, const void* g, void* out, int64_t batch, int64_t n,
+                     int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* ws, size_t ws_bytes,
+                     int32_t* dev_flags, void* hip_stream) {
+  if (int rc = check_product(f, g, out, batch, n, stride_f, stride_g, dt, ws, ws_bytes, dev_flags)) return rc;
+  return launch_tropical(RTC_OP_MAXCONV, f, g, out, batch, n, stride_f, stride_g, dt, nullptr, ws, ws_bytes,
+                         dev_flags, static_cast<hipStream_t>(hip_stream));
+}
+
+int rtc_minplus_deconv(const void* f, const void* g, void* out, int64_t batch, int64_t n,
+                       int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* ws, size_t ws_bytes,
+                       int32_t* dev_flags, void* hip_stream) {
+  if (int rc = check_product(f, g, out, batch, n, stride_f, stride_g, dt, ws, ws_bytes, dev_flags)) return rc;
+  return launch_tropical(RTC_OP_MINDECONV, f, g, out, batch, n, stride_f, stride_g, dt, nullptr, ws, ws_bytes,
                          dev_flags, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -47,7 +63,7 @@ int rtc_maxplus_deconv(const void* f, const void* g, void* out, int64_t batch, i
                        int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* ws, size_t ws_bytes,
                        int32_t* dev_flags, void* hip_stream) {
   if (int rc = check_product(f, g, out, batch, n, stride_f, stride_g, dt, ws, ws_bytes, dev_flags)) return rc;
-  return launch_tropical(true, f, g, out, batch, n, stride_f, stride_g, dt, nullptr, ws, ws_bytes,
+  return launch_tropical(RTC_OP_DECONV, f, g, out, batch, n, stride_f, stride_g, dt, nullptr, ws, ws_bytes,
                          dev_flags, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -99,10 +115,10 @@ int rtc_gpc_step(const rtc_gpc_args* a, void* hip_stream) {
   const size_t c_bytes = ((size_t)batch * n * es + 255) / 256 * 256;
   void* sub_ws = c + c_bytes;
   const size_t sub_bytes = a->ws_bytes - c_bytes;
-  int rc = launch_tropical(false, a->alpha_u, a->beta_u, c, batch, n, n, n, a->dt, nullptr, sub_ws,
+  int rc = launch_tropical(RTC_OP_CONV, a->alpha_u, a->beta_u, c, batch, n, n, n, a->dt, nullptr, sub_ws,
                            sub_bytes, a->dev_flags, stream);
   if (rc != RTC_OK) return rc;
-  rc = launch_tropical(true, c, a->beta_l, a->alpha_u_out, batch, n, n, n, a->dt, a->beta_u, sub_ws,
+  rc = launch_tropical(RTC_OP_DECONV, c, a->beta_l, a->alpha_u_out, batch, n, n, n, a->dt, a->beta_u, sub_ws,
                        sub_bytes, a->dev_flags, stream);
   if (rc != RTC_OK) return rc;
   rc = launch_residual_service(a->beta_l, a->alpha_u, a->beta_l_out, batch, n, a->dt, stream);
@@ -148,6 +164,8 @@ size_t rtc_workspace_bytes(int op, int64_t batch, int64_t n, rtc_dtype dt) {
   switch (op) {
     case RTC_OP_CONV:
     case RTC_OP_DECONV:
+    case RTC_OP_MAXCONV:
+    case RTC_OP_MINDECONV:
       return prod;
     case RTC_OP_GPC:
       return ((size_t)batch * n * es + 255) / 256 * 256 + prod;

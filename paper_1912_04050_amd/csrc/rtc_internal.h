@@ -14,10 +14,10 @@ inline size_t elem_size(int dt) {
   return dt == RTC_I32 ? 4 : (dt == RTC_I64 || dt == RTC_F64) ? 8 : 0;
 }
 
-// Tropical product launchers (tropical.hip).  `deconv` selects max-plus deconvolution.
+// Tropical product launchers (tropical.hip).  `op` is RTC_OP_CONV, _DECONV, _MAXCONV or _MINDECONV.
 // `cap` (optional, dense [batch][n]) fuses out = min(out, cap) into the store, which is how
 // the greedy-processing-component step applies its final min with beta^u.
-int launch_tropical(bool deconv, const void* f, const void* g, void* out, int64_t batch, int64_t n,
+int launch_tropical(int op, const void* f, const void* g, void* out, int64_t batch, int64_t n,
                     int64_t stride_f, int64_t stride_g, int dt, const void* cap, void* ws,
                     size_t ws_bytes, int32_t* dev_flags, hipStream_t stream);
 size_t tropical_workspace_bytes(int64_t batch, int64_t n, int dt);
@@ -35,7 +35,7 @@ int launch_max_hdev(const void* alpha, const void* beta, int32_t* out, int64_t b
 int launch_max_vdev(const void* alpha, const void* beta, void* out, int64_t batch, int64_t n, int dt,
                     hipStream_t stream);
 
-// Optional kernel timing (profile.hip).  kind = RTC_PROFILE_KIND(dtype, packed, deconv).
+// Optional kernel timing (profile.hip).  kind = RTC_PROFILE_KIND(dtype, packed, product).
 void prof_begin(int kind, hipStream_t stream);
 void prof_end(hipStream_t stream);
 

@@ -87,10 +87,18 @@ __device__ __forceinline__ double sel_min(double a, double b) { return __builtin
 __device__ __forceinline__ double sel_max(double a, double b) { return __builtin_fmax(a, b); }
 
 // The semiring of one product: identity of REDUCE, COMBINE(window, uniform), REDUCE.
-template <typename T, bool DECONV> struct Semiring {
-  static __device__ __forceinline__ T identity() { return DECONV ? Lim<T>::lo() : Lim<T>::hi(); }
-  static __device__ __forceinline__ T combine(T w, T u) { return DECONV ? wrap_sub(w, u) : wrap_add(w, u); }
-  static __device__ __forceinline__ T reduce(T x, T y) { return DECONV ? sel_max(x, y) : sel_min(x, y); }
+// OP selects the product (the values of rtc_op for the four products):
+//   0 min-plus convolution    min_s f[s] + g[t-s]        2 max-plus convolution    max_s f[s] + g[t-s]
+//   1 max-plus deconvolution  max_u f[t+u] - g[u]        3 min-plus deconvolution  min_u f[t+u] - g[u]
+// op_sub: COMBINE subtracts and the window operand / output index are reversed (the two
+// deconvolutions); op_max: REDUCE is max.
+constexpr bool op_sub(int op) { return op == 1 || op == 3; }
+constexpr bool op_max(int op) { return op == 1 || op == 2; }
+
+template <typename T, int OP> struct Semiring {
+  static __device__ __forceinline__ T identity() { return op_max(OP) ? Lim<T>::lo() : Lim<T>::hi(); }
+  static __device__ __forceinline__ T combine(T w, T u) { return op_sub(OP) ? wrap_sub(w, u) : wrap_add(w, u); }
+  static __device__ __forceinline__ T reduce(T x, T y) { return op_max(OP) ? sel_max(x, y) : sel_min(x, y); }
 };
 
 __device__ __forceinline__ void atomic_min(int32_t* p, int32_t v) { atomicMin(p, v); }
@@ -230,9 +238,9 @@ template <typename T, int R> constexpr int lds_bytes() { return Tile<T, R>::kSlo
 
 // Body of one work item of the generic (32-bit / 64-bit / fp64) product.  `lds` is the
 // workgroup's window buffer of lds_bytes<T, R>() bytes.
-template <typename T, typename OutT, bool DECONV, int R, bool ATOMIC>
+template <typename T, typename OutT, int OP, int R, bool ATOMIC>
 __device__ __forceinline__ void tropical_body(const TropicalArgs& p, unsigned char* lds, uint32_t item) {
-  using SR = Semiring<T, DECONV>;
+  using SR = Semiring<T, OP>;
   using TL = Tile<T, R>;
 
   const int lane = threadIdx.x;
@@ -241,7 +249,7 @@ __device__ __forceinline__ void tropical_body(const TropicalArgs& p, unsigned ch
   if (!decode_item<TL::kW>(p, item, &row, &t0, &sa, &sb)) return;
   // with the packed path active (int32 only) the chunks owned by packed items are skipped
   const bool aux = std::is_same<T, int32_t>::value && p.use_aux != 0;
-  constexpr bool rev = DECONV;
+  constexpr bool rev = op_sub(OP);
 
   const T* __restrict__ arow = static_cast<const T*>(p.a) + (int64_t)row * p.stride_a;
   const T* __restrict__ brow = static_cast<const T*>(p.b) + (int64_t)row * p.stride_b;
@@ -335,13 +343,13 @@ __device__ __forceinline__ void tropical_body(const TropicalArgs& p, unsigned ch
     const int x = r * 64 + lane;          // output offset inside the tile
     const int t = t0 + x;
     if (t < n) {
-      const int ot = DECONV ? n - 1 - t : t;
+      const int ot = op_sub(OP) ? n - 1 - t : t;
       const T av = xp[x + x / R];
       if (ATOMIC && av == SR::identity()) continue;   // this item saw no candidate of that output
       OutT v = (OutT)av;
       if (crow) v = sel_min(v, crow[ot]);
       if (ATOMIC) {
-        if (DECONV) atomic_max(&orow[ot], v); else atomic_min(&orow[ot], v);
+        if (op_max(OP)) atomic_max(&orow[ot], v); else atomic_min(&orow[ot], v);
       } else {
         orow[ot] = v;
       }
@@ -357,7 +365,7 @@ typedef unsigned short us2 __attribute__((ext_vector_type(2)));
 // The combined values of a whole step are formed before the reductions so that no instruction
 // reads the result of its immediate predecessor (the compiler otherwise pads each pair with a
 // wait state).
-template <bool DECONV>
+template <bool MAXF>
 __device__ __forceinline__ void block_steps_packed(uint32_t (&acc)[kPkR], const uint32_t (&u)[kPkR],
                                                    const uint32_t (&lo)[kPkR], const uint32_t (&hi)[kPkR]) {
 #pragma unroll
@@ -367,12 +375,12 @@ __device__ __forceinline__ void block_steps_packed(uint32_t (&acc)[kPkR], const 
     for (int r = 0; r < kPkR; ++r) {
       const us2 w = __builtin_bit_cast(us2, (r >= k) ? hi[r - k] : lo[kPkR + r - k]);
       const us2 uu = __builtin_bit_cast(us2, u[k]);
-      s[r] = DECONV ? __builtin_elementwise_sub_sat(w, uu) : __builtin_elementwise_add_sat(w, uu);
+      s[r] = MAXF ? __builtin_elementwise_sub_sat(w, uu) : __builtin_elementwise_add_sat(w, uu);
     }
 #pragma unroll
     for (int r = 0; r < kPkR; ++r) {
       const us2 av = __builtin_bit_cast(us2, acc[r]);
-      acc[r] = __builtin_bit_cast(uint32_t, DECONV ? __builtin_elementwise_max(av, s[r])
+      acc[r] = __builtin_bit_cast(uint32_t, MAXF ? __builtin_elementwise_max(av, s[r])
                                                    : __builtin_elementwise_min(av, s[r]));
     }
   }
@@ -385,7 +393,7 @@ __device__ __forceinline__ void block_steps_packed(uint32_t (&acc)[kPkR], const 
 //   convolution:   lane value = (bd - gb) + (ad - ab); poison 0xFFFF (saturating add, min)
 //   deconvolution: lane value = (bd - gb) + ar + 1 - (ad - ab) >= 1; poison 0 for the window,
 //                  0xFFFF for the uniform operand (saturating subtract gives 0, max ignores it)
-template <typename OutT, bool DECONV>
+template <typename OutT, int OP>
 __device__ __forceinline__ void packed_body(const TropicalArgs& p, unsigned char* lds, uint32_t item) {
   using TL = Tile<int32_t, kPkR>;
   const int lane = threadIdx.x;
@@ -398,9 +406,10 @@ __device__ __forceinline__ void packed_body(const TropicalArgs& p, unsigned char
   const int32_t* __restrict__ bd = x.bd + (int64_t)row * n;
   const int32_t* __restrict__ ab = x.ab + (int64_t)row * x.nchunk;
   const int32_t* __restrict__ ar = x.ar + (int64_t)row * x.nchunk;
-  constexpr int32_t kIdent = DECONV ? INT32_MIN : INT32_MAX;
-  constexpr uint32_t kWinPoison = DECONV ? 0u : kPkPoison;   // staged for window positions that do not exist
-  constexpr uint32_t kAccPoison = DECONV ? 0u : kPkPoison;   // a 16-bit lane that saw no existing candidate
+  constexpr bool MAXF = op_max(OP);   // arithmetic flavour: saturating subtract + max, or saturating add + min
+  constexpr int32_t kIdent = MAXF ? INT32_MIN : INT32_MAX;
+  constexpr uint32_t kWinPoison = MAXF ? 0u : kPkPoison;   // staged for window positions that do not exist
+  constexpr uint32_t kAccPoison = MAXF ? 0u : kPkPoison;   // a 16-bit lane that saw no existing candidate
 
   int32_t acc_lo[kPkR], acc_hi[kPkR];
 #pragma unroll
@@ -414,7 +423,7 @@ __device__ __forceinline__ void packed_body(const TropicalArgs& p, unsigned char
     const int nblk = (ce - sc + kPkR - 1) / kPkR;
     const int gbase = t0 - (sc + nblk * kPkR);
     const int count = (64 + nblk) * kPkR;
-    const uint32_t lift = DECONV ? (uint32_t)ar[c] + 1u : 0u;
+    const uint32_t lift = MAXF ? (uint32_t)ar[c] + 1u : 0u;
     __syncthreads();
     for (int e = lane; e < count; e += 64) {
       const int il = gbase + e, ih = il + kPkHalf;
@@ -437,7 +446,7 @@ __device__ __forceinline__ void packed_body(const TropicalArgs& p, unsigned char
         uint32_t u[kPkR];
 #pragma unroll
         for (int k = 0; k < kPkR; ++k) u[k] = apk[s0 + k];
-        block_steps_packed<DECONV>(acc, u, w1, w0);
+        block_steps_packed<MAXF>(acc, u, w1, w0);
       }
       if (i + 1 < nblk) {
         const int s0 = sc + (i + 1) * kPkR;
@@ -445,19 +454,19 @@ __device__ __forceinline__ void packed_body(const TropicalArgs& p, unsigned char
         uint32_t u[kPkR];
 #pragma unroll
         for (int k = 0; k < kPkR; ++k) u[k] = apk[s0 + k];
-        block_steps_packed<DECONV>(acc, u, w0, w1);
+        block_steps_packed<MAXF>(acc, u, w0, w1);
       }
     }
     // fold the chunk into the 32-bit accumulators (detrended domain, wrap-around arithmetic:
     // every folded value is a true candidate, which fits)
-    const uint32_t cb = DECONV ? (uint32_t)gb - (uint32_t)ab[c] - lift : (uint32_t)ab[c] + (uint32_t)gb;
+    const uint32_t cb = MAXF ? (uint32_t)gb - (uint32_t)ab[c] - lift : (uint32_t)ab[c] + (uint32_t)gb;
 #pragma unroll
     for (int r = 0; r < kPkR; ++r) {
       const uint32_t vl = acc[r] & 0xFFFFu, vh = acc[r] >> 16;
       const int32_t cl = vl != kAccPoison ? (int32_t)(cb + vl) : kIdent;
       const int32_t ch = vh != kAccPoison ? (int32_t)(cb + vh) : kIdent;
-      acc_lo[r] = DECONV ? max(acc_lo[r], cl) : min(acc_lo[r], cl);
-      acc_hi[r] = DECONV ? max(acc_hi[r], ch) : min(acc_hi[r], ch);
+      acc_lo[r] = MAXF ? max(acc_lo[r], cl) : min(acc_lo[r], cl);
+      acc_hi[r] = MAXF ? max(acc_hi[r], ch) : min(acc_hi[r], ch);
     }
   }
 
@@ -478,31 +487,31 @@ __device__ __forceinline__ void packed_body(const TropicalArgs& p, unsigned char
       const int t = t0 + half * kPkHalf + xo;
       const int32_t av = xp[xo + xo / kPkR];
       if (t < n && av != kIdent) {
-        const int ot = DECONV ? n - 1 - t : t;
-        OutT v = (OutT)(DECONV ? wrap_sub(av, rho * t) : wrap_add(av, rho * t));
+        const int ot = op_sub(OP) ? n - 1 - t : t;
+        OutT v = (OutT)(op_sub(OP) ? wrap_sub(av, rho * t) : wrap_add(av, rho * t));
         if (crow) v = sel_min(v, crow[ot]);
-        if (DECONV) atomic_max(&orow[ot], v); else atomic_min(&orow[ot], v);
+        if (op_max(OP)) atomic_max(&orow[ot], v); else atomic_min(&orow[ot], v);
       }
     }
   }
 }
 
-template <typename T, typename OutT, bool DECONV, int R, bool ATOMIC>
+template <typename T, typename OutT, int OP, int R, bool ATOMIC>
 __global__ __launch_bounds__(64) void tropical_kernel(const TropicalArgs p) {
   __shared__ __align__(16) unsigned char lds[lds_bytes<T, R>()];
-  tropical_body<T, OutT, DECONV, R, ATOMIC>(p, lds, blockIdx.x);
+  tropical_body<T, OutT, OP, R, ATOMIC>(p, lds, blockIdx.x);
 }
 
 // One launch for an int32 product with the packed path: the first n_packed workgroups are
 // items of the packed kernel, the rest are items of the 32-bit kernel (which skip the chunks
 // the packed items own).  Issuing both kinds together keeps the machine full whatever share of
 // the chunks qualifies for 16 bits.
-template <typename OutT, bool DECONV>
+template <typename OutT, int OP>
 __global__ __launch_bounds__(64) void fused_kernel(const TropicalArgs pk, const TropicalArgs pg,
                                                    uint32_t n_packed) {
   __shared__ __align__(16) unsigned char lds[lds_bytes<int32_t, kPkR>()];
-  if (blockIdx.x < n_packed) packed_body<OutT, DECONV>(pk, lds, blockIdx.x);
-  else tropical_body<int32_t, OutT, DECONV, kPkR, true>(pg, lds, blockIdx.x - n_packed);
+  if (blockIdx.x < n_packed) packed_body<OutT, OP>(pk, lds, blockIdx.x);
+  else tropical_body<int32_t, OutT, OP, kPkR, true>(pg, lds, blockIdx.x - n_packed);
 }
 
 template <typename T>
@@ -604,7 +613,7 @@ __device__ __forceinline__ int32_t wave_max(int32_t v) {
 // records the chunk range of a and the minima / maxima of b per block of 256.
 __global__ __launch_bounds__(1024) void prep_kernel(const int32_t* __restrict__ a, int64_t stride_a,
                                                     const int32_t* __restrict__ b, int64_t stride_b, int n,
-                                                    bool deconv, int npad, int nchunk, int nblk,
+                                                    bool deconv, bool neg, int npad, int nchunk, int nblk,
                                                     const int32_t* __restrict__ rho,
                                                     const int32_t* __restrict__ pack_ok,
                                                     uint32_t* __restrict__ apk, int32_t* __restrict__ bd, int32_t* __restrict__ ab,
@@ -617,7 +626,8 @@ __global__ __launch_bounds__(1024) void prep_kernel(const int32_t* __restrict__ 
   const int i = c * kPkChunk + threadIdx.x;
   const int32_t r = rho[row];
   const bool valid = i < n;
-  const int32_t adv = valid ? wrap_sub(a[(int64_t)row * stride_a + i], r * i) : 0;
+  int32_t adv = valid ? wrap_sub(a[(int64_t)row * stride_a + i], r * i) : 0;
+  if (neg) adv = wrap_sub(0, adv);   // max-plus convolution / min-plus deconvolution: see packed_body
   int32_t bdv = 0;
   if (valid) bdv = deconv ? wrap_add(b[(int64_t)row * stride_b + (n - 1 - i)], r * i)
                           : wrap_sub(b[(int64_t)row * stride_b + i], r * i);
@@ -687,10 +697,10 @@ __global__ __launch_bounds__(256) void decide_kernel(PackAux x, int n, int32_t* 
 template <typename T> struct RFor { static constexpr int value = 16; };
 
 // Identity of the reduction as a host value (used to pre-fill outputs merged by atomics).
-template <typename T, bool DECONV> T host_identity() {
+template <typename T, int OP> T host_identity() {
   if (std::numeric_limits<T>::has_infinity)
-    return DECONV ? -std::numeric_limits<T>::infinity() : std::numeric_limits<T>::infinity();
-  return DECONV ? std::numeric_limits<T>::lowest() : std::numeric_limits<T>::max();
+    return op_max(OP) ? -std::numeric_limits<T>::infinity() : std::numeric_limits<T>::infinity();
+  return op_max(OP) ? std::numeric_limits<T>::lowest() : std::numeric_limits<T>::max();
 }
 
 struct Plan {
@@ -730,17 +740,17 @@ template <typename T> Plan make_plan(int64_t batch, int64_t n) {
   return make_plan(batch, n, TL::kW, TL::kChunk);
 }
 
-template <typename OutT, bool DECONV>
+template <typename OutT, int OP>
 void launch_fill(OutT* out, int64_t count, hipStream_t stream) {
   const int64_t want = (count + 2047) / 2048;
   const int blocks = (int)(want < 65535 ? want : 65535);
   hipLaunchKernelGGL(fill_kernel<OutT>, dim3(blocks), dim3(256), 0, stream, out, count,
-                     host_identity<OutT, DECONV>());
+                     host_identity<OutT, OP>());
 }
 
 // One launch of the generic kernel.  `force_atomic` is set when several kernels contribute to
 // one output (the output is then already filled with the identity).
-template <typename T, typename OutT, bool DECONV>
+template <typename T, typename OutT, int OP>
 int run_product(const T* a, int64_t stride_a, const T* b, int64_t stride_b, OutT* out, const OutT* cap,
                 const int32_t* sel, int sel_want, int64_t batch, int64_t n, hipStream_t stream,
                 bool prefilled, bool force_atomic, const PackAux* aux) {
@@ -755,13 +765,13 @@ int run_product(const T* a, int64_t stride_a, const T* b, int64_t stride_b, OutT
   if (aux != nullptr) { args.use_aux = 1; args.aux = *aux; }
   constexpr int dtype_code = std::is_same<T, int32_t>::value ? RTC_I32 : std::is_same<T, int64_t>::value ? RTC_I64 : RTC_F64;
   if (pl.atomic || force_atomic) {
-    if (!prefilled) launch_fill<OutT, DECONV>(out, batch * n, stream);
-    prof_begin(RTC_PROFILE_KIND(dtype_code, 0, DECONV ? 1 : 0), stream);
-    hipLaunchKernelGGL((tropical_kernel<T, OutT, DECONV, R, true>), dim3((uint32_t)pl.items), dim3(64), 0,
+    if (!prefilled) launch_fill<OutT, OP>(out, batch * n, stream);
+    prof_begin(RTC_PROFILE_KIND(dtype_code, 0, OP), stream);
+    hipLaunchKernelGGL((tropical_kernel<T, OutT, OP, R, true>), dim3((uint32_t)pl.items), dim3(64), 0,
                        stream, args);
   } else {
-    prof_begin(RTC_PROFILE_KIND(dtype_code, 0, DECONV ? 1 : 0), stream);
-    hipLaunchKernelGGL((tropical_kernel<T, OutT, DECONV, R, false>), dim3((uint32_t)pl.items), dim3(64), 0,
+    prof_begin(RTC_PROFILE_KIND(dtype_code, 0, OP), stream);
+    hipLaunchKernelGGL((tropical_kernel<T, OutT, OP, R, false>), dim3((uint32_t)pl.items), dim3(64), 0,
                        stream, args);
   }
   prof_end(stream);
@@ -797,7 +807,7 @@ PackLayout pack_layout(int64_t batch, int64_t n) {
 // or the narrowed copies of int64 rows); pack_ok / rho were written by the probe and the output
 // is already filled with the identity.  `sel` (optional) restricts both kernels to rows with
 // sel[row] == 1.
-template <typename OutT, bool DECONV>
+template <typename OutT, int OP>
 int run_packed(const int32_t* f32, int64_t stride_f, const int32_t* g32, int64_t stride_g, OutT* out,
                const OutT* cap, const int32_t* sel, int64_t batch, int64_t n, char* wsp, const PackLayout& L,
                hipStream_t stream) {
@@ -814,8 +824,8 @@ int run_packed(const int32_t* f32, int64_t stride_f, const int32_t* g32, int64_t
   if (batch * L.nchunk > 0x7fffffffLL) return RTC_ERR_SHAPE;
   // uniform operand: f for the convolution, g for the deconvolution; window operand: the other
   hipLaunchKernelGGL(prep_kernel, dim3((uint32_t)(batch * L.nchunk)), dim3(1024), 0, stream,
-                     DECONV ? g32 : f32, DECONV ? stride_g : stride_f, DECONV ? f32 : g32,
-                     DECONV ? stride_f : stride_g, (int)n, DECONV, (int)L.npad, (int)L.nchunk, (int)L.nblk,
+                     op_sub(OP) ? g32 : f32, op_sub(OP) ? stride_g : stride_f, op_sub(OP) ? f32 : g32,
+                     op_sub(OP) ? stride_f : stride_g, (int)n, op_sub(OP), op_sub(OP) != op_max(OP), (int)L.npad, (int)L.nchunk, (int)L.nblk,
                      aux.rho, aux.pack_ok, const_cast<uint32_t*>(aux.apk), const_cast<int32_t*>(aux.bd), const_cast<int32_t*>(aux.ab), const_cast<int32_t*>(aux.ar),
                      const_cast<int32_t*>(aux.bmn), const_cast<int32_t*>(aux.bmx));
   hipLaunchKernelGGL(decide_kernel, dim3((uint32_t)batch), dim3(256), 0, stream, aux, (int)n,
@@ -830,11 +840,11 @@ int run_packed(const int32_t* f32, int64_t stride_f, const int32_t* g32, int64_t
   ak.use_aux = 1; ak.aux = aux;
   // the 32-bit items work on the caller's rows and skip the chunks owned by the packed items
   TropicalArgs ag = ak;
-  ag.a = DECONV ? g32 : f32; ag.stride_a = DECONV ? stride_g : stride_f;
-  ag.b = DECONV ? f32 : g32; ag.stride_b = DECONV ? stride_f : stride_g;
+  ag.a = op_sub(OP) ? g32 : f32; ag.stride_a = op_sub(OP) ? stride_g : stride_f;
+  ag.b = op_sub(OP) ? f32 : g32; ag.stride_b = op_sub(OP) ? stride_f : stride_g;
   ag.n_tiles = pg.n_tiles; ag.fold_width = pg.fold_width; ag.seg = pg.seg;
-  prof_begin(RTC_PROFILE_KIND(RTC_I32, 1, DECONV ? 1 : 0), stream);
-  hipLaunchKernelGGL((fused_kernel<OutT, DECONV>), dim3((uint32_t)(pk.items + pg.items)), dim3(64), 0, stream,
+  prof_begin(RTC_PROFILE_KIND(RTC_I32, 1, OP), stream);
+  hipLaunchKernelGGL((fused_kernel<OutT, OP>), dim3((uint32_t)(pk.items + pg.items)), dim3(64), 0, stream,
                      ak, ag, (uint32_t)pk.items);
   prof_end(stream);
   return hip_ok();
@@ -850,15 +860,15 @@ bool packed_worthwhile(int64_t batch, int64_t n) {
   return (double)batch * (double)n * (double)n >= g_packed_min_work;
 }
 
-template <typename T, bool DECONV>
+template <typename T, int OP>
 int run_typed(const void* f, const void* g, void* out, int64_t batch, int64_t n, int64_t stride_f,
               int64_t stride_g, const void* cap, void* ws, size_t ws_bytes, int32_t* dev_flags,
               hipStream_t stream) {
   // convolution: uniform operand f, window g.  deconvolution: uniform g, window f (reversed).
-  const T* a = static_cast<const T*>(DECONV ? g : f);
-  const T* b = static_cast<const T*>(DECONV ? f : g);
-  const int64_t sa = DECONV ? stride_g : stride_f;
-  const int64_t sb = DECONV ? stride_f : stride_g;
+  const T* a = static_cast<const T*>(op_sub(OP) ? g : f);
+  const T* b = static_cast<const T*>(op_sub(OP) ? f : g);
+  const int64_t sa = op_sub(OP) ? stride_g : stride_f;
+  const int64_t sb = op_sub(OP) ? stride_f : stride_g;
   if constexpr (std::is_same<T, int32_t>::value) {
     const PackLayout L = pack_layout(batch, n);
     // tiny problems are launch-bound: the extra kernels of the packed path would only cost
@@ -866,11 +876,11 @@ int run_typed(const void* f, const void* g, void* out, int64_t batch, int64_t n,
       char* wsp = static_cast<char*>(ws);
       hipLaunchKernelGGL(probe_kernel<int32_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,
                          static_cast<const int32_t*>(f), stride_f, static_cast<const int32_t*>(g), stride_g,
-                         (int)n, DECONV, (int32_t*)nullptr, (int32_t*)nullptr, (int32_t*)nullptr,
+                         (int)n, op_sub(OP), (int32_t*)nullptr, (int32_t*)nullptr, (int32_t*)nullptr,
                          reinterpret_cast<int32_t*>(wsp + L.off_ok), reinterpret_cast<int32_t*>(wsp + L.off_rho),
                          dev_flags);
-      launch_fill<int32_t, DECONV>(static_cast<int32_t*>(out), batch * n, stream);
-      return run_packed<int32_t, DECONV>(static_cast<const int32_t*>(f), stride_f,
+      launch_fill<int32_t, OP>(static_cast<int32_t*>(out), batch * n, stream);
+      return run_packed<int32_t, OP>(static_cast<const int32_t*>(f), stride_f,
                                          static_cast<const int32_t*>(g), stride_g, static_cast<int32_t*>(out),
                                          static_cast<const int32_t*>(cap), nullptr, batch, n, wsp, L, stream);
     }
@@ -878,10 +888,10 @@ int run_typed(const void* f, const void* g, void* out, int64_t batch, int64_t n,
   if (dev_flags != nullptr && std::numeric_limits<T>::is_integer) {
     hipLaunchKernelGGL(probe_kernel<T>, dim3((uint32_t)batch), dim3(1024), 0, stream,
                        static_cast<const T*>(f), stride_f, static_cast<const T*>(g), stride_g, (int)n,
-                       DECONV, (int32_t*)nullptr, (int32_t*)nullptr, (int32_t*)nullptr, (int32_t*)nullptr,
+                       op_sub(OP), (int32_t*)nullptr, (int32_t*)nullptr, (int32_t*)nullptr, (int32_t*)nullptr,
                        (int32_t*)nullptr, dev_flags);
   }
-  return run_product<T, T, DECONV>(a, sa, b, sb, static_cast<T*>(out), static_cast<const T*>(cap),
+  return run_product<T, T, OP>(a, sa, b, sb, static_cast<T*>(out), static_cast<const T*>(cap),
                                    nullptr, 0, batch, n, stream, false, false, nullptr);
 }
 
@@ -890,7 +900,7 @@ size_t narrow_bytes(int64_t batch, int64_t n) {
   return ((size_t)(2 * batch * n + batch) * sizeof(int32_t) + 255) / 256 * 256;
 }
 
-template <bool DECONV>
+template <int OP>
 int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, int64_t stride_f,
             int64_t stride_g, const void* cap, void* ws, int32_t* dev_flags, hipStream_t stream) {
   // workspace: [f32: batch*n][g32: batch*n][narrow_ok: batch][packed-path arrays]
@@ -901,25 +911,25 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
   const PackLayout L = pack_layout(batch, n);
   hipLaunchKernelGGL(probe_kernel<int64_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,
                      static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g,
-                     (int)n, DECONV, f32, g32, ok, reinterpret_cast<int32_t*>(wsp + L.off_ok),
+                     (int)n, op_sub(OP), f32, g32, ok, reinterpret_cast<int32_t*>(wsp + L.off_ok),
                      reinterpret_cast<int32_t*>(wsp + L.off_rho), dev_flags);
   // Several kernels see every row; the selector makes each row run in exactly one family.
   // The output is filled once with the identity, before all of them.
-  launch_fill<int64_t, DECONV>(static_cast<int64_t*>(out), batch * n, stream);
+  launch_fill<int64_t, OP>(static_cast<int64_t*>(out), batch * n, stream);
   int rc;
   if (packed_worthwhile(batch, n)) {
-    rc = run_packed<int64_t, DECONV>(f32, n, g32, n, static_cast<int64_t*>(out),
+    rc = run_packed<int64_t, OP>(f32, n, g32, n, static_cast<int64_t*>(out),
                                      static_cast<const int64_t*>(cap), ok, batch, n, wsp, L, stream);
   } else {
-    rc = run_product<int32_t, int64_t, DECONV>(DECONV ? g32 : f32, n, DECONV ? f32 : g32, n,
+    rc = run_product<int32_t, int64_t, OP>(op_sub(OP) ? g32 : f32, n, op_sub(OP) ? f32 : g32, n,
                                                static_cast<int64_t*>(out), static_cast<const int64_t*>(cap), ok,
                                                1, batch, n, stream, true, true, nullptr);
   }
   if (rc != RTC_OK) return rc;
-  const int64_t* a = static_cast<const int64_t*>(DECONV ? g : f);
-  const int64_t* b = static_cast<const int64_t*>(DECONV ? f : g);
-  return run_product<int64_t, int64_t, DECONV>(a, DECONV ? stride_g : stride_f, b,
-                                               DECONV ? stride_f : stride_g, static_cast<int64_t*>(out),
+  const int64_t* a = static_cast<const int64_t*>(op_sub(OP) ? g : f);
+  const int64_t* b = static_cast<const int64_t*>(op_sub(OP) ? f : g);
+  return run_product<int64_t, int64_t, OP>(a, op_sub(OP) ? stride_g : stride_f, b,
+                                               op_sub(OP) ? stride_f : stride_g, static_cast<int64_t*>(out),
                                                static_cast<const int64_t*>(cap), ok, 0, batch, n, stream,
                                                true, true, nullptr);
 }
@@ -932,24 +942,30 @@ size_t tropical_workspace_bytes(int64_t batch, int64_t n, int dt) {
   return 0;
 }
 
-int launch_tropical(bool deconv, const void* f, const void* g, void* out, int64_t batch, int64_t n,
+int launch_tropical(int op, const void* f, const void* g, void* out, int64_t batch, int64_t n,
                     int64_t stride_f, int64_t stride_g, int dt, const void* cap, void* ws,
                     size_t ws_bytes, int32_t* dev_flags, hipStream_t stream) {
   if (dt == RTC_I64 && (ws == nullptr || ws_bytes < tropical_workspace_bytes(batch, n, dt)))
     return RTC_ERR_WORKSPACE;
+#define RTC_BY_OP(CALL)                                  \
+  switch (op) {                                          \
+    case RTC_OP_CONV: { constexpr int OP = 0; return CALL; }     \
+    case RTC_OP_DECONV: { constexpr int OP = 1; return CALL; }   \
+    case RTC_OP_MAXCONV: { constexpr int OP = 2; return CALL; }  \
+    case RTC_OP_MINDECONV: { constexpr int OP = 3; return CALL; }\
+    default: return RTC_ERR_MODE;                        \
+  }
   switch (dt) {
     case RTC_I32:
-      return deconv ? run_typed<int32_t, true>(f, g, out, batch, n, stride_f, stride_g, cap, ws, ws_bytes, dev_flags, stream)
-                    : run_typed<int32_t, false>(f, g, out, batch, n, stride_f, stride_g, cap, ws, ws_bytes, dev_flags, stream);
+      RTC_BY_OP((run_typed<int32_t, OP>(f, g, out, batch, n, stride_f, stride_g, cap, ws, ws_bytes, dev_flags, stream)))
     case RTC_F64:
-      return deconv ? run_typed<double, true>(f, g, out, batch, n, stride_f, stride_g, cap, ws, ws_bytes, dev_flags, stream)
-                    : run_typed<double, false>(f, g, out, batch, n, stride_f, stride_g, cap, ws, ws_bytes, dev_flags, stream);
+      RTC_BY_OP((run_typed<double, OP>(f, g, out, batch, n, stride_f, stride_g, cap, ws, ws_bytes, dev_flags, stream)))
     case RTC_I64:
-      return deconv ? run_i64<true>(f, g, out, batch, n, stride_f, stride_g, cap, ws, dev_flags, stream)
-                    : run_i64<false>(f, g, out, batch, n, stride_f, stride_g, cap, ws, dev_flags, stream);
+      RTC_BY_OP((run_i64<OP>(f, g, out, batch, n, stride_f, stride_g, cap, ws, dev_flags, stream)))
     default:
       return RTC_ERR_DTYPE;
   }
+#undef RTC_BY_OP
 }
 
 }  // namespace rtc

@@ -24,7 +24,7 @@ _lib = ctypes.CDLL(LIB_PATH)
 
 RTC_I32, RTC_I64, RTC_F64 = 0, 1, 2
 RTC_INV_LOWER, RTC_INV_UPPER = 0, 1
-RTC_OP_CONV, RTC_OP_DECONV, RTC_OP_GPC = 0, 1, 2
+RTC_OP_CONV, RTC_OP_DECONV, RTC_OP_GPC, RTC_OP_MAXCONV, RTC_OP_MINDECONV = 0, 1, 2, 3, 4
 RTC_FLAG_OVERFLOW, RTC_FLAG_DOMAIN, RTC_FLAG_UNBOUNDED = 1, 2, 4
 
 _DT = {torch.int32: RTC_I32, torch.int64: RTC_I64, torch.float64: RTC_F64}
@@ -42,6 +42,8 @@ class rtc_gpc_args(ctypes.Structure):
 _product_sig = [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _int, _vp, _sz, _vp, _vp]
 _lib.rtc_minplus_conv.argtypes = _product_sig
 _lib.rtc_maxplus_deconv.argtypes = _product_sig
+_lib.rtc_maxplus_conv.argtypes = _product_sig
+_lib.rtc_minplus_deconv.argtypes = _product_sig
 _lib.rtc_pseudo_inverse.argtypes = [_vp, _i64, _vp, _i64, _vp, _i64, _int, _int, _vp]
 _lib.rtc_compose.argtypes = [_vp, _i64, _vp, _i64, _vp, _i64, _int, _vp, _vp]
 _lib.rtc_gpc_step.argtypes = [ctypes.POINTER(rtc_gpc_args), _vp]
@@ -52,7 +54,7 @@ _lib.rtc_workspace_bytes.restype = _sz
 _lib.rtc_strerror.argtypes = [_int]
 _lib.rtc_strerror.restype = ctypes.c_char_p
 _lib.rtc_device_info.argtypes = [ctypes.POINTER(_int)] * 3
-for _name in ("rtc_minplus_conv", "rtc_maxplus_deconv", "rtc_pseudo_inverse", "rtc_compose",
+for _name in ("rtc_minplus_conv", "rtc_maxplus_deconv", "rtc_maxplus_conv", "rtc_minplus_deconv", "rtc_pseudo_inverse", "rtc_compose",
               "rtc_gpc_step", "rtc_max_hdev", "rtc_max_vdev", "rtc_device_info"):
     getattr(_lib, _name).restype = _int
 
@@ -121,8 +123,8 @@ _lib.rtc_profile_read.argtypes = [_int, ctypes.POINTER(_int), ctypes.POINTER(cty
 _lib.rtc_profile_read.restype = _int
 
 
-def RTC_PROFILE_KIND(dtype_code: int, packed: int, deconv: int) -> int:
-    return dtype_code * 4 + packed * 2 + deconv
+def RTC_PROFILE_KIND(dtype_code: int, packed: int, product: int) -> int:
+    return dtype_code * 8 + packed * 4 + product
 
 
 _lib.rtc_set_packed_min_work.argtypes = [ctypes.c_double]
@@ -178,6 +180,16 @@ def rtc_minplus_conv(f, g, out=None, ws=None, dev_flags=None):
 def rtc_maxplus_deconv(f, g, out=None, ws=None, dev_flags=None):
     """out[b][t] = max_{0<=u<=n-1-t} f[b][t+u] - g[b][u]."""
     return _product(_lib.rtc_maxplus_deconv, RTC_OP_DECONV, f, g, out, ws, dev_flags)
+
+
+def rtc_maxplus_conv(f, g, out=None, ws=None, dev_flags=None):
+    """out[b][t] = max_{0<=s<=t} f[b][s] + g[b][t-s]."""
+    return _product(_lib.rtc_maxplus_conv, RTC_OP_MAXCONV, f, g, out, ws, dev_flags)
+
+
+def rtc_minplus_deconv(f, g, out=None, ws=None, dev_flags=None):
+    """out[b][t] = min_{0<=u<=n-1-t} f[b][t+u] - g[b][u]."""
+    return _product(_lib.rtc_minplus_deconv, RTC_OP_MINDECONV, f, g, out, ws, dev_flags)
 
 
 def rtc_pseudo_inverse(f, x, mode: int = RTC_INV_LOWER, out=None):

@@ -270,3 +270,60 @@ def test_host_validation_on_device_pointers(rtc):
     with pytest.raises(rtc.RtcError) as e:
         rtc.rtc_minplus_conv(f.to(torch.int64), f.to(torch.int64), ws=torch.empty(16, dtype=torch.uint8, device="cuda"))
     assert e.value.status == -6
+
+
+# ---------------------------------------------------------------------------
+# dual products: max-plus convolution, min-plus deconvolution
+# ---------------------------------------------------------------------------
+
+def check_duals(rtc, f, g, tag, ws=None):
+    say(tag, "maxconv/mindeconv", f.dtype, f.shape)
+    assert np.array_equal(host(rtc.rtc_maxplus_conv(dev(f), dev(g), ws=ws)), oracle.maxplus_conv(f, g)), tag
+    assert np.array_equal(host(rtc.rtc_minplus_deconv(dev(f), dev(g), ws=ws)), oracle.minplus_deconv(f, g)), tag
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_dual_products_ragged_sizes(rtc, dtype):
+    for n in (1, 2, 16, 17, 100, 1023, 1025, 2049, 3300):
+        f = wl.random_monotone(31, 2 * n, 2, n, dtype)
+        g = wl.random_monotone(31, 2 * n + 1, 2, n, dtype)
+        check_duals(rtc, f, g, f"dual ragged n={n}")
+
+
+def test_dual_products_signed_and_mixed_chunks(rtc):
+    rng = np.random.default_rng(32)
+    n = 6500
+    slow = np.cumsum(rng.integers(0, 5, (2, n)), axis=1)
+    jumpy = np.cumsum(rng.integers(0, 5, (2, n)), axis=1)
+    jumpy[:, 2100:] += 150000
+    wild = np.concatenate([rng.integers(-40000, 40000, (1, n)), rng.integers(-9000, 9000, (1, n))])
+    f = np.concatenate([slow, jumpy, wild])
+    g = np.concatenate([slow[::-1], jumpy[::-1], wild[::-1]])
+    tiny = torch.empty(16, dtype=torch.uint8, device="cuda")
+    check_duals(rtc, f.astype(np.int32), g.astype(np.int32), "dual mixed int32")
+    check_duals(rtc, f.astype(np.int32), g.astype(np.int32), "dual mixed int32, 32-bit kernel only", ws=tiny)
+    check_duals(rtc, f.astype(np.int64), g.astype(np.int64), "dual mixed int64")
+    f64 = f.astype(np.int64)
+    f64[1] += 2**41
+    check_duals(rtc, f64, g.astype(np.int64), "dual int64 wide row")
+
+
+def test_dual_products_zero_curve_scans(rtc):
+    """With g = 0 the duals are the running maximum and the suffix minimum."""
+    rng = np.random.default_rng(33)
+    for dtype in DTYPES:
+        f = (rng.integers(-500, 500, (3, 2500))).astype(dtype)
+        zero = np.zeros((1, 2500), dtype)
+        say("dual zero curve", dtype)
+        assert np.array_equal(host(rtc.rtc_maxplus_conv(dev(f), dev(zero))), np.maximum.accumulate(f, axis=1))
+        assert np.array_equal(host(rtc.rtc_minplus_deconv(dev(f), dev(zero))),
+                              np.minimum.accumulate(f[:, ::-1], axis=1)[:, ::-1])
+
+
+def test_many_tiny_rows(rtc):
+    """Large batch of short curves (more rows than tiles per row)."""
+    for n in (1, 3, 70):
+        f = wl.random_monotone(34, n, 6000, n, np.int32)
+        g = wl.random_monotone(34, n + 1, 6000, n, np.int32)
+        check_products(rtc, f, g, f"many tiny rows n={n}")
+        check_duals(rtc, f, g, f"many tiny rows n={n}")

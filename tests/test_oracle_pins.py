@@ -394,3 +394,47 @@ def test_sampled_outputs_agree_with_brute_force(dtype):
     want_d = np.array(bf_deconv(f.tolist(), g.tolist()), dtype)[idx]
     assert np.array_equal(oracle.product_at(f, g, idx, False), want_c)
     assert np.array_equal(oracle.product_at(f, g, idx, True), want_d)
+
+
+# ---------------------------------------------------------------------------
+# the dual products: max-plus convolution, min-plus deconvolution
+# ---------------------------------------------------------------------------
+
+def bf_maxconv(f, g):
+    n = len(f)
+    return [max(f[s] + g[t - s] for s in range(t + 1)) for t in range(n)]
+
+
+def bf_mindeconv(f, g):
+    n = len(f)
+    return [min(f[t + u] - g[u] for u in range(n - t)) for t in range(n)]
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_dual_products_brute_force(dtype):
+    rng = np.random.default_rng(71)
+    for n in list(range(1, 34)) + [48, 64]:
+        f = _curve(rng, n, dtype)
+        g = _curve(rng, n, dtype)
+        assert np.array_equal(oracle.maxplus_conv(f, g)[0], np.array(bf_maxconv(f.tolist(), g.tolist()), dtype)), n
+        assert np.array_equal(oracle.minplus_deconv(f, g)[0], np.array(bf_mindeconv(f.tolist(), g.tolist()), dtype)), n
+
+
+@pytest.mark.parametrize("dtype", [np.int32, np.int64, np.float64])
+def test_dual_products_are_negated_primal_products(dtype):
+    """max_s f+g = -min_s (-f)+(-g) and min_u f-g = -max_u (-f)-(-g): ties the duals to the
+    separately pinned primal operators (exact also in floating point: negation is exact)."""
+    rng = np.random.default_rng(72)
+    n = 150
+    f = _curve(rng, n, dtype) - 300
+    g = _curve(rng, n, dtype)
+    assert np.array_equal(oracle.maxplus_conv(f, g)[0], -oracle.minplus_conv(-f, -g)[0])
+    assert np.array_equal(oracle.minplus_deconv(f, g)[0], -oracle.maxplus_deconv(-f, -g)[0])
+
+
+def test_dual_products_with_zero_curve_are_running_extrema():
+    rng = np.random.default_rng(73)
+    f = rng.integers(-500, 500, 200).astype(np.int64)
+    zero = np.zeros(200, np.int64)
+    assert np.array_equal(oracle.maxplus_conv(f, zero)[0], np.maximum.accumulate(f))
+    assert np.array_equal(oracle.minplus_deconv(f, zero)[0], np.minimum.accumulate(f[::-1])[::-1])
