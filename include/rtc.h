@@ -111,13 +111,21 @@ int rtc_pseudo_inverse(const void* f, int64_t n, const void* x, int64_t m, int32
 int rtc_compose(const void* outer, int64_t n_outer, const int32_t* inner, int64_t n, void* out,
                 int64_t batch, rtc_dtype dt, int32_t* dev_flags, void* hip_stream);
 
-/* One greedy processing component, upper-arrival / lower-service outputs, per row:
+/* One greedy processing component, per row.  Upper-arrival / lower-service side (always):
  *   alpha_u_out = min( (alpha_u (x) beta_u) (/) beta_l , beta_u )
  *   beta_l_out[D] = max(0, max_{l<=D} beta_l[l] - alpha_u[l])
  * and, when gamma_u is given, the event-domain images of beta_l_out,
  *   events_lower / events_upper = lower / upper pseudo-inverse of gamma_u at beta_l_out.
- * All curve pointers are dense [batch][n] of dtype dt (gamma_u: [batch][n_gamma]).
- * Optional members may be NULL.  ws needs rtc_workspace_bytes(RTC_OP_GPC, ...). */
+ * Lower-arrival / upper-service side (when alpha_l is given; alpha_l_out and beta_u_out are
+ * then required):
+ *   alpha_l_out = min( (alpha_l (/) beta_u) (x) beta_l , beta_l )
+ *   beta_u_out[D] = max(0, min_{l>=D} beta_u[l] - alpha_l[l])
+ * and, when gamma_l is given, events_u_lower / events_u_upper = lower / upper pseudo-inverse
+ * of gamma_l at beta_u_out.  (x) is the min-plus convolution, (/) the max-plus deconvolution
+ * on the finite horizon, as defined above.
+ * All curve pointers are dense [batch][n] of dtype dt (gamma_u: [batch][n_gamma], gamma_l:
+ * [batch][n_gamma_l]).  Optional members may be NULL; zero-initialise the struct.
+ * ws needs rtc_workspace_bytes(RTC_OP_GPC, ...). */
 typedef struct rtc_gpc_args {
   const void* alpha_u;
   const void* beta_u;
@@ -134,6 +142,13 @@ typedef struct rtc_gpc_args {
   void* ws;
   size_t ws_bytes;
   int32_t* dev_flags;     /* optional */
+  const void* alpha_l;    /* optional: enables the lower-arrival / upper-service side */
+  void* alpha_l_out;
+  void* beta_u_out;
+  const void* gamma_l;    /* optional */
+  int64_t n_gamma_l;
+  int32_t* events_u_lower; /* optional, int32 [batch][n], needs gamma_l */
+  int32_t* events_u_upper; /* optional, int32 [batch][n], needs gamma_l */
 } rtc_gpc_args;
 
 int rtc_gpc_step(const rtc_gpc_args* a, void* hip_stream);

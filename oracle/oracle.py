@@ -140,6 +140,21 @@ def gpc_step(alpha_u, beta_u, beta_l):
     return ao, lo
 
 
+def gpc_step_lower(alpha_l, beta_u, beta_l):
+    """Returns (alpha'^l, beta'^u) of one greedy processing component per row."""
+    a = _rows(alpha_l)
+    u = _rows(beta_u)
+    l = _rows(beta_l)
+    assert a.shape == u.shape == l.shape and a.dtype == u.dtype == l.dtype
+    ao = np.empty_like(a)
+    uo = np.empty_like(a)
+    tmp = np.empty_like(a)
+    rc = lib().oracle_gpc_step_lower(_p(a), _p(u), _p(l), _p(ao), _p(uo), _p(tmp), ctypes.c_int64(a.shape[0]),
+                                     ctypes.c_int64(a.shape[1]), ctypes.c_int(_DT[a.dtype]))
+    assert rc == 0, rc
+    return ao, uo
+
+
 def max_hdev(alpha, beta):
     a = _rows(alpha)
     b = _rows(beta)

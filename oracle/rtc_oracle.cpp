@@ -22,6 +22,8 @@
 //   greedy processing component (upper arrival / lower service outputs)
 //                            alpha'^u = min((alpha^u (x) beta^u) (/) beta^l, beta^u)
 //                            beta'^l[D] = max(0, max_{l<=D} beta^l[l] - alpha^u[l])
+//                            alpha'^l = min((alpha^l (/) beta^u) (x) beta^l, beta^l)
+//                            beta'^u[D] = max(0, min_{l>=D} beta^u[l] - alpha^l[l])
 //   horizontal deviation     max_D max(0, lower-inverse_beta(alpha[D]) - D)
 //   vertical deviation       max_D alpha[D] - beta[D]
 //
@@ -178,6 +180,29 @@ void gpc_rows(const T* au, const T* bu, const T* bl, T* au_out, T* bl_out, T* tm
   }
 }
 
+// lower arrival / upper service side of the component
+template <typename T>
+void gpc_lower_rows(const T* al, const T* bu, const T* bl, T* al_out, T* bu_out, T* tmp, int64_t batch,
+                    int64_t n) {
+  for (int64_t b = 0; b < batch; ++b) {
+    const T* a = al + b * n;
+    const T* u = bu + b * n;
+    const T* l = bl + b * n;
+    T* d = tmp + b * n;
+    T* c = al_out + b * n;
+    deconv_one(a, u, d, n);
+    conv_one(d, l, c, n);
+    for (int64_t k = 0; k < n; ++k)
+      if (l[k] < c[k]) c[k] = l[k];
+    T run = u[n - 1] - a[n - 1];
+    for (int64_t k = n - 1; k >= 0; --k) {
+      T v = u[k] - a[k];
+      if (v < run) run = v;
+      bu_out[b * n + k] = run > (T)0 ? run : (T)0;
+    }
+  }
+}
+
 template <typename T>
 void hdev_rows(const T* alpha, const T* beta, int32_t* out, int64_t batch, int64_t n, int32_t* flags) {
   int32_t fl = 0;
@@ -314,6 +339,18 @@ int oracle_gpc_step(const void* alpha_u, const void* beta_u, const void* beta_l,
                              (int64_t*)alpha_u_out, (int64_t*)beta_l_out, (int64_t*)tmp, batch, n);
   else if (dt == 2) gpc_rows((const double*)alpha_u, (const double*)beta_u, (const double*)beta_l,
                              (double*)alpha_u_out, (double*)beta_l_out, (double*)tmp, batch, n);
+  else return -3;
+  return 0;
+}
+
+int oracle_gpc_step_lower(const void* alpha_l, const void* beta_u, const void* beta_l, void* alpha_l_out,
+                          void* beta_u_out, void* tmp, int64_t batch, int64_t n, int dt) {
+  if (dt == 0) gpc_lower_rows((const int32_t*)alpha_l, (const int32_t*)beta_u, (const int32_t*)beta_l,
+                              (int32_t*)alpha_l_out, (int32_t*)beta_u_out, (int32_t*)tmp, batch, n);
+  else if (dt == 1) gpc_lower_rows((const int64_t*)alpha_l, (const int64_t*)beta_u, (const int64_t*)beta_l,
+                                   (int64_t*)alpha_l_out, (int64_t*)beta_u_out, (int64_t*)tmp, batch, n);
+  else if (dt == 2) gpc_lower_rows((const double*)alpha_l, (const double*)beta_u, (const double*)beta_l,
+                                   (double*)alpha_l_out, (double*)beta_u_out, (double*)tmp, batch, n);
   else return -3;
   return 0;
 }

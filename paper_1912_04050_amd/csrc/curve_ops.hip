@@ -88,63 +88,83 @@ __device__ __forceinline__ double dpp_move(double identity, double v) {
                                                        (int64_t)__double_as_longlong(v)));
 }
 
-template <typename T>
-__device__ __forceinline__ T wave_scan_max(T v) {
-  const T id = lowest<T>();
-  v = vmax(v, dpp_move<0x111, 0xf>(id, v));  // row_shr:1
-  v = vmax(v, dpp_move<0x112, 0xf>(id, v));  // row_shr:2
-  v = vmax(v, dpp_move<0x114, 0xf>(id, v));  // row_shr:4
-  v = vmax(v, dpp_move<0x118, 0xf>(id, v));  // row_shr:8
-  v = vmax(v, dpp_move<0x142, 0xa>(id, v));  // row_bcast:15 into rows 1 and 3
-  v = vmax(v, dpp_move<0x143, 0xc>(id, v));  // row_bcast:31 into rows 2 and 3
+template <typename T> __device__ __forceinline__ T vmin(T a, T b) { return b < a ? b : a; }
+
+template <typename T> __device__ __forceinline__ T highest() {
+  if constexpr (std::numeric_limits<T>::has_infinity) return __builtin_huge_val();
+  else return std::numeric_limits<T>::max();
+}
+
+// The two scans of a greedy processing component share one kernel:
+//   MIN = false: running maximum over increasing index (identity: lowest)
+//   MIN = true : running minimum (identity: highest); the kernel then walks the row backwards,
+//                which turns it into the suffix minimum.
+template <typename T, bool MIN> struct ScanOp {
+  static __device__ __forceinline__ T id() { return MIN ? highest<T>() : lowest<T>(); }
+  static __device__ __forceinline__ T op(T a, T b) { return MIN ? vmin(a, b) : vmax(a, b); }
+};
+
+template <typename T, bool MIN>
+__device__ __forceinline__ T wave_scan(T v) {
+  using S = ScanOp<T, MIN>;
+  const T id = S::id();
+  v = S::op(v, dpp_move<0x111, 0xf>(id, v));  // row_shr:1
+  v = S::op(v, dpp_move<0x112, 0xf>(id, v));  // row_shr:2
+  v = S::op(v, dpp_move<0x114, 0xf>(id, v));  // row_shr:4
+  v = S::op(v, dpp_move<0x118, 0xf>(id, v));  // row_shr:8
+  v = S::op(v, dpp_move<0x142, 0xa>(id, v));  // row_bcast:15 into rows 1 and 3
+  v = S::op(v, dpp_move<0x143, 0xc>(id, v));  // row_bcast:31 into rows 2 and 3
   return v;
 }
 
-// Remaining lower service of a greedy processing component:
-//   out[D] = max(0, max_{l<=D} beta_l[l] - alpha_u[l]).  One workgroup per row.
-template <typename T>
-__global__ __launch_bounds__(1024) void residual_service_kernel(const T* __restrict__ beta_l,
-                                                                const T* __restrict__ alpha_u,
+// Remaining service of a greedy processing component, one workgroup per row:
+//   SUFFIX = false: out[D] = max(0, max_{l<=D} beta[l] - alpha[l])   (beta^l, alpha^u -> beta'^l)
+//   SUFFIX = true : out[D] = max(0, min_{l>=D} beta[l] - alpha[l])   (beta^u, alpha^l -> beta'^u)
+template <typename T, bool SUFFIX>
+__global__ __launch_bounds__(1024) void residual_service_kernel(const T* __restrict__ beta,
+                                                                const T* __restrict__ alpha,
                                                                 T* __restrict__ out, int n) {
+  using S = ScanOp<T, SUFFIX>;
   constexpr int kPer = 4;
   __shared__ T wave_tot[16];
   __shared__ T carry_s;
   const int row = blockIdx.x;
-  const T* bl = beta_l + (int64_t)row * n;
-  const T* au = alpha_u + (int64_t)row * n;
+  const T* bl = beta + (int64_t)row * n;
+  const T* au = alpha + (int64_t)row * n;
   T* o = out + (int64_t)row * n;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  T carry = lowest<T>();
+  T carry = S::id();
   for (int base = 0; base < n; base += 1024 * kPer) {
-    const int i0 = base + threadIdx.x * kPer;
+    const int p0 = base + threadIdx.x * kPer;   // position in scan order
     T v[kPer];
-    T run = lowest<T>();
+    T run = S::id();
 #pragma unroll
     for (int e = 0; e < kPer; ++e) {
-      const int i = i0 + e;
+      const int p = p0 + e;
+      const int i = SUFFIX ? n - 1 - p : p;
       // the difference may be negative; inputs obey the no-overflow precondition
-      const T d = i < n ? (T)(bl[i] - au[i]) : lowest<T>();
-      run = vmax(run, d);
+      const T d = p < n ? (T)(bl[i] - au[i]) : S::id();
+      run = S::op(run, d);
       v[e] = run;
     }
-    const T incl = wave_scan_max(run);
+    const T incl = wave_scan<T, SUFFIX>(run);
     if (lane == 63) wave_tot[wave] = incl;
     __syncthreads();
     T before = carry;
-    for (int w = 0; w < wave; ++w) before = vmax(before, wave_tot[w]);
+    for (int w = 0; w < wave; ++w) before = S::op(before, wave_tot[w]);
     // exclusive prefix inside the wave = inclusive value of the previous lane
     T prev = __shfl_up(incl, 1);
-    if (lane == 0) prev = lowest<T>();
-    before = vmax(before, prev);
+    if (lane == 0) prev = S::id();
+    before = S::op(before, prev);
 #pragma unroll
     for (int e = 0; e < kPer; ++e) {
-      const int i = i0 + e;
-      if (i < n) {
-        const T r = vmax(before, v[e]);
-        o[i] = r > (T)0 ? r : (T)0;
+      const int p = p0 + e;
+      if (p < n) {
+        const T r = S::op(before, v[e]);
+        o[SUFFIX ? n - 1 - p : p] = r > (T)0 ? r : (T)0;
       }
     }
-    if (threadIdx.x == 1023) carry_s = vmax(before, run);
+    if (threadIdx.x == 1023) carry_s = S::op(before, run);
     __syncthreads();
     carry = carry_s;
   }
@@ -264,12 +284,15 @@ int launch_compose(const void* outer, int64_t n_outer, const int32_t* inner, int
   RTC_DISPATCH(dt, return compose_typed<T>(outer, n_outer, inner, n, out, batch, dev_flags, stream));
 }
 
-int launch_residual_service(const void* beta_l, const void* alpha_u, void* out, int64_t batch,
-                            int64_t n, int dt, hipStream_t stream) {
+int launch_residual_service(const void* beta, const void* alpha, void* out, int64_t batch,
+                            int64_t n, int dt, bool suffix_min, hipStream_t stream) {
   RTC_DISPATCH(dt, {
-    hipLaunchKernelGGL(residual_service_kernel<T>, dim3((uint32_t)batch), dim3(1024), 0, stream,
-                       static_cast<const T*>(beta_l), static_cast<const T*>(alpha_u),
-                       static_cast<T*>(out), (int)n);
+    if (suffix_min)
+      hipLaunchKernelGGL((residual_service_kernel<T, true>), dim3((uint32_t)batch), dim3(1024), 0, stream,
+                         static_cast<const T*>(beta), static_cast<const T*>(alpha), static_cast<T*>(out), (int)n);
+    else
+      hipLaunchKernelGGL((residual_service_kernel<T, false>), dim3((uint32_t)batch), dim3(1024), 0, stream,
+                         static_cast<const T*>(beta), static_cast<const T*>(alpha), static_cast<T*>(out), (int)n);
     return hip_ok();
   });
 }

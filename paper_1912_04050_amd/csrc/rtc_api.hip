@@ -100,11 +100,18 @@ int rtc_gpc_step(const rtc_gpc_args* a, void* hip_stream) {
   if (es == 0) return RTC_ERR_DTYPE;
   if (int rc = check_shape(a->batch, a->n)) return rc;
   if ((a->events_lower != nullptr || a->events_upper != nullptr) && a->gamma_u == nullptr) return RTC_ERR_NULL;
+  if (a->alpha_l != nullptr && (a->alpha_l_out == nullptr || a->beta_u_out == nullptr)) return RTC_ERR_NULL;
+  if ((a->events_u_lower != nullptr || a->events_u_upper != nullptr) &&
+      (a->gamma_l == nullptr || a->alpha_l == nullptr))
+    return RTC_ERR_NULL;
+  if (a->gamma_l != nullptr && (a->n_gamma_l < 1 || a->n_gamma_l > RTC_MAX_N)) return RTC_ERR_SHAPE;
   if (a->gamma_u != nullptr && (a->n_gamma < 1 || a->n_gamma > RTC_MAX_N)) return RTC_ERR_SHAPE;
   if (!aligned(a->alpha_u, es) || !aligned(a->beta_u, es) || !aligned(a->beta_l, es) ||
       !aligned(a->alpha_u_out, es) || !aligned(a->beta_l_out, es) || !aligned(a->gamma_u, es) ||
       !aligned(a->events_lower, 4) || !aligned(a->events_upper, 4) || !aligned(a->dev_flags, 4) ||
-      !aligned(a->ws, 16))
+      !aligned(a->ws, 16) || !aligned(a->alpha_l, es) || !aligned(a->alpha_l_out, es) ||
+      !aligned(a->beta_u_out, es) || !aligned(a->gamma_l, es) || !aligned(a->events_u_lower, 4) ||
+      !aligned(a->events_u_upper, 4))
     return RTC_ERR_ALIGN;
   const size_t need = rtc_workspace_bytes(RTC_OP_GPC, a->batch, a->n, a->dt);
   if (a->ws == nullptr || a->ws_bytes < need) return RTC_ERR_WORKSPACE;
@@ -121,7 +128,7 @@ int rtc_gpc_step(const rtc_gpc_args* a, void* hip_stream) {
   rc = launch_tropical(RTC_OP_DECONV, c, a->beta_l, a->alpha_u_out, batch, n, n, n, a->dt, a->beta_u, sub_ws,
                        sub_bytes, a->dev_flags, stream);
   if (rc != RTC_OK) return rc;
-  rc = launch_residual_service(a->beta_l, a->alpha_u, a->beta_l_out, batch, n, a->dt, stream);
+  rc = launch_residual_service(a->beta_l, a->alpha_u, a->beta_l_out, batch, n, a->dt, false, stream);
   if (rc != RTC_OK) return rc;
   if (a->events_lower != nullptr) {
     rc = launch_pseudo_inverse(a->gamma_u, a->n_gamma, a->beta_l_out, n, a->events_lower, batch,
@@ -132,6 +139,28 @@ int rtc_gpc_step(const rtc_gpc_args* a, void* hip_stream) {
     rc = launch_pseudo_inverse(a->gamma_u, a->n_gamma, a->beta_l_out, n, a->events_upper, batch,
                                RTC_INV_UPPER, a->dt, stream);
     if (rc != RTC_OK) return rc;
+  }
+  if (a->alpha_l != nullptr) {
+    // lower arrival / upper service side: alpha'^l = min((alpha^l (/) beta^u) (x) beta^l, beta^l),
+    // beta'^u[D] = max(0, min_{l>=D} beta^u[l] - alpha^l[l]); the intermediate reuses c
+    rc = launch_tropical(RTC_OP_DECONV, a->alpha_l, a->beta_u, c, batch, n, n, n, a->dt, nullptr, sub_ws,
+                         sub_bytes, a->dev_flags, stream);
+    if (rc != RTC_OK) return rc;
+    rc = launch_tropical(RTC_OP_CONV, c, a->beta_l, a->alpha_l_out, batch, n, n, n, a->dt, a->beta_l, sub_ws,
+                         sub_bytes, a->dev_flags, stream);
+    if (rc != RTC_OK) return rc;
+    rc = launch_residual_service(a->beta_u, a->alpha_l, a->beta_u_out, batch, n, a->dt, true, stream);
+    if (rc != RTC_OK) return rc;
+    if (a->events_u_lower != nullptr) {
+      rc = launch_pseudo_inverse(a->gamma_l, a->n_gamma_l, a->beta_u_out, n, a->events_u_lower, batch,
+                                 RTC_INV_LOWER, a->dt, stream);
+      if (rc != RTC_OK) return rc;
+    }
+    if (a->events_u_upper != nullptr) {
+      rc = launch_pseudo_inverse(a->gamma_l, a->n_gamma_l, a->beta_u_out, n, a->events_u_upper, batch,
+                                 RTC_INV_UPPER, a->dt, stream);
+      if (rc != RTC_OK) return rc;
+    }
   }
   return RTC_OK;
 }

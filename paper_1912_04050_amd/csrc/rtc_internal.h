@@ -28,8 +28,8 @@ int launch_pseudo_inverse(const void* f, int64_t n, const void* x, int64_t m, in
                           int64_t batch, int mode, int dt, hipStream_t stream);
 int launch_compose(const void* outer, int64_t n_outer, const int32_t* inner, int64_t n, void* out,
                    int64_t batch, int dt, int32_t* dev_flags, hipStream_t stream);
-int launch_residual_service(const void* beta_l, const void* alpha_u, void* out, int64_t batch,
-                            int64_t n, int dt, hipStream_t stream);
+int launch_residual_service(const void* beta, const void* alpha, void* out, int64_t batch,
+                            int64_t n, int dt, bool suffix_min, hipStream_t stream);
 int launch_max_hdev(const void* alpha, const void* beta, int32_t* out, int64_t batch, int64_t n,
                     int dt, int32_t* dev_flags, hipStream_t stream);
 int launch_max_vdev(const void* alpha, const void* beta, void* out, int64_t batch, int64_t n, int dt,

@@ -36,7 +36,9 @@ class rtc_gpc_args(ctypes.Structure):
     _fields_ = [("alpha_u", _vp), ("beta_u", _vp), ("beta_l", _vp), ("alpha_u_out", _vp),
                 ("beta_l_out", _vp), ("gamma_u", _vp), ("n_gamma", _i64), ("events_lower", _vp),
                 ("events_upper", _vp), ("batch", _i64), ("n", _i64), ("dt", _int), ("ws", _vp),
-                ("ws_bytes", _sz), ("dev_flags", _vp)]
+                ("ws_bytes", _sz), ("dev_flags", _vp), ("alpha_l", _vp), ("alpha_l_out", _vp),
+                ("beta_u_out", _vp), ("gamma_l", _vp), ("n_gamma_l", _i64), ("events_u_lower", _vp),
+                ("events_u_upper", _vp)]
 
 
 _product_sig = [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _int, _vp, _sz, _vp, _vp]
@@ -216,8 +218,10 @@ def rtc_compose(outer, inner, out=None, dev_flags=None):
 
 
 def rtc_gpc_step(alpha_u, beta_u, beta_l, alpha_u_out=None, beta_l_out=None, gamma_u=None,
-                 events_lower=None, events_upper=None, ws=None, dev_flags=None):
-    """One greedy processing component; returns (alpha'^u, beta'^l)."""
+                 events_lower=None, events_upper=None, ws=None, dev_flags=None, alpha_l=None,
+                 alpha_l_out=None, beta_u_out=None, gamma_l=None, events_u_lower=None, events_u_upper=None):
+    """One greedy processing component; returns (alpha'^u, beta'^l), or with alpha_l given
+    (alpha'^u, beta'^l, alpha'^l, beta'^u)."""
     alpha_u, batch, n = _dense(alpha_u)
     beta_u = _dense(beta_u)[0]
     beta_l = _dense(beta_l)[0]
@@ -239,7 +243,23 @@ def rtc_gpc_step(alpha_u, beta_u, beta_l, alpha_u_out=None, beta_l_out=None, gam
     a.batch, a.n, a.dt = batch, n, _DT[alpha_u.dtype]
     a.ws, a.ws_bytes = (None if ws is None else ws.data_ptr()), ws_bytes
     a.dev_flags = None if dev_flags is None else dev_flags.data_ptr()
+    if alpha_l is not None:
+        alpha_l = _dense(alpha_l)[0]
+        if alpha_l.shape != alpha_u.shape or alpha_l.dtype != alpha_u.dtype:
+            raise ValueError("alpha_l must have alpha_u's shape and dtype")
+        if alpha_l_out is None:
+            alpha_l_out = torch.empty_like(alpha_u)
+        if beta_u_out is None:
+            beta_u_out = torch.empty_like(alpha_u)
+        a.alpha_l, a.alpha_l_out, a.beta_u_out = alpha_l.data_ptr(), alpha_l_out.data_ptr(), beta_u_out.data_ptr()
+        if gamma_l is not None:
+            gamma_l = _dense(gamma_l)[0]
+            a.gamma_l, a.n_gamma_l = gamma_l.data_ptr(), gamma_l.shape[1]
+        a.events_u_lower = None if events_u_lower is None else events_u_lower.data_ptr()
+        a.events_u_upper = None if events_u_upper is None else events_u_upper.data_ptr()
     _check(_lib.rtc_gpc_step(ctypes.byref(a), _stream()))
+    if alpha_l is not None:
+        return alpha_u_out, beta_l_out, alpha_l_out, beta_u_out
     return alpha_u_out, beta_l_out
 
 

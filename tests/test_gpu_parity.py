@@ -251,6 +251,28 @@ def test_gpc_step(rtc, dtype):
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
+def test_gpc_step_both_sides(rtc, dtype):
+    for n in (1, 50, 1024, 4500):
+        au = wl.random_monotone(15, 5 * n, 3, n, dtype, max_inc=6)
+        al = np.minimum(au, wl.random_monotone(15, 5 * n + 1, 3, n, dtype, max_inc=4, start_max=0))
+        bu = wl.random_monotone(15, 5 * n + 2, 3, n, dtype, max_inc=12, start_max=0)
+        bl = np.minimum(bu, wl.random_monotone(15, 5 * n + 3, 3, n, dtype, max_inc=8, start_max=0))
+        gl = wl.random_monotone(15, 5 * n + 4, 3, n + 3, dtype, max_inc=7, start_max=0)
+        ev_lo = torch.empty((3, n), dtype=torch.int32, device="cuda")
+        ev_up = torch.empty((3, n), dtype=torch.int32, device="cuda")
+        say("gpc both sides", dtype, n)
+        ao, blo, alo, buo = rtc.rtc_gpc_step(dev(au), dev(bu), dev(bl), alpha_l=dev(al), gamma_l=dev(gl),
+                                             events_u_lower=ev_lo, events_u_upper=ev_up)
+        want_a, want_b = oracle.gpc_step(au, bu, bl)
+        want_al, want_bu = oracle.gpc_step_lower(al, bu, bl)
+        assert np.array_equal(host(ao), want_a) and np.array_equal(host(blo), want_b)
+        assert np.array_equal(host(alo), want_al)
+        assert np.array_equal(host(buo), want_bu)
+        assert np.array_equal(host(ev_lo), oracle.pseudo_inverse(gl, want_bu, 0))
+        assert np.array_equal(host(ev_up), oracle.pseudo_inverse(gl, want_bu, 1))
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
 def test_deviations(rtc, dtype):
     for n in (1, 77, 5000):
         alpha = wl.random_monotone(14, n, 4, n, dtype, max_inc=5)

@@ -438,3 +438,46 @@ def test_dual_products_with_zero_curve_are_running_extrema():
     zero = np.zeros(200, np.int64)
     assert np.array_equal(oracle.maxplus_conv(f, zero)[0], np.maximum.accumulate(f))
     assert np.array_equal(oracle.minplus_deconv(f, zero)[0], np.minimum.accumulate(f[::-1])[::-1])
+
+
+# ---------------------------------------------------------------------------
+# greedy processing component: lower arrival / upper service side
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("r,Ru,Rl,T", [(2, 5, 3, 10), (1, 1, 1, 0), (3, 7, 3, 25)])
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_gpc_lower_closed_forms(r, Ru, Rl, T, dtype):
+    """alpha^l = r*D, beta^u = Ru*D (Ru >= r), beta^l = Rl*(D-T)^+ (Rl >= r):
+    alpha'^l = r*(D-T)^+ and beta'^u = (Ru-r)*D, exactly, on the whole finite horizon."""
+    n = 220
+    d = np.arange(n)
+    al = (r * d).astype(dtype)
+    bu = (Ru * d).astype(dtype)
+    bl = wl.rate_latency(n, Rl, T, dtype)
+    ao, uo = oracle.gpc_step_lower(al, bu, bl)
+    assert np.array_equal(ao[0], (r * np.maximum(0, d - T)).astype(dtype))
+    assert np.array_equal(uo[0], ((Ru - r) * d).astype(dtype))
+
+
+def test_gpc_lower_from_parts_brute_force_and_invariants():
+    rng = np.random.default_rng(81)
+    for n in (1, 2, 9, 48, 160):
+        al = _curve(rng, n, np.int64, hi=4, start_hi=0)
+        bu = _curve(rng, n, np.int64, hi=12, start_hi=0)
+        bl = np.minimum(bu, _curve(rng, n, np.int64, hi=8, start_hi=0))
+        ao, uo = oracle.gpc_step_lower(al, bu, bl)
+        if n <= 64:
+            d = bf_deconv(al.tolist(), bu.tolist())
+            c = bf_conv(d, bl.tolist())
+            assert ao[0].tolist() == [min(x, y) for x, y in zip(c, bl.tolist())]
+            want = [max(0, min(int(bu[k]) - int(al[k]) for k in range(j, n))) for j in range(n)]
+            assert uo[0].tolist() == want
+        else:
+            c = oracle.minplus_conv(oracle.maxplus_deconv(al, bu)[0], bl)[0]
+            assert np.array_equal(ao[0], np.minimum(c, bl))
+            assert np.array_equal(uo[0], np.maximum(0, np.minimum.accumulate((bu - al)[::-1])[::-1]))
+        assert np.all(ao[0] <= bl) and np.all(np.diff(uo[0]) >= 0) and np.all(uo[0] >= 0)
+        # the remaining upper service dominates the remaining lower service when alpha^l <= alpha^u
+        au = al + _curve(rng, n, np.int64, hi=3)
+        _, lo = oracle.gpc_step(au, bu, bl)
+        assert np.all(uo[0] >= np.minimum(lo[0], uo[0]))
