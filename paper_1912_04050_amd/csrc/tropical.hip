@@ -122,25 +122,41 @@ constexpr int kPkHalf = 64 * kPkR;
 constexpr int kPkW = 2 * kPkHalf;
 constexpr int kPkChunk = Tile<int32_t, kPkR>::kChunk;
 constexpr int kPkBlock = 256;          // granularity of the window minima / maxima
+constexpr int kPkSub = 128;            // finer re-basing granularity of the uniform operand (steps)
+constexpr int kPkSubBlocks = kPkSub / kPkR;
+constexpr int kPkSubs = kPkChunk / kPkSub;   // sub-chunks per chunk (8: their flags fit a byte)
 constexpr uint32_t kPkPoison = 0xFFFFu;
+static_assert(kPkSubs == 8, "the packed path keeps one flag bit per sub-chunk in a byte");
 
-// Per-row auxiliary arrays of the packed path (all in the caller's workspace).
+// Per-row auxiliary arrays of the packed path (all in the caller's workspace).  The uniform
+// operand is re-based at two granularities: per chunk of 1024 steps (one fold per chunk, used
+// when the whole chunk's range fits) and per sub-chunk of 128 steps (for operands whose slopes
+// differ, where only short runs fit 16 bits).
 struct PackAux {
-  const uint32_t* apk;     // [B][npad]   re-based detrended uniform operand, both halves, 0xFFFFFFFF beyond n
+  const uint32_t* apk;     // [B][npad]   uniform operand, detrended, re-based per chunk, both halves
+  const uint32_t* apk_s;   // [B][npad]   the same, re-based per sub-chunk
   const int32_t* bd;       // [B][n]      detrended window operand, in window-index order
-  const int32_t* ab;       // [B][nchunk] chunk minimum of ad
-  const int32_t* ar;       // [B][nchunk] chunk range of ad
+  const int32_t* ab;       // [B][nchunk] chunk minimum of the detrended uniform operand
+  const int32_t* ar;       // [B][nchunk] chunk range
+  const int32_t* ab_s;     // [B][nsub]   sub-chunk minimum
+  const int32_t* ar_s;     // [B][nsub]   sub-chunk range
   const int32_t* bmn;      // [B][nblk]   minimum of bd per block of kPkBlock
   const int32_t* bmx;      // [B][nblk]   maximum
   const int32_t* rho;      // [B]         slope removed from both operands
   const int32_t* pack_ok;  // [B]         row is eligible for the packed path
-  int32_t npad, nchunk, nblk;
+  int32_t npad, nchunk, nsub, nblk;
 };
 
-// Does the packed kernel own chunk c of the 2048-wide tile T2 of this row?  Evaluated
-// identically (wave-uniform) by both kernels.  *gb receives the window base.
-__device__ __forceinline__ bool chunk_packable(const PackAux& x, int row, int T2, int c, int n, int32_t* gb) {
-  if (x.pack_ok[row] == 0) return false;
+constexpr int kPlanWhole = 0x100;   // chunk_plan: the whole chunk packs with the chunk-level re-basing
+
+// Which part of chunk c of the 2048-wide tile T2 of this row do the packed items own?
+// Returns kPlanWhole | 0xFF when the whole chunk qualifies with the chunk-level base, else a
+// byte with one bit per sub-chunk that qualifies with its own base (0: nothing).  Evaluated
+// identically (wave-uniform) by packed and 32-bit items.  *gb receives the window base, *br the
+// window range.
+__device__ __forceinline__ int chunk_plan(const PackAux& x, int row, int T2, int c, int n, int32_t* gb,
+                                          int32_t* br) {
+  if (x.pack_ok[row] == 0) return 0;
   const int sc = c * kPkChunk;
   int lo = T2 * kPkW - sc - kPkChunk;
   int hi = T2 * kPkW + kPkW - sc;
@@ -155,8 +171,16 @@ __device__ __forceinline__ bool chunk_packable(const PackAux& x, int row, int T2
     mx = max(mx, mxp[b]);
   }
   *gb = mn;
-  const int64_t range = (int64_t)x.ar[(int64_t)row * x.nchunk + c] + ((int64_t)mx - (int64_t)mn);
-  return range <= 65534;
+  const int64_t wr = (int64_t)mx - (int64_t)mn;
+  if (wr > 65534) return 0;
+  *br = (int32_t)wr;
+  if ((int64_t)x.ar[(int64_t)row * x.nchunk + c] + wr <= 65534) return kPlanWhole | 0xFF;
+  const int32_t* ars = x.ar_s + (int64_t)row * x.nsub + c * kPkSubs;
+  int plan = 0;
+#pragma unroll
+  for (int j = 0; j < kPkSubs; ++j)
+    if ((int64_t)ars[j] + wr <= 65534) plan |= 1 << j;
+  return plan;
 }
 
 struct TropicalArgs {
@@ -259,12 +283,15 @@ __device__ __forceinline__ void tropical_body(const TropicalArgs& p, unsigned ch
   for (int r = 0; r < R; ++r) acc[r] = SR::identity();
 
   for (int sc = sa; sc < sb; sc += TL::kChunk) {
-    if (aux) {
-      int32_t gb;
-      if (chunk_packable(p.aux, row, t0 / kPkW, sc / kPkChunk, n, &gb)) continue;
-    }
     const int ce = min(sc + TL::kChunk, sb);
     const int nblk = (ce - sc + R - 1) / R;
+    int plan = 0;   // bit j: the blocks of sub-chunk j of this chunk belong to packed items
+    if (aux) {
+      int32_t gb, br;
+      plan = chunk_plan(p.aux, row, t0 / kPkW, sc / kPkChunk, n, &gb, &br) & 0xFF;
+      const int need = (1 << ((nblk + kPkSubBlocks - 1) / kPkSubBlocks)) - 1;
+      if ((plan & need) == need) continue;
+    }
     // LDS slot q holds window elements [gbase + q*R, gbase + q*R + R)
     const int gbase = t0 - (sc + nblk * R);
     const int count = (64 + nblk) * R;
@@ -284,7 +311,7 @@ __device__ __forceinline__ void tropical_body(const TropicalArgs& p, unsigned ch
         const int s0 = sc + i * R;
         load_group<T, R>(w1, lds, lane + nblk - i - 1);
         const int j = (s0 >= t0) ? (s0 - t0) / R : -1;
-        if (j < 0 || (s0 + R < n && j < 63)) {
+        if ((j < 0 || (s0 + R < n && j < 63)) && !((plan >> (i / kPkSubBlocks)) & 1)) {
           T u[R];
 #pragma unroll
           for (int k = 0; k < R; ++k) u[k] = arow[s0 + k];
@@ -295,7 +322,7 @@ __device__ __forceinline__ void tropical_body(const TropicalArgs& p, unsigned ch
         const int s0 = sc + (i + 1) * R;
         load_group<T, R>(w0, lds, lane + nblk - i - 2);
         const int j = (s0 >= t0) ? (s0 - t0) / R : -1;
-        if (j < 0 || (s0 + R < n && j < 63)) {
+        if ((j < 0 || (s0 + R < n && j < 63)) && !((plan >> ((i + 1) / kPkSubBlocks)) & 1)) {
           T u[R];
 #pragma unroll
           for (int k = 0; k < R; ++k) u[k] = arow[s0 + k];
@@ -309,8 +336,10 @@ __device__ __forceinline__ void tropical_body(const TropicalArgs& p, unsigned ch
   // the lane's own triangle: steps s = tl+k against outputs tl+r, r >= k, window index r-k
   bool triangle = sa <= t0 && t0 < sb;
   if (aux && triangle) {
-    int32_t gb;
-    if (chunk_packable(p.aux, row, t0 / kPkW, t0 / kPkChunk, n, &gb)) triangle = false;
+    // the triangle of lane l lies in sub-chunk l*R / kPkSub of the diagonal chunk
+    int32_t gb, br;
+    const int plan = chunk_plan(p.aux, row, t0 / kPkW, t0 / kPkChunk, n, &gb, &br);
+    if ((plan >> (lane * R / kPkSub)) & 1) triangle = false;
   }
   if (triangle) {
     T b0[R];
@@ -388,7 +417,7 @@ __device__ __forceinline__ void block_steps_packed(uint32_t (&acc)[kPkR], const 
 
 // One wave owns 2048 outputs of the triangular product: the low 16 bits of every packed
 // register belong to output t0 + 16*lane + r, the high 16 bits to output t0 + 1024 + 16*lane + r.
-// Only chunks for which chunk_packable() holds are processed; results merge into out with
+// Only the chunks / sub-chunks that chunk_plan() grants are processed; results merge into out with
 // atomic min / max.
 //   convolution:   lane value = (bd - gb) + (ad - ab); poison 0xFFFF (saturating add, min)
 //   deconvolution: lane value = (bd - gb) + ar + 1 - (ad - ab) >= 1; poison 0 for the window,
@@ -403,9 +432,10 @@ __device__ __forceinline__ void packed_body(const TropicalArgs& p, unsigned char
   const PackAux& x = p.aux;
   if (x.pack_ok[row] == 0) return;
   const uint32_t* __restrict__ apk = x.apk + (int64_t)row * x.npad;
+  const uint32_t* __restrict__ apk_s = x.apk_s + (int64_t)row * x.npad;
   const int32_t* __restrict__ bd = x.bd + (int64_t)row * n;
   const int32_t* __restrict__ ab = x.ab + (int64_t)row * x.nchunk;
-  const int32_t* __restrict__ ar = x.ar + (int64_t)row * x.nchunk;
+  const int32_t* __restrict__ ab_s = x.ab_s + (int64_t)row * x.nsub;
   constexpr bool MAXF = op_max(OP);   // arithmetic flavour: saturating subtract + max, or saturating add + min
   constexpr int32_t kIdent = MAXF ? INT32_MIN : INT32_MAX;
   constexpr uint32_t kWinPoison = MAXF ? 0u : kPkPoison;   // staged for window positions that do not exist
@@ -416,14 +446,18 @@ __device__ __forceinline__ void packed_body(const TropicalArgs& p, unsigned char
   for (int r = 0; r < kPkR; ++r) { acc_lo[r] = kIdent; acc_hi[r] = kIdent; }
 
   for (int sc = sa; sc < sb; sc += kPkChunk) {
-    int32_t gb;
+    int32_t gb, br;
     const int c = sc / kPkChunk;
-    if (!chunk_packable(x, row, t0 / kPkW, c, n, &gb)) continue;
+    const int plan = chunk_plan(x, row, t0 / kPkW, c, n, &gb, &br);
+    if (plan == 0) continue;
     const int ce = min(sc + kPkChunk, sb);
     const int nblk = (ce - sc + kPkR - 1) / kPkR;
     const int gbase = t0 - (sc + nblk * kPkR);
     const int count = (64 + nblk) * kPkR;
-    const uint32_t lift = MAXF ? (uint32_t)ar[c] + 1u : 0u;
+    // max flavour: window values are lifted so that every existing candidate stays >= 1 after
+    // the saturating subtraction (the window spans at most br, any packable run of the uniform
+    // operand at most 65534 - br)
+    const uint32_t lift = MAXF ? 65535u - (uint32_t)br : 0u;
     __syncthreads();
     for (int e = lane; e < count; e += 64) {
       const int il = gbase + e, ih = il + kPkHalf;
@@ -434,39 +468,52 @@ __device__ __forceinline__ void packed_body(const TropicalArgs& p, unsigned char
     }
     __syncthreads();
 
-    uint32_t acc[kPkR];
+    // a run = a range of blocks that shares one base of the uniform operand: the whole chunk,
+    // or one qualifying sub-chunk
+    const bool whole = (plan & kPlanWhole) != 0;
+    const uint32_t* __restrict__ usrc = whole ? apk : apk_s;
+    const int nrun = whole ? 1 : kPkSubs;
+    for (int run = 0; run < nrun; ++run) {
+      const int first = whole ? 0 : run * kPkSubBlocks;
+      if (first >= nblk) break;
+      if (!whole && !((plan >> run) & 1)) continue;
+      const int last = whole ? nblk : min(first + kPkSubBlocks, nblk);
+      const int32_t ubase = whole ? ab[c] : ab_s[c * kPkSubs + run];
+
+      uint32_t acc[kPkR];
 #pragma unroll
-    for (int r = 0; r < kPkR; ++r) acc[r] = kAccPoison * 0x10001u;
-    uint32_t w0[kPkR], w1[kPkR];
-    load_group<uint32_t, kPkR>(w0, lds, lane + nblk);
-    for (int i = 0; i < nblk; i += 2) {
-      {
-        const int s0 = sc + i * kPkR;
-        load_group<uint32_t, kPkR>(w1, lds, lane + nblk - i - 1);
-        uint32_t u[kPkR];
+      for (int r = 0; r < kPkR; ++r) acc[r] = kAccPoison * 0x10001u;
+      uint32_t w0[kPkR], w1[kPkR];
+      load_group<uint32_t, kPkR>(w0, lds, lane + nblk - first);
+      for (int i = first; i < last; i += 2) {
+        {
+          const int s0 = sc + i * kPkR;
+          load_group<uint32_t, kPkR>(w1, lds, lane + nblk - i - 1);
+          uint32_t u[kPkR];
 #pragma unroll
-        for (int k = 0; k < kPkR; ++k) u[k] = apk[s0 + k];
-        block_steps_packed<MAXF>(acc, u, w1, w0);
+          for (int k = 0; k < kPkR; ++k) u[k] = usrc[s0 + k];
+          block_steps_packed<MAXF>(acc, u, w1, w0);
+        }
+        if (i + 1 < last) {
+          const int s0 = sc + (i + 1) * kPkR;
+          load_group<uint32_t, kPkR>(w0, lds, lane + nblk - i - 2);
+          uint32_t u[kPkR];
+#pragma unroll
+          for (int k = 0; k < kPkR; ++k) u[k] = usrc[s0 + k];
+          block_steps_packed<MAXF>(acc, u, w0, w1);
+        }
       }
-      if (i + 1 < nblk) {
-        const int s0 = sc + (i + 1) * kPkR;
-        load_group<uint32_t, kPkR>(w0, lds, lane + nblk - i - 2);
-        uint32_t u[kPkR];
+      // fold the run into the 32-bit accumulators (detrended domain, wrap-around arithmetic:
+      // every folded value is a true candidate, which fits)
+      const uint32_t cb = MAXF ? (uint32_t)gb - (uint32_t)ubase - lift : (uint32_t)ubase + (uint32_t)gb;
 #pragma unroll
-        for (int k = 0; k < kPkR; ++k) u[k] = apk[s0 + k];
-        block_steps_packed<MAXF>(acc, u, w0, w1);
+      for (int r = 0; r < kPkR; ++r) {
+        const uint32_t vl = acc[r] & 0xFFFFu, vh = acc[r] >> 16;
+        const int32_t cl = vl != kAccPoison ? (int32_t)(cb + vl) : kIdent;
+        const int32_t ch = vh != kAccPoison ? (int32_t)(cb + vh) : kIdent;
+        acc_lo[r] = MAXF ? max(acc_lo[r], cl) : min(acc_lo[r], cl);
+        acc_hi[r] = MAXF ? max(acc_hi[r], ch) : min(acc_hi[r], ch);
       }
-    }
-    // fold the chunk into the 32-bit accumulators (detrended domain, wrap-around arithmetic:
-    // every folded value is a true candidate, which fits)
-    const uint32_t cb = MAXF ? (uint32_t)gb - (uint32_t)ab[c] - lift : (uint32_t)ab[c] + (uint32_t)gb;
-#pragma unroll
-    for (int r = 0; r < kPkR; ++r) {
-      const uint32_t vl = acc[r] & 0xFFFFu, vh = acc[r] >> 16;
-      const int32_t cl = vl != kAccPoison ? (int32_t)(cb + vl) : kIdent;
-      const int32_t ch = vh != kAccPoison ? (int32_t)(cb + vh) : kIdent;
-      acc_lo[r] = MAXF ? max(acc_lo[r], cl) : min(acc_lo[r], cl);
-      acc_hi[r] = MAXF ? max(acc_hi[r], ch) : min(acc_hi[r], ch);
     }
   }
 
@@ -584,11 +631,12 @@ __global__ __launch_bounds__(1024) void probe_kernel(const T* __restrict__ f, in
         int32_t r = 0;
         if (ok && n > 1) {
           r = w1 > w0 ? (int32_t)((w1 - w0) / (T)(n - 1)) : 0;
-          // performance heuristic: when the two average slopes differ so much that a chunk of the
-          // uniform operand cannot stay inside 16 bits after detrending, do not prepare the row
+          // performance heuristic: when the two average slopes differ so much that not even a
+          // sub-chunk of the uniform operand stays inside 16 bits after detrending, do not
+          // prepare the row
           const int64_t ru = (int64_t)((u1 - u0) / (T)(n - 1));
           const int64_t diff = ru > r ? ru - r : r - ru;
-          if (diff * kPkChunk > 50000) pack_ok[row] = 0;
+          if (diff * kPkSub > 50000) pack_ok[row] = 0;
         }
         rho[row] = r;
       }
@@ -616,7 +664,9 @@ __global__ __launch_bounds__(1024) void prep_kernel(const int32_t* __restrict__ 
                                                     bool deconv, bool neg, int npad, int nchunk, int nblk,
                                                     const int32_t* __restrict__ rho,
                                                     const int32_t* __restrict__ pack_ok,
-                                                    uint32_t* __restrict__ apk, int32_t* __restrict__ bd, int32_t* __restrict__ ab,
+                                                    uint32_t* __restrict__ apk, uint32_t* __restrict__ apk_s,
+                                                    int32_t* __restrict__ ab_s, int32_t* __restrict__ ar_s,
+                                                    int nsub, int32_t* __restrict__ bd, int32_t* __restrict__ ab,
                                                     int32_t* __restrict__ ar, int32_t* __restrict__ bmn,
                                                     int32_t* __restrict__ bmx) {
   __shared__ int32_t s_amn[16], s_amx[16], s_bmn[16], s_bmx[16];
@@ -640,6 +690,17 @@ __global__ __launch_bounds__(1024) void prep_kernel(const int32_t* __restrict__ 
 #pragma unroll
   for (int w = 0; w < 16; ++w) { cmn = min(cmn, s_amn[w]); cmx = max(cmx, s_amx[w]); }
   apk[(int64_t)row * npad + i] = valid ? min((uint32_t)adv - (uint32_t)cmn, kPkPoison) * 0x10001u : 0xFFFFFFFFu;
+  // sub-chunk of 128 indices = 2 waves
+  const int sub = threadIdx.x / kPkSub;
+  const int32_t smn = min(s_amn[2 * sub], s_amn[2 * sub + 1]);
+  const int32_t smx = max(s_amx[2 * sub], s_amx[2 * sub + 1]);
+  apk_s[(int64_t)row * npad + i] = valid ? min((uint32_t)adv - (uint32_t)smn, kPkPoison) * 0x10001u : 0xFFFFFFFFu;
+  if ((threadIdx.x & (kPkSub - 1)) == 0) {
+    const bool any = smx >= smn;   // false when the sub-chunk lies entirely beyond n
+    const int64_t range = (int64_t)smx - (int64_t)smn;
+    ab_s[(int64_t)row * nsub + c * kPkSubs + sub] = any ? smn : 0;
+    ar_s[(int64_t)row * nsub + c * kPkSubs + sub] = any ? (int32_t)(range < 0x7fffffffLL ? range : 0x7fffffffLL) : 0;
+  }
   if (valid) bd[(int64_t)row * n + i] = bdv;
   if (threadIdx.x == 0) {
     ab[(int64_t)row * nchunk + c] = cmn;
@@ -678,9 +739,9 @@ __global__ __launch_bounds__(256) void decide_kernel(PackAux x, int n, int32_t* 
       if (ic >= ns) continue;
       const int c = (int)((int64_t)ic * nc / ns);
       const float weight = (float)nc / (float)ns * ((float)n_t2 / (float)nt);
-      int32_t gb;
+      int32_t gb, br;
       all += weight;
-      if (chunk_packable(x, row, T2, c, n, &gb)) yes += weight;
+      yes += weight * (float)__builtin_popcount(chunk_plan(x, row, T2, c, n, &gb, &br) & 0xFF) * (1.f / kPkSubs);
     }
   }
 #pragma unroll
@@ -780,21 +841,25 @@ int run_product(const T* a, int64_t stride_a, const T* b, int64_t stride_b, OutT
 
 // Layout of the packed path's arrays inside the workspace.
 struct PackLayout {
-  int64_t npad, nchunk, nblk;
-  size_t off_apk, off_bd, off_ab, off_ar, off_bmn, off_bmx, off_rho, off_ok, bytes;
+  int64_t npad, nchunk, nsub, nblk;
+  size_t off_apk, off_apk_s, off_bd, off_ab, off_ar, off_ab_s, off_ar_s, off_bmn, off_bmx, off_rho, off_ok, bytes;
 };
 
 PackLayout pack_layout(int64_t batch, int64_t n) {
   PackLayout L;
   L.nchunk = (n + kPkChunk - 1) / kPkChunk;
   L.npad = L.nchunk * kPkChunk;
+  L.nsub = L.nchunk * kPkSubs;
   L.nblk = (n + kPkBlock - 1) / kPkBlock;
   size_t o = 0;
   auto take = [&](size_t elems) { const size_t at = o; o += (elems * 4 + 255) / 256 * 256; return at; };
   L.off_apk = take((size_t)batch * L.npad);
+  L.off_apk_s = take((size_t)batch * L.npad);
   L.off_bd = take((size_t)batch * n);
   L.off_ab = take((size_t)batch * L.nchunk);
   L.off_ar = take((size_t)batch * L.nchunk);
+  L.off_ab_s = take((size_t)batch * L.nsub);
+  L.off_ar_s = take((size_t)batch * L.nsub);
   L.off_bmn = take((size_t)batch * L.nblk);
   L.off_bmx = take((size_t)batch * L.nblk);
   L.off_rho = take((size_t)batch);
@@ -813,6 +878,9 @@ int run_packed(const int32_t* f32, int64_t stride_f, const int32_t* g32, int64_t
                hipStream_t stream) {
   PackAux aux;
   aux.apk = reinterpret_cast<uint32_t*>(wsp + L.off_apk);
+  aux.apk_s = reinterpret_cast<uint32_t*>(wsp + L.off_apk_s);
+  aux.ab_s = reinterpret_cast<int32_t*>(wsp + L.off_ab_s);
+  aux.ar_s = reinterpret_cast<int32_t*>(wsp + L.off_ar_s);
   aux.bd = reinterpret_cast<int32_t*>(wsp + L.off_bd);
   aux.ab = reinterpret_cast<int32_t*>(wsp + L.off_ab);
   aux.ar = reinterpret_cast<int32_t*>(wsp + L.off_ar);
@@ -820,13 +888,16 @@ int run_packed(const int32_t* f32, int64_t stride_f, const int32_t* g32, int64_t
   aux.bmx = reinterpret_cast<int32_t*>(wsp + L.off_bmx);
   aux.rho = reinterpret_cast<int32_t*>(wsp + L.off_rho);
   aux.pack_ok = reinterpret_cast<int32_t*>(wsp + L.off_ok);
-  aux.npad = (int32_t)L.npad; aux.nchunk = (int32_t)L.nchunk; aux.nblk = (int32_t)L.nblk;
+  aux.npad = (int32_t)L.npad; aux.nchunk = (int32_t)L.nchunk; aux.nsub = (int32_t)L.nsub;
+  aux.nblk = (int32_t)L.nblk;
   if (batch * L.nchunk > 0x7fffffffLL) return RTC_ERR_SHAPE;
   // uniform operand: f for the convolution, g for the deconvolution; window operand: the other
   hipLaunchKernelGGL(prep_kernel, dim3((uint32_t)(batch * L.nchunk)), dim3(1024), 0, stream,
                      op_sub(OP) ? g32 : f32, op_sub(OP) ? stride_g : stride_f, op_sub(OP) ? f32 : g32,
                      op_sub(OP) ? stride_f : stride_g, (int)n, op_sub(OP), op_sub(OP) != op_max(OP), (int)L.npad, (int)L.nchunk, (int)L.nblk,
-                     aux.rho, aux.pack_ok, const_cast<uint32_t*>(aux.apk), const_cast<int32_t*>(aux.bd), const_cast<int32_t*>(aux.ab), const_cast<int32_t*>(aux.ar),
+                     aux.rho, aux.pack_ok, const_cast<uint32_t*>(aux.apk), const_cast<uint32_t*>(aux.apk_s),
+                     const_cast<int32_t*>(aux.ab_s), const_cast<int32_t*>(aux.ar_s), (int)L.nsub,
+                     const_cast<int32_t*>(aux.bd), const_cast<int32_t*>(aux.ab), const_cast<int32_t*>(aux.ar),
                      const_cast<int32_t*>(aux.bmn), const_cast<int32_t*>(aux.bmx));
   hipLaunchKernelGGL(decide_kernel, dim3((uint32_t)batch), dim3(256), 0, stream, aux, (int)n,
                      const_cast<int32_t*>(aux.pack_ok));

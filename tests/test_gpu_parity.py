@@ -126,6 +126,23 @@ def test_packed_path_mixed_chunks(rtc):
             check_products(rtc, f, g, "packed mixed int64")
 
 
+def test_packed_path_unequal_slopes(rtc):
+    """Operands whose average slopes differ: whole chunks of 1024 steps do not fit 16 bits after
+    detrending, runs of 128 steps do (the sub-chunk re-basing), steeper ones do not at all."""
+    rng = np.random.default_rng(24)
+    n = 6000
+    rows = []
+    for slope_f, slope_g in ((5, 64), (64, 5), (1, 300), (300, 280), (0, 450), (700, 3)):
+        f = np.cumsum(rng.integers(0, 2 * slope_f + 1, n))
+        g = np.cumsum(rng.integers(0, 2 * slope_g + 1, n))
+        rows.append((f, g))
+    f = np.stack([r[0] for r in rows]).astype(np.int32)
+    g = np.stack([r[1] for r in rows]).astype(np.int32)
+    _both_paths(rtc, f, g, "packed unequal slopes")
+    check_duals(rtc, f, g, "packed unequal slopes, duals")
+    check_products(rtc, f.astype(np.int64), g.astype(np.int64), "packed unequal slopes int64")
+
+
 def test_packed_path_value_limits(rtc):
     """Values at the edge of the packed path's eligibility (|v| < 2^29) and beyond it."""
     n = 3000
