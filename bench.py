@@ -94,15 +94,19 @@ def per_config_table(seed, peak_ops, with_cpu):
         fn()
         return round(time.perf_counter() - ts, 4)
 
-    def product_rows(cfg, f_h, g_h, cpu_rows, storage):
+    def product_rows(cfg, f_h, g_h, cpu_rows, storage, duals=False):
         B, N = f_h.shape
         f, g = dev(f_h), dev(g_h)
         out = torch.empty_like(f)
         ws = torch.empty(max(16, rtc.rtc_workspace_bytes(rtc.RTC_OP_CONV, B, N, f.dtype)), dtype=torch.uint8,
                          device="cuda")
         po = B * N * (N + 1) // 2
-        for name, fn, ofn in (("minplus_conv", rtc.rtc_minplus_conv, "minplus_conv"),
-                              ("maxplus_deconv", rtc.rtc_maxplus_deconv, "maxplus_deconv")):
+        ops = [("minplus_conv", rtc.rtc_minplus_conv, "minplus_conv"),
+               ("maxplus_deconv", rtc.rtc_maxplus_deconv, "maxplus_deconv")]
+        if duals:
+            ops += [("maxplus_conv", rtc.rtc_maxplus_conv, "maxplus_conv"),
+                    ("minplus_deconv", rtc.rtc_minplus_deconv, "minplus_deconv")]
+        for name, fn, ofn in ops:
             med, mn = gpu_ms(lambda: fn(f, g, out=out, ws=ws))
             r = {"config": cfg, "op": name, "dtype": storage, "batch": B, "n": N, "gpu_ms": round(med, 4),
                  "gpu_ms_min": round(mn, 4), "pair_ops": po, "gpair_ops_per_s": round(po / med / 1e6, 1),
@@ -137,7 +141,7 @@ def per_config_table(seed, peak_ops, with_cpu):
     # config 3: int64 storage (range-probed 32-bit arithmetic), native int32, and forced 64-bit arithmetic
     c = wl.config3(seed, 64, 65536)
     product_rows(3, c["f"], c["g"], 8, "int64 storage, int32 arithmetic")
-    product_rows(3, c["f"].astype(np.int32), c["g"].astype(np.int32), 8, "int32")
+    product_rows(3, c["f"].astype(np.int32), c["g"].astype(np.int32), 8, "int32", duals=True)
     product_rows(3, c["f"][:16] + (1 << 40), c["g"][:16], 4, "int64 arithmetic (values beyond 2^30)")
     # config 4: one component of all 256 chains, then the whole 16-component chain
     c = wl.config4(seed, 256, 16, 16384)
