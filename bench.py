@@ -46,7 +46,7 @@ def parse():
 # HBM traffic of one launch of the dominant kernel on the headline workload, from two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by what the same counters read for a
 # plain 1 GiB device copy; see profiles/.  None for any other workload.
-HEADLINE_TRAFFIC_BYTES = 593862317   # 38.4 MiB fetched + 528 MiB of atomic-merge writes (profiles/fused_kernel_headline_pmc.md)
+HEADLINE_TRAFFIC_BYTES = 615104500   # 58.6 MiB fetched + 528 MiB of atomic-merge writes (profiles/fused_kernel_headline_pmc.md)
 
 
 def headline_traffic(batch, n):
