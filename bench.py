@@ -142,7 +142,8 @@ def per_config_table(seed, peak_ops, with_cpu):
     c = wl.config3(seed, 64, 65536)
     product_rows(3, c["f"], c["g"], 8, "int64 storage, int32 arithmetic")
     product_rows(3, c["f"].astype(np.int32), c["g"].astype(np.int32), 8, "int32", duals=True)
-    product_rows(3, c["f"][:16] + (1 << 40), c["g"][:16], 4, "int64 arithmetic (values beyond 2^30)")
+    product_rows(3, c["f"][:16] + (1 << 40), c["g"][:16] - (1 << 45), 4, "int64 storage with large offsets (re-based, int32 arithmetic)")
+    product_rows(3, c["f"][:16] * 4096, c["g"][:16] * 4096, 4, "int64 arithmetic (value range beyond 2^30)")
     # config 4: one component of all 256 chains, then the whole 16-component chain
     c = wl.config4(seed, 256, 16, 16384)
     gam, abar = dev(c["gamma_u"]), dev(c["alpha_bar_u"])

@@ -61,9 +61,10 @@ typedef enum {
  * Truncated horizon: samples beyond n-1 do not exist, the output has n samples.
  * f, g: [batch] rows with element strides stride_f / stride_g.  out: [batch][n].
  * ws / ws_bytes: device scratch, rtc_workspace_bytes(RTC_OP_CONV, ...) bytes.
- *   RTC_F64 needs none.  RTC_I64 requires it: the rows are probed and, when every value lies
- *   in [-2^30, 2^30), convolved in 32-bit arithmetic on narrowed copies -- exact, because every
- *   candidate then fits -- and widened on store; other rows take the 64-bit kernel.
+ *   RTC_F64 needs none.  RTC_I64 requires it: the rows are probed and, when the value range
+ *   (max - min) of each of the two rows is below 2^30, re-based to their minima, convolved in
+ *   32-bit arithmetic on narrowed copies -- exact, because every candidate then fits -- and
+ *   widened and shifted back on store; other rows take the 64-bit kernel.
  *   For RTC_I32 it is optional: with a workspace of the full size the library also uses its
  *   packed 16-bit kernel on every (tile, chunk of 1024 steps) whose detrended value ranges fit
  *   16 bits (same exact results, up to 1.5x faster); with ws == NULL or a smaller size only the

@@ -197,6 +197,7 @@ struct TropicalArgs {
   int32_t n_tiles;
   int32_t fold_width;   // work items launched per folded tile pair (see decode_item)
   int32_t seg;          // steps of s per segment, a multiple of the chunk length
+  const int64_t* out_base;  // optional per-row constant added to every stored value (re-based int64 rows)
   int32_t use_aux;      // 1: skip the chunks that the packed items of the same launch own (see aux)
   PackAux aux;
 };
@@ -376,6 +377,7 @@ __device__ __forceinline__ void tropical_body(const TropicalArgs& p, unsigned ch
       const T av = xp[x + x / R];
       if (ATOMIC && av == SR::identity()) continue;   // this item saw no candidate of that output
       OutT v = (OutT)av;
+      if (p.out_base != nullptr) v += (OutT)p.out_base[row];
       if (crow) v = sel_min(v, crow[ot]);
       if (ATOMIC) {
         if (op_max(OP)) atomic_max(&orow[ot], v); else atomic_min(&orow[ot], v);
@@ -536,6 +538,7 @@ __device__ __forceinline__ void packed_body(const TropicalArgs& p, unsigned char
       if (t < n && av != kIdent) {
         const int ot = op_sub(OP) ? n - 1 - t : t;
         OutT v = (OutT)(op_sub(OP) ? wrap_sub(av, rho * t) : wrap_add(av, rho * t));
+        if (p.out_base != nullptr) v += (OutT)p.out_base[row];
         if (crow) v = sel_min(v, crow[ot]);
         if (op_max(OP)) atomic_max(&orow[ot], v); else atomic_min(&orow[ot], v);
       }
@@ -569,16 +572,12 @@ __global__ __launch_bounds__(256) void fill_kernel(T* __restrict__ dst, int64_t 
 }
 
 // Range probe of one row pair.  Finds min/max of both rows, raises the overflow flag when
-// the bounds do not prove that every candidate fits, (int64 only) writes 32-bit copies
-// of both rows plus a selector saying whether the 32-bit kernel may be used for this row, and
-// (optionally) decides eligibility for the packed path and the slope to remove.
+// the bounds do not prove that every candidate fits and (optionally) decides eligibility for
+// the packed path and the slope to remove.
 template <typename T>
 __global__ __launch_bounds__(1024) void probe_kernel(const T* __restrict__ f, int64_t stride_f,
                                                      const T* __restrict__ g, int64_t stride_g, int n,
-                                                     bool deconv, int32_t* __restrict__ f32,
-                                                     int32_t* __restrict__ g32,
-                                                     int32_t* __restrict__ narrow_ok,
-                                                     int32_t* __restrict__ pack_ok,
+                                                     bool deconv, int32_t* __restrict__ pack_ok,
                                                      int32_t* __restrict__ rho,
                                                      int32_t* __restrict__ dev_flags) {
   __shared__ T red[4][16];
@@ -590,10 +589,6 @@ __global__ __launch_bounds__(1024) void probe_kernel(const T* __restrict__ f, in
     const T fv = fr[i], gv = gr[i];
     fmin = sel_min(fmin, fv); fmax = sel_max(fmax, fv);
     gmin = sel_min(gmin, gv); gmax = sel_max(gmax, gv);
-    if (f32) {
-      f32[(int64_t)row * n + i] = (int32_t)fv;
-      g32[(int64_t)row * n + i] = (int32_t)gv;
-    }
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) {
@@ -616,10 +611,6 @@ __global__ __launch_bounds__(1024) void probe_kernel(const T* __restrict__ f, in
       const bool bad = deconv ? (__builtin_sub_overflow(fmax, gmin, &dummy) || __builtin_sub_overflow(fmin, gmax, &dummy))
                               : (__builtin_add_overflow(fmax, gmax, &dummy) || __builtin_add_overflow(fmin, gmin, &dummy));
       if (bad && dev_flags) atomicOr(dev_flags, RTC_FLAG_OVERFLOW);
-      if (narrow_ok) {
-        const T lim = (T)1 << 30;
-        narrow_ok[row] = (fmin >= -lim && fmax < lim && gmin >= -lim && gmax < lim) ? 1 : 0;
-      }
       if (pack_ok) {
         // |values| < 2^29 keeps the detrended rows inside int32 (rho*i <= g[n-1]-g[0] < 2^30)
         const T lim = (T)1 << 29;
@@ -640,6 +631,79 @@ __global__ __launch_bounds__(1024) void probe_kernel(const T* __restrict__ f, in
         }
         rho[row] = r;
       }
+    }
+  }
+}
+
+// Range probe of one int64 row pair.  A row whose two value ranges (max - min) are below 2^30
+// is re-based to its minima and copied as int32: every candidate of the re-based rows fits
+// 32 bits, so the 32-bit kernels compute it exactly and add `out_base` (f_min + g_min, or
+// f_min - g_min for the deconvolutions) back on store.  Rows with a wider range keep the
+// 64-bit kernel.  Also: overflow flag, packed-path eligibility and slope, as in probe_kernel.
+__global__ __launch_bounds__(1024) void probe_narrow_kernel(const int64_t* __restrict__ f, int64_t stride_f,
+                                                            const int64_t* __restrict__ g, int64_t stride_g,
+                                                            int n, bool deconv, int32_t* __restrict__ f32,
+                                                            int32_t* __restrict__ g32,
+                                                            int32_t* __restrict__ narrow_ok,
+                                                            int64_t* __restrict__ out_base,
+                                                            int32_t* __restrict__ pack_ok,
+                                                            int32_t* __restrict__ rho,
+                                                            int32_t* __restrict__ dev_flags) {
+  __shared__ int64_t red[4][16];
+  __shared__ int64_t s_base[2];
+  __shared__ int s_narrow;
+  const int row = blockIdx.x;
+  const int64_t* fr = f + (int64_t)row * stride_f;
+  const int64_t* gr = g + (int64_t)row * stride_g;
+  int64_t fmin = INT64_MAX, fmax = INT64_MIN, gmin = INT64_MAX, gmax = INT64_MIN;
+  for (int i = threadIdx.x; i < n; i += blockDim.x) {
+    const int64_t fv = fr[i], gv = gr[i];
+    fmin = sel_min(fmin, fv); fmax = sel_max(fmax, fv);
+    gmin = sel_min(gmin, gv); gmax = sel_max(gmax, gv);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    fmin = sel_min(fmin, __shfl_xor(fmin, off)); fmax = sel_max(fmax, __shfl_xor(fmax, off));
+    gmin = sel_min(gmin, __shfl_xor(gmin, off)); gmax = sel_max(gmax, __shfl_xor(gmax, off));
+  }
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) { red[0][wave] = fmin; red[1][wave] = fmax; red[2][wave] = gmin; red[3][wave] = gmax; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int nw = (blockDim.x + 63) >> 6;
+    for (int w = 1; w < nw; ++w) {
+      fmin = sel_min(fmin, red[0][w]); fmax = sel_max(fmax, red[1][w]);
+      gmin = sel_min(gmin, red[2][w]); gmax = sel_max(gmax, red[3][w]);
+    }
+    int64_t dummy;
+    const bool bad = deconv ? (__builtin_sub_overflow(fmax, gmin, &dummy) || __builtin_sub_overflow(fmin, gmax, &dummy))
+                            : (__builtin_add_overflow(fmax, gmax, &dummy) || __builtin_add_overflow(fmin, gmin, &dummy));
+    if (bad && dev_flags) atomicOr(dev_flags, RTC_FLAG_OVERFLOW);
+    const uint64_t frange = (uint64_t)fmax - (uint64_t)fmin, grange = (uint64_t)gmax - (uint64_t)gmin;
+    const bool narrow = frange < (1ull << 30) && grange < (1ull << 30);
+    narrow_ok[row] = narrow ? 1 : 0;
+    out_base[row] = narrow ? (deconv ? wrap_sub(fmin, gmin) : wrap_add(fmin, gmin)) : 0;
+    s_base[0] = fmin; s_base[1] = gmin; s_narrow = narrow ? 1 : 0;
+    // re-based values lie in [0, 2^29): the detrended rows stay inside int32
+    const bool ok = frange < (1ull << 29) && grange < (1ull << 29);
+    pack_ok[row] = ok ? 1 : 0;
+    int32_t r = 0;
+    if (ok && n > 1) {
+      const int64_t w0 = deconv ? fr[0] : gr[0], w1 = deconv ? fr[n - 1] : gr[n - 1];
+      const int64_t u0 = deconv ? gr[0] : fr[0], u1 = deconv ? gr[n - 1] : fr[n - 1];
+      r = w1 > w0 ? (int32_t)((w1 - w0) / (n - 1)) : 0;
+      const int64_t ru = (u1 - u0) / (n - 1);
+      const int64_t diff = ru > r ? ru - r : r - ru;
+      if (diff * kPkSub > 50000) pack_ok[row] = 0;   // same heuristic as probe_kernel
+    }
+    rho[row] = r;
+  }
+  __syncthreads();
+  if (s_narrow) {
+    const int64_t fb = s_base[0], gb = s_base[1];
+    for (int i = threadIdx.x; i < n; i += blockDim.x) {
+      f32[(int64_t)row * n + i] = (int32_t)(fr[i] - fb);
+      g32[(int64_t)row * n + i] = (int32_t)(gr[i] - gb);
     }
   }
 }
@@ -814,7 +878,7 @@ void launch_fill(OutT* out, int64_t count, hipStream_t stream) {
 template <typename T, typename OutT, int OP>
 int run_product(const T* a, int64_t stride_a, const T* b, int64_t stride_b, OutT* out, const OutT* cap,
                 const int32_t* sel, int sel_want, int64_t batch, int64_t n, hipStream_t stream,
-                bool prefilled, bool force_atomic, const PackAux* aux) {
+                bool prefilled, bool force_atomic, const int64_t* out_base) {
   constexpr int R = RFor<T>::value;
   const Plan pl = make_plan<T>(batch, n);
   if (pl.items > 0x7fffffffLL) return RTC_ERR_SHAPE;
@@ -823,7 +887,7 @@ int run_product(const T* a, int64_t stride_a, const T* b, int64_t stride_b, OutT
   args.stride_a = stride_a; args.stride_b = stride_b; args.sel_want = sel_want;
   args.n = (int32_t)n; args.batch = (int32_t)batch;
   args.n_tiles = pl.n_tiles; args.fold_width = pl.fold_width; args.seg = pl.seg;
-  if (aux != nullptr) { args.use_aux = 1; args.aux = *aux; }
+  args.out_base = out_base;
   constexpr int dtype_code = std::is_same<T, int32_t>::value ? RTC_I32 : std::is_same<T, int64_t>::value ? RTC_I64 : RTC_F64;
   if (pl.atomic || force_atomic) {
     if (!prefilled) launch_fill<OutT, OP>(out, batch * n, stream);
@@ -874,8 +938,8 @@ PackLayout pack_layout(int64_t batch, int64_t n) {
 // sel[row] == 1.
 template <typename OutT, int OP>
 int run_packed(const int32_t* f32, int64_t stride_f, const int32_t* g32, int64_t stride_g, OutT* out,
-               const OutT* cap, const int32_t* sel, int64_t batch, int64_t n, char* wsp, const PackLayout& L,
-               hipStream_t stream) {
+               const OutT* cap, const int32_t* sel, const int64_t* out_base, int64_t batch, int64_t n, char* wsp,
+               const PackLayout& L, hipStream_t stream) {
   PackAux aux;
   aux.apk = reinterpret_cast<uint32_t*>(wsp + L.off_apk);
   aux.apk_s = reinterpret_cast<uint32_t*>(wsp + L.off_apk_s);
@@ -905,7 +969,7 @@ int run_packed(const int32_t* f32, int64_t stride_f, const int32_t* g32, int64_t
   const Plan pg = make_plan<int32_t>(batch, n);
   if (pk.items + pg.items > 0x7fffffffLL) return RTC_ERR_SHAPE;
   TropicalArgs ak = {};
-  ak.out = out; ak.cap = cap; ak.sel = sel; ak.sel_want = 1;
+  ak.out = out; ak.cap = cap; ak.sel = sel; ak.sel_want = 1; ak.out_base = out_base;
   ak.n = (int32_t)n; ak.batch = (int32_t)batch;
   ak.n_tiles = pk.n_tiles; ak.fold_width = pk.fold_width; ak.seg = pk.seg;
   ak.use_aux = 1; ak.aux = aux;
@@ -947,54 +1011,57 @@ int run_typed(const void* f, const void* g, void* out, int64_t batch, int64_t n,
       char* wsp = static_cast<char*>(ws);
       hipLaunchKernelGGL(probe_kernel<int32_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,
                          static_cast<const int32_t*>(f), stride_f, static_cast<const int32_t*>(g), stride_g,
-                         (int)n, op_sub(OP), (int32_t*)nullptr, (int32_t*)nullptr, (int32_t*)nullptr,
-                         reinterpret_cast<int32_t*>(wsp + L.off_ok), reinterpret_cast<int32_t*>(wsp + L.off_rho),
-                         dev_flags);
+                         (int)n, op_sub(OP), reinterpret_cast<int32_t*>(wsp + L.off_ok),
+                         reinterpret_cast<int32_t*>(wsp + L.off_rho), dev_flags);
       launch_fill<int32_t, OP>(static_cast<int32_t*>(out), batch * n, stream);
       return run_packed<int32_t, OP>(static_cast<const int32_t*>(f), stride_f,
                                          static_cast<const int32_t*>(g), stride_g, static_cast<int32_t*>(out),
-                                         static_cast<const int32_t*>(cap), nullptr, batch, n, wsp, L, stream);
+                                         static_cast<const int32_t*>(cap), nullptr, nullptr, batch, n, wsp, L,
+                                         stream);
     }
   }
   if (dev_flags != nullptr && std::numeric_limits<T>::is_integer) {
     hipLaunchKernelGGL(probe_kernel<T>, dim3((uint32_t)batch), dim3(1024), 0, stream,
                        static_cast<const T*>(f), stride_f, static_cast<const T*>(g), stride_g, (int)n,
-                       op_sub(OP), (int32_t*)nullptr, (int32_t*)nullptr, (int32_t*)nullptr, (int32_t*)nullptr,
-                       (int32_t*)nullptr, dev_flags);
+                       op_sub(OP), (int32_t*)nullptr, (int32_t*)nullptr, dev_flags);
   }
   return run_product<T, T, OP>(a, sa, b, sb, static_cast<T*>(out), static_cast<const T*>(cap),
                                    nullptr, 0, batch, n, stream, false, false, nullptr);
 }
 
 // Bytes of the narrowed copies + selector that precede the packed-path arrays for int64 rows.
-size_t narrow_bytes(int64_t batch, int64_t n) {
+size_t narrow_base_offset(int64_t batch, int64_t n) {
   return ((size_t)(2 * batch * n + batch) * sizeof(int32_t) + 255) / 256 * 256;
+}
+size_t narrow_bytes(int64_t batch, int64_t n) {
+  return narrow_base_offset(batch, n) + ((size_t)batch * sizeof(int64_t) + 255) / 256 * 256;
 }
 
 template <int OP>
 int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, int64_t stride_f,
             int64_t stride_g, const void* cap, void* ws, int32_t* dev_flags, hipStream_t stream) {
-  // workspace: [f32: batch*n][g32: batch*n][narrow_ok: batch][packed-path arrays]
+  // workspace: [f32: batch*n][g32: batch*n][narrow_ok: batch][out_base: batch int64][packed-path arrays]
   int32_t* f32 = static_cast<int32_t*>(ws);
   int32_t* g32 = f32 + batch * n;
   int32_t* ok = g32 + batch * n;
+  int64_t* base = reinterpret_cast<int64_t*>(static_cast<char*>(ws) + narrow_base_offset(batch, n));
   char* wsp = static_cast<char*>(ws) + narrow_bytes(batch, n);
   const PackLayout L = pack_layout(batch, n);
-  hipLaunchKernelGGL(probe_kernel<int64_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,
+  hipLaunchKernelGGL(probe_narrow_kernel, dim3((uint32_t)batch), dim3(1024), 0, stream,
                      static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g,
-                     (int)n, op_sub(OP), f32, g32, ok, reinterpret_cast<int32_t*>(wsp + L.off_ok),
+                     (int)n, op_sub(OP), f32, g32, ok, base, reinterpret_cast<int32_t*>(wsp + L.off_ok),
                      reinterpret_cast<int32_t*>(wsp + L.off_rho), dev_flags);
   // Several kernels see every row; the selector makes each row run in exactly one family.
   // The output is filled once with the identity, before all of them.
   launch_fill<int64_t, OP>(static_cast<int64_t*>(out), batch * n, stream);
   int rc;
   if (packed_worthwhile(batch, n)) {
-    rc = run_packed<int64_t, OP>(f32, n, g32, n, static_cast<int64_t*>(out),
-                                     static_cast<const int64_t*>(cap), ok, batch, n, wsp, L, stream);
+    rc = run_packed<int64_t, OP>(f32, n, g32, n, static_cast<int64_t*>(out), static_cast<const int64_t*>(cap),
+                                 ok, base, batch, n, wsp, L, stream);
   } else {
     rc = run_product<int32_t, int64_t, OP>(op_sub(OP) ? g32 : f32, n, op_sub(OP) ? f32 : g32, n,
-                                               static_cast<int64_t*>(out), static_cast<const int64_t*>(cap), ok,
-                                               1, batch, n, stream, true, true, nullptr);
+                                           static_cast<int64_t*>(out), static_cast<const int64_t*>(cap), ok, 1,
+                                           batch, n, stream, true, true, base);
   }
   if (rc != RTC_OK) return rc;
   const int64_t* a = static_cast<const int64_t*>(op_sub(OP) ? g : f);

@@ -178,6 +178,27 @@ def test_int64_wide_and_mixed_rows(rtc):
     check_products(rtc, f, g, "int64 near limit")
 
 
+def test_int64_offset_rows_are_rebased(rtc):
+    """int64 rows far from zero but of small range run in 32-bit arithmetic after re-basing."""
+    n = 2600
+    f = wl.random_monotone(10, 1, 5, n, np.int64, max_inc=30)
+    g = wl.random_monotone(10, 2, 5, n, np.int64, max_inc=30)
+    f[0] += 2**40
+    g[1] -= 2**45
+    f[2] += 2**61
+    g[2] -= 2**61
+    f[3] = -f[3] + 2**50          # falling row
+    g[4] += 2**30 - int(g[4].min()) - 5   # straddles the 2^30 boundary
+    check_products(rtc, f, g, "int64 offsets")
+    check_duals(rtc, f, g, "int64 offsets")
+    au, bu = f[:2] - f[:2].min(axis=1, keepdims=True), g[:2] - g[:2].min(axis=1, keepdims=True) + 2**41
+    bl = np.minimum(bu, bu - 7)
+    say("int64 offsets gpc")
+    ao, blo = rtc.rtc_gpc_step(dev(au), dev(bu), dev(bl))
+    want_a, want_b = oracle.gpc_step(au, bu, bl)
+    assert np.array_equal(host(ao), want_a) and np.array_equal(host(blo), want_b)
+
+
 def test_int32_near_limit(rtc):
     n = 1100
     top = np.iinfo(np.int32).max
