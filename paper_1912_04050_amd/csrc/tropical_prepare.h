@@ -1,0 +1,267 @@
+// Helper kernels of the tropical products: identity fill, range probes (overflow flag, int64
+// re-basing and narrowing, packed-path eligibility and slope), preparation of the packed path's
+// tables, and the per-row packability decision.  Included by tropical.hip only.
+#pragma once
+
+#include "tropical_common.h"
+
+namespace rtc {
+namespace {
+
+template <typename T>
+__global__ __launch_bounds__(256) void fill_kernel(T* __restrict__ dst, int64_t count, T value) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t step = (int64_t)gridDim.x * blockDim.x;
+  for (; i < count; i += step) dst[i] = value;
+}
+
+// Range probe of one row pair.  Finds min/max of both rows, raises the overflow flag when
+// the bounds do not prove that every candidate fits and (optionally) decides eligibility for
+// the packed path and the slope to remove.
+template <typename T>
+__global__ __launch_bounds__(1024) void probe_kernel(const T* __restrict__ f, int64_t stride_f,
+                                                     const T* __restrict__ g, int64_t stride_g, int n,
+                                                     bool deconv, int32_t* __restrict__ pack_ok,
+                                                     int32_t* __restrict__ rho,
+                                                     int32_t* __restrict__ dev_flags) {
+  __shared__ T red[4][16];
+  const int row = blockIdx.x;
+  const T* fr = f + (int64_t)row * stride_f;
+  const T* gr = g + (int64_t)row * stride_g;
+  T fmin = Lim<T>::hi(), fmax = Lim<T>::lo(), gmin = Lim<T>::hi(), gmax = Lim<T>::lo();
+  for (int i = threadIdx.x; i < n; i += blockDim.x) {
+    const T fv = fr[i], gv = gr[i];
+    fmin = sel_min(fmin, fv); fmax = sel_max(fmax, fv);
+    gmin = sel_min(gmin, gv); gmax = sel_max(gmax, gv);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    fmin = sel_min(fmin, __shfl_xor(fmin, off)); fmax = sel_max(fmax, __shfl_xor(fmax, off));
+    gmin = sel_min(gmin, __shfl_xor(gmin, off)); gmax = sel_max(gmax, __shfl_xor(gmax, off));
+  }
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) { red[0][wave] = fmin; red[1][wave] = fmax; red[2][wave] = gmin; red[3][wave] = gmax; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int nw = (blockDim.x + 63) >> 6;
+    for (int w = 1; w < nw; ++w) {
+      fmin = sel_min(fmin, red[0][w]); fmax = sel_max(fmax, red[1][w]);
+      gmin = sel_min(gmin, red[2][w]); gmax = sel_max(gmax, red[3][w]);
+    }
+    if constexpr (!std::numeric_limits<T>::is_integer) {
+      (void)dev_flags;
+    } else {
+      T dummy;
+      const bool bad = deconv ? (__builtin_sub_overflow(fmax, gmin, &dummy) || __builtin_sub_overflow(fmin, gmax, &dummy))
+                              : (__builtin_add_overflow(fmax, gmax, &dummy) || __builtin_add_overflow(fmin, gmin, &dummy));
+      if (bad && dev_flags) atomicOr(dev_flags, RTC_FLAG_OVERFLOW);
+      if (pack_ok) {
+        // |values| < 2^29 keeps the detrended rows inside int32 (rho*i <= g[n-1]-g[0] < 2^30)
+        const T lim = (T)1 << 29;
+        const bool ok = fmin >= -lim && fmax < lim && gmin >= -lim && gmax < lim;
+        pack_ok[row] = ok ? 1 : 0;
+        // slope of the window operand: g for the convolution, f for the deconvolution
+        const T w0 = deconv ? fr[0] : gr[0], w1 = deconv ? fr[n - 1] : gr[n - 1];
+        const T u0 = deconv ? gr[0] : fr[0], u1 = deconv ? gr[n - 1] : fr[n - 1];
+        int32_t r = 0;
+        if (ok && n > 1) {
+          r = w1 > w0 ? (int32_t)((w1 - w0) / (T)(n - 1)) : 0;
+          // performance heuristic: when the two average slopes differ so much that not even a
+          // sub-chunk of the uniform operand stays inside 16 bits after detrending, do not
+          // prepare the row
+          const int64_t ru = (int64_t)((u1 - u0) / (T)(n - 1));
+          const int64_t diff = ru > r ? ru - r : r - ru;
+          if (diff * kPkSub > 50000) pack_ok[row] = 0;
+        }
+        rho[row] = r;
+      }
+    }
+  }
+}
+
+// Range probe of one int64 row pair.  A row whose two value ranges (max - min) are below 2^30
+// is re-based to its minima and copied as int32: every candidate of the re-based rows fits
+// 32 bits, so the 32-bit kernels compute it exactly and add `out_base` (f_min + g_min, or
+// f_min - g_min for the deconvolutions) back on store.  Rows with a wider range keep the
+// 64-bit kernel.  Also: overflow flag, packed-path eligibility and slope, as in probe_kernel.
+__global__ __launch_bounds__(1024) void probe_narrow_kernel(const int64_t* __restrict__ f, int64_t stride_f,
+                                                            const int64_t* __restrict__ g, int64_t stride_g,
+                                                            int n, bool deconv, int32_t* __restrict__ f32,
+                                                            int32_t* __restrict__ g32,
+                                                            int32_t* __restrict__ narrow_ok,
+                                                            int64_t* __restrict__ out_base,
+                                                            int32_t* __restrict__ pack_ok,
+                                                            int32_t* __restrict__ rho,
+                                                            int32_t* __restrict__ dev_flags) {
+  __shared__ int64_t red[4][16];
+  __shared__ int64_t s_base[2];
+  __shared__ int s_narrow;
+  const int row = blockIdx.x;
+  const int64_t* fr = f + (int64_t)row * stride_f;
+  const int64_t* gr = g + (int64_t)row * stride_g;
+  int64_t fmin = INT64_MAX, fmax = INT64_MIN, gmin = INT64_MAX, gmax = INT64_MIN;
+  for (int i = threadIdx.x; i < n; i += blockDim.x) {
+    const int64_t fv = fr[i], gv = gr[i];
+    fmin = sel_min(fmin, fv); fmax = sel_max(fmax, fv);
+    gmin = sel_min(gmin, gv); gmax = sel_max(gmax, gv);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    fmin = sel_min(fmin, __shfl_xor(fmin, off)); fmax = sel_max(fmax, __shfl_xor(fmax, off));
+    gmin = sel_min(gmin, __shfl_xor(gmin, off)); gmax = sel_max(gmax, __shfl_xor(gmax, off));
+  }
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) { red[0][wave] = fmin; red[1][wave] = fmax; red[2][wave] = gmin; red[3][wave] = gmax; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int nw = (blockDim.x + 63) >> 6;
+    for (int w = 1; w < nw; ++w) {
+      fmin = sel_min(fmin, red[0][w]); fmax = sel_max(fmax, red[1][w]);
+      gmin = sel_min(gmin, red[2][w]); gmax = sel_max(gmax, red[3][w]);
+    }
+    int64_t dummy;
+    const bool bad = deconv ? (__builtin_sub_overflow(fmax, gmin, &dummy) || __builtin_sub_overflow(fmin, gmax, &dummy))
+                            : (__builtin_add_overflow(fmax, gmax, &dummy) || __builtin_add_overflow(fmin, gmin, &dummy));
+    if (bad && dev_flags) atomicOr(dev_flags, RTC_FLAG_OVERFLOW);
+    const uint64_t frange = (uint64_t)fmax - (uint64_t)fmin, grange = (uint64_t)gmax - (uint64_t)gmin;
+    const bool narrow = frange < (1ull << 30) && grange < (1ull << 30);
+    narrow_ok[row] = narrow ? 1 : 0;
+    out_base[row] = narrow ? (deconv ? wrap_sub(fmin, gmin) : wrap_add(fmin, gmin)) : 0;
+    s_base[0] = fmin; s_base[1] = gmin; s_narrow = narrow ? 1 : 0;
+    // re-based values lie in [0, 2^29): the detrended rows stay inside int32
+    const bool ok = frange < (1ull << 29) && grange < (1ull << 29);
+    pack_ok[row] = ok ? 1 : 0;
+    int32_t r = 0;
+    if (ok && n > 1) {
+      const int64_t w0 = deconv ? fr[0] : gr[0], w1 = deconv ? fr[n - 1] : gr[n - 1];
+      const int64_t u0 = deconv ? gr[0] : fr[0], u1 = deconv ? gr[n - 1] : fr[n - 1];
+      r = w1 > w0 ? (int32_t)((w1 - w0) / (n - 1)) : 0;
+      const int64_t ru = (u1 - u0) / (n - 1);
+      const int64_t diff = ru > r ? ru - r : r - ru;
+      if (diff * kPkSub > 50000) pack_ok[row] = 0;   // same heuristic as probe_kernel
+    }
+    rho[row] = r;
+  }
+  __syncthreads();
+  if (s_narrow) {
+    const int64_t fb = s_base[0], gb = s_base[1];
+    for (int i = threadIdx.x; i < n; i += blockDim.x) {
+      f32[(int64_t)row * n + i] = (int32_t)(fr[i] - fb);
+      g32[(int64_t)row * n + i] = (int32_t)(gr[i] - gb);
+    }
+  }
+}
+
+__device__ __forceinline__ int32_t wave_min(int32_t v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = min(v, __shfl_xor(v, off));
+  return v;
+}
+__device__ __forceinline__ int32_t wave_max(int32_t v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = max(v, __shfl_xor(v, off));
+  return v;
+}
+
+// Prepares the packed path for one (row, chunk of 1024 indices): detrends both operands
+// (a = uniform operand, b = window operand, stored in window-index order, i.e. reversed for the
+// deconvolution), re-bases the chunk of a to its minimum and packs it into both halves, and
+// records the chunk range of a and the minima / maxima of b per block of 256.
+__global__ __launch_bounds__(1024) void prep_kernel(const int32_t* __restrict__ a, int64_t stride_a,
+                                                    const int32_t* __restrict__ b, int64_t stride_b, int n,
+                                                    bool deconv, bool neg, int npad, int nchunk, int nblk,
+                                                    const int32_t* __restrict__ rho,
+                                                    const int32_t* __restrict__ pack_ok,
+                                                    uint32_t* __restrict__ apk, uint32_t* __restrict__ apk_s,
+                                                    int32_t* __restrict__ ab_s, int32_t* __restrict__ ar_s,
+                                                    int nsub, int32_t* __restrict__ bd, int32_t* __restrict__ ab,
+                                                    int32_t* __restrict__ ar, int32_t* __restrict__ bmn,
+                                                    int32_t* __restrict__ bmx) {
+  __shared__ int32_t s_amn[16], s_amx[16], s_bmn[16], s_bmx[16];
+  const int row = blockIdx.x / nchunk;
+  if (pack_ok[row] == 0) return;   // nothing of this row will be read
+  const int c = blockIdx.x % nchunk;
+  const int i = c * kPkChunk + threadIdx.x;
+  const int32_t r = rho[row];
+  const bool valid = i < n;
+  int32_t adv = valid ? wrap_sub(a[(int64_t)row * stride_a + i], r * i) : 0;
+  if (neg) adv = wrap_sub(0, adv);   // max-plus convolution / min-plus deconvolution: see packed_body
+  int32_t bdv = 0;
+  if (valid) bdv = deconv ? wrap_add(b[(int64_t)row * stride_b + (n - 1 - i)], r * i)
+                          : wrap_sub(b[(int64_t)row * stride_b + i], r * i);
+  const int32_t amn = wave_min(valid ? adv : INT32_MAX), amx = wave_max(valid ? adv : INT32_MIN);
+  const int32_t bmn_w = wave_min(valid ? bdv : INT32_MAX), bmx_w = wave_max(valid ? bdv : INT32_MIN);
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) { s_amn[wave] = amn; s_amx[wave] = amx; s_bmn[wave] = bmn_w; s_bmx[wave] = bmx_w; }
+  __syncthreads();
+  int32_t cmn = INT32_MAX, cmx = INT32_MIN;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) { cmn = min(cmn, s_amn[w]); cmx = max(cmx, s_amx[w]); }
+  apk[(int64_t)row * npad + i] = valid ? min((uint32_t)adv - (uint32_t)cmn, kPkPoison) * 0x10001u : 0xFFFFFFFFu;
+  // sub-chunk of 128 indices = 2 waves
+  const int sub = threadIdx.x / kPkSub;
+  const int32_t smn = min(s_amn[2 * sub], s_amn[2 * sub + 1]);
+  const int32_t smx = max(s_amx[2 * sub], s_amx[2 * sub + 1]);
+  apk_s[(int64_t)row * npad + i] = valid ? min((uint32_t)adv - (uint32_t)smn, kPkPoison) * 0x10001u : 0xFFFFFFFFu;
+  if ((threadIdx.x & (kPkSub - 1)) == 0) {
+    const bool any = smx >= smn;   // false when the sub-chunk lies entirely beyond n
+    const int64_t range = (int64_t)smx - (int64_t)smn;
+    ab_s[(int64_t)row * nsub + c * kPkSubs + sub] = any ? smn : 0;
+    ar_s[(int64_t)row * nsub + c * kPkSubs + sub] = any ? (int32_t)(range < 0x7fffffffLL ? range : 0x7fffffffLL) : 0;
+  }
+  if (valid) bd[(int64_t)row * n + i] = bdv;
+  if (threadIdx.x == 0) {
+    ab[(int64_t)row * nchunk + c] = cmn;
+    const int64_t range = (int64_t)cmx - (int64_t)cmn;
+    ar[(int64_t)row * nchunk + c] = (int32_t)(range < 0x7fffffffLL ? range : 0x7fffffffLL);
+  }
+  if ((threadIdx.x & (kPkBlock - 1)) == 0) {
+    const int j = c * (kPkChunk / kPkBlock) + threadIdx.x / kPkBlock;
+    if (j < nblk) {
+      int32_t mn = INT32_MAX, mx = INT32_MIN;
+#pragma unroll
+      for (int w = 0; w < kPkBlock / 64; ++w) { mn = min(mn, s_bmn[wave + w]); mx = max(mx, s_bmx[wave + w]); }
+      bmn[(int64_t)row * nblk + j] = mn;
+      bmx[(int64_t)row * nblk + j] = mx;
+    }
+  }
+}
+
+// Performance heuristic only (results are exact either way): samples up to 64 x 64
+// (tile, chunk) pairs of a row, weighted by the number of chunks they stand for, and switches the
+// packed path off for the row when less than half of its chunk-tiles would qualify -- a mostly
+// unpackable row is better left to the 32-bit kernel alone.
+__global__ __launch_bounds__(256) void decide_kernel(PackAux x, int n, int32_t* __restrict__ pack_ok) {
+  __shared__ float s_yes[4], s_all[4];
+  const int row = blockIdx.x;
+  const int n_t2 = (n + kPkW - 1) / kPkW;
+  float yes = 0.f, all = 0.f;
+  if (pack_ok[row] != 0) {
+    for (int j = threadIdx.x; j < 64 * 64; j += 256) {
+      const int it = j / 64, ic = j % 64;
+      const int nt = min(n_t2, 64);
+      if (it >= nt) continue;
+      const int T2 = (int)((int64_t)it * n_t2 / nt);
+      const int nc = (min((T2 + 1) * kPkW, n) + kPkChunk - 1) / kPkChunk;   // chunks of this tile
+      const int ns = min(nc, 64);
+      if (ic >= ns) continue;
+      const int c = (int)((int64_t)ic * nc / ns);
+      const float weight = (float)nc / (float)ns * ((float)n_t2 / (float)nt);
+      int32_t gb, br;
+      all += weight;
+      yes += weight * (float)__builtin_popcount(chunk_plan(x, row, T2, c, n, &gb, &br) & 0xFF) * (1.f / kPkSubs);
+    }
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) { yes += __shfl_xor(yes, off); all += __shfl_xor(all, off); }
+  if ((threadIdx.x & 63) == 0) { s_yes[threadIdx.x >> 6] = yes; s_all[threadIdx.x >> 6] = all; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    yes = s_yes[0] + s_yes[1] + s_yes[2] + s_yes[3];
+    all = s_all[0] + s_all[1] + s_all[2] + s_all[3];
+    if (2.f * yes < all) pack_ok[row] = 0;
+  }
+}
+
+}  // namespace
+}  // namespace rtc
