@@ -37,7 +37,10 @@ extern "C" {
 
 typedef enum { RTC_I32 = 0, RTC_I64 = 1, RTC_F64 = 2 } rtc_dtype;
 typedef enum { RTC_INV_LOWER = 0, RTC_INV_UPPER = 1 } rtc_inv_mode;
-typedef enum { RTC_OP_CONV = 0, RTC_OP_DECONV = 1, RTC_OP_GPC = 2, RTC_OP_MAXCONV = 3, RTC_OP_MINDECONV = 4 } rtc_op;
+typedef enum {
+  RTC_OP_CONV = 0, RTC_OP_DECONV = 1, RTC_OP_GPC = 2, RTC_OP_MAXCONV = 3, RTC_OP_MINDECONV = 4,
+  RTC_OP_CLOSURE = 5, RTC_OP_CHAIN = 6
+} rtc_op;
 
 typedef enum {
   RTC_OK = 0,
@@ -153,6 +156,30 @@ typedef struct rtc_gpc_args {
 } rtc_gpc_args;
 
 int rtc_gpc_step(const rtc_gpc_args* a, void* hip_stream);
+
+/* Sub-additive closure on the finite horizon, per row:
+ *   out = min(delta_0, f, f (x) f, f (x) f (x) f, ...),  delta_0[0] = 0 and +infinity elsewhere,
+ * i.e. out[0] = 0 and out[t] = the cheapest way to split t into positive parts priced by f.
+ * Needs f[0] >= 0 (a row with f[0] < 0 has no finite closure: RTC_FLAG_DOMAIN is raised and the
+ * row is treated as if f[0] were 0).  Computed by ceil(log2(n-1)) squarings g <- g (x) g starting
+ * from g = f with g[0] = 0.  rtc_superadditive_closure is the max-plus dual
+ * (max instead of min, rtc_maxplus_conv, needs f[0] <= 0).
+ * Integer dtypes only (RTC_ERR_DTYPE for RTC_F64): the k-fold sums of a closure have no unique
+ * floating-point value, because floating-point addition does not associate.
+ * f, out: dense [batch][n]; ws needs rtc_workspace_bytes(RTC_OP_CLOSURE, ...). */
+int rtc_subadditive_closure(const void* f, void* out, int64_t batch, int64_t n, rtc_dtype dt, void* ws,
+                            size_t ws_bytes, int32_t* dev_flags, void* hip_stream);
+int rtc_superadditive_closure(const void* f, void* out, int64_t batch, int64_t n, rtc_dtype dt, void* ws,
+                              size_t ws_bytes, int32_t* dev_flags, void* hip_stream);
+
+/* Concatenation of `count` curves per row (e.g. the service curves along a path, whose min-plus
+ * convolution is the service the path offers end to end):
+ *   out = curves[0] (x) curves[1] (x) ... (x) curves[count-1]
+ * evaluated left to right (for RTC_F64 this fixes the rounding of every sum).
+ * curves: dense [count][batch][n]; out: [batch][n]; 1 <= count <= 65536;
+ * ws needs rtc_workspace_bytes(RTC_OP_CHAIN, ...). */
+int rtc_conv_chain(const void* curves, int64_t count, void* out, int64_t batch, int64_t n, rtc_dtype dt,
+                   void* ws, size_t ws_bytes, int32_t* dev_flags, void* hip_stream);
 
 /* Delay bound: maximal horizontal deviation per row,
  *   out[b] = max_D max(0, min{k : beta[b][k] >= alpha[b][D]} - D);

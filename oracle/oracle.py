@@ -155,6 +155,30 @@ def gpc_step_lower(alpha_l, beta_u, beta_l):
     return ao, uo
 
 
+def closure(f, super_additive: bool = False):
+    """Sub-additive (default) or super-additive closure per row; returns (closure, flags)."""
+    f = _rows(f)
+    out = np.empty_like(f)
+    scratch = np.empty(3 * f.shape[1], f.dtype)
+    flags = np.zeros(1, np.int32)
+    rc = lib().oracle_closure(_p(f), _p(out), _p(scratch), ctypes.c_int64(f.shape[0]), ctypes.c_int64(f.shape[1]),
+                              ctypes.c_int(1 if super_additive else 0), ctypes.c_int(_DT[f.dtype]), _p(flags))
+    assert rc == 0, rc
+    return out, int(flags[0])
+
+
+def conv_chain(curves):
+    """curves: [count][batch][n]; their min-plus convolution per row."""
+    c = np.ascontiguousarray(curves)
+    assert c.ndim == 3
+    out = np.empty(c.shape[1:], c.dtype)
+    scratch = np.empty(c.shape[2], c.dtype)
+    rc = lib().oracle_conv_chain(_p(c), ctypes.c_int64(c.shape[0]), _p(out), _p(scratch), ctypes.c_int64(c.shape[1]),
+                                 ctypes.c_int64(c.shape[2]), ctypes.c_int(_DT[c.dtype]))
+    assert rc == 0, rc
+    return out
+
+
 def max_hdev(alpha, beta):
     a = _rows(alpha)
     b = _rows(beta)

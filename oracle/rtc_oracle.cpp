@@ -24,6 +24,9 @@
 //                            beta'^l[D] = max(0, max_{l<=D} beta^l[l] - alpha^u[l])
 //                            alpha'^l = min((alpha^l (/) beta^u) (x) beta^l, beta^l)
 //                            beta'^u[D] = max(0, min_{l>=D} beta^u[l] - alpha^l[l])
+//   sub-additive closure     min(delta_0, f, f (x) f, f (x) f (x) f, ...), f[0] read as 0
+//   super-additive closure   the same with max and the max-plus convolution
+//   chain                    curves[0] (x) curves[1] (x) ... (x) curves[count-1]
 //   horizontal deviation     max_D max(0, lower-inverse_beta(alpha[D]) - D)
 //   vertical deviation       max_D alpha[D] - beta[D]
 //
@@ -203,6 +206,41 @@ void gpc_lower_rows(const T* al, const T* bu, const T* bl, T* al_out, T* bu_out,
   }
 }
 
+// Closure by its definition: every k-fold convolution power of f (with f[0] read as 0, the value
+// delta_0 contributes), k = 1 .. max(1, n-1); longer products only add zero-length parts.
+template <typename T>
+void closure_rows(const T* f, T* out, T* h, T* h2, T* f0, int64_t batch, int64_t n, bool super, int32_t* flags) {
+  int32_t fl = 0;
+  for (int64_t b = 0; b < batch; ++b) {
+    const T* fr = f + b * n;
+    T* o = out + b * n;
+    if (super ? fr[0] > (T)0 : fr[0] < (T)0) fl |= 2;
+    for (int64_t t = 0; t < n; ++t) f0[t] = fr[t];
+    f0[0] = (T)0;
+    for (int64_t t = 0; t < n; ++t) { h[t] = f0[t]; o[t] = f0[t]; }
+    for (int64_t k = 2; k <= n - 1; ++k) {
+      if (super) maxconv_one(h, f0, h2, n); else conv_one(h, f0, h2, n);
+      for (int64_t t = 0; t < n; ++t) {
+        h[t] = h2[t];
+        if (super ? h[t] > o[t] : h[t] < o[t]) o[t] = h[t];
+      }
+    }
+  }
+  if (flags) *flags |= fl;
+}
+
+template <typename T>
+void chain_rows(const T* curves, int64_t count, T* out, T* tmp, int64_t batch, int64_t n) {
+  for (int64_t b = 0; b < batch; ++b) {
+    T* o = out + b * n;
+    for (int64_t t = 0; t < n; ++t) o[t] = curves[b * n + t];
+    for (int64_t k = 1; k < count; ++k) {
+      conv_one(o, curves + (k * batch + b) * n, tmp, n);
+      for (int64_t t = 0; t < n; ++t) o[t] = tmp[t];
+    }
+  }
+}
+
 template <typename T>
 void hdev_rows(const T* alpha, const T* beta, int32_t* out, int64_t batch, int64_t n, int32_t* flags) {
   int32_t fl = 0;
@@ -351,6 +389,27 @@ int oracle_gpc_step_lower(const void* alpha_l, const void* beta_u, const void* b
                                    (int64_t*)alpha_l_out, (int64_t*)beta_u_out, (int64_t*)tmp, batch, n);
   else if (dt == 2) gpc_lower_rows((const double*)alpha_l, (const double*)beta_u, (const double*)beta_l,
                                    (double*)alpha_l_out, (double*)beta_u_out, (double*)tmp, batch, n);
+  else return -3;
+  return 0;
+}
+
+// scratch: 3*n elements of the value type
+int oracle_closure(const void* f, void* out, void* scratch, int64_t batch, int64_t n, int super, int dt,
+                   int32_t* flags) {
+  if (dt == 0) { int32_t* s = (int32_t*)scratch; closure_rows((const int32_t*)f, (int32_t*)out, s, s + n, s + 2 * n, batch, n, super != 0, flags); }
+  else if (dt == 1) { int64_t* s = (int64_t*)scratch; closure_rows((const int64_t*)f, (int64_t*)out, s, s + n, s + 2 * n, batch, n, super != 0, flags); }
+  else if (dt == 2) { double* s = (double*)scratch; closure_rows((const double*)f, (double*)out, s, s + n, s + 2 * n, batch, n, super != 0, flags); }
+  else return -3;
+  return 0;
+}
+
+// curves: [count][batch][n]; scratch: n elements
+int oracle_conv_chain(const void* curves, int64_t count, void* out, void* scratch, int64_t batch, int64_t n,
+                      int dt) {
+  if (count < 1) return -2;
+  if (dt == 0) chain_rows((const int32_t*)curves, count, (int32_t*)out, (int32_t*)scratch, batch, n);
+  else if (dt == 1) chain_rows((const int64_t*)curves, count, (int64_t*)out, (int64_t*)scratch, batch, n);
+  else if (dt == 2) chain_rows((const double*)curves, count, (double*)out, (double*)scratch, batch, n);
   else return -3;
   return 0;
 }

@@ -243,6 +243,31 @@ __global__ __launch_bounds__(256) void vdev_kernel(const T* __restrict__ alpha,
   if (threadIdx.x == 0) atomic_max_any(&out[row], vmax(vmax(red[0], red[1]), vmax(red[2], red[3])));
 }
 
+// Start of a closure iteration: out = f with out[0] forced to 0 (the value the unit element
+// delta_0 contributes).  A row whose f[0] has the wrong sign (below 0 for the sub-additive,
+// above 0 for the super-additive closure) has no finite closure: flag it.
+template <typename T>
+__global__ __launch_bounds__(256) void closure_init_kernel(const T* __restrict__ f, T* __restrict__ out, int n,
+                                                           int blocks_per_row, bool super,
+                                                           int32_t* __restrict__ dev_flags) {
+  const int row = blockIdx.x / blocks_per_row;
+  const int i = (blockIdx.x % blocks_per_row) * 256 + threadIdx.x;
+  if (i >= n) return;
+  T v = f[(int64_t)row * n + i];
+  if (i == 0) {
+    if (dev_flags != nullptr && (super ? v > (T)0 : v < (T)0)) atomicOr(dev_flags, RTC_FLAG_DOMAIN);
+    v = (T)0;
+  }
+  out[(int64_t)row * n + i] = v;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void copy_kernel(const T* __restrict__ src, T* __restrict__ dst, int64_t count) {
+  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t step = (int64_t)gridDim.x * 256;
+  for (; i < count; i += step) dst[i] = src[i];
+}
+
 template <typename T>
 int pinv_typed(const void* f, int64_t n, const void* x, int64_t m, int32_t* out, int64_t batch, int mode,
                hipStream_t stream) {
@@ -293,6 +318,27 @@ int launch_residual_service(const void* beta, const void* alpha, void* out, int6
     else
       hipLaunchKernelGGL((residual_service_kernel<T, false>), dim3((uint32_t)batch), dim3(1024), 0, stream,
                          static_cast<const T*>(beta), static_cast<const T*>(alpha), static_cast<T*>(out), (int)n);
+    return hip_ok();
+  });
+}
+
+int launch_closure_init(const void* f, void* out, int64_t batch, int64_t n, int dt, bool super,
+                        int32_t* dev_flags, hipStream_t stream) {
+  const int64_t bpr = (n + 255) / 256;
+  if (bpr * batch > 0x7fffffffLL) return RTC_ERR_SHAPE;
+  RTC_DISPATCH(dt, {
+    hipLaunchKernelGGL(closure_init_kernel<T>, dim3((uint32_t)(bpr * batch)), dim3(256), 0, stream,
+                       static_cast<const T*>(f), static_cast<T*>(out), (int)n, (int)bpr, super, dev_flags);
+    return hip_ok();
+  });
+}
+
+int launch_copy(const void* src, void* dst, int64_t count, int dt, hipStream_t stream) {
+  const int64_t want = (count + 2047) / 2048;
+  const int blocks = (int)(want < 65535 ? want : 65535);
+  RTC_DISPATCH(dt, {
+    hipLaunchKernelGGL(copy_kernel<T>, dim3(blocks), dim3(256), 0, stream, static_cast<const T*>(src),
+                       static_cast<T*>(dst), count);
     return hip_ok();
   });
 }

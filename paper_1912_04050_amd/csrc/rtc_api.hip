@@ -165,6 +165,78 @@ int rtc_gpc_step(const rtc_gpc_args* a, void* hip_stream) {
   return RTC_OK;
 }
 
+namespace {
+
+// Layout of the closure / chain workspace: two ping-pong curves, then the product workspace.
+size_t pingpong_bytes(int64_t batch, int64_t n, size_t es) { return 2 * (((size_t)batch * n * es + 255) / 256 * 256); }
+
+int closure(const void* f, void* out, int64_t batch, int64_t n, int dt, void* ws, size_t ws_bytes,
+            int32_t* dev_flags, hipStream_t stream, bool super) {
+  if (f == nullptr || out == nullptr) return RTC_ERR_NULL;
+  const size_t es = elem_size(dt);
+  // integer curves only: a k-fold sum has no unique floating-point value (addition does not associate)
+  if (es == 0 || dt == RTC_F64) return RTC_ERR_DTYPE;
+  if (int rc = check_shape(batch, n)) return rc;
+  if (!aligned(f, es) || !aligned(out, es) || !aligned(dev_flags, 4) || !aligned(ws, 16)) return RTC_ERR_ALIGN;
+  if (ws == nullptr || ws_bytes < rtc_workspace_bytes(RTC_OP_CLOSURE, batch, n, (rtc_dtype)dt)) return RTC_ERR_WORKSPACE;
+  int squarings = 0;   // after j squarings every k-fold term with k <= 2^j is covered; k <= n-1 suffices
+  while (((int64_t)1 << squarings) < n - 1) ++squarings;
+  const size_t half = pingpong_bytes(batch, n, es) / 2;
+  char* buf[2] = {static_cast<char*>(ws), static_cast<char*>(ws) + half};
+  void* sub_ws = static_cast<char*>(ws) + 2 * half;
+  const size_t sub_bytes = ws_bytes - 2 * half;
+  int rc = launch_closure_init(f, squarings == 0 ? out : buf[0], batch, n, dt, super, dev_flags, stream);
+  if (rc != RTC_OK) return rc;
+  for (int j = 0; j < squarings; ++j) {
+    const void* src = buf[j & 1];
+    void* dst = (j == squarings - 1) ? out : buf[(j + 1) & 1];
+    rc = launch_tropical(super ? RTC_OP_MAXCONV : RTC_OP_CONV, src, src, dst, batch, n, n, n, dt, nullptr, sub_ws,
+                         sub_bytes, dev_flags, stream);
+    if (rc != RTC_OK) return rc;
+  }
+  return RTC_OK;
+}
+
+}  // namespace
+
+int rtc_subadditive_closure(const void* f, void* out, int64_t batch, int64_t n, rtc_dtype dt, void* ws,
+                            size_t ws_bytes, int32_t* dev_flags, void* hip_stream) {
+  return closure(f, out, batch, n, dt, ws, ws_bytes, dev_flags, static_cast<hipStream_t>(hip_stream), false);
+}
+
+int rtc_superadditive_closure(const void* f, void* out, int64_t batch, int64_t n, rtc_dtype dt, void* ws,
+                              size_t ws_bytes, int32_t* dev_flags, void* hip_stream) {
+  return closure(f, out, batch, n, dt, ws, ws_bytes, dev_flags, static_cast<hipStream_t>(hip_stream), true);
+}
+
+int rtc_conv_chain(const void* curves, int64_t count, void* out, int64_t batch, int64_t n, rtc_dtype dt,
+                   void* ws, size_t ws_bytes, int32_t* dev_flags, void* hip_stream) {
+  if (curves == nullptr || out == nullptr) return RTC_ERR_NULL;
+  const size_t es = elem_size(dt);
+  if (es == 0) return RTC_ERR_DTYPE;
+  if (int rc = check_shape(batch, n)) return rc;
+  if (count < 1 || count > 65536) return RTC_ERR_SHAPE;
+  if (!aligned(curves, es) || !aligned(out, es) || !aligned(dev_flags, 4) || !aligned(ws, 16)) return RTC_ERR_ALIGN;
+  if (ws == nullptr || ws_bytes < rtc_workspace_bytes(RTC_OP_CHAIN, batch, n, dt)) return RTC_ERR_WORKSPACE;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const size_t curve_bytes = (size_t)batch * n * es;
+  const char* base = static_cast<const char*>(curves);
+  if (count == 1) return launch_copy(base, out, batch * n, dt, stream);
+  const size_t half = pingpong_bytes(batch, n, es) / 2;
+  char* buf[2] = {static_cast<char*>(ws), static_cast<char*>(ws) + half};
+  void* sub_ws = static_cast<char*>(ws) + 2 * half;
+  const size_t sub_bytes = ws_bytes - 2 * half;
+  const void* acc = base;
+  for (int64_t k = 1; k < count; ++k) {
+    void* dst = (k == count - 1) ? out : buf[k & 1];
+    int rc = launch_tropical(RTC_OP_CONV, acc, base + k * curve_bytes, dst, batch, n, n, n, dt, nullptr, sub_ws,
+                             sub_bytes, dev_flags, stream);
+    if (rc != RTC_OK) return rc;
+    acc = dst;
+  }
+  return RTC_OK;
+}
+
 int rtc_max_hdev(const void* alpha, const void* beta, int32_t* out, int64_t batch, int64_t n,
                  rtc_dtype dt, int32_t* dev_flags, void* hip_stream) {
   if (alpha == nullptr || beta == nullptr || out == nullptr) return RTC_ERR_NULL;
@@ -198,6 +270,9 @@ size_t rtc_workspace_bytes(int op, int64_t batch, int64_t n, rtc_dtype dt) {
       return prod;
     case RTC_OP_GPC:
       return ((size_t)batch * n * es + 255) / 256 * 256 + prod;
+    case RTC_OP_CLOSURE:
+    case RTC_OP_CHAIN:
+      return 2 * (((size_t)batch * n * es + 255) / 256 * 256) + prod;
     default:
       return 0;
   }

@@ -30,6 +30,9 @@ int launch_compose(const void* outer, int64_t n_outer, const int32_t* inner, int
                    int64_t batch, int dt, int32_t* dev_flags, hipStream_t stream);
 int launch_residual_service(const void* beta, const void* alpha, void* out, int64_t batch,
                             int64_t n, int dt, bool suffix_min, hipStream_t stream);
+int launch_closure_init(const void* f, void* out, int64_t batch, int64_t n, int dt, bool super,
+                        int32_t* dev_flags, hipStream_t stream);
+int launch_copy(const void* src, void* dst, int64_t count, int dt, hipStream_t stream);
 int launch_max_hdev(const void* alpha, const void* beta, int32_t* out, int64_t batch, int64_t n,
                     int dt, int32_t* dev_flags, hipStream_t stream);
 int launch_max_vdev(const void* alpha, const void* beta, void* out, int64_t batch, int64_t n, int dt,

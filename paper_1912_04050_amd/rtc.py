@@ -25,6 +25,7 @@ _lib = ctypes.CDLL(LIB_PATH)
 RTC_I32, RTC_I64, RTC_F64 = 0, 1, 2
 RTC_INV_LOWER, RTC_INV_UPPER = 0, 1
 RTC_OP_CONV, RTC_OP_DECONV, RTC_OP_GPC, RTC_OP_MAXCONV, RTC_OP_MINDECONV = 0, 1, 2, 3, 4
+RTC_OP_CLOSURE, RTC_OP_CHAIN = 5, 6
 RTC_FLAG_OVERFLOW, RTC_FLAG_DOMAIN, RTC_FLAG_UNBOUNDED = 1, 2, 4
 
 _DT = {torch.int32: RTC_I32, torch.int64: RTC_I64, torch.float64: RTC_F64}
@@ -261,6 +262,46 @@ def rtc_gpc_step(alpha_u, beta_u, beta_l, alpha_u_out=None, beta_l_out=None, gam
     if alpha_l is not None:
         return alpha_u_out, beta_l_out, alpha_l_out, beta_u_out
     return alpha_u_out, beta_l_out
+
+
+_closure_sig = [_vp, _vp, _i64, _i64, _int, _vp, _sz, _vp, _vp]
+_lib.rtc_subadditive_closure.argtypes = _closure_sig
+_lib.rtc_superadditive_closure.argtypes = _closure_sig
+_lib.rtc_conv_chain.argtypes = [_vp, _i64, _vp, _i64, _i64, _int, _vp, _sz, _vp, _vp]
+for _name in ("rtc_subadditive_closure", "rtc_superadditive_closure", "rtc_conv_chain"):
+    getattr(_lib, _name).restype = _int
+
+
+def _closure(fn, f, out, ws, dev_flags):
+    f, batch, n = _dense(f)
+    if out is None:
+        out = torch.empty_like(f)
+    ws, ws_bytes = _workspace(RTC_OP_CLOSURE, batch, n, f.dtype, f.device, ws)
+    _check(fn(_ptr(f), _ptr(out), batch, n, _DT[f.dtype], _ptr(ws), ws_bytes, _ptr(dev_flags), _stream()))
+    return out
+
+
+def rtc_subadditive_closure(f, out=None, ws=None, dev_flags=None):
+    """min(delta_0, f, f (x) f, ...) per row."""
+    return _closure(_lib.rtc_subadditive_closure, f, out, ws, dev_flags)
+
+
+def rtc_superadditive_closure(f, out=None, ws=None, dev_flags=None):
+    """max(delta_0, f, f max-plus-convolved with itself, ...) per row."""
+    return _closure(_lib.rtc_superadditive_closure, f, out, ws, dev_flags)
+
+
+def rtc_conv_chain(curves, out=None, ws=None, dev_flags=None):
+    """curves: dense [count][batch][n]; returns their min-plus convolution per row, [batch][n]."""
+    if not curves.is_cuda or curves.dim() != 3 or not curves.is_contiguous():
+        raise ValueError("curves must be a dense [count][batch][n] device tensor")
+    count, batch, n = curves.shape
+    if out is None:
+        out = torch.empty((batch, n), dtype=curves.dtype, device=curves.device)
+    ws, ws_bytes = _workspace(RTC_OP_CHAIN, batch, n, curves.dtype, curves.device, ws)
+    _check(_lib.rtc_conv_chain(_ptr(curves), count, _ptr(out), batch, n, _DT[curves.dtype], _ptr(ws), ws_bytes,
+                               _ptr(dev_flags), _stream()))
+    return out
 
 
 def rtc_max_hdev(alpha, beta, out=None, dev_flags=None):

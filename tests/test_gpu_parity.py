@@ -387,3 +387,45 @@ def test_many_tiny_rows(rtc):
         g = wl.random_monotone(34, n + 1, 6000, n, np.int32)
         check_products(rtc, f, g, f"many tiny rows n={n}")
         check_duals(rtc, f, g, f"many tiny rows n={n}")
+
+
+# ---------------------------------------------------------------------------
+# closures and concatenation
+# ---------------------------------------------------------------------------
+
+def test_closure_rejects_floating_point(rtc):
+    f = torch.zeros((1, 8), dtype=torch.float64, device="cuda")
+    with pytest.raises(rtc.RtcError) as e:
+        rtc.rtc_subadditive_closure(f)
+    assert e.value.status == -3
+
+
+@pytest.mark.parametrize("dtype", [np.int32, np.int64])
+def test_closures(rtc, dtype):
+    rng = np.random.default_rng(41)
+    for n in (1, 2, 3, 17, 130, 1500):
+        f = np.abs(wl.random_monotone(41, n, 3, n, dtype, max_inc=9))
+        f[1] = rng.permutation(f[1])                       # not monotone
+        f[2, 0] = -3                                       # wrong sign at 0: flagged, read as 0
+        flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+        say("closure", dtype, n)
+        got = host(rtc.rtc_subadditive_closure(dev(f), dev_flags=flags))
+        want, fl = oracle.closure(f)
+        assert np.array_equal(got, want) and int(host(flags)[0]) == fl == rtc.RTC_FLAG_DOMAIN
+        flags.zero_()
+        got = host(rtc.rtc_superadditive_closure(dev(-f), dev_flags=flags))
+        want, fl = oracle.closure(-f, super_additive=True)
+        assert np.array_equal(got, want) and int(host(flags)[0]) == fl
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_conv_chain(rtc, dtype):
+    for count, n in ((1, 40), (2, 700), (5, 1300)):
+        curves = np.stack([wl.random_monotone(42, 10 * count + k, 3, n, dtype, max_inc=4 + k) for k in range(count)])
+        say("chain", dtype, count, n)
+        got = host(rtc.rtc_conv_chain(dev(curves)))
+        assert np.array_equal(got, oracle.conv_chain(curves))
+    n = 2000
+    params = [(5, 10), (3, 25), (4, 0), (7, 40)]
+    curves = np.stack([wl.rate_latency(n, R, T, dtype)[None, :] for R, T in params])
+    assert np.array_equal(host(rtc.rtc_conv_chain(dev(curves)))[0], wl.rate_latency(n, 3, 75, dtype))

@@ -481,3 +481,82 @@ def test_gpc_lower_from_parts_brute_force_and_invariants():
         au = al + _curve(rng, n, np.int64, hi=3)
         _, lo = oracle.gpc_step(au, bu, bl)
         assert np.all(uo[0] >= np.minimum(lo[0], uo[0]))
+
+
+# ---------------------------------------------------------------------------
+# closures and concatenation
+# ---------------------------------------------------------------------------
+
+def dp_closure(f):
+    """Textbook recursion of the sub-additive closure, independent of k-fold convolutions:
+    c[0] = 0, c[t] = min(f[t], min_{0<s<t} c[s] + c[t-s])."""
+    n = len(f)
+    c = [0] * n
+    for t in range(1, n):
+        c[t] = min([f[t]] + [c[s] + c[t - s] for s in range(1, t)])
+    return c
+
+
+@pytest.mark.parametrize("dtype", [np.int32, np.int64])
+def test_closure_against_recursion_and_invariants(dtype):
+    rng = np.random.default_rng(91)
+    for n in (1, 2, 3, 10, 37, 64):
+        f = rng.integers(0, 60, n).astype(dtype)
+        got, fl = oracle.closure(f)
+        assert fl == 0 and got[0].tolist() == dp_closure(f.tolist()), n
+        c = got[0]
+        assert np.all(c[1:] <= f[1:]) and c[0] == 0
+        for s in range(n):                       # sub-additivity on the horizon
+            assert np.all(c[s:] <= c[s] + c[: n - s])
+        again, _ = oracle.closure(c)
+        assert np.array_equal(again[0], c)       # idempotent
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_closure_closed_forms(dtype):
+    n = 120
+    t = np.arange(n)
+    concave = np.floor(40 * np.sqrt(t)).astype(dtype)         # concave through 0: already sub-additive
+    assert np.array_equal(oracle.closure(concave)[0][0], concave)
+    bucket = (9 + 2 * t).astype(dtype)                         # token bucket: sub-additive for t >= 1
+    want = bucket.copy()
+    want[0] = 0
+    assert np.array_equal(oracle.closure(bucket)[0][0], want)
+    convex = (t * t + 3 * t).astype(dtype)                     # convex through 0: t unit steps are cheapest
+    assert np.array_equal(oracle.closure(convex)[0][0], (t * convex[1]).astype(dtype))
+    latency = wl.rate_latency(n, 5, 7, dtype)                  # zero up to 7: every t splits into free parts
+    assert np.all(oracle.closure(latency)[0][0] == 0)
+    neg = bucket.copy()
+    neg[0] = -1
+    out, fl = oracle.closure(neg)
+    assert fl == 2 and np.array_equal(out[0], want)            # flagged, computed as if f[0] were 0
+
+
+def test_superadditive_closure_is_negated_dual():
+    rng = np.random.default_rng(92)
+    f = -rng.integers(0, 60, 50).astype(np.int64)
+    sup, fl = oracle.closure(f, super_additive=True)
+    sub, _ = oracle.closure(-f)
+    assert fl == 0 and np.array_equal(sup[0], -sub[0])
+    pos = f.copy()
+    pos[0] = 3
+    assert oracle.closure(pos, super_additive=True)[1] == 2
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_chain_of_rate_latency_curves(dtype):
+    """beta_{R1,T1} (x) beta_{R2,T2} (x) ... = beta_{min R, sum T}."""
+    n = 300
+    params = [(5, 10), (3, 25), (4, 0), (7, 40)]
+    curves = np.stack([wl.rate_latency(n, R, T, dtype)[None, :] for R, T in params])
+    got = oracle.conv_chain(curves)
+    assert np.array_equal(got[0], wl.rate_latency(n, 3, 75, dtype))
+    assert np.array_equal(oracle.conv_chain(curves[:1])[0], curves[0, 0])
+    # the order does not matter, and it equals the pairwise products
+    assert np.array_equal(oracle.conv_chain(curves[::-1].copy()), got)
+    step = oracle.minplus_conv(oracle.minplus_conv(curves[0], curves[1]), oracle.minplus_conv(curves[2], curves[3]))
+    assert np.array_equal(step, got)
+    # pay bursts only once: the end-to-end delay bound is at most the sum of the per-node bounds
+    alpha = wl.token_bucket(n, 12, 2, dtype)
+    total = sum(int(oracle.max_hdev(alpha, c[0])[0][0]) for c in curves)
+    assert int(oracle.max_hdev(alpha, got[0])[0][0]) <= total
