@@ -199,3 +199,30 @@ def test_config5_reduced(rtc, seed):
 def test_config5_full(rtc):
     say("config5 full: fp64, N=262144")
     run_config5(rtc, wl.DEFAULT_SEED, 262144)
+
+
+def test_maximum_curve_length(rtc):
+    """n = RTC_MAX_N = 2^24 samples: the HBM-bound operators in full, the products on sampled
+    outputs (one product is 1.4e14 pair-ops: a few seconds on the GPU, out of reach for the
+    oracle except output by output)."""
+    n = 1 << 24
+    rng = np.random.default_rng(5)
+    f = np.cumsum(rng.integers(0, 4, n, dtype=np.int32), dtype=np.int64).astype(np.int32)[None, :]
+    g = np.cumsum(rng.integers(0, 6, n, dtype=np.int32), dtype=np.int64).astype(np.int32)[None, :]
+    fd, gd = dev(f), dev(g)
+    say("max n: vdev, compose, pinv")
+    assert np.array_equal(host(rtc.rtc_max_vdev(fd, gd)), oracle.max_vdev(f, g))
+    inner = rng.integers(0, n, (1, 100000)).astype(np.int32)
+    assert np.array_equal(host(rtc.rtc_compose(fd, dev(inner))), oracle.compose(f, inner)[0])
+    x = rng.integers(-1, int(f[0, -1]) + 2, (1, 3000)).astype(np.int32)
+    for mode in (0, 1):
+        assert np.array_equal(host(rtc.rtc_pseudo_inverse(fd, dev(x), mode)), oracle.pseudo_inverse(f, x, mode))
+    idx = np.unique(np.concatenate([[0, 1, 2047, 2048, n // 2, n - 2049, n - 2, n - 1], rng.integers(0, n, 40)]))
+    say("max n: convolution")
+    got = host(rtc.rtc_minplus_conv(fd, gd))
+    assert np.array_equal(got[0, idx], oracle.product_at(f[0], g[0], idx, False))
+    assert np.all(np.diff(got[0]) >= 0) and got[0, 0] == f[0, 0] + g[0, 0]
+    say("max n: deconvolution")
+    got = host(rtc.rtc_maxplus_deconv(gd, fd))
+    assert np.array_equal(got[0, idx], oracle.product_at(g[0], f[0], idx, True))
+    assert got[0, -1] == g[0, -1] - f[0, 0]
