@@ -112,13 +112,32 @@ struct PackAux {
   int32_t npad, nchunk, nsub, nblk;
 };
 
-constexpr int kPlanWhole = 0x100;   // chunk_plan: the whole chunk packs with the chunk-level re-basing
+constexpr int kPlanWhole = 0x100;    // chunk_plan: the whole chunk packs with the chunk-level re-basing
+constexpr int kPlanNarrow = 0x200;   // chunk_plan: the granted runs also fit the 15-bit flavour
+
+// Two arithmetic flavours of the packed path.
+//   wide:   unsigned 16-bit values, saturating add / subtract, packed integer min / max;
+//           window range + run range of the uniform operand <= kPkWideBudget.
+//   narrow: values stay below 0x7C00, where the bit pattern of a non-negative half float orders
+//           like the integer it encodes, so that the three-operand packed half-float minimum /
+//           maximum of gfx950 reduces two candidates per instruction exactly.  No saturation is
+//           available there: the poison values must survive a plain add / subtract, which costs
+//           the run range twice: window range + 2 * run range <= kPkNarrowBudget.
+constexpr int32_t kPkWideBudget = 65534;
+constexpr int32_t kPkNarrowTop = 0x7BFF;            // largest finite half-float pattern
+constexpr int32_t kPkNarrowBudget = kPkNarrowTop - 1;
+
+// Largest run range of the uniform operand that the narrow flavour accepts next to a window of
+// range br; the narrow poison values are placed relative to it (see packed_body).
+__device__ __forceinline__ int32_t narrow_umax(int32_t br) { return (kPkNarrowBudget - br) / 2; }
 
 // Which part of chunk c of the 2048-wide tile T2 of this row do the packed items own?
-// Returns kPlanWhole | 0xFF when the whole chunk qualifies with the chunk-level base, else a
-// byte with one bit per sub-chunk that qualifies with its own base (0: nothing).  Evaluated
-// identically (wave-uniform) by packed and 32-bit items.  *gb receives the window base, *br the
-// window range.
+// Returns a byte with one bit per sub-chunk of the chunk that packed items process (0: nothing),
+// kPlanWhole when the whole chunk runs on the chunk-level base (else every granted sub-chunk on
+// its own base), kPlanNarrow when the narrow flavour applies.  Evaluated identically
+// (wave-uniform) by packed and 32-bit items.  *gb receives the window base, *br the window range.
+// The choice between a larger wide grant and a smaller narrow one weighs the measured cost of a
+// sub-chunk in the narrow, wide and 32-bit kernels (about 10 : 13 : 24).
 __device__ __forceinline__ int chunk_plan(const PackAux& x, int row, int T2, int c, int n, int32_t* gb,
                                           int32_t* br) {
   if (x.pack_ok[row] == 0) return 0;
@@ -137,15 +156,22 @@ __device__ __forceinline__ int chunk_plan(const PackAux& x, int row, int T2, int
   }
   *gb = mn;
   const int64_t wr = (int64_t)mx - (int64_t)mn;
-  if (wr > 65534) return 0;
+  if (wr > kPkWideBudget) return 0;
   *br = (int32_t)wr;
-  if ((int64_t)x.ar[(int64_t)row * x.nchunk + c] + wr <= 65534) return kPlanWhole | 0xFF;
+  const int64_t cr = x.ar[(int64_t)row * x.nchunk + c];
+  if (wr + 2 * cr <= kPkNarrowBudget) return kPlanNarrow | kPlanWhole | 0xFF;
+  const bool wide_whole = wr + cr <= kPkWideBudget;
   const int32_t* ars = x.ar_s + (int64_t)row * x.nsub + c * kPkSubs;
-  int plan = 0;
+  int narrow = 0, wide = 0;
 #pragma unroll
-  for (int j = 0; j < kPkSubs; ++j)
-    if ((int64_t)ars[j] + wr <= 65534) plan |= 1 << j;
-  return plan;
+  for (int j = 0; j < kPkSubs; ++j) {
+    const int64_t r = ars[j];
+    if (wr + 2 * r <= kPkNarrowBudget) narrow |= 1 << j;
+    if (wr + r <= kPkWideBudget) wide |= 1 << j;
+  }
+  const int n_narrow = __builtin_popcount(narrow), n_wide = wide_whole ? kPkSubs : __builtin_popcount(wide);
+  if (n_narrow > 0 && 14 * n_narrow >= 11 * n_wide) return kPlanNarrow | narrow;
+  return wide_whole ? (kPlanWhole | 0xFF) : wide;
 }
 
 struct TropicalArgs {

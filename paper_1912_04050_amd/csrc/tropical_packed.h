@@ -10,28 +10,89 @@ namespace {
 // ---- packed 16-bit kernel -----------------------------------------------------------------
 
 typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+typedef _Float16 hf2 __attribute__((ext_vector_type(2)));
 
 // 16 steps against the 16 packed accumulators of a lane (window groups as in block_steps).
-// The combined values of a whole step are formed before the reductions so that no instruction
-// reads the result of its immediate predecessor (the compiler otherwise pads each pair with a
-// wait state).
-template <bool MAXF>
+// The combined values of a whole step (wide flavour) or of two steps (narrow flavour) are formed
+// before the reductions so that no instruction reads the result of its immediate predecessor
+// (the compiler otherwise pads each pair with a wait state).
+//   wide:   saturating add / subtract, then one packed integer min / max per step
+//   narrow: plain add / subtract, then one three-operand packed half-float minimum / maximum per
+//           two steps; every value involved is a pattern below 0x7C00, where the half-float
+//           order is the integer order (nested elementwise minimum / maximum compile to the
+//           three-operand instruction)
+template <bool MAXF, bool NARROW>
 __device__ __forceinline__ void block_steps_packed(uint32_t (&acc)[kPkR], const uint32_t (&u)[kPkR],
                                                    const uint32_t (&lo)[kPkR], const uint32_t (&hi)[kPkR]) {
+  if constexpr (NARROW) {
 #pragma unroll
-  for (int k = 0; k < kPkR; ++k) {
-    us2 s[kPkR];
+    for (int k = 0; k < kPkR; k += 2) {
+      const us2 ua = __builtin_bit_cast(us2, u[k]), ub = __builtin_bit_cast(us2, u[k + 1]);
 #pragma unroll
-    for (int r = 0; r < kPkR; ++r) {
-      const us2 w = __builtin_bit_cast(us2, (r >= k) ? hi[r - k] : lo[kPkR + r - k]);
-      const us2 uu = __builtin_bit_cast(us2, u[k]);
-      s[r] = MAXF ? __builtin_elementwise_sub_sat(w, uu) : __builtin_elementwise_add_sat(w, uu);
+      for (int h = 0; h < kPkR; h += kPkR / 2) {   // half of the accumulators at a time: fewer live registers
+        us2 s1[kPkR / 2], s2[kPkR / 2];
+#pragma unroll
+        for (int q = 0; q < kPkR / 2; ++q) {
+          const int r = h + q;
+          const us2 wa = __builtin_bit_cast(us2, (r >= k) ? hi[r - k] : lo[kPkR + r - k]);
+          const us2 wb = __builtin_bit_cast(us2, (r >= k + 1) ? hi[r - k - 1] : lo[kPkR + r - k - 1]);
+          s1[q] = MAXF ? wa - ua : wa + ua;
+          s2[q] = MAXF ? wb - ub : wb + ub;
+        }
+#pragma unroll
+        for (int q = 0; q < kPkR / 2; ++q) {
+          const hf2 av = __builtin_bit_cast(hf2, acc[h + q]);
+          const hf2 x1 = __builtin_bit_cast(hf2, s1[q]), x2 = __builtin_bit_cast(hf2, s2[q]);
+          acc[h + q] = __builtin_bit_cast(
+              uint32_t, MAXF ? __builtin_elementwise_maximum(__builtin_elementwise_maximum(av, x1), x2)
+                             : __builtin_elementwise_minimum(__builtin_elementwise_minimum(av, x1), x2));
+        }
+      }
     }
+  } else {
 #pragma unroll
-    for (int r = 0; r < kPkR; ++r) {
-      const us2 av = __builtin_bit_cast(us2, acc[r]);
-      acc[r] = __builtin_bit_cast(uint32_t, MAXF ? __builtin_elementwise_max(av, s[r])
-                                                   : __builtin_elementwise_min(av, s[r]));
+    for (int k = 0; k < kPkR; ++k) {
+      us2 s[kPkR];
+#pragma unroll
+      for (int r = 0; r < kPkR; ++r) {
+        const us2 w = __builtin_bit_cast(us2, (r >= k) ? hi[r - k] : lo[kPkR + r - k]);
+        const us2 uu = __builtin_bit_cast(us2, u[k]);
+        s[r] = MAXF ? __builtin_elementwise_sub_sat(w, uu) : __builtin_elementwise_add_sat(w, uu);
+      }
+#pragma unroll
+      for (int r = 0; r < kPkR; ++r) {
+        const us2 av = __builtin_bit_cast(us2, acc[r]);
+        acc[r] = __builtin_bit_cast(uint32_t, MAXF ? __builtin_elementwise_max(av, s[r])
+                                                     : __builtin_elementwise_min(av, s[r]));
+      }
+    }
+  }
+}
+
+// Blocks [first, last) of the staged chunk (block i = steps sc + 16 i ...) against the packed
+// accumulators; usrc is the packed uniform operand on the base of this run.
+template <bool MAXF, bool NARROW>
+__device__ __forceinline__ void run_blocks(uint32_t (&acc)[kPkR], const uint32_t* __restrict__ usrc,
+                                           const unsigned char* lds, int lane, int sc, int nblk, int first,
+                                           int last) {
+  uint32_t w0[kPkR], w1[kPkR];
+  load_group<uint32_t, kPkR>(w0, lds, lane + nblk - first);
+  for (int i = first; i < last; i += 2) {
+    {
+      const int s0 = sc + i * kPkR;
+      load_group<uint32_t, kPkR>(w1, lds, lane + nblk - i - 1);
+      uint32_t u[kPkR];
+#pragma unroll
+      for (int k = 0; k < kPkR; ++k) u[k] = usrc[s0 + k];
+      block_steps_packed<MAXF, NARROW>(acc, u, w1, w0);
+    }
+    if (i + 1 < last) {
+      const int s0 = sc + (i + 1) * kPkR;
+      load_group<uint32_t, kPkR>(w0, lds, lane + nblk - i - 2);
+      uint32_t u[kPkR];
+#pragma unroll
+      for (int k = 0; k < kPkR; ++k) u[k] = usrc[s0 + k];
+      block_steps_packed<MAXF, NARROW>(acc, u, w0, w1);
     }
   }
 }
@@ -39,10 +100,14 @@ __device__ __forceinline__ void block_steps_packed(uint32_t (&acc)[kPkR], const 
 // One wave owns 2048 outputs of the triangular product: the low 16 bits of every packed
 // register belong to output t0 + 16*lane + r, the high 16 bits to output t0 + 1024 + 16*lane + r.
 // Only the chunks / sub-chunks that chunk_plan() grants are processed; results merge into out with
-// atomic min / max.
-//   convolution:   lane value = (bd - gb) + (ad - ab); poison 0xFFFF (saturating add, min)
-//   deconvolution: lane value = (bd - gb) + ar + 1 - (ad - ab) >= 1; poison 0 for the window,
-//                  0xFFFF for the uniform operand (saturating subtract gives 0, max ignores it)
+// atomic min / max.  With w = bd - gb in [0, br] (window), u = ad - base in [0, ur] (uniform
+// operand, 0 beyond the row's end, where every window position is poison) a 16-bit lane holds
+//   min flavour:  w + lift + u, window poison P: every poisoned sum stays >= P > any candidate
+//   max flavour:  w + lift - u, window poison Q: every poisoned difference stays <= Q < any candidate
+//   wide:    min: lift 0, P = 0xFFFF (the add saturates);  max: lift 65535 - br, Q = 0 (the
+//            subtraction saturates)
+//   narrow:  with m = narrow_umax(br) >= ur:  min: lift 0, P = 0x7BFF - m;  max: lift 2m + 1,
+//            Q = m;  nothing leaves [0, 0x7BFF]
 template <typename OutT, int OP>
 __device__ __forceinline__ void packed_body(const TropicalArgs& p, unsigned char* lds, uint32_t item) {
   using TL = Tile<int32_t, kPkR>;
@@ -57,10 +122,8 @@ __device__ __forceinline__ void packed_body(const TropicalArgs& p, unsigned char
   const int32_t* __restrict__ bd = x.bd + (int64_t)row * n;
   const int32_t* __restrict__ ab = x.ab + (int64_t)row * x.nchunk;
   const int32_t* __restrict__ ab_s = x.ab_s + (int64_t)row * x.nsub;
-  constexpr bool MAXF = op_max(OP);   // arithmetic flavour: saturating subtract + max, or saturating add + min
+  constexpr bool MAXF = op_max(OP);   // arithmetic flavour: subtract + max, or add + min
   constexpr int32_t kIdent = MAXF ? INT32_MIN : INT32_MAX;
-  constexpr uint32_t kWinPoison = MAXF ? 0u : kPkPoison;   // staged for window positions that do not exist
-  constexpr uint32_t kAccPoison = MAXF ? 0u : kPkPoison;   // a 16-bit lane that saw no existing candidate
 
   int32_t acc_lo[kPkR], acc_hi[kPkR];
 #pragma unroll
@@ -70,27 +133,28 @@ __device__ __forceinline__ void packed_body(const TropicalArgs& p, unsigned char
     int32_t gb, br;
     const int c = sc / kPkChunk;
     const int plan = chunk_plan(x, row, t0 / kPkW, c, n, &gb, &br);
-    if (plan == 0) continue;
+    if ((plan & 0xFF) == 0) continue;
     const int ce = min(sc + kPkChunk, sb);
     const int nblk = (ce - sc + kPkR - 1) / kPkR;
     const int gbase = t0 - (sc + nblk * kPkR);
     const int count = (64 + nblk) * kPkR;
-    // max flavour: window values are lifted so that every existing candidate stays >= 1 after
-    // the saturating subtraction (the window spans at most br, any packable run of the uniform
-    // operand at most 65534 - br)
-    const uint32_t lift = MAXF ? 65535u - (uint32_t)br : 0u;
+    const bool narrow = (plan & kPlanNarrow) != 0;
+    const uint32_t m = (uint32_t)narrow_umax(br);
+    const uint32_t top = narrow ? (uint32_t)kPkNarrowTop : kPkPoison;        // largest value a lane may hold
+    const uint32_t lift = MAXF ? (narrow ? 2u * m + 1u : 65535u - (uint32_t)br) : 0u;
+    const uint32_t poison = MAXF ? (narrow ? m : 0u) : (narrow ? top - m : top);
     __syncthreads();
     for (int e = lane; e < count; e += 64) {
       const int il = gbase + e, ih = il + kPkHalf;
-      uint32_t vl = kWinPoison, vh = kWinPoison;
-      if (il >= 0 && il < n) vl = min((uint32_t)bd[il] - (uint32_t)gb + lift, kPkPoison);
-      if (ih >= 0 && ih < n) vh = min((uint32_t)bd[ih] - (uint32_t)gb + lift, kPkPoison);
+      uint32_t vl = poison, vh = poison;
+      if (il >= 0 && il < n) vl = min((uint32_t)bd[il] - (uint32_t)gb + lift, top);
+      if (ih >= 0 && ih < n) vh = min((uint32_t)bd[ih] - (uint32_t)gb + lift, top);
       *reinterpret_cast<uint32_t*>(lds + (e / kPkR) * TL::kSlotBytes + (e % kPkR) * 4) = vl | (vh << 16);
     }
     __syncthreads();
 
     // a run = a range of blocks that shares one base of the uniform operand: the whole chunk,
-    // or one qualifying sub-chunk
+    // or one granted sub-chunk
     const bool whole = (plan & kPlanWhole) != 0;
     const uint32_t* __restrict__ usrc = whole ? apk : apk_s;
     const int nrun = whole ? 1 : kPkSubs;
@@ -103,35 +167,19 @@ __device__ __forceinline__ void packed_body(const TropicalArgs& p, unsigned char
 
       uint32_t acc[kPkR];
 #pragma unroll
-      for (int r = 0; r < kPkR; ++r) acc[r] = kAccPoison * 0x10001u;
-      uint32_t w0[kPkR], w1[kPkR];
-      load_group<uint32_t, kPkR>(w0, lds, lane + nblk - first);
-      for (int i = first; i < last; i += 2) {
-        {
-          const int s0 = sc + i * kPkR;
-          load_group<uint32_t, kPkR>(w1, lds, lane + nblk - i - 1);
-          uint32_t u[kPkR];
-#pragma unroll
-          for (int k = 0; k < kPkR; ++k) u[k] = usrc[s0 + k];
-          block_steps_packed<MAXF>(acc, u, w1, w0);
-        }
-        if (i + 1 < last) {
-          const int s0 = sc + (i + 1) * kPkR;
-          load_group<uint32_t, kPkR>(w0, lds, lane + nblk - i - 2);
-          uint32_t u[kPkR];
-#pragma unroll
-          for (int k = 0; k < kPkR; ++k) u[k] = usrc[s0 + k];
-          block_steps_packed<MAXF>(acc, u, w0, w1);
-        }
-      }
+      for (int r = 0; r < kPkR; ++r) acc[r] = (MAXF ? 0u : top) * 0x10001u;
+      if (narrow) run_blocks<MAXF, true>(acc, usrc, lds, lane, sc, nblk, first, last);
+      else run_blocks<MAXF, false>(acc, usrc, lds, lane, sc, nblk, first, last);
       // fold the run into the 32-bit accumulators (detrended domain, wrap-around arithmetic:
-      // every folded value is a true candidate, which fits)
+      // every folded value is a true candidate, which fits); a lane on the poison side of the
+      // threshold saw no existing candidate
       const uint32_t cb = MAXF ? (uint32_t)gb - (uint32_t)ubase - lift : (uint32_t)ubase + (uint32_t)gb;
 #pragma unroll
       for (int r = 0; r < kPkR; ++r) {
         const uint32_t vl = acc[r] & 0xFFFFu, vh = acc[r] >> 16;
-        const int32_t cl = vl != kAccPoison ? (int32_t)(cb + vl) : kIdent;
-        const int32_t ch = vh != kAccPoison ? (int32_t)(cb + vh) : kIdent;
+        const bool okl = MAXF ? vl > poison : vl < poison, okh = MAXF ? vh > poison : vh < poison;
+        const int32_t cl = okl ? (int32_t)(cb + vl) : kIdent;
+        const int32_t ch = okh ? (int32_t)(cb + vh) : kIdent;
         acc_lo[r] = MAXF ? max(acc_lo[r], cl) : min(acc_lo[r], cl);
         acc_hi[r] = MAXF ? max(acc_hi[r], ch) : min(acc_hi[r], ch);
       }

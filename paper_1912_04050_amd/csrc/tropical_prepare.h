@@ -186,6 +186,8 @@ __global__ __launch_bounds__(1024) void prep_kernel(const int32_t* __restrict__ 
   const bool valid = i < n;
   int32_t adv = valid ? wrap_sub(a[(int64_t)row * stride_a + i], r * i) : 0;
   if (neg) adv = wrap_sub(0, adv);   // max-plus convolution / min-plus deconvolution: see packed_body
+  // positions beyond the row's end are packed as 0: every window position that meets them is
+  // poison, which decides the outcome whatever the uniform value
   int32_t bdv = 0;
   if (valid) bdv = deconv ? wrap_add(b[(int64_t)row * stride_b + (n - 1 - i)], r * i)
                           : wrap_sub(b[(int64_t)row * stride_b + i], r * i);
@@ -197,12 +199,12 @@ __global__ __launch_bounds__(1024) void prep_kernel(const int32_t* __restrict__ 
   int32_t cmn = INT32_MAX, cmx = INT32_MIN;
 #pragma unroll
   for (int w = 0; w < 16; ++w) { cmn = min(cmn, s_amn[w]); cmx = max(cmx, s_amx[w]); }
-  apk[(int64_t)row * npad + i] = valid ? min((uint32_t)adv - (uint32_t)cmn, kPkPoison) * 0x10001u : 0xFFFFFFFFu;
+  apk[(int64_t)row * npad + i] = valid ? min((uint32_t)adv - (uint32_t)cmn, kPkPoison) * 0x10001u : 0u;
   // sub-chunk of 128 indices = 2 waves
   const int sub = threadIdx.x / kPkSub;
   const int32_t smn = min(s_amn[2 * sub], s_amn[2 * sub + 1]);
   const int32_t smx = max(s_amx[2 * sub], s_amx[2 * sub + 1]);
-  apk_s[(int64_t)row * npad + i] = valid ? min((uint32_t)adv - (uint32_t)smn, kPkPoison) * 0x10001u : 0xFFFFFFFFu;
+  apk_s[(int64_t)row * npad + i] = valid ? min((uint32_t)adv - (uint32_t)smn, kPkPoison) * 0x10001u : 0u;
   if ((threadIdx.x & (kPkSub - 1)) == 0) {
     const bool any = smx >= smn;   // false when the sub-chunk lies entirely beyond n
     const int64_t range = (int64_t)smx - (int64_t)smn;

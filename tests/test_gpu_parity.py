@@ -156,6 +156,50 @@ def test_packed_path_value_limits(rtc):
     _both_paths(rtc, f.astype(np.int32), g.astype(np.int32), "packed limits")
 
 
+def _bounded_rows(rng, n, span, period, offset=None):
+    """Rows without trend whose every aligned run of `period` samples takes both 0 and `span`
+    (so that each run's range is exactly span); offset[j] is added to run j."""
+    v = rng.integers(0, span + 1, n)
+    for s0 in range(0, n, period):
+        m = min(period, n - s0)
+        if m >= 2:
+            i, j = rng.choice(m, 2, replace=False)
+            v[s0 + i], v[s0 + j] = 0, span
+    if offset is not None:
+        v = v + np.repeat(offset, period)[:n]
+    v[-1] = v[0] - 1 if v[0] > 0 else v[0]   # first >= last: the slope estimate stays 0
+    return v
+
+
+def test_packed_path_budget_edges(rtc):
+    """Operand ranges on both sides of the two packed budgets: window range + 2 x run range
+    <= 31742 for the 15-bit flavour, window range + run range <= 65534 for the 16-bit one; whole
+    chunks of 1024 steps and sub-chunks of 128 steps."""
+    rng = np.random.default_rng(25)
+    n = 4300
+    cases = []
+    for span_w, span_u in ((0, 15871), (31742, 0), (11742, 10000), (11743, 10000), (11741, 10000),
+                           (1, 15871), (31743, 0), (20000, 45534), (20000, 45535), (65534, 0), (65535, 0),
+                           (0, 65534), (0, 65535), (3, 3)):
+        cases.append((_bounded_rows(rng, n, span_u, 128), _bounded_rows(rng, n, span_w, 256)))
+    # staircases: sub-chunk ranges fit, chunk ranges do not; narrow and wide sub-chunks mixed
+    nsub = (n + 127) // 128
+    stair = (np.arange(nsub) % 8) * 9000
+    cases.append((_bounded_rows(rng, n, 700, 128, stair), _bounded_rows(rng, n, 30000, 256)))
+    cases.append((_bounded_rows(rng, n, 700, 128, stair), _bounded_rows(rng, n, 30400, 256)))
+    spans = rng.choice([100, 5000, 15000, 40000], nsub)
+    mixed = np.concatenate([_bounded_rows(rng, 128, int(sp), 128) for sp in spans])[:n]
+    mixed[-1] = min(mixed[-1], mixed[0])
+    cases.append((mixed + np.repeat(stair, 128)[:n], _bounded_rows(rng, n, 1500, 256)))
+    cases.append((mixed, _bounded_rows(rng, n, 20000, 256)))
+    f = np.stack([c[0] for c in cases]).astype(np.int32)
+    g = np.stack([c[1] for c in cases]).astype(np.int32)
+    _both_paths(rtc, f, g, "packed budget edges")
+    check_duals(rtc, f, g, "packed budget edges, duals")
+    _both_paths(rtc, g, f, "packed budget edges, swapped")
+    check_duals(rtc, g, f, "packed budget edges, swapped duals")
+
+
 def test_packed_path_ragged_sizes(rtc):
     for n in (1, 17, 255, 256, 257, 1023, 1024, 1025, 2047, 2048, 2049, 3071, 3073, 5121):
         f = wl.random_monotone(23, 2 * n, 2, n, np.int32, max_inc=40)
