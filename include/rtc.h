@@ -199,6 +199,12 @@ int rtc_max_vdev(const void* alpha, const void* beta, void* out, int64_t batch, 
  * depend on it.  Process-wide, not thread-safe. */
 int rtc_set_packed_min_work(double batch_times_n_squared);
 
+/* Planner knob: rows of at most this many samples give the packed work items tiles of 1024
+ * outputs instead of 2048 (fewer candidates wasted on the half-empty diagonal of a tile, more
+ * loop overhead per candidate; default 4096, measured).  0 never does, a value >= RTC_MAX_N always does.  Results do not
+ * depend on it.  Process-wide, not thread-safe.  RTC_ERR_SHAPE for a negative value. */
+int rtc_set_packed_small_n(int64_t n);
+
 /* Bytes of device workspace an operator needs for the given shape (0 on invalid input). */
 size_t rtc_workspace_bytes(int op, int64_t batch, int64_t n, rtc_dtype dt);
 

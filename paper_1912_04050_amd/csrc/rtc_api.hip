@@ -284,6 +284,12 @@ int rtc_set_packed_min_work(double batch_times_n_squared) {
   return RTC_OK;
 }
 
+int rtc_set_packed_small_n(int64_t n) {
+  if (n < 0) return RTC_ERR_SHAPE;
+  rtc::g_packed_small_n = n;
+  return RTC_OK;
+}
+
 const char* rtc_strerror(int status) {
   switch (status) {
     case RTC_OK: return "ok";

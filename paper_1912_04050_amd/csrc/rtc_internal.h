@@ -22,6 +22,7 @@ int launch_tropical(int op, const void* f, const void* g, void* out, int64_t bat
                     size_t ws_bytes, int32_t* dev_flags, hipStream_t stream);
 size_t tropical_workspace_bytes(int64_t batch, int64_t n, int dt);
 extern double g_packed_min_work;  // planner knob, see rtc_set_packed_min_work
+extern int64_t g_packed_small_n;  // planner knob, see rtc_set_packed_small_n
 
 // HBM-bound curve kernels (curve_ops.hip).
 int launch_pseudo_inverse(const void* f, int64_t n, const void* x, int64_t m, int32_t* out,

@@ -50,6 +50,9 @@
 #include "tropical_prepare.h"
 
 namespace rtc {
+
+int64_t g_packed_small_n = 4096;   // rows up to this length use the narrower packed tiles
+
 namespace {
 
 template <typename T, typename OutT, int OP, int R, bool ATOMIC>
@@ -62,11 +65,13 @@ __global__ __launch_bounds__(64) void tropical_kernel(const TropicalArgs p) {
 // items of the packed kernel, the rest are items of the 32-bit kernel (which skip the chunks
 // the packed items own).  Issuing both kinds together keeps the machine full whatever share of
 // the chunks qualifies for 16 bits.
-template <typename OutT, int OP>
+// RP = accumulators per lane of the packed items (their tiles are 128 RP outputs wide).
+template <typename OutT, int OP, int RP>
 __global__ __launch_bounds__(64) void fused_kernel(const TropicalArgs pk, const TropicalArgs pg,
                                                    uint32_t n_packed) {
+  static_assert(lds_bytes<int32_t, RP>() <= lds_bytes<int32_t, kPkR>(), "the 32-bit layout is the larger one");
   __shared__ __align__(16) unsigned char lds[lds_bytes<int32_t, kPkR>()];
-  if (blockIdx.x < n_packed) packed_body<OutT, OP>(pk, lds, blockIdx.x);
+  if (blockIdx.x < n_packed) packed_body<OutT, OP, RP>(pk, lds, blockIdx.x);
   else tropical_body<int32_t, OutT, OP, kPkR, true>(pg, lds, blockIdx.x - n_packed);
 }
 
@@ -216,7 +221,9 @@ int run_packed(const int32_t* f32, int64_t stride_f, const int32_t* g32, int64_t
                      const_cast<int32_t*>(aux.bmn), const_cast<int32_t*>(aux.bmx));
   hipLaunchKernelGGL(decide_kernel, dim3((uint32_t)batch), dim3(256), 0, stream, aux, (int)n,
                      const_cast<int32_t*>(aux.pack_ok));
-  const Plan pk = make_plan(batch, n, kPkW, kPkChunk);
+  // short rows: tiles of 1024 outputs halve the candidates wasted on the diagonal
+  const bool small_tiles = n <= g_packed_small_n;
+  const Plan pk = make_plan(batch, n, small_tiles ? kPkW / 2 : kPkW, kPkChunk);
   const Plan pg = make_plan<int32_t>(batch, n);
   if (pk.items + pg.items > 0x7fffffffLL) return RTC_ERR_SHAPE;
   TropicalArgs ak = {};
@@ -230,8 +237,12 @@ int run_packed(const int32_t* f32, int64_t stride_f, const int32_t* g32, int64_t
   ag.b = op_sub(OP) ? f32 : g32; ag.stride_b = op_sub(OP) ? stride_f : stride_g;
   ag.n_tiles = pg.n_tiles; ag.fold_width = pg.fold_width; ag.seg = pg.seg;
   prof_begin(RTC_PROFILE_KIND(RTC_I32, 1, OP), stream);
-  hipLaunchKernelGGL((fused_kernel<OutT, OP>), dim3((uint32_t)(pk.items + pg.items)), dim3(64), 0, stream,
-                     ak, ag, (uint32_t)pk.items);
+  if (small_tiles)
+    hipLaunchKernelGGL((fused_kernel<OutT, OP, kPkR / 2>), dim3((uint32_t)(pk.items + pg.items)), dim3(64), 0,
+                       stream, ak, ag, (uint32_t)pk.items);
+  else
+    hipLaunchKernelGGL((fused_kernel<OutT, OP, kPkR>), dim3((uint32_t)(pk.items + pg.items)), dim3(64), 0,
+                       stream, ak, ag, (uint32_t)pk.items);
   prof_end(stream);
   return hip_ok();
 }

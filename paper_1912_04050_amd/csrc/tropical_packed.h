@@ -12,7 +12,7 @@ namespace {
 typedef unsigned short us2 __attribute__((ext_vector_type(2)));
 typedef _Float16 hf2 __attribute__((ext_vector_type(2)));
 
-// 16 steps against the 16 packed accumulators of a lane (window groups as in block_steps).
+// R steps against the R packed accumulators of a lane (window groups as in block_steps).
 // The combined values of a whole step (wide flavour) or of two steps (narrow flavour) are formed
 // before the reductions so that no instruction reads the result of its immediate predecessor
 // (the compiler otherwise pads each pair with a wait state).
@@ -21,26 +21,26 @@ typedef _Float16 hf2 __attribute__((ext_vector_type(2)));
 //           two steps; every value involved is a pattern below 0x7C00, where the half-float
 //           order is the integer order (nested elementwise minimum / maximum compile to the
 //           three-operand instruction)
-template <bool MAXF, bool NARROW>
-__device__ __forceinline__ void block_steps_packed(uint32_t (&acc)[kPkR], const uint32_t (&u)[kPkR],
-                                                   const uint32_t (&lo)[kPkR], const uint32_t (&hi)[kPkR]) {
+template <bool MAXF, bool NARROW, int R>
+__device__ __forceinline__ void block_steps_packed(uint32_t (&acc)[R], const uint32_t (&u)[R],
+                                                   const uint32_t (&lo)[R], const uint32_t (&hi)[R]) {
   if constexpr (NARROW) {
 #pragma unroll
-    for (int k = 0; k < kPkR; k += 2) {
+    for (int k = 0; k < R; k += 2) {
       const us2 ua = __builtin_bit_cast(us2, u[k]), ub = __builtin_bit_cast(us2, u[k + 1]);
 #pragma unroll
-      for (int h = 0; h < kPkR; h += kPkR / 2) {   // half of the accumulators at a time: fewer live registers
-        us2 s1[kPkR / 2], s2[kPkR / 2];
+      for (int h = 0; h < R; h += R / 2) {   // half of the accumulators at a time: fewer live registers
+        us2 s1[R / 2], s2[R / 2];
 #pragma unroll
-        for (int q = 0; q < kPkR / 2; ++q) {
+        for (int q = 0; q < R / 2; ++q) {
           const int r = h + q;
-          const us2 wa = __builtin_bit_cast(us2, (r >= k) ? hi[r - k] : lo[kPkR + r - k]);
-          const us2 wb = __builtin_bit_cast(us2, (r >= k + 1) ? hi[r - k - 1] : lo[kPkR + r - k - 1]);
+          const us2 wa = __builtin_bit_cast(us2, (r >= k) ? hi[r - k] : lo[R + r - k]);
+          const us2 wb = __builtin_bit_cast(us2, (r >= k + 1) ? hi[r - k - 1] : lo[R + r - k - 1]);
           s1[q] = MAXF ? wa - ua : wa + ua;
           s2[q] = MAXF ? wb - ub : wb + ub;
         }
 #pragma unroll
-        for (int q = 0; q < kPkR / 2; ++q) {
+        for (int q = 0; q < R / 2; ++q) {
           const hf2 av = __builtin_bit_cast(hf2, acc[h + q]);
           const hf2 x1 = __builtin_bit_cast(hf2, s1[q]), x2 = __builtin_bit_cast(hf2, s2[q]);
           acc[h + q] = __builtin_bit_cast(
@@ -51,16 +51,16 @@ __device__ __forceinline__ void block_steps_packed(uint32_t (&acc)[kPkR], const 
     }
   } else {
 #pragma unroll
-    for (int k = 0; k < kPkR; ++k) {
-      us2 s[kPkR];
+    for (int k = 0; k < R; ++k) {
+      us2 s[R];
 #pragma unroll
-      for (int r = 0; r < kPkR; ++r) {
-        const us2 w = __builtin_bit_cast(us2, (r >= k) ? hi[r - k] : lo[kPkR + r - k]);
+      for (int r = 0; r < R; ++r) {
+        const us2 w = __builtin_bit_cast(us2, (r >= k) ? hi[r - k] : lo[R + r - k]);
         const us2 uu = __builtin_bit_cast(us2, u[k]);
         s[r] = MAXF ? __builtin_elementwise_sub_sat(w, uu) : __builtin_elementwise_add_sat(w, uu);
       }
 #pragma unroll
-      for (int r = 0; r < kPkR; ++r) {
+      for (int r = 0; r < R; ++r) {
         const us2 av = __builtin_bit_cast(us2, acc[r]);
         acc[r] = __builtin_bit_cast(uint32_t, MAXF ? __builtin_elementwise_max(av, s[r])
                                                      : __builtin_elementwise_min(av, s[r]));
@@ -69,36 +69,37 @@ __device__ __forceinline__ void block_steps_packed(uint32_t (&acc)[kPkR], const 
   }
 }
 
-// Blocks [first, last) of the staged chunk (block i = steps sc + 16 i ...) against the packed
+// Blocks [first, last) of the staged chunk (block i = steps sc + R i ...) against the packed
 // accumulators; usrc is the packed uniform operand on the base of this run.
-template <bool MAXF, bool NARROW>
-__device__ __forceinline__ void run_blocks(uint32_t (&acc)[kPkR], const uint32_t* __restrict__ usrc,
+template <bool MAXF, bool NARROW, int R>
+__device__ __forceinline__ void run_blocks(uint32_t (&acc)[R], const uint32_t* __restrict__ usrc,
                                            const unsigned char* lds, int lane, int sc, int nblk, int first,
                                            int last) {
-  uint32_t w0[kPkR], w1[kPkR];
-  load_group<uint32_t, kPkR>(w0, lds, lane + nblk - first);
+  uint32_t w0[R], w1[R];
+  load_group<uint32_t, R>(w0, lds, lane + nblk - first);
   for (int i = first; i < last; i += 2) {
     {
-      const int s0 = sc + i * kPkR;
-      load_group<uint32_t, kPkR>(w1, lds, lane + nblk - i - 1);
-      uint32_t u[kPkR];
+      const int s0 = sc + i * R;
+      load_group<uint32_t, R>(w1, lds, lane + nblk - i - 1);
+      uint32_t u[R];
 #pragma unroll
-      for (int k = 0; k < kPkR; ++k) u[k] = usrc[s0 + k];
-      block_steps_packed<MAXF, NARROW>(acc, u, w1, w0);
+      for (int k = 0; k < R; ++k) u[k] = usrc[s0 + k];
+      block_steps_packed<MAXF, NARROW, R>(acc, u, w1, w0);
     }
     if (i + 1 < last) {
-      const int s0 = sc + (i + 1) * kPkR;
-      load_group<uint32_t, kPkR>(w0, lds, lane + nblk - i - 2);
-      uint32_t u[kPkR];
+      const int s0 = sc + (i + 1) * R;
+      load_group<uint32_t, R>(w0, lds, lane + nblk - i - 2);
+      uint32_t u[R];
 #pragma unroll
-      for (int k = 0; k < kPkR; ++k) u[k] = usrc[s0 + k];
-      block_steps_packed<MAXF, NARROW>(acc, u, w0, w1);
+      for (int k = 0; k < R; ++k) u[k] = usrc[s0 + k];
+      block_steps_packed<MAXF, NARROW, R>(acc, u, w0, w1);
     }
   }
 }
 
-// One wave owns 2048 outputs of the triangular product: the low 16 bits of every packed
-// register belong to output t0 + 16*lane + r, the high 16 bits to output t0 + 1024 + 16*lane + r.
+// One wave owns 128 R outputs of the triangular product (R = 16, or 8 for short rows where the
+// half-empty diagonal of a wide tile weighs more): the low 16 bits of every packed register belong
+// to output t0 + R*lane + r, the high 16 bits to output t0 + 64 R + R*lane + r.
 // Only the chunks / sub-chunks that chunk_plan() grants are processed; results merge into out with
 // atomic min / max.  With w = bd - gb in [0, br] (window), u = ad - base in [0, ur] (uniform
 // operand, 0 beyond the row's end, where every window position is poison) a 16-bit lane holds
@@ -108,13 +109,14 @@ __device__ __forceinline__ void run_blocks(uint32_t (&acc)[kPkR], const uint32_t
 //            subtraction saturates)
 //   narrow:  with m = narrow_umax(br) >= ur:  min: lift 0, P = 0x7BFF - m;  max: lift 2m + 1,
 //            Q = m;  nothing leaves [0, 0x7BFF]
-template <typename OutT, int OP>
+template <typename OutT, int OP, int R>
 __device__ __forceinline__ void packed_body(const TropicalArgs& p, unsigned char* lds, uint32_t item) {
-  using TL = Tile<int32_t, kPkR>;
+  using TL = Tile<int32_t, R>;
   const int lane = threadIdx.x;
   const int n = p.n;
   int row, t0, sa, sb;
-  if (!decode_item<kPkW>(p, item, &row, &t0, &sa, &sb)) return;
+  constexpr int kHalf = 64 * R;          // outputs per 16-bit half of the tile
+  if (!decode_item<2 * kHalf>(p, item, &row, &t0, &sa, &sb)) return;
   const PackAux& x = p.aux;
   if (x.pack_ok[row] == 0) return;
   const uint32_t* __restrict__ apk = x.apk + (int64_t)row * x.npad;
@@ -125,9 +127,9 @@ __device__ __forceinline__ void packed_body(const TropicalArgs& p, unsigned char
   constexpr bool MAXF = op_max(OP);   // arithmetic flavour: subtract + max, or add + min
   constexpr int32_t kIdent = MAXF ? INT32_MIN : INT32_MAX;
 
-  int32_t acc_lo[kPkR], acc_hi[kPkR];
+  int32_t acc_lo[R], acc_hi[R];
 #pragma unroll
-  for (int r = 0; r < kPkR; ++r) { acc_lo[r] = kIdent; acc_hi[r] = kIdent; }
+  for (int r = 0; r < R; ++r) { acc_lo[r] = kIdent; acc_hi[r] = kIdent; }
 
   for (int sc = sa; sc < sb; sc += kPkChunk) {
     int32_t gb, br;
@@ -135,9 +137,9 @@ __device__ __forceinline__ void packed_body(const TropicalArgs& p, unsigned char
     const int plan = chunk_plan(x, row, t0 / kPkW, c, n, &gb, &br);
     if ((plan & 0xFF) == 0) continue;
     const int ce = min(sc + kPkChunk, sb);
-    const int nblk = (ce - sc + kPkR - 1) / kPkR;
-    const int gbase = t0 - (sc + nblk * kPkR);
-    const int count = (64 + nblk) * kPkR;
+    const int nblk = (ce - sc + R - 1) / R;
+    const int gbase = t0 - (sc + nblk * R);
+    const int count = (64 + nblk) * R;
     const bool narrow = (plan & kPlanNarrow) != 0;
     const uint32_t m = (uint32_t)narrow_umax(br);
     const uint32_t top = narrow ? (uint32_t)kPkNarrowTop : kPkPoison;        // largest value a lane may hold
@@ -145,11 +147,11 @@ __device__ __forceinline__ void packed_body(const TropicalArgs& p, unsigned char
     const uint32_t poison = MAXF ? (narrow ? m : 0u) : (narrow ? top - m : top);
     __syncthreads();
     for (int e = lane; e < count; e += 64) {
-      const int il = gbase + e, ih = il + kPkHalf;
+      const int il = gbase + e, ih = il + kHalf;
       uint32_t vl = poison, vh = poison;
       if (il >= 0 && il < n) vl = min((uint32_t)bd[il] - (uint32_t)gb + lift, top);
       if (ih >= 0 && ih < n) vh = min((uint32_t)bd[ih] - (uint32_t)gb + lift, top);
-      *reinterpret_cast<uint32_t*>(lds + (e / kPkR) * TL::kSlotBytes + (e % kPkR) * 4) = vl | (vh << 16);
+      *reinterpret_cast<uint32_t*>(lds + (e / R) * TL::kSlotBytes + (e % R) * 4) = vl | (vh << 16);
     }
     __syncthreads();
 
@@ -159,23 +161,23 @@ __device__ __forceinline__ void packed_body(const TropicalArgs& p, unsigned char
     const uint32_t* __restrict__ usrc = whole ? apk : apk_s;
     const int nrun = whole ? 1 : kPkSubs;
     for (int run = 0; run < nrun; ++run) {
-      const int first = whole ? 0 : run * kPkSubBlocks;
+      const int first = whole ? 0 : run * (kPkSub / R);
       if (first >= nblk) break;
       if (!whole && !((plan >> run) & 1)) continue;
-      const int last = whole ? nblk : min(first + kPkSubBlocks, nblk);
+      const int last = whole ? nblk : min(first + kPkSub / R, nblk);
       const int32_t ubase = whole ? ab[c] : ab_s[c * kPkSubs + run];
 
-      uint32_t acc[kPkR];
+      uint32_t acc[R];
 #pragma unroll
-      for (int r = 0; r < kPkR; ++r) acc[r] = (MAXF ? 0u : top) * 0x10001u;
-      if (narrow) run_blocks<MAXF, true>(acc, usrc, lds, lane, sc, nblk, first, last);
-      else run_blocks<MAXF, false>(acc, usrc, lds, lane, sc, nblk, first, last);
+      for (int r = 0; r < R; ++r) acc[r] = (MAXF ? 0u : top) * 0x10001u;
+      if (narrow) run_blocks<MAXF, true, R>(acc, usrc, lds, lane, sc, nblk, first, last);
+      else run_blocks<MAXF, false, R>(acc, usrc, lds, lane, sc, nblk, first, last);
       // fold the run into the 32-bit accumulators (detrended domain, wrap-around arithmetic:
       // every folded value is a true candidate, which fits); a lane on the poison side of the
       // threshold saw no existing candidate
       const uint32_t cb = MAXF ? (uint32_t)gb - (uint32_t)ubase - lift : (uint32_t)ubase + (uint32_t)gb;
 #pragma unroll
-      for (int r = 0; r < kPkR; ++r) {
+      for (int r = 0; r < R; ++r) {
         const uint32_t vl = acc[r] & 0xFFFFu, vh = acc[r] >> 16;
         const bool okl = MAXF ? vl > poison : vl < poison, okh = MAXF ? vh > poison : vh < poison;
         const int32_t cl = okl ? (int32_t)(cb + vl) : kIdent;
@@ -195,13 +197,13 @@ __device__ __forceinline__ void packed_body(const TropicalArgs& p, unsigned char
   for (int half = 0; half < 2; ++half) {
     __syncthreads();
 #pragma unroll
-    for (int r = 0; r < kPkR; ++r) xp[lane * (kPkR + 1) + r] = half == 0 ? acc_lo[r] : acc_hi[r];
+    for (int r = 0; r < R; ++r) xp[lane * (R + 1) + r] = half == 0 ? acc_lo[r] : acc_hi[r];
     __syncthreads();
 #pragma unroll
-    for (int r = 0; r < kPkR; ++r) {
+    for (int r = 0; r < R; ++r) {
       const int xo = r * 64 + lane;
-      const int t = t0 + half * kPkHalf + xo;
-      const int32_t av = xp[xo + xo / kPkR];
+      const int t = t0 + half * kHalf + xo;
+      const int32_t av = xp[xo + xo / R];
       if (t < n && av != kIdent) {
         const int ot = op_sub(OP) ? n - 1 - t : t;
         OutT v = (OutT)(op_sub(OP) ? wrap_sub(av, rho * t) : wrap_add(av, rho * t));

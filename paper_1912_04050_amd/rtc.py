@@ -138,6 +138,14 @@ def rtc_set_packed_min_work(batch_times_n_squared: float):
     _check(_lib.rtc_set_packed_min_work(float(batch_times_n_squared)))
 
 
+_lib.rtc_set_packed_small_n.argtypes = [_i64]
+_lib.rtc_set_packed_small_n.restype = _int
+
+
+def rtc_set_packed_small_n(n: int):
+    _check(_lib.rtc_set_packed_small_n(int(n)))
+
+
 def rtc_profile_enable(on: bool):
     _check(_lib.rtc_profile_enable(1 if on else 0))
 

@@ -20,14 +20,19 @@ NP2T = {np.dtype(np.int32): torch.int32, np.dtype(np.int64): torch.int64, np.dty
 DTYPES = [np.int32, np.int64, np.float64]
 
 
-@pytest.fixture(scope="module", params=["default-planner", "packed-at-every-size"])
+@pytest.fixture(scope="module", params=["default-planner", "packed-wide-tiles", "packed-small-tiles"])
 def rtc(request):
-    """Every test runs twice: with the default planner (small problems take the 32-bit kernel
-    alone) and with the packed 16-bit path forced on for every size that brings a workspace."""
+    """Every test runs three times: with the default planner (small problems take the 32-bit
+    kernel alone), and with the packed 16-bit path forced on for every size that brings a
+    workspace, once with its tiles of 2048 outputs and once with those of 1024."""
     from paper_1912_04050_amd import rtc as mod
-    mod.rtc_set_packed_min_work(0.0 if request.param == "packed-at-every-size" else 2.0 ** 30)
+    default_small_n = 4096
+    if request.param != "default-planner":
+        mod.rtc_set_packed_min_work(0.0)
+        mod.rtc_set_packed_small_n(0 if request.param == "packed-wide-tiles" else 1 << 24)
     yield mod
     mod.rtc_set_packed_min_work(2.0 ** 30)
+    mod.rtc_set_packed_small_n(default_small_n)
 
 
 def say(*a):
