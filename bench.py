@@ -46,7 +46,7 @@ def parse():
 # HBM traffic of one launch of the dominant kernel on the headline workload, from two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by what the same counters read for a
 # plain 1 GiB device copy; see profiles/.  None for any other workload.
-HEADLINE_TRAFFIC_BYTES = 615104500   # 58.6 MiB fetched + 528 MiB of atomic-merge writes (profiles/fused_kernel_headline_pmc.md)
+HEADLINE_TRAFFIC_BYTES = 657368416   # 94.5 MiB fetched + 532 MiB of atomic-merge writes (profiles/fused_kernel_headline_pmc.md)
 
 
 def headline_traffic(batch, n):
@@ -329,8 +329,10 @@ def main():
         "gpair_ops_per_s": round(B * pair_ops_one / (conv_ms * 1e-3) / 1e9, 2),
         "cu_count": info["cu_count"], "clock_khz": info["clock_khz"], "kernels": kernels,
         "note": "achieved counts 2 lane-ops (add + min) per pair-op by definition, over the kernel's own "
-                "HIP-event duration; peak = CUs x 64 lanes x clock. The kernel issues 1 VALU instruction per "
-                "pair-op (v_pk_add_u16 + v_pk_min_u16 serve two pair-ops), which is how frac exceeds 1; "
+                "HIP-event duration; peak = CUs x 64 lanes x clock. The kernel issues 0.75 VALU instructions per "
+                "pair-op where a chunk fits 15 bits (two v_pk_add_u16 + one v_pk_minimum3_f16 serve four "
+                "pair-ops) and 1 where it needs 16 (v_pk_add_u16 + v_pk_min_u16 serve two), which is how frac "
+                "exceeds 1; "
                 "call_ms is the whole rtc_minplus_conv call (probe, fill, prepare, decide, fused kernel, and the "
                 "64-bit kernel that finds nothing left to do)",
     }
