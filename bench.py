@@ -138,6 +138,24 @@ def per_config_table(seed, peak_ops, with_cpu):
     vd = torch.empty(1024, dtype=torch.int32, device="cuda")
     hbm_row(2, "max_hdev", lambda: rtc.rtc_max_hdev(a, b, out=hd), 2 * 1024 * 4096 * 4 + 4096, "int32", 1024, 4096)
     hbm_row(2, "max_vdev", lambda: rtc.rtc_max_vdev(a, b, out=vd), 2 * 1024 * 4096 * 4 + 4096, "int32", 1024, 4096)
+    # sub-additive closure of config 2's arrival curves: ceil(log2(n-1)) = 12 squarings on the GPU; the
+    # oracle forms all n-2 powers by definition (cubic), so it is timed on shorter rows
+    clo = torch.empty_like(a)
+    ws_c = torch.empty(rtc.rtc_workspace_bytes(rtc.RTC_OP_CLOSURE, 1024, 4096, torch.int32), dtype=torch.uint8,
+                       device="cuda")
+    med, mn = gpu_ms(lambda: rtc.rtc_subadditive_closure(a, out=clo, ws=ws_c), warm=1, reps=5)
+    po_c = 12 * 1024 * 4096 * 4097 // 2
+    r = {"config": 2, "op": "subadditive_closure (12 squarings)", "dtype": "int32", "batch": 1024, "n": 4096,
+         "gpu_ms": round(med, 4), "gpu_ms_min": round(mn, 4), "pair_ops": po_c,
+         "gpair_ops_per_s": round(po_c / med / 1e6, 1),
+         "pct_valu_peak_2ops": round(100 * 2 * po_c / (med * 1e-3) / peak_ops, 1)}
+    if with_cpu:
+        short = np.ascontiguousarray(c["alpha_u"][:16, :512])
+        sec = cpu_s(lambda: oracle.closure(short))
+        r.update({"oracle_s": sec, "oracle_rows": 16, "oracle_threads": threads,
+                  "oracle_note": "16 rows cut to n=512: the oracle takes all 510 powers of a row, "
+                                 "510 x 512*513/2 pair-ops each row"})
+    rows.append(r)
     # config 3: int64 storage (range-probed 32-bit arithmetic), native int32, and forced 64-bit arithmetic
     c = wl.config3(seed, 64, 65536)
     product_rows(3, c["f"], c["g"], 8, "int64 storage, int32 arithmetic")
@@ -186,6 +204,23 @@ def per_config_table(seed, peak_ops, with_cpu):
                  "gpu_ms": round(med, 3), "gpu_ms_min": round(mn, 3), "pair_ops": 16 * po4,
                  "gpair_ops_per_s": round(16 * po4 / med / 1e6, 1),
                  "pct_valu_peak_2ops": round(100 * 2 * 16 * po4 / (med * 1e-3) / peak_ops, 1)})
+    # concatenated service curve of the chain: beta^l_1 (x) ... (x) beta^l_16, 15 products
+    cat = torch.empty_like(a0)
+    ws_k = torch.empty(rtc.rtc_workspace_bytes(rtc.RTC_OP_CHAIN, B4, N4, torch.int32), dtype=torch.uint8,
+                       device="cuda")
+    med, mn = gpu_ms(lambda: rtc.rtc_conv_chain(bl, out=cat, ws=ws_k), warm=1, reps=5)
+    po_k = 15 * B4 * N4 * (N4 + 1) // 2
+    r = {"config": 4, "op": "conv_chain (16 service curves, 15 products)", "dtype": "int32", "batch": B4, "n": N4,
+         "gpu_ms": round(med, 3), "gpu_ms_min": round(mn, 3), "pair_ops": po_k,
+         "gpair_ops_per_s": round(po_k / med / 1e6, 1),
+         "pct_valu_peak_2ops": round(100 * 2 * po_k / (med * 1e-3) / peak_ops, 1)}
+    if with_cpu:
+        few = np.ascontiguousarray(c["beta_l"][:, :4])
+        sec = cpu_s(lambda: oracle.conv_chain(few))
+        r.update({"oracle_s": sec, "oracle_rows": 4, "oracle_threads": threads,
+                  "oracle_gpair_ops_per_s": round(15 * 4 * N4 * (N4 + 1) / 2 / sec / 1e9, 2),
+                  "oracle_note": "first 4 of 256 chains"})
+    rows.append(r)
     hbm_row(4, "pseudo_inverse lower (gamma_u at beta'_l)", lambda: rtc.rtc_pseudo_inverse(gam, blo, 0, out=evl),
             B4 * N4 * 12, "int32", B4, N4)
     # config 5
