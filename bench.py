@@ -162,6 +162,37 @@ def per_config_table(seed, peak_ops, with_cpu):
     product_rows(3, c["f"].astype(np.int32), c["g"].astype(np.int32), 8, "int32", duals=True)
     product_rows(3, c["f"][:16] + (1 << 40), c["g"][:16] - (1 << 45), 4, "int64 storage with large offsets (re-based, int32 arithmetic)")
     product_rows(3, c["f"][:16] * 4096, c["g"][:16] * 4096, 4, "int64 arithmetic (value range beyond 2^30)")
+    # rows of exploitable convexity at the headline shape: token buckets (concave) and rate-latency
+    # curves (convex); the library detects them on the device and evaluates 2 or 2*log2(n) candidates
+    # per output instead of all of them, so the rate below is an equivalent, not executed work
+    rs = np.random.default_rng(seed)
+    tb = np.stack([wl.token_bucket(65536, int(rs.integers(100, 5000)), int(rs.integers(1, 40)), np.int32, at_zero=False)
+                   for _ in range(64)])
+    tb2 = np.stack([wl.token_bucket(65536, int(rs.integers(100, 5000)), int(rs.integers(1, 40)), np.int32, at_zero=False)
+                    for _ in range(64)])
+    rl = np.stack([wl.rate_latency(65536, int(rs.integers(2, 60)), int(rs.integers(0, 3000)), np.int32) for _ in range(64)])
+    rl2 = np.stack([wl.rate_latency(65536, int(rs.integers(2, 60)), int(rs.integers(0, 3000)), np.int32) for _ in range(64)])
+    for label, fn, ofn, f_h, g_h, how in (
+            ("minplus_conv token-bucket x token-bucket", rtc.rtc_minplus_conv, "minplus_conv", tb, tb2, "ends"),
+            ("minplus_conv rate-latency x rate-latency", rtc.rtc_minplus_conv, "minplus_conv", rl, rl2, "bisection"),
+            ("maxplus_deconv token-bucket / rate-latency", rtc.rtc_maxplus_deconv, "maxplus_deconv", tb, rl, "bisection")):
+        f, g = dev(f_h), dev(g_h)
+        out = torch.empty_like(f)
+        ws = torch.empty(rtc.rtc_workspace_bytes(rtc.RTC_OP_CONV, 64, 65536, torch.int32), dtype=torch.uint8, device="cuda")
+        med, mn = gpu_ms(lambda: fn(f, g, out=out, ws=ws))
+        po = 64 * 65536 * 65537 // 2
+        r = {"config": "structured", "op": label, "dtype": "int32", "batch": 64, "n": 65536, "gpu_ms": round(med, 4),
+             "gpu_ms_min": round(mn, 4), "pair_ops": po, "equivalent_gpair_ops_per_s": round(po / med / 1e6, 1),
+             "path": f"structured_kernel ({how}); pair_ops is the definition's count, not executed work"}
+        if with_cpu:
+            sec = cpu_s(lambda: getattr(oracle, ofn)(f_h[:8], g_h[:8]))
+            r.update({"oracle_s": sec, "oracle_rows": 8, "oracle_threads": threads,
+                      "oracle_gpair_ops_per_s": round(8 * 65536 * 65537 / 2 / sec / 1e9, 2)})
+            idx = np.array([0, 1, 777, 40000, 65535])
+            got = out[:8].cpu().numpy()
+            assert np.array_equal(got[:, idx], np.stack([oracle.product_at(f_h[b], g_h[b], idx, "deconv" in ofn)
+                                                         for b in range(8)])), label
+        rows.append(r)
     # config 4: one component of all 256 chains, then the whole 16-component chain
     c = wl.config4(seed, 256, 16, 16384)
     gam, abar = dev(c["gamma_u"]), dev(c["alpha_bar_u"])

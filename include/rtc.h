@@ -193,6 +193,23 @@ int rtc_max_hdev(const void* alpha, const void* beta, int32_t* out, int64_t batc
 int rtc_max_vdev(const void* alpha, const void* beta, void* out, int64_t batch, int64_t n,
                  rtc_dtype dt, void* hip_stream);
 
+/* Which kernel family the four products give a row pair (integer dtypes; fp64 rows are always
+ * RTC_STRUCTURE_GENERAL).  With c(j) the candidates of one output (f[j] + g[t-j] for the
+ * convolutions, f[t+j] - g[j] for the deconvolutions), a pair of convex / concave rows makes c a
+ * convex or concave sequence, and the reduction needs no full scan:
+ *   RTC_STRUCTURE_ENDS    min over a concave / max over a convex sequence: one of its two ends
+ *   RTC_STRUCTURE_BISECT  min over a convex / max over a concave sequence: bisection on the sign
+ *                         of c(j+1) - c(j)
+ * (convolutions: f and g both convex, or both concave; deconvolutions: f convex and g concave,
+ * or f concave and g convex; linear rows count as both).  The products detect this on the device
+ * and compute such pairs in O(n) or O(n log n) candidates with the same result bit for bit, when
+ * a workspace is given and the problem is above the rtc_set_packed_min_work threshold.
+ * rtc_product_structure reports the classification: codes[b] for row pair b, op = RTC_OP_CONV,
+ * _DECONV, _MAXCONV or _MINDECONV.  codes: device, [batch] int32. */
+enum { RTC_STRUCTURE_GENERAL = 1, RTC_STRUCTURE_BISECT = 2, RTC_STRUCTURE_ENDS = 3 };
+int rtc_product_structure(int op, const void* f, const void* g, int32_t* codes, int64_t batch, int64_t n,
+                          int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* hip_stream);
+
 /* Planner knob: the packed 16-bit path of the int32 / narrowed-int64 products is used when a
  * workspace is present and batch * n^2 >= this value (default 2^30; smaller problems are
  * launch-bound and take the 32-bit kernel alone).  0 uses it for every size.  Results do not

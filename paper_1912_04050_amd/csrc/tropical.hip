@@ -48,6 +48,7 @@
 #include "tropical_generic.h"
 #include "tropical_packed.h"
 #include "tropical_prepare.h"
+#include "tropical_structured.h"
 
 namespace rtc {
 
@@ -162,7 +163,7 @@ int run_product(const T* a, int64_t stride_a, const T* b, int64_t stride_b, OutT
 // Layout of the packed path's arrays inside the workspace.
 struct PackLayout {
   int64_t npad, nchunk, nsub, nblk;
-  size_t off_apk, off_apk_s, off_bd, off_ab, off_ar, off_ab_s, off_ar_s, off_bmn, off_bmx, off_rho, off_ok, bytes;
+  size_t off_apk, off_apk_s, off_bd, off_ab, off_ar, off_ab_s, off_ar_s, off_bmn, off_bmx, off_rho, off_ok, off_sel, bytes;
 };
 
 PackLayout pack_layout(int64_t batch, int64_t n) {
@@ -184,6 +185,7 @@ PackLayout pack_layout(int64_t batch, int64_t n) {
   L.off_bmx = take((size_t)batch * L.nblk);
   L.off_rho = take((size_t)batch);
   L.off_ok = take((size_t)batch);
+  L.off_sel = take((size_t)batch);   // per-row selector of int32 products (int64 products keep their own)
   L.bytes = o;
   return L;
 }
@@ -271,21 +273,27 @@ int run_typed(const void* f, const void* g, void* out, int64_t batch, int64_t n,
     // tiny problems are launch-bound: the extra kernels of the packed path would only cost
     if (ws != nullptr && ws_bytes >= L.bytes && packed_worthwhile(batch, n)) {
       char* wsp = static_cast<char*>(ws);
+      int32_t* sel = reinterpret_cast<int32_t*>(wsp + L.off_sel);
       hipLaunchKernelGGL(probe_kernel<int32_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,
                          static_cast<const int32_t*>(f), stride_f, static_cast<const int32_t*>(g), stride_g,
-                         (int)n, op_sub(OP), reinterpret_cast<int32_t*>(wsp + L.off_ok),
-                         reinterpret_cast<int32_t*>(wsp + L.off_rho), dev_flags);
+                         (int)n, OP, reinterpret_cast<int32_t*>(wsp + L.off_ok),
+                         reinterpret_cast<int32_t*>(wsp + L.off_rho), sel, dev_flags);
       launch_fill<int32_t, OP>(static_cast<int32_t*>(out), batch * n, stream);
-      return run_packed<int32_t, OP>(static_cast<const int32_t*>(f), stride_f,
-                                         static_cast<const int32_t*>(g), stride_g, static_cast<int32_t*>(out),
-                                         static_cast<const int32_t*>(cap), nullptr, nullptr, batch, n, wsp, L,
-                                         stream);
+      // general rows (selector 1): packed + 32-bit items; rows of exploitable convexity: structured_kernel
+      const int rc = run_packed<int32_t, OP>(static_cast<const int32_t*>(f), stride_f,
+                                             static_cast<const int32_t*>(g), stride_g, static_cast<int32_t*>(out),
+                                             static_cast<const int32_t*>(cap), sel, nullptr, batch, n, wsp, L,
+                                             stream);
+      if (rc != RTC_OK) return rc;
+      return launch_structured<int32_t, OP>(static_cast<const int32_t*>(f), stride_f,
+                                            static_cast<const int32_t*>(g), stride_g, static_cast<int32_t*>(out),
+                                            static_cast<const int32_t*>(cap), sel, batch, n, stream);
     }
   }
   if (dev_flags != nullptr && std::numeric_limits<T>::is_integer) {
     hipLaunchKernelGGL(probe_kernel<T>, dim3((uint32_t)batch), dim3(1024), 0, stream,
                        static_cast<const T*>(f), stride_f, static_cast<const T*>(g), stride_g, (int)n,
-                       op_sub(OP), (int32_t*)nullptr, (int32_t*)nullptr, dev_flags);
+                       OP, (int32_t*)nullptr, (int32_t*)nullptr, (int32_t*)nullptr, dev_flags);
   }
   return run_product<T, T, OP>(a, sa, b, sb, static_cast<T*>(out), static_cast<const T*>(cap),
                                    nullptr, 0, batch, n, stream, false, false, nullptr);
@@ -311,7 +319,8 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
   const PackLayout L = pack_layout(batch, n);
   hipLaunchKernelGGL(probe_narrow_kernel, dim3((uint32_t)batch), dim3(1024), 0, stream,
                      static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g,
-                     (int)n, op_sub(OP), f32, g32, ok, base, reinterpret_cast<int32_t*>(wsp + L.off_ok),
+                     (int)n, OP, packed_worthwhile(batch, n), f32, g32, ok, base,
+                     reinterpret_cast<int32_t*>(wsp + L.off_ok),
                      reinterpret_cast<int32_t*>(wsp + L.off_rho), dev_flags);
   // Several kernels see every row; the selector makes each row run in exactly one family.
   // The output is filled once with the identity, before all of them.
@@ -328,10 +337,15 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
   if (rc != RTC_OK) return rc;
   const int64_t* a = static_cast<const int64_t*>(op_sub(OP) ? g : f);
   const int64_t* b = static_cast<const int64_t*>(op_sub(OP) ? f : g);
-  return run_product<int64_t, int64_t, OP>(a, op_sub(OP) ? stride_g : stride_f, b,
-                                               op_sub(OP) ? stride_f : stride_g, static_cast<int64_t*>(out),
-                                               static_cast<const int64_t*>(cap), ok, 0, batch, n, stream,
-                                               true, true, nullptr);
+  rc = run_product<int64_t, int64_t, OP>(a, op_sub(OP) ? stride_g : stride_f, b,
+                                         op_sub(OP) ? stride_f : stride_g, static_cast<int64_t*>(out),
+                                         static_cast<const int64_t*>(cap), ok, 0, batch, n, stream, true, true,
+                                         nullptr);
+  if (rc != RTC_OK || !packed_worthwhile(batch, n)) return rc;
+  // rows of exploitable convexity (selector 2 / 3), on the caller's own 64-bit rows
+  return launch_structured<int64_t, OP>(static_cast<const int64_t*>(f), stride_f,
+                                        static_cast<const int64_t*>(g), stride_g, static_cast<int64_t*>(out),
+                                        static_cast<const int64_t*>(cap), ok, batch, n, stream);
 }
 
 }  // namespace
@@ -340,6 +354,26 @@ size_t tropical_workspace_bytes(int64_t batch, int64_t n, int dt) {
   if (dt == RTC_I64) return narrow_bytes(batch, n) + pack_layout(batch, n).bytes;
   if (dt == RTC_I32) return pack_layout(batch, n).bytes;
   return 0;
+}
+
+int launch_structure_probe(int op, const void* f, const void* g, int32_t* codes, int64_t batch, int64_t n,
+                           int64_t stride_f, int64_t stride_g, int dt, hipStream_t stream) {
+  static_assert(kSelSearch == RTC_STRUCTURE_BISECT && kSelEnds == RTC_STRUCTURE_ENDS, "selector codes are public");
+  const int code_op = op == RTC_OP_CONV ? 0 : op == RTC_OP_DECONV ? 1 : op == RTC_OP_MAXCONV ? 2 : 3;
+  if (dt == RTC_I32) {
+    hipLaunchKernelGGL(probe_kernel<int32_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,
+                       static_cast<const int32_t*>(f), stride_f, static_cast<const int32_t*>(g), stride_g, (int)n,
+                       code_op, (int32_t*)nullptr, (int32_t*)nullptr, codes, (int32_t*)nullptr);
+  } else if (dt == RTC_I64) {
+    hipLaunchKernelGGL(probe_kernel<int64_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,
+                       static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g, (int)n,
+                       code_op, (int32_t*)nullptr, (int32_t*)nullptr, codes, (int32_t*)nullptr);
+  } else {
+    const int blocks = (int)((batch + 255) / 256 < 65535 ? (batch + 255) / 256 : 65535);
+    hipLaunchKernelGGL(fill_kernel<int32_t>, dim3(blocks), dim3(256), 0, stream, codes, batch,
+                       (int32_t)RTC_STRUCTURE_GENERAL);
+  }
+  return hip_ok();
 }
 
 int launch_tropical(int op, const void* f, const void* g, void* out, int64_t batch, int64_t n,

@@ -15,42 +15,90 @@ __global__ __launch_bounds__(256) void fill_kernel(T* __restrict__ dst, int64_t 
   for (; i < count; i += step) dst[i] = value;
 }
 
+// Shape bits of a row pair: bit 0 f convex (second differences >= 0), bit 1 f concave, bit 2 g
+// convex, bit 3 g concave.  second_diff_bits() looks at sample i of one row (1 <= i <= n-2) and
+// returns the bits that survive; differences are taken in int64 (int32 rows: always exact; int64
+// rows: exact when the row's range is below 2^62, which the caller checks afterwards).
+template <typename T>
+__device__ __forceinline__ int second_diff_bits(const T* row, int i) {
+  const int64_t a = (int64_t)((uint64_t)(int64_t)row[i + 1] - (uint64_t)(int64_t)row[i]);
+  const int64_t b = (int64_t)((uint64_t)(int64_t)row[i] - (uint64_t)(int64_t)row[i - 1]);
+  return (a >= b ? 1 : 0) | (a <= b ? 2 : 0);
+}
+
+// Selector codes shared by the product kernels: 0 = 64-bit kernel, 1 = 32-bit / packed kernels,
+// kSelSearch / kSelEnds = the row pair is done by structured_kernel.
+constexpr int kSelSearch = 2;
+constexpr int kSelEnds = 3;
+
+// The candidates of one output, c(j) = f[j] + g[t-j] (convolutions) or f[t+j] - g[j]
+// (deconvolutions), form a convex sequence in j when (f, g) are (convex, convex) resp.
+// (convex, concave), a concave one when (concave, concave) resp. (concave, convex).  A min over a
+// concave sequence / max over a convex one sits at an end of the range; a min over a convex / max
+// over a concave one is found by bisection on the sign of c(j+1) - c(j).  Returns the selector
+// code for the row pair, or `general` when it has no such structure.
+__device__ __forceinline__ int structure_code(int op, int bits, int general) {
+  const bool fcvx = bits & 1, fccv = bits & 2, gcvx = bits & 4, gccv = bits & 8;
+  const bool cvx = op_sub(op) ? (fcvx && gccv) : (fcvx && gcvx);
+  const bool ccv = op_sub(op) ? (fccv && gcvx) : (fccv && gccv);
+  if (op_max(op) ? cvx : ccv) return kSelEnds;
+  if (op_max(op) ? ccv : cvx) return kSelSearch;
+  return general;
+}
+
 // Range probe of one row pair.  Finds min/max of both rows, raises the overflow flag when
 // the bounds do not prove that every candidate fits and (optionally) decides eligibility for
-// the packed path and the slope to remove.
+// the packed path and the slope to remove, and (optionally, integers) whether the pair's
+// convexity lets structured_kernel do it (selector code in sel[row], else 1).
 template <typename T>
 __global__ __launch_bounds__(1024) void probe_kernel(const T* __restrict__ f, int64_t stride_f,
                                                      const T* __restrict__ g, int64_t stride_g, int n,
-                                                     bool deconv, int32_t* __restrict__ pack_ok,
-                                                     int32_t* __restrict__ rho,
+                                                     int op, int32_t* __restrict__ pack_ok,
+                                                     int32_t* __restrict__ rho, int32_t* __restrict__ sel,
                                                      int32_t* __restrict__ dev_flags) {
   __shared__ T red[4][16];
+  __shared__ int s_bits[16];
+  const bool deconv = op_sub(op);
   const int row = blockIdx.x;
   const T* fr = f + (int64_t)row * stride_f;
   const T* gr = g + (int64_t)row * stride_g;
   T fmin = Lim<T>::hi(), fmax = Lim<T>::lo(), gmin = Lim<T>::hi(), gmax = Lim<T>::lo();
+  int bits = 15;
   for (int i = threadIdx.x; i < n; i += blockDim.x) {
     const T fv = fr[i], gv = gr[i];
     fmin = sel_min(fmin, fv); fmax = sel_max(fmax, fv);
     gmin = sel_min(gmin, gv); gmax = sel_max(gmax, gv);
+    if constexpr (std::numeric_limits<T>::is_integer) {
+      if (sel != nullptr && bits != 0 && i >= 1 && i <= n - 2)
+        bits &= second_diff_bits(fr, i) | (second_diff_bits(gr, i) << 2);
+    }
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) {
     fmin = sel_min(fmin, __shfl_xor(fmin, off)); fmax = sel_max(fmax, __shfl_xor(fmax, off));
     gmin = sel_min(gmin, __shfl_xor(gmin, off)); gmax = sel_max(gmax, __shfl_xor(gmax, off));
+    bits &= __shfl_xor(bits, off);
   }
   const int wave = threadIdx.x >> 6;
-  if ((threadIdx.x & 63) == 0) { red[0][wave] = fmin; red[1][wave] = fmax; red[2][wave] = gmin; red[3][wave] = gmax; }
+  if ((threadIdx.x & 63) == 0) {
+    red[0][wave] = fmin; red[1][wave] = fmax; red[2][wave] = gmin; red[3][wave] = gmax;
+    s_bits[wave] = bits;
+  }
   __syncthreads();
   if (threadIdx.x == 0) {
     const int nw = (blockDim.x + 63) >> 6;
     for (int w = 1; w < nw; ++w) {
       fmin = sel_min(fmin, red[0][w]); fmax = sel_max(fmax, red[1][w]);
       gmin = sel_min(gmin, red[2][w]); gmax = sel_max(gmax, red[3][w]);
+      bits &= s_bits[w];
     }
     if constexpr (!std::numeric_limits<T>::is_integer) {
       (void)dev_flags;
     } else {
+      // int64 rows: the second differences were exact only if both ranges are below 2^62
+      if (sizeof(T) == 8 && (((uint64_t)fmax - (uint64_t)fmin) >> 62 || ((uint64_t)gmax - (uint64_t)gmin) >> 62)) bits = 0;
+      const int code = sel != nullptr ? structure_code(op, bits, 1) : 1;
+      if (sel != nullptr) sel[row] = code;
       T dummy;
       const bool bad = deconv ? (__builtin_sub_overflow(fmax, gmin, &dummy) || __builtin_sub_overflow(fmin, gmax, &dummy))
                               : (__builtin_add_overflow(fmax, gmax, &dummy) || __builtin_add_overflow(fmin, gmin, &dummy));
@@ -73,6 +121,7 @@ __global__ __launch_bounds__(1024) void probe_kernel(const T* __restrict__ f, in
           const int64_t diff = ru > r ? ru - r : r - ru;
           if (diff * kPkSub > 50000) pack_ok[row] = 0;
         }
+        if (code != 1) pack_ok[row] = 0;   // structured_kernel does the row
         rho[row] = r;
       }
     }
@@ -83,10 +132,12 @@ __global__ __launch_bounds__(1024) void probe_kernel(const T* __restrict__ f, in
 // is re-based to its minima and copied as int32: every candidate of the re-based rows fits
 // 32 bits, so the 32-bit kernels compute it exactly and add `out_base` (f_min + g_min, or
 // f_min - g_min for the deconvolutions) back on store.  Rows with a wider range keep the
-// 64-bit kernel.  Also: overflow flag, packed-path eligibility and slope, as in probe_kernel.
+// 64-bit kernel.  Also: overflow flag, packed-path eligibility and slope, and (when `structure`
+// is set) the convexity test, as in probe_kernel; narrow_ok[row] receives the selector code.
 __global__ __launch_bounds__(1024) void probe_narrow_kernel(const int64_t* __restrict__ f, int64_t stride_f,
                                                             const int64_t* __restrict__ g, int64_t stride_g,
-                                                            int n, bool deconv, int32_t* __restrict__ f32,
+                                                            int n, int op, bool structure,
+                                                            int32_t* __restrict__ f32,
                                                             int32_t* __restrict__ g32,
                                                             int32_t* __restrict__ narrow_ok,
                                                             int64_t* __restrict__ out_base,
@@ -96,40 +147,53 @@ __global__ __launch_bounds__(1024) void probe_narrow_kernel(const int64_t* __res
   __shared__ int64_t red[4][16];
   __shared__ int64_t s_base[2];
   __shared__ int s_narrow;
+  __shared__ int s_bits[16];
+  const bool deconv = op_sub(op);
   const int row = blockIdx.x;
   const int64_t* fr = f + (int64_t)row * stride_f;
   const int64_t* gr = g + (int64_t)row * stride_g;
   int64_t fmin = INT64_MAX, fmax = INT64_MIN, gmin = INT64_MAX, gmax = INT64_MIN;
+  int bits = structure ? 15 : 0;
   for (int i = threadIdx.x; i < n; i += blockDim.x) {
     const int64_t fv = fr[i], gv = gr[i];
     fmin = sel_min(fmin, fv); fmax = sel_max(fmax, fv);
     gmin = sel_min(gmin, gv); gmax = sel_max(gmax, gv);
+    if (bits != 0 && i >= 1 && i <= n - 2) bits &= second_diff_bits(fr, i) | (second_diff_bits(gr, i) << 2);
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) {
     fmin = sel_min(fmin, __shfl_xor(fmin, off)); fmax = sel_max(fmax, __shfl_xor(fmax, off));
     gmin = sel_min(gmin, __shfl_xor(gmin, off)); gmax = sel_max(gmax, __shfl_xor(gmax, off));
+    bits &= __shfl_xor(bits, off);
   }
   const int wave = threadIdx.x >> 6;
-  if ((threadIdx.x & 63) == 0) { red[0][wave] = fmin; red[1][wave] = fmax; red[2][wave] = gmin; red[3][wave] = gmax; }
+  if ((threadIdx.x & 63) == 0) {
+    red[0][wave] = fmin; red[1][wave] = fmax; red[2][wave] = gmin; red[3][wave] = gmax;
+    s_bits[wave] = bits;
+  }
   __syncthreads();
   if (threadIdx.x == 0) {
     const int nw = (blockDim.x + 63) >> 6;
     for (int w = 1; w < nw; ++w) {
       fmin = sel_min(fmin, red[0][w]); fmax = sel_max(fmax, red[1][w]);
       gmin = sel_min(gmin, red[2][w]); gmax = sel_max(gmax, red[3][w]);
+      bits &= s_bits[w];
     }
     int64_t dummy;
     const bool bad = deconv ? (__builtin_sub_overflow(fmax, gmin, &dummy) || __builtin_sub_overflow(fmin, gmax, &dummy))
                             : (__builtin_add_overflow(fmax, gmax, &dummy) || __builtin_add_overflow(fmin, gmin, &dummy));
     if (bad && dev_flags) atomicOr(dev_flags, RTC_FLAG_OVERFLOW);
     const uint64_t frange = (uint64_t)fmax - (uint64_t)fmin, grange = (uint64_t)gmax - (uint64_t)gmin;
+    // the second differences were exact only if both ranges are below 2^62
+    if ((frange >> 62) != 0 || (grange >> 62) != 0) bits = 0;
     const bool narrow = frange < (1ull << 30) && grange < (1ull << 30);
-    narrow_ok[row] = narrow ? 1 : 0;
+    const int code = structure_code(op, bits, narrow ? 1 : 0);
+    const bool general = code < kSelSearch;
+    narrow_ok[row] = code;
     out_base[row] = narrow ? (deconv ? wrap_sub(fmin, gmin) : wrap_add(fmin, gmin)) : 0;
-    s_base[0] = fmin; s_base[1] = gmin; s_narrow = narrow ? 1 : 0;
+    s_base[0] = fmin; s_base[1] = gmin; s_narrow = narrow && general ? 1 : 0;
     // re-based values lie in [0, 2^29): the detrended rows stay inside int32
-    const bool ok = frange < (1ull << 29) && grange < (1ull << 29);
+    const bool ok = general && frange < (1ull << 29) && grange < (1ull << 29);
     pack_ok[row] = ok ? 1 : 0;
     int32_t r = 0;
     if (ok && n > 1) {

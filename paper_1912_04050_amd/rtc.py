@@ -138,6 +138,25 @@ def rtc_set_packed_min_work(batch_times_n_squared: float):
     _check(_lib.rtc_set_packed_min_work(float(batch_times_n_squared)))
 
 
+_lib.rtc_product_structure.argtypes = [_int, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _int, _vp]
+_lib.rtc_product_structure.restype = _int
+RTC_STRUCTURE_GENERAL, RTC_STRUCTURE_BISECT, RTC_STRUCTURE_ENDS = 1, 2, 3
+
+
+def rtc_product_structure(op: int, f, g, out=None):
+    """Per row pair: which kernel family the product `op` (RTC_OP_CONV, ...) gives it."""
+    f, bf, n, _ = _rows(f)
+    g, bg, ng, _ = _rows(g)
+    if ng != n or f.dtype != g.dtype or (bf != bg and 1 not in (bf, bg)):
+        raise ValueError("operands must have the same length and dtype, batch equal or 1")
+    batch = max(bf, bg)
+    if out is None:
+        out = torch.empty(batch, dtype=torch.int32, device=f.device)
+    _check(_lib.rtc_product_structure(op, _ptr(f), _ptr(g), _ptr(out), batch, n, _row_stride(f, bf, batch, n),
+                                      _row_stride(g, bg, batch, n), _DT[f.dtype], _stream()))
+    return out
+
+
 _lib.rtc_set_packed_small_n.argtypes = [_i64]
 _lib.rtc_set_packed_small_n.restype = _int
 

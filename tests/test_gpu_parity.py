@@ -417,6 +417,125 @@ def test_dual_products_signed_and_mixed_chunks(rtc):
     check_duals(rtc, f64, g.astype(np.int64), "dual int64 wide row")
 
 
+def _shaped_rows(rng, n, kind):
+    """One row of a given shape: its second differences are >= 0 (convex), <= 0 (concave), 0
+    (linear), of both signs (general), or of one sign except at a single sample (spoiled)."""
+    inc = rng.integers(-40, 400, max(n - 1, 1))
+    if kind in ("convex", "convex-spoiled-first", "convex-spoiled-last"):
+        inc = np.sort(inc)
+    elif kind in ("concave", "concave-spoiled-mid"):
+        inc = np.sort(inc)[::-1]
+    elif kind == "linear":
+        inc = np.full(max(n - 1, 1), int(rng.integers(-5, 60)))
+    elif kind == "token-bucket":
+        inc = np.concatenate([[int(rng.integers(50, 900))], np.full(max(n - 2, 0), int(rng.integers(1, 30)))])[:max(n - 1, 1)]
+    elif kind == "rate-latency":
+        lat = int(rng.integers(0, max(n, 2)))
+        inc = np.where(np.arange(max(n - 1, 1)) < lat, 0, int(rng.integers(1, 50)))
+    v = np.concatenate([[int(rng.integers(-100, 100))], inc])[:n].cumsum()
+    if n >= 4:
+        if kind == "convex-spoiled-first":
+            v[1] += 1 + (v[2] - 2 * v[1] + v[0]) // 2 + 1      # second difference at 1 turns negative
+        if kind == "convex-spoiled-last":
+            v[n - 1] -= (v[n - 1] - 2 * v[n - 2] + v[n - 3]) + 1
+        if kind == "concave-spoiled-mid":
+            v[n // 2] -= 1 - (v[n // 2 + 1] - 2 * v[n // 2] + v[n // 2 - 1]) // 2 + 1
+    return v
+
+
+SHAPES = ["convex", "concave", "linear", "token-bucket", "rate-latency", "general", "convex-spoiled-first",
+          "convex-spoiled-last", "concave-spoiled-mid"]
+
+
+@pytest.mark.parametrize("dtype", [np.int32, np.int64])
+def test_rows_of_exploitable_convexity(rtc, dtype):
+    """Every pairing of row shapes in one batch: pairs whose candidates form a convex or concave
+    sequence take the structured kernel (ends of the range, or bisection), all others and the
+    rows spoiled at one sample the general kernels; all four products must equal the oracle."""
+    rng = np.random.default_rng(41)
+    for n in (1, 2, 3, 4, 5, 257, 2500):
+        fs, gs = [], []
+        for kf in SHAPES:
+            for kg in SHAPES:
+                fs.append(_shaped_rows(rng, n, kf))
+                gs.append(_shaped_rows(rng, n, kg))
+        f, g = np.stack(fs).astype(dtype), np.stack(gs).astype(dtype)
+        check_products(rtc, f, g, f"shaped n={n}")
+        check_duals(rtc, f, g, f"shaped duals n={n}")
+        if dtype == np.int64:
+            scale = np.where(np.arange(len(fs)) % 3 == 0, 1 << 33, 1)[:, None]   # every third pair beyond 32 bits
+            check_products(rtc, f * scale, g * scale, f"shaped wide n={n}")
+            check_duals(rtc, f * scale, g * scale, f"shaped wide duals n={n}")
+
+
+def _structure_by_definition(f, g, op):
+    """The documented rule, from second differences in exact Python integers."""
+    def shape(v):
+        d2 = [int(v[i + 1]) - 2 * int(v[i]) + int(v[i - 1]) for i in range(1, len(v) - 1)]
+        return all(x >= 0 for x in d2), all(x <= 0 for x in d2)
+    (fcvx, fccv), (gcvx, gccv) = shape(f), shape(g)
+    deconv, is_max = op in ("deconv", "mindeconv"), op in ("deconv", "maxconv")
+    cvx = (fcvx and gccv) if deconv else (fcvx and gcvx)
+    ccv = (fccv and gcvx) if deconv else (fccv and gccv)
+    if (cvx if is_max else ccv):
+        return 3
+    if (ccv if is_max else cvx):
+        return 2
+    return 1
+
+
+@pytest.mark.parametrize("dtype", [np.int32, np.int64, np.float64])
+def test_product_structure_classification(rtc, dtype):
+    rng = np.random.default_rng(44)
+    ops = {"conv": rtc.RTC_OP_CONV, "deconv": rtc.RTC_OP_DECONV, "maxconv": rtc.RTC_OP_MAXCONV,
+           "mindeconv": rtc.RTC_OP_MINDECONV}
+    for n in (1, 2, 3, 4, 300, 2100):
+        fs, gs = [], []
+        for kf in SHAPES:
+            for kg in SHAPES:
+                fs.append(_shaped_rows(rng, n, kf))
+                gs.append(_shaped_rows(rng, n, kg))
+        f, g = np.stack(fs).astype(dtype), np.stack(gs).astype(dtype)
+        if dtype == np.int64 and n >= 3:
+            f[0] = _shaped_rows(rng, n, "convex") * (1 << 40)
+            f[1, :] = 0
+            f[1, -1] = 1 << 62                      # convex, but its range leaves the exact domain of the test
+            g[1] = np.arange(n)
+        for name, op in ops.items():
+            got = host(rtc.rtc_product_structure(op, dev(f), dev(g)))
+            if dtype == np.float64:
+                assert np.all(got == 1), name
+                continue
+            want = np.array([_structure_by_definition(f[b], g[b], name) for b in range(len(fs))])
+            if dtype == np.int64 and n >= 3:
+                want[1] = 1
+            assert np.array_equal(got, want), (name, n, np.nonzero(got != want))
+
+
+def test_structured_rows_inside_gpc_and_closure(rtc):
+    """Token-bucket arrivals through rate-latency service (the textbook closed-form case) next to
+    general rows, through the component step, the closure and a chain."""
+    n = 1800
+    rng = np.random.default_rng(42)
+    alpha = np.stack([wl.token_bucket(n, 300, 7, np.int64, at_zero=False), wl.random_monotone(43, 1, 1, n, np.int64)[0],
+                      wl.token_bucket(n, 40, 2, np.int64, at_zero=False)]).astype(np.int32)
+    beta_l = np.stack([wl.rate_latency(n, 9, 120), wl.rate_latency(n, 11, 15), wl.random_monotone(43, 2, 1, n, np.int64)[0]]).astype(np.int32)
+    beta_u = beta_l + np.stack([wl.token_bucket(n, 500, 3, np.int64), wl.token_bucket(n, 10, 1, np.int64),
+                                wl.token_bucket(n, 0, 0, np.int64)]).astype(np.int32)
+    say("gpc on structured rows")
+    au, bl = rtc.rtc_gpc_step(dev(alpha), dev(beta_u), dev(beta_l))
+    want_au, want_bl = oracle.gpc_step(alpha, beta_u, beta_l)
+    assert np.array_equal(host(au), want_au) and np.array_equal(host(bl), want_bl)
+    say("closure of concave / convex rows")
+    rows = np.stack([alpha[0, :600], beta_l[0, :600], alpha[1, :600]])
+    assert np.array_equal(host(rtc.rtc_subadditive_closure(dev(rows))), oracle.closure(rows)[0])
+    assert np.array_equal(host(rtc.rtc_superadditive_closure(dev(rows))), oracle.closure(rows, True)[0])
+    say("chain of rate-latency curves")
+    curves = np.stack([np.stack([wl.rate_latency(n, int(rng.integers(2, 20)), int(rng.integers(0, 300))) for _ in range(3)])
+                       for _ in range(5)]).astype(np.int32)
+    assert np.array_equal(host(rtc.rtc_conv_chain(dev(curves))), oracle.conv_chain(curves))
+
+
 def test_dual_products_zero_curve_scans(rtc):
     """With g = 0 the duals are the running maximum and the suffix minimum."""
     rng = np.random.default_rng(33)

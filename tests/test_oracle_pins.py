@@ -259,6 +259,35 @@ def test_conv_of_concave_curves_through_origin_is_pointwise_min():
     assert np.array_equal(oracle.minplus_conv(f, g)[0], np.minimum(f, g))
 
 
+def test_products_of_convex_and_concave_rows_closed_forms():
+    """Candidates of one output form a concave sequence for (concave, concave) under the
+    convolutions and (concave, convex) under the deconvolutions, a convex one for (convex, convex)
+    resp. (convex, concave): a min over a concave / max over a convex sequence is the better of
+    its two ends, whatever the rows' values at the origin."""
+    rng = np.random.default_rng(27)
+    n = 257
+    inc = lambda: rng.integers(-30, 60, n - 1)
+    cvx = lambda: np.concatenate([[int(rng.integers(-9, 9))], np.sort(inc())]).cumsum().astype(np.int64)
+    ccv = lambda: np.concatenate([[int(rng.integers(-9, 9))], np.sort(inc())[::-1]]).cumsum().astype(np.int64)
+    t = np.arange(n)
+    f, g = ccv(), ccv()
+    assert np.array_equal(oracle.minplus_conv(f, g)[0], np.minimum(f[0] + g, f + g[0]))
+    f, g = cvx(), cvx()
+    assert np.array_equal(oracle.maxplus_conv(f, g)[0], np.maximum(f[0] + g, f + g[0]))
+    f, g = cvx(), ccv()
+    assert np.array_equal(oracle.maxplus_deconv(f, g)[0], np.maximum(f - g[0], f[n - 1] - g[n - 1 - t]))
+    f, g = ccv(), cvx()
+    assert np.array_equal(oracle.minplus_deconv(f, g)[0], np.minimum(f - g[0], f[n - 1] - g[n - 1 - t]))
+    # the other pairings: the optimum is where the sequence's increments change sign
+    f, g = ccv(), cvx()
+    want = []
+    for tt in range(n):
+        c = f[tt:] - g[:n - tt]
+        up = np.nonzero(np.diff(c) <= 0)[0]
+        want.append(c[up[0]] if len(up) else c[-1])
+    assert np.array_equal(oracle.maxplus_deconv(f, g)[0], np.array(want))
+
+
 # ---------------------------------------------------------------------------
 # pseudo-inverse
 # ---------------------------------------------------------------------------
