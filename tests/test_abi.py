@@ -20,16 +20,20 @@ def lib():
 
 
 def declared_functions():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(rtc_[a-z_]+)\s*\(", text)))
+    names = set()
+    for header in ("rtc.h", "bnn.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b((?:rtc|bnn)_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert {"rtc_minplus_conv", "rtc_maxplus_deconv", "rtc_pseudo_inverse", "rtc_compose",
             "rtc_gpc_step", "rtc_max_hdev", "rtc_max_vdev", "rtc_workspace_bytes",
-            "rtc_strerror"} <= set(names)
+            "rtc_strerror", "bnn_pack_channels", "bnn_weight_words", "bnn_pack_weights", "bnn_binary_conv2d",
+            "bnn_strerror"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
 
@@ -95,3 +99,30 @@ def test_other_entry_points_reject_bad_arguments(lib):
     lib.rtc_set_packed_small_n.argtypes = [ctypes.c_int64]
     assert lib.rtc_set_packed_small_n(-1) == -2
     assert lib.rtc_set_packed_small_n(4096) == 0
+
+
+def test_bnn_entry_points_reject_bad_arguments(lib):
+    p = ctypes.c_void_p(0x1000)
+    i64 = ctypes.c_int64
+    lib.bnn_pack_channels.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, i64, i64, ctypes.c_void_p]
+    assert lib.bnn_pack_channels(None, 0, p, 4, 32, None) == -1
+    assert lib.bnn_pack_channels(p, 2, p, 4, 32, None) == -3
+    assert lib.bnn_pack_channels(p, 0, p, 0, 32, None) == -2
+    assert lib.bnn_pack_channels(ctypes.c_void_p(0x1002), 1, p, 4, 32, None) == -4
+    lib.bnn_weight_words.argtypes = [i64] * 4
+    lib.bnn_weight_words.restype = ctypes.c_size_t
+    assert lib.bnn_weight_words(70, 3, 3, 40) == 9 * 2 * 128 + 9 * 128      # K padded to 128, two words per pixel
+    assert lib.bnn_weight_words(0, 3, 3, 40) == 0
+    lib.bnn_pack_weights.argtypes = [ctypes.c_void_p, ctypes.c_void_p, i64, i64, i64, i64, ctypes.c_void_p]
+    assert lib.bnn_pack_weights(p, None, 8, 3, 3, 32, None) == -1
+    assert lib.bnn_pack_weights(p, p, 8, 3, 0, 32, None) == -2
+    lib.bnn_binary_conv2d.argtypes = [ctypes.c_void_p] * 6 + [i64] * 9 + [ctypes.c_void_p]
+    ok = (1, 8, 8, 32, 64, 3, 3, 1, 1)
+    assert lib.bnn_binary_conv2d(p, p, None, None, None, None, *ok, None) == -1          # no output
+    assert lib.bnn_binary_conv2d(p, p, None, None, None, p, *ok, None) == -1             # x4 without thresholds
+    assert lib.bnn_binary_conv2d(p, p, p, p, p, p, 1, 8, 8, 32, 64, 3, 4, 1, 1, None) == -5    # S = 4
+    assert lib.bnn_binary_conv2d(p, p, p, p, p, p, 1, 8, 8, 32, 64, 3, 3, 3, 1, None) == -5    # stride 3
+    assert lib.bnn_binary_conv2d(p, p, p, p, p, p, 1, 2, 2, 32, 64, 5, 5, 1, 0, None) == -2    # empty output
+    assert lib.bnn_binary_conv2d(p, p, p, p, p, p, 0, 8, 8, 32, 64, 3, 3, 1, 1, None) == -2
+    lib.bnn_strerror.restype = ctypes.c_char_p
+    assert b"width" in lib.bnn_strerror(-5)

@@ -1,0 +1,130 @@
+"""Binary convolution layer: HIP path against the CPU oracle, bit-exact (integers and bits)."""
+import sys
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import bnn as obnn
+from paper_1912_04050_amd import bnn_workloads as bw
+
+pytestmark = pytest.mark.gpu
+SEED = bw.DEFAULT_SEED
+
+
+@pytest.fixture(scope="module")
+def bnn():
+    from paper_1912_04050_amd import bnn as mod
+    return mod
+
+
+def say(*a):
+    print("[case]", *a, flush=True)
+    sys.stdout.flush()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda")
+
+
+def host_words(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy().view(np.uint32)
+
+
+def run_layer(bnn, x, w, xi, gamma, stride, pad):
+    N, H, W, C = x.shape
+    K, R, S, _ = w.shape
+    xw = bnn.bnn_pack_channels(dev(x))
+    wp = bnn.bnn_pack_weights(dev(w))
+    x1, x4 = bnn.bnn_binary_conv2d(xw, wp, (N, H, W, C, K, R, S), dev(xi), dev(gamma), want_x1=True, want_x4=True,
+                                   stride=stride, pad=pad)
+    torch.cuda.synchronize()
+    return x1.cpu().numpy(), host_words(x4), host_words(xw)
+
+
+def check_layer(bnn, layer_id, N, H, W, C, K, R, S, stride, pad):
+    say("layer", (N, H, W, C, K, R, S, stride, pad))
+    x, w, xi, gamma = bw.layer_inputs(SEED, layer_id, N, H, W, C, K, R, S)
+    got_x1, got_x4, got_xw = run_layer(bnn, x, w, xi, gamma, stride, pad)
+    assert np.array_equal(got_xw, obnn.pack(x))
+    want_x1 = obnn.conv2d(x, w, stride, pad)
+    assert np.array_equal(got_x1, want_x1)
+    want_x4 = obnn.pack(obnn.binarize(want_x1, xi, gamma).astype(np.int8))
+    assert np.array_equal(got_x4, want_x4)
+    both = obnn.binarize(want_x1, xi, gamma)
+    return float(both.mean()), float((want_x1.astype(np.float32) == xi[None, None, None, :]).mean())
+
+
+@pytest.mark.parametrize("C", [16, 32, 48, 64, 96, 128, 200, 256, 1024])
+def test_channel_counts(bnn, C):
+    """Whole and ragged words per pixel; 1, 2 or 4 words per pass."""
+    ones, ties = check_layer(bnn, C, 2, 9, 11, C, 40, 3, 3, 1, 1)
+    assert 0.1 < ones < 0.9
+
+
+@pytest.mark.parametrize("K", [1, 8, 31, 32, 33, 64, 65, 96, 130, 512])
+def test_filter_counts(bnn, K):
+    """Filters below, at and above the 64 lanes of a wave; ragged output words."""
+    check_layer(bnn, 100 + K, 1, 8, 10, 64, K, 3, 3, 1, 1)
+
+
+@pytest.mark.parametrize("geom", [
+    # H, W, R, S, stride, pad
+    (7, 7, 1, 1, 1, 0), (8, 9, 3, 3, 1, 0), (8, 9, 3, 3, 1, 1), (13, 13, 3, 3, 1, 1), (26, 26, 3, 3, 1, 1),
+    (10, 17, 5, 5, 1, 2), (9, 9, 5, 5, 1, 0), (11, 12, 3, 3, 2, 1), (16, 16, 5, 5, 2, 2), (8, 8, 1, 1, 2, 0),
+    (6, 30, 2, 3, 1, 1), (3, 3, 3, 3, 1, 1), (1, 1, 3, 3, 1, 1), (5, 1, 3, 3, 1, 1), (4, 40, 7, 5, 1, 3), (12, 8, 3, 5, 2, 2),
+    (9, 9, 3, 3, 1, 2), (15, 15, 3, 3, 1, 0)])
+def test_geometries(bnn, geom):
+    """Filter sizes, strides and paddings; output rows of every length relative to the 7 / 8
+    pixels of a wave; images smaller than the filter; padding wider than needed."""
+    H, W, R, S, stride, pad = geom
+    check_layer(bnn, 200 + H * 31 + W, 2, H, W, 96, 70, R, S, stride, pad)
+
+
+def test_threshold_equality_cases_occur(bnn):
+    """The generator snaps half of the thresholds to attainable values so that x1 = xi happens."""
+    ones, ties = check_layer(bnn, 300, 2, 13, 13, 256, 128, 3, 3, 1, 1)
+    assert ties > 1e-4
+
+
+def test_raw_only_and_packed_only_outputs(bnn):
+    N, H, W, C, K = 1, 10, 10, 64, 96
+    x, w, xi, gamma = bw.layer_inputs(SEED, 301, N, H, W, C, K)
+    xw, wp = bnn.bnn_pack_channels(dev(x)), bnn.bnn_pack_weights(dev(w))
+    want_x1 = obnn.conv2d(x, w, 1, 1)
+    x1, none = bnn.bnn_binary_conv2d(xw, wp, (N, H, W, C, K, 3, 3), want_x1=True, want_x4=False, pad=1)
+    assert none is None
+    torch.cuda.synchronize()
+    assert np.array_equal(x1.cpu().numpy(), want_x1)
+    none, x4 = bnn.bnn_binary_conv2d(xw, wp, (N, H, W, C, K, 3, 3), dev(xi), dev(gamma), want_x1=False, want_x4=True, pad=1)
+    assert none is None
+    assert np.array_equal(host_words(x4), obnn.pack(obnn.binarize(want_x1, xi, gamma).astype(np.int8)))
+
+
+def test_float_inputs_pack_to_their_signs(bnn):
+    rng = np.random.default_rng(5)
+    v = rng.normal(size=(3, 5, 70)).astype(np.float32)
+    v[0, 0, :4] = [0.0, -0.0, 1e-30, -1e-30]
+    got = host_words(bnn.bnn_pack_channels(dev(v)))
+    assert np.array_equal(got, obnn.pack(np.where(v > 0, 1, -1).astype(np.int8)))
+
+
+def test_two_layers_chained(bnn):
+    """The packed output of one layer is the packed input of the next."""
+    N, H, W = 2, 12, 12
+    x, w1, xi1, g1 = bw.layer_inputs(SEED, 302, N, H, W, 64, 96)
+    _, w2, xi2, g2 = bw.layer_inputs(SEED, 303, N, H, W, 96, 128)
+    xw = bnn.bnn_pack_channels(dev(x))
+    _, h1 = bnn.bnn_binary_conv2d(xw, bnn.bnn_pack_weights(dev(w1)), (N, H, W, 64, 96, 3, 3), dev(xi1), dev(g1), pad=1)
+    _, h2 = bnn.bnn_binary_conv2d(h1, bnn.bnn_pack_weights(dev(w2)), (N, H, W, 96, 128, 3, 3), dev(xi2), dev(g2), pad=1)
+    a1 = obnn.binarize(obnn.conv2d(x, w1, 1, 1), xi1, g1).astype(np.int8) * 2 - 1
+    a2 = obnn.binarize(obnn.conv2d(a1, w2, 1, 1), xi2, g2).astype(np.int8)
+    assert np.array_equal(host_words(h2), obnn.pack(a2))
+
+
+def test_detector_layer_shapes_one_image(bnn):
+    """The benchmark's layer shapes at batch 1 (the oracle finishes each in seconds)."""
+    for i, (name, hw, C, K) in enumerate(bw.DETECTOR_LAYERS):
+        check_layer(bnn, 400 + i, 1, hw, hw, C, K, 3, 3, 1, 1)
