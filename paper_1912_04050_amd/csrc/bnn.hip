@@ -111,6 +111,18 @@ __global__ __launch_bounds__(64) void bconv_kernel(const ConvArgs p) {
 #pragma unroll
   for (int j = 0; j < TM; ++j) acc[j] = 0;
 
+  // word offsets of the strip's pixels inside an input row (clamped into the row: the loads
+  // below are unconditional, a pixel outside the image is zeroed after the load)
+  uint32_t poff[PS];
+  bool pin[PS];
+#pragma unroll
+  for (int i = 0; i < PS; ++i) {
+    const int wi = wi0 + i;
+    pin[i] = wi >= 0 && wi < p.W;
+    poff[i] = (uint32_t)(pin[i] ? wi : 0) * (uint32_t)p.Cw;
+  }
+  const uint32_t wstep = (uint32_t)p.Kp;   // words between consecutive (tap, cw) rows of the filter bank
+
   int rows_inside = 0;
   for (int r = 0; r < p.R; ++r) {
     const int hi = ho * STRIDE - p.pad + r;
@@ -122,17 +134,19 @@ __global__ __launch_bounds__(64) void bconv_kernel(const ConvArgs p) {
       uint32_t a[PS][QC];                        // wave-uniform: scalar registers
 #pragma unroll
       for (int i = 0; i < PS; ++i) {
-        const int wi = wi0 + i;
-        const bool inside = wi >= 0 && wi < p.W;
-        const uint32_t* __restrict__ src = xrow + (int64_t)(inside ? wi : 0) * p.Cw + c0;
+        const uint32_t* __restrict__ src = xrow + (poff[i] + (uint32_t)c0);
 #pragma unroll
-        for (int q = 0; q < QC; ++q) a[i][q] = inside ? src[q] : 0u;
+        for (int q = 0; q < QC; ++q) {
+          const uint32_t v = src[q];
+          a[i][q] = pin[i] ? v : 0u;
+        }
       }
 #pragma unroll
       for (int s = 0; s < S; ++s) {
+        const uint32_t* __restrict__ wtap = wrow + (uint32_t)(s * p.Cw + c0) * wstep;
         uint32_t wv[QC];
 #pragma unroll
-        for (int q = 0; q < QC; ++q) wv[q] = (wrow + (int64_t)(s * p.Cw + c0 + q) * p.Kp)[k];
+        for (int q = 0; q < QC; ++q) wv[q] = (wtap + q * wstep)[k];
 #pragma unroll
         for (int j = 0; j < TM; ++j)
 #pragma unroll
