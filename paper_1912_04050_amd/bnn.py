@@ -29,6 +29,10 @@ _lib.bnn_strerror.argtypes = [_int]
 _lib.bnn_strerror.restype = ctypes.c_char_p
 
 
+_lib.bnn_set_planner.argtypes = [_int, _int]
+_lib.bnn_set_planner.restype = _int
+
+
 class BnnError(RuntimeError):
     def __init__(self, status: int):
         super().__init__(f"libbnn status {status}: {_lib.bnn_strerror(status).decode()}")
@@ -52,6 +56,10 @@ def _dense_cuda(t, name):
     if not t.is_cuda or not t.is_contiguous():
         raise ValueError(f"{name} must be a dense device tensor")
     return t
+
+
+def bnn_set_planner(tile_pixels: int = 0, filter_blocks: int = 0):
+    _check(_lib.bnn_set_planner(tile_pixels, filter_blocks))
 
 
 def out_shape(H, W, R, S, stride, pad):

@@ -87,144 +87,419 @@ struct ConvArgs {
   const float* gamma;      // [K] or null
   int32_t* out_x1;         // [N][Ho][Wo][K] or null
   uint32_t* out_x4;        // [N][Ho][Wo][Kw] or null
-  int32_t H, W, C, Cw, K, Kp, Kw, R, pad, Ho, Wo, kblocks, wtiles;
+  int32_t N, H, W, C, Cw, K, Kp, Kw, R, pad, Ho, Wo, kblocks, wtiles;
+  int32_t tiles_per_wave, waves_per_image;   // resident-filter kernel only
 };
 
-// S = filter width, STRIDE, QC = words of a pixel handled per pass (divides Cw), TM = output
-// pixels per wave.
-template <int S, int STRIDE, int QC, int TM>
+// Thresholds of the integrated layer in the integer domain.  For an integer x1 (exact in fp32
+// while |x1| <= 2^24, which the entry point guarantees) and v = (float)x1:
+//   gamma > 0:  (A xor B) or C = not (v < xi) = not (x1 < ceil(xi))
+//   otherwise:  (A xor B) or C = (v <= xi)    = x1 < floor(xi) + 1
+// so the decision is `(x1 < T) xor (gamma > 0)` with T = ceil(xi) resp. floor(xi) + 1, clamped to
+// +-2^30 (infinite thresholds) and -2^30 for a NaN (every comparison with it is false).
+__device__ __forceinline__ int32_t integer_threshold(float xi, bool positive) {
+  if (xi != xi) return -(1 << 30);
+  const float t = positive ? ceilf(xi) : floorf(xi) + 1.0f;
+  return (int32_t)fminf(fmaxf(t, -1073741824.0f), 1073741824.0f);
+}
+
+// v with lane LANE replaced by the wave-uniform value s (v_writelane_b32: one VALU instruction).
+template <int LANE>
+__device__ __forceinline__ uint32_t write_lane(uint32_t v, uint32_t s) {
+  asm("v_writelane_b32 %0, %1, %2" : "+v"(v) : "s"(s), "n"(LANE));
+  return v;
+}
+
+// the same for a lane index that is a constant only after loop unrolling (0..25)
+__device__ __forceinline__ uint32_t write_lane_of(uint32_t v, uint32_t s, int lane) {
+  switch (lane) {
+#define BNN_LANE(L) case L: return write_lane<L>(v, s);
+    BNN_LANE(0) BNN_LANE(1) BNN_LANE(2) BNN_LANE(3) BNN_LANE(4) BNN_LANE(5) BNN_LANE(6) BNN_LANE(7)
+    BNN_LANE(8) BNN_LANE(9) BNN_LANE(10) BNN_LANE(11) BNN_LANE(12) BNN_LANE(13) BNN_LANE(14) BNN_LANE(15)
+    BNN_LANE(16) BNN_LANE(17) BNN_LANE(18) BNN_LANE(19) BNN_LANE(20) BNN_LANE(21) BNN_LANE(22) BNN_LANE(23)
+    BNN_LANE(24) BNN_LANE(25)
+#undef BNN_LANE
+    default: return v;
+  }
+}
+
+// Per-lane constants of the integrated layer for the 64 filters of one block.
+struct Decision {
+  int32_t T;                       // x1 < T decides (see integer_threshold)
+  int32_t U0;                      // interior pixels: x1 < T  <=>  popcount > U0 = floor((R S C - T) / 2)
+  unsigned long long posmask;      // lanes with gamma > 0
+  unsigned long long okmask;       // lanes whose filter exists
+  bool lane_ok;
+};
+
+__device__ __forceinline__ Decision make_decision(const ConvArgs& p, int k, int S) {
+  Decision d;
+  const bool fused = p.out_x4 != nullptr;
+  d.lane_ok = k < p.K;
+  const bool positive = fused && d.lane_ok && p.gamma[k] > 0.f;
+  d.T = fused && d.lane_ok ? integer_threshold(p.xi[k], positive) : 0;
+  d.U0 = (p.R * S * p.C - d.T) >> 1;          // arithmetic shift = floor for either sign
+  d.posmask = __ballot(positive);
+  d.okmask = __ballot(d.lane_ok);
+  return d;
+}
+
+// Epilogue of one tile of TM output pixels and one block of 64 filters: x1 = Len - 2 popcount
+// with Len = C x (taps inside the image) and the popcounts that zeroed border pixels wrongly
+// added taken off; optional store of x1; the integrated layer's bit, its 64-lane compare mask
+// being the two packed output words of the pixel.  `interior`: every tap of every pixel of the
+// tile lies inside the image.
+template <int S, int STRIDE, int TM>
+__device__ __forceinline__ void finish_tile(const ConvArgs& p, const Decision& d, const uint32_t (&acc)[TM], int n,
+                                            int ho, int wo0, int kb, int k, int rows_inside, bool interior) {
+  const int lane = threadIdx.x & 63;
+  const uint32_t* __restrict__ pop = p.w + (int64_t)p.R * S * p.Cw * p.Kp;
+  const int64_t pixel0 = ((int64_t)n * p.Ho + ho) * p.Wo + wo0;
+  const int hi0 = ho * STRIDE - p.pad;
+  uint32_t mine = 0;
+#pragma unroll
+  for (int j = 0; j < TM; ++j) {
+    if (wo0 + j >= p.Wo) break;                  // wave-uniform
+    unsigned long long less;                     // lanes with x1 < T
+    if (interior && p.out_x1 == nullptr) {
+      less = __ballot((int32_t)acc[j] > d.U0);
+    } else {
+      int cols_inside = 0;
+      uint32_t wrong = 0;
+#pragma unroll
+      for (int s = 0; s < S; ++s) {
+        const int wi = (wo0 + j) * STRIDE - p.pad + s;
+        if (wi >= 0 && wi < p.W) { ++cols_inside; continue; }
+        for (int r = 0; r < p.R; ++r)
+          if (hi0 + r >= 0 && hi0 + r < p.H) wrong += pop[(uint32_t)(r * S + s) * (uint32_t)p.Kp + k];
+      }
+      const int32_t x1 = p.C * rows_inside * cols_inside - 2 * (int32_t)(acc[j] - wrong);
+      if (p.out_x1 != nullptr && d.lane_ok) p.out_x1[(pixel0 + j) * p.K + k] = x1;
+      less = __ballot(x1 < d.T);
+    }
+    const unsigned long long mask = (less ^ d.posmask) & d.okmask;
+    mine = write_lane_of(mine, (uint32_t)mask, 2 * j);
+    mine = write_lane_of(mine, (uint32_t)(mask >> 32), 2 * j + 1);
+  }
+  if (p.out_x4 != nullptr) {
+    // lanes 2j and 2j+1 hold the low and high word of pixel j
+    const int j = lane >> 1, word = kb * 2 + (lane & 1);
+    if (j < TM && wo0 + j < p.Wo && word < p.Kw) p.out_x4[(pixel0 + j) * p.Kw + word] = mine;
+  }
+}
+
+// One row of the strip into scalar registers: QC words of each of the PS pixels from word c0 of
+// the pixel on; pixels left or right of the image read as zero words.
+template <int PS, int QC>
+__device__ __forceinline__ void load_strip(uint32_t (&a)[PS][QC], const uint32_t* __restrict__ xrow, int wi0, int c0,
+                                           int Cw, int W, bool cols_interior) {
+  if (cols_interior) {
+#pragma unroll
+    for (int i = 0; i < PS; ++i) {
+      const uint32_t* __restrict__ src = xrow + ((uint32_t)(wi0 + i) * (uint32_t)Cw + (uint32_t)c0);
+#pragma unroll
+      for (int q = 0; q < QC; ++q) a[i][q] = src[q];
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < PS; ++i) {
+      const int wi = wi0 + i;
+      const bool in = wi >= 0 && wi < W;
+      const uint32_t* __restrict__ src = xrow + ((uint32_t)(in ? wi : 0) * (uint32_t)Cw + (uint32_t)c0);
+#pragma unroll
+      for (int q = 0; q < QC; ++q) {
+        const uint32_t v = src[q];               // unconditional (the address is clamped), zeroed afterwards
+        a[i][q] = in ? v : 0u;
+      }
+    }
+  }
+}
+
+// General kernel.  S = filter width, STRIDE, QC = words of a pixel per pass (divides Cw), TM =
+// output pixels per wave, KB = blocks of 64 filters per wave (each scalar activation word then
+// serves KB vector instructions pairs).
+template <int S, int STRIDE, int QC, int TM, int KB>
 __global__ __launch_bounds__(64) void bconv_kernel(const ConvArgs p) {
-  constexpr int PS = (TM - 1) * STRIDE + S;    // input pixels of the strip
+  constexpr int PS = (TM - 1) * STRIDE + S;      // input pixels of the strip
   const int lane = threadIdx.x;
   uint32_t b = blockIdx.x;
-  const int kb = b % p.kblocks; b /= p.kblocks;
+  // tiles fastest, filter blocks slowest: the waves in flight at any time share a few filter
+  // blocks, whose words they then find in the vector caches
   const int wt = b % p.wtiles; b /= p.wtiles;
-  const int ho = b % p.Ho;
-  const int n = b / p.Ho;
-  const int k = kb * 64 + lane;
+  const int ho = b % p.Ho; b /= p.Ho;
+  const int n = b % p.N;
+  const int kb0 = (b / p.N) * KB;
   const int wo0 = wt * TM;
   const int wi0 = wo0 * STRIDE - p.pad;
-  const uint32_t* __restrict__ xw = p.x;
-  const uint32_t* __restrict__ ww = p.w;
+  const bool cols_interior = wi0 >= 0 && wi0 + PS <= p.W;    // wave-uniform
+  const uint32_t wstep = (uint32_t)p.Kp;         // words between consecutive (tap, cw) rows of the filter bank
 
-  uint32_t acc[TM];
+  uint32_t acc[KB][TM];
 #pragma unroll
-  for (int j = 0; j < TM; ++j) acc[j] = 0;
-
-  // word offsets of the strip's pixels inside an input row (clamped into the row: the loads
-  // below are unconditional, a pixel outside the image is zeroed after the load)
-  uint32_t poff[PS];
-  bool pin[PS];
+  for (int u = 0; u < KB; ++u)
 #pragma unroll
-  for (int i = 0; i < PS; ++i) {
-    const int wi = wi0 + i;
-    pin[i] = wi >= 0 && wi < p.W;
-    poff[i] = (uint32_t)(pin[i] ? wi : 0) * (uint32_t)p.Cw;
-  }
-  const uint32_t wstep = (uint32_t)p.Kp;   // words between consecutive (tap, cw) rows of the filter bank
+    for (int j = 0; j < TM; ++j) acc[u][j] = 0;
 
   int rows_inside = 0;
   for (int r = 0; r < p.R; ++r) {
     const int hi = ho * STRIDE - p.pad + r;
     if (hi < 0 || hi >= p.H) continue;           // wave-uniform
     ++rows_inside;
-    const uint32_t* __restrict__ xrow = xw + ((int64_t)n * p.H + hi) * p.W * p.Cw;
-    const uint32_t* __restrict__ wrow = ww + (int64_t)r * S * p.Cw * p.Kp;   // wave-uniform; the lane adds k
+    const uint32_t* __restrict__ xrow = p.x + ((int64_t)n * p.H + hi) * p.W * p.Cw;
+    const uint32_t* __restrict__ wrow = p.w + (int64_t)r * S * p.Cw * p.Kp + kb0 * 64;
     for (int c0 = 0; c0 < p.Cw; c0 += QC) {
       uint32_t a[PS][QC];                        // wave-uniform: scalar registers
-#pragma unroll
-      for (int i = 0; i < PS; ++i) {
-        const uint32_t* __restrict__ src = xrow + (poff[i] + (uint32_t)c0);
-#pragma unroll
-        for (int q = 0; q < QC; ++q) {
-          const uint32_t v = src[q];
-          a[i][q] = pin[i] ? v : 0u;
-        }
-      }
+      load_strip<PS, QC>(a, xrow, wi0, c0, p.Cw, p.W, cols_interior);
 #pragma unroll
       for (int s = 0; s < S; ++s) {
         const uint32_t* __restrict__ wtap = wrow + (uint32_t)(s * p.Cw + c0) * wstep;
-        uint32_t wv[QC];
+        uint32_t wv[KB][QC];
 #pragma unroll
-        for (int q = 0; q < QC; ++q) wv[q] = (wtap + q * wstep)[k];
+        for (int u = 0; u < KB; ++u)
+#pragma unroll
+          for (int q = 0; q < QC; ++q) wv[u][q] = (wtap + (q * wstep + u * 64))[lane];
 #pragma unroll
         for (int j = 0; j < TM; ++j)
 #pragma unroll
-          for (int q = 0; q < QC; ++q) acc[j] += __popc(a[j * STRIDE + s][q] ^ wv[q]);
+          for (int q = 0; q < QC; ++q)
+#pragma unroll
+            for (int u = 0; u < KB; ++u) acc[u][j] += __popc(a[j * STRIDE + s][q] ^ wv[u][q]);
       }
     }
   }
 
-  // epilogue: x1 = Len - 2 popcount, Len = C x (taps inside the image); then the integrated layer
-  const uint32_t* __restrict__ pop = ww + (int64_t)p.R * S * p.Cw * p.Kp;
-  const bool touches_border = wi0 < 0 || wi0 + PS > p.W;   // wave-uniform
-  const float xi = (p.out_x4 != nullptr && k < p.K) ? p.xi[k] : 0.f;
-  const float gamma = (p.out_x4 != nullptr && k < p.K) ? p.gamma[k] : 0.f;
-  unsigned long long mine = 0;
+  const bool interior = cols_interior && rows_inside == p.R;
 #pragma unroll
-  for (int j = 0; j < TM; ++j) {
-    const int wo = wo0 + j;
-    if (wo >= p.Wo) break;                       // wave-uniform
-    int cols_inside = S;
-    uint32_t wrong = 0;
-    if (touches_border) {
-      cols_inside = 0;
-#pragma unroll
-      for (int s = 0; s < S; ++s) {
-        const int wi = wo * STRIDE - p.pad + s;
-        if (wi >= 0 && wi < p.W) { ++cols_inside; continue; }
-        for (int r = 0; r < p.R; ++r) {
-          const int hi = ho * STRIDE - p.pad + r;
-          if (hi >= 0 && hi < p.H) wrong += pop[(int64_t)(r * S + s) * p.Kp + k];
-        }
-      }
-    }
-    const int32_t x1 = p.C * rows_inside * cols_inside - 2 * (int32_t)(acc[j] - wrong);
-    const int64_t pixel = ((int64_t)n * p.Ho + ho) * p.Wo + wo;
-    if (p.out_x1 != nullptr && k < p.K) p.out_x1[pixel * p.K + k] = x1;
-    if (p.out_x4 != nullptr) {
-      const float v = (float)x1;
-      const bool A = v < xi, B = gamma > 0.f, Cq = v == xi;
-      const bool bit = k < p.K && ((A != B) || Cq);
-      const unsigned long long mask = __ballot(bit);
-      if (lane == 2 * j || lane == 2 * j + 1) mine = mask;
-    }
-  }
-  if (p.out_x4 != nullptr) {
-    // lanes 2j and 2j+1 hold the mask of pixel j: its low and high word
-    const int j = lane >> 1, half = lane & 1;
-    const int word = kb * 2 + half;
-    if (j < TM && wo0 + j < p.Wo && word < p.Kw) {
-      const int64_t pixel = ((int64_t)n * p.Ho + ho) * p.Wo + wo0 + j;
-      p.out_x4[pixel * p.Kw + word] = (uint32_t)(half ? mine >> 32 : mine);
-    }
+  for (int u = 0; u < KB; ++u) {
+    const int k = (kb0 + u) * 64 + lane;
+    const Decision d = make_decision(p, k, S);
+    finish_tile<S, STRIDE, TM>(p, d, acc[u], n, ho, wo0, kb0 + u, k, rows_inside, interior);
   }
 }
 
-template <int S, int STRIDE, int QC, int TM>
-void launch_conv(const ConvArgs& a, uint32_t blocks, hipStream_t stream) {
+// Kernel for wide pixels (Cw a multiple of 4).  A workgroup of 4 waves owns one tile of TM
+// output pixels and 4 KB blocks of 64 filters (one KB-group per wave).  The input strip of the
+// tile -- every filter row inside the image, PS pixels, all Cw words -- is staged once in LDS
+// with coalesced 16-byte loads (scalar loads would fetch a 64-byte line per pixel for 16 bytes of
+// use and thrash the small scalar cache); every lane of a wave then reads the same LDS address
+// (a broadcast, free of bank conflicts) and xors it with its own filter word.
+template <int S, int STRIDE, int TM, int KB>
+__global__ __launch_bounds__(256) void bconv_lds_kernel(const ConvArgs p) {
+  extern __shared__ __align__(16) uint32_t strip[];          // [rows inside][PS][Cw]
+  constexpr int PS = (TM - 1) * STRIDE + S;
+  constexpr int QC = 4;
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  uint32_t b = blockIdx.x;
+  const int wt = b % p.wtiles; b /= p.wtiles;
+  const int ho = b % p.Ho; b /= p.Ho;
+  const int n = b % p.N;
+  const int kgroup = b / p.N;
+  const int wo0 = wt * TM;
+  const int wi0 = wo0 * STRIDE - p.pad;
+  const int r_lo = max(0, p.pad - ho * STRIDE);
+  const int r_hi = min(p.R, p.H + p.pad - ho * STRIDE);
+  const int rows_inside = max(r_hi - r_lo, 0);
+  const int cw4 = p.Cw / QC;
+
+  // stage the strip: element e = (row rr, strip pixel i, group of 4 words c4), c4 fastest
+  const int staged = rows_inside * PS * cw4;
+  for (int e = tid; e < staged; e += 256) {
+    const int c4 = e % cw4;
+    const int i = (e / cw4) % PS;
+    const int rr = e / (cw4 * PS);
+    const int wi = wi0 + i, hi = ho * STRIDE - p.pad + r_lo + rr;
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (wi >= 0 && wi < p.W)
+      v = *reinterpret_cast<const u32x4*>(p.x + (((int64_t)n * p.H + hi) * p.W + wi) * p.Cw + c4 * QC);
+    reinterpret_cast<u32x4*>(strip)[e] = v;
+  }
+  __syncthreads();
+
+  const int kb0 = (kgroup * 4 + wave) * KB;
+  if (kb0 >= p.kblocks) return;                  // whole wave, after the only barrier
+  const uint32_t wstep = (uint32_t)p.Kp;
+  uint32_t acc[KB][TM];
+#pragma unroll
+  for (int u = 0; u < KB; ++u)
+#pragma unroll
+    for (int j = 0; j < TM; ++j) acc[u][j] = 0;
+
+  for (int rr = 0; rr < rows_inside; ++rr) {
+    const uint32_t* __restrict__ wrow = p.w + (int64_t)(r_lo + rr) * S * p.Cw * p.Kp + kb0 * 64;
+    const u32x4* __restrict__ srow = reinterpret_cast<const u32x4*>(strip) + rr * PS * cw4;
+    for (int c4 = 0; c4 < cw4; ++c4) {
+      u32x4 a[PS];                               // the same value in every lane
+#pragma unroll
+      for (int i = 0; i < PS; ++i) a[i] = srow[i * cw4 + c4];
+#pragma unroll
+      for (int s = 0; s < S; ++s) {
+        const uint32_t* __restrict__ wtap = wrow + (uint32_t)(s * p.Cw + c4 * QC) * wstep;
+        uint32_t wv[KB][QC];
+#pragma unroll
+        for (int u = 0; u < KB; ++u)
+#pragma unroll
+          for (int q = 0; q < QC; ++q) wv[u][q] = (wtap + (q * wstep + u * 64))[lane];
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+          for (int q = 0; q < QC; ++q)
+#pragma unroll
+            for (int u = 0; u < KB; ++u) acc[u][j] += __popc(a[j * STRIDE + s][q] ^ wv[u][q]);
+      }
+    }
+  }
+
+  const bool interior = wi0 >= 0 && wi0 + PS <= p.W && rows_inside == p.R;
+#pragma unroll
+  for (int u = 0; u < KB; ++u) {
+    const int k = (kb0 + u) * 64 + lane;
+    const Decision d = make_decision(p, k, S);
+    finish_tile<S, STRIDE, TM>(p, d, acc[u], n, ho, wo0, kb0 + u, k, rows_inside, interior);
+  }
+}
+
+// Filters small enough to live in registers (R * S * CW <= 36 words per lane): the wave loads
+// its 64 filters once and then streams over `tiles_per_wave` consecutive (output row, strip)
+// tiles of one image, which is how the paper uses a thread's private memory for layers of few
+// channels.  Per tile and filter row the strip of PS pixels x CW words is one contiguous run of
+// scalar loads.
+template <int R, int S, int STRIDE, int CW, int TM>
+__global__ __launch_bounds__(64) void bconv_resident_kernel(const ConvArgs p) {
+  constexpr int PS = (TM - 1) * STRIDE + S;
+  const int lane = threadIdx.x;
+  uint32_t b = blockIdx.x;
+  const int kb = b % p.kblocks; b /= p.kblocks;
+  const int chunk = b % p.waves_per_image;
+  const int n = b / p.waves_per_image;
+  const int k = kb * 64 + lane;
+  const uint32_t* __restrict__ ximg = p.x + (int64_t)n * p.H * p.W * CW;
+
+  uint32_t wreg[R][S][CW];
+#pragma unroll
+  for (int r = 0; r < R; ++r)
+#pragma unroll
+    for (int s = 0; s < S; ++s)
+#pragma unroll
+      for (int q = 0; q < CW; ++q) wreg[r][s][q] = (p.w + (uint32_t)((r * S + s) * CW + q) * (uint32_t)p.Kp)[k];
+  const Decision d = make_decision(p, k, S);
+
+  const int total_tiles = p.Ho * p.wtiles;
+  const int t_begin = chunk * p.tiles_per_wave;
+  const int t_end = min(t_begin + p.tiles_per_wave, total_tiles);
+  for (int t = t_begin; t < t_end; ++t) {
+    const int ho = t / p.wtiles, wt = t % p.wtiles;
+    const int wo0 = wt * TM;
+    const int wi0 = wo0 * STRIDE - p.pad;
+    const int hi0 = ho * STRIDE - p.pad;
+    const bool cols_interior = wi0 >= 0 && wi0 + PS <= p.W;   // wave-uniform
+    uint32_t acc[TM];
+#pragma unroll
+    for (int j = 0; j < TM; ++j) acc[j] = 0;
+    int rows_inside = 0;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int hi = hi0 + r;
+      if (hi < 0 || hi >= p.H) continue;         // wave-uniform
+      ++rows_inside;
+      uint32_t a[PS][CW];
+      load_strip<PS, CW>(a, ximg + (int64_t)hi * p.W * CW, wi0, 0, CW, p.W, cols_interior);
+#pragma unroll
+      for (int s = 0; s < S; ++s)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+          for (int q = 0; q < CW; ++q) acc[j] += __popc(a[j * STRIDE + s][q] ^ wreg[r][s][q]);
+    }
+    finish_tile<S, STRIDE, TM>(p, d, acc, n, ho, wo0, kb, k, rows_inside, cols_interior && rows_inside == R);
+  }
+}
+
+// ---- launch selection -------------------------------------------------------------------------
+
+template <int S, int STRIDE, int QC, int TM, int KB>
+void launch_general(const ConvArgs& a, uint32_t blocks, hipStream_t stream) {
   rtc::prof_begin(kProfileKind, stream);
-  hipLaunchKernelGGL((bconv_kernel<S, STRIDE, QC, TM>), dim3(blocks), dim3(64), 0, stream, a);
+  hipLaunchKernelGGL((bconv_kernel<S, STRIDE, QC, TM, KB>), dim3(blocks), dim3(64), 0, stream, a);
   rtc::prof_end(stream);
 }
 
-template <int S, int STRIDE, int QC>
-void launch_conv_tm(const ConvArgs& a, int tm, uint32_t blocks, hipStream_t stream) {
-  if (tm == 7) launch_conv<S, STRIDE, QC, 7>(a, blocks, stream);
-  else launch_conv<S, STRIDE, QC, 8>(a, blocks, stream);
+// Instantiated scalar-strip variants (the fallback for pixels whose word count is not a multiple
+// of 4, or whose strip does not fit LDS): tiles of 7 / 8 pixels, one block of filters.
+template <int S>
+bool launch_general_s(const ConvArgs& a, int stride, int qc, int tm, uint32_t blocks, hipStream_t stream) {
+#define BNN_GENERAL(ST, QQ, TT)                                            \
+  if (stride == ST && qc == QQ && tm == TT) {                              \
+    launch_general<S, ST, QQ, TT, 1>(a, blocks, stream);                   \
+    return true;                                                           \
+  }
+  BNN_GENERAL(1, 4, 7) BNN_GENERAL(1, 4, 8) BNN_GENERAL(1, 2, 7) BNN_GENERAL(1, 2, 8) BNN_GENERAL(1, 1, 7) BNN_GENERAL(1, 1, 8)
+  BNN_GENERAL(2, 4, 7) BNN_GENERAL(2, 4, 8) BNN_GENERAL(2, 2, 7) BNN_GENERAL(2, 2, 8) BNN_GENERAL(2, 1, 7) BNN_GENERAL(2, 1, 8)
+#undef BNN_GENERAL
+  return false;
 }
 
-template <int S, int STRIDE>
-void launch_conv_qc(const ConvArgs& a, int qc, int tm, uint32_t blocks, hipStream_t stream) {
-  if (qc == 4) launch_conv_tm<S, STRIDE, 4>(a, tm, blocks, stream);
-  else if (qc == 2) launch_conv_tm<S, STRIDE, 2>(a, tm, blocks, stream);
-  else launch_conv_tm<S, STRIDE, 1>(a, tm, blocks, stream);
+template <int S, int STRIDE, int TM, int KB>
+void launch_lds_one(const ConvArgs& a, uint32_t blocks, size_t lds_bytes, hipStream_t stream) {
+  rtc::prof_begin(kProfileKind, stream);
+  hipLaunchKernelGGL((bconv_lds_kernel<S, STRIDE, TM, KB>), dim3(blocks), dim3(256), lds_bytes, stream, a);
+  rtc::prof_end(stream);
 }
 
 template <int S>
-void launch_conv_stride(const ConvArgs& a, int stride, int qc, int tm, uint32_t blocks, hipStream_t stream) {
-  if (stride == 1) launch_conv_qc<S, 1>(a, qc, tm, blocks, stream);
-  else launch_conv_qc<S, 2>(a, qc, tm, blocks, stream);
+bool launch_lds_s(const ConvArgs& a, int stride, int tm, int kb, uint32_t blocks, size_t lds_bytes, hipStream_t stream) {
+#define BNN_LDS(ST, TT, KK)                                                \
+  if (stride == ST && tm == TT && kb == KK) {                              \
+    launch_lds_one<S, ST, TT, KK>(a, blocks, lds_bytes, stream);           \
+    return true;                                                           \
+  }
+  BNN_LDS(1, 7, 1) BNN_LDS(1, 8, 1) BNN_LDS(1, 13, 1) BNN_LDS(1, 7, 2) BNN_LDS(1, 8, 2) BNN_LDS(1, 13, 2)
+  BNN_LDS(2, 7, 1) BNN_LDS(2, 8, 1) BNN_LDS(2, 7, 2) BNN_LDS(2, 8, 2)
+#undef BNN_LDS
+  return false;
+}
+
+template <int R, int S, int STRIDE, int CW, int TM>
+void launch_resident_one(const ConvArgs& a, uint32_t blocks, hipStream_t stream) {
+  rtc::prof_begin(kProfileKind, stream);
+  hipLaunchKernelGGL((bconv_resident_kernel<R, S, STRIDE, CW, TM>), dim3(blocks), dim3(64), 0, stream, a);
+  rtc::prof_end(stream);
+}
+
+// true when a resident-filter instantiation exists for the shape (and it was launched)
+bool launch_resident(const ConvArgs& a, int R, int S, int stride, int tm, uint32_t blocks, hipStream_t stream) {
+  const int cw = a.Cw;
+#define BNN_RESIDENT_TM(RR, SS, ST, CC, TT)                                \
+  if (R == RR && S == SS && cw == CC && stride == ST && tm == TT) {        \
+    launch_resident_one<RR, SS, ST, CC, TT>(a, blocks, stream);            \
+    return true;                                                           \
+  }
+#define BNN_RESIDENT(RR, SS, CC)                                           \
+  BNN_RESIDENT_TM(RR, SS, 1, CC, 7) BNN_RESIDENT_TM(RR, SS, 1, CC, 8) BNN_RESIDENT_TM(RR, SS, 1, CC, 13) \
+  BNN_RESIDENT_TM(RR, SS, 2, CC, 7) BNN_RESIDENT_TM(RR, SS, 2, CC, 8)
+  BNN_RESIDENT(1, 1, 1) BNN_RESIDENT(1, 1, 2) BNN_RESIDENT(1, 1, 4)
+  BNN_RESIDENT(3, 3, 1) BNN_RESIDENT(3, 3, 2) BNN_RESIDENT(3, 3, 4)
+  BNN_RESIDENT(5, 5, 1)
+#undef BNN_RESIDENT
+#undef BNN_RESIDENT_TM
+  return false;
+}
+
+// Output pixels per wave: the candidate that leaves the fewest idle slots in an output row of
+// Wo pixels (ties: the wider tile).
+int g_force_tm = 0, g_force_kb = 0;   // planner overrides, see bnn_set_planner
+
+int pick_tm(int64_t Wo, bool allow13) {
+  if (g_force_tm == 7 || g_force_tm == 8 || (g_force_tm == 13 && allow13)) return g_force_tm;
+  int best = 8;
+  int64_t best_slots = (Wo + 7) / 8 * 8;
+  const int cands[2] = {7, 13};
+  for (int c : cands) {
+    if (c == 13 && !allow13) continue;
+    const int64_t slots = (Wo + c - 1) / c * c;
+    if (slots < best_slots || (slots == best_slots && c > best)) { best = c; best_slots = slots; }
+  }
+  return best;
 }
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -295,24 +570,74 @@ int bnn_binary_conv2d(const uint32_t* x, const uint32_t* packed, const float* xi
     return BNN_ERR_ALIGN;
   const int64_t Ho = (H + 2 * pad - R) / stride + 1, Wo = (W + 2 * pad - S) / stride + 1;
   const int64_t Cw = (C + 31) / 32, Kp = (K + 63) / 64 * 64, Kw = (K + 31) / 32;
-  // every index the kernel forms in 32 bits, and the popcount accumulator itself
-  if (R * S * C > 0x3fffffffLL || bnn_weight_words(K, R, S, C) > 0x7fffffffULL) return BNN_ERR_SHAPE;
-  // pixels per wave: the one of 7 / 8 that wastes fewer slots of an output row
-  const int tm = ((Wo + 6) / 7 * 7 < (Wo + 7) / 8 * 8) ? 7 : 8;
-  const int64_t wtiles = (Wo + tm - 1) / tm, kblocks = Kp / 64;
-  const int64_t blocks = N * Ho * wtiles * kblocks;
-  if (blocks > 0x7fffffffLL) return BNN_ERR_SHAPE;
+  // offsets inside an input row and inside the filter bank are formed in 32 bits
+  // |x1| <= R S C must convert to fp32 exactly (the threshold comparison is an fp32 one)
+  if (R * S * C > (1 << 24) || bnn_weight_words(K, R, S, C) > 0x7fffffffULL || W * Cw > 0x7fffffffLL) return BNN_ERR_SHAPE;
+  const int64_t kblocks = Kp / 64;
   const int qc = Cw % 4 == 0 ? 4 : Cw % 2 == 0 ? 2 : 1;
   ConvArgs a;
   a.x = x; a.w = packed; a.xi = xi; a.gamma = gamma; a.out_x1 = out_x1; a.out_x4 = out_x4;
-  a.H = (int32_t)H; a.W = (int32_t)W; a.C = (int32_t)C; a.Cw = (int32_t)Cw; a.K = (int32_t)K; a.Kp = (int32_t)Kp;
+  a.N = (int32_t)N; a.H = (int32_t)H; a.W = (int32_t)W; a.C = (int32_t)C; a.Cw = (int32_t)Cw; a.K = (int32_t)K; a.Kp = (int32_t)Kp;
   a.Kw = (int32_t)Kw; a.R = (int32_t)R; a.pad = (int32_t)pad; a.Ho = (int32_t)Ho; a.Wo = (int32_t)Wo;
-  a.kblocks = (int32_t)kblocks; a.wtiles = (int32_t)wtiles;
+  a.kblocks = (int32_t)kblocks;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  if (S == 1) launch_conv_stride<1>(a, (int)stride, qc, tm, (uint32_t)blocks, stream);
-  else if (S == 3) launch_conv_stride<3>(a, (int)stride, qc, tm, (uint32_t)blocks, stream);
-  else launch_conv_stride<5>(a, (int)stride, qc, tm, (uint32_t)blocks, stream);
+
+  // few channels: the filters stay in registers and a wave streams over several tiles, enough
+  // of them that a launch has about 16K waves
+  const bool resident_shape = R == S && Cw <= 4 && (Cw & (Cw - 1)) == 0 && R * S * Cw <= 36;
+  if (resident_shape) {
+    const int tm = pick_tm(Wo, stride == 1);
+    const int64_t wtiles = (Wo + tm - 1) / tm;
+    const int64_t tiles_per_image = Ho * wtiles;
+    int64_t tpw = (N * tiles_per_image * kblocks + 16383) / 16384;
+    if (tpw > tiles_per_image) tpw = tiles_per_image;
+    if (tpw > 64) tpw = 64;
+    const int64_t wpi = (tiles_per_image + tpw - 1) / tpw;
+    if (N * wpi * kblocks > 0x7fffffffLL) return BNN_ERR_SHAPE;
+    a.wtiles = (int32_t)wtiles; a.tiles_per_wave = (int32_t)tpw; a.waves_per_image = (int32_t)wpi;
+    if (launch_resident(a, (int)R, (int)S, (int)stride, tm, (uint32_t)(N * wpi * kblocks), stream)) return hip_status();
+  }
+  // wide pixels: the strip goes through LDS, 4 waves = 4 groups of KB filter blocks per tile
+  if (qc == 4 && aligned(x, 16)) {
+    const int tm = pick_tm(Wo, stride == 1);
+    // one block of filters per wave measured faster than two (registers, occupancy); two only on request,
+    // and only when no wave would own half a pair
+    const int kb = g_force_kb == 2 && kblocks % 2 == 0 ? 2 : 1;
+    const int ps = (tm - 1) * (int)stride + (int)S;
+    const size_t lds_bytes = (size_t)R * ps * Cw * 4;
+    const int64_t wtiles = (Wo + tm - 1) / tm;
+    const int64_t kgroups = (kblocks + 4 * kb - 1) / (4 * kb);
+    const int64_t blocks = N * Ho * wtiles * kgroups;
+    if (blocks > 0x7fffffffLL) return BNN_ERR_SHAPE;
+    a.wtiles = (int32_t)wtiles; a.tiles_per_wave = 0; a.waves_per_image = 0;
+    if (lds_bytes <= 64 * 1024) {
+      bool launched;
+      if (S == 1) launched = launch_lds_s<1>(a, (int)stride, tm, kb, (uint32_t)blocks, lds_bytes, stream);
+      else if (S == 3) launched = launch_lds_s<3>(a, (int)stride, tm, kb, (uint32_t)blocks, lds_bytes, stream);
+      else launched = launch_lds_s<5>(a, (int)stride, tm, kb, (uint32_t)blocks, lds_bytes, stream);
+      if (launched) return hip_status();
+    }
+  }
+  const int tm = pick_tm(Wo, false);
+  const int64_t wtiles = (Wo + tm - 1) / tm;
+  const int64_t blocks = N * Ho * wtiles * kblocks;
+  if (blocks > 0x7fffffffLL) return BNN_ERR_SHAPE;
+  a.wtiles = (int32_t)wtiles; a.tiles_per_wave = 0; a.waves_per_image = 0;
+  bool launched;
+  if (S == 1) launched = launch_general_s<1>(a, (int)stride, qc, tm, (uint32_t)blocks, stream);
+  else if (S == 3) launched = launch_general_s<3>(a, (int)stride, qc, tm, (uint32_t)blocks, stream);
+  else launched = launch_general_s<5>(a, (int)stride, qc, tm, (uint32_t)blocks, stream);
+  if (!launched) return BNN_ERR_UNSUPPORTED;
   return hip_status();
+}
+
+int bnn_set_planner(int tile_pixels, int filter_blocks) {
+  if ((tile_pixels != 0 && tile_pixels != 7 && tile_pixels != 8 && tile_pixels != 13) || filter_blocks < 0 ||
+      filter_blocks > 2)
+    return BNN_ERR_SHAPE;
+  bnn::g_force_tm = tile_pixels;
+  bnn::g_force_kb = filter_blocks;
+  return BNN_OK;
 }
 
 const char* bnn_strerror(int status) {
