@@ -13,10 +13,15 @@ pytestmark = pytest.mark.gpu
 SEED = bw.DEFAULT_SEED
 
 
-@pytest.fixture(scope="module")
-def bnn():
+@pytest.fixture(scope="module", params=[(0, 0), (7, 1), (8, 2), (13, 2)],
+                ids=["automatic", "tiles-of-7", "tiles-of-8-two-blocks", "tiles-of-13-two-blocks"])
+def bnn(request):
+    """Every test runs under the automatic planner and with the tile width / filter blocks per
+    wave forced to each instantiated value (settings that do not apply to a shape are ignored)."""
     from paper_1912_04050_amd import bnn as mod
-    return mod
+    mod.bnn_set_planner(*request.param)
+    yield mod
+    mod.bnn_set_planner(0, 0)
 
 
 def say(*a):
@@ -128,3 +133,36 @@ def test_detector_layer_shapes_one_image(bnn):
     """The benchmark's layer shapes at batch 1 (the oracle finishes each in seconds)."""
     for i, (name, hw, C, K) in enumerate(bw.DETECTOR_LAYERS):
         check_layer(bnn, 400 + i, 1, hw, hw, C, K, 3, 3, 1, 1)
+
+
+def test_unaligned_activations_take_the_scalar_strip_kernel(bnn):
+    """Wide pixels normally go through LDS with 16-byte loads; a tensor that starts at an address
+    that is not a multiple of 16 must still be computed (scalar-strip kernel)."""
+    N, H, W, C, K = 2, 9, 14, 256, 130
+    x, w, xi, gamma = bw.layer_inputs(SEED, 304, N, H, W, C, K)
+    packed = obnn.pack(x).view(np.int32)
+    buf = torch.zeros(packed.size + 1, dtype=torch.int32, device="cuda")
+    buf[1:] = dev(packed.reshape(-1))
+    xw = buf[1:].view(N, H, W, C // 32)
+    assert xw.data_ptr() % 16 == 4
+    x1, x4 = bnn.bnn_binary_conv2d(xw, bnn.bnn_pack_weights(dev(w)), (N, H, W, C, K, 3, 3), dev(xi), dev(gamma),
+                                   want_x1=True, pad=1)
+    want_x1 = obnn.conv2d(x, w, 1, 1)
+    torch.cuda.synchronize()
+    assert np.array_equal(x1.cpu().numpy(), want_x1)
+    assert np.array_equal(host_words(x4), obnn.pack(obnn.binarize(want_x1, xi, gamma).astype(np.int8)))
+
+
+def test_special_thresholds(bnn):
+    """Infinite and NaN thresholds follow the fp32 comparisons of the boolean form literally."""
+    N, H, W, C, K = 1, 6, 7, 64, 8
+    x, w, xi, gamma = bw.layer_inputs(SEED, 305, N, H, W, C, K)
+    xi = np.array([np.inf, -np.inf, np.nan, np.nan, 0.5, -0.5, 3e9, -3e9], np.float32)
+    gamma = np.array([1, 1, 1, -1, 1, -1, -1, 1], np.float32)
+    _, x4 = bnn.bnn_binary_conv2d(bnn.bnn_pack_channels(dev(x)), bnn.bnn_pack_weights(dev(w)), (N, H, W, C, K, 3, 3),
+                                  dev(xi), dev(gamma), pad=1)
+    x1 = obnn.conv2d(x, w, 1, 1).astype(np.float32)
+    with np.errstate(invalid="ignore"):
+        A, B, Cq = x1 < xi, gamma > 0, x1 == xi
+    want = np.logical_or(np.logical_xor(A, B), Cq)
+    assert np.array_equal(host_words(x4), obnn.pack(want.astype(np.int8)))
