@@ -38,6 +38,10 @@ def parse():
                     help="also time every operator on each of the five configurations (adds per_config)")
     ap.add_argument("--only", default="", help="profiling aid: restrict the step to a comma list of "
                     "conv,deconv,pinv,compose,gpc,dev (the JSON line then describes that subset)")
+    ap.add_argument("--bnn", action="store_true",
+                    help="measure the binary convolution layer instead (detector trunk conv2..conv8); "
+                         "prints its own JSON line")
+    ap.add_argument("--bnn-batch", type=int, default=64, help="images per step of --bnn")
     ap.add_argument("--copy-mib", type=int, default=0, help="profiling aid: also run one plain device copy "
                     "of this many MiB, the known-size kernel that FETCH_SIZE / WRITE_SIZE are scaled by")
     return ap.parse_args()
@@ -265,12 +269,139 @@ def per_config_table(seed, peak_ops, with_cpu):
     return rows
 
 
+# HBM traffic of one launch of the dominant kernel of --bnn (conv8 at batch 64), measured like
+# HEADLINE_TRAFFIC_BYTES; see profiles/.  None until measured / for any other batch.
+BNN_TRAFFIC_BYTES = None
+
+
+def bnn_main(args):
+    """One step = the seven binary layers of the detector trunk (3x3, stride 1, padding 1) on a
+    batch of synthetic images: xor / popcount convolution with the integrated threshold,
+    binarisation and packing, packed activations in, packed activations out.  Layers are timed on
+    independent random inputs (pooling between them is not part of the measured path); the filter
+    banks are packed beforehand, as the paper prepares its model offline."""
+    import numpy as np
+    import torch
+
+    from paper_1912_04050_amd import bnn, bnn_workloads as bw, rtc
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    seed = bw.DEFAULT_SEED if args.seed is None else args.seed
+    N = args.bnn_batch
+    info = rtc.rtc_device_info()
+    layers = []
+    for i, (name, hw, C, K) in enumerate(bw.DETECTOR_LAYERS):
+        # activations: random words generated on the device (N x hw x hw x C bits would take minutes on the
+        # host); filters and thresholds from the seeded host generators
+        g = torch.Generator(device="cuda")
+        g.manual_seed(seed + i)
+        Cw = (C + 31) // 32
+        xw = torch.randint(-2**31, 2**31 - 1, (N, hw, hw, Cw), dtype=torch.int32, device="cuda", generator=g)
+        if C % 32:
+            xw &= (1 << (C % 32)) - 1
+        w_h = bw.random_signs(seed, 10 * i + 2, (K, 3, 3, C))
+        xi_h, gamma_h = bw.thresholds(seed, 10 * i + 3, K, 9 * C)
+        wp = bnn.bnn_pack_weights(torch.from_numpy(w_h).cuda())
+        out = torch.empty((N, hw, hw, (K + 31) // 32), dtype=torch.int32, device="cuda")
+        layers.append({"name": name, "hw": hw, "C": C, "K": K, "xw": xw, "wp": wp, "w_h": w_h, "xi_h": xi_h,
+                       "gamma_h": gamma_h, "xi": torch.from_numpy(xi_h).cuda(), "gamma": torch.from_numpy(gamma_h).cuda(),
+                       "out": out, "macs": N * hw * hw * K * 9 * C})
+    torch.cuda.synchronize()
+
+    def run_layer(L):
+        bnn.bnn_binary_conv2d(L["xw"], L["wp"], (N, L["hw"], L["hw"], L["C"], L["K"], 3, 3), L["xi"], L["gamma"],
+                              want_x1=False, out_x4=L["out"], pad=1)
+
+    def step():
+        for L in layers:
+            run_layer(L)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    rtc.rtc_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    times = [ms for kind, ms in rtc.rtc_profile_read() if kind == bnn.BNN_PROFILE_KIND]
+    rtc.rtc_profile_enable(False)
+    ms_per_step = wall * 1e3 / args.steps
+    total_macs = sum(L["macs"] for L in layers)
+    per_layer = []
+    for i, L in enumerate(layers):
+        ts = times[i::len(layers)][:args.steps]
+        avg = sum(ts) / max(len(ts), 1)
+        per_layer.append({"layer": L["name"], "map": L["hw"], "C": L["C"], "K": L["K"], "kernel_ms": round(avg, 4),
+                          "tmac_per_s": round(L["macs"] / avg / 1e9, 1) if avg else None})
+    # roofline of the dominant kernel (the last, largest layer): 2 VALU instructions (xor, popcount-accumulate)
+    # per 32 multiply-accumulates and lane; peak = CUs x 64 lanes x clock lane-ops/s
+    peak_ops = info["cu_count"] * 64 * info["clock_khz"] * 1e3
+    dom = layers[-1]
+    dom_ms = per_layer[-1]["kernel_ms"]
+    achieved = dom["macs"] / 16 / (dom_ms * 1e-3)
+    roofline = {"bound": "alu", "kernel": "bconv_lds_kernel (conv8: 13x13 map, 1024 -> 1024 channels)",
+                "achieved": round(achieved / 1e12, 4), "peak": round(peak_ops / 1e12, 4), "unit": "TOP/s",
+                "frac": round(achieved / peak_ops, 4), "traffic": BNN_TRAFFIC_BYTES if N == 64 else None,
+                "launch_ms": dom_ms, "macs_per_launch": dom["macs"],
+                "tmac_per_s": round(dom["macs"] / dom_ms / 1e9, 1),
+                "note": "a lane-op is one VALU lane-instruction; the kernel needs v_xor_b32 + v_bcnt_u32_b32 per 32 "
+                        "binary multiply-accumulates, so peak = 16 x 39.32 T = 629 TMAC/s"}
+
+    # sampled parity and CPU baseline: the oracle on a few images of each layer
+    cpu_baseline, parity = None, None
+    if args.cpu_seconds > 0:
+        from oracle import bnn as obnn
+        from oracle import oracle
+        spent, macs_done, checked = 0.0, 0, 0
+        budget_per_layer = args.cpu_seconds / len(layers)
+        for L in layers:
+            hw, C, K = L["hw"], L["C"], L["K"]
+            per_image = hw * hw * K * 9 * C
+            n_img = max(1, min(N, int(budget_per_layer * 4e10 / per_image)))   # ~40 GMAC/s assumed for sizing only
+            words = L["xw"][:n_img].cpu().numpy().view(np.uint32)
+            bits = np.unpackbits(words.view(np.uint8).reshape(n_img, hw, hw, -1), axis=-1, bitorder="little")[..., :C]
+            x_h = (bits.astype(np.int8) * 2 - 1)
+            ts = time.perf_counter()
+            x1 = obnn.conv2d(x_h, L["w_h"], 1, 1)
+            spent += time.perf_counter() - ts
+            macs_done += n_img * per_image
+            if not args.no_parity:
+                want = obnn.pack(obnn.binarize(x1, L["xi_h"], L["gamma_h"]).astype(np.int8))
+                run_layer(L)
+                torch.cuda.synchronize()
+                got = L["out"][:n_img].cpu().numpy().view(np.uint32)
+                assert np.array_equal(got, want), L["name"]
+                checked += n_img
+        cpu_baseline = {"value": round(macs_done / spent / 1e12, 5), "unit": "TMAC/s", "cores": oracle.num_threads(),
+                        "kind": "oracle", "sample": f"the same layers on the first few images of the batch "
+                                                    f"({macs_done / 1e9:.1f} GMAC in {spent:.1f} s)"}
+        if not args.no_parity:
+            parity = f"packed outputs of {checked} images bit-exact"
+
+    line = {"metric": "binary convolution TMAC/s (xor/popcount, integrated threshold + packing), detector trunk",
+            "value": round(total_macs / (ms_per_step * 1e-3) / 1e12, 2), "unit": "TMAC/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32 (1-bit values, 32 per word)",
+            "data": "synthetic",
+            "config": {"workload": f"binary layers conv2..conv8 of a 416x416 single-shot detector trunk, batch {N}, "
+                                   "3x3 / stride 1 / padding 1, packed NHWC in and out", "batch": N, "seed": seed},
+            "per_layer": per_layer, "roofline": roofline, "cpu_baseline": cpu_baseline, "parity": parity}
+    print(json.dumps(line))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path "
               "(the batch would shard by pair with no exchange); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.bnn:
+        return bnn_main(args)
 
     import numpy as np
     import torch
