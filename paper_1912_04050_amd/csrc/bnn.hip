@@ -157,13 +157,20 @@ __device__ __forceinline__ void finish_tile(const ConvArgs& p, const Decision& d
   const int64_t pixel0 = ((int64_t)n * p.Ho + ho) * p.Wo + wo0;
   const int hi0 = ho * STRIDE - p.pad;
   uint32_t mine = 0;
+  if (interior && p.out_x1 == nullptr) {
+    // every tap inside the image and no x1 wanted: one integer compare per pixel (pixels beyond
+    // the end of the output row are computed too and never stored)
 #pragma unroll
-  for (int j = 0; j < TM; ++j) {
-    if (wo0 + j >= p.Wo) break;                  // wave-uniform
-    unsigned long long less;                     // lanes with x1 < T
-    if (interior && p.out_x1 == nullptr) {
-      less = __ballot((int32_t)acc[j] > d.U0);
-    } else {
+    for (int j = 0; j < TM; ++j) {
+      const unsigned long long less = __ballot((int32_t)acc[j] > d.U0);      // lanes with x1 < T
+      const unsigned long long mask = (less ^ d.posmask) & d.okmask;
+      mine = write_lane_of(mine, (uint32_t)mask, 2 * j);
+      mine = write_lane_of(mine, (uint32_t)(mask >> 32), 2 * j + 1);
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+      if (wo0 + j >= p.Wo) break;                // wave-uniform
       int cols_inside = 0;
       uint32_t wrong = 0;
 #pragma unroll
@@ -175,11 +182,11 @@ __device__ __forceinline__ void finish_tile(const ConvArgs& p, const Decision& d
       }
       const int32_t x1 = p.C * rows_inside * cols_inside - 2 * (int32_t)(acc[j] - wrong);
       if (p.out_x1 != nullptr && d.lane_ok) p.out_x1[(pixel0 + j) * p.K + k] = x1;
-      less = __ballot(x1 < d.T);
+      const unsigned long long less = __ballot(x1 < d.T);
+      const unsigned long long mask = (less ^ d.posmask) & d.okmask;
+      mine = write_lane_of(mine, (uint32_t)mask, 2 * j);
+      mine = write_lane_of(mine, (uint32_t)(mask >> 32), 2 * j + 1);
     }
-    const unsigned long long mask = (less ^ d.posmask) & d.okmask;
-    mine = write_lane_of(mine, (uint32_t)mask, 2 * j);
-    mine = write_lane_of(mine, (uint32_t)(mask >> 32), 2 * j + 1);
   }
   if (p.out_x4 != nullptr) {
     // lanes 2j and 2j+1 hold the low and high word of pixel j
@@ -219,7 +226,13 @@ __device__ __forceinline__ void load_strip(uint32_t (&a)[PS][QC], const uint32_t
 // output pixels per wave, KB = blocks of 64 filters per wave (each scalar activation word then
 // serves KB vector instructions pairs).
 template <int S, int STRIDE, int QC, int TM, int KB>
-__global__ __launch_bounds__(64) void bconv_kernel(const ConvArgs p) {
+__global__ __launch_bounds__(64) void bconv_kernel(
+    const uint32_t* __restrict__ x, const uint32_t* __restrict__ w, const float* __restrict__ xi,
+    const float* __restrict__ gamma, int32_t* __restrict__ out_x1, uint32_t* __restrict__ out_x4, const ConvArgs dims) {
+  // the pointers travel as restrict-qualified kernel parameters (so that loads of the read-only
+  // operands stay scalar loads even though the kernel also stores), the sizes in `dims`
+  ConvArgs p = dims;
+  p.x = x; p.w = w; p.xi = xi; p.gamma = gamma; p.out_x1 = out_x1; p.out_x4 = out_x4;
   constexpr int PS = (TM - 1) * STRIDE + S;      // input pixels of the strip
   const int lane = threadIdx.x;
   uint32_t b = blockIdx.x;
@@ -284,7 +297,13 @@ __global__ __launch_bounds__(64) void bconv_kernel(const ConvArgs p) {
 // use and thrash the small scalar cache); every lane of a wave then reads the same LDS address
 // (a broadcast, free of bank conflicts) and xors it with its own filter word.
 template <int S, int STRIDE, int TM, int KB>
-__global__ __launch_bounds__(256) void bconv_lds_kernel(const ConvArgs p) {
+__global__ __launch_bounds__(256) void bconv_lds_kernel(
+    const uint32_t* __restrict__ x, const uint32_t* __restrict__ w, const float* __restrict__ xi,
+    const float* __restrict__ gamma, int32_t* __restrict__ out_x1, uint32_t* __restrict__ out_x4, const ConvArgs dims) {
+  // the pointers travel as restrict-qualified kernel parameters (so that loads of the read-only
+  // operands stay scalar loads even though the kernel also stores), the sizes in `dims`
+  ConvArgs p = dims;
+  p.x = x; p.w = w; p.xi = xi; p.gamma = gamma; p.out_x1 = out_x1; p.out_x4 = out_x4;
   extern __shared__ __align__(16) uint32_t strip[];          // [rows inside][PS][Cw]
   constexpr int PS = (TM - 1) * STRIDE + S;
   constexpr int QC = 4;
@@ -362,11 +381,22 @@ __global__ __launch_bounds__(256) void bconv_lds_kernel(const ConvArgs p) {
 // Filters small enough to live in registers (R * S * CW <= 36 words per lane): the wave loads
 // its 64 filters once and then streams over `tiles_per_wave` consecutive (output row, strip)
 // tiles of one image, which is how the paper uses a thread's private memory for layers of few
-// channels.  Per tile and filter row the strip of PS pixels x CW words is one contiguous run of
-// scalar loads.
+// channels.  A strip row is PS * CW <= 64 contiguous words: lane i fetches word i with one
+// coalesced vector load, issued one tile ahead so that its latency hides behind the current
+// tile's arithmetic; the row then passes through a wave-private LDS line, from which every lane
+// reads the same 16 bytes at a time (a broadcast), so each lane holds the whole strip.
 template <int R, int S, int STRIDE, int CW, int TM>
-__global__ __launch_bounds__(64) void bconv_resident_kernel(const ConvArgs p) {
+__global__ __launch_bounds__(64) void bconv_resident_kernel(
+    const uint32_t* __restrict__ x, const uint32_t* __restrict__ w, const float* __restrict__ xi,
+    const float* __restrict__ gamma, int32_t* __restrict__ out_x1, uint32_t* __restrict__ out_x4, const ConvArgs dims) {
+  ConvArgs p = dims;
+  p.x = x; p.w = w; p.xi = xi; p.gamma = gamma; p.out_x1 = out_x1; p.out_x4 = out_x4;
   constexpr int PS = (TM - 1) * STRIDE + S;
+  constexpr int WORDS = PS * CW;                 // words of one strip row
+  constexpr int QUADS = (WORDS + 3) / 4;
+  if (WORDS > 64) return;                        // one lane per strip word: the host never launches such a shape
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  __shared__ __align__(16) uint32_t line[R][64];
   const int lane = threadIdx.x;
   uint32_t b = blockIdx.x;
   const int kb = b % p.kblocks; b /= p.kblocks;
@@ -384,15 +414,38 @@ __global__ __launch_bounds__(64) void bconv_resident_kernel(const ConvArgs p) {
       for (int q = 0; q < CW; ++q) wreg[r][s][q] = (p.w + (uint32_t)((r * S + s) * CW + q) * (uint32_t)p.Kp)[k];
   const Decision d = make_decision(p, k, S);
 
+  // lane i's word of each strip row of the tile (ho, wt); 0 outside the image
+  auto fetch = [&](uint32_t (&dst)[R], int ho, int wt) {
+    const int wi = wt * TM * STRIDE - p.pad + lane / CW;
+    const bool col_ok = lane < WORDS && wi >= 0 && wi < p.W;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int hi = ho * STRIDE - p.pad + r;
+      uint32_t v = 0;
+      if (col_ok && hi >= 0 && hi < p.H) v = ximg[((int64_t)hi * p.W + wi) * CW + lane % CW];
+      dst[r] = v;
+    }
+  };
+
   const int total_tiles = p.Ho * p.wtiles;
   const int t_begin = chunk * p.tiles_per_wave;
   const int t_end = min(t_begin + p.tiles_per_wave, total_tiles);
+  if (t_begin >= t_end) return;
+  int ho = t_begin / p.wtiles, wt = t_begin % p.wtiles;   // advanced incrementally below
+  uint32_t cur[R], nxt[R];
+  fetch(cur, ho, wt);
   for (int t = t_begin; t < t_end; ++t) {
-    const int ho = t / p.wtiles, wt = t % p.wtiles;
+    int ho_next = ho, wt_next = wt + 1;
+    if (wt_next == p.wtiles) { wt_next = 0; ++ho_next; }
+    if (t + 1 < t_end) fetch(nxt, ho_next, wt_next);
+
     const int wo0 = wt * TM;
     const int wi0 = wo0 * STRIDE - p.pad;
     const int hi0 = ho * STRIDE - p.pad;
-    const bool cols_interior = wi0 >= 0 && wi0 + PS <= p.W;   // wave-uniform
+#pragma unroll
+    for (int r = 0; r < R; ++r) line[r][lane] = cur[r];
+    __syncthreads();                             // one wave: orders the LDS writes before the broadcast reads
+
     uint32_t acc[TM];
 #pragma unroll
     for (int j = 0; j < TM; ++j) acc[j] = 0;
@@ -402,16 +455,25 @@ __global__ __launch_bounds__(64) void bconv_resident_kernel(const ConvArgs p) {
       const int hi = hi0 + r;
       if (hi < 0 || hi >= p.H) continue;         // wave-uniform
       ++rows_inside;
-      uint32_t a[PS][CW];
-      load_strip<PS, CW>(a, ximg + (int64_t)hi * p.W * CW, wi0, 0, CW, p.W, cols_interior);
+      u32x4 a[QUADS];                            // the same value in every lane
+#pragma unroll
+      for (int v = 0; v < QUADS; ++v) a[v] = reinterpret_cast<const u32x4*>(line[r])[v];
 #pragma unroll
       for (int s = 0; s < S; ++s)
 #pragma unroll
         for (int j = 0; j < TM; ++j)
 #pragma unroll
-          for (int q = 0; q < CW; ++q) acc[j] += __popc(a[j * STRIDE + s][q] ^ wreg[r][s][q]);
+          for (int q = 0; q < CW; ++q) {
+            const int word = (j * STRIDE + s) * CW + q;
+            acc[j] += __popc(a[word / 4][word % 4] ^ wreg[r][s][q]);
+          }
     }
-    finish_tile<S, STRIDE, TM>(p, d, acc, n, ho, wo0, kb, k, rows_inside, cols_interior && rows_inside == R);
+    __syncthreads();                             // reads done before the next tile's writes
+    const bool interior = wi0 >= 0 && wi0 + PS <= p.W && rows_inside == R;
+    finish_tile<S, STRIDE, TM>(p, d, acc, n, ho, wo0, kb, k, rows_inside, interior);
+#pragma unroll
+    for (int r = 0; r < R; ++r) cur[r] = nxt[r];
+    ho = ho_next; wt = wt_next;
   }
 }
 
@@ -420,7 +482,8 @@ __global__ __launch_bounds__(64) void bconv_resident_kernel(const ConvArgs p) {
 template <int S, int STRIDE, int QC, int TM, int KB>
 void launch_general(const ConvArgs& a, uint32_t blocks, hipStream_t stream) {
   rtc::prof_begin(kProfileKind, stream);
-  hipLaunchKernelGGL((bconv_kernel<S, STRIDE, QC, TM, KB>), dim3(blocks), dim3(64), 0, stream, a);
+  hipLaunchKernelGGL((bconv_kernel<S, STRIDE, QC, TM, KB>), dim3(blocks), dim3(64), 0, stream, a.x, a.w, a.xi, a.gamma,
+                     a.out_x1, a.out_x4, a);
   rtc::prof_end(stream);
 }
 
@@ -442,7 +505,8 @@ bool launch_general_s(const ConvArgs& a, int stride, int qc, int tm, uint32_t bl
 template <int S, int STRIDE, int TM, int KB>
 void launch_lds_one(const ConvArgs& a, uint32_t blocks, size_t lds_bytes, hipStream_t stream) {
   rtc::prof_begin(kProfileKind, stream);
-  hipLaunchKernelGGL((bconv_lds_kernel<S, STRIDE, TM, KB>), dim3(blocks), dim3(256), lds_bytes, stream, a);
+  hipLaunchKernelGGL((bconv_lds_kernel<S, STRIDE, TM, KB>), dim3(blocks), dim3(256), lds_bytes, stream, a.x, a.w, a.xi,
+                     a.gamma, a.out_x1, a.out_x4, a);
   rtc::prof_end(stream);
 }
 
@@ -462,7 +526,8 @@ bool launch_lds_s(const ConvArgs& a, int stride, int tm, int kb, uint32_t blocks
 template <int R, int S, int STRIDE, int CW, int TM>
 void launch_resident_one(const ConvArgs& a, uint32_t blocks, hipStream_t stream) {
   rtc::prof_begin(kProfileKind, stream);
-  hipLaunchKernelGGL((bconv_resident_kernel<R, S, STRIDE, CW, TM>), dim3(blocks), dim3(64), 0, stream, a);
+  hipLaunchKernelGGL((bconv_resident_kernel<R, S, STRIDE, CW, TM>), dim3(blocks), dim3(64), 0, stream, a.x, a.w, a.xi,
+                     a.gamma, a.out_x1, a.out_x4, a);
   rtc::prof_end(stream);
 }
 
@@ -586,7 +651,8 @@ int bnn_binary_conv2d(const uint32_t* x, const uint32_t* packed, const float* xi
   // of them that a launch has about 16K waves
   const bool resident_shape = R == S && Cw <= 4 && (Cw & (Cw - 1)) == 0 && R * S * Cw <= 36;
   if (resident_shape) {
-    const int tm = pick_tm(Wo, stride == 1);
+    int tm = pick_tm(Wo, stride == 1);
+    if (((tm - 1) * stride + S) * Cw > 64) tm = 7;          // one lane per word of a strip row
     const int64_t wtiles = (Wo + tm - 1) / tm;
     const int64_t tiles_per_image = Ho * wtiles;
     int64_t tpw = (N * tiles_per_image * kblocks + 16383) / 16384;
@@ -595,7 +661,9 @@ int bnn_binary_conv2d(const uint32_t* x, const uint32_t* packed, const float* xi
     const int64_t wpi = (tiles_per_image + tpw - 1) / tpw;
     if (N * wpi * kblocks > 0x7fffffffLL) return BNN_ERR_SHAPE;
     a.wtiles = (int32_t)wtiles; a.tiles_per_wave = (int32_t)tpw; a.waves_per_image = (int32_t)wpi;
-    if (launch_resident(a, (int)R, (int)S, (int)stride, tm, (uint32_t)(N * wpi * kblocks), stream)) return hip_status();
+    if (((tm - 1) * stride + S) * Cw <= 64 &&
+        launch_resident(a, (int)R, (int)S, (int)stride, tm, (uint32_t)(N * wpi * kblocks), stream))
+      return hip_status();
   }
   // wide pixels: the strip goes through LDS, 4 waves = 4 groups of KB filter blocks per tile
   if (qc == 4 && aligned(x, 16)) {
