@@ -648,14 +648,14 @@ int bnn_binary_conv2d(const uint32_t* x, const uint32_t* packed, const float* xi
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
   // few channels: the filters stay in registers and a wave streams over several tiles, enough
-  // of them that a launch has about 16K waves
+  // of them that a launch has about 32K waves (measured: better than 8K or 16K)
   const bool resident_shape = R == S && Cw <= 4 && (Cw & (Cw - 1)) == 0 && R * S * Cw <= 36;
   if (resident_shape) {
     int tm = pick_tm(Wo, stride == 1);
     if (((tm - 1) * stride + S) * Cw > 64) tm = 7;          // one lane per word of a strip row
     const int64_t wtiles = (Wo + tm - 1) / tm;
     const int64_t tiles_per_image = Ho * wtiles;
-    int64_t tpw = (N * tiles_per_image * kblocks + 16383) / 16384;
+    int64_t tpw = (N * tiles_per_image * kblocks + 32767) / 32768;
     if (tpw > tiles_per_image) tpw = tiles_per_image;
     if (tpw > 64) tpw = 64;
     const int64_t wpi = (tiles_per_image + tpw - 1) / tpw;
