@@ -42,6 +42,8 @@ def parse():
                     help="measure the binary convolution layer instead (detector trunk conv2..conv8); "
                          "prints its own JSON line")
     ap.add_argument("--bnn-batch", type=int, default=64, help="images per step of --bnn")
+    ap.add_argument("--bnn-layers", default="", help="profiling aid: restrict the --bnn step to a comma list of "
+                    "layer names (conv2..conv8)")
     ap.add_argument("--copy-mib", type=int, default=0, help="profiling aid: also run one plain device copy "
                     "of this many MiB, the known-size kernel that FETCH_SIZE / WRITE_SIZE are scaled by")
     return ap.parse_args()
@@ -271,7 +273,7 @@ def per_config_table(seed, peak_ops, with_cpu):
 
 # HBM traffic of one launch of the dominant kernel of --bnn (conv8 at batch 64), measured like
 # HEADLINE_TRAFFIC_BYTES; see profiles/.  None until measured / for any other batch.
-BNN_TRAFFIC_BYTES = None
+BNN_TRAFFIC_BYTES = 15270768   # 13.2 MiB fetched + 1.3 MiB written (profiles/bconv_lds_kernel_conv8_pmc.md)
 
 
 def bnn_main(args):
@@ -293,7 +295,15 @@ def bnn_main(args):
     N = args.bnn_batch
     info = rtc.rtc_device_info()
     layers = []
+    wanted = set(x for x in args.bnn_layers.split(",") if x)
+    if args.copy_mib > 0:
+        src = torch.zeros(args.copy_mib << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
     for i, (name, hw, C, K) in enumerate(bw.DETECTOR_LAYERS):
+        if wanted and name not in wanted:
+            continue
         # activations: random words generated on the device (N x hw x hw x C bits would take minutes on the
         # host); filters and thresholds from the seeded host generators
         g = torch.Generator(device="cuda")
@@ -344,9 +354,9 @@ def bnn_main(args):
     dom = layers[-1]
     dom_ms = per_layer[-1]["kernel_ms"]
     achieved = dom["macs"] / 16 / (dom_ms * 1e-3)
-    roofline = {"bound": "alu", "kernel": "bconv_lds_kernel (conv8: 13x13 map, 1024 -> 1024 channels)",
+    roofline = {"bound": "alu", "kernel": f"bconv_lds_kernel ({dom['name']}: {dom['hw']}x{dom['hw']} map, {dom['C']} -> {dom['K']} channels)",
                 "achieved": round(achieved / 1e12, 4), "peak": round(peak_ops / 1e12, 4), "unit": "TOP/s",
-                "frac": round(achieved / peak_ops, 4), "traffic": BNN_TRAFFIC_BYTES if N == 64 else None,
+                "frac": round(achieved / peak_ops, 4), "traffic": BNN_TRAFFIC_BYTES if N == 64 and dom["name"] == "conv8" else None,
                 "launch_ms": dom_ms, "macs_per_launch": dom["macs"],
                 "tmac_per_s": round(dom["macs"] / dom_ms / 1e9, 1),
                 "note": "a lane-op is one VALU lane-instruction; the kernel needs v_xor_b32 + v_bcnt_u32_b32 per 32 "
