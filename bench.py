@@ -41,7 +41,7 @@ def parse():
     ap.add_argument("--bnn", action="store_true",
                     help="measure the binary convolution layer instead (detector trunk conv2..conv8); "
                          "prints its own JSON line")
-    ap.add_argument("--bnn-batch", type=int, default=64, help="images per step of --bnn")
+    ap.add_argument("--bnn-batch", type=int, default=256, help="images per step of --bnn")
     ap.add_argument("--bnn-layers", default="", help="profiling aid: restrict the --bnn step to a comma list of "
                     "layer names (conv2..conv8)")
     ap.add_argument("--copy-mib", type=int, default=0, help="profiling aid: also run one plain device copy "
@@ -271,9 +271,9 @@ def per_config_table(seed, peak_ops, with_cpu):
     return rows
 
 
-# HBM traffic of one launch of the dominant kernel of --bnn (conv8 at batch 64), measured like
+# HBM traffic of one launch of the dominant kernel of --bnn (conv8 at batch 256), measured like
 # HEADLINE_TRAFFIC_BYTES; see profiles/.  None until measured / for any other batch.
-BNN_TRAFFIC_BYTES = 15270768   # 13.2 MiB fetched + 1.3 MiB written (profiles/bconv_lds_kernel_conv8_pmc.md)
+BNN_TRAFFIC_BYTES = 40881110   # 33.7 MiB fetched + 5.3 MiB written (profiles/bconv_lds_kernel_conv8_pmc.md)
 
 
 def bnn_main(args):
@@ -356,7 +356,7 @@ def bnn_main(args):
     achieved = dom["macs"] / 16 / (dom_ms * 1e-3)
     roofline = {"bound": "alu", "kernel": f"bconv_lds_kernel ({dom['name']}: {dom['hw']}x{dom['hw']} map, {dom['C']} -> {dom['K']} channels)",
                 "achieved": round(achieved / 1e12, 4), "peak": round(peak_ops / 1e12, 4), "unit": "TOP/s",
-                "frac": round(achieved / peak_ops, 4), "traffic": BNN_TRAFFIC_BYTES if N == 64 and dom["name"] == "conv8" else None,
+                "frac": round(achieved / peak_ops, 4), "traffic": BNN_TRAFFIC_BYTES if N == 256 and dom["name"] == "conv8" else None,
                 "launch_ms": dom_ms, "macs_per_launch": dom["macs"],
                 "tmac_per_s": round(dom["macs"] / dom_ms / 1e9, 1),
                 "note": "a lane-op is one VALU lane-instruction; the kernel needs v_xor_b32 + v_bcnt_u32_b32 per 32 "
