@@ -233,6 +233,14 @@ const char* rtc_strerror(int status);
  * Any pointer may be NULL.  Host pointers. */
 int rtc_device_info(int* cu_count, int* clock_khz, int* lds_bytes);
 
+/* Device self-test of the arithmetic identity that the 15-bit flavour of the packed product
+ * kernels rests on: for 16-bit patterns below 0x7C00 the packed three-operand half-float minimum /
+ * maximum equals the integer minimum / maximum of the patterns (denormal patterns included).
+ * Checks every pattern x in [0, 0x7C00) against 4096 partner pairs each (equal values, the range
+ * ends, neighbours and a hash of the rest) and ADDS the number of mismatches to the device word
+ * *mismatches (the caller zeroes it).  0 is the only acceptable outcome. */
+int rtc_selftest_half_minmax(uint32_t* mismatches, void* hip_stream);
+
 /* Measurement aid (not part of the curve algebra).  While enabled, every product kernel that
  * rtc_minplus_conv / rtc_maxplus_deconv / rtc_gpc_step launch is bracketed by a HIP event pair
  * on the call's stream (up to 1024 kernels; helper kernels such as probes and fills are not

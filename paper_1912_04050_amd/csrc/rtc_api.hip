@@ -318,6 +318,12 @@ const char* rtc_strerror(int status) {
   }
 }
 
+int rtc_selftest_half_minmax(uint32_t* mismatches, void* hip_stream) {
+  if (mismatches == nullptr) return RTC_ERR_NULL;
+  if (!aligned(mismatches, 4)) return RTC_ERR_ALIGN;
+  return launch_selftest_half_minmax(mismatches, static_cast<hipStream_t>(hip_stream));
+}
+
 int rtc_device_info(int* cu_count, int* clock_khz, int* lds_bytes) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return RTC_ERR_HIP;

@@ -356,6 +356,36 @@ size_t tropical_workspace_bytes(int64_t batch, int64_t n, int dt) {
   return 0;
 }
 
+namespace {
+
+// see rtc_selftest_half_minmax: one thread per pattern x, 4096 partner pairs (y, z) each
+__global__ __launch_bounds__(256) void selftest_half_minmax_kernel(uint32_t* __restrict__ mismatches) {
+  const uint32_t x = blockIdx.x * 256 + threadIdx.x;
+  if (x >= 0x7C00u) return;
+  uint32_t bad = 0;
+  for (uint32_t j = 0; j < 4096; ++j) {
+    uint32_t y = (x * 2654435761u + j * 40503u) % 0x7C00u;
+    uint32_t z = (x * 40503u + j * 2654435761u + 77u) % 0x7C00u;
+    if (j == 0) { y = x; z = x; }
+    if (j == 1) { y = 0; z = 0x7BFF; }
+    if (j == 2) { y = x ? x - 1 : 0; z = x < 0x7BFF ? x + 1 : x; }
+    const hf2 a = __builtin_bit_cast(hf2, x | (y << 16)), b = __builtin_bit_cast(hf2, y | (z << 16)),
+              c = __builtin_bit_cast(hf2, z | (x << 16));
+    const uint32_t mn = __builtin_bit_cast(uint32_t, __builtin_elementwise_minimum(__builtin_elementwise_minimum(a, b), c));
+    const uint32_t mx = __builtin_bit_cast(uint32_t, __builtin_elementwise_maximum(__builtin_elementwise_maximum(a, b), c));
+    const uint32_t lo = min(min(x, y), z), hi = max(max(x, y), z);
+    bad += (mn != (lo | (lo << 16))) + (mx != (hi | (hi << 16)));
+  }
+  if (bad != 0) atomicAdd(mismatches, bad);
+}
+
+}  // namespace
+
+int launch_selftest_half_minmax(uint32_t* mismatches, hipStream_t stream) {
+  hipLaunchKernelGGL(selftest_half_minmax_kernel, dim3(0x7C00 / 256), dim3(256), 0, stream, mismatches);
+  return hip_ok();
+}
+
 int launch_structure_probe(int op, const void* f, const void* g, int32_t* codes, int64_t batch, int64_t n,
                            int64_t stride_f, int64_t stride_g, int dt, hipStream_t stream) {
   static_assert(kSelSearch == RTC_STRUCTURE_BISECT && kSelEnds == RTC_STRUCTURE_ENDS, "selector codes are public");

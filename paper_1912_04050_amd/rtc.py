@@ -138,6 +138,18 @@ def rtc_set_packed_min_work(batch_times_n_squared: float):
     _check(_lib.rtc_set_packed_min_work(float(batch_times_n_squared)))
 
 
+_lib.rtc_selftest_half_minmax.argtypes = [_vp, _vp]
+_lib.rtc_selftest_half_minmax.restype = _int
+
+
+def rtc_selftest_half_minmax() -> int:
+    """Mismatches of the packed half-float min3 / max3 against integer min / max (must be 0)."""
+    word = torch.zeros(1, dtype=torch.int32, device="cuda")
+    _check(_lib.rtc_selftest_half_minmax(_ptr(word), _stream()))
+    torch.cuda.synchronize()
+    return int(word.item())
+
+
 _lib.rtc_product_structure.argtypes = [_int, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _int, _vp]
 _lib.rtc_product_structure.restype = _int
 RTC_STRUCTURE_GENERAL, RTC_STRUCTURE_BISECT, RTC_STRUCTURE_ENDS = 1, 2, 3

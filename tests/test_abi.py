@@ -96,6 +96,7 @@ def test_other_entry_points_reject_bad_arguments(lib):
     assert lib.rtc_product_structure(2, p, p, p, 1, 8, 8, 8, 0, None) == -8     # RTC_OP_GPC is no product
     assert lib.rtc_product_structure(0, p, p, p, 1, 8, 4, 8, 0, None) == -5
     assert lib.rtc_product_structure(0, p, p, p, 0, 8, 8, 8, 0, None) == -2
+    assert lib.rtc_selftest_half_minmax(None, None) == -1
     lib.rtc_set_packed_small_n.argtypes = [ctypes.c_int64]
     assert lib.rtc_set_packed_small_n(-1) == -2
     assert lib.rtc_set_packed_small_n(4096) == 0

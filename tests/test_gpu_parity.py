@@ -597,3 +597,8 @@ def test_conv_chain(rtc, dtype):
     params = [(5, 10), (3, 25), (4, 0), (7, 40)]
     curves = np.stack([wl.rate_latency(n, R, T, dtype)[None, :] for R, T in params])
     assert np.array_equal(host(rtc.rtc_conv_chain(dev(curves)))[0], wl.rate_latency(n, 3, 75, dtype))
+
+
+def test_half_float_minmax_is_integer_minmax_on_this_device(rtc):
+    """The 15-bit packed flavour relies on it; the kernel checks every pattern below 0x7C00."""
+    assert rtc.rtc_selftest_half_minmax() == 0
