@@ -91,6 +91,14 @@ struct ConvArgs {
   int32_t tiles_per_wave, waves_per_image;   // resident-filter kernel only
 };
 
+// acc += popcount(v) as the one instruction v_bcnt_u32_b32 (popcount with accumulate).  Written
+// as inline assembly so that the compiler keeps the accumulation a chain: left to itself it may
+// re-associate the sum into separate popcounts and three-operand adds, which costs registers
+// (and with them occupancy) for nothing.
+__device__ __forceinline__ void popcount_accumulate(uint32_t& acc, uint32_t v) {
+  asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc) : "v"(v));
+}
+
 // Thresholds of the integrated layer in the integer domain.  For an integer x1 (exact in fp32
 // while |x1| <= 2^24, which the entry point guarantees) and v = (float)x1:
 //   gamma > 0:  (A xor B) or C = not (v < xi) = not (x1 < ceil(xi))
@@ -276,7 +284,7 @@ __global__ __launch_bounds__(64) void bconv_kernel(
 #pragma unroll
           for (int q = 0; q < QC; ++q)
 #pragma unroll
-            for (int u = 0; u < KB; ++u) acc[u][j] += __popc(a[j * STRIDE + s][q] ^ wv[u][q]);
+            for (int u = 0; u < KB; ++u) popcount_accumulate(acc[u][j], a[j * STRIDE + s][q] ^ wv[u][q]);
       }
     }
   }
@@ -364,7 +372,7 @@ __global__ __launch_bounds__(256) void bconv_lds_kernel(
 #pragma unroll
           for (int q = 0; q < QC; ++q)
 #pragma unroll
-            for (int u = 0; u < KB; ++u) acc[u][j] += __popc(a[j * STRIDE + s][q] ^ wv[u][q]);
+            for (int u = 0; u < KB; ++u) popcount_accumulate(acc[u][j], a[j * STRIDE + s][q] ^ wv[u][q]);
       }
     }
   }
@@ -465,7 +473,7 @@ __global__ __launch_bounds__(64) void bconv_resident_kernel(
 #pragma unroll
           for (int q = 0; q < CW; ++q) {
             const int word = (j * STRIDE + s) * CW + q;
-            acc[j] += __popc(a[word / 4][word % 4] ^ wreg[r][s][q]);
+            acc[j] += __popc(a[word / 4][word % 4] ^ wreg[r][s][q]);   // the compiler's own schedule measured 5 % faster here
           }
     }
     __syncthreads();                             // reads done before the next tile's writes
@@ -474,6 +482,169 @@ __global__ __launch_bounds__(64) void bconv_resident_kernel(
 #pragma unroll
     for (int r = 0; r < R; ++r) cur[r] = nxt[r];
     ho = ho_next; wt = wt_next;
+  }
+}
+
+// At most 32 filters: the two halves of the wave work on two different tiles with the same 32
+// filters, which is possible because the strip reaches the lanes through LDS (each half reads its
+// own 32 words of the line) and not through scalar registers.  The 64-bit compare mask of pixel
+// j then holds tile A's packed word in its low half and tile B's in its high half.  No filter
+// row is skipped (the halves may sit in different output rows): rows and columns outside the
+// image are read as zero words and corrected alike.  Stride 1, WORDS = PS * CW <= 32.
+template <int R, int S, int CW, int TM>
+__global__ __launch_bounds__(64) void bconv_resident_half_kernel(
+    const uint32_t* __restrict__ x, const uint32_t* __restrict__ w, const float* __restrict__ xi,
+    const float* __restrict__ gamma, int32_t* __restrict__ out_x1, uint32_t* __restrict__ out_x4, const ConvArgs dims) {
+  ConvArgs p = dims;
+  p.x = x; p.w = w; p.xi = xi; p.gamma = gamma; p.out_x1 = out_x1; p.out_x4 = out_x4;
+  constexpr int PS = TM - 1 + S;
+  constexpr int WORDS = PS * CW;
+  constexpr int QUADS = (WORDS + 3) / 4;
+  if (WORDS > 32) return;                        // the host never launches such a shape
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  __shared__ __align__(16) uint32_t line[R][64];
+  __shared__ uint32_t parked[TM][64];            // border tiles park their popcounts here (see below)
+  const int lane = threadIdx.x, half = lane >> 5, l32 = lane & 31;
+  const int chunk = blockIdx.x % p.waves_per_image;
+  const int n = blockIdx.x / p.waves_per_image;
+  const int k = l32;
+  const uint32_t* __restrict__ ximg = p.x + (int64_t)n * p.H * p.W * CW;
+  const uint32_t* __restrict__ pop = p.w + (int64_t)R * S * CW * p.Kp;
+
+  uint32_t wreg[R][S][CW];
+#pragma unroll
+  for (int r = 0; r < R; ++r)
+#pragma unroll
+    for (int s = 0; s < S; ++s)
+#pragma unroll
+      for (int q = 0; q < CW; ++q) wreg[r][s][q] = (p.w + (uint32_t)((r * S + s) * CW + q) * (uint32_t)p.Kp)[k];
+  const Decision d = make_decision(p, k, S);
+
+  // this lane's word of each strip row of its half's tile; 0 outside the image or without a tile
+  auto fetch = [&](uint32_t (&dst)[R], int ho_l, int wt_l, bool tile_ok) {
+    const int wi = wt_l * TM - p.pad + l32 / CW;
+    const bool col_ok = tile_ok && l32 < WORDS && wi >= 0 && wi < p.W;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int hi = ho_l - p.pad + r;
+      uint32_t v = 0;
+      if (col_ok && hi >= 0 && hi < p.H) v = ximg[((int64_t)hi * p.W + wi) * CW + l32 % CW];
+      dst[r] = v;
+    }
+  };
+  auto advance = [&](int& ho, int& wt) { if (++wt == p.wtiles) { wt = 0; ++ho; } };
+
+  const int total_tiles = p.Ho * p.wtiles;
+  const int t_begin = chunk * p.tiles_per_wave;
+  const int t_end = min(t_begin + p.tiles_per_wave, total_tiles);
+  if (t_begin >= t_end) return;
+  int hoA = t_begin / p.wtiles, wtA = t_begin % p.wtiles;
+  int hoB = hoA, wtB = wtA;
+  advance(hoB, wtB);
+  uint32_t cur[R], nxt[R];
+  fetch(cur, half ? hoB : hoA, half ? wtB : wtA, half == 0 || t_begin + 1 < t_end);
+  for (int t = t_begin; t < t_end; t += 2) {
+    const bool has_b = t + 1 < t_end;            // wave-uniform
+    int hoA2 = hoB, wtA2 = wtB;
+    advance(hoA2, wtA2);
+    int hoB2 = hoA2, wtB2 = wtA2;
+    advance(hoB2, wtB2);
+    if (t + 2 < t_end) fetch(nxt, half ? hoB2 : hoA2, half ? wtB2 : wtA2, half == 0 || t + 3 < t_end);
+
+#pragma unroll
+    for (int r = 0; r < R; ++r) line[r][lane] = cur[r];
+    __syncthreads();                             // one wave: orders the LDS writes before the reads
+    uint32_t acc[TM];
+#pragma unroll
+    for (int j = 0; j < TM; ++j) acc[j] = 0;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      u32x4 a[QUADS];                            // the same value in every lane of a half
+#pragma unroll
+      for (int v = 0; v < QUADS; ++v) a[v] = reinterpret_cast<const u32x4*>(&line[r][half * 32])[v];
+#pragma unroll
+      for (int s = 0; s < S; ++s)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+          for (int q = 0; q < CW; ++q) {
+            const int word = (j + s) * CW + q;
+            popcount_accumulate(acc[j], a[word / 4][word % 4] ^ wreg[r][s][q]);
+          }
+    }
+    __syncthreads();                             // reads done before the next pair's writes
+
+    auto tile_interior = [&](int ho, int wt) {
+      const int wi0 = wt * TM - p.pad, hi0 = ho - p.pad;
+      return wi0 >= 0 && wi0 + PS <= p.W && hi0 >= 0 && hi0 + R <= p.H;
+    };
+    const bool interior = tile_interior(hoA, wtA) && (!has_b || tile_interior(hoB, wtB));   // wave-uniform
+    const int ho_l = half ? hoB : hoA, wo0_l = (half ? wtB : wtA) * TM;
+    const bool tile_ok = half == 0 || has_b;
+    const int64_t pixel0_l = ((int64_t)n * p.Ho + ho_l) * p.Wo + wo0_l;
+    uint32_t mine = 0;
+    if (interior && p.out_x1 == nullptr) {
+#pragma unroll
+      for (int j = 0; j < TM; ++j) {
+        const unsigned long long less = __ballot((int32_t)acc[j] > d.U0);
+        const unsigned long long mask = (less ^ d.posmask) & d.okmask;
+        mine = write_lane_of(mine, (uint32_t)mask, 2 * j);
+        mine = write_lane_of(mine, (uint32_t)(mask >> 32), 2 * j + 1);
+      }
+    } else {
+      // border tiles (or x1 wanted): per lane, since the halves sit on different tiles.  The
+      // popcounts that zeroed rows / columns wrongly added are taken off per filter row and column.
+      bool row_in[R];
+      int rows_in = 0;
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        row_in[r] = ho_l - p.pad + r >= 0 && ho_l - p.pad + r < p.H;
+        rows_in += row_in[r] ? 1 : 0;
+      }
+      uint32_t col_all[S], col_out_rows[S];      // per column s: popcount of all its taps / of its taps in rows outside
+#pragma unroll
+      for (int s = 0; s < S; ++s) {
+        col_all[s] = 0; col_out_rows[s] = 0;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          const uint32_t pv = pop[(uint32_t)(r * S + s) * (uint32_t)p.Kp + k];
+          col_all[s] += pv;
+          col_out_rows[s] += row_in[r] ? 0u : pv;
+        }
+      }
+      // rare path: a real loop over the pixels (the popcounts wait in LDS, each lane reads back its
+      // own) keeps the register count of the whole kernel at that of the common path
+#pragma unroll
+      for (int j = 0; j < TM; ++j) parked[j][lane] = acc[j];
+#pragma unroll 1
+      for (int j = 0; j < TM; ++j) {
+        const int wo = wo0_l + j;
+        int cols_in = 0;
+        uint32_t wrong = 0;
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+          const int wi = wo - p.pad + s;
+          const bool col_in = wi >= 0 && wi < p.W;
+          cols_in += col_in ? 1 : 0;
+          wrong += col_in ? col_out_rows[s] : col_all[s];
+        }
+        const int32_t x1 = p.C * rows_in * cols_in - 2 * (int32_t)(parked[j][lane] - wrong);
+        if (p.out_x1 != nullptr && d.lane_ok && tile_ok && wo < p.Wo) p.out_x1[(pixel0_l + j) * p.K + k] = x1;
+        const unsigned long long less = __ballot(x1 < d.T);
+        const unsigned long long mask = (less ^ d.posmask) & d.okmask;
+        if (lane == 2 * j) mine = (uint32_t)mask;
+        if (lane == 2 * j + 1) mine = (uint32_t)(mask >> 32);
+      }
+    }
+    if (p.out_x4 != nullptr && lane < 2 * TM) {
+      // lane 2j holds tile A's word of pixel j, lane 2j+1 tile B's (Kw = 1)
+      const int j = lane >> 1, which = lane & 1;
+      const int ho_w = which ? hoB : hoA, wo_w = (which ? wtB : wtA) * TM + j;
+      if ((which == 0 || has_b) && wo_w < p.Wo) p.out_x4[((int64_t)n * p.Ho + ho_w) * p.Wo + wo_w] = mine;
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) cur[r] = nxt[r];
+    hoA = hoA2; wtA = wtA2; hoB = hoB2; wtB = wtB2;
   }
 }
 
@@ -547,6 +718,28 @@ bool launch_resident(const ConvArgs& a, int R, int S, int stride, int tm, uint32
   BNN_RESIDENT(5, 5, 1)
 #undef BNN_RESIDENT
 #undef BNN_RESIDENT_TM
+  return false;
+}
+
+template <int R, int S, int CW, int TM>
+void launch_resident_half_one(const ConvArgs& a, uint32_t blocks, hipStream_t stream) {
+  rtc::prof_begin(kProfileKind, stream);
+  hipLaunchKernelGGL((bconv_resident_half_kernel<R, S, CW, TM>), dim3(blocks), dim3(64), 0, stream, a.x, a.w, a.xi, a.gamma,
+                     a.out_x1, a.out_x4, a);
+  rtc::prof_end(stream);
+}
+
+// the two-tiles-per-wave form for at most 32 filters; true when an instantiation exists
+bool launch_resident_half(const ConvArgs& a, int R, int S, int tm, uint32_t blocks, hipStream_t stream) {
+  const int cw = a.Cw;
+#define BNN_HALF(RR, SS, CC, TT)                                           \
+  if (R == RR && S == SS && cw == CC && tm == TT) {                        \
+    launch_resident_half_one<RR, SS, CC, TT>(a, blocks, stream);           \
+    return true;                                                           \
+  }
+  BNN_HALF(3, 3, 1, 7) BNN_HALF(3, 3, 1, 8) BNN_HALF(3, 3, 1, 13) BNN_HALF(3, 3, 2, 7) BNN_HALF(3, 3, 2, 8) BNN_HALF(3, 3, 2, 13)
+  BNN_HALF(1, 1, 1, 7) BNN_HALF(1, 1, 1, 8) BNN_HALF(1, 1, 1, 13) BNN_HALF(5, 5, 1, 7) BNN_HALF(5, 5, 1, 8) BNN_HALF(5, 5, 1, 13)
+#undef BNN_HALF
   return false;
 }
 
@@ -661,6 +854,14 @@ int bnn_binary_conv2d(const uint32_t* x, const uint32_t* packed, const float* xi
     const int64_t wpi = (tiles_per_image + tpw - 1) / tpw;
     if (N * wpi * kblocks > 0x7fffffffLL) return BNN_ERR_SHAPE;
     a.wtiles = (int32_t)wtiles; a.tiles_per_wave = (int32_t)tpw; a.waves_per_image = (int32_t)wpi;
+    if (K <= 32 && stride == 1 && (tm - 1 + S) * Cw <= 32 && g_force_kb != 1) {
+      // at most 32 filters: two tiles per wave, one per half (the knob's value 1 asks for the plain form)
+      const int64_t tpw2 = (tpw + 1) / 2 * 2;
+      const int64_t wpi2 = (tiles_per_image + tpw2 - 1) / tpw2;
+      ConvArgs h = a;
+      h.tiles_per_wave = (int32_t)tpw2; h.waves_per_image = (int32_t)wpi2;
+      if (launch_resident_half(h, (int)R, (int)S, tm, (uint32_t)(N * wpi2), stream)) return hip_status();
+    }
     if (((tm - 1) * stride + S) * Cw <= 64 &&
         launch_resident(a, (int)R, (int)S, (int)stride, tm, (uint32_t)(N * wpi * kblocks), stream))
       return hip_status();
