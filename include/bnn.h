@@ -67,7 +67,8 @@ int bnn_binary_conv2d(const uint32_t* x, const uint32_t* packed, const float* xi
                       int64_t K, int64_t R, int64_t S, int64_t stride, int64_t pad, void* hip_stream);
 
 /* Planner knobs (results do not depend on them; process-wide, not thread-safe): output pixels
- * per wavefront (7, 8 or 13; 13 only where stride is 1) and blocks of 64 filters per wavefront
+ * per wavefront (7, 8 or 13; 13 only where stride is 1; tiles of 26 were measured slower) and blocks of 64
+ * filters per wavefront
  * (1 or 2; 2 only for pixels of a multiple of 4 words and an even number of blocks).
  * 0 = choose automatically.  A value that does not apply to a shape is ignored for that shape. */
 int bnn_set_planner(int tile_pixels, int filter_blocks);

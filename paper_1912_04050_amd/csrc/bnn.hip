@@ -118,14 +118,17 @@ __device__ __forceinline__ uint32_t write_lane(uint32_t v, uint32_t s) {
   return v;
 }
 
-// the same for a lane index that is a constant only after loop unrolling (0..25)
+// the same for a lane index that is a constant only after loop unrolling (0..51)
 __device__ __forceinline__ uint32_t write_lane_of(uint32_t v, uint32_t s, int lane) {
   switch (lane) {
 #define BNN_LANE(L) case L: return write_lane<L>(v, s);
     BNN_LANE(0) BNN_LANE(1) BNN_LANE(2) BNN_LANE(3) BNN_LANE(4) BNN_LANE(5) BNN_LANE(6) BNN_LANE(7)
     BNN_LANE(8) BNN_LANE(9) BNN_LANE(10) BNN_LANE(11) BNN_LANE(12) BNN_LANE(13) BNN_LANE(14) BNN_LANE(15)
     BNN_LANE(16) BNN_LANE(17) BNN_LANE(18) BNN_LANE(19) BNN_LANE(20) BNN_LANE(21) BNN_LANE(22) BNN_LANE(23)
-    BNN_LANE(24) BNN_LANE(25)
+    BNN_LANE(24) BNN_LANE(25) BNN_LANE(26) BNN_LANE(27) BNN_LANE(28) BNN_LANE(29) BNN_LANE(30) BNN_LANE(31)
+    BNN_LANE(32) BNN_LANE(33) BNN_LANE(34) BNN_LANE(35) BNN_LANE(36) BNN_LANE(37) BNN_LANE(38) BNN_LANE(39)
+    BNN_LANE(40) BNN_LANE(41) BNN_LANE(42) BNN_LANE(43) BNN_LANE(44) BNN_LANE(45) BNN_LANE(46) BNN_LANE(47)
+    BNN_LANE(48) BNN_LANE(49) BNN_LANE(50) BNN_LANE(51)
 #undef BNN_LANE
     default: return v;
   }
@@ -134,7 +137,6 @@ __device__ __forceinline__ uint32_t write_lane_of(uint32_t v, uint32_t s, int la
 // Per-lane constants of the integrated layer for the 64 filters of one block.
 struct Decision {
   int32_t T;                       // x1 < T decides (see integer_threshold)
-  int32_t U0;                      // interior pixels: x1 < T  <=>  popcount > U0 = floor((R S C - T) / 2)
   unsigned long long posmask;      // lanes with gamma > 0
   unsigned long long okmask;       // lanes whose filter exists
   bool lane_ok;
@@ -146,7 +148,6 @@ __device__ __forceinline__ Decision make_decision(const ConvArgs& p, int k, int 
   d.lane_ok = k < p.K;
   const bool positive = fused && d.lane_ok && p.gamma[k] > 0.f;
   d.T = fused && d.lane_ok ? integer_threshold(p.xi[k], positive) : 0;
-  d.U0 = (p.R * S * p.C - d.T) >> 1;          // arithmetic shift = floor for either sign
   d.posmask = __ballot(positive);
   d.okmask = __ballot(d.lane_ok);
   return d;
@@ -165,36 +166,52 @@ __device__ __forceinline__ void finish_tile(const ConvArgs& p, const Decision& d
   const int64_t pixel0 = ((int64_t)n * p.Ho + ho) * p.Wo + wo0;
   const int hi0 = ho * STRIDE - p.pad;
   uint32_t mine = 0;
-  if (interior && p.out_x1 == nullptr) {
-    // every tap inside the image and no x1 wanted: one integer compare per pixel (pixels beyond
-    // the end of the output row are computed too and never stored)
+  // Pixels all of whose columns lie inside the image need no correction (filter rows outside
+  // were skipped, not zeroed): x1 = Len - 2 popcount with Len = C S rows_inside, so
+  // x1 < T  <=>  popcount > U = floor((Len - T) / 2): one integer compare.  Only the one or two
+  // pixels of a border tile whose columns reach outside take the long way.
+  (void)interior;
+  const int32_t U = (p.C * rows_inside * S - d.T) >> 1;       // arithmetic shift = floor for either sign
+  constexpr int PS = (TM - 1) * STRIDE + S;
+  const int wi0 = wo0 * STRIDE - p.pad;
+  const bool tile_cols_inside = wi0 >= 0 && wi0 + PS <= p.W;  // wave-uniform
+  if (tile_cols_inside && p.out_x1 == nullptr) {
+    // the common case, straight-line (pixels beyond the end of the output row are computed too
+    // and never stored)
 #pragma unroll
     for (int j = 0; j < TM; ++j) {
-      const unsigned long long less = __ballot((int32_t)acc[j] > d.U0);      // lanes with x1 < T
+      const unsigned long long less = __ballot((int32_t)acc[j] > U);
       const unsigned long long mask = (less ^ d.posmask) & d.okmask;
       mine = write_lane_of(mine, (uint32_t)mask, 2 * j);
       mine = write_lane_of(mine, (uint32_t)(mask >> 32), 2 * j + 1);
     }
-  } else {
+  } else
 #pragma unroll
-    for (int j = 0; j < TM; ++j) {
-      if (wo0 + j >= p.Wo) break;                // wave-uniform
+  for (int j = 0; j < TM; ++j) {
+    const int wi_first = (wo0 + j) * STRIDE - p.pad;
+    const bool cols_inside_all = wi_first >= 0 && wi_first + S <= p.W;    // wave-uniform
+    unsigned long long less;                     // lanes with x1 < T
+    if (cols_inside_all && p.out_x1 == nullptr) {
+      less = __ballot((int32_t)acc[j] > U);
+    } else if (wo0 + j < p.Wo) {
       int cols_inside = 0;
       uint32_t wrong = 0;
 #pragma unroll
       for (int s = 0; s < S; ++s) {
-        const int wi = (wo0 + j) * STRIDE - p.pad + s;
+        const int wi = wi_first + s;
         if (wi >= 0 && wi < p.W) { ++cols_inside; continue; }
         for (int r = 0; r < p.R; ++r)
           if (hi0 + r >= 0 && hi0 + r < p.H) wrong += pop[(uint32_t)(r * S + s) * (uint32_t)p.Kp + k];
       }
       const int32_t x1 = p.C * rows_inside * cols_inside - 2 * (int32_t)(acc[j] - wrong);
       if (p.out_x1 != nullptr && d.lane_ok) p.out_x1[(pixel0 + j) * p.K + k] = x1;
-      const unsigned long long less = __ballot(x1 < d.T);
-      const unsigned long long mask = (less ^ d.posmask) & d.okmask;
-      mine = write_lane_of(mine, (uint32_t)mask, 2 * j);
-      mine = write_lane_of(mine, (uint32_t)(mask >> 32), 2 * j + 1);
+      less = __ballot(x1 < d.T);
+    } else {
+      less = 0;                                  // beyond the end of the output row: never stored
     }
+    const unsigned long long mask = (less ^ d.posmask) & d.okmask;
+    mine = write_lane_of(mine, (uint32_t)mask, 2 * j);
+    mine = write_lane_of(mine, (uint32_t)(mask >> 32), 2 * j + 1);
   }
   if (p.out_x4 != nullptr) {
     // lanes 2j and 2j+1 hold the low and high word of pixel j
@@ -503,7 +520,6 @@ __global__ __launch_bounds__(64) void bconv_resident_half_kernel(
   if (WORDS > 32) return;                        // the host never launches such a shape
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   __shared__ __align__(16) uint32_t line[R][64];
-  __shared__ uint32_t parked[TM][64];            // border tiles park their popcounts here (see below)
   const int lane = threadIdx.x, half = lane >> 5, l32 = lane & 31;
   const int chunk = blockIdx.x % p.waves_per_image;
   const int n = blockIdx.x / p.waves_per_image;
@@ -519,6 +535,11 @@ __global__ __launch_bounds__(64) void bconv_resident_half_kernel(
 #pragma unroll
       for (int q = 0; q < CW; ++q) wreg[r][s][q] = (p.w + (uint32_t)((r * S + s) * CW + q) * (uint32_t)p.Kp)[k];
   const Decision d = make_decision(p, k, S);
+  uint32_t popv[R][S];                           // popcount of each tap of this lane's filter (border corrections)
+#pragma unroll
+  for (int r = 0; r < R; ++r)
+#pragma unroll
+    for (int s = 0; s < S; ++s) popv[r][s] = pop[(uint32_t)(r * S + s) * (uint32_t)p.Kp + k];
 
   // this lane's word of each strip row of its half's tile; 0 outside the image or without a tile
   auto fetch = [&](uint32_t (&dst)[R], int ho_l, int wt_l, bool tile_ok) {
@@ -574,67 +595,63 @@ __global__ __launch_bounds__(64) void bconv_resident_half_kernel(
     }
     __syncthreads();                             // reads done before the next pair's writes
 
-    auto tile_interior = [&](int ho, int wt) {
-      const int wi0 = wt * TM - p.pad, hi0 = ho - p.pad;
-      return wi0 >= 0 && wi0 + PS <= p.W && hi0 >= 0 && hi0 + R <= p.H;
-    };
-    const bool interior = tile_interior(hoA, wtA) && (!has_b || tile_interior(hoB, wtB));   // wave-uniform
+    // Per lane (the halves sit on different tiles): filter rows outside the image were read as
+    // zero words, which added popcount(w) of their taps; with those taken off,
+    // x1 = C S rows_in - 2 (popcount - wrong_rows), so for pixels whose columns all lie inside
+    // x1 < T  <=>  popcount > U = floor((C S rows_in + 2 wrong_rows - T) / 2): one compare.
     const int ho_l = half ? hoB : hoA, wo0_l = (half ? wtB : wtA) * TM;
     const bool tile_ok = half == 0 || has_b;
     const int64_t pixel0_l = ((int64_t)n * p.Ho + ho_l) * p.Wo + wo0_l;
+    bool row_in[R];
+    int rows_in = 0;
+    uint32_t wrong_rows = 0;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      row_in[r] = ho_l - p.pad + r >= 0 && ho_l - p.pad + r < p.H;
+      rows_in += row_in[r] ? 1 : 0;
+#pragma unroll
+      for (int s = 0; s < S; ++s) wrong_rows += row_in[r] ? 0u : popv[r][s];
+    }
+    const int32_t U = (p.C * rows_in * S + 2 * (int32_t)wrong_rows - d.T) >> 1;
     uint32_t mine = 0;
-    if (interior && p.out_x1 == nullptr) {
+    const int wi0A = wtA * TM - p.pad, wi0B = wtB * TM - p.pad;
+    const bool tiles_cols_inside = wi0A >= 0 && wi0A + PS <= p.W && (!has_b || (wi0B >= 0 && wi0B + PS <= p.W));
+    if (tiles_cols_inside && p.out_x1 == nullptr) {
+      // the common case, straight-line
 #pragma unroll
       for (int j = 0; j < TM; ++j) {
-        const unsigned long long less = __ballot((int32_t)acc[j] > d.U0);
+        const unsigned long long less = __ballot((int32_t)acc[j] > U);
         const unsigned long long mask = (less ^ d.posmask) & d.okmask;
         mine = write_lane_of(mine, (uint32_t)mask, 2 * j);
         mine = write_lane_of(mine, (uint32_t)(mask >> 32), 2 * j + 1);
       }
-    } else {
-      // border tiles (or x1 wanted): per lane, since the halves sit on different tiles.  The
-      // popcounts that zeroed rows / columns wrongly added are taken off per filter row and column.
-      bool row_in[R];
-      int rows_in = 0;
+    } else
 #pragma unroll
-      for (int r = 0; r < R; ++r) {
-        row_in[r] = ho_l - p.pad + r >= 0 && ho_l - p.pad + r < p.H;
-        rows_in += row_in[r] ? 1 : 0;
-      }
-      uint32_t col_all[S], col_out_rows[S];      // per column s: popcount of all its taps / of its taps in rows outside
-#pragma unroll
-      for (int s = 0; s < S; ++s) {
-        col_all[s] = 0; col_out_rows[s] = 0;
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-          const uint32_t pv = pop[(uint32_t)(r * S + s) * (uint32_t)p.Kp + k];
-          col_all[s] += pv;
-          col_out_rows[s] += row_in[r] ? 0u : pv;
-        }
-      }
-      // rare path: a real loop over the pixels (the popcounts wait in LDS, each lane reads back its
-      // own) keeps the register count of the whole kernel at that of the common path
-#pragma unroll
-      for (int j = 0; j < TM; ++j) parked[j][lane] = acc[j];
-#pragma unroll 1
-      for (int j = 0; j < TM; ++j) {
+    for (int j = 0; j < TM; ++j) {
+      const int wiA = wtA * TM + j - p.pad, wiB = wtB * TM + j - p.pad;
+      const bool cols_all = wiA >= 0 && wiA + S <= p.W && (!has_b || (wiB >= 0 && wiB + S <= p.W));   // wave-uniform
+      unsigned long long less;                   // lanes with x1 < T
+      if (cols_all && p.out_x1 == nullptr) {
+        less = __ballot((int32_t)acc[j] > U);
+      } else {
         const int wo = wo0_l + j;
         int cols_in = 0;
-        uint32_t wrong = 0;
+        uint32_t wrong = wrong_rows;
 #pragma unroll
         for (int s = 0; s < S; ++s) {
           const int wi = wo - p.pad + s;
           const bool col_in = wi >= 0 && wi < p.W;
           cols_in += col_in ? 1 : 0;
-          wrong += col_in ? col_out_rows[s] : col_all[s];
+#pragma unroll
+          for (int r = 0; r < R; ++r) wrong += (!col_in && row_in[r]) ? popv[r][s] : 0u;
         }
-        const int32_t x1 = p.C * rows_in * cols_in - 2 * (int32_t)(parked[j][lane] - wrong);
+        const int32_t x1 = p.C * rows_in * cols_in - 2 * (int32_t)(acc[j] - wrong);
         if (p.out_x1 != nullptr && d.lane_ok && tile_ok && wo < p.Wo) p.out_x1[(pixel0_l + j) * p.K + k] = x1;
-        const unsigned long long less = __ballot(x1 < d.T);
-        const unsigned long long mask = (less ^ d.posmask) & d.okmask;
-        if (lane == 2 * j) mine = (uint32_t)mask;
-        if (lane == 2 * j + 1) mine = (uint32_t)(mask >> 32);
+        less = __ballot(x1 < d.T);
       }
+      const unsigned long long mask = (less ^ d.posmask) & d.okmask;
+      mine = write_lane_of(mine, (uint32_t)mask, 2 * j);
+      mine = write_lane_of(mine, (uint32_t)(mask >> 32), 2 * j + 1);
     }
     if (p.out_x4 != nullptr && lane < 2 * TM) {
       // lane 2j holds tile A's word of pixel j, lane 2j+1 tile B's (Kw = 1)
