@@ -439,15 +439,19 @@ __global__ __launch_bounds__(64) void bconv_resident_kernel(
       for (int q = 0; q < CW; ++q) wreg[r][s][q] = (p.w + (uint32_t)((r * S + s) * CW + q) * (uint32_t)p.Kp)[k];
   const Decision d = make_decision(p, k, S);
 
-  // lane i's word of each strip row of the tile (ho, wt); 0 outside the image
+  // lane i's word of each strip row of the tile (ho, wt); 0 outside the image.  Offsets inside an
+  // image fit 32 bits (checked by the entry point).
+  const int lane_pixel = lane / CW, lane_word = lane % CW;
+  const uint32_t row_words = (uint32_t)p.W * CW;
   auto fetch = [&](uint32_t (&dst)[R], int ho, int wt) {
-    const int wi = wt * TM * STRIDE - p.pad + lane / CW;
-    const bool col_ok = lane < WORDS && wi >= 0 && wi < p.W;
+    const int wi = wt * TM * STRIDE - p.pad + lane_pixel;
+    const bool col_ok = lane < WORDS && (uint32_t)wi < (uint32_t)p.W;
+    const uint32_t col_off = (uint32_t)wi * CW + lane_word;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       const int hi = ho * STRIDE - p.pad + r;
       uint32_t v = 0;
-      if (col_ok && hi >= 0 && hi < p.H) v = ximg[((int64_t)hi * p.W + wi) * CW + lane % CW];
+      if (col_ok && (uint32_t)hi < (uint32_t)p.H) v = ximg[(uint32_t)hi * row_words + col_off];
       dst[r] = v;
     }
   };
@@ -542,14 +546,17 @@ __global__ __launch_bounds__(64) void bconv_resident_half_kernel(
     for (int s = 0; s < S; ++s) popv[r][s] = pop[(uint32_t)(r * S + s) * (uint32_t)p.Kp + k];
 
   // this lane's word of each strip row of its half's tile; 0 outside the image or without a tile
+  const int lane_pixel = l32 / CW, lane_word = l32 % CW;
+  const uint32_t row_words = (uint32_t)p.W * CW;   // offsets inside an image fit 32 bits (checked by the entry point)
   auto fetch = [&](uint32_t (&dst)[R], int ho_l, int wt_l, bool tile_ok) {
-    const int wi = wt_l * TM - p.pad + l32 / CW;
-    const bool col_ok = tile_ok && l32 < WORDS && wi >= 0 && wi < p.W;
+    const int wi = wt_l * TM - p.pad + lane_pixel;
+    const bool col_ok = tile_ok && l32 < WORDS && (uint32_t)wi < (uint32_t)p.W;
+    const uint32_t col_off = (uint32_t)wi * CW + lane_word;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       const int hi = ho_l - p.pad + r;
       uint32_t v = 0;
-      if (col_ok && hi >= 0 && hi < p.H) v = ximg[((int64_t)hi * p.W + wi) * CW + l32 % CW];
+      if (col_ok && (uint32_t)hi < (uint32_t)p.H) v = ximg[(uint32_t)hi * row_words + col_off];
       dst[r] = v;
     }
   };
@@ -845,9 +852,9 @@ int bnn_binary_conv2d(const uint32_t* x, const uint32_t* packed, const float* xi
     return BNN_ERR_ALIGN;
   const int64_t Ho = (H + 2 * pad - R) / stride + 1, Wo = (W + 2 * pad - S) / stride + 1;
   const int64_t Cw = (C + 31) / 32, Kp = (K + 63) / 64 * 64, Kw = (K + 31) / 32;
-  // offsets inside an input row and inside the filter bank are formed in 32 bits
+  // offsets inside one image and inside the filter bank are formed in 32 bits
   // |x1| <= R S C must convert to fp32 exactly (the threshold comparison is an fp32 one)
-  if (R * S * C > (1 << 24) || bnn_weight_words(K, R, S, C) > 0x7fffffffULL || W * Cw > 0x7fffffffLL) return BNN_ERR_SHAPE;
+  if (R * S * C > (1 << 24) || bnn_weight_words(K, R, S, C) > 0x7fffffffULL || H * W * Cw > 0x7fffffffLL) return BNN_ERR_SHAPE;
   const int64_t kblocks = Kp / 64;
   const int qc = Cw % 4 == 0 ? 4 : Cw % 2 == 0 ? 2 : 1;
   ConvArgs a;
