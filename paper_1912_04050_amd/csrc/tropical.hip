@@ -62,6 +62,20 @@ __global__ __launch_bounds__(64) void tropical_kernel(const TropicalArgs p) {
   tropical_body<T, OutT, OP, R, ATOMIC>(p, lds, blockIdx.x);
 }
 
+// The same work for a launch most of whose rows are expected to be handled elsewhere (the 64-bit
+// kernel behind the range probe): `parts` workgroups per row, each looks at its row's selector
+// once and either leaves or walks every parts-th item of the row (items are numbered rows
+// fastest).  A full grid of workgroups that only find out that they have nothing to do costs
+// ~15 us of dispatch per call.
+template <typename T, typename OutT, int OP, int R>
+__global__ __launch_bounds__(64) void tropical_rows_kernel(const TropicalArgs p, uint32_t items_per_row, uint32_t parts) {
+  __shared__ __align__(16) unsigned char lds[lds_bytes<T, R>()];
+  const uint32_t row = blockIdx.x % (uint32_t)p.batch, part = blockIdx.x / (uint32_t)p.batch;
+  if (p.sel != nullptr && p.sel[row] != p.sel_want) return;
+  for (uint32_t j = part; j < items_per_row; j += parts)
+    tropical_body<T, OutT, OP, R, true>(p, lds, j * (uint32_t)p.batch + row);
+}
+
 // One launch for an int32 product with the packed path: the first n_packed workgroups are
 // items of the packed kernel, the rest are items of the 32-bit kernel (which skip the chunks
 // the packed items own).  Issuing both kinds together keeps the machine full whatever share of
@@ -149,8 +163,17 @@ int run_product(const T* a, int64_t stride_a, const T* b, int64_t stride_b, OutT
   if (pl.atomic || force_atomic) {
     if (!prefilled) launch_fill<OutT, OP>(out, batch * n, stream);
     prof_begin(RTC_PROFILE_KIND(dtype_code, 0, OP), stream);
-    hipLaunchKernelGGL((tropical_kernel<T, OutT, OP, R, true>), dim3((uint32_t)pl.items), dim3(64), 0,
-                       stream, args);
+    if (sel != nullptr && sizeof(T) == 8 && pl.items > 8192) {
+      const uint32_t items_per_row = (uint32_t)(pl.items / batch);
+      uint32_t parts = (uint32_t)(4096 / batch);
+      if (parts < 1) parts = 1;
+      if (parts > items_per_row) parts = items_per_row;
+      hipLaunchKernelGGL((tropical_rows_kernel<T, OutT, OP, R>), dim3((uint32_t)batch * parts), dim3(64), 0, stream,
+                         args, items_per_row, parts);
+    } else {
+      hipLaunchKernelGGL((tropical_kernel<T, OutT, OP, R, true>), dim3((uint32_t)pl.items), dim3(64), 0,
+                         stream, args);
+    }
   } else {
     prof_begin(RTC_PROFILE_KIND(dtype_code, 0, OP), stream);
     hipLaunchKernelGGL((tropical_kernel<T, OutT, OP, R, false>), dim3((uint32_t)pl.items), dim3(64), 0,
@@ -303,8 +326,12 @@ int run_typed(const void* f, const void* g, void* out, int64_t batch, int64_t n,
 size_t narrow_base_offset(int64_t batch, int64_t n) {
   return ((size_t)(2 * batch * n + batch) * sizeof(int32_t) + 255) / 256 * 256;
 }
-size_t narrow_bytes(int64_t batch, int64_t n) {
+constexpr int kProbeMaxSegs = 16;   // segments per row of the two-pass range probe
+size_t narrow_partial_offset(int64_t batch, int64_t n) {
   return narrow_base_offset(batch, n) + ((size_t)batch * sizeof(int64_t) + 255) / 256 * 256;
+}
+size_t narrow_bytes(int64_t batch, int64_t n) {
+  return narrow_partial_offset(batch, n) + ((size_t)batch * kProbeMaxSegs * 5 * sizeof(int64_t) + 255) / 256 * 256;
 }
 
 template <int OP>
@@ -317,11 +344,21 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
   int64_t* base = reinterpret_cast<int64_t*>(static_cast<char*>(ws) + narrow_base_offset(batch, n));
   char* wsp = static_cast<char*>(ws) + narrow_bytes(batch, n);
   const PackLayout L = pack_layout(batch, n);
-  hipLaunchKernelGGL(probe_narrow_kernel, dim3((uint32_t)batch), dim3(1024), 0, stream,
+  // long rows and few of them: several workgroups per row, extrema in a first pass
+  int segs = 1;
+  while (segs < kProbeMaxSegs && batch * segs < 512 && n / (2 * segs) >= 4096) segs *= 2;
+  int64_t* partial = reinterpret_cast<int64_t*>(static_cast<char*>(ws) + narrow_partial_offset(batch, n));
+  const bool structure = packed_worthwhile(batch, n);
+  if (segs > 1)
+    hipLaunchKernelGGL(probe_partial_kernel, dim3((uint32_t)(batch * segs)), dim3(1024), 0, stream,
+                       static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g, (int)n,
+                       structure, segs, partial);
+  hipLaunchKernelGGL(probe_narrow_kernel, dim3((uint32_t)(batch * segs)), dim3(1024), 0, stream,
                      static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g,
-                     (int)n, OP, packed_worthwhile(batch, n), f32, g32, ok, base,
+                     (int)n, OP, structure, f32, g32, ok, base,
                      reinterpret_cast<int32_t*>(wsp + L.off_ok),
-                     reinterpret_cast<int32_t*>(wsp + L.off_rho), dev_flags);
+                     reinterpret_cast<int32_t*>(wsp + L.off_rho), dev_flags, segs,
+                     segs > 1 ? partial : (const int64_t*)nullptr);
   // Several kernels see every row; the selector makes each row run in exactly one family.
   // The output is filled once with the identity, before all of them.
   launch_fill<int64_t, OP>(static_cast<int64_t*>(out), batch * n, stream);

@@ -128,6 +128,51 @@ __global__ __launch_bounds__(1024) void probe_kernel(const T* __restrict__ f, in
   }
 }
 
+// First half of the range probe of long int64 rows: extrema and shape bits of one segment of
+// one row pair, [fmin, fmax, gmin, gmax, bits] at partial[(row * segs + seg) * 5].
+__global__ __launch_bounds__(1024) void probe_partial_kernel(const int64_t* __restrict__ f, int64_t stride_f,
+                                                             const int64_t* __restrict__ g, int64_t stride_g,
+                                                             int n, bool structure, int segs,
+                                                             int64_t* __restrict__ partial) {
+  __shared__ int64_t red[4][16];
+  __shared__ int s_bits[16];
+  const int row = blockIdx.x / segs, seg = blockIdx.x % segs;
+  const int seg_len = (n + segs - 1) / segs;
+  const int i_begin = seg * seg_len, i_end = min(n, i_begin + seg_len);
+  const int64_t* fr = f + (int64_t)row * stride_f;
+  const int64_t* gr = g + (int64_t)row * stride_g;
+  int64_t fmin = INT64_MAX, fmax = INT64_MIN, gmin = INT64_MAX, gmax = INT64_MIN;
+  int bits = structure ? 15 : 0;
+  for (int i = i_begin + threadIdx.x; i < i_end; i += blockDim.x) {
+    const int64_t fv = fr[i], gv = gr[i];
+    fmin = sel_min(fmin, fv); fmax = sel_max(fmax, fv);
+    gmin = sel_min(gmin, gv); gmax = sel_max(gmax, gv);
+    if (bits != 0 && i >= 1 && i <= n - 2) bits &= second_diff_bits(fr, i) | (second_diff_bits(gr, i) << 2);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    fmin = sel_min(fmin, __shfl_xor(fmin, off)); fmax = sel_max(fmax, __shfl_xor(fmax, off));
+    gmin = sel_min(gmin, __shfl_xor(gmin, off)); gmax = sel_max(gmax, __shfl_xor(gmax, off));
+    bits &= __shfl_xor(bits, off);
+  }
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) {
+    red[0][wave] = fmin; red[1][wave] = fmax; red[2][wave] = gmin; red[3][wave] = gmax;
+    s_bits[wave] = bits;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int nw = (blockDim.x + 63) >> 6;
+    for (int w = 1; w < nw; ++w) {
+      fmin = sel_min(fmin, red[0][w]); fmax = sel_max(fmax, red[1][w]);
+      gmin = sel_min(gmin, red[2][w]); gmax = sel_max(gmax, red[3][w]);
+      bits &= s_bits[w];
+    }
+    int64_t* q = partial + ((int64_t)row * segs + seg) * 5;
+    q[0] = fmin; q[1] = fmax; q[2] = gmin; q[3] = gmax; q[4] = bits;
+  }
+}
+
 // Range probe of one int64 row pair.  A row whose two value ranges (max - min) are below 2^30
 // is re-based to its minima and copied as int32: every candidate of the re-based rows fits
 // 32 bits, so the 32-bit kernels compute it exactly and add `out_base` (f_min + g_min, or
@@ -143,18 +188,32 @@ __global__ __launch_bounds__(1024) void probe_narrow_kernel(const int64_t* __res
                                                             int64_t* __restrict__ out_base,
                                                             int32_t* __restrict__ pack_ok,
                                                             int32_t* __restrict__ rho,
-                                                            int32_t* __restrict__ dev_flags) {
+                                                            int32_t* __restrict__ dev_flags, int segs,
+                                                            const int64_t* __restrict__ partial) {
   __shared__ int64_t red[4][16];
   __shared__ int64_t s_base[2];
   __shared__ int s_narrow;
   __shared__ int s_bits[16];
   const bool deconv = op_sub(op);
-  const int row = blockIdx.x;
+  // long rows are cut into `segs` segments, one workgroup each: the row's extrema and shape bits
+  // then come from probe_partial_kernel's table and every workgroup repeats the (cheap)
+  // decision; segment 0 publishes it, every segment copies its own part
+  const int row = blockIdx.x / segs, seg = blockIdx.x % segs;
+  const int seg_len = (n + segs - 1) / segs;
+  const int i_begin = seg * seg_len, i_end = min(n, i_begin + seg_len);
   const int64_t* fr = f + (int64_t)row * stride_f;
   const int64_t* gr = g + (int64_t)row * stride_g;
   int64_t fmin = INT64_MAX, fmax = INT64_MIN, gmin = INT64_MAX, gmax = INT64_MIN;
   int bits = structure ? 15 : 0;
-  for (int i = threadIdx.x; i < n; i += blockDim.x) {
+  if (partial != nullptr && threadIdx.x == 0) {
+    for (int sg = 0; sg < segs; ++sg) {
+      const int64_t* q = partial + ((int64_t)row * segs + sg) * 5;
+      fmin = sel_min(fmin, q[0]); fmax = sel_max(fmax, q[1]);
+      gmin = sel_min(gmin, q[2]); gmax = sel_max(gmax, q[3]);
+      bits &= (int)q[4];
+    }
+  }
+  for (int i = threadIdx.x; partial == nullptr && i < n; i += blockDim.x) {
     const int64_t fv = fr[i], gv = gr[i];
     fmin = sel_min(fmin, fv); fmax = sel_max(fmax, fv);
     gmin = sel_min(gmin, gv); gmax = sel_max(gmax, gv);
@@ -182,21 +241,24 @@ __global__ __launch_bounds__(1024) void probe_narrow_kernel(const int64_t* __res
     int64_t dummy;
     const bool bad = deconv ? (__builtin_sub_overflow(fmax, gmin, &dummy) || __builtin_sub_overflow(fmin, gmax, &dummy))
                             : (__builtin_add_overflow(fmax, gmax, &dummy) || __builtin_add_overflow(fmin, gmin, &dummy));
-    if (bad && dev_flags) atomicOr(dev_flags, RTC_FLAG_OVERFLOW);
+    const bool publish = seg == 0;
+    if (bad && dev_flags && publish) atomicOr(dev_flags, RTC_FLAG_OVERFLOW);
     const uint64_t frange = (uint64_t)fmax - (uint64_t)fmin, grange = (uint64_t)gmax - (uint64_t)gmin;
     // the second differences were exact only if both ranges are below 2^62
     if ((frange >> 62) != 0 || (grange >> 62) != 0) bits = 0;
     const bool narrow = frange < (1ull << 30) && grange < (1ull << 30);
     const int code = structure_code(op, bits, narrow ? 1 : 0);
     const bool general = code < kSelSearch;
-    narrow_ok[row] = code;
-    out_base[row] = narrow ? (deconv ? wrap_sub(fmin, gmin) : wrap_add(fmin, gmin)) : 0;
     s_base[0] = fmin; s_base[1] = gmin; s_narrow = narrow && general ? 1 : 0;
     // re-based values lie in [0, 2^29): the detrended rows stay inside int32
     const bool ok = general && frange < (1ull << 29) && grange < (1ull << 29);
-    pack_ok[row] = ok ? 1 : 0;
+    if (publish) {
+      narrow_ok[row] = code;
+      out_base[row] = narrow ? (deconv ? wrap_sub(fmin, gmin) : wrap_add(fmin, gmin)) : 0;
+      pack_ok[row] = ok ? 1 : 0;
+    }
     int32_t r = 0;
-    if (ok && n > 1) {
+    if (publish && ok && n > 1) {
       const int64_t w0 = deconv ? fr[0] : gr[0], w1 = deconv ? fr[n - 1] : gr[n - 1];
       const int64_t u0 = deconv ? gr[0] : fr[0], u1 = deconv ? gr[n - 1] : fr[n - 1];
       r = w1 > w0 ? (int32_t)((w1 - w0) / (n - 1)) : 0;
@@ -204,12 +266,12 @@ __global__ __launch_bounds__(1024) void probe_narrow_kernel(const int64_t* __res
       const int64_t diff = ru > r ? ru - r : r - ru;
       if (diff * kPkSub > 50000) pack_ok[row] = 0;   // same heuristic as probe_kernel
     }
-    rho[row] = r;
+    if (publish) rho[row] = r;
   }
   __syncthreads();
   if (s_narrow) {
     const int64_t fb = s_base[0], gb = s_base[1];
-    for (int i = threadIdx.x; i < n; i += blockDim.x) {
+    for (int i = i_begin + threadIdx.x; i < i_end; i += blockDim.x) {
       f32[(int64_t)row * n + i] = (int32_t)(fr[i] - fb);
       g32[(int64_t)row * n + i] = (int32_t)(gr[i] - gb);
     }
@@ -293,23 +355,25 @@ __global__ __launch_bounds__(1024) void prep_kernel(const int32_t* __restrict__ 
   }
 }
 
-// Performance heuristic only (results are exact either way): samples up to 64 x 64
+// Performance heuristic only (results are exact either way): samples up to 32 x 32
 // (tile, chunk) pairs of a row, weighted by the number of chunks they stand for, and switches the
 // packed path off for the row when less than half of its chunk-tiles would qualify -- a mostly
 // unpackable row is better left to the 32-bit kernel alone.
+constexpr int kDecideSide = 32;   // sampled tiles x sampled chunks per tile
+
 __global__ __launch_bounds__(256) void decide_kernel(PackAux x, int n, int32_t* __restrict__ pack_ok) {
   __shared__ float s_yes[4], s_all[4];
   const int row = blockIdx.x;
   const int n_t2 = (n + kPkW - 1) / kPkW;
   float yes = 0.f, all = 0.f;
   if (pack_ok[row] != 0) {
-    for (int j = threadIdx.x; j < 64 * 64; j += 256) {
-      const int it = j / 64, ic = j % 64;
-      const int nt = min(n_t2, 64);
+    for (int j = threadIdx.x; j < kDecideSide * kDecideSide; j += 256) {
+      const int it = j / kDecideSide, ic = j % kDecideSide;
+      const int nt = min(n_t2, kDecideSide);
       if (it >= nt) continue;
       const int T2 = (int)((int64_t)it * n_t2 / nt);
       const int nc = (min((T2 + 1) * kPkW, n) + kPkChunk - 1) / kPkChunk;   // chunks of this tile
-      const int ns = min(nc, 64);
+      const int ns = min(nc, kDecideSide);
       if (ic >= ns) continue;
       const int c = (int)((int64_t)ic * nc / ns);
       const float weight = (float)nc / (float)ns * ((float)n_t2 / (float)nt);
