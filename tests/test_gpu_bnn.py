@@ -166,3 +166,9 @@ def test_special_thresholds(bnn):
         A, B, Cq = x1 < xi, gamma > 0, x1 == xi
     want = np.logical_or(np.logical_xor(A, B), Cq)
     assert np.array_equal(host_words(x4), obnn.pack(want.astype(np.int8)))
+
+
+def test_classifier_layer_shapes(bnn):
+    """The 32 x 32 classifier trunk's layer shapes (maps down to 2 x 2, where every pixel is a border pixel)."""
+    for i, (name, hw, C, K) in enumerate(bw.CLASSIFIER_LAYERS):
+        check_layer(bnn, 500 + i, 3, hw, hw, C, K, 3, 3, 1, 1)
