@@ -3,19 +3,26 @@
 // packing (the paper's binary convolution operation, channel compression, layer integration,
 // workload optimisation and branch-free selection sections).
 //
-// Mapping.  One wave64 per workgroup.  The 64 lanes are 64 consecutive filters k; the wave owns
-// TM consecutive output pixels of one output row.  An activation word is then the same for all
-// lanes, so it lives in a scalar register and is the scalar source of v_xor_b32; a lane's
-// filter word is the vector source.  Per (pixel, word) the kernel issues v_xor_b32 +
-// v_bcnt_u32_b32 (popcount with accumulate): 2 VALU instructions per 32 binary
-// multiply-accumulates per lane, nothing else in the inner loop.  The TM pixels share one strip
-// of (TM-1) stride + S input pixels per filter row, loaded once into scalar registers.  The
-// paper's "one thread computes 8 filters and packs a byte" becomes "one wavefront computes 64
-// filters and a ballot packs two words": the 64 binarised results of a pixel are the 64 bits of
-// the wave's compare mask.
+// Mapping.  The 64 lanes of a wave are 64 consecutive filters k; the wave owns TM consecutive
+// output pixels of one output row.  An activation word is then the same for all lanes and a
+// lane's filter word its own, and per (pixel, word) the kernels issue v_xor_b32 + v_bcnt_u32_b32
+// (popcount with accumulate): 2 VALU instructions per 32 binary multiply-accumulates per lane,
+// nothing else in the inner loop.  The TM pixels share one strip of (TM-1) stride + S input
+// pixels per filter row.  The paper's "one thread computes 8 filters and packs a byte" becomes
+// "one wavefront computes 64 filters and a ballot packs two words": the 64 binarised results of a
+// pixel are the 64 bits of the wave's compare mask.
 //
-// Image borders: a filter row outside the image is skipped (the same for all pixels of the
-// strip); a strip pixel left or right of the image is read as an all-zero word, and what the
+// Three kernels differ in how the strip reaches the lanes:
+//   bconv_resident_kernel (+ _half)  pixels of 1, 2 or 4 words: filters live in registers, the
+//                                    strip is fetched one tile ahead by a coalesced vector load
+//                                    and broadcast through a wave-private LDS line
+//   bconv_lds_kernel                 pixels of a multiple of 4 words: 4 waves share a strip staged
+//                                    once in LDS, filter words stream from the transposed bank
+//   bconv_kernel                     everything else: the strip sits in scalar registers and is
+//                                    the scalar source of v_xor_b32
+//
+// Image borders: a filter row outside the image is skipped (it only lowers Len, i.e. the tile's
+// threshold); a strip pixel left or right of the image is read as an all-zero word, and what the
 // zero word wrongly contributed, popcount(w[k][r][s][:]), is taken off again in the epilogue
 // from the per-(tap, filter) table that bnn_pack_weights appends to the filter bank.
 #include <hip/hip_runtime.h>
