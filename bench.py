@@ -178,10 +178,16 @@ def per_config_table(seed, peak_ops, with_cpu):
                     for _ in range(64)])
     rl = np.stack([wl.rate_latency(65536, int(rs.integers(2, 60)), int(rs.integers(0, 3000)), np.int32) for _ in range(64)])
     rl2 = np.stack([wl.rate_latency(65536, int(rs.integers(2, 60)), int(rs.integers(0, 3000)), np.int32) for _ in range(64)])
+    arb = c["f"].astype(np.int32)
     for label, fn, ofn, f_h, g_h, how in (
             ("minplus_conv token-bucket x token-bucket", rtc.rtc_minplus_conv, "minplus_conv", tb, tb2, "ends"),
             ("minplus_conv rate-latency x rate-latency", rtc.rtc_minplus_conv, "minplus_conv", rl, rl2, "bisection"),
-            ("maxplus_deconv token-bucket / rate-latency", rtc.rtc_maxplus_deconv, "maxplus_deconv", tb, rl, "bisection")):
+            ("maxplus_deconv token-bucket / rate-latency", rtc.rtc_maxplus_deconv, "maxplus_deconv", tb, rl, "bisection"),
+            # one operand of the right shape only: the configuration's own arbitrary curves against
+            # rate-latency service / from token-bucket arrivals
+            ("minplus_conv arbitrary x rate-latency", rtc.rtc_minplus_conv, "minplus_conv", arb, rl, "anchors + brackets"),
+            ("minplus_conv rate-latency x arbitrary", rtc.rtc_minplus_conv, "minplus_conv", rl, arb, "anchors + brackets, operands exchanged"),
+            ("maxplus_deconv token-bucket / arbitrary", rtc.rtc_maxplus_deconv, "maxplus_deconv", tb, arb, "anchors + brackets")):
         f, g = dev(f_h), dev(g_h)
         out = torch.empty_like(f)
         ws = torch.empty(rtc.rtc_workspace_bytes(rtc.RTC_OP_CONV, 64, 65536, torch.int32), dtype=torch.uint8, device="cuda")

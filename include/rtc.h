@@ -201,12 +201,21 @@ int rtc_max_vdev(const void* alpha, const void* beta, void* out, int64_t batch, 
  *   RTC_STRUCTURE_BISECT  min over a convex / max over a concave sequence: bisection on the sign
  *                         of c(j+1) - c(j)
  * (convolutions: f and g both convex, or both concave; deconvolutions: f convex and g concave,
- * or f concave and g convex; linear rows count as both).  The products detect this on the device
- * and compute such pairs in O(n) or O(n log n) candidates with the same result bit for bit, when
- * a workspace is given and the problem is above the rtc_set_packed_min_work threshold.
+ * or f concave and g convex; linear rows count as both).  With only one operand of the right
+ * shape -- g (RTC_STRUCTURE_BRACKET) or f (RTC_STRUCTURE_BRACKET_SWAPPED) convex under the
+ * min-plus convolution, concave under the max-plus one; f concave under the max-plus
+ * deconvolution, convex under the min-plus one; the other operand arbitrary, e.g. any arrival
+ * curve against a rate-latency service curve -- the optimal j still moves monotonically with
+ * t: every 256th output is scanned in full and the outputs in between only between their
+ * neighbours' optima, n^2/512 + 256 n candidates instead of n^2/2.  The products detect all this
+ * on the device and compute such pairs with the same result bit for bit, when a workspace is
+ * given and the problem is above the rtc_set_packed_min_work threshold.
  * rtc_product_structure reports the classification: codes[b] for row pair b, op = RTC_OP_CONV,
  * _DECONV, _MAXCONV or _MINDECONV.  codes: device, [batch] int32. */
-enum { RTC_STRUCTURE_GENERAL = 1, RTC_STRUCTURE_BISECT = 2, RTC_STRUCTURE_ENDS = 3 };
+enum {
+  RTC_STRUCTURE_GENERAL = 1, RTC_STRUCTURE_BISECT = 2, RTC_STRUCTURE_ENDS = 3, RTC_STRUCTURE_BRACKET = 4,
+  RTC_STRUCTURE_BRACKET_SWAPPED = 5
+};
 int rtc_product_structure(int op, const void* f, const void* g, int32_t* codes, int64_t batch, int64_t n,
                           int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* hip_stream);
 

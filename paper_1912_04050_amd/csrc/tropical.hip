@@ -186,7 +186,7 @@ int run_product(const T* a, int64_t stride_a, const T* b, int64_t stride_b, OutT
 // Layout of the packed path's arrays inside the workspace.
 struct PackLayout {
   int64_t npad, nchunk, nsub, nblk;
-  size_t off_apk, off_apk_s, off_bd, off_ab, off_ar, off_ab_s, off_ar_s, off_bmn, off_bmx, off_rho, off_ok, off_sel, bytes;
+  size_t off_apk, off_apk_s, off_bd, off_ab, off_ar, off_ab_s, off_ar_s, off_bmn, off_bmx, off_rho, off_ok, off_sel, off_jstar, bytes;
 };
 
 PackLayout pack_layout(int64_t batch, int64_t n) {
@@ -209,6 +209,7 @@ PackLayout pack_layout(int64_t batch, int64_t n) {
   L.off_rho = take((size_t)batch);
   L.off_ok = take((size_t)batch);
   L.off_sel = take((size_t)batch);   // per-row selector of int32 products (int64 products keep their own)
+  L.off_jstar = take((size_t)batch * (L.nblk + 1));   // anchor optima of the bracket path (kPkBlock = its block of 256)
   L.bytes = o;
   return L;
 }
@@ -310,7 +311,8 @@ int run_typed(const void* f, const void* g, void* out, int64_t batch, int64_t n,
       if (rc != RTC_OK) return rc;
       return launch_structured<int32_t, OP>(static_cast<const int32_t*>(f), stride_f,
                                             static_cast<const int32_t*>(g), stride_g, static_cast<int32_t*>(out),
-                                            static_cast<const int32_t*>(cap), sel, batch, n, stream);
+                                            static_cast<const int32_t*>(cap), sel,
+                                            reinterpret_cast<int32_t*>(wsp + L.off_jstar), batch, n, stream);
     }
   }
   if (dev_flags != nullptr && std::numeric_limits<T>::is_integer) {
@@ -382,7 +384,8 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
   // rows of exploitable convexity (selector 2 / 3), on the caller's own 64-bit rows
   return launch_structured<int64_t, OP>(static_cast<const int64_t*>(f), stride_f,
                                         static_cast<const int64_t*>(g), stride_g, static_cast<int64_t*>(out),
-                                        static_cast<const int64_t*>(cap), ok, batch, n, stream);
+                                        static_cast<const int64_t*>(cap), ok,
+                                        reinterpret_cast<int32_t*>(wsp + L.off_jstar), batch, n, stream);
 }
 
 }  // namespace
@@ -425,7 +428,10 @@ int launch_selftest_half_minmax(uint32_t* mismatches, hipStream_t stream) {
 
 int launch_structure_probe(int op, const void* f, const void* g, int32_t* codes, int64_t batch, int64_t n,
                            int64_t stride_f, int64_t stride_g, int dt, hipStream_t stream) {
-  static_assert(kSelSearch == RTC_STRUCTURE_BISECT && kSelEnds == RTC_STRUCTURE_ENDS, "selector codes are public");
+  static_assert(kSelSearch == RTC_STRUCTURE_BISECT && kSelEnds == RTC_STRUCTURE_ENDS &&
+                    kSelBracket == RTC_STRUCTURE_BRACKET && kSelBracketSwapped == RTC_STRUCTURE_BRACKET_SWAPPED &&
+                    kBracketBlock == kPkBlock,
+                "selector codes are public; the bracket path's anchors share the packed path's block size");
   const int code_op = op == RTC_OP_CONV ? 0 : op == RTC_OP_DECONV ? 1 : op == RTC_OP_MAXCONV ? 2 : 3;
   if (dt == RTC_I32) {
     hipLaunchKernelGGL(probe_kernel<int32_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,

@@ -30,6 +30,8 @@ __device__ __forceinline__ int second_diff_bits(const T* row, int i) {
 // kSelSearch / kSelEnds = the row pair is done by structured_kernel.
 constexpr int kSelSearch = 2;
 constexpr int kSelEnds = 3;
+constexpr int kSelBracket = 4;          // one operand of the right shape: anchors + brackets, see tropical_structured.h
+constexpr int kSelBracketSwapped = 5;   // the same with the convolution's operands exchanged
 
 // The candidates of one output, c(j) = f[j] + g[t-j] (convolutions) or f[t+j] - g[j]
 // (deconvolutions), form a convex sequence in j when (f, g) are (convex, convex) resp.
@@ -43,6 +45,14 @@ __device__ __forceinline__ int structure_code(int op, int bits, int general) {
   const bool ccv = op_sub(op) ? (fccv && gcvx) : (fccv && gccv);
   if (op_max(op) ? cvx : ccv) return kSelEnds;
   if (op_max(op) ? ccv : cvx) return kSelSearch;
+  // One operand alone: the candidate matrix M[t][j] = c_t(j) is a Monge matrix when the operand
+  // that is indexed by t (g for the convolutions -- or f, they commute -- and f for the
+  // deconvolutions) is convex under a min / concave under a max, whatever the other operand is;
+  // the optimal j then moves monotonically with t.
+  const bool want_cvx = !op_max(op);
+  if (op_sub(op)) return (want_cvx ? fcvx : fccv) ? kSelBracket : general;
+  if (want_cvx ? gcvx : gccv) return kSelBracket;
+  if (want_cvx ? fcvx : fccv) return kSelBracketSwapped;
   return general;
 }
 

@@ -8,6 +8,51 @@
 namespace rtc {
 namespace {
 
+constexpr int kBracketBlock = 256;   // outputs between two anchors = threads of a workgroup
+
+// Bracket path, first pass.  When the operand indexed by t is convex (min) / concave (max), the
+// leftmost optimal j of output t is monotone in t: nondecreasing for the convolutions,
+// nonincreasing for the deconvolutions (Monge property of c_t(j); candidates that do not exist
+// count as +-infinity and keep it).  Anchor a is output t_a = min(256 a, n-1); one workgroup scans
+// all its candidates and records the leftmost optimal j in jstar[row][a].  The outputs between
+// two anchors then only need the candidates between the anchors' optima (structured_kernel),
+// n^2 / 512 + 256 n candidates per row pair instead of n^2 / 2.
+template <typename T, int OP>
+__global__ __launch_bounds__(256) void bracket_anchor_kernel(const T* __restrict__ f, int64_t stride_f,
+                                                             const T* __restrict__ g, int64_t stride_g,
+                                                             const int32_t* __restrict__ sel,
+                                                             int32_t* __restrict__ jstar, int n, int anchors) {
+  __shared__ T s_val[4];
+  __shared__ int s_idx[4];
+  const int row = blockIdx.x / anchors, a = blockIdx.x % anchors;
+  const int code = sel[row];
+  if (code != kSelBracket && code != kSelBracketSwapped) return;
+  const int t = min(a * kBracketBlock, n - 1);
+  const bool swapped = code == kSelBracketSwapped;       // convolutions only: they commute
+  const T* fr = (swapped ? g + (int64_t)row * stride_g : f + (int64_t)row * stride_f);
+  const T* gr = (swapped ? f + (int64_t)row * stride_f : g + (int64_t)row * stride_g);
+  const int m = op_sub(OP) ? n - 1 - t : t;
+  T best = Semiring<T, OP>::identity();
+  int best_j = 0x7fffffff;
+  for (int j = threadIdx.x; j <= m; j += 256) {
+    const T c = op_sub(OP) ? wrap_sub(fr[t + j], gr[j]) : wrap_add(fr[j], gr[t - j]);
+    if (best_j == 0x7fffffff || (op_max(OP) ? c > best : c < best)) { best = c; best_j = j; }   // ascending j: the first optimum stays
+  }
+  // leftmost optimum over the workgroup: better value, or equal value and smaller j
+  auto merge = [&](T v, int j) {
+    if (j == 0x7fffffff) return;
+    if (best_j == 0x7fffffff || (op_max(OP) ? v > best : v < best) || (v == best && j < best_j)) { best = v; best_j = j; }
+  };
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) merge(__shfl_xor(best, off), __shfl_xor(best_j, off));
+  if ((threadIdx.x & 63) == 0) { s_val[threadIdx.x >> 6] = best; s_idx[threadIdx.x >> 6] = best_j; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w) merge(s_val[w], s_idx[w]);
+    jstar[(int64_t)row * anchors + a] = best_j;
+  }
+}
+
 // Rows with sel[row] == kSelEnds or kSelSearch (decided by the probe kernels, see
 // structure_code) are computed here, every other row is left alone.  The candidates of output t
 // are c(j), 0 <= j <= m:
@@ -16,26 +61,39 @@ namespace {
 // kSelEnds:   the reduction of c(0) and c(m) (min over a concave / max over a convex sequence).
 // kSelSearch: bisection for the first j with c(j+1) >= c(j) (min over a convex sequence) resp.
 //             c(j+1) <= c(j) (max over a concave one); c there is the result.
+// kSelBracket(Swapped): the reduction over the candidates between the optima of the two anchors
+//             around t (bracket_anchor_kernel; one workgroup = the 256 outputs between two anchors).
 // Each candidate is formed exactly as the general kernels form it (one wrap-around add or
 // subtract), so the result is the same value bit for bit.
 template <typename T, int OP>
 __global__ __launch_bounds__(256) void structured_kernel(const T* __restrict__ f, int64_t stride_f,
                                                          const T* __restrict__ g, int64_t stride_g,
                                                          T* __restrict__ out, const T* __restrict__ cap,
-                                                         const int32_t* __restrict__ sel, int n,
+                                                         const int32_t* __restrict__ sel,
+                                                         const int32_t* __restrict__ jstar, int n,
                                                          int blocks_per_row) {
+  static_assert(kBracketBlock == 256, "one workgroup = the outputs between two anchors");
   const int row = blockIdx.x / blocks_per_row;
   const int code = sel[row];
   if (code < kSelSearch) return;
-  const int t = (blockIdx.x % blocks_per_row) * 256 + threadIdx.x;
+  const int block = blockIdx.x % blocks_per_row;
+  const int t = block * 256 + threadIdx.x;
   if (t >= n) return;
-  const T* fr = f + (int64_t)row * stride_f;
-  const T* gr = g + (int64_t)row * stride_g;
+  const bool swapped = code == kSelBracketSwapped;
+  const T* fr = swapped ? g + (int64_t)row * stride_g : f + (int64_t)row * stride_f;
+  const T* gr = swapped ? f + (int64_t)row * stride_f : g + (int64_t)row * stride_g;
   auto c = [&](int j) -> T { return op_sub(OP) ? wrap_sub(fr[t + j], gr[j]) : wrap_add(fr[j], gr[t - j]); };
   const int m = op_sub(OP) ? n - 1 - t : t;
   T v;
   if (code == kSelEnds) {
     v = Semiring<T, OP>::reduce(c(0), c(m));
+  } else if (code >= kSelBracket) {
+    const int32_t* js = jstar + (int64_t)row * (blocks_per_row + 1) + block;
+    const int ja = js[0], jb = js[1];            // optima of the anchors below and above t
+    const int lo = op_sub(OP) ? jb : ja;
+    const int hi = min(op_sub(OP) ? ja : jb, m);
+    v = c(lo);
+    for (int j = lo + 1; j <= hi; ++j) v = Semiring<T, OP>::reduce(v, c(j));
   } else {
     int lo = 0, hi = m;
     while (lo < hi) {
@@ -51,11 +109,14 @@ __global__ __launch_bounds__(256) void structured_kernel(const T* __restrict__ f
 
 template <typename T, int OP>
 int launch_structured(const T* f, int64_t stride_f, const T* g, int64_t stride_g, T* out, const T* cap,
-                      const int32_t* sel, int64_t batch, int64_t n, hipStream_t stream) {
+                      const int32_t* sel, int32_t* jstar, int64_t batch, int64_t n, hipStream_t stream) {
   const int64_t bpr = (n + 255) / 256;
-  if (batch * bpr > 0x7fffffffLL) return RTC_ERR_SHAPE;
+  if (batch * (bpr + 1) > 0x7fffffffLL) return RTC_ERR_SHAPE;
+  // jstar: [batch][bpr + 1] anchor optima of the bracket path
+  hipLaunchKernelGGL((bracket_anchor_kernel<T, OP>), dim3((uint32_t)(batch * (bpr + 1))), dim3(256), 0, stream, f,
+                     stride_f, g, stride_g, sel, jstar, (int)n, (int)(bpr + 1));
   hipLaunchKernelGGL((structured_kernel<T, OP>), dim3((uint32_t)(batch * bpr)), dim3(256), 0, stream, f, stride_f, g,
-                     stride_g, out, cap, sel, (int)n, (int)bpr);
+                     stride_g, out, cap, sel, jstar, (int)n, (int)bpr);
   return hip_ok();
 }
 

@@ -153,6 +153,7 @@ def rtc_selftest_half_minmax() -> int:
 _lib.rtc_product_structure.argtypes = [_int, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _int, _vp]
 _lib.rtc_product_structure.restype = _int
 RTC_STRUCTURE_GENERAL, RTC_STRUCTURE_BISECT, RTC_STRUCTURE_ENDS = 1, 2, 3
+RTC_STRUCTURE_BRACKET, RTC_STRUCTURE_BRACKET_SWAPPED = 4, 5
 
 
 def rtc_product_structure(op: int, f, g, out=None):

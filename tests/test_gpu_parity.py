@@ -432,6 +432,8 @@ def _shaped_rows(rng, n, kind):
     elif kind == "rate-latency":
         lat = int(rng.integers(0, max(n, 2)))
         inc = np.where(np.arange(max(n - 1, 1)) < lat, 0, int(rng.integers(1, 50)))
+    elif kind == "staircase":      # long flat runs: many candidates tie
+        inc = np.where(rng.integers(0, 40, max(n - 1, 1)) == 0, rng.integers(1, 4, max(n - 1, 1)) * 100, 0)
     v = np.concatenate([[int(rng.integers(-100, 100))], inc])[:n].cumsum()
     if n >= 4:
         if kind == "convex-spoiled-first":
@@ -443,15 +445,16 @@ def _shaped_rows(rng, n, kind):
     return v
 
 
-SHAPES = ["convex", "concave", "linear", "token-bucket", "rate-latency", "general", "convex-spoiled-first",
+SHAPES = ["convex", "concave", "linear", "token-bucket", "rate-latency", "general", "staircase", "convex-spoiled-first",
           "convex-spoiled-last", "concave-spoiled-mid"]
 
 
 @pytest.mark.parametrize("dtype", [np.int32, np.int64])
 def test_rows_of_exploitable_convexity(rtc, dtype):
     """Every pairing of row shapes in one batch: pairs whose candidates form a convex or concave
-    sequence take the structured kernel (ends of the range, or bisection), all others and the
-    rows spoiled at one sample the general kernels; all four products must equal the oracle."""
+    sequence take the structured kernel (ends of the range, or bisection), pairs with one operand
+    of the right shape its anchors-and-brackets branch, all others and the rows spoiled at one
+    sample the general kernels; all four products must equal the oracle."""
     rng = np.random.default_rng(41)
     for n in (1, 2, 3, 4, 5, 257, 2500):
         fs, gs = [], []
@@ -468,6 +471,34 @@ def test_rows_of_exploitable_convexity(rtc, dtype):
             check_duals(rtc, f * scale, g * scale, f"shaped wide duals n={n}")
 
 
+@pytest.mark.parametrize("dtype", [np.int32, np.int64])
+def test_one_operand_of_exploitable_convexity_long_rows(rtc, dtype):
+    """Arbitrary curves against convex / concave ones at a length of many anchor blocks with a
+    ragged last block: plateaus and bursts make candidates tie, the rate-latency curves' long zero
+    prefix makes brackets as wide as the row, and a length of 256 k + 1 makes the last two anchors
+    coincide."""
+    rng = np.random.default_rng(45)
+    for n in (20001, 14849, 512):
+        arb = np.stack([wl.random_monotone(46, 1, 1, n, np.int64)[0], _shaped_rows(rng, n, "staircase"),
+                        _shaped_rows(rng, n, "general"), np.zeros(n, np.int64), _shaped_rows(rng, n, "staircase")])
+        cvx = np.stack([wl.rate_latency(n, 7, n // 3), wl.rate_latency(n, 1, n - 2), _shaped_rows(rng, n, "convex"),
+                        wl.rate_latency(n, 3, 0), np.maximum(0, np.arange(n) - 50) ** 2 // 64])
+        ccv = np.stack([wl.token_bucket(n, 900, 5, np.int64, at_zero=False), wl.token_bucket(n, 0, 0, np.int64),
+                        _shaped_rows(rng, n, "concave"), wl.token_bucket(n, 5, 1, np.int64), np.sqrt(np.arange(n) * 4096.0).astype(np.int64)])
+        for tag, f, g in (("arbitrary, convex", arb, cvx), ("convex, arbitrary", cvx, arb), ("arbitrary, concave", arb, ccv),
+                          ("concave, arbitrary", ccv, arb)):
+            # every row against two partners (10 pairs: enough work for the planner to take these paths at each n)
+            f, g = np.concatenate([f, np.roll(f, 1, axis=0)]).astype(dtype), np.concatenate([g, g]).astype(dtype)
+            for name, op in (("conv", rtc.RTC_OP_CONV), ("deconv", rtc.RTC_OP_DECONV), ("maxconv", rtc.RTC_OP_MAXCONV),
+                             ("mindeconv", rtc.RTC_OP_MINDECONV)):
+                want = np.array([_structure_by_definition(f[b], g[b], name) for b in range(len(f))])
+                assert np.array_equal(host(rtc.rtc_product_structure(op, dev(f), dev(g))), want), (tag, name, n)
+            check_products(rtc, f, g, f"one-sided {tag} n={n}")
+            check_duals(rtc, f, g, f"one-sided duals {tag} n={n}")
+            if dtype == np.int64:
+                check_products(rtc, f * (1 << 34), g * (1 << 34), f"one-sided wide {tag} n={n}")
+
+
 def _structure_by_definition(f, g, op):
     """The documented rule, from second differences in exact Python integers."""
     def shape(v):
@@ -481,7 +512,13 @@ def _structure_by_definition(f, g, op):
         return 3
     if (ccv if is_max else cvx):
         return 2
-    return 1
+    # one operand of the right shape: f for the deconvolutions, g (4) or else f (5) for the convolutions
+    want_f, want_g = (fccv, gccv) if is_max else (fcvx, gcvx)
+    if deconv:
+        return 4 if want_f else 1
+    if want_g:
+        return 4
+    return 5 if want_f else 1
 
 
 @pytest.mark.parametrize("dtype", [np.int32, np.int64, np.float64])
