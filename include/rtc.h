@@ -206,8 +206,9 @@ int rtc_max_vdev(const void* alpha, const void* beta, void* out, int64_t batch, 
  * min-plus convolution, concave under the max-plus one; f concave under the max-plus
  * deconvolution, convex under the min-plus one; the other operand arbitrary, e.g. any arrival
  * curve against a rate-latency service curve -- the optimal j still moves monotonically with
- * t: every 256th output is scanned in full and the outputs in between only between their
- * neighbours' optima, n^2/512 + 256 n candidates instead of n^2/2.  The products detect all this
+ * t: every 4096th output is scanned in full, every 64th between the optima of those, and the
+ * outputs in between only between their neighbours' optima, about n^2/8192 + 128 n candidates
+ * instead of n^2/2.  The products detect all this
  * on the device and compute such pairs with the same result bit for bit, when a workspace is
  * given and the problem is above the rtc_set_packed_min_work threshold.
  * rtc_product_structure reports the classification: codes[b] for row pair b, op = RTC_OP_CONV,

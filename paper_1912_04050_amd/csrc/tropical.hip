@@ -209,7 +209,7 @@ PackLayout pack_layout(int64_t batch, int64_t n) {
   L.off_rho = take((size_t)batch);
   L.off_ok = take((size_t)batch);
   L.off_sel = take((size_t)batch);   // per-row selector of int32 products (int64 products keep their own)
-  L.off_jstar = take((size_t)batch * (L.nblk + 1));   // anchor optima of the bracket path (kPkBlock = its block of 256)
+  L.off_jstar = take(bracket_jstar_elems(batch, n));   // anchor optima of the bracket path
   L.bytes = o;
   return L;
 }
@@ -429,9 +429,8 @@ int launch_selftest_half_minmax(uint32_t* mismatches, hipStream_t stream) {
 int launch_structure_probe(int op, const void* f, const void* g, int32_t* codes, int64_t batch, int64_t n,
                            int64_t stride_f, int64_t stride_g, int dt, hipStream_t stream) {
   static_assert(kSelSearch == RTC_STRUCTURE_BISECT && kSelEnds == RTC_STRUCTURE_ENDS &&
-                    kSelBracket == RTC_STRUCTURE_BRACKET && kSelBracketSwapped == RTC_STRUCTURE_BRACKET_SWAPPED &&
-                    kBracketBlock == kPkBlock,
-                "selector codes are public; the bracket path's anchors share the packed path's block size");
+                    kSelBracket == RTC_STRUCTURE_BRACKET && kSelBracketSwapped == RTC_STRUCTURE_BRACKET_SWAPPED,
+                "selector codes are public");
   const int code_op = op == RTC_OP_CONV ? 0 : op == RTC_OP_DECONV ? 1 : op == RTC_OP_MAXCONV ? 2 : 3;
   if (dt == RTC_I32) {
     hipLaunchKernelGGL(probe_kernel<int32_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,
