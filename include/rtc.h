@@ -208,14 +208,26 @@ int rtc_max_vdev(const void* alpha, const void* beta, void* out, int64_t batch, 
  * curve against a rate-latency service curve -- the optimal j still moves monotonically with
  * t: every 4096th output is scanned in full, every 64th between the optima of those, and the
  * outputs in between only between their neighbours' optima, about n^2/8192 + 128 n candidates
- * instead of n^2/2.  The products detect all this
- * on the device and compute such pairs with the same result bit for bit, when a workspace is
- * given and the problem is above the rtc_set_packed_min_work threshold.
+ * instead of n^2/2.
+ * Pairs without such convexity are looked at for periodicity: a row w is periodic from index 1
+ * on when w[i+p] = w[i] + c for all 1 <= i <= n-1-p (event streams with jitter, TDMA service;
+ * index 0 is left out because such curves are 0 there), with a period p <= min(1024, n/16).
+ * RTC_STRUCTURE_PERIODIC: g is (its smallest such period is used); RTC_STRUCTURE_PERIODIC_SWAPPED
+ * (convolutions only): f is, and g is not or has a longer period that exceeds
+ * min(max(n/64, 32), 256).  Grouping the candidates by residue class of j turns the product into
+ * one scan along each class of the other operand plus a window of p candidates per output,
+ * n p candidates instead of n^2/2.  Not taken when the other row's range plus w's would leave
+ * the type.  The search tests each period at 128 consecutive and a few spread positions first
+ * and fully verifies at most four survivors per row, so a contrived row can escape it (and takes
+ * the general kernels); a row it accepts is periodic.
+ * The products detect all this on the device and compute such pairs with the same result bit
+ * for bit, when a workspace is given, the problem is above the rtc_set_packed_min_work
+ * threshold and rtc_set_structure_paths is on.
  * rtc_product_structure reports the classification: codes[b] for row pair b, op = RTC_OP_CONV,
  * _DECONV, _MAXCONV or _MINDECONV.  codes: device, [batch] int32. */
 enum {
   RTC_STRUCTURE_GENERAL = 1, RTC_STRUCTURE_BISECT = 2, RTC_STRUCTURE_ENDS = 3, RTC_STRUCTURE_BRACKET = 4,
-  RTC_STRUCTURE_BRACKET_SWAPPED = 5
+  RTC_STRUCTURE_BRACKET_SWAPPED = 5, RTC_STRUCTURE_PERIODIC = 6, RTC_STRUCTURE_PERIODIC_SWAPPED = 7
 };
 int rtc_product_structure(int op, const void* f, const void* g, int32_t* codes, int64_t batch, int64_t n,
                           int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* hip_stream);
@@ -231,6 +243,12 @@ int rtc_set_packed_min_work(double batch_times_n_squared);
  * loop overhead per candidate; default 4096, measured).  0 never does, a value >= RTC_MAX_N always does.  Results do not
  * depend on it.  Process-wide, not thread-safe.  RTC_ERR_SHAPE for a negative value. */
 int rtc_set_packed_small_n(int64_t n);
+
+/* Planner knob: 0 sends every row pair of the integer products through the general kernels,
+ * whatever its convexity or periodicity (rtc_product_structure still reports what it finds);
+ * non-zero (default) lets the structure-exploiting paths take the rows they recognise.  Results
+ * do not depend on it.  Process-wide, not thread-safe. */
+int rtc_set_structure_paths(int enabled);
 
 /* Bytes of device workspace an operator needs for the given shape (0 on invalid input). */
 size_t rtc_workspace_bytes(int op, int64_t batch, int64_t n, rtc_dtype dt);

@@ -303,6 +303,11 @@ int rtc_set_packed_small_n(int64_t n) {
   return RTC_OK;
 }
 
+int rtc_set_structure_paths(int enabled) {
+  rtc::g_structure_paths = enabled != 0;
+  return RTC_OK;
+}
+
 const char* rtc_strerror(int status) {
   switch (status) {
     case RTC_OK: return "ok";

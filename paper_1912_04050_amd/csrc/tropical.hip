@@ -53,6 +53,7 @@
 namespace rtc {
 
 int64_t g_packed_small_n = 4096;   // rows up to this length use the narrower packed tiles
+bool g_structure_paths = true;     // rows of exploitable convexity / periodicity take their own kernels
 
 namespace {
 
@@ -186,7 +187,7 @@ int run_product(const T* a, int64_t stride_a, const T* b, int64_t stride_b, OutT
 // Layout of the packed path's arrays inside the workspace.
 struct PackLayout {
   int64_t npad, nchunk, nsub, nblk;
-  size_t off_apk, off_apk_s, off_bd, off_ab, off_ar, off_ab_s, off_ar_s, off_bmn, off_bmx, off_rho, off_ok, off_sel, off_jstar, bytes;
+  size_t off_apk, off_apk_s, off_bd, off_ab, off_ar, off_ab_s, off_ar_s, off_bmn, off_bmx, off_rho, off_ok, off_sel, off_jstar, off_period, off_F, bytes;
 };
 
 PackLayout pack_layout(int64_t batch, int64_t n) {
@@ -210,6 +211,8 @@ PackLayout pack_layout(int64_t batch, int64_t n) {
   L.off_ok = take((size_t)batch);
   L.off_sel = take((size_t)batch);   // per-row selector of int32 products (int64 products keep their own)
   L.off_jstar = take(bracket_jstar_elems(batch, n));   // anchor optima of the bracket path
+  L.off_period = take((size_t)batch);                  // period per row of the periodic path
+  L.off_F = take((size_t)batch * n * 2);               // its scan F, [batch][n] of the rows' own type
   L.bytes = o;
   return L;
 }
@@ -300,19 +303,26 @@ int run_typed(const void* f, const void* g, void* out, int64_t batch, int64_t n,
       int32_t* sel = reinterpret_cast<int32_t*>(wsp + L.off_sel);
       hipLaunchKernelGGL(probe_kernel<int32_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,
                          static_cast<const int32_t*>(f), stride_f, static_cast<const int32_t*>(g), stride_g,
-                         (int)n, OP, reinterpret_cast<int32_t*>(wsp + L.off_ok),
+                         (int)n, g_structure_paths ? OP : OP | kProbeGeneralOnly,
+                         reinterpret_cast<int32_t*>(wsp + L.off_ok),
                          reinterpret_cast<int32_t*>(wsp + L.off_rho), sel, dev_flags);
+      if (g_structure_paths)
+        launch_period<int32_t>(static_cast<const int32_t*>(f), stride_f, static_cast<const int32_t*>(g), stride_g, sel,
+                             reinterpret_cast<int32_t*>(wsp + L.off_period),
+                             reinterpret_cast<int32_t*>(wsp + L.off_ok), batch, n, OP, stream);
       launch_fill<int32_t, OP>(static_cast<int32_t*>(out), batch * n, stream);
       // general rows (selector 1): packed + 32-bit items; rows of exploitable convexity: structured_kernel
       const int rc = run_packed<int32_t, OP>(static_cast<const int32_t*>(f), stride_f,
                                              static_cast<const int32_t*>(g), stride_g, static_cast<int32_t*>(out),
                                              static_cast<const int32_t*>(cap), sel, nullptr, batch, n, wsp, L,
                                              stream);
-      if (rc != RTC_OK) return rc;
+      if (rc != RTC_OK || !g_structure_paths) return rc;
       return launch_structured<int32_t, OP>(static_cast<const int32_t*>(f), stride_f,
                                             static_cast<const int32_t*>(g), stride_g, static_cast<int32_t*>(out),
                                             static_cast<const int32_t*>(cap), sel,
-                                            reinterpret_cast<int32_t*>(wsp + L.off_jstar), batch, n, stream);
+                                            reinterpret_cast<int32_t*>(wsp + L.off_jstar),
+                                            reinterpret_cast<const int32_t*>(wsp + L.off_period),
+                                            reinterpret_cast<int32_t*>(wsp + L.off_F), batch, n, stream);
     }
   }
   if (dev_flags != nullptr && std::numeric_limits<T>::is_integer) {
@@ -350,7 +360,7 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
   int segs = 1;
   while (segs < kProbeMaxSegs && batch * segs < 512 && n / (2 * segs) >= 4096) segs *= 2;
   int64_t* partial = reinterpret_cast<int64_t*>(static_cast<char*>(ws) + narrow_partial_offset(batch, n));
-  const bool structure = packed_worthwhile(batch, n);
+  const bool structure = packed_worthwhile(batch, n) && g_structure_paths;
   if (segs > 1)
     hipLaunchKernelGGL(probe_partial_kernel, dim3((uint32_t)(batch * segs)), dim3(1024), 0, stream,
                        static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g, (int)n,
@@ -361,6 +371,10 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
                      reinterpret_cast<int32_t*>(wsp + L.off_ok),
                      reinterpret_cast<int32_t*>(wsp + L.off_rho), dev_flags, segs,
                      segs > 1 ? partial : (const int64_t*)nullptr);
+  if (structure)
+    launch_period<int64_t>(static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g, ok,
+                           reinterpret_cast<int32_t*>(wsp + L.off_period),
+                             reinterpret_cast<int32_t*>(wsp + L.off_ok), batch, n, OP, stream);
   // Several kernels see every row; the selector makes each row run in exactly one family.
   // The output is filled once with the identity, before all of them.
   launch_fill<int64_t, OP>(static_cast<int64_t*>(out), batch * n, stream);
@@ -380,12 +394,14 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
                                          op_sub(OP) ? stride_f : stride_g, static_cast<int64_t*>(out),
                                          static_cast<const int64_t*>(cap), ok, 0, batch, n, stream, true, true,
                                          nullptr);
-  if (rc != RTC_OK || !packed_worthwhile(batch, n)) return rc;
+  if (rc != RTC_OK || !structure) return rc;
   // rows of exploitable convexity (selector 2 / 3), on the caller's own 64-bit rows
   return launch_structured<int64_t, OP>(static_cast<const int64_t*>(f), stride_f,
                                         static_cast<const int64_t*>(g), stride_g, static_cast<int64_t*>(out),
                                         static_cast<const int64_t*>(cap), ok,
-                                        reinterpret_cast<int32_t*>(wsp + L.off_jstar), batch, n, stream);
+                                        reinterpret_cast<int32_t*>(wsp + L.off_jstar),
+                                        reinterpret_cast<const int32_t*>(wsp + L.off_period),
+                                        reinterpret_cast<int64_t*>(wsp + L.off_F), batch, n, stream);
 }
 
 }  // namespace
@@ -429,17 +445,22 @@ int launch_selftest_half_minmax(uint32_t* mismatches, hipStream_t stream) {
 int launch_structure_probe(int op, const void* f, const void* g, int32_t* codes, int64_t batch, int64_t n,
                            int64_t stride_f, int64_t stride_g, int dt, hipStream_t stream) {
   static_assert(kSelSearch == RTC_STRUCTURE_BISECT && kSelEnds == RTC_STRUCTURE_ENDS &&
-                    kSelBracket == RTC_STRUCTURE_BRACKET && kSelBracketSwapped == RTC_STRUCTURE_BRACKET_SWAPPED,
+                    kSelBracket == RTC_STRUCTURE_BRACKET && kSelBracketSwapped == RTC_STRUCTURE_BRACKET_SWAPPED &&
+                    kSelPeriodic == RTC_STRUCTURE_PERIODIC && kSelPeriodicSwapped == RTC_STRUCTURE_PERIODIC_SWAPPED,
                 "selector codes are public");
   const int code_op = op == RTC_OP_CONV ? 0 : op == RTC_OP_DECONV ? 1 : op == RTC_OP_MAXCONV ? 2 : 3;
   if (dt == RTC_I32) {
     hipLaunchKernelGGL(probe_kernel<int32_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,
                        static_cast<const int32_t*>(f), stride_f, static_cast<const int32_t*>(g), stride_g, (int)n,
                        code_op, (int32_t*)nullptr, (int32_t*)nullptr, codes, (int32_t*)nullptr);
+    launch_period<int32_t>(static_cast<const int32_t*>(f), stride_f, static_cast<const int32_t*>(g), stride_g, codes,
+                           nullptr, nullptr, batch, n, code_op, stream);
   } else if (dt == RTC_I64) {
     hipLaunchKernelGGL(probe_kernel<int64_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,
                        static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g, (int)n,
                        code_op, (int32_t*)nullptr, (int32_t*)nullptr, codes, (int32_t*)nullptr);
+    launch_period<int64_t>(static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g, codes,
+                           nullptr, nullptr, batch, n, code_op, stream);
   } else {
     const int blocks = (int)((batch + 255) / 256 < 65535 ? (batch + 255) / 256 : 65535);
     hipLaunchKernelGGL(fill_kernel<int32_t>, dim3(blocks), dim3(256), 0, stream, codes, batch,

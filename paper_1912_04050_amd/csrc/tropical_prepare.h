@@ -32,6 +32,8 @@ constexpr int kSelSearch = 2;
 constexpr int kSelEnds = 3;
 constexpr int kSelBracket = 4;          // one operand of the right shape: anchors + brackets, see tropical_structured.h
 constexpr int kSelBracketSwapped = 5;   // the same with the convolution's operands exchanged
+constexpr int kSelPeriodic = 6;         // g is periodic from index 1 on: scan + short window, see tropical_structured.h
+constexpr int kSelPeriodicSwapped = 7;  // the same for f of a convolution
 
 // The candidates of one output, c(j) = f[j] + g[t-j] (convolutions) or f[t+j] - g[j]
 // (deconvolutions), form a convex sequence in j when (f, g) are (convex, convex) resp.
@@ -59,7 +61,9 @@ __device__ __forceinline__ int structure_code(int op, int bits, int general) {
 // Range probe of one row pair.  Finds min/max of both rows, raises the overflow flag when
 // the bounds do not prove that every candidate fits and (optionally) decides eligibility for
 // the packed path and the slope to remove, and (optionally, integers) whether the pair's
-// convexity lets structured_kernel do it (selector code in sel[row], else 1).
+// convexity lets structured_kernel do it (selector code in sel[row], else 1; always 1 when
+// kProbeGeneralOnly is added to op).
+constexpr int kProbeGeneralOnly = 0x100;
 template <typename T>
 __global__ __launch_bounds__(1024) void probe_kernel(const T* __restrict__ f, int64_t stride_f,
                                                      const T* __restrict__ g, int64_t stride_g, int n,
@@ -68,12 +72,14 @@ __global__ __launch_bounds__(1024) void probe_kernel(const T* __restrict__ f, in
                                                      int32_t* __restrict__ dev_flags) {
   __shared__ T red[4][16];
   __shared__ int s_bits[16];
+  const bool classify = (op & kProbeGeneralOnly) == 0;
+  op &= ~kProbeGeneralOnly;
   const bool deconv = op_sub(op);
   const int row = blockIdx.x;
   const T* fr = f + (int64_t)row * stride_f;
   const T* gr = g + (int64_t)row * stride_g;
   T fmin = Lim<T>::hi(), fmax = Lim<T>::lo(), gmin = Lim<T>::hi(), gmax = Lim<T>::lo();
-  int bits = 15;
+  int bits = classify ? 15 : 0;
   for (int i = threadIdx.x; i < n; i += blockDim.x) {
     const T fv = fr[i], gv = gr[i];
     fmin = sel_min(fmin, fv); fmax = sel_max(fmax, fv);

@@ -56,6 +56,7 @@ __global__ __launch_bounds__(256) void bracket_anchor_kernel(const T* __restrict
   }
   T best = Semiring<T, OP>::identity();
   int best_j = kNone;
+#pragma unroll 4
   for (int j = lo + lane; j <= hi; j += kThreads) {
     const T c = op_sub(OP) ? wrap_sub(fr[t + j], gr[j]) : wrap_add(fr[j], gr[t - j]);
     if (best_j == kNone || (op_max(OP) ? c > best : c < best)) { best = c; best_j = j; }   // ascending j: the first optimum stays
@@ -76,6 +77,269 @@ __global__ __launch_bounds__(256) void bracket_anchor_kernel(const T* __restrict
   if (lane == 0) jstar[(int64_t)row * anchors + a] = best_j;
 }
 
+// ---- periodic operands -------------------------------------------------------------------------
+// A row w is periodic from index 1 on with period p and increment c when w[i+p] = w[i] + c for
+// all 1 <= i, i+p <= n-1 (periodic event streams with jitter, TDMA service; index 0 is left out
+// because such curves are 0 there whatever follows).  With the candidates of the convolution
+// (f (x) w)[t] = min_j f[t-j] + w[j] grouped by j = 1 + r + q p, 0 <= r < p:
+//   F[u]   = min_{q >= 0, u - q p >= 0} f[u - q p] + q c        (one scan along each residue class)
+//   out[t] = min( f[t] + w[0],  min_{0 <= r < p, r <= t-1} F[t-1-r] + w[1+r] )
+// and for the deconvolution (f (/) w)[t] = max_j f[t+j] - w[j]:
+//   F[u]   = max_{q >= 0, u + q p <= n-1} f[u + q p] - q c
+//   out[t] = max( f[t] - w[0],  max_{0 <= r < p, t+1+r <= n-1} F[t+1+r] - w[1+r] )
+// (max-plus convolution and min-plus deconvolution alike).  n p candidates per row pair instead of
+// n^2 / 2, in exact integer arithmetic: F holds f[s] + (w[j] - w[1+r]), which the row ranges
+// must keep inside the type (checked by period_kernel), and F + w[1+r] is the definition's
+// candidate itself.  Any multiple of a period is a period: short periods are multiplied up so
+// that the scan has enough independent residue classes.
+constexpr int kPeriodMax = 1024;     // longest period looked for
+constexpr int kPeriodTries = 4;      // full verifications per operand
+constexpr int kPeriodRun = 128;      // consecutive positions of the first test
+__host__ __device__ inline int period_limit(int64_t n) { return n / 16 < kPeriodMax ? (int)(n / 16) : kPeriodMax; }
+
+// One workgroup per row pair that no other structured path took (sel < kSelSearch): looks for
+// the smallest period <= period_limit(n) of g, and for the convolutions (unless g's is short
+// enough already) of f, by testing every candidate period at kPeriodRun consecutive positions,
+// three spread ones and across the whole row along two residue classes, and the survivors (in
+// ascending order, at most kPeriodTries per operand) at all positions.  On success sel[row] becomes kSelPeriodic /
+// kSelPeriodicSwapped and period[row] (if given) the period to use.
+constexpr int kPeriodThreads = 1024;
+
+template <typename T>
+__global__ __launch_bounds__(kPeriodThreads) void period_kernel(const T* __restrict__ f, int64_t stride_f,
+                                                                const T* __restrict__ g, int64_t stride_g,
+                                                                int32_t* __restrict__ sel,
+                                                                int32_t* __restrict__ period,
+                                                                int32_t* __restrict__ pack_ok, int n, int op) {
+  constexpr int kWaves = kPeriodThreads / 64;
+  __shared__ uint32_t s_cand[2][kPeriodMax / 32];
+  __shared__ T s_red[4][kWaves];
+  __shared__ T s_w[2][kPeriodRun + kPeriodMax];       // w[1 ...], the head of each row
+  const int row = blockIdx.x;
+  if (sel[row] >= kSelSearch) return;
+  const int pmax = period_limit(n);
+  if (pmax < 1) return;
+  const int run = min(kPeriodRun, n - 2 - pmax);      // positions 1 .. run of the first test; >= 1 as n >= 16 pmax
+  const int nrows = op_sub(op) ? 1 : 2;               // g, and f of a convolution
+  const T* rows[2] = {g + (int64_t)row * stride_g, f + (int64_t)row * stride_f};
+  // every period starts as a candidate; the tests below strike out those that fail
+  for (int k = threadIdx.x; k < 2 * (kPeriodMax / 32); k += kPeriodThreads) {
+    const int first = (k % (kPeriodMax / 32)) * 32 + 1;                     // period of bit 0 of this word
+    const bool live = k / (kPeriodMax / 32) < nrows && first <= pmax;
+    (&s_cand[0][0])[k] = !live ? 0u : pmax - first >= 31 ? 0xffffffffu : (1u << (pmax - first + 1)) - 1u;
+  }
+  for (int which = 0; which < nrows; ++which)
+    for (int k = threadIdx.x; k < run + pmax; k += kPeriodThreads) s_w[which][k] = rows[which][1 + k];
+  __syncthreads();
+  // first test of every candidate period: a run of consecutive positions (staircases agree with
+  // many wrong periods at scattered ones), a quarter of it per thread and eight positions at a
+  // time; then (first quarter's thread) three positions spread over the row and the far ends of
+  // two residue classes, w[i + k p] = w[i] + k c (a plateau longer than the run agrees with
+  // every short period locally, never over the whole row)
+  // (items in blocks of 64 periods, so that a wavefront's 64 items share a row and a quarter and
+  // strike from two words of the candidate set with one atomic each)
+  const int quarter = (run + 3) / 4;
+  const int pmax64 = (pmax + 63) & ~63;
+  for (int item = threadIdx.x; item < nrows * 4 * pmax64; item += kPeriodThreads) {
+    const int p = min(item % pmax64 + 1, pmax), part = (item / pmax64) & 3, which = item / (4 * pmax64);
+    const T* w = rows[which];
+    const T* sw = s_w[which];
+    const T c = wrap_sub(sw[p], sw[0]);
+    const int begin = part * quarter, end = min(begin + quarter, run);
+    bool ok = true;
+    for (int i = begin; ok && i < end; i += 8) {
+      int same = 1;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {             // all sixteen reads in flight; past the end: the last position again
+        const int at = min(i + k, run - 1);
+        same &= wrap_sub(sw[at + p], sw[at]) == c;
+      }
+      ok = same != 0;
+    }
+    if (ok && part == 0) {
+      const int span = n - 2 - p;               // positions 1 .. 1 + span have a partner
+      const int i2 = 1 + p / 2;
+      const int k1 = (n - 2) / p, k2 = (n - 1 - i2) / p;
+      const T a0 = w[1 + span], a1 = w[1 + span + p], b0 = w[1 + span / 2], b1 = w[1 + span / 2 + p];
+      const T c0 = w[1 + span / 3], c1 = w[1 + span / 3 + p], d0 = w[1], d1 = w[1 + k1 * p];
+      const T e0 = w[i2], e1 = w[i2 + k2 * p];
+      // (bitwise: the ten loads go out together instead of one pair per decided comparison)
+      ok = (int(wrap_sub(a1, a0) == c) & int(wrap_sub(b1, b0) == c) & int(wrap_sub(c1, c0) == c) &
+            int(wrap_sub(d1, d0) == (T)((T)k1 * c)) & int(wrap_sub(e1, e0) == (T)((T)k2 * c))) != 0;
+    }
+    const uint64_t fail = __ballot(!ok);        // bit k: period (item % pmax64 + 1) of lane k (beyond pmax: no candidate anyway)
+    const int word = (item % pmax64) >> 5;      // lanes 0 and 32: the two words of this block
+    if ((threadIdx.x & 31) == 0) {
+      const uint32_t strike = (threadIdx.x & 32) ? (uint32_t)(fail >> 32) : (uint32_t)fail;
+      if (strike != 0) atomicAnd(&s_cand[which][word], ~strike);
+    }
+  }
+  __syncthreads();
+  // full test of the survivors in ascending order; the first full pass also takes the extrema of
+  // both rows over the indices >= 1
+  const int target = n / 64 < 32 ? 32 : n / 64 > 256 ? 256 : n / 64;    // periods below it are multiplied up anyway
+  int best_p = 0, best_which = 0;
+  bool have_mm = false;
+  int mm_which = 0;                                                     // the row that wmn / wmx describe
+  T wmn = 0, wmx = 0, omn = 0, omx = 0;
+  for (int which = 0; which < nrows; ++which) {
+    if (best_p != 0 && best_p <= target) break;
+    const T* w = rows[which];
+    const T* o = rows[which ^ 1];
+    int tries = 0;
+    bool done = false;
+    for (int word = 0; word < kPeriodMax / 32 && !done; ++word) {
+      uint32_t bits = s_cand[which][word];
+      while (bits != 0 && !done) {
+        const int p = word * 32 + __builtin_ctz(bits) + 1;
+        bits &= bits - 1;
+        if ((best_p != 0 && p >= best_p) || tries++ == kPeriodTries) { done = true; break; }
+        const T c = wrap_sub(s_w[which][p], s_w[which][0]);
+        int bad = 0;
+        if (!have_mm) {
+          wmn = wmx = w[1]; omn = omx = o[1];
+#pragma unroll 4
+          for (int i = 1 + threadIdx.x; i <= n - 1; i += kPeriodThreads) {
+            const T wv = w[i], ov = o[i], wp = w[min(i + p, n - 1)];
+            bad |= (i + p <= n - 1) && wrap_sub(wp, wv) != c;
+            wmn = sel_min(wmn, wv); wmx = sel_max(wmx, wv);
+            omn = sel_min(omn, ov); omx = sel_max(omx, ov);
+          }
+          have_mm = true;
+          mm_which = which;
+        } else {
+#pragma unroll 8
+          for (int i = 1 + threadIdx.x; i + p <= n - 1; i += kPeriodThreads) bad |= wrap_sub(w[i + p], w[i]) != c;
+        }
+        if (__syncthreads_or(bad) == 0) { best_p = p; best_which = which; done = true; }
+      }
+    }
+  }
+  if (best_p == 0) return;
+  // ranges: every f[s] +- (w[j] - w[j']) must fit the type
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    wmn = sel_min(wmn, __shfl_xor(wmn, off)); wmx = sel_max(wmx, __shfl_xor(wmx, off));
+    omn = sel_min(omn, __shfl_xor(omn, off)); omx = sel_max(omx, __shfl_xor(omx, off));
+  }
+  if ((threadIdx.x & 63) == 0) {
+    const int wave = threadIdx.x >> 6;
+    s_red[0][wave] = wmn; s_red[1][wave] = wmx; s_red[2][wave] = omn; s_red[3][wave] = omx;
+  }
+  __syncthreads();
+  if (threadIdx.x != 0) return;
+  for (int k = 1; k < kWaves; ++k) {
+    wmn = sel_min(wmn, s_red[0][k]); wmx = sel_max(wmx, s_red[1][k]);
+    omn = sel_min(omn, s_red[2][k]); omx = sel_max(omx, s_red[3][k]);
+  }
+  const bool same = best_which == mm_which;
+  const T wmin = same ? wmn : omn, wmax = same ? wmx : omx;
+  const T u0 = rows[best_which ^ 1][0];
+  const T umin = sel_min(same ? omn : wmn, u0), umax = sel_max(same ? omx : wmx, u0);
+  T span, dummy;
+  if (__builtin_sub_overflow(wmax, wmin, &span) || __builtin_add_overflow(umax, span, &dummy) ||
+      __builtin_sub_overflow(umin, span, &dummy))
+    return;
+  // multiply short periods up: enough residue classes for the scan, still a short window
+  int p = best_p;
+  if (p < target) {
+    p = best_p * ((target + best_p - 1) / best_p);
+    if (p > pmax) p = best_p * (pmax / best_p);
+  }
+  sel[row] = best_which ? kSelPeriodicSwapped : kSelPeriodic;
+  if (period != nullptr) period[row] = p;
+  if (pack_ok != nullptr) pack_ok[row] = 0;          // no packed-path preparation for this row
+}
+
+// F of the rows that period_kernel selected: one thread per residue class.
+template <typename T, int OP>
+__global__ __launch_bounds__(256) void periodic_scan_kernel(const T* __restrict__ f, int64_t stride_f,
+                                                            const T* __restrict__ g, int64_t stride_g,
+                                                            const int32_t* __restrict__ sel,
+                                                            const int32_t* __restrict__ period, T* __restrict__ F,
+                                                            int n, int blocks_per_row) {
+  const int row = blockIdx.x / blocks_per_row;
+  const int code = sel[row];
+  if (code != kSelPeriodic && code != kSelPeriodicSwapped) return;
+  const int p = period[row];
+  const int rho = (blockIdx.x % blocks_per_row) * 256 + threadIdx.x;
+  if (rho >= p) return;
+  const bool swapped = code == kSelPeriodicSwapped;
+  const T* u = swapped ? g + (int64_t)row * stride_g : f + (int64_t)row * stride_f;
+  const T* w = swapped ? f + (int64_t)row * stride_f : g + (int64_t)row * stride_g;
+  T* Fr = F + (int64_t)row * n;
+  const T c = wrap_sub(w[1 + p], w[1]);
+  const int steps = (n - 1 - rho) / p;               // the class is rho, rho + p, ..., rho + steps p
+  if (!op_sub(OP)) {
+    T acc = u[rho];
+    Fr[rho] = acc;
+#pragma unroll 8
+    for (int k = 1; k <= steps; ++k) {
+      const int i = rho + k * p;
+      acc = Semiring<T, OP>::reduce(u[i], wrap_add(acc, c));
+      Fr[i] = acc;
+    }
+  } else {
+    T acc = u[rho + steps * p];
+    Fr[rho + steps * p] = acc;
+#pragma unroll 8
+    for (int k = steps - 1; k >= 0; --k) {
+      const int i = rho + k * p;
+      acc = Semiring<T, OP>::reduce(u[i], wrap_sub(acc, c));
+      Fr[i] = acc;
+    }
+  }
+}
+
+// The short window over F: one workgroup per 256 outputs of a selected row, the F values they
+// need (256 + p - 1 of them) staged in LDS, the periodic operand's first period read through
+// uniform loads.  Candidates outside the triangle exist only in a row's first (convolutions) or
+// last (deconvolutions) workgroups, which take the checked loop.
+template <typename T, int OP>
+__global__ __launch_bounds__(256) void periodic_product_kernel(const T* __restrict__ f, int64_t stride_f,
+                                                               const T* __restrict__ g, int64_t stride_g,
+                                                               T* __restrict__ out, const T* __restrict__ cap,
+                                                               const int32_t* __restrict__ sel,
+                                                               const int32_t* __restrict__ period,
+                                                               const T* __restrict__ F, int n, int blocks_per_row) {
+  __shared__ T s_F[256 + kPeriodMax];
+  const int row = blockIdx.x / blocks_per_row;
+  const int code = sel[row];
+  if (code != kSelPeriodic && code != kSelPeriodicSwapped) return;
+  const int p = period[row];
+  const int t0 = (blockIdx.x % blocks_per_row) * 256;
+  const int t = t0 + threadIdx.x;
+  const bool swapped = code == kSelPeriodicSwapped;
+  const T* u = swapped ? g + (int64_t)row * stride_g : f + (int64_t)row * stride_f;
+  const T* w = swapped ? f + (int64_t)row * stride_f : g + (int64_t)row * stride_g;
+  const T* Fr = F + (int64_t)row * n;
+  // convolutions read F[t - r1], deconvolutions F[t + r1], r1 = 1 .. p:  s_F[k] = F[base + k]
+  const int base = op_sub(OP) ? t0 + 1 : t0 - p;
+  for (int k = threadIdx.x; k < 255 + p; k += 256) {
+    const int i = base + k;
+    s_F[k] = (i >= 0 && i < n) ? Fr[i] : T(0);       // never used where it does not exist
+  }
+  __syncthreads();
+  if (t >= n) return;
+  T v = op_sub(OP) ? wrap_sub(u[t], w[0]) : wrap_add(u[t], w[0]);
+  const bool whole = op_sub(OP) ? t0 + 255 + p <= n - 1 : t0 >= p;      // every candidate of every lane exists
+  if (whole) {
+#pragma unroll 8
+    for (int r1 = 1; r1 <= p; ++r1) {
+      const T fv = s_F[op_sub(OP) ? (int)threadIdx.x + r1 - 1 : (int)threadIdx.x + p - r1];
+      v = Semiring<T, OP>::reduce(v, op_sub(OP) ? wrap_sub(fv, w[r1]) : wrap_add(fv, w[r1]));
+    }
+  } else {
+    const int last = min(p, op_sub(OP) ? n - 1 - t : t);
+    for (int r1 = 1; r1 <= last; ++r1) {
+      const T fv = s_F[op_sub(OP) ? (int)threadIdx.x + r1 - 1 : (int)threadIdx.x + p - r1];
+      v = Semiring<T, OP>::reduce(v, op_sub(OP) ? wrap_sub(fv, w[r1]) : wrap_add(fv, w[r1]));
+    }
+  }
+  if (cap != nullptr) v = sel_min(v, cap[(int64_t)row * n + t]);
+  out[(int64_t)row * n + t] = v;
+}
+
 // Rows with sel[row] == kSelEnds or kSelSearch (decided by the probe kernels, see
 // structure_code) are computed here, every other row is left alone.  The candidates of output t
 // are c(j), 0 <= j <= m:
@@ -87,8 +351,9 @@ __global__ __launch_bounds__(256) void bracket_anchor_kernel(const T* __restrict
 // kSelBracket(Swapped): the reduction over the candidates between the optima of the two anchors
 //             around t (bracket_anchor_kernel's fine level; one wavefront = the 64 outputs
 //             between two anchors).
+// kSelPeriodic(Swapped): left to periodic_product_kernel.
 // Each candidate is formed exactly as the general kernels form it (one wrap-around add or
-// subtract), so the result is the same value bit for bit.
+// subtract; the periodic path's in two exact steps), so the result is the same value bit for bit.
 template <typename T, int OP>
 __global__ __launch_bounds__(256) void structured_kernel(const T* __restrict__ f, int64_t stride_f,
                                                          const T* __restrict__ g, int64_t stride_g,
@@ -111,12 +376,15 @@ __global__ __launch_bounds__(256) void structured_kernel(const T* __restrict__ f
   T v;
   if (code == kSelEnds) {
     v = Semiring<T, OP>::reduce(c(0), c(m));
+  } else if (code >= kSelPeriodic) {
+    return;                                          // periodic_product_kernel
   } else if (code >= kSelBracket) {
     const int32_t* js = jstar + (int64_t)row * bracket_anchors(n, kBracketFine) + t / kBracketFine;
     const int ja = js[0], jb = js[1];            // optima of the fine anchors below and above t
     const int lo = op_sub(OP) ? jb : ja;
     const int hi = min(op_sub(OP) ? ja : jb, m);
     v = c(lo);
+#pragma unroll 4
     for (int j = lo + 1; j <= hi; ++j) v = Semiring<T, OP>::reduce(v, c(j));
   } else {
     int lo = 0, hi = m;
@@ -131,13 +399,23 @@ __global__ __launch_bounds__(256) void structured_kernel(const T* __restrict__ f
   out[(int64_t)row * n + t] = v;
 }
 
+// Runs after the probe kernels (which write sel) and before any kernel that reads sel.
+template <typename T>
+void launch_period(const T* f, int64_t stride_f, const T* g, int64_t stride_g, int32_t* sel, int32_t* period,
+                   int32_t* pack_ok, int64_t batch, int64_t n, int op, hipStream_t stream) {
+  if (period_limit(n) < 1) return;
+  hipLaunchKernelGGL(period_kernel<T>, dim3((uint32_t)batch), dim3(kPeriodThreads), 0, stream, f, stride_f, g, stride_g, sel,
+                     period, pack_ok, (int)n, op);
+}
+
 inline size_t bracket_jstar_elems(int64_t batch, int64_t n) {
   return (size_t)batch * ((size_t)bracket_anchors(n, kBracketFine) + (size_t)bracket_anchors(n, kBracketCoarse));
 }
 
 template <typename T, int OP>
 int launch_structured(const T* f, int64_t stride_f, const T* g, int64_t stride_g, T* out, const T* cap,
-                      const int32_t* sel, int32_t* jstar, int64_t batch, int64_t n, hipStream_t stream) {
+                      const int32_t* sel, int32_t* jstar, const int32_t* period, T* F, int64_t batch, int64_t n,
+                      hipStream_t stream) {
   const int64_t bpr = (n + 255) / 256;
   const int fine = bracket_anchors(n, kBracketFine), coarse = bracket_anchors(n, kBracketCoarse);
   if (batch * fine > 0x7fffffffLL) return RTC_ERR_SHAPE;
@@ -148,8 +426,15 @@ int launch_structured(const T* f, int64_t stride_f, const T* g, int64_t stride_g
                      stream, f, stride_f, g, stride_g, sel, nullptr, 0, jcoarse, (int)n, coarse);
   hipLaunchKernelGGL((bracket_anchor_kernel<T, OP, kBracketFine, false>), dim3((uint32_t)(batch * ((fine + 3) / 4))),
                      dim3(256), 0, stream, f, stride_f, g, stride_g, sel, jcoarse, coarse, jstar, (int)n, fine);
+  const int pblocks = (period_limit(n) + 255) / 256;
+  if (pblocks > 0)
+    hipLaunchKernelGGL((periodic_scan_kernel<T, OP>), dim3((uint32_t)(batch * pblocks)), dim3(256), 0, stream, f,
+                       stride_f, g, stride_g, sel, period, F, (int)n, pblocks);
   hipLaunchKernelGGL((structured_kernel<T, OP>), dim3((uint32_t)(batch * bpr)), dim3(256), 0, stream, f, stride_f, g,
                      stride_g, out, cap, sel, jstar, (int)n, (int)bpr);
+  if (pblocks > 0)
+    hipLaunchKernelGGL((periodic_product_kernel<T, OP>), dim3((uint32_t)(batch * bpr)), dim3(256), 0, stream, f,
+                       stride_f, g, stride_g, out, cap, sel, period, F, (int)n, (int)bpr);
   return hip_ok();
 }
 

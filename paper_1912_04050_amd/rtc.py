@@ -154,6 +154,7 @@ _lib.rtc_product_structure.argtypes = [_int, _vp, _vp, _vp, _i64, _i64, _i64, _i
 _lib.rtc_product_structure.restype = _int
 RTC_STRUCTURE_GENERAL, RTC_STRUCTURE_BISECT, RTC_STRUCTURE_ENDS = 1, 2, 3
 RTC_STRUCTURE_BRACKET, RTC_STRUCTURE_BRACKET_SWAPPED = 4, 5
+RTC_STRUCTURE_PERIODIC, RTC_STRUCTURE_PERIODIC_SWAPPED = 6, 7
 
 
 def rtc_product_structure(op: int, f, g, out=None):
@@ -176,6 +177,14 @@ _lib.rtc_set_packed_small_n.restype = _int
 
 def rtc_set_packed_small_n(n: int):
     _check(_lib.rtc_set_packed_small_n(int(n)))
+
+
+_lib.rtc_set_structure_paths.argtypes = [_int]
+_lib.rtc_set_structure_paths.restype = _int
+
+
+def rtc_set_structure_paths(enabled: bool):
+    _check(_lib.rtc_set_structure_paths(1 if enabled else 0))
 
 
 def rtc_profile_enable(on: bool):
