@@ -25,22 +25,22 @@ __host__ __device__ inline int bracket_anchors(int64_t n, int step) { return (in
 // structured_kernel those between two fine anchors: about n^2 / 8192 + 128 n candidates per row
 // pair instead of n^2 / 2.
 template <typename T, int OP, int STEP, bool SHARED>
-__global__ __launch_bounds__(256) void bracket_anchor_kernel(const T* __restrict__ f, int64_t stride_f,
-                                                                 const T* __restrict__ g, int64_t stride_g,
-                                                                 const int32_t* __restrict__ sel,
-                                                                 const int32_t* __restrict__ coarse, int coarse_anchors,
-                                                                 int32_t* __restrict__ jstar, int n, int anchors) {
+__device__ __forceinline__ void bracket_anchor_body(const T* __restrict__ f, int64_t stride_f,
+                                                    const T* __restrict__ g, int64_t stride_g,
+                                                    const int32_t* __restrict__ sel,
+                                                    const int32_t* __restrict__ coarse, int coarse_anchors,
+                                                    int32_t* __restrict__ jstar, int n, int anchors, int block) {
   constexpr int kWaves = 4;
   constexpr int kThreads = SHARED ? 256 : 64;    // lanes that share one anchor
   constexpr int kNone = 0x7fffffff;
   __shared__ T s_val[kWaves];
   __shared__ int s_idx[kWaves];
   const int groups = SHARED ? anchors : (anchors + kWaves - 1) / kWaves;   // workgroups per row
-  const int row = blockIdx.x / groups;
+  const int row = block / groups;
   const int code = sel[row];
   if (code != kSelBracket && code != kSelBracketSwapped) return;
   const int lane = SHARED ? threadIdx.x : threadIdx.x & 63;
-  const int a = SHARED ? blockIdx.x % groups : (blockIdx.x % groups) * kWaves + (threadIdx.x >> 6);
+  const int a = SHARED ? block % groups : (block % groups) * kWaves + (threadIdx.x >> 6);
   if (a >= anchors) return;                       // SHARED: never; else whole wavefronts, and no barrier follows
   const int t = min(a * STEP, n - 1);
   const bool swapped = code == kSelBracketSwapped;       // convolutions only: they commute
@@ -253,16 +253,16 @@ __global__ __launch_bounds__(kPeriodThreads) void period_kernel(const T* __restr
 
 // F of the rows that period_kernel selected: one thread per residue class.
 template <typename T, int OP>
-__global__ __launch_bounds__(256) void periodic_scan_kernel(const T* __restrict__ f, int64_t stride_f,
-                                                            const T* __restrict__ g, int64_t stride_g,
-                                                            const int32_t* __restrict__ sel,
-                                                            const int32_t* __restrict__ period, T* __restrict__ F,
-                                                            int n, int blocks_per_row) {
-  const int row = blockIdx.x / blocks_per_row;
+__device__ __forceinline__ void periodic_scan_body(const T* __restrict__ f, int64_t stride_f,
+                                                   const T* __restrict__ g, int64_t stride_g,
+                                                   const int32_t* __restrict__ sel,
+                                                   const int32_t* __restrict__ period, T* __restrict__ F, int n,
+                                                   int blocks_per_row, int block) {
+  const int row = block / blocks_per_row;
   const int code = sel[row];
   if (code != kSelPeriodic && code != kSelPeriodicSwapped) return;
   const int p = period[row];
-  const int rho = (blockIdx.x % blocks_per_row) * 256 + threadIdx.x;
+  const int rho = (block % blocks_per_row) * 256 + threadIdx.x;
   if (rho >= p) return;
   const bool swapped = code == kSelPeriodicSwapped;
   const T* u = swapped ? g + (int64_t)row * stride_g : f + (int64_t)row * stride_f;
@@ -291,23 +291,19 @@ __global__ __launch_bounds__(256) void periodic_scan_kernel(const T* __restrict_
   }
 }
 
-// The short window over F: one workgroup per 256 outputs of a selected row, the F values they
-// need (256 + p - 1 of them) staged in LDS, the periodic operand's first period read through
-// uniform loads.  Candidates outside the triangle exist only in a row's first (convolutions) or
-// last (deconvolutions) workgroups, which take the checked loop.
+// The short window over F for the 256 outputs from t0 on of a selected row (the whole
+// workgroup comes here): the F values they need (256 + p - 1 of them) staged in LDS (s_F,
+// 256 + kPeriodMax values), the periodic operand's first period read through uniform loads.
+// Candidates outside the triangle exist only in a row's first (convolutions) or last
+// (deconvolutions) workgroups, which take the checked loop.
 template <typename T, int OP>
-__global__ __launch_bounds__(256) void periodic_product_kernel(const T* __restrict__ f, int64_t stride_f,
-                                                               const T* __restrict__ g, int64_t stride_g,
-                                                               T* __restrict__ out, const T* __restrict__ cap,
-                                                               const int32_t* __restrict__ sel,
-                                                               const int32_t* __restrict__ period,
-                                                               const T* __restrict__ F, int n, int blocks_per_row) {
-  __shared__ T s_F[256 + kPeriodMax];
-  const int row = blockIdx.x / blocks_per_row;
-  const int code = sel[row];
-  if (code != kSelPeriodic && code != kSelPeriodicSwapped) return;
+__device__ __forceinline__ void periodic_product_body(const T* __restrict__ f, int64_t stride_f,
+                                                      const T* __restrict__ g, int64_t stride_g,
+                                                      T* __restrict__ out, const T* __restrict__ cap,
+                                                      const int32_t* __restrict__ period,
+                                                      const T* __restrict__ F, T* s_F, int n, int row, int code,
+                                                      int t0) {
   const int p = period[row];
-  const int t0 = (blockIdx.x % blocks_per_row) * 256;
   const int t = t0 + threadIdx.x;
   const bool swapped = code == kSelPeriodicSwapped;
   const T* u = swapped ? g + (int64_t)row * stride_g : f + (int64_t)row * stride_f;
@@ -349,9 +345,9 @@ __global__ __launch_bounds__(256) void periodic_product_kernel(const T* __restri
 // kSelSearch: bisection for the first j with c(j+1) >= c(j) (min over a convex sequence) resp.
 //             c(j+1) <= c(j) (max over a concave one); c there is the result.
 // kSelBracket(Swapped): the reduction over the candidates between the optima of the two anchors
-//             around t (bracket_anchor_kernel's fine level; one wavefront = the 64 outputs
+//             around t (bracket_fine_kernel; one wavefront = the 64 outputs
 //             between two anchors).
-// kSelPeriodic(Swapped): left to periodic_product_kernel.
+// kSelPeriodic(Swapped): the short window over F, periodic_product_body.
 // Each candidate is formed exactly as the general kernels form it (one wrap-around add or
 // subtract; the periodic path's in two exact steps), so the result is the same value bit for bit.
 template <typename T, int OP>
@@ -359,13 +355,19 @@ __global__ __launch_bounds__(256) void structured_kernel(const T* __restrict__ f
                                                          const T* __restrict__ g, int64_t stride_g,
                                                          T* __restrict__ out, const T* __restrict__ cap,
                                                          const int32_t* __restrict__ sel,
-                                                         const int32_t* __restrict__ jstar, int n,
-                                                         int blocks_per_row) {
+                                                         const int32_t* __restrict__ jstar,
+                                                         const int32_t* __restrict__ period,
+                                                         const T* __restrict__ F, int n, int blocks_per_row) {
   static_assert(256 % kBracketFine == 0 && kBracketFine == 64, "one wavefront = the outputs between two fine anchors");
+  __shared__ T s_F[256 + kPeriodMax];
   const int row = blockIdx.x / blocks_per_row;
   const int code = sel[row];
   if (code < kSelSearch) return;
   const int block = blockIdx.x % blocks_per_row;
+  if (code >= kSelPeriodic) {
+    periodic_product_body<T, OP>(f, stride_f, g, stride_g, out, cap, period, F, s_F, n, row, code, block * 256);
+    return;
+  }
   const int t = block * 256 + threadIdx.x;
   if (t >= n) return;
   const bool swapped = code == kSelBracketSwapped;
@@ -376,8 +378,6 @@ __global__ __launch_bounds__(256) void structured_kernel(const T* __restrict__ f
   T v;
   if (code == kSelEnds) {
     v = Semiring<T, OP>::reduce(c(0), c(m));
-  } else if (code >= kSelPeriodic) {
-    return;                                          // periodic_product_kernel
   } else if (code >= kSelBracket) {
     const int32_t* js = jstar + (int64_t)row * bracket_anchors(n, kBracketFine) + t / kBracketFine;
     const int ja = js[0], jb = js[1];            // optima of the fine anchors below and above t
@@ -400,6 +400,33 @@ __global__ __launch_bounds__(256) void structured_kernel(const T* __restrict__ f
 }
 
 // Runs after the probe kernels (which write sel) and before any kernel that reads sel.
+// First launch of the structured rows: the coarse anchors of the bracket path and the scan of
+// the periodic path (different rows; both feed the launches that follow).
+template <typename T, int OP>
+__global__ __launch_bounds__(256) void structured_first_kernel(const T* __restrict__ f, int64_t stride_f,
+                                                               const T* __restrict__ g, int64_t stride_g,
+                                                               const int32_t* __restrict__ sel,
+                                                               int32_t* __restrict__ jcoarse, int coarse_anchors,
+                                                               int anchor_blocks, const int32_t* __restrict__ period,
+                                                               T* __restrict__ F, int n, int scan_blocks_per_row) {
+  if ((int)blockIdx.x < anchor_blocks)
+    bracket_anchor_body<T, OP, kBracketCoarse, true>(f, stride_f, g, stride_g, sel, nullptr, 0, jcoarse, n,
+                                                     coarse_anchors, blockIdx.x);
+  else
+    periodic_scan_body<T, OP>(f, stride_f, g, stride_g, sel, period, F, n, scan_blocks_per_row,
+                              blockIdx.x - anchor_blocks);
+}
+
+template <typename T, int OP>
+__global__ __launch_bounds__(256) void bracket_fine_kernel(const T* __restrict__ f, int64_t stride_f,
+                                                           const T* __restrict__ g, int64_t stride_g,
+                                                           const int32_t* __restrict__ sel,
+                                                           const int32_t* __restrict__ jcoarse, int coarse_anchors,
+                                                           int32_t* __restrict__ jstar, int n, int anchors) {
+  bracket_anchor_body<T, OP, kBracketFine, false>(f, stride_f, g, stride_g, sel, jcoarse, coarse_anchors, jstar, n,
+                                                  anchors, blockIdx.x);
+}
+
 template <typename T>
 void launch_period(const T* f, int64_t stride_f, const T* g, int64_t stride_g, int32_t* sel, int32_t* period,
                    int32_t* pack_ok, int64_t batch, int64_t n, int op, hipStream_t stream) {
@@ -422,19 +449,15 @@ int launch_structured(const T* f, int64_t stride_f, const T* g, int64_t stride_g
   // jstar: [batch][fine] optima of the fine anchors, then [batch][coarse] of the coarse ones
   // (bracket_jstar_elems() int32 in all)
   int32_t* jcoarse = jstar + batch * fine;
-  hipLaunchKernelGGL((bracket_anchor_kernel<T, OP, kBracketCoarse, true>), dim3((uint32_t)(batch * coarse)), dim3(256), 0,
-                     stream, f, stride_f, g, stride_g, sel, nullptr, 0, jcoarse, (int)n, coarse);
-  hipLaunchKernelGGL((bracket_anchor_kernel<T, OP, kBracketFine, false>), dim3((uint32_t)(batch * ((fine + 3) / 4))),
-                     dim3(256), 0, stream, f, stride_f, g, stride_g, sel, jcoarse, coarse, jstar, (int)n, fine);
   const int pblocks = (period_limit(n) + 255) / 256;
-  if (pblocks > 0)
-    hipLaunchKernelGGL((periodic_scan_kernel<T, OP>), dim3((uint32_t)(batch * pblocks)), dim3(256), 0, stream, f,
-                       stride_f, g, stride_g, sel, period, F, (int)n, pblocks);
+  if (batch * (coarse + pblocks) > 0x7fffffffLL) return RTC_ERR_SHAPE;
+  hipLaunchKernelGGL((structured_first_kernel<T, OP>), dim3((uint32_t)(batch * (coarse + pblocks))), dim3(256), 0,
+                     stream, f, stride_f, g, stride_g, sel, jcoarse, coarse, (int)(batch * coarse), period, F, (int)n,
+                     pblocks);
+  hipLaunchKernelGGL((bracket_fine_kernel<T, OP>), dim3((uint32_t)(batch * ((fine + 3) / 4))), dim3(256), 0, stream,
+                     f, stride_f, g, stride_g, sel, jcoarse, coarse, jstar, (int)n, fine);
   hipLaunchKernelGGL((structured_kernel<T, OP>), dim3((uint32_t)(batch * bpr)), dim3(256), 0, stream, f, stride_f, g,
-                     stride_g, out, cap, sel, jstar, (int)n, (int)bpr);
-  if (pblocks > 0)
-    hipLaunchKernelGGL((periodic_product_kernel<T, OP>), dim3((uint32_t)(batch * bpr)), dim3(256), 0, stream, f,
-                       stride_f, g, stride_g, out, cap, sel, period, F, (int)n, (int)bpr);
+                     stride_g, out, cap, sel, jstar, period, F, (int)n, (int)bpr);
   return hip_ok();
 }
 
