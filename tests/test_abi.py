@@ -127,3 +127,33 @@ def test_bnn_entry_points_reject_bad_arguments(lib):
     assert lib.bnn_binary_conv2d(p, p, p, p, p, p, 0, 8, 8, 32, 64, 3, 3, 1, 1, None) == -2
     lib.bnn_strerror.restype = ctypes.c_char_p
     assert b"width" in lib.bnn_strerror(-5)
+
+
+def test_binding_constants_match_the_headers():
+    """Every enumerator and flag of the two headers that the Python bindings also define has the
+    header's value there (the bindings restate them; nothing generates one from the other)."""
+    from paper_1912_04050_amd import bnn, rtc
+
+    def constants(path):
+        text = re.sub(r"/\*.*?\*/", "", open(path).read(), flags=re.S)
+        found = {m.group(1): int(m.group(2), 0) for m in re.finditer(r"#define\s+((?:RTC|BNN)_\w+)\s+(-?\w+)\s*$", text, re.M)
+                 if re.fullmatch(r"-?(0x[0-9a-fA-F]+|\d+)", m.group(2))}
+        for body in re.findall(r"enum\s*\w*\s*\{(.*?)\}", text, re.S):
+            nxt = 0
+            for item in body.split(","):
+                item = item.strip()
+                if not item:
+                    continue
+                name, _, val = item.partition("=")
+                nxt = int(val.strip(), 0) if val.strip() else nxt
+                found[name.strip()] = nxt
+                nxt += 1
+        return found
+
+    checked = 0
+    for mod, header in ((rtc, HEADER), (bnn, os.path.join(ROOT, "include", "bnn.h"))):
+        for name, value in constants(header).items():
+            if hasattr(mod, name):
+                assert getattr(mod, name) == value, (name, getattr(mod, name), value)
+                checked += 1
+    assert checked >= 20

@@ -35,8 +35,15 @@ def draw_rows(rng, batch, n, dtype):
     """A batch of rows in one of several styles (chosen per row)."""
     rows = []
     for _ in range(batch):
-        style = rng.integers(0, 6)
-        if style == 0:      # slow staircase
+        style = rng.integers(0, 8)
+        if style == 6:      # periodic from index 1 on (event stream with jitter, TDMA-like service)
+            p = int(rng.integers(1, max(2, min(300, n // 8 + 1))))
+            pat = rng.integers(0, 6, p) * (rng.random(p) < 0.4)
+            v = np.concatenate([[0, int(rng.integers(0, 40))], np.tile(pat, n // p + 2)])[:n]
+            v[1:] = np.cumsum(v[1:])
+        elif style == 7:    # plateaus and rare steps
+            v = np.cumsum(np.where(rng.random(n) < 0.01, rng.integers(1, 50, n), 0))
+        elif style == 0:    # slow staircase
             v = np.cumsum(rng.integers(0, 4, n))
         elif style == 1:    # bursts
             v = np.cumsum(np.where(rng.random(n) < 0.02, rng.integers(100, 5000, n), rng.integers(0, 3, n)))
@@ -50,7 +57,7 @@ def draw_rows(rng, batch, n, dtype):
         else:               # constant / plateau
             v = np.full(n, int(rng.integers(-9, 9)))
         if np.issubdtype(dtype, np.floating):
-            v = v * 0.37 + rng.random(n) * (style != 5)
+            v = v * 0.37 + rng.random(n) * (style not in (5, 6, 7))
         rows.append(v)
     return np.stack(rows).astype(dtype)
 
