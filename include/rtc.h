@@ -213,8 +213,8 @@ int rtc_max_vdev(const void* alpha, const void* beta, void* out, int64_t batch, 
  * on when w[i+p] = w[i] + c for all 1 <= i <= n-1-p (event streams with jitter, TDMA service;
  * index 0 is left out because such curves are 0 there), with a period p <= min(1024, n/16).
  * RTC_STRUCTURE_PERIODIC: g is (its smallest such period is used); RTC_STRUCTURE_PERIODIC_SWAPPED
- * (convolutions only): f is, and g is not or has a longer period that exceeds
- * min(max(n/64, 32), 256).  Grouping the candidates by residue class of j turns the product into
+ * (convolutions only): f is, and g is not or has a longer period that exceeds the length up to
+ * which periods are multiplied anyway (between 32 and 256, about sqrt(1.2e6 / batch)).  Grouping the candidates by residue class of j turns the product into
  * one scan along each class of the other operand plus a window of p candidates per output,
  * n p candidates instead of n^2/2.  Not taken when the other row's range plus w's would leave
  * the type.  The search tests each period at 128 consecutive and a few spread positions first

@@ -90,11 +90,19 @@ __device__ __forceinline__ void bracket_anchor_body(const T* __restrict__ f, int
 // (max-plus convolution and min-plus deconvolution alike).  n p candidates per row pair instead of
 // n^2 / 2, in exact integer arithmetic: F holds f[s] + (w[j] - w[1+r]), which the row ranges
 // must keep inside the type (checked by period_kernel), and F + w[1+r] is the definition's
-// candidate itself.  Any multiple of a period is a period: short periods are multiplied up so
-// that the scan has enough independent residue classes.
+// candidate itself.  Any multiple of a period is a period: short periods are multiplied up
+// (period_target).
 constexpr int kPeriodMax = 1024;     // longest period looked for
 constexpr int kPeriodTries = 4;      // full verifications per operand
 constexpr int kPeriodRun = 128;      // consecutive positions of the first test
+// Periods shorter than this are multiplied up.  The scan walks n / p steps per residue class one
+// after the other (about 0.1 us each, whatever the batch), the window product reduces
+// batch n p candidates at about 12 T/s: the sum is smallest near p = sqrt(1.2e6 / batch).
+__host__ __device__ inline int period_target(int64_t batch) {
+  int t = 32;
+  while (t < 256 && (int64_t)(t + 1) * (t + 1) * batch <= 1200000) ++t;
+  return t;
+}
 __host__ __device__ inline int period_limit(int64_t n) { return n / 16 < kPeriodMax ? (int)(n / 16) : kPeriodMax; }
 
 // One workgroup per row pair that no other structured path took (sel < kSelSearch): looks for
@@ -177,7 +185,7 @@ __global__ __launch_bounds__(kPeriodThreads) void period_kernel(const T* __restr
   __syncthreads();
   // full test of the survivors in ascending order; the first full pass also takes the extrema of
   // both rows over the indices >= 1
-  const int target = n / 64 < 32 ? 32 : n / 64 > 256 ? 256 : n / 64;    // periods below it are multiplied up anyway
+  const int target = period_target(gridDim.x);                          // periods below it are multiplied up anyway
   int best_p = 0, best_which = 0;
   bool have_mm = false;
   int mm_which = 0;                                                     // the row that wmn / wmx describe

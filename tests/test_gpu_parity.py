@@ -491,7 +491,7 @@ def test_one_operand_of_exploitable_convexity_long_rows(rtc, dtype):
             f, g = np.concatenate([f, np.roll(f, 1, axis=0)]).astype(dtype), np.concatenate([g, g]).astype(dtype)
             for name, op in (("conv", rtc.RTC_OP_CONV), ("deconv", rtc.RTC_OP_DECONV), ("maxconv", rtc.RTC_OP_MAXCONV),
                              ("mindeconv", rtc.RTC_OP_MINDECONV)):
-                want = np.array([_structure_by_definition(f[b], g[b], name) for b in range(len(f))])
+                want = np.array([_structure_by_definition(f[b], g[b], name, batch=len(f)) for b in range(len(f))])
                 assert np.array_equal(host(rtc.rtc_product_structure(op, dev(f), dev(g))), want), (tag, name, n)
             check_products(rtc, f, g, f"one-sided {tag} n={n}")
             check_duals(rtc, f, g, f"one-sided duals {tag} n={n}")
@@ -547,7 +547,7 @@ def test_periodic_operands(rtc, dtype):
         for name, op in ops:
             got = host(rtc.rtc_product_structure(op, dev(f), dev(g)))
             for b in range(len(fs)):
-                want = _structure_by_definition(f[b], g[b], name)
+                want = _structure_by_definition(f[b], g[b], name, batch=len(fs))
                 assert got[b] == want, (name, n, b, got[b], want)
         check_products(rtc, f, g, f"periodic n={n}")
         check_duals(rtc, f, g, f"periodic duals n={n}")
@@ -580,14 +580,16 @@ def test_structure_paths_knob(rtc):
         check_duals(rtc, fd, gd, "structured kernels")
 
 
-def _structure_by_definition(f, g, op, exact_differences=True):
+def _structure_by_definition(f, g, op, exact_differences=True, batch=1):
     """The documented rule: convexity first, then periodicity."""
     code = _convexity_by_definition(f, g, op) if exact_differences else 1
     n = len(f)
     if code != 1 or n // 16 < 1:
         return code
     pg = _period_by_definition(g, n)
-    target = min(max(n // 64, 32), 256)       # shorter periods are multiplied up to it: f is not looked at then
+    target = 32                               # shorter periods are multiplied up to it: f is not looked at then
+    while target < 256 and (target + 1) ** 2 * batch <= 1200000:
+        target += 1
     pf = _period_by_definition(f, n) if op in ("conv", "maxconv") and not (0 < pg <= target) else 0
     return 6 if pg and (not pf or pg <= pf) else 7 if pf else 1
 
@@ -636,9 +638,9 @@ def test_product_structure_classification(rtc, dtype):
             if dtype == np.float64:
                 assert np.all(got == 1), name
                 continue
-            want = np.array([_structure_by_definition(f[b], g[b], name) for b in range(len(fs))])
+            want = np.array([_structure_by_definition(f[b], g[b], name, batch=len(fs)) for b in range(len(fs))])
             if dtype == np.int64 and n >= 3:    # second differences of that row are not exact on the device: not used
-                want[1] = _structure_by_definition(f[1], g[1], name, exact_differences=False)
+                want[1] = _structure_by_definition(f[1], g[1], name, exact_differences=False, batch=len(fs))
             assert np.array_equal(got, want), (name, n, np.nonzero(got != want))
 
 
