@@ -107,9 +107,10 @@ __host__ __device__ inline int period_limit(int64_t n) { return n / 16 < kPeriod
 
 // One workgroup per row pair that no other structured path took (sel < kSelSearch): looks for
 // the smallest period <= period_limit(n) of g, and for the convolutions (unless g's is short
-// enough already) of f, by testing every candidate period at kPeriodRun consecutive positions,
-// three spread ones and across the whole row along two residue classes, and the survivors (in
-// ascending order, at most kPeriodTries per operand) at all positions.  On success sel[row] becomes kSelPeriodic /
+// enough already) of f: every period is screened at a few positions, what passes is tested at
+// kPeriodRun consecutive positions, three spread ones and across the whole row along two residue
+// classes, and the survivors (in ascending order, at most kPeriodTries per operand) at all
+// positions.  On success sel[row] becomes kSelPeriodic /
 // kSelPeriodicSwapped and period[row] (if given) the period to use.
 constexpr int kPeriodThreads = 1024;
 
@@ -122,7 +123,9 @@ __global__ __launch_bounds__(kPeriodThreads) void period_kernel(const T* __restr
   constexpr int kWaves = kPeriodThreads / 64;
   __shared__ uint32_t s_cand[2][kPeriodMax / 32];
   __shared__ T s_red[4][kWaves];
-  __shared__ T s_w[2][kPeriodRun + kPeriodMax];       // w[1 ...], the head of each row
+  __shared__ T s_w[2][kPeriodRun + 2 * kPeriodMax];   // w[1 ...], the head of each row
+  __shared__ uint32_t s_seen[2][kPeriodMax / 32];     // periods that passed the screening
+  __shared__ int s_first[2];                          // smallest period that passed the first test
   const int row = blockIdx.x;
   if (sel[row] >= kSelSearch) return;
   const int pmax = period_limit(n);
@@ -130,56 +133,91 @@ __global__ __launch_bounds__(kPeriodThreads) void period_kernel(const T* __restr
   const int run = min(kPeriodRun, n - 2 - pmax);      // positions 1 .. run of the first test; >= 1 as n >= 16 pmax
   const int nrows = op_sub(op) ? 1 : 2;               // g, and f of a convolution
   const T* rows[2] = {g + (int64_t)row * stride_g, f + (int64_t)row * stride_f};
-  // every period starts as a candidate; the tests below strike out those that fail
   for (int k = threadIdx.x; k < 2 * (kPeriodMax / 32); k += kPeriodThreads) {
-    const int first = (k % (kPeriodMax / 32)) * 32 + 1;                     // period of bit 0 of this word
-    const bool live = k / (kPeriodMax / 32) < nrows && first <= pmax;
-    (&s_cand[0][0])[k] = !live ? 0u : pmax - first >= 31 ? 0xffffffffu : (1u << (pmax - first + 1)) - 1u;
+    (&s_cand[0][0])[k] = 0;
+    (&s_seen[0][0])[k] = 0;
   }
+  if (threadIdx.x < 2) s_first[threadIdx.x] = 0x7fffffff;
+  const int staged = min(run + 2 * pmax, n - 1);      // w[1 .. staged]
   for (int which = 0; which < nrows; ++which)
-    for (int k = threadIdx.x; k < run + pmax; k += kPeriodThreads) s_w[which][k] = rows[which][1 + k];
+    for (int k = threadIdx.x; k < staged; k += kPeriodThreads) s_w[which][k] = rows[which][1 + k];
   __syncthreads();
-  // first test of every candidate period: a run of consecutive positions (staircases agree with
-  // many wrong periods at scattered ones), a quarter of it per thread and eight positions at a
-  // time; then (first quarter's thread) three positions spread over the row and the far ends of
-  // two residue classes, w[i + k p] = w[i] + k c (a plateau longer than the run agrees with
-  // every short period locally, never over the whole row)
-  // (items in blocks of 64 periods, so that a wavefront's 64 items share a row and a quarter and
-  // strike from two words of the candidate set with one atomic each)
-  const int quarter = (run + 3) / 4;
-  const int pmax64 = (pmax + 63) & ~63;
-  for (int item = threadIdx.x; item < nrows * 4 * pmax64; item += kPeriodThreads) {
-    const int p = min(item % pmax64 + 1, pmax), part = (item / pmax64) & 3, which = item / (4 * pmax64);
-    const T* w = rows[which];
+  // Screening, one thread per (row, period), from the staged head of the row alone: eight
+  // consecutive positions and the far ends, inside the staged window, of the residue classes
+  // of positions 1 and 1 + p/2, w[i + k p] = w[i] + k c (a plateau agrees with every short
+  // period locally, not across a window longer than the true period).
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int pmax64 = (pmax + 63) & ~63;                // a wavefront's 64 periods share a row and two words
+  for (int item = threadIdx.x; item < nrows * pmax64; item += kPeriodThreads) {
+    const int which = item / pmax64, p = min(item % pmax64 + 1, pmax);
     const T* sw = s_w[which];
     const T c = wrap_sub(sw[p], sw[0]);
-    const int begin = part * quarter, end = min(begin + quarter, run);
-    bool ok = true;
-    for (int i = begin; ok && i < end; i += 8) {
-      int same = 1;
+    const int i2 = p / 2;
+    const int k1 = (staged - 1) / p, k2 = (staged - 1 - i2) / p;
+    int same = (wrap_sub(sw[k1 * p], sw[0]) == (T)((T)k1 * c)) & (wrap_sub(sw[i2 + k2 * p], sw[i2]) == (T)((T)k2 * c));
 #pragma unroll
-      for (int k = 0; k < 8; ++k) {             // all sixteen reads in flight; past the end: the last position again
-        const int at = min(i + k, run - 1);
-        same &= wrap_sub(sw[at + p], sw[at]) == c;
+    for (int k = 0; k < 8; ++k) {
+      const int at = min(k, run - 1);
+      same &= wrap_sub(sw[at + p], sw[at]) == c;
+    }
+    const uint64_t pass = __ballot(same != 0 && item % pmax64 < pmax);
+    if ((lane & 31) == 0) s_seen[which][(item % pmax64) >> 5] = (lane & 32) ? (uint32_t)(pass >> 32) : (uint32_t)pass;
+  }
+  __syncthreads();
+  // First test of what passed, in ascending order, one wavefront per period and kWaves at a
+  // time: a run of consecutive positions (staircases agree with many wrong periods at scattered
+  // ones), three positions spread over the row and the far ends of two residue classes over
+  // the whole row.  What passes becomes a candidate; nothing above the smallest candidate so far
+  // is tested (every multiple of a period passes too).
+  {
+    // the wavefronts are shared out between the rows, so that one round serves both
+    const int per = kWaves / nrows;                    // wavefronts per row
+    const int which = wave / per, slot = wave % per;
+    const T* w = rows[which];
+    const T* sw = s_w[which];
+    // position of a period in a row's set: prefix popcounts over its 32 words
+    uint32_t word[2];
+    int incl[2], total[2];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+      word[r] = (r < nrows && lane < kPeriodMax / 32) ? s_seen[r][lane] : 0u;
+      incl[r] = __popc(word[r]);
+#pragma unroll
+      for (int off = 1; off < 32; off <<= 1) {
+        const int up = __shfl_up(incl[r], off);
+        if (lane >= off) incl[r] += up;
       }
-      ok = same != 0;
+      total[r] = __shfl(incl[r], 31);
     }
-    if (ok && part == 0) {
-      const int span = n - 2 - p;               // positions 1 .. 1 + span have a partner
-      const int i2 = 1 + p / 2;
-      const int k1 = (n - 2) / p, k2 = (n - 1 - i2) / p;
-      const T a0 = w[1 + span], a1 = w[1 + span + p], b0 = w[1 + span / 2], b1 = w[1 + span / 2 + p];
-      const T c0 = w[1 + span / 3], c1 = w[1 + span / 3 + p], d0 = w[1], d1 = w[1 + k1 * p];
-      const T e0 = w[i2], e1 = w[i2 + k2 * p];
-      // (bitwise: the ten loads go out together instead of one pair per decided comparison)
-      ok = (int(wrap_sub(a1, a0) == c) & int(wrap_sub(b1, b0) == c) & int(wrap_sub(c1, c0) == c) &
-            int(wrap_sub(d1, d0) == (T)((T)k1 * c)) & int(wrap_sub(e1, e0) == (T)((T)k2 * c))) != 0;
-    }
-    const uint64_t fail = __ballot(!ok);        // bit k: period (item % pmax64 + 1) of lane k (beyond pmax: no candidate anyway)
-    const int word = (item % pmax64) >> 5;      // lanes 0 and 32: the two words of this block
-    if ((threadIdx.x & 31) == 0) {
-      const uint32_t strike = (threadIdx.x & 32) ? (uint32_t)(fail >> 32) : (uint32_t)fail;
-      if (strike != 0) atomicAnd(&s_cand[which][word], ~strike);
+    const uint32_t my_word = which ? word[1] : word[0];
+    const int my_incl = which ? incl[1] : incl[0], my_total = which ? total[1] : total[0];
+    // this wavefront tests the slot-th, (slot + per)-th, ... period of its row's set, until one
+    // at or below its own has passed somewhere (no barrier: the wavefronts run on their own)
+    for (int k = slot; k < my_total; k += per) {
+      {
+        const uint64_t holds = __ballot(lane < 32 && my_incl > k);       // first word whose prefix count exceeds k
+        const int wi = __builtin_ctzll(holds);
+        uint32_t bits = __shfl(my_word, wi);
+        int skip = k - (__shfl(my_incl, wi) - __popc(bits));
+        while (skip-- > 0) bits &= bits - 1;
+        const int p = wi * 32 + __builtin_ctz(bits) + 1;
+        if (p > *(volatile int*)&s_first[which]) break;
+        const T c = wrap_sub(sw[p], sw[0]);
+        bool ok = true;
+        for (int i = lane; i < run; i += 64) ok = ok && wrap_sub(sw[i + p], sw[i]) == c;
+        ok = __all(ok);                               // (the row itself is only read for periods that got this far)
+        if (ok && lane < 5) {
+          const int span = n - 2 - p;                  // positions 1 .. 1 + span have a partner
+          const int i2 = 1 + p / 2;
+          const int first = lane == 0 ? 1 + span : lane == 1 ? 1 + span / 2 : lane == 2 ? 1 + span / 3 : lane == 3 ? 1 : i2;
+          const int steps = lane == 3 ? (n - 2) / p : lane == 4 ? (n - 1 - i2) / p : 1;
+          ok = wrap_sub(w[first + steps * p], w[first]) == (T)((T)steps * c);
+        }
+        if (__all(ok) && lane == 0) {
+          atomicOr(&s_cand[which][(p - 1) >> 5], 1u << ((p - 1) & 31));
+          atomicMin(&s_first[which], p);
+        }
+      }
     }
   }
   __syncthreads();
@@ -299,11 +337,15 @@ __device__ __forceinline__ void periodic_scan_body(const T* __restrict__ f, int6
   }
 }
 
-// The short window over F for the 256 outputs from t0 on of a selected row (the whole
-// workgroup comes here): the F values they need (256 + p - 1 of them) staged in LDS (s_F,
-// 256 + kPeriodMax values), the periodic operand's first period read through uniform loads.
-// Candidates outside the triangle exist only in a row's first (convolutions) or last
-// (deconvolutions) workgroups, which take the checked loop.
+// The short window over F for the kPeriodicOutputs = 1024 outputs from t0 on of a selected row
+// (the whole workgroup comes here; each thread takes four outputs 256 apart, which spreads the
+// fixed cost of a workgroup -- a chain of dependent loads before the first candidate -- over
+// four times the work): the F values they need (1024 + p - 1 of them) staged in LDS (s_F,
+// kPeriodicOutputs + kPeriodMax values), the periodic operand's first period read through
+// uniform loads.  Candidates outside the triangle exist only in a row's first (convolutions) or
+// last (deconvolutions) workgroup, which takes the checked loop.
+constexpr int kPeriodicPer = 4;                         // outputs per thread
+constexpr int kPeriodicOutputs = 256 * kPeriodicPer;
 template <typename T, int OP>
 __device__ __forceinline__ void periodic_product_body(const T* __restrict__ f, int64_t stride_f,
                                                       const T* __restrict__ g, int64_t stride_g,
@@ -311,37 +353,62 @@ __device__ __forceinline__ void periodic_product_body(const T* __restrict__ f, i
                                                       const int32_t* __restrict__ period,
                                                       const T* __restrict__ F, T* s_F, int n, int row, int code,
                                                       int t0) {
+  constexpr int E = kPeriodicPer;
   const int p = period[row];
-  const int t = t0 + threadIdx.x;
+  const int tid = threadIdx.x;
   const bool swapped = code == kSelPeriodicSwapped;
   const T* u = swapped ? g + (int64_t)row * stride_g : f + (int64_t)row * stride_f;
   const T* w = swapped ? f + (int64_t)row * stride_f : g + (int64_t)row * stride_g;
   const T* Fr = F + (int64_t)row * n;
   // convolutions read F[t - r1], deconvolutions F[t + r1], r1 = 1 .. p:  s_F[k] = F[base + k]
+  // (index clamped where F does not exist: never used there; unrolled so that the loads of
+  // several rounds are in flight together)
   const int base = op_sub(OP) ? t0 + 1 : t0 - p;
-  for (int k = threadIdx.x; k < 255 + p; k += 256) {
-    const int i = base + k;
-    s_F[k] = (i >= 0 && i < n) ? Fr[i] : T(0);       // never used where it does not exist
+  const T w_0 = w[0];
+  T v[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    const T u_t = u[min(t0 + e * 256 + tid, n - 1)];
+    v[e] = op_sub(OP) ? wrap_sub(u_t, w_0) : wrap_add(u_t, w_0);
   }
+#pragma unroll 4
+  for (int k = tid; k < kPeriodicOutputs - 1 + p; k += 256) s_F[k] = Fr[min(max(base + k, 0), n - 1)];
   __syncthreads();
-  if (t >= n) return;
-  T v = op_sub(OP) ? wrap_sub(u[t], w[0]) : wrap_add(u[t], w[0]);
-  const bool whole = op_sub(OP) ? t0 + 255 + p <= n - 1 : t0 >= p;      // every candidate of every lane exists
+  const int at = op_sub(OP) ? tid - 1 : tid + p;        // output e, step r1: s_F[at + 256 e +- r1]
+  const bool whole = op_sub(OP) ? t0 + kPeriodicOutputs - 1 + p <= n - 1 : t0 >= p;   // every candidate of every output exists
   if (whole) {
-#pragma unroll 8
+#pragma unroll 4
     for (int r1 = 1; r1 <= p; ++r1) {
-      const T fv = s_F[op_sub(OP) ? (int)threadIdx.x + r1 - 1 : (int)threadIdx.x + p - r1];
-      v = Semiring<T, OP>::reduce(v, op_sub(OP) ? wrap_sub(fv, w[r1]) : wrap_add(fv, w[r1]));
+      const T wv = w[r1];
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        const T fv = s_F[at + e * 256 + (op_sub(OP) ? r1 : -r1)];
+        v[e] = Semiring<T, OP>::reduce(v[e], op_sub(OP) ? wrap_sub(fv, wv) : wrap_add(fv, wv));
+      }
     }
   } else {
-    const int last = min(p, op_sub(OP) ? n - 1 - t : t);
-    for (int r1 = 1; r1 <= last; ++r1) {
-      const T fv = s_F[op_sub(OP) ? (int)threadIdx.x + r1 - 1 : (int)threadIdx.x + p - r1];
-      v = Semiring<T, OP>::reduce(v, op_sub(OP) ? wrap_sub(fv, w[r1]) : wrap_add(fv, w[r1]));
+#pragma unroll 2
+    for (int r1 = 1; r1 <= p; ++r1) {
+      const T wv = w[r1];
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        const int t = t0 + e * 256 + tid;
+        const bool exists = op_sub(OP) ? r1 <= n - 1 - t : r1 <= t;
+        const T fv = s_F[at + e * 256 + (op_sub(OP) ? r1 : -r1)];
+        const T r = Semiring<T, OP>::reduce(v[e], op_sub(OP) ? wrap_sub(fv, wv) : wrap_add(fv, wv));
+        v[e] = exists ? r : v[e];
+      }
     }
   }
-  if (cap != nullptr) v = sel_min(v, cap[(int64_t)row * n + t]);
-  out[(int64_t)row * n + t] = v;
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    const int t = t0 + e * 256 + tid;
+    if (t < n) {
+      T r = v[e];
+      if (cap != nullptr) r = sel_min(r, cap[(int64_t)row * n + t]);
+      out[(int64_t)row * n + t] = r;
+    }
+  }
 }
 
 // Rows with sel[row] == kSelEnds or kSelSearch (decided by the probe kernels, see
@@ -365,15 +432,20 @@ __global__ __launch_bounds__(256) void structured_kernel(const T* __restrict__ f
                                                          const int32_t* __restrict__ sel,
                                                          const int32_t* __restrict__ jstar,
                                                          const int32_t* __restrict__ period,
-                                                         const T* __restrict__ F, int n, int blocks_per_row) {
+                                                         const T* __restrict__ F, int n, int blocks_per_row,
+                                                         int batch) {
   static_assert(256 % kBracketFine == 0 && kBracketFine == 64, "one wavefront = the outputs between two fine anchors");
-  __shared__ T s_F[256 + kPeriodMax];
-  const int row = blockIdx.x / blocks_per_row;
+  __shared__ T s_F[kPeriodicOutputs + kPeriodMax];
+  // rows fastest: the workgroups that have work (every kPeriodicPer-th block of a periodic row)
+  // then come in runs of `batch` consecutive ones, which the dispatcher spreads over all XCDs and
+  // CUs; with blocks fastest they would all land on a quarter of them
+  const int row = blockIdx.x % batch;
   const int code = sel[row];
   if (code < kSelSearch) return;
-  const int block = blockIdx.x % blocks_per_row;
-  if (code >= kSelPeriodic) {
-    periodic_product_body<T, OP>(f, stride_f, g, stride_g, out, cap, period, F, s_F, n, row, code, block * 256);
+  const int block = blockIdx.x / batch;
+  if (code >= kSelPeriodic) {      // every kPeriodicPer-th workgroup of the row, for that many blocks of 256 outputs
+    if (block % kPeriodicPer == 0)
+      periodic_product_body<T, OP>(f, stride_f, g, stride_g, out, cap, period, F, s_F, n, row, code, block * 256);
     return;
   }
   const int t = block * 256 + threadIdx.x;
@@ -465,7 +537,7 @@ int launch_structured(const T* f, int64_t stride_f, const T* g, int64_t stride_g
   hipLaunchKernelGGL((bracket_fine_kernel<T, OP>), dim3((uint32_t)(batch * ((fine + 3) / 4))), dim3(256), 0, stream,
                      f, stride_f, g, stride_g, sel, jcoarse, coarse, jstar, (int)n, fine);
   hipLaunchKernelGGL((structured_kernel<T, OP>), dim3((uint32_t)(batch * bpr)), dim3(256), 0, stream, f, stride_f, g,
-                     stride_g, out, cap, sel, jstar, period, F, (int)n, (int)bpr);
+                     stride_g, out, cap, sel, jstar, period, F, (int)n, (int)bpr, (int)batch);
   return hip_ok();
 }
 
