@@ -98,7 +98,7 @@ constexpr int kPeriodRun = 128;      // consecutive positions of the first test
 // Periods shorter than this are multiplied up.  The scan walks n / p steps per residue class one
 // after the other (about 0.1 us each, whatever the batch), the window product reduces
 // batch n p candidates at about 12 T/s: the sum is smallest near p = sqrt(1.2e6 / batch).
-__host__ __device__ inline int period_target(int64_t batch) {
+inline int period_target(int64_t batch) {
   int t = 32;
   while (t < 256 && (int64_t)(t + 1) * (t + 1) * batch <= 1200000) ++t;
   return t;
@@ -119,7 +119,7 @@ __global__ __launch_bounds__(kPeriodThreads) void period_kernel(const T* __restr
                                                                 const T* __restrict__ g, int64_t stride_g,
                                                                 int32_t* __restrict__ sel,
                                                                 int32_t* __restrict__ period,
-                                                                int32_t* __restrict__ pack_ok, int n, int op) {
+                                                                int32_t* __restrict__ pack_ok, int n, int op, int target) {
   constexpr int kWaves = kPeriodThreads / 64;
   __shared__ uint32_t s_cand[2][kPeriodMax / 32];
   __shared__ T s_red[4][kWaves];
@@ -139,8 +139,12 @@ __global__ __launch_bounds__(kPeriodThreads) void period_kernel(const T* __restr
   }
   if (threadIdx.x < 2) s_first[threadIdx.x] = 0x7fffffff;
   const int staged = min(run + 2 * pmax, n - 1);      // w[1 .. staged]
-  for (int which = 0; which < nrows; ++which)
-    for (int k = threadIdx.x; k < staged; k += kPeriodThreads) s_w[which][k] = rows[which][1 + k];
+  // (both rows in one unrolled loop: all loads of a thread in flight together)
+#pragma unroll 6
+  for (int k = threadIdx.x; k < nrows * staged; k += kPeriodThreads) {
+    const int which = k >= staged, at = k - which * staged;
+    s_w[which][at] = rows[which][1 + at];
+  }
   __syncthreads();
   // Screening, one thread per (row, period), from the staged head of the row alone: eight
   // consecutive positions and the far ends, inside the staged window, of the residue classes
@@ -223,7 +227,7 @@ __global__ __launch_bounds__(kPeriodThreads) void period_kernel(const T* __restr
   __syncthreads();
   // full test of the survivors in ascending order; the first full pass also takes the extrema of
   // both rows over the indices >= 1
-  const int target = period_target(gridDim.x);                          // periods below it are multiplied up anyway
+  // (target = period_target(batch): periods below it are multiplied up anyway)
   int best_p = 0, best_which = 0;
   bool have_mm = false;
   int mm_which = 0;                                                     // the row that wmn / wmx describe
@@ -512,7 +516,7 @@ void launch_period(const T* f, int64_t stride_f, const T* g, int64_t stride_g, i
                    int32_t* pack_ok, int64_t batch, int64_t n, int op, hipStream_t stream) {
   if (period_limit(n) < 1) return;
   hipLaunchKernelGGL(period_kernel<T>, dim3((uint32_t)batch), dim3(kPeriodThreads), 0, stream, f, stride_f, g, stride_g, sel,
-                     period, pack_ok, (int)n, op);
+                     period, pack_ok, (int)n, op, period_target(batch));
 }
 
 inline size_t bracket_jstar_elems(int64_t batch, int64_t n) {
