@@ -99,6 +99,26 @@ def test_products_broadcast_rows(rtc, dtype):
     assert np.array_equal(host(rtc.rtc_maxplus_deconv(dev(g), dev(f))), oracle.maxplus_deconv(g, f))
 
 
+@pytest.mark.parametrize("dtype", [np.int32, np.int64])
+def test_structured_products_broadcast_rows(rtc, dtype):
+    """One curve against a batch (row stride 0) where the pairs take the structure-exploiting
+    kernels: a periodic, a convex and a concave curve broadcast as g and as f."""
+    n = 4200
+    rng = np.random.default_rng(51)
+    many = np.stack([wl.random_monotone(52, k, 1, n, np.int64)[0] for k in range(60)]
+                    + [wl.rate_latency(n, 3, 40), wl.token_bucket(n, 50, 2, np.int64, at_zero=False),
+                       wl.tdma_lower(n, 4, 19), wl.periodic_jitter_upper(n, 25, 7)]).astype(dtype)
+    for name, one in (("periodic", wl.tdma_lower(n, 9, 33)), ("convex", wl.rate_latency(n, 5, 700)),
+                      ("concave", wl.token_bucket(n, 300, 4, np.int64, at_zero=False))):
+        one = one.astype(dtype)[None, :]
+        say("broadcast", name, "as g", dtype)
+        check_products(rtc, many, one, f"broadcast {name} g")
+        check_duals(rtc, many, one, f"broadcast {name} g")
+        say("broadcast", name, "as f", dtype)
+        check_products(rtc, one, many, f"broadcast {name} f")
+        check_duals(rtc, one, many, f"broadcast {name} f")
+
+
 def _both_paths(rtc, f, g, tag):
     """int32 products with the workspace (packed 16-bit chunks where they qualify) and with a
     token workspace (32-bit kernel only): both must equal the oracle."""
