@@ -583,6 +583,11 @@ def main():
         "launch_ms": round(conv_ms, 4), "call_ms": round(conv_call_ms, 4),
         "pair_ops_per_launch": B * pair_ops_one,
         "gpair_ops_per_s": round(B * pair_ops_one / (conv_ms * 1e-3) / 1e9, 2),
+        # the same launch against the rate at which the SIMDs can issue instructions at all: a
+        # wave64 VALU instruction occupies its SIMD for 4 cycles, 4 SIMDs per CU; the product needs at
+        # least 0.75 such instructions per 64 pair-ops (see note).  This fraction cannot exceed 1.
+        "frac_of_valu_issue_rate": round(0.75 * B * pair_ops_one / 64 / (conv_ms * 1e-3)
+                                         / (info["cu_count"] * 4 * info["clock_khz"] * 1e3 / 4), 4),
         "cu_count": info["cu_count"], "clock_khz": info["clock_khz"], "kernels": kernels,
         "note": "achieved counts 2 lane-ops (add + min) per pair-op by definition, over the kernel's own "
                 "HIP-event duration; peak = CUs x 64 lanes x clock. The kernel issues 0.75 VALU instructions per "
