@@ -125,9 +125,21 @@ def per_config_table(seed, peak_ops, with_cpu):
             # call is timed again with those paths switched off
             if f.dtype != torch.float64 and B * N * N >= 2 ** 30:
                 paths = {}
-                for code in rtc.rtc_product_structure(op_codes[name], f, g).cpu().numpy().tolist():
+                codes, periods = rtc.rtc_product_periods(op_codes[name], f, g)
+                codes, periods = codes.cpu().numpy(), periods.cpu().numpy().astype(np.int64)
+                for code in codes.tolist():
                     paths[path_names[code]] = paths.get(path_names[code], 0) + 1
                 r["rows_by_path"] = paths
+                # candidates the chosen kernels evaluate (upper bounds where the count depends on
+                # the data): general N(N+1)/2; ends 2N; bisection 2 ceil(log2(m+1)) per output;
+                # brackets: every 4096th output in full, then <= 2N for the 64-spaced anchors
+                # and <= 65N for the outputs; periodic N (window + 1) + N for the scan
+                m = np.arange(N, dtype=np.int64)
+                per_code = {1: N * (N + 1) // 2, 2: int(2 * np.ceil(np.log2(m + 1.0)).sum()), 3: 2 * N,
+                            4: int((np.minimum(np.arange(0, N + 4096, 4096), N - 1) + 1).sum()) + 67 * N}
+                per_code[5] = per_code[4]
+                r["executed_candidates_upper_bound"] = int(sum(
+                    per_code[c] if c < 6 else N * (int(pw) + 2) for c, pw in zip(codes.tolist(), periods.tolist())))
                 if set(paths) != {"general"}:
                     rtc.rtc_set_structure_paths(False)
                     try:

@@ -232,6 +232,13 @@ enum {
 int rtc_product_structure(int op, const void* f, const void* g, int32_t* codes, int64_t batch, int64_t n,
                           int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* hip_stream);
 
+/* rtc_product_structure, and in periods[b] (optional; device, [batch] int32) the window length
+ * the periodic path uses for row pair b: a multiple of the period found, 0 for a pair that is
+ * not RTC_STRUCTURE_PERIODIC(_SWAPPED).  Such a pair costs about n (periods[b] + 1) candidates
+ * plus one scan of n steps. */
+int rtc_product_periods(int op, const void* f, const void* g, int32_t* codes, int32_t* periods, int64_t batch,
+                        int64_t n, int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* hip_stream);
+
 /* Planner knob: the packed 16-bit path of the int32 / narrowed-int64 products is used when a
  * workspace is present and batch * n^2 >= this value (default 2^30; smaller problems are
  * launch-bound and take the 32-bit kernel alone).  0 uses it for every size.  Results do not

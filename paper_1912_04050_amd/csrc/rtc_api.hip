@@ -69,14 +69,19 @@ int rtc_maxplus_deconv(const void* f, const void* g, void* out, int64_t batch, i
 
 int rtc_product_structure(int op, const void* f, const void* g, int32_t* codes, int64_t batch, int64_t n,
                           int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* hip_stream) {
+  return rtc_product_periods(op, f, g, codes, nullptr, batch, n, stride_f, stride_g, dt, hip_stream);
+}
+
+int rtc_product_periods(int op, const void* f, const void* g, int32_t* codes, int32_t* periods, int64_t batch,
+                        int64_t n, int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* hip_stream) {
   if (f == nullptr || g == nullptr || codes == nullptr) return RTC_ERR_NULL;
   const size_t es = elem_size(dt);
   if (es == 0) return RTC_ERR_DTYPE;
   if (op != RTC_OP_CONV && op != RTC_OP_DECONV && op != RTC_OP_MAXCONV && op != RTC_OP_MINDECONV) return RTC_ERR_MODE;
   if (int rc = check_shape(batch, n)) return rc;
   if ((stride_f != 0 && stride_f < n) || (stride_g != 0 && stride_g < n)) return RTC_ERR_STRIDE;
-  if (!aligned(f, es) || !aligned(g, es) || !aligned(codes, 4)) return RTC_ERR_ALIGN;
-  return launch_structure_probe(op, f, g, codes, batch, n, stride_f, stride_g, dt,
+  if (!aligned(f, es) || !aligned(g, es) || !aligned(codes, 4) || !aligned(periods, 4)) return RTC_ERR_ALIGN;
+  return launch_structure_probe(op, f, g, codes, periods, batch, n, stride_f, stride_g, dt,
                                 static_cast<hipStream_t>(hip_stream));
 }
 

@@ -22,8 +22,8 @@ int launch_tropical(int op, const void* f, const void* g, void* out, int64_t bat
                     size_t ws_bytes, int32_t* dev_flags, hipStream_t stream);
 size_t tropical_workspace_bytes(int64_t batch, int64_t n, int dt);
 // Per-row selector codes of the products' convexity test (RTC_STRUCTURE_*), see rtc_product_structure.
-int launch_structure_probe(int op, const void* f, const void* g, int32_t* codes, int64_t batch, int64_t n,
-                           int64_t stride_f, int64_t stride_g, int dt, hipStream_t stream);
+int launch_structure_probe(int op, const void* f, const void* g, int32_t* codes, int32_t* periods, int64_t batch,
+                           int64_t n, int64_t stride_f, int64_t stride_g, int dt, hipStream_t stream);
 int launch_selftest_half_minmax(uint32_t* mismatches, hipStream_t stream);
 extern double g_packed_min_work;  // planner knob, see rtc_set_packed_min_work
 extern int64_t g_packed_small_n;  // planner knob, see rtc_set_packed_small_n

@@ -442,25 +442,29 @@ int launch_selftest_half_minmax(uint32_t* mismatches, hipStream_t stream) {
   return hip_ok();
 }
 
-int launch_structure_probe(int op, const void* f, const void* g, int32_t* codes, int64_t batch, int64_t n,
-                           int64_t stride_f, int64_t stride_g, int dt, hipStream_t stream) {
+int launch_structure_probe(int op, const void* f, const void* g, int32_t* codes, int32_t* periods, int64_t batch,
+                           int64_t n, int64_t stride_f, int64_t stride_g, int dt, hipStream_t stream) {
   static_assert(kSelSearch == RTC_STRUCTURE_BISECT && kSelEnds == RTC_STRUCTURE_ENDS &&
                     kSelBracket == RTC_STRUCTURE_BRACKET && kSelBracketSwapped == RTC_STRUCTURE_BRACKET_SWAPPED &&
                     kSelPeriodic == RTC_STRUCTURE_PERIODIC && kSelPeriodicSwapped == RTC_STRUCTURE_PERIODIC_SWAPPED,
                 "selector codes are public");
   const int code_op = op == RTC_OP_CONV ? 0 : op == RTC_OP_DECONV ? 1 : op == RTC_OP_MAXCONV ? 2 : 3;
+  if (periods != nullptr) {       // period_kernel writes the rows it accepts only
+    const int blocks = (int)((batch + 255) / 256 < 65535 ? (batch + 255) / 256 : 65535);
+    hipLaunchKernelGGL(fill_kernel<int32_t>, dim3(blocks), dim3(256), 0, stream, periods, batch, (int32_t)0);
+  }
   if (dt == RTC_I32) {
     hipLaunchKernelGGL(probe_kernel<int32_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,
                        static_cast<const int32_t*>(f), stride_f, static_cast<const int32_t*>(g), stride_g, (int)n,
                        code_op, (int32_t*)nullptr, (int32_t*)nullptr, codes, (int32_t*)nullptr);
     launch_period<int32_t>(static_cast<const int32_t*>(f), stride_f, static_cast<const int32_t*>(g), stride_g, codes,
-                           nullptr, nullptr, batch, n, code_op, stream);
+                           periods, nullptr, batch, n, code_op, stream);
   } else if (dt == RTC_I64) {
     hipLaunchKernelGGL(probe_kernel<int64_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,
                        static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g, (int)n,
                        code_op, (int32_t*)nullptr, (int32_t*)nullptr, codes, (int32_t*)nullptr);
     launch_period<int64_t>(static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g, codes,
-                           nullptr, nullptr, batch, n, code_op, stream);
+                           periods, nullptr, batch, n, code_op, stream);
   } else {
     const int blocks = (int)((batch + 255) / 256 < 65535 ? (batch + 255) / 256 : 65535);
     hipLaunchKernelGGL(fill_kernel<int32_t>, dim3(blocks), dim3(256), 0, stream, codes, batch,

@@ -152,9 +152,25 @@ def rtc_selftest_half_minmax() -> int:
 
 _lib.rtc_product_structure.argtypes = [_int, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _int, _vp]
 _lib.rtc_product_structure.restype = _int
+_lib.rtc_product_periods.argtypes = [_int, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _int, _vp]
+_lib.rtc_product_periods.restype = _int
 RTC_STRUCTURE_GENERAL, RTC_STRUCTURE_BISECT, RTC_STRUCTURE_ENDS = 1, 2, 3
 RTC_STRUCTURE_BRACKET, RTC_STRUCTURE_BRACKET_SWAPPED = 4, 5
 RTC_STRUCTURE_PERIODIC, RTC_STRUCTURE_PERIODIC_SWAPPED = 6, 7
+
+
+def rtc_product_periods(op: int, f, g):
+    """(codes, periods) per row pair: rtc_product_structure plus the periodic path's window length."""
+    f, bf, n, _ = _rows(f)
+    g, bg, ng, _ = _rows(g)
+    if ng != n or f.dtype != g.dtype or (bf != bg and 1 not in (bf, bg)):
+        raise ValueError("operands must have the same length and dtype, batch equal or 1")
+    batch = max(bf, bg)
+    codes = torch.empty(batch, dtype=torch.int32, device=f.device)
+    periods = torch.empty(batch, dtype=torch.int32, device=f.device)
+    _check(_lib.rtc_product_periods(op, _ptr(f), _ptr(g), _ptr(codes), _ptr(periods), batch, n,
+                                    _row_stride(f, bf, batch, n), _row_stride(g, bg, batch, n), _DT[f.dtype], _stream()))
+    return codes, periods
 
 
 def rtc_product_structure(op: int, f, g, out=None):

@@ -532,6 +532,13 @@ def _periodic_row(rng, n, p, first=None, spoil=None):
     return w
 
 
+def _period_target(batch):
+    target = 32
+    while target < 256 and (target + 1) ** 2 * batch <= 1200000:
+        target += 1
+    return target
+
+
 def _period_by_definition(w, n):
     """Smallest p <= min(1024, n // 16) with w[i+p] - w[i] constant over 1 <= i <= n-1-p, else 0."""
     w = np.asarray(w).astype(object) if np.abs(np.asarray(w, dtype=np.float64)).max() > 2.0 ** 61 else np.asarray(w, dtype=np.int64)
@@ -566,9 +573,19 @@ def test_periodic_operands(rtc, dtype):
         f, g = np.stack(fs).astype(dtype), np.stack(gs).astype(dtype)
         for name, op in ops:
             got = host(rtc.rtc_product_structure(op, dev(f), dev(g)))
+            codes, periods = rtc.rtc_product_periods(op, dev(f), dev(g))
+            codes, periods = host(codes), host(periods)
+            assert np.array_equal(codes, got)
+            target, pmax = _period_target(len(fs)), min(1024, n // 16)
             for b in range(len(fs)):
                 want = _structure_by_definition(f[b], g[b], name, batch=len(fs))
                 assert got[b] == want, (name, n, b, got[b], want)
+                if want in (6, 7):     # the window length: the period found, multiplied up to the target if shorter
+                    p = _period_by_definition(g[b] if want == 6 else f[b], n)
+                    use = p if p >= target else p * -(-target // p) if p * -(-target // p) <= pmax else p * (pmax // p)
+                    assert periods[b] == use, (name, n, b, periods[b], p, use)
+                else:
+                    assert periods[b] == 0
         check_products(rtc, f, g, f"periodic n={n}")
         check_duals(rtc, f, g, f"periodic duals n={n}")
         if dtype == np.int64:
@@ -607,9 +624,7 @@ def _structure_by_definition(f, g, op, exact_differences=True, batch=1):
     if code != 1 or n // 16 < 1:
         return code
     pg = _period_by_definition(g, n)
-    target = 32                               # shorter periods are multiplied up to it: f is not looked at then
-    while target < 256 and (target + 1) ** 2 * batch <= 1200000:
-        target += 1
+    target = _period_target(batch)            # shorter periods are multiplied up to it: f is not looked at then
     pf = _period_by_definition(f, n) if op in ("conv", "maxconv") and not (0 < pg <= target) else 0
     return 6 if pg and (not pf or pg <= pf) else 7 if pf else 1
 
