@@ -589,3 +589,58 @@ def test_chain_of_rate_latency_curves(dtype):
     alpha = wl.token_bucket(n, 12, 2, dtype)
     total = sum(int(oracle.max_hdev(alpha, c[0])[0][0]) for c in curves)
     assert int(oracle.max_hdev(alpha, got[0])[0][0]) <= total
+
+
+# ---------------------------------------------------------------- structure of the products
+def _periodic(rng, n, p):
+    """w[0] = 0, w[1] arbitrary, increments from index 1 on repeat with period p."""
+    pat = rng.integers(0, 9, p)
+    w = np.zeros(n, np.int64)
+    w[1] = rng.integers(0, 50)
+    w[2:] = w[1] + np.cumsum(np.tile(pat, n // p + 2)[:n - 2])
+    return w
+
+
+@pytest.mark.parametrize("p", [1, 2, 5, 17, 64])
+def test_products_with_a_periodic_operand_decompose_by_residue_class(p):
+    """With w[i+p] = w[i] + c for i >= 1, grouping the candidates by j = 1 + r + q p gives
+      (f (x) w)[t] = min(f[t] + w[0], min_{r < p, r <= t-1} F[t-1-r] + w[1+r]),  F[u] = min(f[u], F[u-p] + c)
+      (f (/) w)[t] = max(f[t] - w[0], max_{r < p, t+1+r <= n-1} G[t+1+r] - w[1+r]),  G[u] = max(f[u], G[u+p] - c)
+    and the same with max / min exchanged for the dual products: a second way to the four products
+    that shares nothing with the oracle's double loop."""
+    rng = np.random.default_rng(600 + p)
+    n = 300
+    f = np.cumsum(rng.integers(-3, 12, n))
+    w = _periodic(rng, n, p)
+    c = w[1 + p] - w[1]
+    for red, acc, conv_ref, deconv_ref in ((min, np.minimum, oracle.minplus_conv, oracle.minplus_deconv),
+                                            (max, np.maximum, oracle.maxplus_conv, oracle.maxplus_deconv)):
+        F = f.copy()
+        for u in range(p, n):
+            F[u] = red(f[u], F[u - p] + c)
+        conv = [red([f[t] + w[0]] + [F[t - 1 - r] + w[1 + r] for r in range(min(p, t))]) for t in range(n)]
+        assert np.array_equal(conv_ref(f[None], w[None])[0], conv)
+        assert np.array_equal(conv_ref(w[None], f[None])[0], conv)          # commutes
+        G = f.copy()
+        for u in range(n - 1 - p, -1, -1):
+            G[u] = red(f[u], G[u + p] - c)
+        deconv = [red([f[t] - w[0]] + [G[t + 1 + r] - w[1 + r] for r in range(min(p, n - 1 - t))]) for t in range(n)]
+        assert np.array_equal(deconv_ref(f[None], w[None])[0], deconv)
+
+
+def test_one_convex_operand_makes_the_optimal_split_monotone():
+    """f arbitrary, g convex: the leftmost s that attains (f (x) g)[t] never moves left as t grows
+    (the candidates form a Monge array), and for f (/) g with f concave the leftmost optimal u never
+    moves right.  The oracle's values must be attained at such monotone positions."""
+    rng = np.random.default_rng(77)
+    n = 200
+    for _ in range(6):
+        f = np.cumsum(rng.integers(-5, 30, n))
+        g = np.cumsum(np.sort(rng.integers(0, 40, n)))                 # convex
+        conv = oracle.minplus_conv(f[None], g[None])[0]
+        arg = [min(s for s in range(t + 1) if f[s] + g[t - s] == conv[t]) for t in range(n)]
+        assert all(a <= b for a, b in zip(arg, arg[1:]))
+        h = np.cumsum(np.sort(rng.integers(0, 40, n))[::-1])           # concave
+        dec = oracle.maxplus_deconv(h[None], f[None])[0]
+        argd = [min(u for u in range(n - t) if h[t + u] - f[u] == dec[t]) for t in range(n)]
+        assert all(a >= b for a, b in zip(argd, argd[1:]))
