@@ -251,6 +251,13 @@ int rtc_set_packed_min_work(double batch_times_n_squared);
  * depend on it.  Process-wide, not thread-safe.  RTC_ERR_SHAPE for a negative value. */
 int rtc_set_packed_small_n(int64_t n);
 
+/* Planner knob: a product that the general kernel would cut into fewer work items than this
+ * (default 256, the number of CUs: e.g. one pair of 4096 samples gives 10) runs with tiles of 256
+ * outputs and chunks of 256 steps instead of 1024 x 1024, which costs more instructions per
+ * candidate and finishes sooner because more CUs take part.  0 never does.  Results do not depend
+ * on it.  Process-wide, not thread-safe.  RTC_ERR_SHAPE for a negative value. */
+int rtc_set_small_problem_items(int64_t items);
+
 /* Planner knob: 0 sends every row pair of the integer products through the general kernels,
  * whatever its convexity or periodicity (rtc_product_structure still reports what it finds);
  * non-zero (default) lets the structure-exploiting paths take the rows they recognise.  Results

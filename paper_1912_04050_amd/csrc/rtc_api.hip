@@ -308,6 +308,12 @@ int rtc_set_packed_small_n(int64_t n) {
   return RTC_OK;
 }
 
+int rtc_set_small_problem_items(int64_t items) {
+  if (items < 0) return RTC_ERR_SHAPE;
+  rtc::g_small_items = items;
+  return RTC_OK;
+}
+
 int rtc_set_structure_paths(int enabled) {
   rtc::g_structure_paths = enabled != 0;
   return RTC_OK;

@@ -54,6 +54,7 @@ namespace rtc {
 
 int64_t g_packed_small_n = 4096;   // rows up to this length use the narrower packed tiles
 bool g_structure_paths = true;     // rows of exploitable convexity / periodicity take their own kernels
+int64_t g_small_items = 256;       // problems with fewer work items than this get the small tiles, see kSmallR
 
 namespace {
 
@@ -132,10 +133,16 @@ Plan make_plan(int64_t batch, int64_t n, int width, int chunk) {
   return pl;
 }
 
-template <typename T> Plan make_plan(int64_t batch, int64_t n) {
-  using TL = Tile<T, RFor<T>::value>;
+template <typename T, int R> Plan make_plan(int64_t batch, int64_t n) {
+  using TL = Tile<T, R>;
   return make_plan(batch, n, TL::kW, TL::kChunk);
 }
+
+// Accumulators per lane of the generic kernel: 16, or 4 for problems so small that 16 would give
+// fewer work items than the chip has CUs (a single pair of 4096 samples: 10 items of 1024 x 1024
+// candidates, 67 us; with tiles of 256 outputs and chunks of 256 steps 136 items that finish in a
+// sixth of that, although each candidate costs more instructions).
+constexpr int kSmallR = 4;
 
 template <typename OutT, int OP>
 void launch_fill(OutT* out, int64_t count, hipStream_t stream) {
@@ -147,12 +154,11 @@ void launch_fill(OutT* out, int64_t count, hipStream_t stream) {
 
 // One launch of the generic kernel.  `force_atomic` is set when several kernels contribute to
 // one output (the output is then already filled with the identity).
-template <typename T, typename OutT, int OP>
-int run_product(const T* a, int64_t stride_a, const T* b, int64_t stride_b, OutT* out, const OutT* cap,
-                const int32_t* sel, int sel_want, int64_t batch, int64_t n, hipStream_t stream,
-                bool prefilled, bool force_atomic, const int64_t* out_base) {
-  constexpr int R = RFor<T>::value;
-  const Plan pl = make_plan<T>(batch, n);
+template <typename T, typename OutT, int OP, int R>
+int run_product_r(const T* a, int64_t stride_a, const T* b, int64_t stride_b, OutT* out, const OutT* cap,
+                  const int32_t* sel, int sel_want, int64_t batch, int64_t n, hipStream_t stream,
+                  bool prefilled, bool force_atomic, const int64_t* out_base) {
+  const Plan pl = make_plan<T, R>(batch, n);
   if (pl.items > 0x7fffffffLL) return RTC_ERR_SHAPE;
   TropicalArgs args = {};
   args.a = a; args.b = b; args.out = out; args.cap = cap; args.sel = sel;
@@ -182,6 +188,17 @@ int run_product(const T* a, int64_t stride_a, const T* b, int64_t stride_b, OutT
   }
   prof_end(stream);
   return hip_ok();
+}
+
+template <typename T, typename OutT, int OP>
+int run_product(const T* a, int64_t stride_a, const T* b, int64_t stride_b, OutT* out, const OutT* cap,
+                const int32_t* sel, int sel_want, int64_t batch, int64_t n, hipStream_t stream,
+                bool prefilled, bool force_atomic, const int64_t* out_base) {
+  if (make_plan<T, RFor<T>::value>(batch, n).items < g_small_items && n > Tile<T, kSmallR>::kW)
+    return run_product_r<T, OutT, OP, kSmallR>(a, stride_a, b, stride_b, out, cap, sel, sel_want, batch, n, stream,
+                                               prefilled, force_atomic, out_base);
+  return run_product_r<T, OutT, OP, RFor<T>::value>(a, stride_a, b, stride_b, out, cap, sel, sel_want, batch, n,
+                                                    stream, prefilled, force_atomic, out_base);
 }
 
 // Layout of the packed path's arrays inside the workspace.
@@ -253,7 +270,7 @@ int run_packed(const int32_t* f32, int64_t stride_f, const int32_t* g32, int64_t
   // short rows: tiles of 1024 outputs halve the candidates wasted on the diagonal
   const bool small_tiles = n <= g_packed_small_n;
   const Plan pk = make_plan(batch, n, small_tiles ? kPkW / 2 : kPkW, kPkChunk);
-  const Plan pg = make_plan<int32_t>(batch, n);
+  const Plan pg = make_plan<int32_t, kPkR>(batch, n);
   if (pk.items + pg.items > 0x7fffffffLL) return RTC_ERR_SHAPE;
   TropicalArgs ak = {};
   ak.out = out; ak.cap = cap; ak.sel = sel; ak.sel_want = 1; ak.out_base = out_base;

@@ -195,6 +195,14 @@ def rtc_set_packed_small_n(n: int):
     _check(_lib.rtc_set_packed_small_n(int(n)))
 
 
+_lib.rtc_set_small_problem_items.argtypes = [_i64]
+_lib.rtc_set_small_problem_items.restype = _int
+
+
+def rtc_set_small_problem_items(items: int):
+    _check(_lib.rtc_set_small_problem_items(int(items)))
+
+
 _lib.rtc_set_structure_paths.argtypes = [_int]
 _lib.rtc_set_structure_paths.restype = _int
 

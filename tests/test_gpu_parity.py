@@ -22,17 +22,20 @@ DTYPES = [np.int32, np.int64, np.float64]
 
 @pytest.fixture(scope="module", params=["default-planner", "packed-wide-tiles", "packed-small-tiles"])
 def rtc(request):
-    """Every test runs three times: with the default planner (small problems take the 32-bit
-    kernel alone), and with the packed 16-bit path forced on for every size that brings a
-    workspace, once with its tiles of 2048 outputs and once with those of 1024."""
+    """Every test runs three times: with the default planner (small problems take the generic
+    kernel alone, with its small tiles), and with the packed 16-bit path forced on for every size
+    that brings a workspace, once with its tiles of 2048 outputs and once with those of 1024
+    (both with the generic kernel's large tiles for every size)."""
     from paper_1912_04050_amd import rtc as mod
     default_small_n = 4096
     if request.param != "default-planner":
         mod.rtc_set_packed_min_work(0.0)
         mod.rtc_set_packed_small_n(0 if request.param == "packed-wide-tiles" else 1 << 24)
+        mod.rtc_set_small_problem_items(0)      # the generic kernel keeps its large tiles whatever the size
     yield mod
     mod.rtc_set_packed_min_work(2.0 ** 30)
     mod.rtc_set_packed_small_n(default_small_n)
+    mod.rtc_set_small_problem_items(256)
 
 
 def say(*a):

@@ -18,8 +18,10 @@ def rtc(request):
     from paper_1912_04050_amd import rtc as mod
     if request.param == "packed-forced":
         mod.rtc_set_packed_min_work(0.0)
+        mod.rtc_set_small_problem_items(0)      # and the generic kernel's large tiles for every size
     yield mod
     mod.rtc_set_packed_min_work(2.0 ** 30)
+    mod.rtc_set_small_problem_items(256)
 
 
 def dev(a):
