@@ -150,7 +150,7 @@ def per_config_table(seed, peak_ops, with_cpu):
                     r["equivalent_gpair_ops_per_s"] = r.pop("gpair_ops_per_s")
                     r["general_kernels_gpu_ms"] = round(med_g, 4)
                     r["general_kernels_gpair_ops_per_s"] = round(po / med_g / 1e6, 1)
-            if with_cpu:
+            if with_cpu and cpu_rows > 0:
                 sub = slice(0, cpu_rows)
                 sec = cpu_s(lambda: getattr(oracle, ofn)(f_h[sub], g_h[sub]))
                 r.update({"oracle_s": sec, "oracle_rows": min(cpu_rows, B), "oracle_threads": threads,
@@ -218,7 +218,15 @@ def per_config_table(seed, peak_ops, with_cpu):
     product_rows(3, c["f"], c["g"], 8, "int64 storage, int32 arithmetic")
     product_rows(3, c["f"].astype(np.int32), c["g"].astype(np.int32), 8, "int32", duals=True)
     product_rows(3, c["f"][:16] + (1 << 40), c["g"][:16] - (1 << 45), 4, "int64 storage with large offsets (re-based, int32 arithmetic)")
-    product_rows(3, c["f"][:16] * 4096, c["g"][:16] * 4096, 4, "int64 arithmetic (value range beyond 2^30)")
+    # values spanning 2^40: beyond the row-level narrowing, but slowly varying, so the chunks are
+    # re-based and reduced in 32-bit arithmetic; then the same rows with that path off (64-bit kernel)
+    product_rows(3, c["f"][:16] * 4096, c["g"][:16] * 4096, 4,
+                 "int64 storage, value range beyond 2^30 (32-bit arithmetic re-based per chunk)")
+    rtc.rtc_set_rebase_wide(False)
+    try:
+        product_rows(3, c["f"][:16] * 4096, c["g"][:16] * 4096, 0, "int64 arithmetic (the same rows, 64-bit kernel)")
+    finally:
+        rtc.rtc_set_rebase_wide(True)
     # rows of exploitable convexity at the headline shape: token buckets (concave) and rate-latency
     # curves (convex); the library detects them on the device and evaluates 2 or 2*log2(n) candidates
     # per output instead of all of them, so the rate below is an equivalent, not executed work

@@ -258,6 +258,13 @@ int rtc_set_packed_small_n(int64_t n);
  * on it.  Process-wide, not thread-safe.  RTC_ERR_SHAPE for a negative value. */
 int rtc_set_small_problem_items(int64_t items);
 
+/* Planner knob for int64 rows whose values span more than 2^30 (which the 64-bit kernel takes):
+ * non-zero (default) lets row pairs that vary slowly -- for every chunk of 1024 steps and window
+ * of 2048 samples, range(chunk of one row) + range(window of the other) <= 2^31 - 2 -- run in
+ * 32-bit arithmetic on values re-based per chunk, about three times as fast; 0 keeps them with
+ * the 64-bit kernel.  Results do not depend on it.  Process-wide, not thread-safe. */
+int rtc_set_rebase_wide(int enabled);
+
 /* Planner knob: 0 sends every row pair of the integer products through the general kernels,
  * whatever its convexity or periodicity (rtc_product_structure still reports what it finds);
  * non-zero (default) lets the structure-exploiting paths take the rows they recognise.  Results

@@ -314,6 +314,11 @@ int rtc_set_small_problem_items(int64_t items) {
   return RTC_OK;
 }
 
+int rtc_set_rebase_wide(int enabled) {
+  rtc::g_rebase_wide = enabled != 0;
+  return RTC_OK;
+}
+
 int rtc_set_structure_paths(int enabled) {
   rtc::g_structure_paths = enabled != 0;
   return RTC_OK;

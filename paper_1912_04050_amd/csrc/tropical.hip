@@ -49,12 +49,14 @@
 #include "tropical_packed.h"
 #include "tropical_prepare.h"
 #include "tropical_structured.h"
+#include "tropical_rebased.h"
 
 namespace rtc {
 
 int64_t g_packed_small_n = 4096;   // rows up to this length use the narrower packed tiles
 bool g_structure_paths = true;     // rows of exploitable convexity / periodicity take their own kernels
 int64_t g_small_items = 256;       // problems with fewer work items than this get the small tiles, see kSmallR
+bool g_rebase_wide = true;         // slowly varying int64 rows beyond 32 bits: 32-bit arithmetic re-based per chunk
 
 namespace {
 
@@ -359,14 +361,18 @@ constexpr int kProbeMaxSegs = 16;   // segments per row of the two-pass range pr
 size_t narrow_partial_offset(int64_t batch, int64_t n) {
   return narrow_base_offset(batch, n) + ((size_t)batch * sizeof(int64_t) + 255) / 256 * 256;
 }
-size_t narrow_bytes(int64_t batch, int64_t n) {
+size_t narrow_tables_offset(int64_t batch, int64_t n) {
   return narrow_partial_offset(batch, n) + ((size_t)batch * kProbeMaxSegs * 5 * sizeof(int64_t) + 255) / 256 * 256;
+}
+size_t narrow_bytes(int64_t batch, int64_t n) {
+  return narrow_tables_offset(batch, n) + (wide_table_elems(batch, n) * sizeof(int64_t) + 255) / 256 * 256;
 }
 
 template <int OP>
 int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, int64_t stride_f,
             int64_t stride_g, const void* cap, void* ws, int32_t* dev_flags, hipStream_t stream) {
-  // workspace: [f32: batch*n][g32: batch*n][narrow_ok: batch][out_base: batch int64][packed-path arrays]
+  // workspace: [f32: batch*n][g32: batch*n][narrow_ok: batch][out_base: batch int64][probe partials]
+  // [block tables of the re-based path][packed-path arrays]
   int32_t* f32 = static_cast<int32_t*>(ws);
   int32_t* g32 = f32 + batch * n;
   int32_t* ok = g32 + batch * n;
@@ -392,6 +398,17 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
     launch_period<int64_t>(static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g, ok,
                            reinterpret_cast<int32_t*>(wsp + L.off_period),
                              reinterpret_cast<int32_t*>(wsp + L.off_ok), batch, n, OP, stream);
+  // rows still with the 64-bit kernel (selector 0): those whose values vary slowly enough go to the
+  // re-based 32-bit items instead
+  int64_t* tab = reinterpret_cast<int64_t*>(static_cast<char*>(ws) + narrow_tables_offset(batch, n));
+  const int nb = wide_blocks(n);
+  const Plan pw = make_plan<int32_t, kWideR>(batch, n);
+  const bool rebase = g_rebase_wide && n > kWideBlock && pw.items <= 0x7fffffffLL;
+  if (rebase) {
+    hipLaunchKernelGGL(wide_tables_kernel<OP>, dim3((uint32_t)batch), dim3(kWideThreads), 0, stream,
+                       static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g, ok, tab,
+                       (int)n, nb);
+  }
   // Several kernels see every row; the selector makes each row run in exactly one family.
   // The output is filled once with the identity, before all of them.
   launch_fill<int64_t, OP>(static_cast<int64_t*>(out), batch * n, stream);
@@ -411,7 +428,24 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
                                          op_sub(OP) ? stride_f : stride_g, static_cast<int64_t*>(out),
                                          static_cast<const int64_t*>(cap), ok, 0, batch, n, stream, true, true,
                                          nullptr);
-  if (rc != RTC_OK || !structure) return rc;
+  if (rc != RTC_OK) return rc;
+  if (rebase) {
+    TropicalArgs args = {};
+    args.a = a; args.b = b; args.out = out; args.cap = cap; args.sel = ok; args.sel_want = kSelRebased;
+    args.stride_a = op_sub(OP) ? stride_g : stride_f; args.stride_b = op_sub(OP) ? stride_f : stride_g;
+    args.n = (int32_t)n; args.batch = (int32_t)batch;
+    args.n_tiles = pw.n_tiles; args.fold_width = pw.fold_width; args.seg = pw.seg;
+    const uint32_t items_per_row = (uint32_t)(pw.items / batch);
+    uint32_t parts = (uint32_t)(16384 / batch);
+    if (parts < 1) parts = 1;
+    if (parts > items_per_row) parts = items_per_row;
+    prof_begin(RTC_PROFILE_KIND(RTC_I64, 0, OP), stream);
+    hipLaunchKernelGGL(rebased_rows_kernel<OP>, dim3((uint32_t)batch * parts), dim3(64), 0, stream, args, tab, nb,
+                       items_per_row, parts);
+    prof_end(stream);
+    if (int hrc = hip_ok()) return hrc;
+  }
+  if (!structure) return RTC_OK;
   // rows of exploitable convexity (selector 2 / 3), on the caller's own 64-bit rows
   return launch_structured<int64_t, OP>(static_cast<const int64_t*>(f), stride_f,
                                         static_cast<const int64_t*>(g), stride_g, static_cast<int64_t*>(out),

@@ -203,6 +203,14 @@ def rtc_set_small_problem_items(items: int):
     _check(_lib.rtc_set_small_problem_items(int(items)))
 
 
+_lib.rtc_set_rebase_wide.argtypes = [_int]
+_lib.rtc_set_rebase_wide.restype = _int
+
+
+def rtc_set_rebase_wide(enabled: bool):
+    _check(_lib.rtc_set_rebase_wide(1 if enabled else 0))
+
+
 _lib.rtc_set_structure_paths.argtypes = [_int]
 _lib.rtc_set_structure_paths.restype = _int
 

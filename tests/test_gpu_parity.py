@@ -596,6 +596,34 @@ def test_periodic_operands(rtc, dtype):
             check_duals(rtc, f * (1 << 35), g * (1 << 33), f"periodic wide duals n={n}")
 
 
+def test_wide_int64_rows_rebased_per_chunk(rtc):
+    """int64 rows that span far more than 32 bits but vary slowly take 32-bit arithmetic re-based
+    per chunk; rows with a jump beyond the budget, or steep ones, stay with the 64-bit kernel.  Both
+    next to each other in one batch, all four products, with the path on and off."""
+    rng = np.random.default_rng(53)
+    for n in (1025, 5000, 20011):
+        def slow(offset):               # monotone, increments up to 4e5: about 1.2e9 over a chunk plus a window
+            return offset + np.cumsum(rng.integers(0, 400000, n))
+        def walk(offset):               # not monotone
+            return offset + np.cumsum(rng.integers(-300000, 300000, n))
+        jump = slow(0)
+        jump[n // 2:] += 1 << 40        # one step beyond any 32-bit budget: this pair is not re-based
+        steep = np.cumsum(rng.integers(0, 1 << 24, n))
+        edge = np.zeros(n, np.int64)    # ranges that just fit, and (next row) just do not
+        edge[512:] = (1 << 30) - 1
+        over = edge.copy()
+        over[512:] += 2
+        f = np.stack([slow(1 << 45), walk(-(1 << 50)), jump, slow(0), steep, edge, over, slow(7)]).astype(np.int64)
+        g = np.stack([slow(-(1 << 44)), slow(1 << 33), slow(5), walk(1 << 41), slow(0), edge, over, walk(0)]).astype(np.int64)
+        for on in (True, False):
+            rtc.rtc_set_rebase_wide(on)
+            try:
+                check_products(rtc, f, g, f"wide rows n={n} rebased={on}")
+                check_duals(rtc, f, g, f"wide rows duals n={n} rebased={on}")
+            finally:
+                rtc.rtc_set_rebase_wide(True)
+
+
 def test_structure_paths_knob(rtc):
     """The same rows through the structure-exploiting kernels and, with the knob off, through the
     general ones: the classification does not change, and both results equal the oracle."""
