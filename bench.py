@@ -218,15 +218,23 @@ def per_config_table(seed, peak_ops, with_cpu):
     product_rows(3, c["f"], c["g"], 8, "int64 storage, int32 arithmetic")
     product_rows(3, c["f"].astype(np.int32), c["g"].astype(np.int32), 8, "int32", duals=True)
     product_rows(3, c["f"][:16] + (1 << 40), c["g"][:16] - (1 << 45), 4, "int64 storage with large offsets (re-based, int32 arithmetic)")
+    # cumulative curves on a fine time base: the same increments on top of a slope of 10^6 per step
+    # (values up to 6.5e10).  Too wide for narrowing by the row minima; with the pair's common slope
+    # removed they are configuration 3's own rows again and take the packed kernels
+    ramp = np.arange(65536, dtype=np.int64)
+    product_rows(3, c["f"][:16] + 1000003 * ramp, c["g"][:16] + 999983 * ramp, 4,
+                 "int64 storage, slope 10^6 per step (common slope removed, int32 / packed arithmetic)")
     # values spanning 2^40: beyond the row-level narrowing, but slowly varying, so the chunks are
     # re-based and reduced in 32-bit arithmetic; then the same rows with that path off (64-bit kernel)
     product_rows(3, c["f"][:16] * 4096, c["g"][:16] * 4096, 4,
-                 "int64 storage, value range beyond 2^30 (32-bit arithmetic re-based per chunk)")
-    rtc.rtc_set_rebase_wide(False)
-    try:
-        product_rows(3, c["f"][:16] * 4096, c["g"][:16] * 4096, 0, "int64 arithmetic (the same rows, 64-bit kernel)")
-    finally:
-        rtc.rtc_set_rebase_wide(True)
+                 "int64 storage, value range beyond 2^30 (common slope removed, int32 arithmetic)")
+    for mode, label in ((1, "int64 storage (the same rows, 32-bit arithmetic re-based per chunk)"),
+                        (0, "int64 arithmetic (the same rows, 64-bit kernel)")):
+        rtc.rtc_set_rebase_wide(mode)
+        try:
+            product_rows(3, c["f"][:16] * 4096, c["g"][:16] * 4096, 0, label)
+        finally:
+            rtc.rtc_set_rebase_wide(2)
     # rows of exploitable convexity at the headline shape: token buckets (concave) and rate-latency
     # curves (convex); the library detects them on the device and evaluates 2 or 2*log2(n) candidates
     # per output instead of all of them, so the rate below is an equivalent, not executed work

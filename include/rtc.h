@@ -258,12 +258,17 @@ int rtc_set_packed_small_n(int64_t n);
  * on it.  Process-wide, not thread-safe.  RTC_ERR_SHAPE for a negative value. */
 int rtc_set_small_problem_items(int64_t items);
 
-/* Planner knob for int64 rows whose values span more than 2^30 (which the 64-bit kernel takes):
- * non-zero (default) lets row pairs that vary slowly -- for every chunk of 1024 steps and window
- * of 2048 samples, range(chunk of one row) + range(window of the other) <= 2^31 - 2 -- run in
- * 32-bit arithmetic on values re-based per chunk, about three times as fast; 0 keeps them with
- * the 64-bit kernel.  Results do not depend on it.  Process-wide, not thread-safe. */
-int rtc_set_rebase_wide(int enabled);
+/* Planner knob for int64 row pairs whose values span 2^30 or more (too wide to be narrowed to
+ * 32 bits by subtracting the row minima).  mode 2 (default): a pair that stays within 2^30 of a
+ * line -- both rows minus i times the pair's common slope, half the sum of their mean slopes --
+ * is narrowed with the slope removed and takes the 32-bit and packed kernels at their full rate
+ * (cumulative curves in nanoseconds or cycles are of this kind); otherwise a pair that varies
+ * slowly -- for every chunk of 1024 steps and window of 2048 samples, range(chunk of one row) +
+ * range(window of the other) <= 2^31 - 2 -- runs in 32-bit arithmetic on values re-based per
+ * chunk, about 2.5 times as fast as the 64-bit kernel, which takes the rest.  mode 1: without the
+ * first of the two; mode 0: without both.  Results do not depend on it.  Process-wide, not
+ * thread-safe.  RTC_ERR_MODE for other values. */
+int rtc_set_rebase_wide(int mode);
 
 /* Planner knob: 0 sends every row pair of the integer products through the general kernels,
  * whatever its convexity or periodicity (rtc_product_structure still reports what it finds);

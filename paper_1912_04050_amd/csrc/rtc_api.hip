@@ -314,8 +314,9 @@ int rtc_set_small_problem_items(int64_t items) {
   return RTC_OK;
 }
 
-int rtc_set_rebase_wide(int enabled) {
-  rtc::g_rebase_wide = enabled != 0;
+int rtc_set_rebase_wide(int mode) {
+  if (mode < 0 || mode > 2) return RTC_ERR_MODE;
+  rtc::g_rebase_wide = mode;
   return RTC_OK;
 }
 

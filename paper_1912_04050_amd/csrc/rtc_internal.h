@@ -29,7 +29,7 @@ extern double g_packed_min_work;  // planner knob, see rtc_set_packed_min_work
 extern int64_t g_packed_small_n;  // planner knob, see rtc_set_packed_small_n
 extern bool g_structure_paths;    // planner knob, see rtc_set_structure_paths
 extern int64_t g_small_items;     // planner knob, see rtc_set_small_problem_items
-extern bool g_rebase_wide;        // planner knob, see rtc_set_rebase_wide
+extern int g_rebase_wide;         // planner knob, see rtc_set_rebase_wide
 
 // HBM-bound curve kernels (curve_ops.hip).
 int launch_pseudo_inverse(const void* f, int64_t n, const void* x, int64_t m, int32_t* out,

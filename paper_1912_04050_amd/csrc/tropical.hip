@@ -56,7 +56,7 @@ namespace rtc {
 int64_t g_packed_small_n = 4096;   // rows up to this length use the narrower packed tiles
 bool g_structure_paths = true;     // rows of exploitable convexity / periodicity take their own kernels
 int64_t g_small_items = 256;       // problems with fewer work items than this get the small tiles, see kSmallR
-bool g_rebase_wide = true;         // slowly varying int64 rows beyond 32 bits: 32-bit arithmetic re-based per chunk
+int g_rebase_wide = 2;             // int64 rows beyond 32 bits: 0 64-bit kernel, 1 also re-based per chunk, 2 also common slope removed
 
 namespace {
 
@@ -359,10 +359,10 @@ size_t narrow_base_offset(int64_t batch, int64_t n) {
 }
 constexpr int kProbeMaxSegs = 16;   // segments per row of the two-pass range probe
 size_t narrow_partial_offset(int64_t batch, int64_t n) {
-  return narrow_base_offset(batch, n) + ((size_t)batch * sizeof(int64_t) + 255) / 256 * 256;
+  return narrow_base_offset(batch, n) + ((size_t)batch * 2 * sizeof(int64_t) + 255) / 256 * 256;   // [base, slope] per row
 }
 size_t narrow_tables_offset(int64_t batch, int64_t n) {
-  return narrow_partial_offset(batch, n) + ((size_t)batch * kProbeMaxSegs * 5 * sizeof(int64_t) + 255) / 256 * 256;
+  return narrow_partial_offset(batch, n) + ((size_t)batch * kProbeMaxSegs * kProbePartial * sizeof(int64_t) + 255) / 256 * 256;
 }
 size_t narrow_bytes(int64_t batch, int64_t n) {
   return narrow_tables_offset(batch, n) + (wide_table_elems(batch, n) * sizeof(int64_t) + 255) / 256 * 256;
@@ -371,7 +371,7 @@ size_t narrow_bytes(int64_t batch, int64_t n) {
 template <int OP>
 int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, int64_t stride_f,
             int64_t stride_g, const void* cap, void* ws, int32_t* dev_flags, hipStream_t stream) {
-  // workspace: [f32: batch*n][g32: batch*n][narrow_ok: batch][out_base: batch int64][probe partials]
+  // workspace: [f32: batch*n][g32: batch*n][narrow_ok: batch][out_base: 2*batch int64][probe partials]
   // [block tables of the re-based path][packed-path arrays]
   int32_t* f32 = static_cast<int32_t*>(ws);
   int32_t* g32 = f32 + batch * n;
@@ -393,7 +393,7 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
                      (int)n, OP, structure, f32, g32, ok, base,
                      reinterpret_cast<int32_t*>(wsp + L.off_ok),
                      reinterpret_cast<int32_t*>(wsp + L.off_rho), dev_flags, segs,
-                     segs > 1 ? partial : (const int64_t*)nullptr);
+                     segs > 1 ? partial : (const int64_t*)nullptr, g_rebase_wide >= 2);
   if (structure)
     launch_period<int64_t>(static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g, ok,
                            reinterpret_cast<int32_t*>(wsp + L.off_period),
@@ -403,7 +403,7 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
   int64_t* tab = reinterpret_cast<int64_t*>(static_cast<char*>(ws) + narrow_tables_offset(batch, n));
   const int nb = wide_blocks(n);
   const Plan pw = make_plan<int32_t, kWideR>(batch, n);
-  const bool rebase = g_rebase_wide && n > kWideBlock && pw.items <= 0x7fffffffLL;
+  const bool rebase = g_rebase_wide >= 1 && n > kWideBlock && pw.items <= 0x7fffffffLL;
   if (rebase) {
     hipLaunchKernelGGL(wide_tables_kernel<OP>, dim3((uint32_t)batch), dim3(kWideThreads), 0, stream,
                        static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g, ok, tab,

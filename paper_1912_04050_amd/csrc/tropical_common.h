@@ -188,7 +188,7 @@ struct TropicalArgs {
   int32_t n_tiles;
   int32_t fold_width;   // work items launched per folded tile pair (see decode_item)
   int32_t seg;          // steps of s per segment, a multiple of the chunk length
-  const int64_t* out_base;  // optional per-row constant added to every stored value (re-based int64 rows)
+  const int64_t* out_base;  // optional per-row [constant, slope]: constant + slope * (output index) is added to every stored value (narrowed int64 rows)
   int32_t use_aux;      // 1: skip the chunks that the packed items of the same launch own (see aux)
   PackAux aux;
 };

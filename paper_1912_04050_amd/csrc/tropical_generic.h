@@ -138,7 +138,7 @@ __device__ __forceinline__ void tropical_body(const TropicalArgs& p, unsigned ch
       const T av = xp[x + x / R];
       if (ATOMIC && av == SR::identity()) continue;   // this item saw no candidate of that output
       OutT v = (OutT)av;
-      if (p.out_base != nullptr) v += (OutT)p.out_base[row];
+      if (p.out_base != nullptr) v += (OutT)(p.out_base[2 * row] + p.out_base[2 * row + 1] * ot);   // base + slope * output index
       if (crow) v = sel_min(v, crow[ot]);
       if (ATOMIC) {
         if (op_max(OP)) atomic_max(&orow[ot], v); else atomic_min(&orow[ot], v);

@@ -207,7 +207,7 @@ __device__ __forceinline__ void packed_body(const TropicalArgs& p, unsigned char
       if (t < n && av != kIdent) {
         const int ot = op_sub(OP) ? n - 1 - t : t;
         OutT v = (OutT)(op_sub(OP) ? wrap_sub(av, rho * t) : wrap_add(av, rho * t));
-        if (p.out_base != nullptr) v += (OutT)p.out_base[row];
+        if (p.out_base != nullptr) v += (OutT)(p.out_base[2 * row] + p.out_base[2 * row + 1] * ot);   // base + slope * output index
         if (crow) v = sel_min(v, crow[ot]);
         if (op_max(OP)) atomic_max(&orow[ot], v); else atomic_min(&orow[ot], v);
       }

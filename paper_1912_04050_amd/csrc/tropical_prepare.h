@@ -144,13 +144,30 @@ __global__ __launch_bounds__(1024) void probe_kernel(const T* __restrict__ f, in
   }
 }
 
+// Values of the table probe_partial_kernel leaves per (row, segment).
+constexpr int kProbePartial = 9;
+
+// Common slope of a row pair, removed from both rows before they are narrowed to 32 bits: with
+// f[i] = Bf + fd[i] + rho i and g[i] = Bg + gd[i] + rho i every candidate of the four products is
+// the candidate of (fd, gd) plus (Bf +- Bg) + rho t, so cumulative curves that grow far beyond
+// 32 bits but stay close to a line (time in nanoseconds, cycles) still take the 32-bit and packed
+// kernels.  Half the sum of the two mean slopes; all of this is exact whenever both rows' ranges
+// are below 2^62, which the caller checks once it has the extrema.
+__device__ __forceinline__ int64_t common_slope(const int64_t* fr, const int64_t* gr, int n) {
+  if (n < 2) return 0;
+  return wrap_sub(fr[n - 1], fr[0]) / (n - 1) / 2 + wrap_sub(gr[n - 1], gr[0]) / (n - 1) / 2;
+}
+__device__ __forceinline__ int64_t detrended(int64_t v, int64_t v0, int64_t slope, int i) {
+  return wrap_sub(wrap_sub(v, v0), (int64_t)((uint64_t)slope * (uint64_t)i));
+}
+
 // First half of the range probe of long int64 rows: extrema and shape bits of one segment of
 // one row pair, [fmin, fmax, gmin, gmax, bits] at partial[(row * segs + seg) * 5].
 __global__ __launch_bounds__(1024) void probe_partial_kernel(const int64_t* __restrict__ f, int64_t stride_f,
                                                              const int64_t* __restrict__ g, int64_t stride_g,
                                                              int n, bool structure, int segs,
                                                              int64_t* __restrict__ partial) {
-  __shared__ int64_t red[4][16];
+  __shared__ int64_t red[8][16];
   __shared__ int s_bits[16];
   const int row = blockIdx.x / segs, seg = blockIdx.x % segs;
   const int seg_len = (n + segs - 1) / segs;
@@ -158,22 +175,30 @@ __global__ __launch_bounds__(1024) void probe_partial_kernel(const int64_t* __re
   const int64_t* fr = f + (int64_t)row * stride_f;
   const int64_t* gr = g + (int64_t)row * stride_g;
   int64_t fmin = INT64_MAX, fmax = INT64_MIN, gmin = INT64_MAX, gmax = INT64_MIN;
+  int64_t dfmin = INT64_MAX, dfmax = INT64_MIN, dgmin = INT64_MAX, dgmax = INT64_MIN;   // with the common slope removed
+  const int64_t f0 = fr[0], g0 = gr[0], slope = common_slope(fr, gr, n);
   int bits = structure ? 15 : 0;
   for (int i = i_begin + threadIdx.x; i < i_end; i += blockDim.x) {
     const int64_t fv = fr[i], gv = gr[i];
     fmin = sel_min(fmin, fv); fmax = sel_max(fmax, fv);
     gmin = sel_min(gmin, gv); gmax = sel_max(gmax, gv);
+    const int64_t fd = detrended(fv, f0, slope, i), gd = detrended(gv, g0, slope, i);
+    dfmin = sel_min(dfmin, fd); dfmax = sel_max(dfmax, fd);
+    dgmin = sel_min(dgmin, gd); dgmax = sel_max(dgmax, gd);
     if (bits != 0 && i >= 1 && i <= n - 2) bits &= second_diff_bits(fr, i) | (second_diff_bits(gr, i) << 2);
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) {
     fmin = sel_min(fmin, __shfl_xor(fmin, off)); fmax = sel_max(fmax, __shfl_xor(fmax, off));
     gmin = sel_min(gmin, __shfl_xor(gmin, off)); gmax = sel_max(gmax, __shfl_xor(gmax, off));
+    dfmin = sel_min(dfmin, __shfl_xor(dfmin, off)); dfmax = sel_max(dfmax, __shfl_xor(dfmax, off));
+    dgmin = sel_min(dgmin, __shfl_xor(dgmin, off)); dgmax = sel_max(dgmax, __shfl_xor(dgmax, off));
     bits &= __shfl_xor(bits, off);
   }
   const int wave = threadIdx.x >> 6;
   if ((threadIdx.x & 63) == 0) {
     red[0][wave] = fmin; red[1][wave] = fmax; red[2][wave] = gmin; red[3][wave] = gmax;
+    red[4][wave] = dfmin; red[5][wave] = dfmax; red[6][wave] = dgmin; red[7][wave] = dgmax;
     s_bits[wave] = bits;
   }
   __syncthreads();
@@ -182,17 +207,23 @@ __global__ __launch_bounds__(1024) void probe_partial_kernel(const int64_t* __re
     for (int w = 1; w < nw; ++w) {
       fmin = sel_min(fmin, red[0][w]); fmax = sel_max(fmax, red[1][w]);
       gmin = sel_min(gmin, red[2][w]); gmax = sel_max(gmax, red[3][w]);
+      dfmin = sel_min(dfmin, red[4][w]); dfmax = sel_max(dfmax, red[5][w]);
+      dgmin = sel_min(dgmin, red[6][w]); dgmax = sel_max(dgmax, red[7][w]);
       bits &= s_bits[w];
     }
-    int64_t* q = partial + ((int64_t)row * segs + seg) * 5;
+    int64_t* q = partial + ((int64_t)row * segs + seg) * kProbePartial;
     q[0] = fmin; q[1] = fmax; q[2] = gmin; q[3] = gmax; q[4] = bits;
+    q[5] = dfmin; q[6] = dfmax; q[7] = dgmin; q[8] = dgmax;
   }
 }
 
 // Range probe of one int64 row pair.  A row whose two value ranges (max - min) are below 2^30
 // is re-based to its minima and copied as int32: every candidate of the re-based rows fits
-// 32 bits, so the 32-bit kernels compute it exactly and add `out_base` (f_min + g_min, or
-// f_min - g_min for the deconvolutions) back on store.  Rows with a wider range keep the
+// 32 bits, so the 32-bit kernels compute it exactly and add `out_base[2 row]` (f_min + g_min,
+// or f_min - g_min for the deconvolutions) back on store.  With `detrend`, a pair that is too
+// wide for that but narrow once the pair's common slope is removed (common_slope) is copied
+// without the slope, and `out_base[2 row + 1]`, the slope, times the output index is added
+// back as well.  Rows with a wider range keep the
 // 64-bit kernel.  Also: overflow flag, packed-path eligibility and slope, and (when `structure`
 // is set) the convexity test, as in probe_kernel; narrow_ok[row] receives the selector code.
 __global__ __launch_bounds__(1024) void probe_narrow_kernel(const int64_t* __restrict__ f, int64_t stride_f,
@@ -205,9 +236,9 @@ __global__ __launch_bounds__(1024) void probe_narrow_kernel(const int64_t* __res
                                                             int32_t* __restrict__ pack_ok,
                                                             int32_t* __restrict__ rho,
                                                             int32_t* __restrict__ dev_flags, int segs,
-                                                            const int64_t* __restrict__ partial) {
-  __shared__ int64_t red[4][16];
-  __shared__ int64_t s_base[2];
+                                                            const int64_t* __restrict__ partial, bool detrend) {
+  __shared__ int64_t red[8][16];
+  __shared__ int64_t s_base[3];
   __shared__ int s_narrow;
   __shared__ int s_bits[16];
   const bool deconv = op_sub(op);
@@ -220,30 +251,40 @@ __global__ __launch_bounds__(1024) void probe_narrow_kernel(const int64_t* __res
   const int64_t* fr = f + (int64_t)row * stride_f;
   const int64_t* gr = g + (int64_t)row * stride_g;
   int64_t fmin = INT64_MAX, fmax = INT64_MIN, gmin = INT64_MAX, gmax = INT64_MIN;
+  int64_t dfmin = INT64_MAX, dfmax = INT64_MIN, dgmin = INT64_MAX, dgmax = INT64_MIN;   // with the common slope removed
+  const int64_t f0 = fr[0], g0 = gr[0], slope = common_slope(fr, gr, n);
   int bits = structure ? 15 : 0;
   if (partial != nullptr && threadIdx.x == 0) {
     for (int sg = 0; sg < segs; ++sg) {
-      const int64_t* q = partial + ((int64_t)row * segs + sg) * 5;
+      const int64_t* q = partial + ((int64_t)row * segs + sg) * kProbePartial;
       fmin = sel_min(fmin, q[0]); fmax = sel_max(fmax, q[1]);
       gmin = sel_min(gmin, q[2]); gmax = sel_max(gmax, q[3]);
       bits &= (int)q[4];
+      dfmin = sel_min(dfmin, q[5]); dfmax = sel_max(dfmax, q[6]);
+      dgmin = sel_min(dgmin, q[7]); dgmax = sel_max(dgmax, q[8]);
     }
   }
   for (int i = threadIdx.x; partial == nullptr && i < n; i += blockDim.x) {
     const int64_t fv = fr[i], gv = gr[i];
     fmin = sel_min(fmin, fv); fmax = sel_max(fmax, fv);
     gmin = sel_min(gmin, gv); gmax = sel_max(gmax, gv);
+    const int64_t fd = detrended(fv, f0, slope, i), gd = detrended(gv, g0, slope, i);
+    dfmin = sel_min(dfmin, fd); dfmax = sel_max(dfmax, fd);
+    dgmin = sel_min(dgmin, gd); dgmax = sel_max(dgmax, gd);
     if (bits != 0 && i >= 1 && i <= n - 2) bits &= second_diff_bits(fr, i) | (second_diff_bits(gr, i) << 2);
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) {
     fmin = sel_min(fmin, __shfl_xor(fmin, off)); fmax = sel_max(fmax, __shfl_xor(fmax, off));
     gmin = sel_min(gmin, __shfl_xor(gmin, off)); gmax = sel_max(gmax, __shfl_xor(gmax, off));
+    dfmin = sel_min(dfmin, __shfl_xor(dfmin, off)); dfmax = sel_max(dfmax, __shfl_xor(dfmax, off));
+    dgmin = sel_min(dgmin, __shfl_xor(dgmin, off)); dgmax = sel_max(dgmax, __shfl_xor(dgmax, off));
     bits &= __shfl_xor(bits, off);
   }
   const int wave = threadIdx.x >> 6;
   if ((threadIdx.x & 63) == 0) {
     red[0][wave] = fmin; red[1][wave] = fmax; red[2][wave] = gmin; red[3][wave] = gmax;
+    red[4][wave] = dfmin; red[5][wave] = dfmax; red[6][wave] = dgmin; red[7][wave] = dgmax;
     s_bits[wave] = bits;
   }
   __syncthreads();
@@ -252,6 +293,8 @@ __global__ __launch_bounds__(1024) void probe_narrow_kernel(const int64_t* __res
     for (int w = 1; w < nw; ++w) {
       fmin = sel_min(fmin, red[0][w]); fmax = sel_max(fmax, red[1][w]);
       gmin = sel_min(gmin, red[2][w]); gmax = sel_max(gmax, red[3][w]);
+      dfmin = sel_min(dfmin, red[4][w]); dfmax = sel_max(dfmax, red[5][w]);
+      dgmin = sel_min(dgmin, red[6][w]); dgmax = sel_max(dgmax, red[7][w]);
       bits &= s_bits[w];
     }
     int64_t dummy;
@@ -262,21 +305,32 @@ __global__ __launch_bounds__(1024) void probe_narrow_kernel(const int64_t* __res
     const uint64_t frange = (uint64_t)fmax - (uint64_t)fmin, grange = (uint64_t)gmax - (uint64_t)gmin;
     // the second differences were exact only if both ranges are below 2^62
     if ((frange >> 62) != 0 || (grange >> 62) != 0) bits = 0;
-    const bool narrow = frange < (1ull << 30) && grange < (1ull << 30);
+    // narrow as the rows are, or (the rows' ranges permitting exact arithmetic) with the common slope removed
+    const bool raw = frange < (1ull << 30) && grange < (1ull << 30);
+    const uint64_t dfrange = (uint64_t)dfmax - (uint64_t)dfmin, dgrange = (uint64_t)dgmax - (uint64_t)dgmin;
+    const bool lined = !raw && detrend && (frange >> 62) == 0 && (grange >> 62) == 0 && dfrange < (1ull << 30) &&
+                       dgrange < (1ull << 30);
+    const bool narrow = raw || lined;
+    const int64_t rho_row = lined ? slope : 0;
+    const int64_t fb = lined ? wrap_add(f0, dfmin) : fmin, gb = lined ? wrap_add(g0, dgmin) : gmin;
+    const uint64_t fr32 = lined ? dfrange : frange, gr32 = lined ? dgrange : grange;   // ranges of the int32 copies
     const int code = structure_code(op, bits, narrow ? 1 : 0);
     const bool general = code < kSelSearch;
-    s_base[0] = fmin; s_base[1] = gmin; s_narrow = narrow && general ? 1 : 0;
+    s_base[0] = fb; s_base[1] = gb; s_base[2] = rho_row; s_narrow = narrow && general ? 1 : 0;
     // re-based values lie in [0, 2^29): the detrended rows stay inside int32
-    const bool ok = general && frange < (1ull << 29) && grange < (1ull << 29);
+    const bool ok = general && narrow && fr32 < (1ull << 29) && gr32 < (1ull << 29);
     if (publish) {
       narrow_ok[row] = code;
-      out_base[row] = narrow ? (deconv ? wrap_sub(fmin, gmin) : wrap_add(fmin, gmin)) : 0;
+      out_base[2 * row] = narrow ? (deconv ? wrap_sub(fb, gb) : wrap_add(fb, gb)) : 0;
+      out_base[2 * row + 1] = rho_row;
       pack_ok[row] = ok ? 1 : 0;
     }
     int32_t r = 0;
     if (publish && ok && n > 1) {
-      const int64_t w0 = deconv ? fr[0] : gr[0], w1 = deconv ? fr[n - 1] : gr[n - 1];
-      const int64_t u0 = deconv ? gr[0] : fr[0], u1 = deconv ? gr[n - 1] : fr[n - 1];
+      // end points of the int32 copies
+      const int64_t fa = 0, fz = detrended(fr[n - 1], f0, rho_row, n - 1), ga = 0, gz = detrended(gr[n - 1], g0, rho_row, n - 1);
+      const int64_t w0 = deconv ? fa : ga, w1 = deconv ? fz : gz;
+      const int64_t u0 = deconv ? ga : fa, u1 = deconv ? gz : fz;
       r = w1 > w0 ? (int32_t)((w1 - w0) / (n - 1)) : 0;
       const int64_t ru = (u1 - u0) / (n - 1);
       const int64_t diff = ru > r ? ru - r : r - ru;
@@ -287,9 +341,10 @@ __global__ __launch_bounds__(1024) void probe_narrow_kernel(const int64_t* __res
   __syncthreads();
   if (s_narrow) {
     const int64_t fb = s_base[0], gb = s_base[1];
+    const uint64_t rho_row = (uint64_t)s_base[2];
     for (int i = i_begin + threadIdx.x; i < i_end; i += blockDim.x) {
-      f32[(int64_t)row * n + i] = (int32_t)(fr[i] - fb);
-      g32[(int64_t)row * n + i] = (int32_t)(gr[i] - gb);
+      f32[(int64_t)row * n + i] = (int32_t)(uint32_t)((uint64_t)fr[i] - (uint64_t)fb - rho_row * (uint64_t)i);
+      g32[(int64_t)row * n + i] = (int32_t)(uint32_t)((uint64_t)gr[i] - (uint64_t)gb - rho_row * (uint64_t)i);
     }
   }
 }

@@ -207,8 +207,10 @@ _lib.rtc_set_rebase_wide.argtypes = [_int]
 _lib.rtc_set_rebase_wide.restype = _int
 
 
-def rtc_set_rebase_wide(enabled: bool):
-    _check(_lib.rtc_set_rebase_wide(1 if enabled else 0))
+def rtc_set_rebase_wide(mode: int):
+    """0: wide int64 rows stay with the 64-bit kernel; 1: slowly varying ones are re-based per chunk;
+    2 (default): before that, pairs close to a line are narrowed with their common slope removed."""
+    _check(_lib.rtc_set_rebase_wide(int(mode)))
 
 
 _lib.rtc_set_structure_paths.argtypes = [_int]

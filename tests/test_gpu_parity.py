@@ -597,9 +597,10 @@ def test_periodic_operands(rtc, dtype):
 
 
 def test_wide_int64_rows_rebased_per_chunk(rtc):
-    """int64 rows that span far more than 32 bits but vary slowly take 32-bit arithmetic re-based
-    per chunk; rows with a jump beyond the budget, or steep ones, stay with the 64-bit kernel.  Both
-    next to each other in one batch, all four products, with the path on and off."""
+    """int64 rows that span far more than 32 bits: pairs close to a common line are narrowed with
+    the slope removed, pairs that vary slowly take 32-bit arithmetic re-based per chunk, pairs
+    with a jump beyond the budget, or steep ones, stay with the 64-bit kernel.  All kinds next to
+    each other in one batch, all four products, under the three settings of the knob."""
     rng = np.random.default_rng(53)
     for n in (1025, 5000, 20011):
         def slow(offset):               # monotone, increments up to 4e5: about 1.2e9 over a chunk plus a window
@@ -615,13 +616,13 @@ def test_wide_int64_rows_rebased_per_chunk(rtc):
         over[512:] += 2
         f = np.stack([slow(1 << 45), walk(-(1 << 50)), jump, slow(0), steep, edge, over, slow(7)]).astype(np.int64)
         g = np.stack([slow(-(1 << 44)), slow(1 << 33), slow(5), walk(1 << 41), slow(0), edge, over, walk(0)]).astype(np.int64)
-        for on in (True, False):
-            rtc.rtc_set_rebase_wide(on)
+        for mode in (2, 1, 0):
+            rtc.rtc_set_rebase_wide(mode)
             try:
-                check_products(rtc, f, g, f"wide rows n={n} rebased={on}")
-                check_duals(rtc, f, g, f"wide rows duals n={n} rebased={on}")
+                check_products(rtc, f, g, f"wide rows n={n} mode={mode}")
+                check_duals(rtc, f, g, f"wide rows duals n={n} mode={mode}")
             finally:
-                rtc.rtc_set_rebase_wide(True)
+                rtc.rtc_set_rebase_wide(2)
 
 
 def test_structure_paths_knob(rtc):
