@@ -644,3 +644,19 @@ def test_one_convex_operand_makes_the_optimal_split_monotone():
         dec = oracle.maxplus_deconv(h[None], f[None])[0]
         argd = [min(u for u in range(n - t) if h[t + u] - f[u] == dec[t]) for t in range(n)]
         assert all(a >= b for a, b in zip(argd, argd[1:]))
+
+
+def test_a_common_slope_passes_through_the_products():
+    """(f + rho i) (x) (g + rho i) = (f (x) g) + rho t, and the same for the deconvolutions and the
+    dual products (every candidate of output t gains rho t); constants pass through with the sign
+    of the operand."""
+    rng = np.random.default_rng(88)
+    n = 150
+    f = np.cumsum(rng.integers(-20, 50, n))[None]
+    g = np.cumsum(rng.integers(-5, 70, n))[None]
+    ramp = np.arange(n, dtype=np.int64)[None]
+    for rho, cf, cg in ((3, 0, 0), (-7, 11, -5), (1 << 33, 1 << 40, -(1 << 41))):
+        fs, gs = f + rho * ramp + cf, g + rho * ramp + cg
+        for prod, sign in ((oracle.minplus_conv, 1), (oracle.maxplus_conv, 1), (oracle.maxplus_deconv, -1),
+                           (oracle.minplus_deconv, -1)):
+            assert np.array_equal(prod(fs, gs), prod(f, g) + rho * ramp + cf + sign * cg)
