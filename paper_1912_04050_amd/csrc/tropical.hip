@@ -436,7 +436,7 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
     args.n = (int32_t)n; args.batch = (int32_t)batch;
     args.n_tiles = pw.n_tiles; args.fold_width = pw.fold_width; args.seg = pw.seg;
     const uint32_t items_per_row = (uint32_t)(pw.items / batch);
-    uint32_t parts = (uint32_t)(16384 / batch);
+    uint32_t parts = (uint32_t)(4096 / batch);
     if (parts < 1) parts = 1;
     if (parts > items_per_row) parts = items_per_row;
     prof_begin(RTC_PROFILE_KIND(RTC_I64, 0, OP), stream);

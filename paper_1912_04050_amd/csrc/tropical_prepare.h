@@ -157,6 +157,15 @@ __device__ __forceinline__ int64_t common_slope(const int64_t* fr, const int64_t
   if (n < 2) return 0;
   return wrap_sub(fr[n - 1], fr[0]) / (n - 1) / 2 + wrap_sub(gr[n - 1], gr[0]) / (n - 1) / 2;
 }
+// The detrended extrema cost as much again as the plain ones, and a pair of monotone rows whose
+// end points are less than 2^30 apart is narrow as it is: only pairs with an end-to-end rise of
+// 2^30 or more are looked at (a non-monotone pair that is wide between close end points then
+// goes without this remedy).
+__device__ __forceinline__ bool worth_detrending(const int64_t* fr, const int64_t* gr, int n) {
+  const uint64_t lim = 1ull << 30;
+  const int64_t df = wrap_sub(fr[n - 1], fr[0]), dg = wrap_sub(gr[n - 1], gr[0]);
+  return (uint64_t)(df < 0 ? -(uint64_t)df : (uint64_t)df) >= lim || (uint64_t)(dg < 0 ? -(uint64_t)dg : (uint64_t)dg) >= lim;
+}
 __device__ __forceinline__ int64_t detrended(int64_t v, int64_t v0, int64_t slope, int i) {
   return wrap_sub(wrap_sub(v, v0), (int64_t)((uint64_t)slope * (uint64_t)i));
 }
@@ -176,29 +185,37 @@ __global__ __launch_bounds__(1024) void probe_partial_kernel(const int64_t* __re
   const int64_t* gr = g + (int64_t)row * stride_g;
   int64_t fmin = INT64_MAX, fmax = INT64_MIN, gmin = INT64_MAX, gmax = INT64_MIN;
   int64_t dfmin = INT64_MAX, dfmax = INT64_MIN, dgmin = INT64_MAX, dgmax = INT64_MIN;   // with the common slope removed
-  const int64_t f0 = fr[0], g0 = gr[0], slope = common_slope(fr, gr, n);
+  const bool lines = worth_detrending(fr, gr, n);
+  const int64_t f0 = fr[0], g0 = gr[0], slope = lines ? common_slope(fr, gr, n) : 0;   // (64-bit divisions: not for nothing)
   int bits = structure ? 15 : 0;
   for (int i = i_begin + threadIdx.x; i < i_end; i += blockDim.x) {
     const int64_t fv = fr[i], gv = gr[i];
     fmin = sel_min(fmin, fv); fmax = sel_max(fmax, fv);
     gmin = sel_min(gmin, gv); gmax = sel_max(gmax, gv);
-    const int64_t fd = detrended(fv, f0, slope, i), gd = detrended(gv, g0, slope, i);
-    dfmin = sel_min(dfmin, fd); dfmax = sel_max(dfmax, fd);
-    dgmin = sel_min(dgmin, gd); dgmax = sel_max(dgmax, gd);
+    if (lines) {
+      const int64_t fd = detrended(fv, f0, slope, i), gd = detrended(gv, g0, slope, i);
+      dfmin = sel_min(dfmin, fd); dfmax = sel_max(dfmax, fd);
+      dgmin = sel_min(dgmin, gd); dgmax = sel_max(dgmax, gd);
+    }
     if (bits != 0 && i >= 1 && i <= n - 2) bits &= second_diff_bits(fr, i) | (second_diff_bits(gr, i) << 2);
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) {
     fmin = sel_min(fmin, __shfl_xor(fmin, off)); fmax = sel_max(fmax, __shfl_xor(fmax, off));
     gmin = sel_min(gmin, __shfl_xor(gmin, off)); gmax = sel_max(gmax, __shfl_xor(gmax, off));
-    dfmin = sel_min(dfmin, __shfl_xor(dfmin, off)); dfmax = sel_max(dfmax, __shfl_xor(dfmax, off));
-    dgmin = sel_min(dgmin, __shfl_xor(dgmin, off)); dgmax = sel_max(dgmax, __shfl_xor(dgmax, off));
     bits &= __shfl_xor(bits, off);
+  }
+  if (lines) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      dfmin = sel_min(dfmin, __shfl_xor(dfmin, off)); dfmax = sel_max(dfmax, __shfl_xor(dfmax, off));
+      dgmin = sel_min(dgmin, __shfl_xor(dgmin, off)); dgmax = sel_max(dgmax, __shfl_xor(dgmax, off));
+    }
   }
   const int wave = threadIdx.x >> 6;
   if ((threadIdx.x & 63) == 0) {
     red[0][wave] = fmin; red[1][wave] = fmax; red[2][wave] = gmin; red[3][wave] = gmax;
-    red[4][wave] = dfmin; red[5][wave] = dfmax; red[6][wave] = dgmin; red[7][wave] = dgmax;
+    if (lines) { red[4][wave] = dfmin; red[5][wave] = dfmax; red[6][wave] = dgmin; red[7][wave] = dgmax; }
     s_bits[wave] = bits;
   }
   __syncthreads();
@@ -207,8 +224,10 @@ __global__ __launch_bounds__(1024) void probe_partial_kernel(const int64_t* __re
     for (int w = 1; w < nw; ++w) {
       fmin = sel_min(fmin, red[0][w]); fmax = sel_max(fmax, red[1][w]);
       gmin = sel_min(gmin, red[2][w]); gmax = sel_max(gmax, red[3][w]);
-      dfmin = sel_min(dfmin, red[4][w]); dfmax = sel_max(dfmax, red[5][w]);
-      dgmin = sel_min(dgmin, red[6][w]); dgmax = sel_max(dgmax, red[7][w]);
+      if (lines) {
+        dfmin = sel_min(dfmin, red[4][w]); dfmax = sel_max(dfmax, red[5][w]);
+        dgmin = sel_min(dgmin, red[6][w]); dgmax = sel_max(dgmax, red[7][w]);
+      }
       bits &= s_bits[w];
     }
     int64_t* q = partial + ((int64_t)row * segs + seg) * kProbePartial;
@@ -252,7 +271,8 @@ __global__ __launch_bounds__(1024) void probe_narrow_kernel(const int64_t* __res
   const int64_t* gr = g + (int64_t)row * stride_g;
   int64_t fmin = INT64_MAX, fmax = INT64_MIN, gmin = INT64_MAX, gmax = INT64_MIN;
   int64_t dfmin = INT64_MAX, dfmax = INT64_MIN, dgmin = INT64_MAX, dgmax = INT64_MIN;   // with the common slope removed
-  const int64_t f0 = fr[0], g0 = gr[0], slope = common_slope(fr, gr, n);
+  const bool lines = worth_detrending(fr, gr, n);
+  const int64_t f0 = fr[0], g0 = gr[0], slope = lines ? common_slope(fr, gr, n) : 0;   // (64-bit divisions: not for nothing)
   int bits = structure ? 15 : 0;
   if (partial != nullptr && threadIdx.x == 0) {
     for (int sg = 0; sg < segs; ++sg) {
@@ -268,23 +288,30 @@ __global__ __launch_bounds__(1024) void probe_narrow_kernel(const int64_t* __res
     const int64_t fv = fr[i], gv = gr[i];
     fmin = sel_min(fmin, fv); fmax = sel_max(fmax, fv);
     gmin = sel_min(gmin, gv); gmax = sel_max(gmax, gv);
-    const int64_t fd = detrended(fv, f0, slope, i), gd = detrended(gv, g0, slope, i);
-    dfmin = sel_min(dfmin, fd); dfmax = sel_max(dfmax, fd);
-    dgmin = sel_min(dgmin, gd); dgmax = sel_max(dgmax, gd);
+    if (lines) {
+      const int64_t fd = detrended(fv, f0, slope, i), gd = detrended(gv, g0, slope, i);
+      dfmin = sel_min(dfmin, fd); dfmax = sel_max(dfmax, fd);
+      dgmin = sel_min(dgmin, gd); dgmax = sel_max(dgmax, gd);
+    }
     if (bits != 0 && i >= 1 && i <= n - 2) bits &= second_diff_bits(fr, i) | (second_diff_bits(gr, i) << 2);
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) {
     fmin = sel_min(fmin, __shfl_xor(fmin, off)); fmax = sel_max(fmax, __shfl_xor(fmax, off));
     gmin = sel_min(gmin, __shfl_xor(gmin, off)); gmax = sel_max(gmax, __shfl_xor(gmax, off));
-    dfmin = sel_min(dfmin, __shfl_xor(dfmin, off)); dfmax = sel_max(dfmax, __shfl_xor(dfmax, off));
-    dgmin = sel_min(dgmin, __shfl_xor(dgmin, off)); dgmax = sel_max(dgmax, __shfl_xor(dgmax, off));
     bits &= __shfl_xor(bits, off);
+  }
+  if (lines) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      dfmin = sel_min(dfmin, __shfl_xor(dfmin, off)); dfmax = sel_max(dfmax, __shfl_xor(dfmax, off));
+      dgmin = sel_min(dgmin, __shfl_xor(dgmin, off)); dgmax = sel_max(dgmax, __shfl_xor(dgmax, off));
+    }
   }
   const int wave = threadIdx.x >> 6;
   if ((threadIdx.x & 63) == 0) {
     red[0][wave] = fmin; red[1][wave] = fmax; red[2][wave] = gmin; red[3][wave] = gmax;
-    red[4][wave] = dfmin; red[5][wave] = dfmax; red[6][wave] = dgmin; red[7][wave] = dgmax;
+    if (lines) { red[4][wave] = dfmin; red[5][wave] = dfmax; red[6][wave] = dgmin; red[7][wave] = dgmax; }
     s_bits[wave] = bits;
   }
   __syncthreads();
@@ -293,8 +320,10 @@ __global__ __launch_bounds__(1024) void probe_narrow_kernel(const int64_t* __res
     for (int w = 1; w < nw; ++w) {
       fmin = sel_min(fmin, red[0][w]); fmax = sel_max(fmax, red[1][w]);
       gmin = sel_min(gmin, red[2][w]); gmax = sel_max(gmax, red[3][w]);
-      dfmin = sel_min(dfmin, red[4][w]); dfmax = sel_max(dfmax, red[5][w]);
-      dgmin = sel_min(dgmin, red[6][w]); dgmax = sel_max(dgmax, red[7][w]);
+      if (lines) {
+        dfmin = sel_min(dfmin, red[4][w]); dfmax = sel_max(dfmax, red[5][w]);
+        dgmin = sel_min(dgmin, red[6][w]); dgmax = sel_max(dgmax, red[7][w]);
+      }
       bits &= s_bits[w];
     }
     int64_t dummy;
@@ -308,7 +337,7 @@ __global__ __launch_bounds__(1024) void probe_narrow_kernel(const int64_t* __res
     // narrow as the rows are, or (the rows' ranges permitting exact arithmetic) with the common slope removed
     const bool raw = frange < (1ull << 30) && grange < (1ull << 30);
     const uint64_t dfrange = (uint64_t)dfmax - (uint64_t)dfmin, dgrange = (uint64_t)dgmax - (uint64_t)dgmin;
-    const bool lined = !raw && detrend && (frange >> 62) == 0 && (grange >> 62) == 0 && dfrange < (1ull << 30) &&
+    const bool lined = !raw && detrend && lines && (frange >> 62) == 0 && (grange >> 62) == 0 && dfrange < (1ull << 30) &&
                        dgrange < (1ull << 30);
     const bool narrow = raw || lined;
     const int64_t rho_row = lined ? slope : 0;
@@ -342,9 +371,16 @@ __global__ __launch_bounds__(1024) void probe_narrow_kernel(const int64_t* __res
   if (s_narrow) {
     const int64_t fb = s_base[0], gb = s_base[1];
     const uint64_t rho_row = (uint64_t)s_base[2];
-    for (int i = i_begin + threadIdx.x; i < i_end; i += blockDim.x) {
-      f32[(int64_t)row * n + i] = (int32_t)(uint32_t)((uint64_t)fr[i] - (uint64_t)fb - rho_row * (uint64_t)i);
-      g32[(int64_t)row * n + i] = (int32_t)(uint32_t)((uint64_t)gr[i] - (uint64_t)gb - rho_row * (uint64_t)i);
+    if (rho_row == 0) {
+      for (int i = i_begin + threadIdx.x; i < i_end; i += blockDim.x) {
+        f32[(int64_t)row * n + i] = (int32_t)(fr[i] - fb);
+        g32[(int64_t)row * n + i] = (int32_t)(gr[i] - gb);
+      }
+    } else {
+      for (int i = i_begin + threadIdx.x; i < i_end; i += blockDim.x) {
+        f32[(int64_t)row * n + i] = (int32_t)(uint32_t)((uint64_t)fr[i] - (uint64_t)fb - rho_row * (uint64_t)i);
+        g32[(int64_t)row * n + i] = (int32_t)(uint32_t)((uint64_t)gr[i] - (uint64_t)gb - rho_row * (uint64_t)i);
+      }
     }
   }
 }
