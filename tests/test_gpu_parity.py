@@ -625,6 +625,37 @@ def test_wide_int64_rows_rebased_per_chunk(rtc):
                 rtc.rtc_set_rebase_wide(2)
 
 
+def test_wide_int64_rows_broadcast_and_inside_the_component_step(rtc):
+    """Steep int64 curves (slope 10^6 per step: far beyond 32 bits, close to a line) as a broadcast
+    operand, through the greedy-processing-component step (whose deconvolution stores through the
+    min with beta^u) and through a closure, under the three settings of the wide-row knob."""
+    rng = np.random.default_rng(57)
+    n = 3000
+    ramp = np.arange(n, dtype=np.int64)
+    def curve(rate, jitter):
+        v = rate * ramp + np.cumsum(rng.integers(0, jitter, n))
+        v[0] = 0
+        return v
+    alpha = np.stack([curve(1000000, 900), curve(999000, 50), curve(1000500, 4000)])
+    beta_l = np.stack([curve(1000200, 300), curve(1001000, 10), curve(1000500, 2000)])
+    beta_u = beta_l + np.stack([curve(3, 40), curve(0, 9), curve(10, 100)])
+    one = curve(1000100, 700)[None, :]
+    for mode in (2, 1, 0):
+        rtc.rtc_set_rebase_wide(mode)
+        try:
+            check_products(rtc, alpha, one, f"wide broadcast g mode={mode}")
+            check_duals(rtc, one, beta_l, f"wide broadcast f mode={mode}")
+            say("gpc on steep int64 curves, mode", mode)
+            au, bl = rtc.rtc_gpc_step(dev(alpha), dev(beta_u), dev(beta_l))
+            want_au, want_bl = oracle.gpc_step(alpha, beta_u, beta_l)
+            assert np.array_equal(host(au), want_au) and np.array_equal(host(bl), want_bl)
+            say("closure of steep int64 curves, mode", mode)
+            rows = alpha[:, :700]
+            assert np.array_equal(host(rtc.rtc_subadditive_closure(dev(rows))), oracle.closure(rows)[0])
+        finally:
+            rtc.rtc_set_rebase_wide(2)
+
+
 def test_structure_paths_knob(rtc):
     """The same rows through the structure-exploiting kernels and, with the knob off, through the
     general ones: the classification does not change, and both results equal the oracle."""
