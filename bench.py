@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--no-parity", action="store_true", help="skip the sampled parity check")
     ap.add_argument("--all-configs", action="store_true",
                     help="also time every operator on each of the five configurations (adds per_config)")
+    ap.add_argument("--configs", default="", help="profiling aid: restrict --all-configs to a comma list of "
+                    "configuration numbers 1..5 (3 includes the rows of exploitable convexity)")
     ap.add_argument("--only", default="", help="profiling aid: restrict the step to a comma list of "
                     "conv,deconv,pinv,compose,gpc,dev (the JSON line then describes that subset)")
     ap.add_argument("--bnn", action="store_true",
@@ -79,7 +81,7 @@ def gpu_ms(fn, warm=3, reps=10):
     return ts[len(ts) // 2], ts[0]
 
 
-def per_config_table(seed, peak_ops, with_cpu):
+def per_config_table(seed, peak_ops, with_cpu, configs=(1, 2, 3, 4, 5)):
     """GPU time of every exported operator on the five configurations, oracle time beside it."""
     import numpy as np
     import torch
@@ -184,167 +186,172 @@ def per_config_table(seed, peak_ops, with_cpu):
             r.update(extra)
         rows.append(r)
 
-    # config 1
-    c = wl.config1(seed)
-    product_rows(1, c["f"], c["g"], 1, "int32")
-    # config 2
-    c = wl.config2(seed, 1024, 4096)
-    a, b = product_rows(2, c["alpha_u"], c["beta_l"], 1024, "int32")
-    hd = torch.empty(1024, dtype=torch.int32, device="cuda")
-    vd = torch.empty(1024, dtype=torch.int32, device="cuda")
-    hbm_row(2, "max_hdev", lambda: rtc.rtc_max_hdev(a, b, out=hd), 2 * 1024 * 4096 * 4 + 4096, "int32", 1024, 4096)
-    hbm_row(2, "max_vdev", lambda: rtc.rtc_max_vdev(a, b, out=vd), 2 * 1024 * 4096 * 4 + 4096, "int32", 1024, 4096)
-    # sub-additive closure of config 2's arrival curves: ceil(log2(n-1)) = 12 squarings on the GPU; the
-    # oracle forms all n-2 powers by definition (cubic), so it is timed on shorter rows
-    clo = torch.empty_like(a)
-    ws_c = torch.empty(rtc.rtc_workspace_bytes(rtc.RTC_OP_CLOSURE, 1024, 4096, torch.int32), dtype=torch.uint8,
-                       device="cuda")
-    med, mn = gpu_ms(lambda: rtc.rtc_subadditive_closure(a, out=clo, ws=ws_c), warm=1, reps=5)
-    po_c = 12 * 1024 * 4096 * 4097 // 2
-    r = {"config": 2, "op": "subadditive_closure (12 squarings)", "dtype": "int32", "batch": 1024, "n": 4096,
-         "gpu_ms": round(med, 4), "gpu_ms_min": round(mn, 4), "pair_ops": po_c,
-         "gpair_ops_per_s": round(po_c / med / 1e6, 1),
-         "pct_valu_peak_2ops": round(100 * 2 * po_c / (med * 1e-3) / peak_ops, 1)}
-    also_general(r, lambda: rtc.rtc_subadditive_closure(a, out=clo, ws=ws_c), po_c, warm=1, reps=5)
-    if with_cpu:
-        short = np.ascontiguousarray(c["alpha_u"][:16, :512])
-        sec = cpu_s(lambda: oracle.closure(short))
-        r.update({"oracle_s": sec, "oracle_rows": 16, "oracle_threads": threads,
-                  "oracle_note": "16 rows cut to n=512: the oracle takes all 510 powers of a row, "
-                                 "510 x 512*513/2 pair-ops each row"})
-    rows.append(r)
-    # config 3: int64 storage (range-probed 32-bit arithmetic), native int32, and forced 64-bit arithmetic
-    c = wl.config3(seed, 64, 65536)
-    product_rows(3, c["f"], c["g"], 8, "int64 storage, int32 arithmetic")
-    product_rows(3, c["f"].astype(np.int32), c["g"].astype(np.int32), 8, "int32", duals=True)
-    product_rows(3, c["f"][:16] + (1 << 40), c["g"][:16] - (1 << 45), 4, "int64 storage with large offsets (re-based, int32 arithmetic)")
-    # cumulative curves on a fine time base: the same increments on top of a slope of 10^6 per step
-    # (values up to 6.5e10).  Too wide for narrowing by the row minima; with the pair's common slope
-    # removed they are configuration 3's own rows again and take the packed kernels
-    ramp = np.arange(65536, dtype=np.int64)
-    product_rows(3, c["f"][:16] + 1000003 * ramp, c["g"][:16] + 999983 * ramp, 4,
-                 "int64 storage, slope 10^6 per step (common slope removed, int32 / packed arithmetic)")
-    # values spanning 2^40: beyond the row-level narrowing, but slowly varying, so the chunks are
-    # re-based and reduced in 32-bit arithmetic; then the same rows with that path off (64-bit kernel)
-    product_rows(3, c["f"][:16] * 4096, c["g"][:16] * 4096, 4,
-                 "int64 storage, value range beyond 2^30 (common slope removed, int32 arithmetic)")
-    for mode, label in ((1, "int64 storage (the same rows, 32-bit arithmetic re-based per chunk)"),
-                        (0, "int64 arithmetic (the same rows, 64-bit kernel)")):
-        rtc.rtc_set_rebase_wide(mode)
-        try:
-            product_rows(3, c["f"][:16] * 4096, c["g"][:16] * 4096, 0, label)
-        finally:
-            rtc.rtc_set_rebase_wide(2)
-    # rows of exploitable convexity at the headline shape: token buckets (concave) and rate-latency
-    # curves (convex); the library detects them on the device and evaluates 2 or 2*log2(n) candidates
-    # per output instead of all of them, so the rate below is an equivalent, not executed work
-    rs = np.random.default_rng(seed)
-    tb = np.stack([wl.token_bucket(65536, int(rs.integers(100, 5000)), int(rs.integers(1, 40)), np.int32, at_zero=False)
-                   for _ in range(64)])
-    tb2 = np.stack([wl.token_bucket(65536, int(rs.integers(100, 5000)), int(rs.integers(1, 40)), np.int32, at_zero=False)
-                    for _ in range(64)])
-    rl = np.stack([wl.rate_latency(65536, int(rs.integers(2, 60)), int(rs.integers(0, 3000)), np.int32) for _ in range(64)])
-    rl2 = np.stack([wl.rate_latency(65536, int(rs.integers(2, 60)), int(rs.integers(0, 3000)), np.int32) for _ in range(64)])
-    arb = c["f"].astype(np.int32)
-    for label, fn, ofn, f_h, g_h, how in (
-            ("minplus_conv token-bucket x token-bucket", rtc.rtc_minplus_conv, "minplus_conv", tb, tb2, "ends"),
-            ("minplus_conv rate-latency x rate-latency", rtc.rtc_minplus_conv, "minplus_conv", rl, rl2, "bisection"),
-            ("maxplus_deconv token-bucket / rate-latency", rtc.rtc_maxplus_deconv, "maxplus_deconv", tb, rl, "bisection"),
-            # one operand of the right shape only: the configuration's own arbitrary curves against
-            # rate-latency service / from token-bucket arrivals
-            ("minplus_conv arbitrary x rate-latency", rtc.rtc_minplus_conv, "minplus_conv", arb, rl, "anchors + brackets"),
-            ("minplus_conv rate-latency x arbitrary", rtc.rtc_minplus_conv, "minplus_conv", rl, arb, "anchors + brackets, operands exchanged"),
-            ("maxplus_deconv token-bucket / arbitrary", rtc.rtc_maxplus_deconv, "maxplus_deconv", tb, arb, "anchors + brackets")):
-        f, g = dev(f_h), dev(g_h)
-        out = torch.empty_like(f)
-        ws = torch.empty(rtc.rtc_workspace_bytes(rtc.RTC_OP_CONV, 64, 65536, torch.int32), dtype=torch.uint8, device="cuda")
-        med, mn = gpu_ms(lambda: fn(f, g, out=out, ws=ws))
-        po = 64 * 65536 * 65537 // 2
-        r = {"config": "structured", "op": label, "dtype": "int32", "batch": 64, "n": 65536, "gpu_ms": round(med, 4),
-             "gpu_ms_min": round(mn, 4), "pair_ops": po, "equivalent_gpair_ops_per_s": round(po / med / 1e6, 1),
-             "path": f"structured_kernel ({how}); pair_ops is the definition's count, not executed work"}
+    if 1 in configs:
+        # config 1
+        c = wl.config1(seed)
+        product_rows(1, c["f"], c["g"], 1, "int32")
+    if 2 in configs:
+        # config 2
+        c = wl.config2(seed, 1024, 4096)
+        a, b = product_rows(2, c["alpha_u"], c["beta_l"], 1024, "int32")
+        hd = torch.empty(1024, dtype=torch.int32, device="cuda")
+        vd = torch.empty(1024, dtype=torch.int32, device="cuda")
+        hbm_row(2, "max_hdev", lambda: rtc.rtc_max_hdev(a, b, out=hd), 2 * 1024 * 4096 * 4 + 4096, "int32", 1024, 4096)
+        hbm_row(2, "max_vdev", lambda: rtc.rtc_max_vdev(a, b, out=vd), 2 * 1024 * 4096 * 4 + 4096, "int32", 1024, 4096)
+        # sub-additive closure of config 2's arrival curves: ceil(log2(n-1)) = 12 squarings on the GPU; the
+        # oracle forms all n-2 powers by definition (cubic), so it is timed on shorter rows
+        clo = torch.empty_like(a)
+        ws_c = torch.empty(rtc.rtc_workspace_bytes(rtc.RTC_OP_CLOSURE, 1024, 4096, torch.int32), dtype=torch.uint8,
+                           device="cuda")
+        med, mn = gpu_ms(lambda: rtc.rtc_subadditive_closure(a, out=clo, ws=ws_c), warm=1, reps=5)
+        po_c = 12 * 1024 * 4096 * 4097 // 2
+        r = {"config": 2, "op": "subadditive_closure (12 squarings)", "dtype": "int32", "batch": 1024, "n": 4096,
+             "gpu_ms": round(med, 4), "gpu_ms_min": round(mn, 4), "pair_ops": po_c,
+             "gpair_ops_per_s": round(po_c / med / 1e6, 1),
+             "pct_valu_peak_2ops": round(100 * 2 * po_c / (med * 1e-3) / peak_ops, 1)}
+        also_general(r, lambda: rtc.rtc_subadditive_closure(a, out=clo, ws=ws_c), po_c, warm=1, reps=5)
         if with_cpu:
-            sec = cpu_s(lambda: getattr(oracle, ofn)(f_h[:8], g_h[:8]))
-            r.update({"oracle_s": sec, "oracle_rows": 8, "oracle_threads": threads,
-                      "oracle_gpair_ops_per_s": round(8 * 65536 * 65537 / 2 / sec / 1e9, 2)})
-            idx = np.array([0, 1, 777, 40000, 65535])
-            got = out[:8].cpu().numpy()
-            assert np.array_equal(got[:, idx], np.stack([oracle.product_at(f_h[b], g_h[b], idx, "deconv" in ofn)
-                                                         for b in range(8)])), label
+            short = np.ascontiguousarray(c["alpha_u"][:16, :512])
+            sec = cpu_s(lambda: oracle.closure(short))
+            r.update({"oracle_s": sec, "oracle_rows": 16, "oracle_threads": threads,
+                      "oracle_note": "16 rows cut to n=512: the oracle takes all 510 powers of a row, "
+                                     "510 x 512*513/2 pair-ops each row"})
         rows.append(r)
-    # config 4: one component of all 256 chains, then the whole 16-component chain
-    c = wl.config4(seed, 256, 16, 16384)
-    gam, abar = dev(c["gamma_u"]), dev(c["alpha_bar_u"])
-    bu, bl = dev(c["beta_u"]), dev(c["beta_l"])
-    a0 = torch.empty((256, 16384), dtype=torch.int32, device="cuda")
-    B4, N4 = 256, 16384
-    hbm_row(4, "compose", lambda: rtc.rtc_compose(gam, abar, out=a0), B4 * N4 * 12, "int32", B4, N4)
-    au, blo = torch.empty_like(a0), torch.empty_like(a0)
-    au2 = torch.empty_like(a0)
-    evl, evu = torch.empty_like(a0), torch.empty_like(a0)
-    ws = torch.empty(rtc.rtc_workspace_bytes(rtc.RTC_OP_GPC, B4, N4, torch.int32), dtype=torch.uint8, device="cuda")
-    po4 = 2 * B4 * N4 * (N4 + 1) // 2
+    if 3 in configs:
+        # config 3: int64 storage (range-probed 32-bit arithmetic), native int32, and forced 64-bit arithmetic
+        c = wl.config3(seed, 64, 65536)
+        product_rows(3, c["f"], c["g"], 8, "int64 storage, int32 arithmetic")
+        product_rows(3, c["f"].astype(np.int32), c["g"].astype(np.int32), 8, "int32", duals=True)
+        product_rows(3, c["f"][:16] + (1 << 40), c["g"][:16] - (1 << 45), 4, "int64 storage with large offsets (re-based, int32 arithmetic)")
+        # cumulative curves on a fine time base: the same increments on top of a slope of 10^6 per step
+        # (values up to 6.5e10).  Too wide for narrowing by the row minima; with the pair's common slope
+        # removed they are configuration 3's own rows again and take the packed kernels
+        ramp = np.arange(65536, dtype=np.int64)
+        product_rows(3, c["f"][:16] + 1000003 * ramp, c["g"][:16] + 999983 * ramp, 4,
+                     "int64 storage, slope 10^6 per step (common slope removed, int32 / packed arithmetic)")
+        # values spanning 2^40: beyond the row-level narrowing, but slowly varying, so the chunks are
+        # re-based and reduced in 32-bit arithmetic; then the same rows with that path off (64-bit kernel)
+        product_rows(3, c["f"][:16] * 4096, c["g"][:16] * 4096, 4,
+                     "int64 storage, value range beyond 2^30 (common slope removed, int32 arithmetic)")
+        for mode, label in ((1, "int64 storage (the same rows, 32-bit arithmetic re-based per chunk)"),
+                            (0, "int64 arithmetic (the same rows, 64-bit kernel)")):
+            rtc.rtc_set_rebase_wide(mode)
+            try:
+                product_rows(3, c["f"][:16] * 4096, c["g"][:16] * 4096, 0, label)
+            finally:
+                rtc.rtc_set_rebase_wide(2)
+        # rows of exploitable convexity at the headline shape: token buckets (concave) and rate-latency
+        # curves (convex); the library detects them on the device and evaluates 2 or 2*log2(n) candidates
+        # per output instead of all of them, so the rate below is an equivalent, not executed work
+        rs = np.random.default_rng(seed)
+        tb = np.stack([wl.token_bucket(65536, int(rs.integers(100, 5000)), int(rs.integers(1, 40)), np.int32, at_zero=False)
+                       for _ in range(64)])
+        tb2 = np.stack([wl.token_bucket(65536, int(rs.integers(100, 5000)), int(rs.integers(1, 40)), np.int32, at_zero=False)
+                        for _ in range(64)])
+        rl = np.stack([wl.rate_latency(65536, int(rs.integers(2, 60)), int(rs.integers(0, 3000)), np.int32) for _ in range(64)])
+        rl2 = np.stack([wl.rate_latency(65536, int(rs.integers(2, 60)), int(rs.integers(0, 3000)), np.int32) for _ in range(64)])
+        arb = c["f"].astype(np.int32)
+        for label, fn, ofn, f_h, g_h, how in (
+                ("minplus_conv token-bucket x token-bucket", rtc.rtc_minplus_conv, "minplus_conv", tb, tb2, "ends"),
+                ("minplus_conv rate-latency x rate-latency", rtc.rtc_minplus_conv, "minplus_conv", rl, rl2, "bisection"),
+                ("maxplus_deconv token-bucket / rate-latency", rtc.rtc_maxplus_deconv, "maxplus_deconv", tb, rl, "bisection"),
+                # one operand of the right shape only: the configuration's own arbitrary curves against
+                # rate-latency service / from token-bucket arrivals
+                ("minplus_conv arbitrary x rate-latency", rtc.rtc_minplus_conv, "minplus_conv", arb, rl, "anchors + brackets"),
+                ("minplus_conv rate-latency x arbitrary", rtc.rtc_minplus_conv, "minplus_conv", rl, arb, "anchors + brackets, operands exchanged"),
+                ("maxplus_deconv token-bucket / arbitrary", rtc.rtc_maxplus_deconv, "maxplus_deconv", tb, arb, "anchors + brackets")):
+            f, g = dev(f_h), dev(g_h)
+            out = torch.empty_like(f)
+            ws = torch.empty(rtc.rtc_workspace_bytes(rtc.RTC_OP_CONV, 64, 65536, torch.int32), dtype=torch.uint8, device="cuda")
+            med, mn = gpu_ms(lambda: fn(f, g, out=out, ws=ws))
+            po = 64 * 65536 * 65537 // 2
+            r = {"config": "structured", "op": label, "dtype": "int32", "batch": 64, "n": 65536, "gpu_ms": round(med, 4),
+                 "gpu_ms_min": round(mn, 4), "pair_ops": po, "equivalent_gpair_ops_per_s": round(po / med / 1e6, 1),
+                 "path": f"structured_kernel ({how}); pair_ops is the definition's count, not executed work"}
+            if with_cpu:
+                sec = cpu_s(lambda: getattr(oracle, ofn)(f_h[:8], g_h[:8]))
+                r.update({"oracle_s": sec, "oracle_rows": 8, "oracle_threads": threads,
+                          "oracle_gpair_ops_per_s": round(8 * 65536 * 65537 / 2 / sec / 1e9, 2)})
+                idx = np.array([0, 1, 777, 40000, 65535])
+                got = out[:8].cpu().numpy()
+                assert np.array_equal(got[:, idx], np.stack([oracle.product_at(f_h[b], g_h[b], idx, "deconv" in ofn)
+                                                             for b in range(8)])), label
+            rows.append(r)
+    if 4 in configs:
+        # config 4: one component of all 256 chains, then the whole 16-component chain
+        c = wl.config4(seed, 256, 16, 16384)
+        gam, abar = dev(c["gamma_u"]), dev(c["alpha_bar_u"])
+        bu, bl = dev(c["beta_u"]), dev(c["beta_l"])
+        a0 = torch.empty((256, 16384), dtype=torch.int32, device="cuda")
+        B4, N4 = 256, 16384
+        hbm_row(4, "compose", lambda: rtc.rtc_compose(gam, abar, out=a0), B4 * N4 * 12, "int32", B4, N4)
+        au, blo = torch.empty_like(a0), torch.empty_like(a0)
+        au2 = torch.empty_like(a0)
+        evl, evu = torch.empty_like(a0), torch.empty_like(a0)
+        ws = torch.empty(rtc.rtc_workspace_bytes(rtc.RTC_OP_GPC, B4, N4, torch.int32), dtype=torch.uint8, device="cuda")
+        po4 = 2 * B4 * N4 * (N4 + 1) // 2
 
-    def one_component():
-        rtc.rtc_gpc_step(a0, bu[0], bl[0], alpha_u_out=au, beta_l_out=blo, gamma_u=gam, events_lower=evl,
-                         events_upper=evu, ws=ws)
+        def one_component():
+            rtc.rtc_gpc_step(a0, bu[0], bl[0], alpha_u_out=au, beta_l_out=blo, gamma_u=gam, events_lower=evl,
+                             events_upper=evu, ws=ws)
 
-    def whole_chain():
-        src = a0
-        for i in range(16):
-            dst = au if i % 2 == 0 else au2
-            rtc.rtc_gpc_step(src, bu[i], bl[i], alpha_u_out=dst, beta_l_out=blo, gamma_u=gam,
-                             events_lower=evl, events_upper=evu, ws=ws)
-            src = dst
+        def whole_chain():
+            src = a0
+            for i in range(16):
+                dst = au if i % 2 == 0 else au2
+                rtc.rtc_gpc_step(src, bu[i], bl[i], alpha_u_out=dst, beta_l_out=blo, gamma_u=gam,
+                                 events_lower=evl, events_upper=evu, ws=ws)
+                src = dst
 
-    med, mn = gpu_ms(one_component)
-    r = {"config": 4, "op": "gpc_step (1 component, 256 chains)", "dtype": "int32", "batch": B4, "n": N4,
-         "gpu_ms": round(med, 4), "gpu_ms_min": round(mn, 4), "pair_ops": po4,
-         "gpair_ops_per_s": round(po4 / med / 1e6, 1),
-         "pct_valu_peak_2ops": round(100 * 2 * po4 / (med * 1e-3) / peak_ops, 1)}
-    also_general(r, one_component, po4)
-    if with_cpu:
-        a0_h = oracle.compose(c["gamma_u"][:16], c["alpha_bar_u"][:16])[0]
-        sec = cpu_s(lambda: oracle.gpc_step(a0_h, c["beta_u"][0][:16], c["beta_l"][0][:16]))
-        r.update({"oracle_s": sec, "oracle_rows": 16, "oracle_threads": threads,
-                  "oracle_gpair_ops_per_s": round(2 * 16 * N4 * (N4 + 1) / 2 / sec / 1e9, 2),
-                  "oracle_note": "first 16 of 256 chains, one component; the full configuration is 256 x 16 of these"})
-    rows.append(r)
-    med, mn = gpu_ms(whole_chain, warm=1, reps=5)
-    r = {"config": 4, "op": "16-component chain, 256 chains", "dtype": "int32", "batch": B4, "n": N4,
-         "gpu_ms": round(med, 3), "gpu_ms_min": round(mn, 3), "pair_ops": 16 * po4,
-         "gpair_ops_per_s": round(16 * po4 / med / 1e6, 1),
-         "pct_valu_peak_2ops": round(100 * 2 * 16 * po4 / (med * 1e-3) / peak_ops, 1)}
-    also_general(r, whole_chain, 16 * po4, warm=1, reps=5)
-    rows.append(r)
-    # concatenated service curve of the chain: beta^l_1 (x) ... (x) beta^l_16, 15 products
-    cat = torch.empty_like(a0)
-    ws_k = torch.empty(rtc.rtc_workspace_bytes(rtc.RTC_OP_CHAIN, B4, N4, torch.int32), dtype=torch.uint8,
-                       device="cuda")
-    med, mn = gpu_ms(lambda: rtc.rtc_conv_chain(bl, out=cat, ws=ws_k), warm=1, reps=5)
-    po_k = 15 * B4 * N4 * (N4 + 1) // 2
-    r = {"config": 4, "op": "conv_chain (16 service curves, 15 products)", "dtype": "int32", "batch": B4, "n": N4,
-         "gpu_ms": round(med, 3), "gpu_ms_min": round(mn, 3), "pair_ops": po_k,
-         "gpair_ops_per_s": round(po_k / med / 1e6, 1),
-         "pct_valu_peak_2ops": round(100 * 2 * po_k / (med * 1e-3) / peak_ops, 1)}
-    also_general(r, lambda: rtc.rtc_conv_chain(bl, out=cat, ws=ws_k), po_k, warm=1, reps=5)
-    if with_cpu:
-        few = np.ascontiguousarray(c["beta_l"][:, :4])
-        sec = cpu_s(lambda: oracle.conv_chain(few))
-        r.update({"oracle_s": sec, "oracle_rows": 4, "oracle_threads": threads,
-                  "oracle_gpair_ops_per_s": round(15 * 4 * N4 * (N4 + 1) / 2 / sec / 1e9, 2),
-                  "oracle_note": "first 4 of 256 chains"})
-    rows.append(r)
-    hbm_row(4, "pseudo_inverse lower (gamma_u at beta'_l)", lambda: rtc.rtc_pseudo_inverse(gam, blo, 0, out=evl),
-            B4 * N4 * 12, "int32", B4, N4)
-    # config 5
-    c = wl.config5(seed, 262144)
-    f, g = product_rows(5, c["f"], c["g"], 1, "float64")
-    x = dev(c["x"])
-    inv = torch.empty((1, 262144), dtype=torch.int32, device="cuda")
-    for mode, nm in ((0, "lower"), (1, "upper")):
-        hbm_row(5, f"pseudo_inverse {nm}", lambda: rtc.rtc_pseudo_inverse(f, x, mode, out=inv), 262144 * 20,
-                "float64", 1, 262144)
+        med, mn = gpu_ms(one_component)
+        r = {"config": 4, "op": "gpc_step (1 component, 256 chains)", "dtype": "int32", "batch": B4, "n": N4,
+             "gpu_ms": round(med, 4), "gpu_ms_min": round(mn, 4), "pair_ops": po4,
+             "gpair_ops_per_s": round(po4 / med / 1e6, 1),
+             "pct_valu_peak_2ops": round(100 * 2 * po4 / (med * 1e-3) / peak_ops, 1)}
+        also_general(r, one_component, po4)
+        if with_cpu:
+            a0_h = oracle.compose(c["gamma_u"][:16], c["alpha_bar_u"][:16])[0]
+            sec = cpu_s(lambda: oracle.gpc_step(a0_h, c["beta_u"][0][:16], c["beta_l"][0][:16]))
+            r.update({"oracle_s": sec, "oracle_rows": 16, "oracle_threads": threads,
+                      "oracle_gpair_ops_per_s": round(2 * 16 * N4 * (N4 + 1) / 2 / sec / 1e9, 2),
+                      "oracle_note": "first 16 of 256 chains, one component; the full configuration is 256 x 16 of these"})
+        rows.append(r)
+        med, mn = gpu_ms(whole_chain, warm=1, reps=5)
+        r = {"config": 4, "op": "16-component chain, 256 chains", "dtype": "int32", "batch": B4, "n": N4,
+             "gpu_ms": round(med, 3), "gpu_ms_min": round(mn, 3), "pair_ops": 16 * po4,
+             "gpair_ops_per_s": round(16 * po4 / med / 1e6, 1),
+             "pct_valu_peak_2ops": round(100 * 2 * 16 * po4 / (med * 1e-3) / peak_ops, 1)}
+        also_general(r, whole_chain, 16 * po4, warm=1, reps=5)
+        rows.append(r)
+        # concatenated service curve of the chain: beta^l_1 (x) ... (x) beta^l_16, 15 products
+        cat = torch.empty_like(a0)
+        ws_k = torch.empty(rtc.rtc_workspace_bytes(rtc.RTC_OP_CHAIN, B4, N4, torch.int32), dtype=torch.uint8,
+                           device="cuda")
+        med, mn = gpu_ms(lambda: rtc.rtc_conv_chain(bl, out=cat, ws=ws_k), warm=1, reps=5)
+        po_k = 15 * B4 * N4 * (N4 + 1) // 2
+        r = {"config": 4, "op": "conv_chain (16 service curves, 15 products)", "dtype": "int32", "batch": B4, "n": N4,
+             "gpu_ms": round(med, 3), "gpu_ms_min": round(mn, 3), "pair_ops": po_k,
+             "gpair_ops_per_s": round(po_k / med / 1e6, 1),
+             "pct_valu_peak_2ops": round(100 * 2 * po_k / (med * 1e-3) / peak_ops, 1)}
+        also_general(r, lambda: rtc.rtc_conv_chain(bl, out=cat, ws=ws_k), po_k, warm=1, reps=5)
+        if with_cpu:
+            few = np.ascontiguousarray(c["beta_l"][:, :4])
+            sec = cpu_s(lambda: oracle.conv_chain(few))
+            r.update({"oracle_s": sec, "oracle_rows": 4, "oracle_threads": threads,
+                      "oracle_gpair_ops_per_s": round(15 * 4 * N4 * (N4 + 1) / 2 / sec / 1e9, 2),
+                      "oracle_note": "first 4 of 256 chains"})
+        rows.append(r)
+        hbm_row(4, "pseudo_inverse lower (gamma_u at beta'_l)", lambda: rtc.rtc_pseudo_inverse(gam, blo, 0, out=evl),
+                B4 * N4 * 12, "int32", B4, N4)
+    if 5 in configs:
+        # config 5
+        c = wl.config5(seed, 262144)
+        f, g = product_rows(5, c["f"], c["g"], 1, "float64")
+        x = dev(c["x"])
+        inv = torch.empty((1, 262144), dtype=torch.int32, device="cuda")
+        for mode, nm in ((0, "lower"), (1, "upper")):
+            hbm_row(5, f"pseudo_inverse {nm}", lambda: rtc.rtc_pseudo_inverse(f, x, mode, out=inv), 262144 * 20,
+                    "float64", 1, 262144)
     return rows
 
 
@@ -668,7 +675,8 @@ def main():
         "roofline": roofline, "cpu_baseline": cpu_baseline, "parity": parity,
     }
     if args.all_configs:
-        line["per_config"] = per_config_table(seed, peak_ops, args.cpu_seconds > 0)
+        wanted = tuple(int(k) for k in args.configs.split(",")) if args.configs else (1, 2, 3, 4, 5)
+        line["per_config"] = per_config_table(seed, peak_ops, args.cpu_seconds > 0, wanted)
     print(json.dumps(line))
     if parity == "MISMATCH":
         sys.exit(1)
