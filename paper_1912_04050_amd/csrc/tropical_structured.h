@@ -51,8 +51,10 @@ __device__ __forceinline__ void bracket_anchor_body(const T* __restrict__ f, int
   if (coarse != nullptr) {
     const int32_t* cs = coarse + (int64_t)row * coarse_anchors + min(t / kBracketCoarse, coarse_anchors - 2);
     const int ja = cs[0], jb = cs[1];            // optima of the coarse anchors below and above t
-    lo = op_sub(OP) ? jb : ja;
-    hi = min(op_sub(OP) ? ja : jb, m);
+    // (clamped: with exact sums 0 <= lo <= hi <= m holds by monotonicity; rows that break the
+    // API's no-overflow precondition must still index inside the row)
+    lo = min(max(op_sub(OP) ? jb : ja, 0), m);
+    hi = max(min(op_sub(OP) ? ja : jb, m), lo);
   }
   T best = Semiring<T, OP>::identity();
   int best_j = kNone;
@@ -465,7 +467,7 @@ __global__ __launch_bounds__(256) void structured_kernel(const T* __restrict__ f
   } else if (code >= kSelBracket) {
     const int32_t* js = jstar + (int64_t)row * bracket_anchors(n, kBracketFine) + t / kBracketFine;
     const int ja = js[0], jb = js[1];            // optima of the fine anchors below and above t
-    const int lo = op_sub(OP) ? jb : ja;
+    const int lo = min(max(op_sub(OP) ? jb : ja, 0), m);     // clamped as in bracket_anchor_body
     const int hi = min(op_sub(OP) ? ja : jb, m);
     v = c(lo);
 #pragma unroll 4
