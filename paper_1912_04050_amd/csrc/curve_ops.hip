@@ -39,17 +39,110 @@ __device__ __forceinline__ int upper_index(const T* __restrict__ f, int n, T x) 
   return lo - 1;
 }
 
+// ---- searches of a whole workgroup's queries through a window of the curve in LDS ----------
+// A binary search in HBM / L2 is a chain of ~log2(n) dependent loads.  The queries of one
+// workgroup (consecutive samples of another curve) mostly fall into a short stretch of f, so:
+// the wavefronts 0 and 1 locate the answers of the smallest and of the largest query with a
+// 64-ary search (three dependent loads for n = 65536), the stretch between them is staged in
+// LDS, and every query is searched there.  A stretch longer than the window (queries that are
+// not clustered) falls back to the plain search per thread.  Both give the answer of the plain
+// search for every nondecreasing f.
+constexpr int kSearchWindow = 2048;    // samples of f staged per workgroup
+constexpr int kSearchPerThread = 4;    // queries per thread
+constexpr int kSearchPerBlock = 256 * kSearchPerThread;
+
+// Whether f[k] lies beyond the query: LOWER counts the samples < x (the first index with
+// f[k] >= x is their number), UPPER the samples <= x (the last index with f[k] <= x is their
+// number - 1).
+template <typename T> __device__ __forceinline__ bool beyond(T fk, T x, bool upper) { return upper ? fk > x : fk >= x; }
+
+// First index in [0, n) at which pred turns true (n if it never does); pred nondecreasing in
+// the index.  All 64 lanes of the wavefront take part: each round probes 64 evenly spaced
+// positions and keeps the stretch between the last false and the first true one.
+template <typename Pred>
+__device__ __forceinline__ int wave_first_true(int n, Pred pred) {
+  const int lane = threadIdx.x & 63;
+  int lo = 0, hi = n;
+  while (hi > lo) {
+    const int width = hi - lo, step = (width + 63) >> 6;
+    const int p = lo + min((lane + 1) * step, width) - 1;
+    const uint64_t b = __ballot(pred(p));
+    if (b == 0) { lo = hi; break; }
+    const int first = __builtin_ctzll(b);
+    hi = lo + min((first + 1) * step, width) - 1;
+    lo = lo + first * step;
+  }
+  return lo;
+}
+
+// Number of samples of fr[0, n) not beyond each of the calling workgroup's (256 threads)
+// queries xv[0 .. kSearchPerThread), in cnt[]: for every thread, whether its queries are real
+// or repeats of a real one.  s_win: kSearchWindow values of LDS.
+template <typename T>
+__device__ __forceinline__ void windowed_counts(const T* __restrict__ fr, int n, const T (&xv)[kSearchPerThread],
+                                                bool upper, T* s_win, int (&cnt)[kSearchPerThread]) {
+  __shared__ T s_mm[2][4];
+  __shared__ int s_ab[2];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  T xmin = xv[0], xmax = xv[0];
+#pragma unroll
+  for (int e = 1; e < kSearchPerThread; ++e) { xmin = xv[e] < xmin ? xv[e] : xmin; xmax = vmax(xmax, xv[e]); }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const T a = __shfl_xor(xmin, off), b = __shfl_xor(xmax, off);
+    xmin = a < xmin ? a : xmin; xmax = vmax(xmax, b);
+  }
+  if (lane == 0) { s_mm[0][wave] = xmin; s_mm[1][wave] = xmax; }
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < 4; ++w) { xmin = s_mm[0][w] < xmin ? s_mm[0][w] : xmin; xmax = vmax(xmax, s_mm[1][w]); }
+  if (wave < 2) {
+    const T q = wave == 0 ? xmin : xmax;
+    const int at = wave_first_true(n, [&](int k) { return beyond(fr[k], q, upper); });
+    if (lane == 0) s_ab[wave] = at;
+  }
+  __syncthreads();
+  const int a = s_ab[0], len = s_ab[1] - a;
+  if (len >= 0 && len <= kSearchWindow) {
+#pragma unroll 4
+    for (int i = threadIdx.x; i < len; i += 256) s_win[i] = fr[a + i];
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < kSearchPerThread; ++e) {
+      int lo = 0, hi = len;
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (beyond(s_win[mid], xv[e], upper)) hi = mid; else lo = mid + 1;
+      }
+      cnt[e] = a + lo;
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < kSearchPerThread; ++e) cnt[e] = upper ? upper_index(fr, n, xv[e]) + 1 : lower_index(fr, n, xv[e]);
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void pinv_kernel(const T* __restrict__ f, int n,
                                                    const T* __restrict__ x, int m,
                                                    int32_t* __restrict__ out, int blocks_per_row,
                                                    int mode) {
+  __shared__ T s_win[kSearchWindow];
   const int row = blockIdx.x / blocks_per_row;
-  const int j = (blockIdx.x % blocks_per_row) * 256 + threadIdx.x;
-  if (j >= m) return;
+  const int base = (blockIdx.x % blocks_per_row) * kSearchPerBlock;
   const T* fr = f + (int64_t)row * n;
-  const T xv = x[(int64_t)row * m + j];
-  out[(int64_t)row * m + j] = mode == RTC_INV_LOWER ? lower_index(fr, n, xv) : upper_index(fr, n, xv);
+  const bool upper = mode != RTC_INV_LOWER;
+  T xv[kSearchPerThread];
+#pragma unroll
+  for (int e = 0; e < kSearchPerThread; ++e)      // past the end: the last query again
+    xv[e] = x[(int64_t)row * m + min(base + e * 256 + (int)threadIdx.x, m - 1)];
+  int cnt[kSearchPerThread];
+  windowed_counts(fr, n, xv, upper, s_win, cnt);
+#pragma unroll
+  for (int e = 0; e < kSearchPerThread; ++e) {
+    const int j = base + e * 256 + threadIdx.x;
+    if (j < m) out[(int64_t)row * m + j] = upper ? cnt[e] - 1 : cnt[e];
+  }
 }
 
 template <typename T>
@@ -191,19 +284,26 @@ __global__ __launch_bounds__(256) void hdev_kernel(const T* __restrict__ alpha,
                                                    const T* __restrict__ beta, int32_t* __restrict__ out,
                                                    int n, int blocks_per_row,
                                                    int32_t* __restrict__ dev_flags) {
+  static_assert(kDevPerThread == kSearchPerThread, "the deviation kernels search kSearchPerThread samples per thread");
+  __shared__ T s_win[kSearchWindow];
   __shared__ int32_t red[4];
   __shared__ int32_t unb[4];
   const int row = blockIdx.x / blocks_per_row;
   const int base = (blockIdx.x % blocks_per_row) * kDevPerBlock;
   const T* a = alpha + (int64_t)row * n;
   const T* b = beta + (int64_t)row * n;
+  T xv[kSearchPerThread];
+#pragma unroll
+  for (int e = 0; e < kDevPerThread; ++e) xv[e] = a[min(base + e * 256 + (int)threadIdx.x, n - 1)];   // past the end: the last sample again
+  int cnt[kSearchPerThread];
+  windowed_counts(b, n, xv, false, s_win, cnt);
   int32_t h = 0;
   bool unbounded = false;
 #pragma unroll
   for (int e = 0; e < kDevPerThread; ++e) {
     const int d = base + e * 256 + threadIdx.x;
     if (d < n) {
-      const int k = lower_index(b, n, a[d]);
+      const int k = cnt[e];
       unbounded |= (k == n);
       h = max(h, k - d);
     }
@@ -271,7 +371,7 @@ __global__ __launch_bounds__(256) void copy_kernel(const T* __restrict__ src, T*
 template <typename T>
 int pinv_typed(const void* f, int64_t n, const void* x, int64_t m, int32_t* out, int64_t batch, int mode,
                hipStream_t stream) {
-  const int64_t bpr = (m + 255) / 256;
+  const int64_t bpr = (m + kSearchPerBlock - 1) / kSearchPerBlock;
   if (bpr * batch > 0x7fffffffLL) return RTC_ERR_SHAPE;
   hipLaunchKernelGGL(pinv_kernel<T>, dim3((uint32_t)(bpr * batch)), dim3(256), 0, stream,
                      static_cast<const T*>(f), (int)n, static_cast<const T*>(x), (int)m, out, (int)bpr, mode);
