@@ -267,7 +267,7 @@ int run_packed(const int32_t* f32, int64_t stride_f, const int32_t* g32, int64_t
                      const_cast<int32_t*>(aux.ab_s), const_cast<int32_t*>(aux.ar_s), (int)L.nsub,
                      const_cast<int32_t*>(aux.bd), const_cast<int32_t*>(aux.ab), const_cast<int32_t*>(aux.ar),
                      const_cast<int32_t*>(aux.bmn), const_cast<int32_t*>(aux.bmx));
-  hipLaunchKernelGGL(decide_kernel, dim3((uint32_t)batch), dim3(256), 0, stream, aux, (int)n,
+  hipLaunchKernelGGL(decide_kernel, dim3((uint32_t)batch), dim3(kDecideThreads), 0, stream, aux, (int)n,
                      const_cast<int32_t*>(aux.pack_ok));
   // short rows: tiles of 1024 outputs halve the candidates wasted on the diagonal
   const bool small_tiles = n <= g_packed_small_n;

@@ -468,13 +468,15 @@ __global__ __launch_bounds__(1024) void prep_kernel(const int32_t* __restrict__ 
 // unpackable row is better left to the 32-bit kernel alone.
 constexpr int kDecideSide = 32;   // sampled tiles x sampled chunks per tile
 
-__global__ __launch_bounds__(256) void decide_kernel(PackAux x, int n, int32_t* __restrict__ pack_ok) {
-  __shared__ float s_yes[4], s_all[4];
+constexpr int kDecideThreads = kDecideSide * kDecideSide;   // one sample per thread: one chain of dependent loads
+
+__global__ __launch_bounds__(kDecideThreads) void decide_kernel(PackAux x, int n, int32_t* __restrict__ pack_ok) {
+  __shared__ float s_yes[kDecideThreads / 64], s_all[kDecideThreads / 64];
   const int row = blockIdx.x;
   const int n_t2 = (n + kPkW - 1) / kPkW;
   float yes = 0.f, all = 0.f;
   if (pack_ok[row] != 0) {
-    for (int j = threadIdx.x; j < kDecideSide * kDecideSide; j += 256) {
+    for (int j = threadIdx.x; j < kDecideSide * kDecideSide; j += kDecideThreads) {
       const int it = j / kDecideSide, ic = j % kDecideSide;
       const int nt = min(n_t2, kDecideSide);
       if (it >= nt) continue;
@@ -494,8 +496,8 @@ __global__ __launch_bounds__(256) void decide_kernel(PackAux x, int n, int32_t* 
   if ((threadIdx.x & 63) == 0) { s_yes[threadIdx.x >> 6] = yes; s_all[threadIdx.x >> 6] = all; }
   __syncthreads();
   if (threadIdx.x == 0) {
-    yes = s_yes[0] + s_yes[1] + s_yes[2] + s_yes[3];
-    all = s_all[0] + s_all[1] + s_all[2] + s_all[3];
+    yes = all = 0.f;
+    for (int w = 0; w < kDecideThreads / 64; ++w) { yes += s_yes[w]; all += s_all[w]; }
     if (2.f * yes < all) pack_ok[row] = 0;
   }
 }
