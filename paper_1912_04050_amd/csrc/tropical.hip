@@ -260,7 +260,7 @@ int run_packed(const int32_t* f32, int64_t stride_f, const int32_t* g32, int64_t
   aux.nblk = (int32_t)L.nblk;
   if (batch * L.nchunk > 0x7fffffffLL) return RTC_ERR_SHAPE;
   // uniform operand: f for the convolution, g for the deconvolution; window operand: the other
-  hipLaunchKernelGGL(prep_kernel, dim3((uint32_t)(batch * L.nchunk)), dim3(1024), 0, stream,
+  hipLaunchKernelGGL(prep_kernel, dim3((uint32_t)(batch * L.nchunk)), dim3(kPrepThreads), 0, stream,
                      op_sub(OP) ? g32 : f32, op_sub(OP) ? stride_g : stride_f, op_sub(OP) ? f32 : g32,
                      op_sub(OP) ? stride_f : stride_g, (int)n, op_sub(OP), op_sub(OP) != op_max(OP), (int)L.npad, (int)L.nchunk, (int)L.nblk,
                      aux.rho, aux.pack_ok, const_cast<uint32_t*>(aux.apk), const_cast<uint32_t*>(aux.apk_s),

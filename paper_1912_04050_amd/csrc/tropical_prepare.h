@@ -400,65 +400,84 @@ __device__ __forceinline__ int32_t wave_max(int32_t v) {
 // (a = uniform operand, b = window operand, stored in window-index order, i.e. reversed for the
 // deconvolution), re-bases the chunk of a to its minimum and packs it into both halves, and
 // records the chunk range of a and the minima / maxima of b per block of 256.
-__global__ __launch_bounds__(1024) void prep_kernel(const int32_t* __restrict__ a, int64_t stride_a,
-                                                    const int32_t* __restrict__ b, int64_t stride_b, int n,
-                                                    bool deconv, bool neg, int npad, int nchunk, int nblk,
-                                                    const int32_t* __restrict__ rho,
-                                                    const int32_t* __restrict__ pack_ok,
-                                                    uint32_t* __restrict__ apk, uint32_t* __restrict__ apk_s,
-                                                    int32_t* __restrict__ ab_s, int32_t* __restrict__ ar_s,
-                                                    int nsub, int32_t* __restrict__ bd, int32_t* __restrict__ ab,
-                                                    int32_t* __restrict__ ar, int32_t* __restrict__ bmn,
-                                                    int32_t* __restrict__ bmx) {
-  __shared__ int32_t s_amn[16], s_amx[16], s_bmn[16], s_bmx[16];
+constexpr int kPrepThreads = 256;      // per chunk of kPkChunk indices: kPkChunk / kPrepThreads = 4 per thread, 256 apart
+__global__ __launch_bounds__(kPrepThreads) void prep_kernel(const int32_t* __restrict__ a, int64_t stride_a,
+                                                            const int32_t* __restrict__ b, int64_t stride_b, int n,
+                                                            bool deconv, bool neg, int npad, int nchunk, int nblk,
+                                                            const int32_t* __restrict__ rho,
+                                                            const int32_t* __restrict__ pack_ok,
+                                                            uint32_t* __restrict__ apk, uint32_t* __restrict__ apk_s,
+                                                            int32_t* __restrict__ ab_s, int32_t* __restrict__ ar_s,
+                                                            int nsub, int32_t* __restrict__ bd, int32_t* __restrict__ ab,
+                                                            int32_t* __restrict__ ar, int32_t* __restrict__ bmn,
+                                                            int32_t* __restrict__ bmx) {
+  constexpr int kPer = kPkChunk / kPrepThreads;
+  static_assert(kPer * kPrepThreads == kPkChunk && kPrepThreads == kPkBlock && kPkSub == 128,
+                "element k * 256 + t of the chunk: block k, sub-chunk 2k + t / 128, group of 64 number 4k + t / 64");
+  __shared__ int32_t s_amn[16], s_amx[16], s_bmn[16], s_bmx[16];    // per group of 64 indices of the chunk
   const int row = blockIdx.x / nchunk;
   if (pack_ok[row] == 0) return;   // nothing of this row will be read
   const int c = blockIdx.x % nchunk;
-  const int i = c * kPkChunk + threadIdx.x;
   const int32_t r = rho[row];
-  const bool valid = i < n;
-  int32_t adv = valid ? wrap_sub(a[(int64_t)row * stride_a + i], r * i) : 0;
-  if (neg) adv = wrap_sub(0, adv);   // max-plus convolution / min-plus deconvolution: see packed_body
-  // positions beyond the row's end are packed as 0: every window position that meets them is
-  // poison, which decides the outcome whatever the uniform value
-  int32_t bdv = 0;
-  if (valid) bdv = deconv ? wrap_add(b[(int64_t)row * stride_b + (n - 1 - i)], r * i)
-                          : wrap_sub(b[(int64_t)row * stride_b + i], r * i);
-  const int32_t amn = wave_min(valid ? adv : INT32_MAX), amx = wave_max(valid ? adv : INT32_MIN);
-  const int32_t bmn_w = wave_min(valid ? bdv : INT32_MAX), bmx_w = wave_max(valid ? bdv : INT32_MIN);
   const int wave = threadIdx.x >> 6;
-  if ((threadIdx.x & 63) == 0) { s_amn[wave] = amn; s_amx[wave] = amx; s_bmn[wave] = bmn_w; s_bmx[wave] = bmx_w; }
+  int32_t adv[kPer], bdv[kPer];
+#pragma unroll
+  for (int k = 0; k < kPer; ++k) {
+    const int i = c * kPkChunk + k * kPrepThreads + threadIdx.x;
+    const bool valid = i < n;
+    adv[k] = valid ? wrap_sub(a[(int64_t)row * stride_a + i], r * i) : 0;
+    if (neg) adv[k] = wrap_sub(0, adv[k]);   // max-plus convolution / min-plus deconvolution: see packed_body
+    // positions beyond the row's end are packed as 0: every window position that meets them is
+    // poison, which decides the outcome whatever the uniform value
+    bdv[k] = 0;
+    if (valid) bdv[k] = deconv ? wrap_add(b[(int64_t)row * stride_b + (n - 1 - i)], r * i)
+                               : wrap_sub(b[(int64_t)row * stride_b + i], r * i);
+  }
+#pragma unroll
+  for (int k = 0; k < kPer; ++k) {
+    const bool valid = c * kPkChunk + k * kPrepThreads + (int)threadIdx.x < n;
+    const int32_t amn = wave_min(valid ? adv[k] : INT32_MAX), amx = wave_max(valid ? adv[k] : INT32_MIN);
+    const int32_t bmn_w = wave_min(valid ? bdv[k] : INT32_MAX), bmx_w = wave_max(valid ? bdv[k] : INT32_MIN);
+    if ((threadIdx.x & 63) == 0) {
+      s_amn[4 * k + wave] = amn; s_amx[4 * k + wave] = amx; s_bmn[4 * k + wave] = bmn_w; s_bmx[4 * k + wave] = bmx_w;
+    }
+  }
   __syncthreads();
   int32_t cmn = INT32_MAX, cmx = INT32_MIN;
 #pragma unroll
   for (int w = 0; w < 16; ++w) { cmn = min(cmn, s_amn[w]); cmx = max(cmx, s_amx[w]); }
-  apk[(int64_t)row * npad + i] = valid ? min((uint32_t)adv - (uint32_t)cmn, kPkPoison) * 0x10001u : 0u;
-  // sub-chunk of 128 indices = 2 waves
-  const int sub = threadIdx.x / kPkSub;
-  const int32_t smn = min(s_amn[2 * sub], s_amn[2 * sub + 1]);
-  const int32_t smx = max(s_amx[2 * sub], s_amx[2 * sub + 1]);
-  apk_s[(int64_t)row * npad + i] = valid ? min((uint32_t)adv - (uint32_t)smn, kPkPoison) * 0x10001u : 0u;
-  if ((threadIdx.x & (kPkSub - 1)) == 0) {
-    const bool any = smx >= smn;   // false when the sub-chunk lies entirely beyond n
-    const int64_t range = (int64_t)smx - (int64_t)smn;
-    ab_s[(int64_t)row * nsub + c * kPkSubs + sub] = any ? smn : 0;
-    ar_s[(int64_t)row * nsub + c * kPkSubs + sub] = any ? (int32_t)(range < 0x7fffffffLL ? range : 0x7fffffffLL) : 0;
+#pragma unroll
+  for (int k = 0; k < kPer; ++k) {
+    const int i = c * kPkChunk + k * kPrepThreads + threadIdx.x;
+    const bool valid = i < n;
+    apk[(int64_t)row * npad + i] = valid ? min((uint32_t)adv[k] - (uint32_t)cmn, kPkPoison) * 0x10001u : 0u;
+    // sub-chunk of 128 indices = 2 groups of 64
+    const int sub = 2 * k + (threadIdx.x >> 7);
+    const int32_t smn = min(s_amn[2 * sub], s_amn[2 * sub + 1]);
+    const int32_t smx = max(s_amx[2 * sub], s_amx[2 * sub + 1]);
+    apk_s[(int64_t)row * npad + i] = valid ? min((uint32_t)adv[k] - (uint32_t)smn, kPkPoison) * 0x10001u : 0u;
+    if ((threadIdx.x & (kPkSub - 1)) == 0) {
+      const bool any = smx >= smn;   // false when the sub-chunk lies entirely beyond n
+      const int64_t range = (int64_t)smx - (int64_t)smn;
+      ab_s[(int64_t)row * nsub + c * kPkSubs + sub] = any ? smn : 0;
+      ar_s[(int64_t)row * nsub + c * kPkSubs + sub] = any ? (int32_t)(range < 0x7fffffffLL ? range : 0x7fffffffLL) : 0;
+    }
+    if (valid) bd[(int64_t)row * n + i] = bdv[k];
+    if (threadIdx.x == 0) {        // block k of 256 indices
+      const int j = c * (kPkChunk / kPkBlock) + k;
+      if (j < nblk) {
+        int32_t mn = INT32_MAX, mx = INT32_MIN;
+#pragma unroll
+        for (int w = 0; w < kPkBlock / 64; ++w) { mn = min(mn, s_bmn[4 * k + w]); mx = max(mx, s_bmx[4 * k + w]); }
+        bmn[(int64_t)row * nblk + j] = mn;
+        bmx[(int64_t)row * nblk + j] = mx;
+      }
+    }
   }
-  if (valid) bd[(int64_t)row * n + i] = bdv;
   if (threadIdx.x == 0) {
     ab[(int64_t)row * nchunk + c] = cmn;
     const int64_t range = (int64_t)cmx - (int64_t)cmn;
     ar[(int64_t)row * nchunk + c] = (int32_t)(range < 0x7fffffffLL ? range : 0x7fffffffLL);
-  }
-  if ((threadIdx.x & (kPkBlock - 1)) == 0) {
-    const int j = c * (kPkChunk / kPkBlock) + threadIdx.x / kPkBlock;
-    if (j < nblk) {
-      int32_t mn = INT32_MAX, mx = INT32_MIN;
-#pragma unroll
-      for (int w = 0; w < kPkBlock / 64; ++w) { mn = min(mn, s_bmn[wave + w]); mx = max(mx, s_bmx[wave + w]); }
-      bmn[(int64_t)row * nblk + j] = mn;
-      bmx[(int64_t)row * nblk + j] = mx;
-    }
   }
 }
 
