@@ -64,16 +64,23 @@ def draw_rows(rng, batch, n, dtype):
     return np.stack(rows).astype(dtype)
 
 
-@pytest.mark.parametrize("case", range(60))
+@pytest.mark.parametrize("case", range(96))
 def test_random_products(rtc, case):
     rng = np.random.default_rng(1000 + case)
     dtype = [np.int32, np.int64, np.float64][case % 3]
     n = int(rng.choice([1, 2, 3, 17, 100, 1023, 1024, 1025, 2048, 2500, 4097, 6000]))
     batch = int(rng.integers(1, 5))
     f, g = draw_rows(rng, batch, n, dtype), draw_rows(rng, batch, n, dtype)
-    if dtype == np.int64 and case % 2:
-        f = f * (1 << 34)       # beyond the 32-bit kernels
-        g = g * (1 << 34)
+    if dtype == np.int64:
+        kind = (case // 3) % 4
+        ramp = np.arange(n, dtype=np.int64)
+        if kind == 1:           # beyond the 32-bit kernels in every respect
+            f, g = f * (1 << 34), g * (1 << 34)
+        elif kind == 2:         # steep lines: narrow once the pair's common slope is removed
+            f, g = f + int(rng.integers(900000, 1100000)) * ramp, g + int(rng.integers(900000, 1100000)) * ramp
+        elif kind == 3:         # far from zero and slowly varying: re-based per chunk
+            f = f + np.cumsum(rng.integers(0, 300000, (batch, n)), axis=1) + (1 << 44)
+            g = g + np.cumsum(rng.integers(0, 300000, (batch, n)), axis=1) - (1 << 45)
     print("[case]", case, dtype.__name__, batch, n, flush=True)
     sys.stdout.flush()
     fd, gd = dev(f), dev(g)
