@@ -229,6 +229,10 @@ def per_config_table(seed, peak_ops, with_cpu, configs=(1, 2, 3, 4, 5)):
         ramp = np.arange(65536, dtype=np.int64)
         product_rows(3, c["f"][:16] + 1000003 * ramp, c["g"][:16] + 999983 * ramp, 4,
                      "int64 storage, slope 10^6 per step (common slope removed, int32 / packed arithmetic)")
+        # slopes that differ (10^6 and 1.7 * 10^6 per step): still wide with the common slope removed,
+        # but every chunk and window of the detrended rows fits 32 bits
+        product_rows(3, c["f"][:16] + 1000003 * ramp, c["g"][:16] + 1700021 * ramp, 4,
+                     "int64 storage, slopes 1.0 and 1.7 * 10^6 per step (common slope removed, re-based per chunk)")
         # values spanning 2^40: beyond the row-level narrowing, but slowly varying, so the chunks are
         # re-based and reduced in 32-bit arithmetic; then the same rows with that path off (64-bit kernel)
         product_rows(3, c["f"][:16] * 4096, c["g"][:16] * 4096, 4,

@@ -262,11 +262,11 @@ int rtc_set_small_problem_items(int64_t items);
  * 32 bits by subtracting the row minima).  mode 2 (default): a pair that stays within 2^30 of a
  * line -- both rows minus i times the pair's common slope, half the sum of their mean slopes --
  * is narrowed with the slope removed and takes the 32-bit and packed kernels at their full rate
- * (cumulative curves in nanoseconds or cycles are of this kind); otherwise a pair that varies
- * slowly -- for every chunk of 1024 steps and window of 2048 samples, range(chunk of one row) +
- * range(window of the other) <= 2^31 - 2 -- runs in 32-bit arithmetic on values re-based per
- * chunk, about 2.5 times as fast as the 64-bit kernel, which takes the rest.  mode 1: without the
- * first of the two; mode 0: without both.  Results do not depend on it.  Process-wide, not
+ * (cumulative curves in nanoseconds or cycles are of this kind); otherwise a pair that, minus the
+ * same slope, varies slowly -- for every chunk of 1024 steps and window of 2048 samples,
+ * range(chunk of one row) + range(window of the other) <= 2^31 - 2 -- runs in 32-bit arithmetic
+ * on values re-based per chunk, about 2.5 times as fast as the 64-bit kernel, which takes the
+ * rest.  mode 1: the second of the two only, without any slope removed; mode 0: neither.  Results do not depend on it.  Process-wide, not
  * thread-safe.  RTC_ERR_MODE for other values. */
 int rtc_set_rebase_wide(int mode);
 

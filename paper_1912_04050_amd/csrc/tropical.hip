@@ -407,7 +407,7 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
   if (rebase) {
     hipLaunchKernelGGL(wide_tables_kernel<OP>, dim3((uint32_t)batch), dim3(kWideThreads), 0, stream,
                        static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g, ok, tab,
-                       (int)n, nb);
+                       tab + (size_t)batch * nb * 4, (int)n, nb, g_rebase_wide >= 2);
   }
   // Several kernels see every row; the selector makes each row run in exactly one family.
   // The output is filled once with the identity, before all of them.
@@ -440,8 +440,8 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
     if (parts < 1) parts = 1;
     if (parts > items_per_row) parts = items_per_row;
     prof_begin(RTC_PROFILE_KIND(RTC_I64, 0, OP), stream);
-    hipLaunchKernelGGL(rebased_rows_kernel<OP>, dim3((uint32_t)batch * parts), dim3(64), 0, stream, args, tab, nb,
-                       items_per_row, parts);
+    hipLaunchKernelGGL(rebased_rows_kernel<OP>, dim3((uint32_t)batch * parts), dim3(64), 0, stream, args, tab,
+                       tab + (size_t)batch * nb * 4, nb, items_per_row, parts);
     prof_end(stream);
     if (int hrc = hip_ok()) return hrc;
   }

@@ -5,8 +5,10 @@
 // the uniform operand and a window of at most 2048 consecutive values of the window operand
 // (both aligned to 1024).  When for every chunk and window of a row pair
 //     range(chunk of a) + range(window of b) <= 2^31 - 2
-// (decided per row from tables of block minima / maxima), each chunk's candidates, taken
-// relative to (min of the chunk) +- (min of the window), fit 32 bits: the chunk is reduced by the
+// (decided per row from tables of block minima / maxima; with `detrend`, of the rows minus the
+// pair's common slope times the index, see common_slope, so that steep lines of different slopes
+// qualify as long as the slopes differ by less than about 10^6 per step), each chunk's candidates,
+// taken relative to (min of the chunk) +- (min of the window), fit 32 bits: the chunk is reduced by the
 // 32-bit inner loop (1.5 VALU instructions per candidate instead of the 4 to 5 of the 64-bit one)
 // and its partial results are folded into 64-bit accumulators with the bases added back, once
 // per chunk.  Every candidate is the exact integer of the definition, so the result has the same
@@ -15,6 +17,7 @@
 
 #include "tropical_common.h"
 #include "tropical_generic.h"
+#include "tropical_prepare.h"
 
 namespace rtc {
 namespace {
@@ -26,7 +29,7 @@ static_assert(kWideBlock == Tile<int32_t, kWideR>::kW, "windows are pairs of ali
 constexpr uint64_t kWideBudget = 0x7ffffffeull;
 
 __host__ __device__ inline int wide_blocks(int64_t n) { return (int)((n + kWideBlock - 1) / kWideBlock); }
-inline size_t wide_table_elems(int64_t batch, int64_t n) { return (size_t)batch * wide_blocks(n) * 4; }
+inline size_t wide_table_elems(int64_t batch, int64_t n) { return (size_t)batch * wide_blocks(n) * 4 + (size_t)batch; }   // tables, then the slope per row
 
 // One workgroup of 16 wavefronts per row pair with sel[row] == 0.
 // tab[(row * nb + m) * 4 + {0, 1, 2, 3}] = min a, max a, min b, max b over block m, where a is
@@ -40,14 +43,21 @@ template <int OP>
 __global__ __launch_bounds__(kWideThreads) void wide_tables_kernel(const int64_t* __restrict__ f, int64_t stride_f,
                                                                    const int64_t* __restrict__ g, int64_t stride_g,
                                                                    int32_t* __restrict__ sel, int64_t* __restrict__ tab,
-                                                                   int n, int nb) {
+                                                                   int64_t* __restrict__ slopes, int n, int nb,
+                                                                   bool detrend) {
   constexpr int kWaves = kWideThreads / 64;
   __shared__ uint64_t red[2][kWaves];
+  __shared__ int64_t s_raw[4][kWaves];
+  __shared__ int64_t s_rho;
   const int row = blockIdx.x;
   if (sel[row] != 0) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t* a = op_sub(OP) ? g + (int64_t)row * stride_g : f + (int64_t)row * stride_f;
   const int64_t* b = op_sub(OP) ? f + (int64_t)row * stride_f : g + (int64_t)row * stride_g;
+  if (threadIdx.x == 0) s_rho = detrend ? common_slope(a, b, n) : 0;     // (64-bit divisions: one thread)
+  __syncthreads();
+  const uint64_t rho = (uint64_t)s_rho;
+  int64_t ra_lo = Lim<int64_t>::hi(), ra_hi = Lim<int64_t>::lo(), rb_lo = ra_lo, rb_hi = ra_hi;   // extrema of the rows as they are
   const int per = (nb + kWaves - 1) / kWaves;
   const int first = wave * per, last = min(first + per, nb);       // this wavefront's blocks [first, last)
   uint64_t ra = 0, rb = 0;
@@ -58,7 +68,11 @@ __global__ __launch_bounds__(kWideThreads) void wide_tables_kernel(const int64_t
 #pragma unroll 8
     for (int i = lane; i < kWideBlock; i += 64) {
       const int idx = min(m * kWideBlock + i, n - 1);          // past the end: the last value again
-      const int64_t av = a[idx], bv = b[op_sub(OP) ? n - 1 - idx : idx];
+      const int bi = op_sub(OP) ? n - 1 - idx : idx;
+      const int64_t ar = a[idx], br = b[bi];
+      ra_lo = sel_min(ra_lo, ar); ra_hi = sel_max(ra_hi, ar);
+      rb_lo = sel_min(rb_lo, br); rb_hi = sel_max(rb_hi, br);
+      const int64_t av = (int64_t)((uint64_t)ar - rho * (uint64_t)idx), bv = (int64_t)((uint64_t)br - rho * (uint64_t)bi);
       amin = sel_min(amin, av); amax = sel_max(amax, av);
       bmin = sel_min(bmin, bv); bmax = sel_max(bmax, bv);
     }
@@ -81,19 +95,35 @@ __global__ __launch_bounds__(kWideThreads) void wide_tables_kernel(const int64_t
     if (m >= first) rb = w > rb ? w : rb;
     prev_lo = bmin; prev_hi = bmax; have_prev = true;
   }
-  if (lane == 0) { red[0][wave] = ra; red[1][wave] = rb; }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    ra_lo = sel_min(ra_lo, __shfl_xor(ra_lo, off)); ra_hi = sel_max(ra_hi, __shfl_xor(ra_hi, off));
+    rb_lo = sel_min(rb_lo, __shfl_xor(rb_lo, off)); rb_hi = sel_max(rb_hi, __shfl_xor(rb_hi, off));
+  }
+  if (lane == 0) {
+    red[0][wave] = ra; red[1][wave] = rb;
+    s_raw[0][wave] = ra_lo; s_raw[1][wave] = ra_hi; s_raw[2][wave] = rb_lo; s_raw[3][wave] = rb_hi;
+  }
   __syncthreads();
   if (threadIdx.x == 0) {
-    for (int w = 1; w < kWaves; ++w) { ra = red[0][w] > ra ? red[0][w] : ra; rb = red[1][w] > rb ? red[1][w] : rb; }
-    if (ra <= kWideBudget && rb <= kWideBudget && ra + rb <= kWideBudget) sel[row] = kSelRebased;
+    for (int w = 1; w < kWaves; ++w) {
+      ra = red[0][w] > ra ? red[0][w] : ra; rb = red[1][w] > rb ? red[1][w] : rb;
+      ra_lo = sel_min(ra_lo, s_raw[0][w]); ra_hi = sel_max(ra_hi, s_raw[1][w]);
+      rb_lo = sel_min(rb_lo, s_raw[2][w]); rb_hi = sel_max(rb_hi, s_raw[3][w]);
+    }
+    // with a slope removed the arithmetic is exact only for rows whose own ranges stay below 2^62
+    const bool exact = rho == 0 || ((((uint64_t)ra_hi - (uint64_t)ra_lo) >> 62) == 0 && (((uint64_t)rb_hi - (uint64_t)rb_lo) >> 62) == 0);
+    slopes[row] = (int64_t)rho;
+    if (exact && ra <= kWideBudget && rb <= kWideBudget && ra + rb <= kWideBudget) sel[row] = kSelRebased;
   }
 }
 
 // Work item of the re-based product: tropical_body's walk over the chunks of a segment with a
 // 32-bit inner loop per chunk and 64-bit accumulators across chunks.
 template <int OP>
-__device__ __forceinline__ void rebased_body(const TropicalArgs& p, const int64_t* __restrict__ tab, int nb,
-                                             unsigned char* lds, uint32_t item) {
+__device__ __forceinline__ void rebased_body(const TropicalArgs& p, const int64_t* __restrict__ tab,
+                                             const int64_t* __restrict__ slopes, int nb, unsigned char* lds,
+                                             uint32_t item) {
   constexpr int R = kWideR;
   using SR = Semiring<int32_t, OP>;
   using SR64 = Semiring<int64_t, OP>;
@@ -106,6 +136,10 @@ __device__ __forceinline__ void rebased_body(const TropicalArgs& p, const int64_
   const int64_t* __restrict__ arow = static_cast<const int64_t*>(p.a) + (int64_t)row * p.stride_a;
   const int64_t* __restrict__ brow = static_cast<const int64_t*>(p.b) + (int64_t)row * p.stride_b;
   const int64_t* __restrict__ trow = tab + (int64_t)row * nb * 4;
+  const uint64_t rho = (uint64_t)slopes[row];     // common slope removed from both rows (0: none)
+  // value of the window operand at window index idx / of the uniform operand at step s, slope removed
+  auto b_at = [&](int idx) { const int ri = rev ? n - 1 - idx : idx; return (uint64_t)brow[ri] - rho * (uint64_t)ri; };
+  auto a_at = [&](int s) { return (uint64_t)arow[s] - rho * (uint64_t)s; };
 
   int64_t acc[R];
 #pragma unroll
@@ -132,7 +166,7 @@ __device__ __forceinline__ void rebased_body(const TropicalArgs& p, const int64_
     for (int e = lane; e < count; e += 64) {
       const int idx = gbase + e;
       int32_t v = 0;
-      if (idx >= 0 && idx < n) v = (int32_t)(uint32_t)((uint64_t)brow[rev ? n - 1 - idx : idx] - (uint64_t)wbase);
+      if (idx >= 0 && idx < n) v = (int32_t)(uint32_t)(b_at(idx) - (uint64_t)wbase);
       *reinterpret_cast<int32_t*>(lds + (e / R) * TL::kSlotBytes + (e % R) * 4) = v;
     }
     __syncthreads();
@@ -150,7 +184,7 @@ __device__ __forceinline__ void rebased_body(const TropicalArgs& p, const int64_
         if (j < 0 || (s0 + R < n && j < 63)) {
           int32_t u[R];
 #pragma unroll
-          for (int k = 0; k < R; ++k) u[k] = (int32_t)(uint32_t)((uint64_t)arow[s0 + k] - (uint64_t)abase);
+          for (int k = 0; k < R; ++k) u[k] = (int32_t)(uint32_t)(a_at(s0 + k) - (uint64_t)abase);
           if (lane > j) block_steps<SR, int32_t, R>(part, u, w1, w0);
         }
       }
@@ -161,7 +195,7 @@ __device__ __forceinline__ void rebased_body(const TropicalArgs& p, const int64_
         if (j < 0 || (s0 + R < n && j < 63)) {
           int32_t u[R];
 #pragma unroll
-          for (int k = 0; k < R; ++k) u[k] = (int32_t)(uint32_t)((uint64_t)arow[s0 + k] - (uint64_t)abase);
+          for (int k = 0; k < R; ++k) u[k] = (int32_t)(uint32_t)(a_at(s0 + k) - (uint64_t)abase);
           if (lane > j) block_steps<SR, int32_t, R>(part, u, w0, w1);
         }
       }
@@ -177,12 +211,12 @@ __device__ __forceinline__ void rebased_body(const TropicalArgs& p, const int64_
 #pragma unroll
     for (int q = 0; q < R; ++q) {
       const int idx = min(q, n - 1);
-      b0[q] = (int32_t)(uint32_t)((uint64_t)brow[rev ? n - 1 - idx : idx] - (uint64_t)wbase);
+      b0[q] = (int32_t)(uint32_t)(b_at(idx) - (uint64_t)wbase);
       part[q] = SR::identity();
     }
 #pragma unroll
     for (int k = 0; k < R; ++k) {
-      const int32_t ak = (int32_t)(uint32_t)((uint64_t)arow[min(tl + k, n - 1)] - (uint64_t)abase);
+      const int32_t ak = (int32_t)(uint32_t)(a_at(min(tl + k, n - 1)) - (uint64_t)abase);
 #pragma unroll
       for (int r = k; r < R; ++r) part[r] = SR::reduce(part[r], SR::combine(b0[r - k], ak));
     }
@@ -206,6 +240,7 @@ __device__ __forceinline__ void rebased_body(const TropicalArgs& p, const int64_
       const int ot = op_sub(OP) ? n - 1 - t : t;
       int64_t v = xp[x + x / R];
       if (v == SR64::identity()) continue;        // this item saw no candidate of that output
+      v = (int64_t)((uint64_t)v + rho * (uint64_t)ot);   // the slope's share of every candidate of output ot
       if (crow) v = sel_min(v, crow[ot]);
       if (op_max(OP)) atomic_max(&orow[ot], v); else atomic_min(&orow[ot], v);
     }
@@ -215,12 +250,13 @@ __device__ __forceinline__ void rebased_body(const TropicalArgs& p, const int64_
 // `parts` workgroups per row, each looks at its row's selector once and either leaves or walks
 // every parts-th item of the row (items are numbered rows fastest).
 template <int OP>
-__global__ __launch_bounds__(64) void rebased_rows_kernel(const TropicalArgs p, const int64_t* __restrict__ tab, int nb,
+__global__ __launch_bounds__(64) void rebased_rows_kernel(const TropicalArgs p, const int64_t* __restrict__ tab,
+                                                          const int64_t* __restrict__ slopes, int nb,
                                                           uint32_t items_per_row, uint32_t parts) {
   __shared__ __align__(16) unsigned char lds[lds_bytes<int32_t, kWideR>()];
   const uint32_t row = blockIdx.x % (uint32_t)p.batch, part = blockIdx.x / (uint32_t)p.batch;
   if (p.sel[row] != p.sel_want) return;
-  for (uint32_t j = part; j < items_per_row; j += parts) rebased_body<OP>(p, tab, nb, lds, j * (uint32_t)p.batch + row);
+  for (uint32_t j = part; j < items_per_row; j += parts) rebased_body<OP>(p, tab, slopes, nb, lds, j * (uint32_t)p.batch + row);
 }
 
 }  // namespace

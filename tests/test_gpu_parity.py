@@ -614,8 +614,15 @@ def test_wide_int64_rows_rebased_per_chunk(rtc):
         edge[512:] = (1 << 30) - 1
         over = edge.copy()
         over[512:] += 2
-        f = np.stack([slow(1 << 45), walk(-(1 << 50)), jump, slow(0), steep, edge, over, slow(7)]).astype(np.int64)
-        g = np.stack([slow(-(1 << 44)), slow(1 << 33), slow(5), walk(1 << 41), slow(0), edge, over, walk(0)]).astype(np.int64)
+        ramp = np.arange(n, dtype=np.int64)
+        def line(rate):                 # steep line plus small increments
+            return rate * ramp + np.cumsum(rng.integers(0, 90, n))
+        # steep lines of different slopes: wide even with their common slope removed, yet every
+        # chunk and window then fits (slopes 7e5 apart); 3e6 apart they do not
+        f = np.stack([slow(1 << 45), walk(-(1 << 50)), jump, slow(0), steep, edge, over, slow(7),
+                      line(1000000), line(1700000), line(1000000), -line(500000)]).astype(np.int64)
+        g = np.stack([slow(-(1 << 44)), slow(1 << 33), slow(5), walk(1 << 41), slow(0), edge, over, walk(0),
+                      line(1700000), line(1000000), line(4000000), line(200000)]).astype(np.int64)
         for mode in (2, 1, 0):
             rtc.rtc_set_rebase_wide(mode)
             try:
