@@ -1,5 +1,12 @@
-// Tropical products of row pairs whose convexity makes the reduction trivial: one thread per
-// output, O(1) or O(log n) candidates instead of all of them.  Included by tropical.hip only.
+// Tropical products of row pairs whose shape makes most candidates superfluous (integers only;
+// every candidate that is formed is the definition's exact integer, so the results have the same
+// bits as the general kernels'):
+//   both rows convex / concave    the ends of the candidate range, or a bisection   (structured_kernel)
+//   one row convex / concave      monotone optima: anchors, then brackets          (bracket_anchor_body)
+//   one row periodic              a scan along residue classes, then a window of one period
+//                                 (period_kernel, periodic_scan_body, periodic_product_body)
+// Three launches serve all of them: structured_first_kernel, bracket_fine_kernel,
+// structured_kernel.  Included by tropical.hip only.
 #pragma once
 
 #include "tropical_common.h"
@@ -485,7 +492,6 @@ __global__ __launch_bounds__(256) void structured_kernel(const T* __restrict__ f
   out[(int64_t)row * n + t] = v;
 }
 
-// Runs after the probe kernels (which write sel) and before any kernel that reads sel.
 // First launch of the structured rows: the coarse anchors of the bracket path and the scan of
 // the periodic path (different rows; both feed the launches that follow).
 template <typename T, int OP>
@@ -513,6 +519,7 @@ __global__ __launch_bounds__(256) void bracket_fine_kernel(const T* __restrict__
                                                   anchors, blockIdx.x);
 }
 
+// Runs after the probe kernels (which write sel) and before any kernel that reads sel.
 template <typename T>
 void launch_period(const T* f, int64_t stride_f, const T* g, int64_t stride_g, int32_t* sel, int32_t* period,
                    int32_t* pack_ok, int64_t batch, int64_t n, int op, hipStream_t stream) {
