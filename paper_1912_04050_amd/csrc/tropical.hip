@@ -38,6 +38,16 @@
 // The decision is made per (row, tile, chunk) from precomputed block minima / maxima; chunks
 // that do not qualify are done by the 32-bit kernel, which evaluates the same predicate and
 // skips exactly the chunks the packed kernel owns.  Results are exact in both cases.
+// (tropical_packed.h also has the flavour for chunks that fit 15 bits, where the packed
+// three-operand half-float minimum / maximum acts as an exact integer min3 / max3: 0.75 VALU
+// instructions per pair-op.)
+//
+// Other row-dependent paths, each chosen per row pair on the device, all with bit-identical
+// results: rows of exploitable convexity or periodicity (tropical_structured.h); int64 rows
+// narrowed to 32 bits by their minima or with the pair's common slope removed (the probe kernels
+// of tropical_prepare.h), or re-based per chunk (tropical_rebased.h); the 64-bit kernel takes what
+// is left.  Problems with too few work items to fill the chip use the same kernel with small
+// tiles (kSmallR).
 #include <hip/hip_runtime.h>
 
 #include <limits>
