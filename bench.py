@@ -233,6 +233,11 @@ def per_config_table(seed, peak_ops, with_cpu, configs=(1, 2, 3, 4, 5)):
         # but every chunk and window of the detrended rows fits 32 bits
         product_rows(3, c["f"][:16] + 1000003 * ramp, c["g"][:16] + 1700021 * ramp, 4,
                      "int64 storage, slopes 1.0 and 1.7 * 10^6 per step (common slope removed, re-based per chunk)")
+        # a step of 2^40 in mid-row: no chunk-wise re-basing either, but all values lie within +-2^51,
+        # where fp64 adds and compares integers exactly
+        step = (ramp >= 32768).astype(np.int64) << 40
+        product_rows(3, c["f"][:16] + step, c["g"][:16] + 2 * step, 4,
+                     "int64 storage with a step of 2^40 (fp64 arithmetic on exact integers)")
         # values spanning 2^40: beyond the row-level narrowing, but slowly varying, so the chunks are
         # re-based and reduced in 32-bit arithmetic; then the same rows with that path off (64-bit kernel)
         product_rows(3, c["f"][:16] * 4096, c["g"][:16] * 4096, 4,

@@ -265,8 +265,10 @@ int rtc_set_small_problem_items(int64_t items);
  * (cumulative curves in nanoseconds or cycles are of this kind); otherwise a pair that, minus the
  * same slope, varies slowly -- for every chunk of 1024 steps and window of 2048 samples,
  * range(chunk of one row) + range(window of the other) <= 2^31 - 2 -- runs in 32-bit arithmetic
- * on values re-based per chunk, about 2.5 times as fast as the 64-bit kernel, which takes the
- * rest.  mode 1: the second of the two only, without any slope removed; mode 0: neither.  Results do not depend on it.  Process-wide, not
+ * on values re-based per chunk, about 2.5 times as fast as the 64-bit kernel; of the rest, pairs
+ * whose values all lie within +-2^51 run in fp64 arithmetic, which is exact on such integers
+ * (about 1.8 times as fast), and only the others in the 64-bit integer kernel.  mode 1: without
+ * any slope removed; mode 0: the 64-bit integer kernel for every pair that spans 2^30 or more.  Results do not depend on it.  Process-wide, not
  * thread-safe.  RTC_ERR_MODE for other values. */
 int rtc_set_rebase_wide(int mode);
 

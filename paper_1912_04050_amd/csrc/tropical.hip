@@ -216,7 +216,7 @@ int run_product(const T* a, int64_t stride_a, const T* b, int64_t stride_b, OutT
 // Layout of the packed path's arrays inside the workspace.
 struct PackLayout {
   int64_t npad, nchunk, nsub, nblk;
-  size_t off_apk, off_apk_s, off_bd, off_ab, off_ar, off_ab_s, off_ar_s, off_bmn, off_bmx, off_rho, off_ok, off_sel, off_jstar, off_period, off_F, bytes;
+  size_t off_apk, off_apk_s, off_bd, off_ab, off_ar, off_ab_s, off_ar_s, off_bmn, off_bmx, off_rho, off_ok, off_sel, off_jstar, off_period, off_F, off_dbl, bytes;
 };
 
 PackLayout pack_layout(int64_t batch, int64_t n) {
@@ -242,6 +242,7 @@ PackLayout pack_layout(int64_t batch, int64_t n) {
   L.off_jstar = take(bracket_jstar_elems(batch, n));   // anchor optima of the bracket path
   L.off_period = take((size_t)batch);                  // period per row of the periodic path
   L.off_F = take((size_t)batch * n * 2);               // its scan F, [batch][n] of the rows' own type
+  L.off_dbl = take((size_t)batch * n * 2);             // second fp64 copy of wide int64 rows (the first one shares F)
   L.bytes = o;
   return L;
 }
@@ -417,7 +418,8 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
   if (rebase) {
     hipLaunchKernelGGL(wide_tables_kernel<OP>, dim3((uint32_t)batch), dim3(kWideThreads), 0, stream,
                        static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g, ok, tab,
-                       tab + (size_t)batch * nb * 4, (int)n, nb, g_rebase_wide >= 2);
+                       tab + (size_t)batch * nb * 4, reinterpret_cast<double*>(wsp + L.off_F),
+                       reinterpret_cast<double*>(wsp + L.off_dbl), (int)n, nb, g_rebase_wide >= 2);
   }
   // Several kernels see every row; the selector makes each row run in exactly one family.
   // The output is filled once with the identity, before all of them.
@@ -454,6 +456,13 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
                        tab + (size_t)batch * nb * 4, nb, items_per_row, parts);
     prof_end(stream);
     if (int hrc = hip_ok()) return hrc;
+    // ... and the pairs within +-2^51 that did not qualify: the fp64 kernel on the double copies
+    // (uniform operand a, window operand b, as wide_tables_kernel wrote them)
+    rc = run_product<double, int64_t, OP>(reinterpret_cast<const double*>(wsp + L.off_F), n,
+                                          reinterpret_cast<const double*>(wsp + L.off_dbl), n,
+                                          static_cast<int64_t*>(out), static_cast<const int64_t*>(cap), ok,
+                                          kSelDouble, batch, n, stream, true, true, nullptr);
+    if (rc != RTC_OK) return rc;
   }
   if (!structure) return RTC_OK;
   // rows of exploitable convexity (selector 2 / 3), on the caller's own 64-bit rows

@@ -23,6 +23,13 @@ namespace rtc {
 namespace {
 
 constexpr int kSelRebased = -1;        // selector of the row pairs this path takes (narrow_ok array)
+// Row pairs that do not qualify but whose values all lie within +-2^51: every sum and difference
+// of two of them is an integer below 2^53 in magnitude, which fp64 adds, subtracts and compares
+// exactly -- they run through the fp64 kernel (one add and one min per candidate instead of the
+// 64-bit integer kernel's four to five instructions) on copies converted to double, and the
+// results convert back exactly.
+constexpr int kSelDouble = -2;
+constexpr int64_t kDoubleExact = (int64_t)1 << 51;
 constexpr int kWideR = 16;
 constexpr int kWideBlock = Tile<int32_t, kWideR>::kChunk;   // 1024: chunk of steps = tile of outputs
 static_assert(kWideBlock == Tile<int32_t, kWideR>::kW, "windows are pairs of aligned blocks");
@@ -43,8 +50,9 @@ template <int OP>
 __global__ __launch_bounds__(kWideThreads) void wide_tables_kernel(const int64_t* __restrict__ f, int64_t stride_f,
                                                                    const int64_t* __restrict__ g, int64_t stride_g,
                                                                    int32_t* __restrict__ sel, int64_t* __restrict__ tab,
-                                                                   int64_t* __restrict__ slopes, int n, int nb,
-                                                                   bool detrend) {
+                                                                   int64_t* __restrict__ slopes,
+                                                                   double* __restrict__ a_dbl, double* __restrict__ b_dbl,
+                                                                   int n, int nb, bool detrend) {
   constexpr int kWaves = kWideThreads / 64;
   __shared__ uint64_t red[2][kWaves];
   __shared__ int64_t s_raw[4][kWaves];
@@ -72,6 +80,10 @@ __global__ __launch_bounds__(kWideThreads) void wide_tables_kernel(const int64_t
       const int64_t ar = a[idx], br = b[bi];
       ra_lo = sel_min(ra_lo, ar); ra_hi = sel_max(ra_hi, ar);
       rb_lo = sel_min(rb_lo, br); rb_hi = sel_max(rb_hi, br);
+      if (m >= first) {     // copies for the fp64 kernel (exact if the pair ends up there), rows as they are
+        a_dbl[(int64_t)row * n + idx] = (double)ar;
+        b_dbl[(int64_t)row * n + bi] = (double)br;
+      }
       const int64_t av = (int64_t)((uint64_t)ar - rho * (uint64_t)idx), bv = (int64_t)((uint64_t)br - rho * (uint64_t)bi);
       amin = sel_min(amin, av); amax = sel_max(amax, av);
       bmin = sel_min(bmin, bv); bmax = sel_max(bmax, bv);
@@ -114,7 +126,9 @@ __global__ __launch_bounds__(kWideThreads) void wide_tables_kernel(const int64_t
     // with a slope removed the arithmetic is exact only for rows whose own ranges stay below 2^62
     const bool exact = rho == 0 || ((((uint64_t)ra_hi - (uint64_t)ra_lo) >> 62) == 0 && (((uint64_t)rb_hi - (uint64_t)rb_lo) >> 62) == 0);
     slopes[row] = (int64_t)rho;
+    const bool small = ra_lo >= -kDoubleExact && ra_hi <= kDoubleExact && rb_lo >= -kDoubleExact && rb_hi <= kDoubleExact;
     if (exact && ra <= kWideBudget && rb <= kWideBudget && ra + rb <= kWideBudget) sel[row] = kSelRebased;
+    else if (small) sel[row] = kSelDouble;
   }
 }
 

@@ -599,7 +599,8 @@ def test_periodic_operands(rtc, dtype):
 def test_wide_int64_rows_rebased_per_chunk(rtc):
     """int64 rows that span far more than 32 bits: pairs close to a common line are narrowed with
     the slope removed, pairs that vary slowly take 32-bit arithmetic re-based per chunk, pairs
-    with a jump beyond the budget, or steep ones, stay with the 64-bit kernel.  All kinds next to
+    with a jump beyond the budget, or steep ones, take the fp64 kernel if all their values are within
+    +-2^51 and the 64-bit integer kernel otherwise.  All kinds next to
     each other in one batch, all four products, under the three settings of the knob."""
     rng = np.random.default_rng(53)
     for n in (1025, 5000, 20011):
@@ -620,9 +621,11 @@ def test_wide_int64_rows_rebased_per_chunk(rtc):
         # steep lines of different slopes: wide even with their common slope removed, yet every
         # chunk and window then fits (slopes 7e5 apart); 3e6 apart they do not
         f = np.stack([slow(1 << 45), walk(-(1 << 50)), jump, slow(0), steep, edge, over, slow(7),
-                      line(1000000), line(1700000), line(1000000), -line(500000)]).astype(np.int64)
+                      line(1000000), line(1700000), line(1000000), -line(500000), jump + (1 << 55), jump - (1 << 51)]).astype(np.int64)
         g = np.stack([slow(-(1 << 44)), slow(1 << 33), slow(5), walk(1 << 41), slow(0), edge, over, walk(0),
-                      line(1700000), line(1000000), line(4000000), line(200000)]).astype(np.int64)
+                      line(1700000), line(1000000), line(4000000), line(200000), slow(0), slow(3)]).astype(np.int64)
+        # (the pairs with `jump`: a step of 2^40 keeps them off the re-based path; within +-2^51 they
+        # take the fp64 kernel, the pair lifted to 2^55 and the one reaching below -2^51 the 64-bit one)
         for mode in (2, 1, 0):
             rtc.rtc_set_rebase_wide(mode)
             try:
