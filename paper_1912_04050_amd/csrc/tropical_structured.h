@@ -134,7 +134,6 @@ __global__ __launch_bounds__(kPeriodThreads) void period_kernel(const T* __restr
   __shared__ T s_red[4][kWaves];
   __shared__ T s_w[2][kPeriodRun + 2 * kPeriodMax];   // w[1 ...], the head of each row
   __shared__ uint32_t s_seen[2][kPeriodMax / 32];     // periods that passed the screening
-  __shared__ int s_first[2];                          // smallest period that passed the first test
   const int row = blockIdx.x;
   if (sel[row] >= kSelSearch) return;
   const int pmax = period_limit(n);
@@ -146,7 +145,6 @@ __global__ __launch_bounds__(kPeriodThreads) void period_kernel(const T* __restr
     (&s_cand[0][0])[k] = 0;
     (&s_seen[0][0])[k] = 0;
   }
-  if (threadIdx.x < 2) s_first[threadIdx.x] = 0x7fffffff;
   const int staged = min(run + 2 * pmax, n - 1);      // w[1 .. staged]
   // (both rows in one unrolled loop: all loads of a thread in flight together)
 #pragma unroll 6
@@ -180,8 +178,8 @@ __global__ __launch_bounds__(kPeriodThreads) void period_kernel(const T* __restr
   // First test of what passed, in ascending order, one wavefront per period and kWaves at a
   // time: a run of consecutive positions (staircases agree with many wrong periods at scattered
   // ones), three positions spread over the row and the far ends of two residue classes over
-  // the whole row.  What passes becomes a candidate; nothing above the smallest candidate so far
-  // is tested (every multiple of a period passes too).
+  // the whole row.  What passes becomes a candidate (every multiple of a period passes too: the
+  // search of a row ends with its kPeriodTries smallest candidates).
   {
     // the wavefronts are shared out between the rows, so that one round serves both
     const int per = kWaves / nrows;                    // wavefronts per row
@@ -204,8 +202,8 @@ __global__ __launch_bounds__(kPeriodThreads) void period_kernel(const T* __restr
     }
     const uint32_t my_word = which ? word[1] : word[0];
     const int my_incl = which ? incl[1] : incl[0], my_total = which ? total[1] : total[0];
-    // this wavefront tests the slot-th, (slot + per)-th, ... period of its row's set, until one
-    // at or below its own has passed somewhere (no barrier: the wavefronts run on their own)
+    // this wavefront tests the slot-th, (slot + per)-th, ... period of its row's set (no barrier:
+    // the wavefronts run on their own)
     for (int k = slot; k < my_total; k += per) {
       {
         const uint64_t holds = __ballot(lane < 32 && my_incl > k);       // first word whose prefix count exceeds k
@@ -214,7 +212,17 @@ __global__ __launch_bounds__(kPeriodThreads) void period_kernel(const T* __restr
         int skip = k - (__shfl(my_incl, wi) - __popc(bits));
         while (skip-- > 0) bits &= bits - 1;
         const int p = wi * 32 + __builtin_ctz(bits) + 1;
-        if (p > *(volatile int*)&s_first[which]) break;
+        // stop once kPeriodTries smaller periods have passed: the full test below looks at no more
+        // than that many, in ascending order, so the kPeriodTries smallest that pass are always
+        // found, whatever the order in which the wavefronts get here
+        {
+          const int below = p - 1 - lane * 32;       // bits of word `lane` that stand for periods < p
+          const uint32_t seen = lane < kPeriodMax / 32 ? ((volatile uint32_t*)s_cand[which])[lane] : 0u;
+          int passed = __popc(below >= 32 ? seen : below <= 0 ? 0u : seen & ((1u << below) - 1u));
+#pragma unroll
+          for (int off = 32; off > 0; off >>= 1) passed += __shfl_xor(passed, off);
+          if (passed >= kPeriodTries) break;
+        }
         const T c = wrap_sub(sw[p], sw[0]);
         bool ok = true;
         for (int i = lane; i < run; i += 64) ok = ok && wrap_sub(sw[i + p], sw[i]) == c;
@@ -226,10 +234,7 @@ __global__ __launch_bounds__(kPeriodThreads) void period_kernel(const T* __restr
           const int steps = lane == 3 ? (n - 2) / p : lane == 4 ? (n - 1 - i2) / p : 1;
           ok = wrap_sub(w[first + steps * p], w[first]) == (T)((T)steps * c);
         }
-        if (__all(ok) && lane == 0) {
-          atomicOr(&s_cand[which][(p - 1) >> 5], 1u << ((p - 1) & 31));
-          atomicMin(&s_first[which], p);
-        }
+        if (__all(ok) && lane == 0) atomicOr(&s_cand[which][(p - 1) >> 5], 1u << ((p - 1) & 31));
       }
     }
   }
