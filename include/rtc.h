@@ -59,6 +59,7 @@ typedef enum {
 #define RTC_FLAG_OVERFLOW 1  /* integer range precondition not provable from the rows' min/max */
 #define RTC_FLAG_DOMAIN 2    /* rtc_compose: an index was outside [0, n_outer-1] and was clamped */
 #define RTC_FLAG_UNBOUNDED 4 /* rtc_max_hdev: some alpha[D] is never reached by beta within the horizon */
+#define RTC_FLAG_NOT_MONOTONE 8 /* rtc_validate_monotone: some row decreases somewhere */
 
 /* Min-plus convolution, out[b][t] = min_{0<=s<=t} f[b][s] + g[b][t-s], t = 0..n-1.
  * Truncated horizon: samples beyond n-1 do not exist, the output has n samples.
@@ -192,6 +193,14 @@ int rtc_max_hdev(const void* alpha, const void* beta, int32_t* out, int64_t batc
  * (equal to (alpha (/) beta)[0]).  out: [batch] of dtype dt. */
 int rtc_max_vdev(const void* alpha, const void* beta, void* out, int64_t batch, int64_t n,
                  rtc_dtype dt, void* hip_stream);
+
+/* Debug aid: the pseudo-inverse, the composition's inner curve, the deviations and the component
+ * step take nondecreasing rows and do not check it.  This does: RTC_FLAG_NOT_MONOTONE is raised in
+ * dev_flags (required) when some f[b][i+1] < f[b][i], and first_bad[b] (optional; device, [batch]
+ * int32) receives the smallest such i, or -1 for a nondecreasing row.  f: [batch][n], row stride
+ * `stride` elements (0 = one row for every b). */
+int rtc_validate_monotone(const void* f, int64_t batch, int64_t n, int64_t stride, rtc_dtype dt,
+                          int32_t* first_bad, int32_t* dev_flags, void* hip_stream);
 
 /* Which kernel family the four products give a row pair (integer dtypes; fp64 rows are always
  * RTC_STRUCTURE_GENERAL).  With c(j) the candidates of one output (f[j] + g[t-j] for the

@@ -457,6 +457,39 @@ int launch_max_hdev(const void* alpha, const void* beta, int32_t* out, int64_t b
   });
 }
 
+namespace {
+// One workgroup per row: smallest i with f[i+1] < f[i], or -1.
+template <typename T>
+__global__ __launch_bounds__(256) void validate_monotone_kernel(const T* __restrict__ f, int64_t stride, int n,
+                                                                int32_t* __restrict__ first_bad,
+                                                                int32_t* __restrict__ dev_flags) {
+  __shared__ int red[4];
+  const int row = blockIdx.x;
+  const T* fr = f + (int64_t)row * stride;
+  int bad = 0x7fffffff;
+  for (int i = threadIdx.x; i + 1 < n; i += 256)
+    if (fr[i + 1] < fr[i]) { bad = i; break; }       // ascending i per thread: its first one
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) bad = min(bad, __shfl_xor(bad, off));
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = bad;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    bad = min(min(red[0], red[1]), min(red[2], red[3]));
+    if (first_bad != nullptr) first_bad[row] = bad == 0x7fffffff ? -1 : bad;
+    if (bad != 0x7fffffff) atomicOr(dev_flags, RTC_FLAG_NOT_MONOTONE);
+  }
+}
+}  // namespace
+
+int launch_validate_monotone(const void* f, int64_t batch, int64_t n, int64_t stride, int dt, int32_t* first_bad,
+                             int32_t* dev_flags, hipStream_t stream) {
+  RTC_DISPATCH(dt, {
+    hipLaunchKernelGGL(validate_monotone_kernel<T>, dim3((uint32_t)batch), dim3(256), 0, stream,
+                       static_cast<const T*>(f), stride, (int)n, first_bad, dev_flags);
+    return hip_ok();
+  });
+}
+
 int launch_max_vdev(const void* alpha, const void* beta, void* out, int64_t batch, int64_t n, int dt,
                     hipStream_t stream) {
   const int64_t bpr = (n + kDevPerBlock - 1) / kDevPerBlock;

@@ -266,6 +266,17 @@ int rtc_max_hdev(const void* alpha, const void* beta, int32_t* out, int64_t batc
   return launch_max_hdev(alpha, beta, out, batch, n, dt, dev_flags, static_cast<hipStream_t>(hip_stream));
 }
 
+int rtc_validate_monotone(const void* f, int64_t batch, int64_t n, int64_t stride, rtc_dtype dt,
+                          int32_t* first_bad, int32_t* dev_flags, void* hip_stream) {
+  if (f == nullptr || dev_flags == nullptr) return RTC_ERR_NULL;
+  const size_t es = elem_size(dt);
+  if (es == 0) return RTC_ERR_DTYPE;
+  if (int rc = check_shape(batch, n)) return rc;
+  if (stride != 0 && stride < n) return RTC_ERR_STRIDE;
+  if (!aligned(f, es) || !aligned(first_bad, 4) || !aligned(dev_flags, 4)) return RTC_ERR_ALIGN;
+  return launch_validate_monotone(f, batch, n, stride, dt, first_bad, dev_flags, static_cast<hipStream_t>(hip_stream));
+}
+
 int rtc_max_vdev(const void* alpha, const void* beta, void* out, int64_t batch, int64_t n,
                  rtc_dtype dt, void* hip_stream) {
   if (alpha == nullptr || beta == nullptr || out == nullptr) return RTC_ERR_NULL;

@@ -43,6 +43,8 @@ int launch_closure_init(const void* f, void* out, int64_t batch, int64_t n, int 
 int launch_copy(const void* src, void* dst, int64_t count, int dt, hipStream_t stream);
 int launch_max_hdev(const void* alpha, const void* beta, int32_t* out, int64_t batch, int64_t n,
                     int dt, int32_t* dev_flags, hipStream_t stream);
+int launch_validate_monotone(const void* f, int64_t batch, int64_t n, int64_t stride, int dt, int32_t* first_bad,
+                             int32_t* dev_flags, hipStream_t stream);
 int launch_max_vdev(const void* alpha, const void* beta, void* out, int64_t batch, int64_t n, int dt,
                     hipStream_t stream);
 

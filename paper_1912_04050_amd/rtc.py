@@ -159,6 +159,22 @@ RTC_STRUCTURE_BRACKET, RTC_STRUCTURE_BRACKET_SWAPPED = 4, 5
 RTC_STRUCTURE_PERIODIC, RTC_STRUCTURE_PERIODIC_SWAPPED = 6, 7
 
 
+_lib.rtc_validate_monotone.argtypes = [_vp, _i64, _i64, _i64, _int, _vp, _vp, _vp]
+_lib.rtc_validate_monotone.restype = _int
+RTC_FLAG_NOT_MONOTONE = 8
+
+
+def rtc_validate_monotone(f, dev_flags=None):
+    """(first_bad, dev_flags): per row the first index i with f[i+1] < f[i] or -1; the flag word gets
+    RTC_FLAG_NOT_MONOTONE when there is one."""
+    f, batch, n, stride = _rows(f)
+    if dev_flags is None:
+        dev_flags = torch.zeros(1, dtype=torch.int32, device=f.device)
+    first_bad = torch.empty(batch, dtype=torch.int32, device=f.device)
+    _check(_lib.rtc_validate_monotone(_ptr(f), batch, n, stride, _DT[f.dtype], _ptr(first_bad), _ptr(dev_flags), _stream()))
+    return first_bad, dev_flags
+
+
 def rtc_product_periods(op: int, f, g):
     """(codes, periods) per row pair: rtc_product_structure plus the periodic path's window length."""
     f, bf, n, _ = _rows(f)

@@ -87,6 +87,12 @@ def test_other_entry_points_reject_bad_arguments(lib):
     lib.rtc_max_vdev.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
                                  ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]
     assert lib.rtc_max_vdev(p, p, p, 1, 8, 5, None) == -3
+    lib.rtc_validate_monotone.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
+                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    assert lib.rtc_validate_monotone(p, 1, 8, 8, 0, None, None, None) == -1    # the flag word is required
+    assert lib.rtc_validate_monotone(p, 2, 8, 4, 0, None, p, None) == -5
+    assert lib.rtc_validate_monotone(p, 2, 8, 8, 7, None, p, None) == -3
+    assert lib.rtc_validate_monotone(p, 2, 0, 8, 0, None, p, None) == -2
     lib.rtc_gpc_step.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
     assert lib.rtc_gpc_step(None, None) == -1
     lib.rtc_product_structure.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,

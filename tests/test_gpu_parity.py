@@ -397,6 +397,35 @@ def test_deviations(rtc, dtype):
         assert np.array_equal(v, oracle.max_vdev(alpha, beta))
 
 
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_validate_monotone(rtc, dtype):
+    """The debug check of the precondition that the inverse, the composition and the deviations do not
+    check: expectation straight from the definition (first index whose successor is smaller)."""
+    rng = np.random.default_rng(99)
+    for n in (1, 2, 255, 256, 257, 5000):
+        f = wl.random_monotone(15, n, 9, n, dtype, max_inc=5)
+        want = np.full(9, -1, dtype=np.int32)
+        if n >= 2:
+            for row in (1, 4, 8):                      # plant one to three decreases in three rows
+                at = np.sort(rng.integers(0, n - 1, size=1 + row % 3))
+                for i in at[::-1]:
+                    f[row, i + 1 :] -= 7 + f[row, i + 1] - f[row, i]   # a drop by 7 at i, the rest shifted alike
+                want[row] = at[0]
+            f[8, n - 1] = f[8, n - 2] - 1              # and one at the very end of a row
+            want[8] = min(want[8], n - 2)
+        for i in range(9):
+            d = np.nonzero(f[i, 1:] < f[i, :-1])[0]
+            assert want[i] == (d[0] if d.size else -1)
+        say("validate_monotone", dtype, n)
+        first_bad, flags = rtc.rtc_validate_monotone(dev(f))
+        assert np.array_equal(host(first_bad), want)
+        assert int(host(flags)[0]) == (8 if n >= 2 else 0)
+        first_bad, flags = rtc.rtc_validate_monotone(dev(f[0]))    # one clean row
+        assert host(first_bad)[0] == -1 and int(host(flags)[0]) == 0
+        first_bad, flags = rtc.rtc_validate_monotone(dev(f)[::2])  # strided rows 0 2 4 6 8
+        assert np.array_equal(host(first_bad), want[::2])
+
+
 def test_host_validation_on_device_pointers(rtc):
     f = torch.zeros((2, 64), dtype=torch.int32, device="cuda")
     with pytest.raises(rtc.RtcError) as e:
