@@ -609,7 +609,9 @@ def main():
                   rtc.RTC_PROFILE_KIND(0, 0, 0): "tropical_kernel<int32, min-plus>",
                   rtc.RTC_PROFILE_KIND(0, 0, 1): "tropical_kernel<int32, max-plus>",
                   rtc.RTC_PROFILE_KIND(1, 0, 0): "tropical_kernel<int64, min-plus>",
-                  rtc.RTC_PROFILE_KIND(1, 0, 1): "tropical_kernel<int64, max-plus>"}
+                  rtc.RTC_PROFILE_KIND(1, 0, 1): "tropical_kernel<int64, max-plus>",
+                  rtc.RTC_PROFILE_KIND(2, 0, 0): "tropical_kernel<fp64, min-plus>",
+                  rtc.RTC_PROFILE_KIND(2, 0, 1): "tropical_kernel<fp64, max-plus>"}
     per_kind = {}
     for kind, ms in kernel_times:
         per_kind.setdefault(kind_names.get(kind, str(kind)), []).append(ms)
