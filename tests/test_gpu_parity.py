@@ -426,6 +426,28 @@ def test_validate_monotone(rtc, dtype):
         assert np.array_equal(host(first_bad), want[::2])
 
 
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_burst_delay_curves_shift(rtc, dtype):
+    """Products with delta_T (0 up to T, a value above every sum beyond) delay or advance the other,
+    nondecreasing operand by T: a closed form that needs no oracle, over several tiles and a ragged
+    tail, the jump also beyond 32 bits for int64 rows."""
+    n = 5000
+    f = wl.random_monotone(17, n, 4, n, dtype, max_inc=6)
+    t = np.arange(n)
+    for T, big in ((0, 1 << 20), (1, 1 << 20), (777, 1 << 20), (4999, 1 << 20), (1500, 1 << 40)):
+        if big > 1 << 30 and np.dtype(dtype) == np.int32:
+            continue
+        delta = np.broadcast_to(np.where(t <= T, 0, big).astype(dtype), f.shape).copy()
+        say("burst delay", dtype, T, big)
+        delayed, advanced = f[:, np.maximum(t - T, 0)], f[:, np.minimum(t + T, n - 1)]
+        assert np.array_equal(host(rtc.rtc_minplus_conv(dev(f), dev(delta))), delayed)
+        assert np.array_equal(host(rtc.rtc_minplus_conv(dev(delta), dev(f))), delayed)
+        assert np.array_equal(host(rtc.rtc_maxplus_deconv(dev(f), dev(delta))), advanced)
+        assert np.array_equal(host(rtc.rtc_maxplus_conv(dev(-f), dev(-delta))), -delayed)
+        assert np.array_equal(host(rtc.rtc_minplus_deconv(dev(-f), dev(-delta))), -advanced)
+        assert np.array_equal(oracle.minplus_conv(f, delta), delayed)
+
+
 def test_host_validation_on_device_pointers(rtc):
     f = torch.zeros((2, 64), dtype=torch.int32, device="cuda")
     with pytest.raises(rtc.RtcError) as e:

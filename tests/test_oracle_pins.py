@@ -224,6 +224,28 @@ def test_conv_identity_and_zero_curve(dtype):
     assert np.array_equal(oracle.minplus_conv(wild, zero)[0], np.minimum.accumulate(wild))
 
 
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_products_with_a_burst_delay_curve_shift_the_other_operand(dtype):
+    """delta_T (0 up to T, 'infinite' beyond; here a finite value above every sum) delays a
+    nondecreasing curve by T under the convolution and advances it by T, inside the horizon, under
+    the deconvolution: (f (x) delta_T)[t] = f[max(t - T, 0)], (f (/) delta_T)[t] = f[min(t + T, n - 1)].
+    A reversed or transposed operand index anywhere in the oracle shifts the wrong way."""
+    rng = np.random.default_rng(27)
+    n = 150
+    f = _curve(rng, n, dtype)
+    big = dtype(1 << 20)                                   # far above f's values, far below overflow
+    assert float(f[-1]) * 2 < float(big)
+    t = np.arange(n)
+    for T in (0, 1, 37, n - 1):
+        delta = np.where(t <= T, 0, big).astype(dtype)
+        assert np.array_equal(oracle.minplus_conv(f, delta)[0], f[np.maximum(t - T, 0)])
+        assert np.array_equal(oracle.minplus_conv(delta, f)[0], f[np.maximum(t - T, 0)])
+        assert np.array_equal(oracle.maxplus_deconv(f, delta)[0], f[np.minimum(t + T, n - 1)])
+        # the duals do the same to a nonincreasing curve (here -f) with -delta_T
+        assert np.array_equal(oracle.maxplus_conv(-f, -delta)[0], -f[np.maximum(t - T, 0)])
+        assert np.array_equal(oracle.minplus_deconv(-f, -delta)[0], -f[np.minimum(t + T, n - 1)])
+
+
 @pytest.mark.parametrize("dtype", [np.int32, np.int64])
 def test_deconv_duality(dtype):
     rng = np.random.default_rng(24)
