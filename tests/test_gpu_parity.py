@@ -893,3 +893,36 @@ def test_conv_chain(rtc, dtype):
 def test_half_float_minmax_is_integer_minmax_on_this_device(rtc):
     """The 15-bit packed flavour relies on it; the kernel checks every pattern below 0x7C00."""
     assert rtc.rtc_selftest_half_minmax() == 0
+
+
+# ---------------------------------------------------------------------------
+# measurement aids of the boundary
+# ---------------------------------------------------------------------------
+def test_device_info_and_kernel_timing_record(rtc):
+    """rtc_device_info reports the device the roofline is derived from; the timing record holds one
+    entry per product kernel launched while it is enabled, of the documented kinds, and none after
+    it is stopped."""
+    info = rtc.rtc_device_info()
+    props = torch.cuda.get_device_properties(0)
+    assert info["cu_count"] == props.multi_processor_count and info["clock_khz"] > 100000
+    assert info["lds_bytes"] >= 64 * 1024
+    f = dev(wl.random_monotone(18, 3000, 3, 3000, np.int32, max_inc=5))
+    say("timing record")
+    try:
+        rtc.rtc_profile_enable(True)
+        rtc.rtc_minplus_conv(f, f)
+        rtc.rtc_maxplus_deconv(f, f)
+        got = rtc.rtc_profile_read()
+    finally:
+        rtc.rtc_profile_enable(False)
+    kinds = {k for k, _ in got}
+    conv_kinds = {rtc.RTC_PROFILE_KIND(0, p, 0) for p in (0, 1)}
+    deconv_kinds = {rtc.RTC_PROFILE_KIND(0, p, 1) for p in (0, 1)}
+    assert kinds & conv_kinds and kinds & deconv_kinds and kinds <= conv_kinds | deconv_kinds
+    assert all(0.0 < ms < 1000.0 for _, ms in got)
+    rtc.rtc_minplus_conv(f, f)
+    rtc.rtc_profile_enable(True)          # restarting clears the record; nothing launched since
+    try:
+        assert rtc.rtc_profile_read() == []
+    finally:
+        rtc.rtc_profile_enable(False)
