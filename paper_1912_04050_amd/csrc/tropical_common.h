@@ -235,7 +235,12 @@ __device__ __forceinline__ void load_group(T (&dst)[R], const unsigned char* lds
   }
 }
 
-template <typename T, int R> constexpr int lds_bytes() { return Tile<T, R>::kSlots * Tile<T, R>::kSlotBytes; }
+// Window buffer of one workgroup; tiles of 4 accumulators also stage a chunk of the uniform operand
+// behind it (tropical_body).
+template <typename T, int R> constexpr int window_bytes() { return Tile<T, R>::kSlots * Tile<T, R>::kSlotBytes; }
+template <typename T, int R> constexpr int lds_bytes() {
+  return window_bytes<T, R>() + (R == 4 ? Tile<T, R>::kChunk * (int)sizeof(T) : 0);
+}
 
 }  // namespace
 }  // namespace rtc

@@ -64,11 +64,61 @@ __device__ __forceinline__ void tropical_body(const TropicalArgs& p, unsigned ch
       if (idx >= 0 && idx < n) v = brow[rev ? n - 1 - idx : idx];
       *reinterpret_cast<T*>(lds + (e / R) * TL::kSlotBytes + (e % R) * (int)sizeof(T)) = v;
     }
+    if constexpr (R == 4) {
+      // small tiles also stage the chunk of the uniform operand (see the grouped blocks below)
+      T* ust = reinterpret_cast<T*>(lds + window_bytes<T, R>());
+      if (!aux)
+        for (int e = lane; e < nblk * R; e += 64) ust[e] = arow[min(sc + e, n - 1)];
+    }
     __syncthreads();
 
     T w0[R], w1[R];
     load_group<T, R>(w0, lds, lane + nblk);
-    for (int i = 0; i < nblk; i += 2) {
+    int i = 0;
+    if constexpr (R == 4) {
+      // Small tiles: a block is only 16 candidates per lane, and a problem that takes them has about
+      // one wavefront per CU, so nothing hides the loads that every block waits for: a scalar load
+      // of the uniform operand that misses the scalar cache once per 64 bytes, and an LDS read.
+      // Here the chunk of the uniform operand was staged in LDS with the window (all its cache
+      // misses in flight at once), and four blocks are taken at a time: their 16 operand values and
+      // four window groups are read together, with one wait for all.  Each block keeps its own
+      // conditions (inside the row; from the tile's first output on, only the lanes behind it).
+      if (!aux) {
+        typedef T Vec __attribute__((ext_vector_type(TL::kVec)));
+        const T* ust = reinterpret_cast<const T*>(lds + window_bytes<T, R>());
+        for (; i + 4 <= nblk; i += 4) {
+          T ug[4 * R], wa[R], wb[R], wc[R], wd[R];
+          const Vec* up = reinterpret_cast<const Vec*>(ust + i * R);
+#pragma unroll
+          for (int q = 0; q < 4 * R / TL::kVec; ++q) {
+            const Vec v = up[q];
+#pragma unroll
+            for (int e = 0; e < TL::kVec; ++e) ug[q * TL::kVec + e] = v[e];
+          }
+          load_group<T, R>(wa, lds, lane + nblk - i - 1);
+          load_group<T, R>(wb, lds, lane + nblk - i - 2);
+          load_group<T, R>(wc, lds, lane + nblk - i - 3);
+          load_group<T, R>(wd, lds, lane + nblk - i - 4);
+          T u0[R], u1[R], u2[R], u3[R];
+#pragma unroll
+          for (int k = 0; k < R; ++k) { u0[k] = ug[k]; u1[k] = ug[R + k]; u2[k] = ug[2 * R + k]; u3[k] = ug[3 * R + k]; }
+          auto one = [&](int b, const T (&u)[R], const T (&lo)[R], const T (&hi)[R]) {
+            const int s0 = sc + (i + b) * R;
+            const int j = (s0 >= t0) ? (s0 - t0) / R : -1;
+            if (j < 0 || (s0 + R < n && j < 63)) {
+              if (lane > j) block_steps<SR, T, R>(acc, u, lo, hi);
+            }
+          };
+          one(0, u0, wa, w0);
+          one(1, u1, wb, wa);
+          one(2, u2, wc, wb);
+          one(3, u3, wd, wc);
+#pragma unroll
+          for (int k = 0; k < R; ++k) w0[k] = wd[k];
+        }
+      }
+    }
+    for (; i < nblk; i += 2) {
       {
         const int s0 = sc + i * R;
         load_group<T, R>(w1, lds, lane + nblk - i - 1);
@@ -123,7 +173,7 @@ __device__ __forceinline__ void tropical_body(const TropicalArgs& p, unsigned ch
       p.cap ? static_cast<const OutT*>(p.cap) + (int64_t)row * n : nullptr;
   // Transpose the accumulators through LDS (lane-major [lane][R+1] -> output-major) so that
   // the 64 lanes of one store / atomic instruction touch 64 consecutive outputs.
-  static_assert(64 * (R + 1) * sizeof(T) <= lds_bytes<T, R>(), "transpose buffer must fit the window buffer");
+  static_assert(64 * (R + 1) * sizeof(T) <= window_bytes<T, R>(), "transpose buffer must fit the window buffer");
   T* xp = reinterpret_cast<T*>(lds);
   __syncthreads();
 #pragma unroll
