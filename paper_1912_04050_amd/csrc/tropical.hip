@@ -414,7 +414,10 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
   int64_t* tab = reinterpret_cast<int64_t*>(static_cast<char*>(ws) + narrow_tables_offset(batch, n));
   const int nb = wide_blocks(n);
   const Plan pw = make_plan<int32_t, kWideR>(batch, n);
-  const bool rebase = g_rebase_wide >= 1 && n > kWideBlock && pw.items <= 0x7fffffffLL;
+  // (not for problems so small that the launches themselves are the cost: their rows stay with
+  // the 64-bit kernel, which the same criterion gives small tiles)
+  const bool small = make_plan<int64_t, RFor<int64_t>::value>(batch, n).items < g_small_items;
+  const bool rebase = g_rebase_wide >= 1 && n > kWideBlock && pw.items <= 0x7fffffffLL && !small;
   if (rebase) {
     hipLaunchKernelGGL(wide_tables_kernel<OP>, dim3((uint32_t)batch), dim3(kWideThreads), 0, stream,
                        static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g, ok, tab,
