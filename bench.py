@@ -54,7 +54,7 @@ def parse():
 # HBM traffic of one launch of the dominant kernel on the headline workload, from two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by what the same counters read for a
 # plain 1 GiB device copy; see profiles/.  None for any other workload.
-HEADLINE_TRAFFIC_BYTES = 649716044   # fetched + 532 MiB of atomic-merge writes (profiles/fused_kernel_headline_pmc.md)
+HEADLINE_TRAFFIC_BYTES = 649751657   # fetched + 532 MiB of atomic-merge writes (profiles/fused_kernel_headline_pmc.md)
 
 
 def headline_traffic(batch, n):

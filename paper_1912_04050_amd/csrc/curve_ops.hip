@@ -210,36 +210,67 @@ __device__ __forceinline__ T wave_scan(T v) {
   return v;
 }
 
-// Remaining service of a greedy processing component, one workgroup per row:
+// Remaining service of a greedy processing component:
 //   SUFFIX = false: out[D] = max(0, max_{l<=D} beta[l] - alpha[l])   (beta^l, alpha^u -> beta'^l)
 //   SUFFIX = true : out[D] = max(0, min_{l>=D} beta[l] - alpha[l])   (beta^u, alpha^l -> beta'^u)
+// `parts` workgroups per row (few rows would otherwise leave most CUs idle): each scans one segment
+// of the row in scan order, after reducing everything before its segment itself (maximum and
+// minimum are exact and order-free, so the extra reads cost time only, and no workgroup waits for
+// another).  seg = segment length, a multiple of the 4096 positions one pass covers.
 template <typename T, bool SUFFIX>
 __global__ __launch_bounds__(1024) void residual_service_kernel(const T* __restrict__ beta,
                                                                 const T* __restrict__ alpha,
-                                                                T* __restrict__ out, int n) {
+                                                                T* __restrict__ out, int n, int parts, int seg) {
   using S = ScanOp<T, SUFFIX>;
   constexpr int kPer = 4;
   __shared__ T wave_tot[16];
   __shared__ T carry_s;
-  const int row = blockIdx.x;
+  const int row = blockIdx.x / parts, part = blockIdx.x % parts;
+  const int start = part * seg;
+  if (start >= n) return;
+  const int end = min(n, start + seg);
   const T* bl = beta + (int64_t)row * n;
   const T* au = alpha + (int64_t)row * n;
   T* o = out + (int64_t)row * n;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   T carry = S::id();
-  for (int base = 0; base < n; base += 1024 * kPer) {
+  if (start > 0) {
+    // everything before the segment; the loads of eight passes are independent and in flight together
+    T acc = S::id();
+#pragma unroll 8
+    for (int p = threadIdx.x; p < start; p += 1024) {
+      const int i = SUFFIX ? n - 1 - p : p;
+      acc = S::op(acc, (T)(bl[i] - au[i]));
+    }
+    const T incl = wave_scan<T, SUFFIX>(acc);
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < 16; ++w) carry = S::op(carry, wave_tot[w]);
+    __syncthreads();
+  }
+  // the differences of one pass, loaded one pass ahead of their use
+  auto load = [&](int base, T (&d)[kPer]) {
+#pragma unroll
+    for (int e = 0; e < kPer; ++e) {
+      const int p = base + threadIdx.x * kPer + e;
+      const int i = SUFFIX ? n - 1 - p : p;
+      // the difference may be negative; inputs obey the no-overflow precondition
+      d[e] = p < n ? (T)(bl[i] - au[i]) : S::id();
+    }
+  };
+  T next[kPer];
+  load(start, next);
+  for (int base = start; base < end; base += 1024 * kPer) {
     const int p0 = base + threadIdx.x * kPer;   // position in scan order
     T v[kPer];
     T run = S::id();
 #pragma unroll
     for (int e = 0; e < kPer; ++e) {
-      const int p = p0 + e;
-      const int i = SUFFIX ? n - 1 - p : p;
-      // the difference may be negative; inputs obey the no-overflow precondition
-      const T d = p < n ? (T)(bl[i] - au[i]) : S::id();
-      run = S::op(run, d);
+      run = S::op(run, next[e]);
       v[e] = run;
     }
+    if (base + 1024 * kPer < end) load(base + 1024 * kPer, next);
     const T incl = wave_scan<T, SUFFIX>(run);
     if (lane == 63) wave_tot[wave] = incl;
     __syncthreads();
@@ -411,13 +442,32 @@ int launch_compose(const void* outer, int64_t n_outer, const int32_t* inner, int
 
 int launch_residual_service(const void* beta, const void* alpha, void* out, int64_t batch,
                             int64_t n, int dt, bool suffix_min, hipStream_t stream) {
+  // Several workgroups per row when the rows alone would not fill the chip.  A workgroup's passes
+  // over its segment are bound by latency (about 3.3 us each, measured), the whole launch by its
+  // traffic: 3 arrays, plus (parts - 1) more for what the workgroups re-read before their segments
+  // (at about 3.5 TB/s).  Take the power of two that minimises the larger of the two.
+  int64_t parts = 1;
+  {
+    const double array_bytes = (double)batch * (double)n * (dt == RTC_I32 ? 4.0 : 8.0);
+    double best = 1e300;
+    for (int64_t p = 1; p <= 16 && (p == 1 || (batch * p <= 512 && n / p >= 8192)); p *= 2) {
+      const double latency_us = (double)((n + p * 4096 - 1) / (p * 4096)) * 3.3;
+      const double traffic_us = (2.0 + (double)p) * array_bytes / 3.5e6;
+      const double t = latency_us > traffic_us ? latency_us : traffic_us;
+      if (t < best) { best = t; parts = p; }
+    }
+  }
+  const int64_t seg = ((n + parts - 1) / parts + 4095) / 4096 * 4096;
+  if (batch * parts > 0x7fffffffLL) return RTC_ERR_SHAPE;
   RTC_DISPATCH(dt, {
     if (suffix_min)
-      hipLaunchKernelGGL((residual_service_kernel<T, true>), dim3((uint32_t)batch), dim3(1024), 0, stream,
-                         static_cast<const T*>(beta), static_cast<const T*>(alpha), static_cast<T*>(out), (int)n);
+      hipLaunchKernelGGL((residual_service_kernel<T, true>), dim3((uint32_t)(batch * parts)), dim3(1024), 0, stream,
+                         static_cast<const T*>(beta), static_cast<const T*>(alpha), static_cast<T*>(out), (int)n,
+                         (int)parts, (int)seg);
     else
-      hipLaunchKernelGGL((residual_service_kernel<T, false>), dim3((uint32_t)batch), dim3(1024), 0, stream,
-                         static_cast<const T*>(beta), static_cast<const T*>(alpha), static_cast<T*>(out), (int)n);
+      hipLaunchKernelGGL((residual_service_kernel<T, false>), dim3((uint32_t)(batch * parts)), dim3(1024), 0, stream,
+                         static_cast<const T*>(beta), static_cast<const T*>(alpha), static_cast<T*>(out), (int)n,
+                         (int)parts, (int)seg);
     return hip_ok();
   });
 }

@@ -383,6 +383,26 @@ def test_gpc_step_both_sides(rtc, dtype):
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
+def test_component_step_long_rows_few_pairs(rtc, dtype):
+    """Few long rows: the remaining-service scans split a row over several workgroups (each reduces
+    what lies before its segment itself); both sides of the component against the oracle, with the
+    extremum of the difference placed early, late and at a segment boundary."""
+    for batch, n, jumps in ((1, 16384, (8192,)), (3, 20001, (5, 19998, 12288)), (2, 70000, (12287, 69997))):
+        alpha_u = wl.random_monotone(19, n, batch, n, dtype, max_inc=4)
+        beta_l = wl.random_monotone(20, n + 1, batch, n, dtype, max_inc=4, start_max=0)
+        beta_u = beta_l + wl.random_monotone(21, n + 2, batch, n, dtype, max_inc=2)
+        alpha_l = alpha_u // 2 if np.dtype(dtype) != np.float64 else alpha_u / 2
+        for row, at in zip(range(batch), jumps):
+            beta_l[row, at:] += 1000           # a jump of beta - alpha at a chosen place
+            beta_u[row, at:] += 1000
+        say("component step, long rows", dtype, batch, n)
+        got = rtc.rtc_gpc_step(dev(alpha_u), dev(beta_u), dev(beta_l), alpha_l=dev(np.ascontiguousarray(alpha_l)))
+        want = (*oracle.gpc_step(alpha_u, beta_u, beta_l), *oracle.gpc_step_lower(np.ascontiguousarray(alpha_l), beta_u, beta_l))
+        for name, g, w in zip(("alpha_u'", "beta_l'", "alpha_l'", "beta_u'"), got, want):
+            assert np.array_equal(host(g), w), name
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
 def test_deviations(rtc, dtype):
     for n in (1, 77, 5000):
         alpha = wl.random_monotone(14, n, 4, n, dtype, max_inc=5)
