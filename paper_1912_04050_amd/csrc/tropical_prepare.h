@@ -80,13 +80,30 @@ __global__ __launch_bounds__(1024) void probe_kernel(const T* __restrict__ f, in
   const T* gr = g + (int64_t)row * stride_g;
   T fmin = Lim<T>::hi(), fmax = Lim<T>::lo(), gmin = Lim<T>::hi(), gmax = Lim<T>::lo();
   int bits = classify ? 15 : 0;
-  for (int i = threadIdx.x; i < n; i += blockDim.x) {
-    const T fv = fr[i], gv = gr[i];
-    fmin = sel_min(fmin, fv); fmax = sel_max(fmax, fv);
-    gmin = sel_min(gmin, gv); gmax = sel_max(gmax, gv);
+  // four strides per trip, their loads in flight together: with few rows one workgroup walks a long
+  // row alone and every trip is a round trip to memory
+  for (int i0 = threadIdx.x; i0 < n; i0 += 4 * blockDim.x) {
+    T fv[4], gv[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int i = min(i0 + k * (int)blockDim.x, n - 1);   // a repeated sample changes no extremum
+      fv[k] = fr[i]; gv[k] = gr[i];
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      fmin = sel_min(fmin, fv[k]); fmax = sel_max(fmax, fv[k]);
+      gmin = sel_min(gmin, gv[k]); gmax = sel_max(gmax, gv[k]);
+    }
     if constexpr (std::numeric_limits<T>::is_integer) {
-      if (sel != nullptr && bits != 0 && i >= 1 && i <= n - 2)
-        bits &= second_diff_bits(fr, i) | (second_diff_bits(gr, i) << 2);
+      if (sel != nullptr && bits != 0) {
+        int b[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int i = min(max(i0 + k * (int)blockDim.x, 1), n - 2);   // interior samples only; needs n >= 3
+          b[k] = n >= 3 ? second_diff_bits(fr, i) | (second_diff_bits(gr, i) << 2) : 15;
+        }
+        bits &= b[0] & b[1] & b[2] & b[3];
+      }
     }
   }
 #pragma unroll
