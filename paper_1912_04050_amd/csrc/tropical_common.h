@@ -48,8 +48,21 @@ __device__ __forceinline__ int32_t sel_min(int32_t a, int32_t b) { return b < a 
 __device__ __forceinline__ int32_t sel_max(int32_t a, int32_t b) { return b > a ? b : a; }
 __device__ __forceinline__ int64_t sel_min(int64_t a, int64_t b) { return b < a ? b : a; }
 __device__ __forceinline__ int64_t sel_max(int64_t a, int64_t b) { return b > a ? b : a; }
-__device__ __forceinline__ double sel_min(double a, double b) { return __builtin_fmin(a, b); }
-__device__ __forceinline__ double sel_max(double a, double b) { return __builtin_fmax(a, b); }
+// fp64: the instruction itself.  Written through the compiler's fmin / fmax, every accumulator is
+// first re-canonicalised (x = max(x, x)) wherever it enters a basic block, 16 of 528 instructions
+// per block of the product kernel, only so that a signalling NaN would be ignored rather than
+// quieted; inputs are finite by contract, a quiet NaN is still ignored, and all other values give
+// the same bits.
+__device__ __forceinline__ double sel_min(double a, double b) {
+  double r;
+  asm("v_min_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+__device__ __forceinline__ double sel_max(double a, double b) {
+  double r;
+  asm("v_max_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
 
 // The semiring of one product: identity of REDUCE, COMBINE(window, uniform), REDUCE.
 // OP selects the product (the values of rtc_op for the four products):
