@@ -146,7 +146,7 @@ def per_config_table(seed, peak_ops, with_cpu, configs=(1, 2, 3, 4, 5)):
             # which kernels did the rows take?  Rows on a structure-exploiting path execute fewer
             # candidates than the definition counts: their rate is an equivalent, and the same
             # call is timed again with those paths switched off
-            if f.dtype != torch.float64 and B * N * N >= 2 ** 30:
+            if f.dtype != torch.float64 and B * N * N >= rtc.RTC_DEFAULT_PACKED_MIN_WORK:
                 paths = {}
                 codes, periods = rtc.rtc_product_periods(op_codes[name], f, g)
                 codes, periods = codes.cpu().numpy(), periods.cpu().numpy().astype(np.int64)

@@ -248,10 +248,13 @@ int rtc_product_structure(int op, const void* f, const void* g, int32_t* codes, 
 int rtc_product_periods(int op, const void* f, const void* g, int32_t* codes, int32_t* periods, int64_t batch,
                         int64_t n, int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* hip_stream);
 
-/* Planner knob: the packed 16-bit path of the int32 / narrowed-int64 products is used when a
- * workspace is present and batch * n^2 >= this value (default 2^30; smaller problems are
- * launch-bound and take the 32-bit kernel alone).  0 uses it for every size.  Results do not
+/* Planner knob: the packed 16-bit path of the int32 / narrowed-int64 products, and with it the
+ * detection of convex, concave and periodic rows, is used when a workspace is present and
+ * batch * n^2 >= this value (default RTC_DEFAULT_PACKED_MIN_WORK = 2^33, the measured break-even
+ * on MI355X: below it the probes and preparation kernels cost more than the faster kernel
+ * gains, and the 32-bit kernel alone is quicker).  0 uses it for every size.  Results do not
  * depend on it.  Process-wide, not thread-safe. */
+#define RTC_DEFAULT_PACKED_MIN_WORK 8589934592
 int rtc_set_packed_min_work(double batch_times_n_squared);
 
 /* Planner knob: rows of at most this many samples give the packed work items tiles of 1024

@@ -308,7 +308,7 @@ int run_packed(const int32_t* f32, int64_t stride_f, const int32_t* g32, int64_t
 
 }  // namespace
 
-double g_packed_min_work = 1073741824.0;   // batch * n^2 from which the packed path is used
+double g_packed_min_work = (double)RTC_DEFAULT_PACKED_MIN_WORK;   // batch * n^2 from which the packed path is used
 
 namespace {
 

@@ -134,6 +134,9 @@ _lib.rtc_set_packed_min_work.argtypes = [ctypes.c_double]
 _lib.rtc_set_packed_min_work.restype = _int
 
 
+RTC_DEFAULT_PACKED_MIN_WORK = 2 ** 33
+
+
 def rtc_set_packed_min_work(batch_times_n_squared: float):
     _check(_lib.rtc_set_packed_min_work(float(batch_times_n_squared)))
 

@@ -86,4 +86,4 @@ def test_products_and_component_step_replay_in_a_graph(dtype):
             # the program's own eager work between replays
             assert np.array_equal(host(rtc.rtc_minplus_conv(f, g)), oracle.minplus_conv(f_new, g_new))
     finally:
-        rtc.rtc_set_packed_min_work(2.0 ** 30)
+        rtc.rtc_set_packed_min_work(rtc.RTC_DEFAULT_PACKED_MIN_WORK)

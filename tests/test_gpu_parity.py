@@ -33,7 +33,7 @@ def rtc(request):
         mod.rtc_set_packed_small_n(0 if request.param == "packed-wide-tiles" else 1 << 24)
         mod.rtc_set_small_problem_items(0)      # the generic kernel keeps its large tiles whatever the size
     yield mod
-    mod.rtc_set_packed_min_work(2.0 ** 30)
+    mod.rtc_set_packed_min_work(mod.RTC_DEFAULT_PACKED_MIN_WORK)
     mod.rtc_set_packed_small_n(default_small_n)
     mod.rtc_set_small_problem_items(256)
 

@@ -20,7 +20,7 @@ def rtc(request):
         mod.rtc_set_packed_min_work(0.0)
         mod.rtc_set_small_problem_items(0)      # and the generic kernel's large tiles for every size
     yield mod
-    mod.rtc_set_packed_min_work(2.0 ** 30)
+    mod.rtc_set_packed_min_work(mod.RTC_DEFAULT_PACKED_MIN_WORK)
     mod.rtc_set_small_problem_items(256)
 
 
