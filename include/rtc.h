@@ -264,10 +264,13 @@ int rtc_set_packed_min_work(double batch_times_n_squared);
 int rtc_set_packed_small_n(int64_t n);
 
 /* Planner knob: a product that the general kernel would cut into fewer work items than this
- * (default 256, the number of CUs: e.g. one pair of 4096 samples gives 10) runs with tiles of 256
- * outputs and chunks of 256 steps instead of 1024 x 1024, which costs more instructions per
- * candidate and finishes sooner because more CUs take part.  0 never does.  Results do not depend
- * on it.  Process-wide, not thread-safe.  RTC_ERR_SHAPE for a negative value. */
+ * (default RTC_DEFAULT_SMALL_PROBLEM_ITEMS = 8192, eight wavefronts per SIMD of the chip, measured:
+ * one pair of 4096 samples gives 10, one of 65536 gives 2080) runs with tiles of 256 outputs and
+ * chunks of 256 steps instead of 1024 x 1024, which costs more instructions per candidate and
+ * finishes sooner because more CUs take part and more wavefronts hide each other's waits.  0 never
+ * does.  Results do not depend on it.  Process-wide, not thread-safe.  RTC_ERR_SHAPE for a negative
+ * value. */
+#define RTC_DEFAULT_SMALL_PROBLEM_ITEMS 8192
 int rtc_set_small_problem_items(int64_t items);
 
 /* Planner knob for int64 row pairs whose values span 2^30 or more (too wide to be narrowed to

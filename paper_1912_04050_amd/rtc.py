@@ -218,6 +218,9 @@ _lib.rtc_set_small_problem_items.argtypes = [_i64]
 _lib.rtc_set_small_problem_items.restype = _int
 
 
+RTC_DEFAULT_SMALL_PROBLEM_ITEMS = 8192
+
+
 def rtc_set_small_problem_items(items: int):
     _check(_lib.rtc_set_small_problem_items(int(items)))
 

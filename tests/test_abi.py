@@ -108,7 +108,7 @@ def test_other_entry_points_reject_bad_arguments(lib):
     assert lib.rtc_set_packed_small_n(4096) == 0
     lib.rtc_set_small_problem_items.argtypes = [ctypes.c_int64]
     assert lib.rtc_set_small_problem_items(-1) == -2
-    assert lib.rtc_set_small_problem_items(256) == 0
+    assert lib.rtc_set_small_problem_items(8192) == 0
     assert lib.rtc_set_structure_paths(1) == 0
     lib.rtc_product_periods.argtypes = [ctypes.c_int] + [ctypes.c_void_p] * 4 + [ctypes.c_int64] * 4 + [ctypes.c_int, ctypes.c_void_p]
     assert lib.rtc_product_periods(0, p, p, None, p, 1, 8, 8, 8, 0, None) == -1      # codes are required

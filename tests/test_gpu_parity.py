@@ -35,7 +35,7 @@ def rtc(request):
     yield mod
     mod.rtc_set_packed_min_work(mod.RTC_DEFAULT_PACKED_MIN_WORK)
     mod.rtc_set_packed_small_n(default_small_n)
-    mod.rtc_set_small_problem_items(256)
+    mod.rtc_set_small_problem_items(mod.RTC_DEFAULT_SMALL_PROBLEM_ITEMS)
 
 
 def say(*a):

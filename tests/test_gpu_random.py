@@ -21,7 +21,7 @@ def rtc(request):
         mod.rtc_set_small_problem_items(0)      # and the generic kernel's large tiles for every size
     yield mod
     mod.rtc_set_packed_min_work(mod.RTC_DEFAULT_PACKED_MIN_WORK)
-    mod.rtc_set_small_problem_items(256)
+    mod.rtc_set_small_problem_items(mod.RTC_DEFAULT_SMALL_PROBLEM_ITEMS)
 
 
 def dev(a):
