@@ -293,6 +293,22 @@ int rtc_set_rebase_wide(int mode);
  * do not depend on it.  Process-wide, not thread-safe. */
 int rtc_set_structure_paths(int enabled);
 
+/* rtc_minplus_conv for callers that cannot allocate device memory: code running under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * status codes as rtc_minplus_conv, without ws / ws_bytes: the workspace is a device array of
+ * RTC_STATIC_SCRATCH_BYTES inside the library (each GPU the library runs on holds it until the
+ * process ends), and the call allocates and frees nothing.  A shape whose
+ * rtc_workspace_bytes(RTC_OP_CONV, batch, n, dt) exceeds RTC_STATIC_SCRATCH_BYTES returns
+ * RTC_ERR_WORKSPACE and launches nothing (int32: batch * n up to about 1.1 million samples,
+ * int64: about 0.9 million; fp64 needs no workspace and is never refused for it).
+ * All calls on one GPU share that array: calls that overlap in time on one GPU (different streams,
+ * or different host threads) race and give undefined results; calls ordered on one stream are safe.
+ * Nothing in the array has to be cleared between calls. */
+#define RTC_STATIC_SCRATCH_BYTES (32 << 20)
+int rtc_minplus_conv_static(const void* f, const void* g, void* out, int64_t batch, int64_t n,
+                            int64_t stride_f, int64_t stride_g, rtc_dtype dt, int32_t* dev_flags,
+                            void* hip_stream);
+
 /* Bytes of device workspace an operator needs for the given shape (0 on invalid input). */
 size_t rtc_workspace_bytes(int op, int64_t batch, int64_t n, rtc_dtype dt);
 

@@ -285,6 +285,25 @@ def rtc_minplus_conv(f, g, out=None, ws=None, dev_flags=None):
     return _product(_lib.rtc_minplus_conv, RTC_OP_CONV, f, g, out, ws, dev_flags)
 
 
+_lib.rtc_minplus_conv_static.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _int, _vp, _vp]
+_lib.rtc_minplus_conv_static.restype = _int
+RTC_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def rtc_minplus_conv_static(f, g, out, dev_flags=None):
+    """rtc_minplus_conv on the library's own static workspace; `out` is the caller's ([batch][n])."""
+    f, bf, n, _ = _rows(f)
+    g, bg, ng, _ = _rows(g)
+    if ng != n or f.dtype != g.dtype or (bf != bg and 1 not in (bf, bg)):
+        raise ValueError("operands must have the same length and dtype, batch equal or 1")
+    batch = max(bf, bg)
+    if out.dtype != f.dtype or out.numel() != batch * n or not out.is_contiguous():
+        raise ValueError("out must be a dense [batch][n] tensor of the operands' dtype")
+    _check(_lib.rtc_minplus_conv_static(_ptr(f), _ptr(g), _ptr(out), batch, n, _row_stride(f, bf, batch, n),
+                                        _row_stride(g, bg, batch, n), _DT[f.dtype], _ptr(dev_flags), _stream()))
+    return out
+
+
 def rtc_maxplus_deconv(f, g, out=None, ws=None, dev_flags=None):
     """out[b][t] = max_{0<=u<=n-1-t} f[b][t+u] - g[b][u]."""
     return _product(_lib.rtc_maxplus_deconv, RTC_OP_DECONV, f, g, out, ws, dev_flags)
