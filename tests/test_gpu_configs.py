@@ -1,9 +1,11 @@
 """The five benchmark configurations end to end: HIP path against the CPU oracle, bit-exact.
 
 Reduced sizes run three seeds with every output compared.  Full sizes run in the launch
-configuration the benchmark uses; configurations 1, 2, 3 and 5 are still compared output by
-output (the oracle finishes each in seconds on the GPU machine's cores), configuration 4 is
-compared in full for a subset of chains and by invariants for the rest.
+configuration the benchmark uses and every output of every configuration is compared with the
+oracle (configuration 4: all 256 chains x 16 components, the GPU run once over the whole batch,
+the oracle in eight slices of 32 chains so that each test reports within half a minute);
+only configuration 5's pseudo-inverse, whose linear-scan oracle is quadratic, is compared on
+sampled queries plus the two-sided inequality that fixes every answer.
 """
 import sys
 
@@ -94,19 +96,9 @@ def test_config3_full_int64_storage(rtc):
 
 
 def test_config3_full_native_int32(rtc):
-    say("config3 full, int32 rows, sampled rows")
+    say("config3 full, int32 rows, all 64 rows in full")
     c = wl.config3(wl.DEFAULT_SEED, 64, 65536, np.int32)
-    f, g = c["f"], c["g"]
-    got_c = host(rtc.rtc_minplus_conv(dev(f), dev(g)))
-    got_d = host(rtc.rtc_maxplus_deconv(dev(f), dev(g)))
-    rows = [0, 17, 63]
-    assert np.array_equal(got_c[rows], oracle.minplus_conv(f[rows], g[rows]))
-    assert np.array_equal(got_d[rows], oracle.maxplus_deconv(f[rows], g[rows]))
-    rng = np.random.default_rng(3)
-    for b in range(64):
-        idx = np.unique(np.concatenate([[0, 1023, 1024, 65535], rng.integers(0, 65536, 12)]))
-        assert np.array_equal(got_c[b, idx], oracle.product_at(f[b], g[b], idx, False)), b
-        assert np.array_equal(got_d[b, idx], oracle.product_at(f[b], g[b], idx, True)), b
+    products_equal(rtc, c["f"], c["g"])
 
 
 def run_chain_gpu(rtc, c, chains, components):
@@ -149,14 +141,28 @@ def test_config4_reduced(rtc, seed):
     check_chain_oracle(c, np.arange(6), a0, outs)
 
 
-def test_config4_full(rtc):
-    say("config4 full: 256 chains x 16 components, N=16384")
+@pytest.fixture(scope="module")
+def config4_full(rtc):
+    """Configuration 4 at full size, run once on the GPU over the whole batch of 256 chains (the
+    launch configuration the benchmark times); the tests below compare slices of it."""
     chains, comps = 256, 16
     c = wl.config4(wl.DEFAULT_SEED, chains, comps, 16384)
     a0, outs = run_chain_gpu(rtc, c, chains, comps)
-    rows = np.array([0, 1, 2, 3, 100, 101, 254, 255])
-    say("config4 full: oracle on", len(rows), "chains")
+    return c, a0, outs
+
+
+@pytest.mark.parametrize("part", range(8))
+def test_config4_full(config4_full, part):
+    """Every output of every component of chains 32*part .. 32*part+31 against the oracle:
+    alpha'^u, beta'^l and both event-domain images (the eight parts cover all 256 x 16)."""
+    c, a0, outs = config4_full
+    rows = np.arange(32 * part, 32 * part + 32)
+    say("config4 full: oracle on chains", rows[0], "..", rows[-1])
     check_chain_oracle(c, rows, a0, outs)
+
+
+def test_config4_full_invariants(config4_full):
+    c, a0, outs = config4_full
     gam = c["gamma_u"]
     for i, (au, bl, lo, up) in enumerate(outs):
         assert np.all(au <= c["beta_u"][i]) and np.all(np.diff(au, axis=1) >= 0), i
@@ -166,6 +172,42 @@ def test_config4_full(rtc):
         assert np.all(gam[r[0], lo[r]] >= bl[r])                      # gamma(gamma^-1(x)) >= x
         assert np.all(np.take_along_axis(gam, np.maximum(up, 0), 1)[up >= 0] <= bl[up >= 0])
         assert np.all(up >= lo - 1)
+
+
+def run_chain_bounds(rtc, c, chains, components):
+    """Delay and backlog bounds of a whole chain: the service curves of its components are
+    concatenated (beta_1 (x) beta_2 (x) ...), then the arrival curve's horizontal and vertical
+    deviation from the concatenation, all on the GPU, against the oracle doing the same."""
+    gam, ab = c["gamma_u"][:chains], c["alpha_bar_u"][:chains]
+    curves = np.ascontiguousarray(c["beta_l"][:components, :chains])
+    flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+    a = rtc.rtc_compose(dev(gam), dev(ab), dev_flags=flags)
+    path = rtc.rtc_conv_chain(dev(curves), dev_flags=flags)
+    hflags = torch.zeros(1, dtype=torch.int32, device="cuda")
+    h = host(rtc.rtc_max_hdev(a, path, dev_flags=hflags))
+    v = host(rtc.rtc_max_vdev(a, path))
+    assert int(host(flags)[0]) == 0
+    want_a, _ = oracle.compose(gam, ab)
+    want_path = oracle.conv_chain(curves)
+    assert np.array_equal(host(path), want_path)
+    want_h, fl = oracle.max_hdev(want_a, want_path)
+    assert np.array_equal(h, want_h) and int(host(hflags)[0]) == fl
+    assert np.array_equal(v, oracle.max_vdev(want_a, want_path))
+    # "pay bursts only once": the bound through the concatenation is at most the sum of the
+    # per-component bounds of the same arrival curve
+    per_node = sum(oracle.max_hdev(want_a, curves[i])[0].astype(np.int64) for i in range(components))
+    assert np.all(h <= per_node)
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_chain_bounds_reduced(rtc, seed):
+    say("chain delay / backlog bounds, reduced", seed)
+    run_chain_bounds(rtc, wl.config4(seed, chains=6, components=4, n=2500), 6, 4)
+
+
+def test_chain_bounds_config4_shape(rtc):
+    say("chain delay / backlog bounds, 24 chains x 16 components, N=16384")
+    run_chain_bounds(rtc, wl.config4(wl.DEFAULT_SEED, 24, 16, 16384), 24, 16)
 
 
 def run_config5(rtc, seed, n):
