@@ -96,7 +96,7 @@ __global__ __launch_bounds__(64) void tropical_rows_kernel(const TropicalArgs p,
 // the chunks qualifies for 16 bits.
 // RP = accumulators per lane of the packed items (their tiles are 128 RP outputs wide).
 template <typename OutT, int OP, int RP>
-__global__ __launch_bounds__(64) void fused_kernel(const TropicalArgs pk, const TropicalArgs pg,
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(4, 4))) void fused_kernel(const TropicalArgs pk, const TropicalArgs pg,
                                                    uint32_t n_packed) {
   static_assert(lds_bytes<int32_t, RP>() <= lds_bytes<int32_t, kPkR>(), "the 32-bit layout is the larger one");
   __shared__ __align__(16) unsigned char lds[lds_bytes<int32_t, kPkR>()];
@@ -227,9 +227,9 @@ PackLayout pack_layout(int64_t batch, int64_t n) {
   L.nblk = (n + kPkBlock - 1) / kPkBlock;
   size_t o = 0;
   auto take = [&](size_t elems) { const size_t at = o; o += (elems * 4 + 255) / 256 * 256; return at; };
-  L.off_apk = take((size_t)batch * L.npad);
-  L.off_apk_s = take((size_t)batch * L.npad);
-  L.off_bd = take((size_t)batch * n);
+  L.off_apk = take((size_t)batch * (L.npad + 16));     // rows of npad + 16 words, see prep_kernel
+  L.off_apk_s = take((size_t)batch * (L.npad + 16));
+  L.off_bd = take((size_t)batch * ((n + 3) & ~(int64_t)3));   // row pitch: a multiple of 16 bytes
   L.off_ab = take((size_t)batch * L.nchunk);
   L.off_ar = take((size_t)batch * L.nchunk);
   L.off_ab_s = take((size_t)batch * L.nsub);

@@ -111,9 +111,9 @@ static_assert(kPkSubs == 8, "the packed path keeps one flag bit per sub-chunk in
 // when the whole chunk's range fits) and per sub-chunk of 128 steps (for operands whose slopes
 // differ, where only short runs fit 16 bits).
 struct PackAux {
-  const uint32_t* apk;     // [B][npad]   uniform operand, detrended, re-based per chunk, both halves
-  const uint32_t* apk_s;   // [B][npad]   the same, re-based per sub-chunk
-  const int32_t* bd;       // [B][n]      detrended window operand, in window-index order
+  const uint32_t* apk;     // [B][npad+16] uniform operand, detrended, re-based per chunk, both halves, descending step order
+  const uint32_t* apk_s;   // [B][npad+16] the same, re-based per sub-chunk
+  const int32_t* bd;       // [B][n up to a multiple of 4]  detrended window operand, in window-index order
   const int32_t* ab;       // [B][nchunk] chunk minimum of the detrended uniform operand
   const int32_t* ar;       // [B][nchunk] chunk range
   const int32_t* ab_s;     // [B][nsub]   sub-chunk minimum
@@ -124,6 +124,15 @@ struct PackAux {
   const int32_t* pack_ok;  // [B]         row is eligible for the packed path
   int32_t npad, nchunk, nsub, nblk;
 };
+
+// The tables of the packed path were written by earlier launches and do not change while a product
+// kernel runs.  Reading them through the constant address space tells the compiler so: a load at a
+// wave-uniform address then becomes a scalar load whatever stores and atomics the kernel contains
+// (otherwise it falls back to a vector load with all lanes on one address).
+template <typename T>
+__device__ __forceinline__ const __attribute__((address_space(4))) T* as_invariant(const T* p) {
+  return (const __attribute__((address_space(4))) T*)p;
+}
 
 constexpr int kPlanWhole = 0x100;    // chunk_plan: the whole chunk packs with the chunk-level re-basing
 constexpr int kPlanNarrow = 0x200;   // chunk_plan: the granted runs also fit the 15-bit flavour
@@ -153,15 +162,15 @@ __device__ __forceinline__ int32_t narrow_umax(int32_t br) { return (kPkNarrowBu
 // sub-chunk in the narrow, wide and 32-bit kernels (about 10 : 13 : 24).
 __device__ __forceinline__ int chunk_plan(const PackAux& x, int row, int T2, int c, int n, int32_t* gb,
                                           int32_t* br) {
-  if (x.pack_ok[row] == 0) return 0;
+  if (as_invariant(x.pack_ok)[row] == 0) return 0;
   const int sc = c * kPkChunk;
   int lo = T2 * kPkW - sc - kPkChunk;
   int hi = T2 * kPkW + kPkW - sc;
   lo = max(lo, 0);
   hi = min(hi, n);
   const int b0 = lo / kPkBlock, b1 = (hi - 1) / kPkBlock;
-  const int32_t* mnp = x.bmn + (int64_t)row * x.nblk;
-  const int32_t* mxp = x.bmx + (int64_t)row * x.nblk;
+  const auto* mnp = as_invariant(x.bmn + (int64_t)row * x.nblk);
+  const auto* mxp = as_invariant(x.bmx + (int64_t)row * x.nblk);
   int32_t mn = INT32_MAX, mx = INT32_MIN;
   for (int b = b0; b <= b1; ++b) {
     mn = min(mn, mnp[b]);
@@ -171,10 +180,10 @@ __device__ __forceinline__ int chunk_plan(const PackAux& x, int row, int T2, int
   const int64_t wr = (int64_t)mx - (int64_t)mn;
   if (wr > kPkWideBudget) return 0;
   *br = (int32_t)wr;
-  const int64_t cr = x.ar[(int64_t)row * x.nchunk + c];
+  const int64_t cr = as_invariant(x.ar)[(int64_t)row * x.nchunk + c];
   if (wr + 2 * cr <= kPkNarrowBudget) return kPlanNarrow | kPlanWhole | 0xFF;
   const bool wide_whole = wr + cr <= kPkWideBudget;
-  const int32_t* ars = x.ar_s + (int64_t)row * x.nsub + c * kPkSubs;
+  const auto* ars = as_invariant(x.ar_s + (int64_t)row * x.nsub + c * kPkSubs);
   int narrow = 0, wide = 0;
 #pragma unroll
   for (int j = 0; j < kPkSubs; ++j) {

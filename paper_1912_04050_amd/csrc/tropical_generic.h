@@ -58,11 +58,22 @@ __device__ __forceinline__ void tropical_body(const TropicalArgs& p, unsigned ch
     const int gbase = t0 - (sc + nblk * R);
     const int count = (64 + nblk) * R;
     __syncthreads();
-    for (int e = lane; e < count; e += 64) {
-      const int idx = gbase + e;
-      T v = T(0);
-      if (idx >= 0 && idx < n) v = brow[rev ? n - 1 - idx : idx];
-      *reinterpret_cast<T*>(lds + (e / R) * TL::kSlotBytes + (e % R) * (int)sizeof(T)) = v;
+    // eight strides of loads in flight per trip (clamped addresses, no branches) instead of one
+    // round trip to memory per stride
+    constexpr int kStageBatch = 8;
+    for (int e0 = lane; e0 < count; e0 += 64 * kStageBatch) {
+      T raw[kStageBatch];
+#pragma unroll
+      for (int q = 0; q < kStageBatch; ++q) {
+        const int idx = min(max(gbase + e0 + 64 * q, 0), n - 1);
+        raw[q] = brow[rev ? n - 1 - idx : idx];
+      }
+#pragma unroll
+      for (int q = 0; q < kStageBatch; ++q) {
+        const int e = e0 + 64 * q, idx = gbase + e;
+        const T v = (idx >= 0 && idx < n) ? raw[q] : T(0);
+        if (e < count) *reinterpret_cast<T*>(lds + (e / R) * TL::kSlotBytes + (e % R) * (int)sizeof(T)) = v;
+      }
     }
     if constexpr (R == 4) {
       // small tiles also stage the chunk of the uniform operand (see the grouped blocks below)

@@ -467,19 +467,22 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(const int32_t* __res
   for (int k = 0; k < kPer; ++k) {
     const int i = c * kPkChunk + k * kPrepThreads + threadIdx.x;
     const bool valid = i < n;
-    apk[(int64_t)row * npad + i] = valid ? min((uint32_t)adv[k] - (uint32_t)cmn, kPkPoison) * 0x10001u : 0u;
+    // both packed arrays run in descending order of the step: word [npad + 15 - i] of a row of
+    // npad + 16 words holds step i (the 16 steps of a block are then one aligned run of 16 words;
+    // words 0..14 of a row are unused)
+    apk[(int64_t)row * (npad + 16) + (npad + 15 - i)] = valid ? min((uint32_t)adv[k] - (uint32_t)cmn, kPkPoison) * 0x10001u : 0u;
     // sub-chunk of 128 indices = 2 groups of 64
     const int sub = 2 * k + (threadIdx.x >> 7);
     const int32_t smn = min(s_amn[2 * sub], s_amn[2 * sub + 1]);
     const int32_t smx = max(s_amx[2 * sub], s_amx[2 * sub + 1]);
-    apk_s[(int64_t)row * npad + i] = valid ? min((uint32_t)adv[k] - (uint32_t)smn, kPkPoison) * 0x10001u : 0u;
+    apk_s[(int64_t)row * (npad + 16) + (npad + 15 - i)] = valid ? min((uint32_t)adv[k] - (uint32_t)smn, kPkPoison) * 0x10001u : 0u;
     if ((threadIdx.x & (kPkSub - 1)) == 0) {
       const bool any = smx >= smn;   // false when the sub-chunk lies entirely beyond n
       const int64_t range = (int64_t)smx - (int64_t)smn;
       ab_s[(int64_t)row * nsub + c * kPkSubs + sub] = any ? smn : 0;
       ar_s[(int64_t)row * nsub + c * kPkSubs + sub] = any ? (int32_t)(range < 0x7fffffffLL ? range : 0x7fffffffLL) : 0;
     }
-    if (valid) bd[(int64_t)row * n + i] = bdv[k];
+    if (valid) bd[(int64_t)row * ((n + 3) & ~3) + i] = bdv[k];   // rows start 16-byte aligned
     if (threadIdx.x == 0) {        // block k of 256 indices
       const int j = c * (kPkChunk / kPkBlock) + k;
       if (j < nblk) {
