@@ -10,6 +10,10 @@ probe, so the products run in int32 arithmetic):
   horizontal / vertical deviations.
 `value` counts the pair-ops of the four O(N^2) products of a step (N(N+1)/2 per product and
 pair, whatever the kernel does internally) over the wall time of the whole step.
+The same line carries the roofline of the dominant kernel (against the instruction-issue ceiling
+of the arithmetic mix it ran, from rtc_product_census), a device-copy rate measured in the same
+run with every HBM-bound operator against it (`hbm`), the other configurations and arithmetic
+paths (`per_config`), and the CPU oracle timed on this machine's host cores (`cpu_baseline`).
 Prints ONE JSON line.
 """
 import argparse
@@ -35,7 +39,10 @@ def parse():
                     help="approximate CPU time to spend on the oracle baseline (0 disables it)")
     ap.add_argument("--no-parity", action="store_true", help="skip the sampled parity check")
     ap.add_argument("--all-configs", action="store_true",
-                    help="also time every operator on each of the five configurations (adds per_config)")
+                    help="also the detailed table: every operator on each configuration with the oracle timed "
+                         "beside it (adds per_config_detail)")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the compact per_config rows (configurations 1, 2, 4, 5 and the other arithmetic paths)")
     ap.add_argument("--configs", default="", help="profiling aid: restrict --all-configs to a comma list of "
                     "configuration numbers 1..5 (3 includes the rows of exploitable convexity)")
     ap.add_argument("--only", default="", help="profiling aid: restrict the step to a comma list of "
@@ -55,6 +62,8 @@ def parse():
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by what the same counters read for a
 # plain 1 GiB device copy; see profiles/.  None for any other workload.
 HEADLINE_TRAFFIC_BYTES = 649751657   # fetched + 532 MiB of atomic-merge writes (profiles/fused_kernel_headline_pmc.md)
+HEADLINE_TRAFFIC_SOURCE = ("profiles/fused_kernel_headline_pmc.md: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, "
+                           "scaled by a 1 GiB device copy; a stored figure, not measured in this run")
 
 
 def headline_traffic(batch, n):
@@ -518,6 +527,204 @@ def bnn_main(args):
     print(json.dumps(line))
 
 
+def copy_rate_gbs(mib=1024):
+    """Achievable HBM rate of a plain device-to-device copy of `mib` MiB: (bytes read + bytes written) / time."""
+    import torch
+    src = torch.zeros(mib << 20, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    med, _ = gpu_ms(lambda: dst.copy_(src), warm=2, reps=7)
+    return 2.0 * (mib << 20) / (med * 1e-3) / 1e9
+
+
+def hbm_entry(name, fn, nbytes, copy_gbs, note=None):
+    """One HBM-bound operator: HIP-event time, algorithmic bytes, and the rate against the measured copy."""
+    med, mn = gpu_ms(fn)
+    gbs = nbytes / (med * 1e-3) / 1e9
+    r = {"op": name, "gpu_ms": round(med, 4), "gpu_ms_min": round(mn, 4), "algorithmic_bytes": int(nbytes),
+         "gb_per_s": round(gbs, 1), "frac_of_copy_rate": round(gbs / copy_gbs, 3), "frac_of_8tb_per_s": round(gbs / 8000.0, 3)}
+    if note:
+        r["note"] = note
+    return r
+
+
+def mix_ceiling(census, lane_rate):
+    """Instruction-issue ceiling of a product launch whose iteration space splits as `census` says
+    (rtc_product_census): VALU instructions per pair-op of each flavour, weighted by its share, against
+    one wave64 VALU instruction per SIMD every 4 cycles (lane_rate = CUs x 64 lanes x clock lane-instructions/s)."""
+    per = [0.5, 0.5, 1.0, 1.5]
+    units = [float(census[k]) for k in range(4)]
+    tot = sum(units)
+    if tot <= 0:
+        return None, None
+    instr = sum(p * u for p, u in zip(per, units)) / tot
+    return instr, lane_rate / instr
+
+
+def compact_configs(seed, lane_rate, copy_gbs):
+    """The configurations the step above does not time (1, 2, 4, 5) and the other arithmetic paths on the
+    headline rows (32-bit kernel alone, 64-bit kernel), one compact row per operator: HIP-event time,
+    rate, and for products the fraction of the issue ceiling of the arithmetic that ran."""
+    import numpy as np
+    import torch
+
+    from paper_1912_04050_amd import rtc, workloads as wl
+    rows = []
+
+    def dev(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    def product(cfg, name, fn, op_code, f, g, storage, packed=True, instr=None, note=None, reps=10):
+        B, N = f.shape
+        out = torch.empty_like(f)
+        need = rtc.rtc_workspace_bytes(rtc.RTC_OP_CONV, B, N, f.dtype)
+        ws = torch.empty(max(16, need), dtype=torch.uint8, device="cuda")
+        if not packed:      # the 32-bit kernel alone: packed path and structure detection off for this row
+            rtc.rtc_set_packed_min_work(1e30)
+        try:
+            med, mn = gpu_ms(lambda: fn(f, g, out=out, ws=ws), reps=reps)
+        finally:
+            rtc.rtc_set_packed_min_work(rtc.RTC_DEFAULT_PACKED_MIN_WORK)
+        po = B * N * (N + 1) // 2
+        r = {"config": cfg, "op": name, "dtype": storage, "batch": B, "n": N, "gpu_ms": round(med, 4),
+             "gpu_ms_min": round(mn, 4), "gpair_ops_per_s": round(po / med / 1e6, 1),
+             "pct_valu_peak_2ops": round(100 * 2 * po / (med * 1e-3) / lane_rate, 1)}
+        paths = None
+        if f.dtype != torch.float64 and packed and B * N * N >= rtc.RTC_DEFAULT_PACKED_MIN_WORK:
+            codes = rtc.rtc_product_structure(op_code, f, g).cpu().numpy()
+            names = {1: "general", 2: "bisection", 3: "ends", 4: "brackets", 5: "brackets", 6: "periodic", 7: "periodic"}
+            paths = {}
+            for c in codes.tolist():
+                paths[names[c]] = paths.get(names[c], 0) + 1
+            r["rows_by_path"] = paths
+        if paths is not None and set(paths) != {"general"}:
+            # rows on a structure-exploiting path execute fewer candidates than the definition counts
+            r["equivalent_gpair_ops_per_s"] = r.pop("gpair_ops_per_s")
+            r.pop("pct_valu_peak_2ops")
+            rtc.rtc_set_structure_paths(False)
+            try:
+                med_g, _ = gpu_ms(lambda: fn(f, g, out=out, ws=ws), reps=reps)
+            finally:
+                rtc.rtc_set_structure_paths(True)
+            r["general_kernels_gpu_ms"] = round(med_g, 4)
+            r["general_kernels_gpair_ops_per_s"] = round(po / med_g / 1e6, 1)
+            med = med_g
+        if instr is None and f.dtype != torch.float64:
+            rtc.rtc_set_structure_paths(False)
+            try:
+                cen = rtc.rtc_product_census(op_code, f, g, ws=ws).cpu().numpy().tolist()
+            finally:
+                rtc.rtc_set_structure_paths(True)
+            instr, _ = mix_ceiling(cen, lane_rate)
+            if cen[4] > 0:
+                instr = None      # part of the rows runs in 64-bit kernels: no single ceiling
+        if instr is not None:
+            r["valu_instr_per_pair_op"] = round(instr, 3)
+            r["frac_of_issue_ceiling"] = round(po / (med * 1e-3) * instr / lane_rate, 3)
+        if note:
+            r["note"] = note
+        rows.append(r)
+        return out
+
+    def hbm(cfg, name, fn, nbytes, storage, B, N):
+        r = hbm_entry(name, fn, nbytes, copy_gbs)
+        r.update({"config": cfg, "dtype": storage, "batch": B, "n": N})
+        rows.append(r)
+
+    # config 1: one pair of 4096 samples (launch-bound: reported, not a measure of the kernel)
+    c = wl.config1(seed)
+    f, g = dev(c["f"]), dev(c["g"])
+    product(1, "minplus_conv", rtc.rtc_minplus_conv, rtc.RTC_OP_CONV, f, g, "int32", note="launch-bound")
+    product(1, "maxplus_deconv", rtc.rtc_maxplus_deconv, rtc.RTC_OP_DECONV, f, g, "int32", note="launch-bound")
+    # config 2: 1024 pairs of 4096 samples, periodic curves
+    c = wl.config2(seed, 1024, 4096)
+    a, b = dev(c["alpha_u"]), dev(c["beta_l"])
+    product(2, "minplus_conv", rtc.rtc_minplus_conv, rtc.RTC_OP_CONV, a, b, "int32")
+    product(2, "maxplus_deconv", rtc.rtc_maxplus_deconv, rtc.RTC_OP_DECONV, a, b, "int32")
+    hd = torch.empty(1024, dtype=torch.int32, device="cuda")
+    vd = torch.empty(1024, dtype=torch.int32, device="cuda")
+    hbm(2, "max_hdev", lambda: rtc.rtc_max_hdev(a, b, out=hd), 2 * 1024 * 4096 * 4 + 4096, "int32", 1024, 4096)
+    hbm(2, "max_vdev", lambda: rtc.rtc_max_vdev(a, b, out=vd), 2 * 1024 * 4096 * 4 + 4096, "int32", 1024, 4096)
+    del a, b
+    # headline rows through the other arithmetic paths
+    c3 = wl.config3(seed, 64, 65536)
+    f32, g32 = dev(c3["f"].astype(np.int32)), dev(c3["g"].astype(np.int32))
+    product(3, "minplus_conv, native int32 rows (packed path)", rtc.rtc_minplus_conv, rtc.RTC_OP_CONV, f32, g32, "int32")
+    product(3, "minplus_conv, native int32 rows, packed path off (32-bit kernel alone)", rtc.rtc_minplus_conv,
+            rtc.RTC_OP_CONV, f32, g32, "int32", packed=False, instr=1.5,
+            note="v_add_u32 per candidate + v_min3_i32 per two")
+    product(3, "maxplus_deconv, native int32 rows, packed path off (32-bit kernel alone)", rtc.rtc_maxplus_deconv,
+            rtc.RTC_OP_DECONV, f32, g32, "int32", packed=False, instr=1.5)
+    del f32, g32
+    # values beyond +-2^51 with a jump in mid-row: no narrowing remedy applies, the 64-bit integer kernel runs
+    big = (np.arange(65536) >= 32768).astype(np.int64) << 53
+    f64i, g64i = dev(c3["f"][:16] + big), dev(c3["g"][:16] + 2 * big)
+    product(3, "minplus_conv, int64 rows beyond every narrowing (64-bit kernel)", rtc.rtc_minplus_conv, rtc.RTC_OP_CONV,
+            f64i, g64i, "int64", instr=5.0, reps=5,
+            note="5 VALU instructions per candidate: add, add-with-carry, compare, two selects")
+    del f64i, g64i
+    # config 4: one component of all 256 chains, then the 16-component chain
+    c = wl.config4(seed, 256, 16, 16384)
+    gam, abar = dev(c["gamma_u"]), dev(c["alpha_bar_u"])
+    bu, bl = dev(c["beta_u"]), dev(c["beta_l"])
+    B4, N4 = 256, 16384
+    a0 = torch.empty((B4, N4), dtype=torch.int32, device="cuda")
+    hbm(4, "compose", lambda: rtc.rtc_compose(gam, abar, out=a0), B4 * N4 * 12, "int32", B4, N4)
+    au, au2, blo = torch.empty_like(a0), torch.empty_like(a0), torch.empty_like(a0)
+    evl, evu = torch.empty_like(a0), torch.empty_like(a0)
+    ws = torch.empty(rtc.rtc_workspace_bytes(rtc.RTC_OP_GPC, B4, N4, torch.int32), dtype=torch.uint8, device="cuda")
+    po4 = 2 * B4 * N4 * (N4 + 1) // 2
+
+    def whole_chain():
+        src = a0
+        for i in range(16):
+            dst = au if i % 2 == 0 else au2
+            rtc.rtc_gpc_step(src, bu[i], bl[i], alpha_u_out=dst, beta_l_out=blo, gamma_u=gam, events_lower=evl,
+                             events_upper=evu, ws=ws)
+            src = dst
+
+    med, mn = gpu_ms(whole_chain, warm=1, reps=5)
+    rtc.rtc_set_structure_paths(False)
+    try:
+        med_g, _ = gpu_ms(whole_chain, warm=1, reps=3)
+    finally:
+        rtc.rtc_set_structure_paths(True)
+    rows.append({"config": 4, "op": "16-component GPC chain, 256 chains (32 products + scans + inverses)", "dtype": "int32",
+                 "batch": B4, "n": N4, "gpu_ms": round(med, 3), "gpu_ms_min": round(mn, 3),
+                 "equivalent_gpair_ops_per_s": round(16 * po4 / med / 1e6, 1),
+                 "general_kernels_gpu_ms": round(med_g, 3),
+                 "general_kernels_gpair_ops_per_s": round(16 * po4 / med_g / 1e6, 1),
+                 "note": "TDMA / periodic-arrival rows take the periodic path by default (fewer candidates than the "
+                         "definition counts); general_kernels_* is the same chain with that path off"})
+    # the tail kernel of a component (scan + both event-domain inverses), from the library's own event pairs
+    rtc.rtc_profile_enable(True)
+    for _ in range(5):
+        rtc.rtc_gpc_step(a0, bu[0], bl[0], alpha_u_out=au, beta_l_out=blo, gamma_u=gam, events_lower=evl,
+                         events_upper=evu, ws=ws)
+    torch.cuda.synchronize()
+    tail = [ms for kind, ms in rtc.rtc_profile_read() if kind == rtc.RTC_PROFILE_KIND_TAIL]
+    rtc.rtc_profile_enable(False)
+    if tail:
+        tail.sort()
+        t_ms, nb = tail[len(tail) // 2], B4 * N4 * (4 * 4 + 8)
+        rows.append({"config": 4, "op": "GPC tail kernel: residual-service scan + both event-domain inverses", "dtype": "int32",
+                     "batch": B4, "n": N4, "gpu_ms": round(t_ms, 4), "algorithmic_bytes": nb,
+                     "gb_per_s": round(nb / (t_ms * 1e-3) / 1e9, 1), "frac_of_copy_rate": round(nb / (t_ms * 1e-3) / 1e9 / copy_gbs, 3)})
+    hbm(4, "pseudo_inverse lower (gamma_u at beta'_l)", lambda: rtc.rtc_pseudo_inverse(gam, blo, 0, out=evl), B4 * N4 * 12,
+        "int32", B4, N4)
+    del gam, abar, bu, bl, a0, au, au2, blo, evl, evu, ws
+    # config 5: one fp64 pair of 262144 samples
+    c = wl.config5(seed, 262144)
+    f, g = dev(c["f"]), dev(c["g"])
+    product(5, "minplus_conv", rtc.rtc_minplus_conv, rtc.RTC_OP_CONV, f, g, "float64", instr=2.0,
+            note="v_add_f64 + v_min_f64 per candidate")
+    product(5, "maxplus_deconv", rtc.rtc_maxplus_deconv, rtc.RTC_OP_DECONV, f, g, "float64", instr=2.0)
+    x = dev(c["x"])
+    inv = torch.empty((1, 262144), dtype=torch.int32, device="cuda")
+    for mode, nm in ((0, "lower"), (1, "upper")):
+        hbm(5, f"pseudo_inverse {nm}", lambda: rtc.rtc_pseudo_inverse(f, x, mode, out=inv), 262144 * 20, "float64", 1, 262144)
+    return rows
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -573,6 +780,7 @@ def main():
         dst = torch.empty_like(src)
         dst.copy_(src)
         torch.cuda.synchronize()
+        del src, dst
 
     def step(record):
         if "conv" in only:
@@ -612,7 +820,7 @@ def main():
     total_pair_ops = products_per_step * B * pair_ops_one
     value = total_pair_ops / (ms_per_step * 1e-3) / 1e9
 
-    # ---- roofline of the dominant kernel: the packed 16-bit min-plus kernel -----------------
+    # ---- roofline of the dominant kernel: the fused launch of the min-plus convolution ------
     if not conv_events:   # profiling subset without the convolution: time it on its own
         rtc.rtc_profile_enable(True)
         for _ in range(3):
@@ -632,7 +840,8 @@ def main():
                   rtc.RTC_PROFILE_KIND(1, 0, 0): "tropical_kernel<int64, min-plus>",
                   rtc.RTC_PROFILE_KIND(1, 0, 1): "tropical_kernel<int64, max-plus>",
                   rtc.RTC_PROFILE_KIND(2, 0, 0): "tropical_kernel<fp64, min-plus>",
-                  rtc.RTC_PROFILE_KIND(2, 0, 1): "tropical_kernel<fp64, max-plus>"}
+                  rtc.RTC_PROFILE_KIND(2, 0, 1): "tropical_kernel<fp64, max-plus>",
+                  rtc.RTC_PROFILE_KIND_TAIL: "gpc_tail_kernel"}
     per_kind = {}
     for kind, ms in kernel_times:
         per_kind.setdefault(kind_names.get(kind, str(kind)), []).append(ms)
@@ -640,33 +849,76 @@ def main():
     dom = per_kind.get("fused_kernel<min-plus>")
     conv_ms = sum(dom) / len(dom) if dom else conv_call_ms
     info = rtc.rtc_device_info()
-    peak_ops = info["cu_count"] * 64 * info["clock_khz"] * 1e3   # int32 VALU lane-ops per second
+    lane_rate = info["cu_count"] * 64 * info["clock_khz"] * 1e3   # VALU lane-instructions per second
     alg_ops = 2.0 * B * pair_ops_one                              # one add + one min per pair-op
     achieved = alg_ops / (conv_ms * 1e-3)
+    # the arithmetic mix this launch ran, from the library's own plan (evaluated on the device)
+    census = rtc.rtc_product_census(rtc.RTC_OP_CONV, f, g, ws=ws).cpu().numpy().tolist()
+    instr, ceiling_pair_ops = mix_ceiling(census, lane_rate)
+    if instr is None:
+        instr, ceiling_pair_ops = 1.5, lane_rate / 1.5
+    peak = 2.0 * ceiling_pair_ops
+    units = max(1, sum(census[:4]))
     roofline = {
-        "bound": "alu", "kernel": "fused_kernel<out int64, min-plus> (packed 16-bit items + 32-bit items)",
-        "achieved": round(achieved / 1e12, 4), "peak": round(peak_ops / 1e12, 4), "unit": "TOP/s",
-        "frac": round(achieved / peak_ops, 4), "traffic": headline_traffic(B, N),
+        "bound": "alu", "kernel": "fused_kernel<out int64, min-plus> (packed 16-bit work items + 32-bit work items in one launch)",
+        "achieved": round(achieved / 1e12, 4), "peak": round(peak / 1e12, 4), "unit": "TOP/s",
+        "frac": round(achieved / peak, 4), "traffic": headline_traffic(B, N),
+        "traffic_source": HEADLINE_TRAFFIC_SOURCE if headline_traffic(B, N) is not None else None,
         "launch_ms": round(conv_ms, 4), "call_ms": round(conv_call_ms, 4),
         "pair_ops_per_launch": B * pair_ops_one,
         "gpair_ops_per_s": round(B * pair_ops_one / (conv_ms * 1e-3) / 1e9, 2),
-        # the same launch against the rate at which the SIMDs can issue instructions at all: a
-        # wave64 VALU instruction occupies its SIMD for 4 cycles, 4 SIMDs per CU; the product needs at
-        # least 0.75 such instructions per 64 pair-ops (see note).  This fraction cannot exceed 1.
-        "frac_of_valu_issue_rate": round(0.75 * B * pair_ops_one / 64 / (conv_ms * 1e-3)
-                                         / (info["cu_count"] * 4 * info["clock_khz"] * 1e3 / 4), 4),
+        "valu_instr_per_pair_op": round(instr, 4),
+        "arithmetic_shares": {"packed 15-bit, chunk base (0.5 instr/pair-op)": round(census[0] / units, 4),
+                              "packed 15-bit, sub-chunk bases (0.5)": round(census[1] / units, 4),
+                              "packed 16-bit saturating (1.0)": round(census[2] / units, 4),
+                              "32-bit items (1.5)": round(census[3] / units, 4),
+                              "units_on_other_kernels": census[4]},
+        "pct_valu_peak_2ops": round(100.0 * achieved / lane_rate, 2),
         "cu_count": info["cu_count"], "clock_khz": info["clock_khz"], "kernels": kernels,
-        "note": "achieved counts 2 lane-ops (add + min) per pair-op by definition, over the kernel's own "
-                "HIP-event duration; peak = CUs x 64 lanes x clock. The kernel issues 0.75 VALU instructions per "
-                "pair-op where a chunk fits 15 bits (two v_pk_add_u16 + one v_pk_minimum3_f16 serve four "
-                "pair-ops) and 1 where it needs 16 (v_pk_add_u16 + v_pk_min_u16 serve two), which is how frac "
-                "exceeds 1; "
-                "call_ms is the whole rtc_minplus_conv call (probe, fill, prepare, decide, fused kernel, and the "
-                "64-bit kernel that finds nothing left to do); traffic (HBM bytes per launch from the "
-                "FETCH_SIZE / WRITE_SIZE counters) is 6 x the 3*N*w*B algorithmic bytes because each of the 33792 "
-                "work items merges its 2048 partial minima into the output with 8-byte atomics (532 MiB, under "
-                "3 % of the HBM rate over the launch): not re-reads, and not what bounds the kernel",
+        "note": "achieved = 2 lane-ops (add + min) per pair-op, N(N+1)/2 pair-ops per pair, over the kernel's own "
+                "HIP-event duration. peak = the rate at which the SIMDs can issue this launch's arithmetic: one wave64 "
+                "VALU instruction per SIMD every 4 cycles (CUs x 64 lanes x clock lane-instructions/s) divided by the "
+                "VALU instructions per pair-op of the mix that ran (arithmetic_shares, from rtc_product_census), times "
+                "the same 2 lane-ops per pair-op; frac cannot exceed 1. The 15-bit flavour forms four candidates with "
+                "one v_lshl_add_u64 and reduces them with one v_pk_minimum3_f16. pct_valu_peak_2ops is the metric's "
+                "own convention (2 lane-ops per pair-op against CUs x 64 x clock), which packed arithmetic exceeds. "
+                "call_ms is the whole rtc_minplus_conv call (probes, fill, prepare, decide, the fused kernel, and the "
+                "kernels for rows of other kinds, which find none here).",
     }
+
+    # ---- HBM-bound operators against a device copy measured in the same run -----------------
+    hbm = None
+    per_config = None
+    if not args.only:
+        w = 8
+        copy_gbs = copy_rate_gbs()
+        hbm = {"copy_gb_per_s": round(copy_gbs, 1), "copy_frac_of_8tb_per_s": round(copy_gbs / 8000.0, 3),
+               "copy": "torch device-to-device copy of 1 GiB, bytes read + bytes written over HIP-event time",
+               "workload": f"the step's own operands: {B} rows of N={N}, int64",
+               "ops": [
+                   hbm_entry("pseudo_inverse lower", lambda: rtc.rtc_pseudo_inverse(f, g, rtc.RTC_INV_LOWER, out=inv_lo),
+                             B * N * (2 * w + 4), copy_gbs),
+                   hbm_entry("pseudo_inverse upper", lambda: rtc.rtc_pseudo_inverse(f, g, rtc.RTC_INV_UPPER, out=inv_up),
+                             B * N * (2 * w + 4), copy_gbs),
+                   hbm_entry("compose", lambda: rtc.rtc_compose(g, inner, out=comp, dev_flags=flags), B * N * (4 + 2 * w), copy_gbs),
+                   hbm_entry("max_hdev", lambda: rtc.rtc_max_hdev(f, g, out=hdev, dev_flags=flags), B * N * 2 * w + 4 * B, copy_gbs),
+                   hbm_entry("max_vdev", lambda: rtc.rtc_max_vdev(f, g, out=vdev), B * N * 2 * w + w * B, copy_gbs),
+               ]}
+        hv = torch.empty(B, dtype=torch.int32, device="cuda")
+        hbm["ops"].append(hbm_entry("max_deviations (hdev + vdev in one pass)",
+                                    lambda: rtc.rtc_max_deviations(f, g, out_h=hv, out_v=vdev, dev_flags=flags),
+                                    B * N * 2 * w + (4 + w) * B, copy_gbs))
+        tail = sorted(per_kind.get("gpc_tail_kernel", []))
+        if tail:
+            t_ms, nb = tail[len(tail) // 2], B * N * (4 * w + 8)
+            gbs = nb / (t_ms * 1e-3) / 1e9
+            hbm["ops"].append({"op": "GPC tail kernel: residual-service scan + both event-domain inverses (inside rtc_gpc_step)",
+                               "gpu_ms": round(t_ms, 4), "algorithmic_bytes": nb, "gb_per_s": round(gbs, 1),
+                               "frac_of_copy_rate": round(gbs / copy_gbs, 3), "frac_of_8tb_per_s": round(gbs / 8000.0, 3),
+                               "note": "kernel duration from the library's event pairs during the timed steps; bytes: "
+                                       "beta^l, alpha^u and gamma^u read once, beta'^l and two int32 index rows written once"})
+        if not args.no_configs:
+            per_config = compact_configs(seed, lane_rate, copy_gbs)
 
     # ---- sampled parity + CPU baseline (the oracle as it stands, on this machine's host cores) --
     parity = None
@@ -701,17 +953,24 @@ def main():
         "metric": "min-plus conv Gpair-ops/s at N=65536 (int32) + % of VALU int32 peak",
         "value": round(value, 2), "unit": "Gpair-ops/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
-        "config": {"workload": f"config 3: {B} pairs, N={N}, int64 storage, range-probed int32 arithmetic; "
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": "i64 storage; packed 15-bit integer arithmetic on re-based, int32-exact values "
+                 "(v_lshl_add_u64 + v_pk_minimum3_f16), exact int64 results",
+        "data": "synthetic",
+        "config": {"workload": f"config 3: {B} pairs, N={N}, int64 storage; "
                                "step = conv + deconv + pseudo-inverses + compose + GPC step + deviations",
                    "batch": B, "n": N, "seed": seed, "products_per_step": products_per_step,
                    "ops": sorted(only)},
-        "pct_valu_peak": round(100.0 * achieved / peak_ops, 2),
-        "roofline": roofline, "cpu_baseline": cpu_baseline, "parity": parity,
+        "value_scope": "pair-ops of all four O(N^2) products of a step (convolution, deconvolution and the two inside the "
+                       "GPC step) over the wall time of the whole step, HBM-bound operators included; the min-plus "
+                       "convolution alone is roofline.gpair_ops_per_s (kernel) and pair_ops_per_launch / call_ms (call)",
+        "conv_call_gpair_ops_per_s": round(B * pair_ops_one / (conv_call_ms * 1e-3) / 1e9, 2),
+        "pct_valu_peak": round(100.0 * achieved / lane_rate, 2),
+        "roofline": roofline, "hbm": hbm, "per_config": per_config, "cpu_baseline": cpu_baseline, "parity": parity,
     }
     if args.all_configs:
         wanted = tuple(int(k) for k in args.configs.split(",")) if args.configs else (1, 2, 3, 4, 5)
-        line["per_config"] = per_config_table(seed, peak_ops, args.cpu_seconds > 0, wanted)
+        line["per_config_detail"] = per_config_table(seed, lane_rate, args.cpu_seconds > 0, wanted)
     print(json.dumps(line))
     if parity == "MISMATCH":
         sys.exit(1)

@@ -194,6 +194,11 @@ int rtc_max_hdev(const void* alpha, const void* beta, int32_t* out, int64_t batc
 int rtc_max_vdev(const void* alpha, const void* beta, void* out, int64_t batch, int64_t n,
                  rtc_dtype dt, void* hip_stream);
 
+/* Both bounds from one pass over alpha and beta: out_h as rtc_max_hdev, out_v as rtc_max_vdev
+ * (same definitions, flags and results; alpha is read once instead of twice). */
+int rtc_max_deviations(const void* alpha, const void* beta, int32_t* out_h, void* out_v, int64_t batch, int64_t n,
+                       rtc_dtype dt, int32_t* dev_flags, void* hip_stream);
+
 /* Debug aid: the pseudo-inverse, the composition's inner curve, the deviations and the component
  * step take nondecreasing rows and do not check it.  This does: RTC_FLAG_NOT_MONOTONE is raised in
  * dev_flags (required) when some f[b][i+1] < f[b][i], and first_bad[b] (optional; device, [batch]
@@ -247,6 +252,24 @@ int rtc_product_structure(int op, const void* f, const void* g, int32_t* codes, 
  * plus one scan of n steps. */
 int rtc_product_periods(int op, const void* f, const void* g, int32_t* codes, int32_t* periods, int64_t batch,
                         int64_t n, int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* hip_stream);
+
+/* Measurement aid: how the iteration space of a product splits over the arithmetic flavours of
+ * its kernels.  Takes the arguments of the product `op` (RTC_OP_CONV, _DECONV, _MAXCONV,
+ * _MINDECONV) without `out`, classifies and prepares the rows in the workspace exactly as the
+ * product would, and instead of computing it ADDS to the device array counts[RTC_CENSUS_COUNTS]
+ * (the caller zeroes it) the number of units each flavour would take; a unit is one sub-chunk of
+ * 128 steps of one tile of 2048 outputs (the diagonal's half-empty units count in full):
+ *   counts[0]  15-bit packed flavour on the chunk's base     (0.5 VALU instructions per pair-op:
+ *   counts[1]  15-bit packed flavour on sub-chunk bases       one 64-bit add + one packed min3 per four)
+ *   counts[2]  16-bit saturating packed flavour               (1 per pair-op)
+ *   counts[3]  32-bit work items                              (1.5 per pair-op)
+ *   counts[4]  rows that other kernels do (64-bit, fp64, structure-exploiting paths)
+ * so that a benchmark can price a launch against the instruction-issue ceiling of the mix it
+ * actually ran. */
+#define RTC_CENSUS_COUNTS 5
+int rtc_product_census(int op, const void* f, const void* g, int64_t batch, int64_t n, int64_t stride_f,
+                       int64_t stride_g, rtc_dtype dt, void* ws, size_t ws_bytes, uint64_t* counts,
+                       void* hip_stream);
 
 /* Planner knob: the packed 16-bit path of the int32 / narrowed-int64 products, and with it the
  * detection of convex, concave and periodic rows, is used when a workspace is present and
@@ -338,6 +361,7 @@ int rtc_selftest_half_minmax(uint32_t* mismatches, void* hip_stream);
  * product), product = 0 min-plus convolution, 1 max-plus deconvolution, 2 max-plus convolution,
  * 3 min-plus deconvolution.  Not thread-safe. */
 #define RTC_PROFILE_KIND(dtype, packed, product) ((dtype) * 8 + (packed) * 4 + (product))
+#define RTC_PROFILE_KIND_TAIL 64   /* the scan (+ event-domain inverses) kernel of rtc_gpc_step */
 int rtc_profile_enable(int on);
 int rtc_profile_read(int max_entries, int* kinds, float* ms);
 

@@ -122,6 +122,69 @@ __device__ __forceinline__ void windowed_counts(const T* __restrict__ fr, int n,
   }
 }
 
+// Both pseudo-inverses of a workgroup's queries from ONE staged window: with a = the number of
+// samples below the smallest query and b = the number of samples not above the largest one, the
+// stretch fr[a, b) holds every sample that lies inside the queries' range, so for each query
+//   lower count (samples <  x) = a + (samples of the window <  x)
+//   upper count (samples <= x) = a + (samples of the window <= x).
+// THREADS threads (a multiple of 64, at most 1024), PER queries per thread, WINDOW samples of LDS
+// in s_win; a longer stretch falls back to the plain searches per thread.
+template <typename T, int THREADS, int PER, int WINDOW>
+__device__ __forceinline__ void windowed_counts_both(const T* __restrict__ fr, int n, const T (&xv)[PER], T* s_win,
+                                                     int (&cnt_lo)[PER], int (&cnt_up)[PER]) {
+  constexpr int NW = THREADS / 64;
+  __shared__ T s_mm[2][NW];
+  __shared__ int s_ab[2];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  T xmin = xv[0], xmax = xv[0];
+#pragma unroll
+  for (int e = 1; e < PER; ++e) { xmin = xv[e] < xmin ? xv[e] : xmin; xmax = vmax(xmax, xv[e]); }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const T a = __shfl_xor(xmin, off), b = __shfl_xor(xmax, off);
+    xmin = a < xmin ? a : xmin; xmax = vmax(xmax, b);
+  }
+  if (lane == 0) { s_mm[0][wave] = xmin; s_mm[1][wave] = xmax; }
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < NW; ++w) { xmin = s_mm[0][w] < xmin ? s_mm[0][w] : xmin; xmax = vmax(xmax, s_mm[1][w]); }
+  if (wave < 2) {
+    const T q = wave == 0 ? xmin : xmax;
+    const bool upper = wave == 1;
+    const int at = wave_first_true(n, [&](int k) { return beyond(fr[k], q, upper); });
+    if (lane == 0) s_ab[wave] = at;
+  }
+  __syncthreads();
+  const int a = s_ab[0], len = s_ab[1] - a;
+  if (len >= 0 && len <= WINDOW) {
+#pragma unroll 4
+    for (int i = threadIdx.x; i < len; i += THREADS) s_win[i] = fr[a + i];
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+      int lo = 0, hi = len;
+      while (lo < hi) {                       // samples < x
+        const int mid = (lo + hi) >> 1;
+        if (s_win[mid] >= xv[e]) hi = mid; else lo = mid + 1;
+      }
+      cnt_lo[e] = a + lo;
+      hi = len;                               // samples <= x: from the first one >= x on
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (s_win[mid] > xv[e]) hi = mid; else lo = mid + 1;
+      }
+      cnt_up[e] = a + lo;
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+      cnt_lo[e] = lower_index(fr, n, xv[e]);
+      cnt_up[e] = upper_index(fr, n, xv[e]) + 1;
+    }
+  }
+  __syncthreads();   // s_win and the small arrays may be reused by the caller's next pass
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void pinv_kernel(const T* __restrict__ f, int n,
                                                    const T* __restrict__ x, int m,
@@ -294,6 +357,102 @@ __global__ __launch_bounds__(1024) void residual_service_kernel(const T* __restr
   }
 }
 
+// The tail of a greedy processing component in one kernel: the remaining service as in
+// residual_service_kernel, and the event-domain images of the values while they are still in
+// registers -- ev_lo / ev_up (each optional) = lower / upper pseudo-inverse of gamma at out[D].
+// The values of a pass are monotone in scan order, so their answers fall into one stretch of
+// gamma, which windowed_counts_both stages once for both inverses: gamma and out are read resp.
+// written once instead of twice and three times.
+template <typename T> constexpr int tail_window() { return sizeof(T) == 8 ? 6144 : 8192; }
+
+template <typename T, bool SUFFIX>
+__global__ __launch_bounds__(1024) void gpc_tail_kernel(const T* __restrict__ beta, const T* __restrict__ alpha,
+                                                        T* __restrict__ out, int n, int parts, int seg,
+                                                        const T* __restrict__ gamma, int n_gamma,
+                                                        int32_t* __restrict__ ev_lo, int32_t* __restrict__ ev_up) {
+  using S = ScanOp<T, SUFFIX>;
+  constexpr int kPer = 4;
+  __shared__ T s_win[tail_window<T>()];
+  __shared__ T wave_tot[16];
+  __shared__ T carry_s;
+  const int row = blockIdx.x / parts, part = blockIdx.x % parts;
+  const int start = part * seg;
+  if (start >= n) return;
+  const int end = min(n, start + seg);
+  const T* bl = beta + (int64_t)row * n;
+  const T* au = alpha + (int64_t)row * n;
+  const T* gr = gamma + (int64_t)row * n_gamma;
+  T* o = out + (int64_t)row * n;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  T carry = S::id();
+  if (start > 0) {
+    T acc = S::id();
+#pragma unroll 8
+    for (int p = threadIdx.x; p < start; p += 1024) {
+      const int i = SUFFIX ? n - 1 - p : p;
+      acc = S::op(acc, (T)(bl[i] - au[i]));
+    }
+    const T incl = wave_scan<T, SUFFIX>(acc);
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < 16; ++w) carry = S::op(carry, wave_tot[w]);
+    __syncthreads();
+  }
+  auto load = [&](int base, T (&d)[kPer]) {
+#pragma unroll
+    for (int e = 0; e < kPer; ++e) {
+      const int p = base + threadIdx.x * kPer + e;
+      const int i = SUFFIX ? n - 1 - p : p;
+      d[e] = p < n ? (T)(bl[i] - au[i]) : S::id();
+    }
+  };
+  T next[kPer];
+  load(start, next);
+  for (int base = start; base < end; base += 1024 * kPer) {
+    const int p0 = base + threadIdx.x * kPer;   // position in scan order
+    T v[kPer];
+    T run = S::id();
+#pragma unroll
+    for (int e = 0; e < kPer; ++e) {
+      run = S::op(run, next[e]);
+      v[e] = run;
+    }
+    if (base + 1024 * kPer < end) load(base + 1024 * kPer, next);
+    const T incl = wave_scan<T, SUFFIX>(run);
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    T before = carry;
+    for (int w = 0; w < wave; ++w) before = S::op(before, wave_tot[w]);
+    T prev = __shfl_up(incl, 1);
+    if (lane == 0) prev = S::id();
+    before = S::op(before, prev);
+    // a position past the row's end repeats the value before it (its difference is the scan's
+    // identity), i.e. a real query, which is what the windowed search asks for
+    T q[kPer];
+#pragma unroll
+    for (int e = 0; e < kPer; ++e) {
+      const T r = S::op(before, v[e]);
+      q[e] = r > (T)0 ? r : (T)0;
+      const int p = p0 + e;
+      if (p < n) o[SUFFIX ? n - 1 - p : p] = q[e];
+    }
+    if (threadIdx.x == 1023) carry_s = S::op(before, run);
+    int cnt_lo[kPer], cnt_up[kPer];
+    windowed_counts_both<T, 1024, kPer, tail_window<T>()>(gr, n_gamma, q, s_win, cnt_lo, cnt_up);   // (has barriers)
+#pragma unroll
+    for (int e = 0; e < kPer; ++e) {
+      const int p = p0 + e;
+      if (p < n) {
+        const int64_t at = (int64_t)row * n + (SUFFIX ? n - 1 - p : p);
+        if (ev_lo != nullptr) ev_lo[at] = cnt_lo[e];
+        if (ev_up != nullptr) ev_up[at] = cnt_up[e] - 1;
+      }
+    }
+    carry = carry_s;
+  }
+}
+
 __device__ __forceinline__ void atomic_max_any(int32_t* p, int32_t v) { atomicMax(p, v); }
 __device__ __forceinline__ void atomic_max_any(int64_t* p, int64_t v) { atomicMax((long long*)p, (long long)v); }
 __device__ __forceinline__ void atomic_max_any(double* p, double v) { atomicMax(p, v); }
@@ -304,21 +463,34 @@ __global__ __launch_bounds__(256) void init_kernel(T* __restrict__ dst, int coun
   if (i < count) dst[i] = value;
 }
 
+// h[i] = 0 and (v optional) v[i] = value for i < count: the starting values of the deviation kernels' atomic maxima
+template <typename T>
+__global__ __launch_bounds__(256) void init2_kernel(int32_t* __restrict__ h, T* __restrict__ v, int count, T value) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < count) {
+    h[i] = 0;
+    if (v != nullptr) v[i] = value;
+  }
+}
+
 constexpr int kDevPerThread = 4;   // alpha samples per thread in the deviation kernels
 constexpr int kDevPerBlock = 256 * kDevPerThread;
 
 // Maximal horizontal deviation: each thread searches beta for a few alpha[D]; a workgroup
 // covers kDevPerBlock consecutive D of one row and merges into out[row] (pre-set to 0) with
 // an atomic max.
+// With out_v (optional; pre-set to the lowest value) the same pass also takes the maximal vertical
+// deviation of its samples, alpha[D] - beta[D]: delay and backlog bound from one read of alpha.
 template <typename T>
 __global__ __launch_bounds__(256) void hdev_kernel(const T* __restrict__ alpha,
                                                    const T* __restrict__ beta, int32_t* __restrict__ out,
                                                    int n, int blocks_per_row,
-                                                   int32_t* __restrict__ dev_flags) {
+                                                   int32_t* __restrict__ dev_flags, T* __restrict__ out_v) {
   static_assert(kDevPerThread == kSearchPerThread, "the deviation kernels search kSearchPerThread samples per thread");
   __shared__ T s_win[kSearchWindow];
   __shared__ int32_t red[4];
   __shared__ int32_t unb[4];
+  __shared__ T redv[4];
   const int row = blockIdx.x / blocks_per_row;
   const int base = (blockIdx.x % blocks_per_row) * kDevPerBlock;
   const T* a = alpha + (int64_t)row * n;
@@ -326,6 +498,15 @@ __global__ __launch_bounds__(256) void hdev_kernel(const T* __restrict__ alpha,
   T xv[kSearchPerThread];
 #pragma unroll
   for (int e = 0; e < kDevPerThread; ++e) xv[e] = a[min(base + e * 256 + (int)threadIdx.x, n - 1)];   // past the end: the last sample again
+  T vmaxdev = lowest<T>();
+  if (out_v != nullptr) {
+#pragma unroll
+    for (int e = 0; e < kDevPerThread; ++e)     // (a repeated last sample changes no maximum)
+      vmaxdev = vmax(vmaxdev, (T)(xv[e] - b[min(base + e * 256 + (int)threadIdx.x, n - 1)]));
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) vmaxdev = vmax(vmaxdev, __shfl_xor(vmaxdev, off));
+    if ((threadIdx.x & 63) == 0) redv[threadIdx.x >> 6] = vmaxdev;    // read after the barriers of the search below
+  }
   int cnt[kSearchPerThread];
   windowed_counts(b, n, xv, false, s_win, cnt);
   int32_t h = 0;
@@ -348,6 +529,7 @@ __global__ __launch_bounds__(256) void hdev_kernel(const T* __restrict__ alpha,
     const int32_t m = max(max(red[0], red[1]), max(red[2], red[3]));
     if (m > 0) atomicMax(&out[row], m);
     if (dev_flags != nullptr && (unb[0] | unb[1] | unb[2] | unb[3])) atomicOr(dev_flags, RTC_FLAG_UNBOUNDED);
+    if (out_v != nullptr) atomic_max_any(&out_v[row], vmax(vmax(redv[0], redv[1]), vmax(redv[2], redv[3])));
   }
 }
 
@@ -441,33 +623,48 @@ int launch_compose(const void* outer, int64_t n_outer, const int32_t* inner, int
 }
 
 int launch_residual_service(const void* beta, const void* alpha, void* out, int64_t batch,
-                            int64_t n, int dt, bool suffix_min, hipStream_t stream) {
+                            int64_t n, int dt, bool suffix_min, hipStream_t stream, const void* gamma,
+                            int64_t n_gamma, int32_t* ev_lo, int32_t* ev_up) {
   // Several workgroups per row when the rows alone would not fill the chip.  A workgroup's passes
   // over its segment are bound by latency (about 3.3 us each, measured), the whole launch by its
   // traffic: 3 arrays, plus (parts - 1) more for what the workgroups re-read before their segments
   // (at about 3.5 TB/s).  Take the power of two that minimises the larger of the two.
+  const bool events = gamma != nullptr && (ev_lo != nullptr || ev_up != nullptr);
   int64_t parts = 1;
   {
     const double array_bytes = (double)batch * (double)n * (dt == RTC_I32 ? 4.0 : 8.0);
     double best = 1e300;
     for (int64_t p = 1; p <= 16 && (p == 1 || (batch * p <= 512 && n / p >= 8192)); p *= 2) {
-      const double latency_us = (double)((n + p * 4096 - 1) / (p * 4096)) * 3.3;
-      const double traffic_us = (2.0 + (double)p) * array_bytes / 3.5e6;
+      // with the event-domain images a pass also searches (two barriers and a staged window more)
+      const double latency_us = (double)((n + p * 4096 - 1) / (p * 4096)) * (events ? 6.0 : 3.3);
+      const double traffic_us = ((events ? 4.0 : 2.0) + (double)p) * array_bytes / 3.5e6;
       const double t = latency_us > traffic_us ? latency_us : traffic_us;
       if (t < best) { best = t; parts = p; }
     }
   }
   const int64_t seg = ((n + parts - 1) / parts + 4095) / 4096 * 4096;
   if (batch * parts > 0x7fffffffLL) return RTC_ERR_SHAPE;
+  prof_begin(RTC_PROFILE_KIND_TAIL, stream);
   RTC_DISPATCH(dt, {
-    if (suffix_min)
+    if (events) {
+      if (suffix_min)
+        hipLaunchKernelGGL((gpc_tail_kernel<T, true>), dim3((uint32_t)(batch * parts)), dim3(1024), 0, stream,
+                           static_cast<const T*>(beta), static_cast<const T*>(alpha), static_cast<T*>(out), (int)n,
+                           (int)parts, (int)seg, static_cast<const T*>(gamma), (int)n_gamma, ev_lo, ev_up);
+      else
+        hipLaunchKernelGGL((gpc_tail_kernel<T, false>), dim3((uint32_t)(batch * parts)), dim3(1024), 0, stream,
+                           static_cast<const T*>(beta), static_cast<const T*>(alpha), static_cast<T*>(out), (int)n,
+                           (int)parts, (int)seg, static_cast<const T*>(gamma), (int)n_gamma, ev_lo, ev_up);
+    } else if (suffix_min) {
       hipLaunchKernelGGL((residual_service_kernel<T, true>), dim3((uint32_t)(batch * parts)), dim3(1024), 0, stream,
                          static_cast<const T*>(beta), static_cast<const T*>(alpha), static_cast<T*>(out), (int)n,
                          (int)parts, (int)seg);
-    else
+    } else {
       hipLaunchKernelGGL((residual_service_kernel<T, false>), dim3((uint32_t)(batch * parts)), dim3(1024), 0, stream,
                          static_cast<const T*>(beta), static_cast<const T*>(alpha), static_cast<T*>(out), (int)n,
                          (int)parts, (int)seg);
+    }
+    prof_end(stream);
     return hip_ok();
   });
 }
@@ -494,15 +691,16 @@ int launch_copy(const void* src, void* dst, int64_t count, int dt, hipStream_t s
 }
 
 int launch_max_hdev(const void* alpha, const void* beta, int32_t* out, int64_t batch, int64_t n,
-                    int dt, int32_t* dev_flags, hipStream_t stream) {
+                    int dt, int32_t* dev_flags, hipStream_t stream, void* out_v) {
   const int64_t bpr = (n + kDevPerBlock - 1) / kDevPerBlock;
   if (bpr * batch > 0x7fffffffLL) return RTC_ERR_SHAPE;
-  hipLaunchKernelGGL(init_kernel<int32_t>, dim3((uint32_t)((batch + 255) / 256)), dim3(256), 0, stream, out,
-                     (int)batch, 0);
   RTC_DISPATCH(dt, {
+    hipLaunchKernelGGL(init2_kernel<T>, dim3((uint32_t)((batch + 255) / 256)), dim3(256), 0, stream, out,
+                       static_cast<T*>(out_v), (int)batch, std::numeric_limits<T>::has_infinity
+                           ? (T)-std::numeric_limits<T>::infinity() : std::numeric_limits<T>::lowest());
     hipLaunchKernelGGL(hdev_kernel<T>, dim3((uint32_t)(bpr * batch)), dim3(256), 0, stream,
                        static_cast<const T*>(alpha), static_cast<const T*>(beta), out, (int)n, (int)bpr,
-                       dev_flags);
+                       dev_flags, static_cast<T*>(out_v));
     return hip_ok();
   });
 }

@@ -67,6 +67,19 @@ int rtc_maxplus_deconv(const void* f, const void* g, void* out, int64_t batch, i
                          dev_flags, static_cast<hipStream_t>(hip_stream));
 }
 
+int rtc_product_census(int op, const void* f, const void* g, int64_t batch, int64_t n, int64_t stride_f,
+                       int64_t stride_g, rtc_dtype dt, void* ws, size_t ws_bytes, uint64_t* counts,
+                       void* hip_stream) {
+  if (counts == nullptr) return RTC_ERR_NULL;
+  if (op != RTC_OP_CONV && op != RTC_OP_DECONV && op != RTC_OP_MAXCONV && op != RTC_OP_MINDECONV) return RTC_ERR_MODE;
+  if (!aligned(counts, 8)) return RTC_ERR_ALIGN;
+  // `counts` stands in for the output in the argument check (non-null, aligned); no output is written
+  if (int rc = check_product(f, g, counts, batch, n, stride_f, stride_g, dt, ws, ws_bytes, nullptr)) return rc;
+  static_assert(sizeof(unsigned long long) == sizeof(uint64_t), "census words");
+  return launch_tropical(op, f, g, nullptr, batch, n, stride_f, stride_g, dt, nullptr, ws, ws_bytes, nullptr,
+                         static_cast<hipStream_t>(hip_stream), reinterpret_cast<unsigned long long*>(counts));
+}
+
 int rtc_product_structure(int op, const void* f, const void* g, int32_t* codes, int64_t batch, int64_t n,
                           int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* hip_stream) {
   return rtc_product_periods(op, f, g, codes, nullptr, batch, n, stride_f, stride_g, dt, hip_stream);
@@ -146,18 +159,10 @@ int rtc_gpc_step(const rtc_gpc_args* a, void* hip_stream) {
   rc = launch_tropical(RTC_OP_DECONV, c, a->beta_l, a->alpha_u_out, batch, n, n, n, a->dt, a->beta_u, sub_ws,
                        sub_bytes, a->dev_flags, stream);
   if (rc != RTC_OK) return rc;
-  rc = launch_residual_service(a->beta_l, a->alpha_u, a->beta_l_out, batch, n, a->dt, false, stream);
+  // beta'^l and, while its values are in registers, their event-domain images: one kernel
+  rc = launch_residual_service(a->beta_l, a->alpha_u, a->beta_l_out, batch, n, a->dt, false, stream, a->gamma_u,
+                               a->n_gamma, a->events_lower, a->events_upper);
   if (rc != RTC_OK) return rc;
-  if (a->events_lower != nullptr) {
-    rc = launch_pseudo_inverse(a->gamma_u, a->n_gamma, a->beta_l_out, n, a->events_lower, batch,
-                               RTC_INV_LOWER, a->dt, stream);
-    if (rc != RTC_OK) return rc;
-  }
-  if (a->events_upper != nullptr) {
-    rc = launch_pseudo_inverse(a->gamma_u, a->n_gamma, a->beta_l_out, n, a->events_upper, batch,
-                               RTC_INV_UPPER, a->dt, stream);
-    if (rc != RTC_OK) return rc;
-  }
   if (a->alpha_l != nullptr) {
     // lower arrival / upper service side: alpha'^l = min((alpha^l (/) beta^u) (x) beta^l, beta^l),
     // beta'^u[D] = max(0, min_{l>=D} beta^u[l] - alpha^l[l]); the intermediate reuses c
@@ -167,18 +172,9 @@ int rtc_gpc_step(const rtc_gpc_args* a, void* hip_stream) {
     rc = launch_tropical(RTC_OP_CONV, c, a->beta_l, a->alpha_l_out, batch, n, n, n, a->dt, a->beta_l, sub_ws,
                          sub_bytes, a->dev_flags, stream);
     if (rc != RTC_OK) return rc;
-    rc = launch_residual_service(a->beta_u, a->alpha_l, a->beta_u_out, batch, n, a->dt, true, stream);
+    rc = launch_residual_service(a->beta_u, a->alpha_l, a->beta_u_out, batch, n, a->dt, true, stream, a->gamma_l,
+                                 a->n_gamma_l, a->events_u_lower, a->events_u_upper);
     if (rc != RTC_OK) return rc;
-    if (a->events_u_lower != nullptr) {
-      rc = launch_pseudo_inverse(a->gamma_l, a->n_gamma_l, a->beta_u_out, n, a->events_u_lower, batch,
-                                 RTC_INV_LOWER, a->dt, stream);
-      if (rc != RTC_OK) return rc;
-    }
-    if (a->events_u_upper != nullptr) {
-      rc = launch_pseudo_inverse(a->gamma_l, a->n_gamma_l, a->beta_u_out, n, a->events_u_upper, batch,
-                                 RTC_INV_UPPER, a->dt, stream);
-      if (rc != RTC_OK) return rc;
-    }
   }
   return RTC_OK;
 }
@@ -264,6 +260,17 @@ int rtc_max_hdev(const void* alpha, const void* beta, int32_t* out, int64_t batc
   if (!aligned(alpha, es) || !aligned(beta, es) || !aligned(out, 4) || !aligned(dev_flags, 4))
     return RTC_ERR_ALIGN;
   return launch_max_hdev(alpha, beta, out, batch, n, dt, dev_flags, static_cast<hipStream_t>(hip_stream));
+}
+
+int rtc_max_deviations(const void* alpha, const void* beta, int32_t* out_h, void* out_v, int64_t batch, int64_t n,
+                       rtc_dtype dt, int32_t* dev_flags, void* hip_stream) {
+  if (alpha == nullptr || beta == nullptr || out_h == nullptr || out_v == nullptr) return RTC_ERR_NULL;
+  const size_t es = elem_size(dt);
+  if (es == 0) return RTC_ERR_DTYPE;
+  if (int rc = check_shape(batch, n)) return rc;
+  if (!aligned(alpha, es) || !aligned(beta, es) || !aligned(out_h, 4) || !aligned(out_v, es) || !aligned(dev_flags, 4))
+    return RTC_ERR_ALIGN;
+  return launch_max_hdev(alpha, beta, out_h, batch, n, dt, dev_flags, static_cast<hipStream_t>(hip_stream), out_v);
 }
 
 int rtc_validate_monotone(const void* f, int64_t batch, int64_t n, int64_t stride, rtc_dtype dt,

@@ -17,9 +17,13 @@ inline size_t elem_size(int dt) {
 // Tropical product launchers (tropical.hip).  `op` is RTC_OP_CONV, _DECONV, _MAXCONV or _MINDECONV.
 // `cap` (optional, dense [batch][n]) fuses out = min(out, cap) into the store, which is how
 // the greedy-processing-component step applies its final min with beta^u.
+// With `census` (device, RTC_CENSUS_COUNTS words) the call classifies and prepares the rows exactly
+// as the product would and then, instead of computing it, adds to census[] how much of the
+// iteration space each arithmetic flavour would take (rtc_product_census); `out` is not touched.
 int launch_tropical(int op, const void* f, const void* g, void* out, int64_t batch, int64_t n,
                     int64_t stride_f, int64_t stride_g, int dt, const void* cap, void* ws,
-                    size_t ws_bytes, int32_t* dev_flags, hipStream_t stream);
+                    size_t ws_bytes, int32_t* dev_flags, hipStream_t stream,
+                    unsigned long long* census = nullptr);
 size_t tropical_workspace_bytes(int64_t batch, int64_t n, int dt);
 // Per-row selector codes of the products' convexity test (RTC_STRUCTURE_*), see rtc_product_structure.
 int launch_structure_probe(int op, const void* f, const void* g, int32_t* codes, int32_t* periods, int64_t batch,
@@ -36,13 +40,17 @@ int launch_pseudo_inverse(const void* f, int64_t n, const void* x, int64_t m, in
                           int64_t batch, int mode, int dt, hipStream_t stream);
 int launch_compose(const void* outer, int64_t n_outer, const int32_t* inner, int64_t n, void* out,
                    int64_t batch, int dt, int32_t* dev_flags, hipStream_t stream);
+// Remaining service of a component and, with gamma and at least one of ev_lo / ev_up, its
+// event-domain images (lower / upper pseudo-inverse of gamma at the result) in the same kernel.
 int launch_residual_service(const void* beta, const void* alpha, void* out, int64_t batch,
-                            int64_t n, int dt, bool suffix_min, hipStream_t stream);
+                            int64_t n, int dt, bool suffix_min, hipStream_t stream, const void* gamma = nullptr,
+                            int64_t n_gamma = 0, int32_t* ev_lo = nullptr, int32_t* ev_up = nullptr);
 int launch_closure_init(const void* f, void* out, int64_t batch, int64_t n, int dt, bool super,
                         int32_t* dev_flags, hipStream_t stream);
 int launch_copy(const void* src, void* dst, int64_t count, int dt, hipStream_t stream);
+// out_v (optional, [batch] of dtype dt): the maximal vertical deviation from the same pass
 int launch_max_hdev(const void* alpha, const void* beta, int32_t* out, int64_t batch, int64_t n,
-                    int dt, int32_t* dev_flags, hipStream_t stream);
+                    int dt, int32_t* dev_flags, hipStream_t stream, void* out_v = nullptr);
 int launch_validate_monotone(const void* f, int64_t batch, int64_t n, int64_t stride, int dt, int32_t* first_bad,
                              int32_t* dev_flags, hipStream_t stream);
 int launch_max_vdev(const void* alpha, const void* beta, void* out, int64_t batch, int64_t n, int dt,

@@ -247,6 +247,48 @@ PackLayout pack_layout(int64_t batch, int64_t n) {
   return L;
 }
 
+// rtc_product_census: which arithmetic would do how much.  One workgroup per (row, tile of 2048
+// outputs), its threads over the chunks of the tile; the unit is one sub-chunk (128 steps) of one
+// such tile.  counts: [0] 15-bit flavour on the chunk base, [1] 15-bit flavour on sub-chunk bases,
+// [2] 16-bit saturating flavour, [3] 32-bit items, [4] rows that other kernels do.
+__global__ __launch_bounds__(64) void census_kernel(PackAux x, const int32_t* __restrict__ sel, int n, int batch,
+                                                    int plain_kind, unsigned long long* __restrict__ counts) {
+  const int row = blockIdx.x % batch, T2 = blockIdx.x / batch;
+  const int s_end = min((T2 + 1) * kPkW, n);
+  unsigned long long c[RTC_CENSUS_COUNTS] = {};
+  for (int ch = threadIdx.x; ch * kPkChunk < s_end; ch += 64) {
+    const int left = s_end - ch * kPkChunk;
+    const int valid = min((left + kPkSub - 1) / kPkSub, kPkSubs);
+    const int mask = (1 << valid) - 1;
+    if (sel != nullptr && sel[row] != 1) { c[4] += valid; continue; }
+    if (x.apk == nullptr) { c[plain_kind] += valid; continue; }   // no packed path in this call
+    int32_t gb, br;
+    const int plan = chunk_plan(x, row, T2, ch, n, &gb, &br);
+    const int taken = __builtin_popcount(plan & mask);
+    if (plan & kPlanNarrow) c[(plan & kPlanWhole) ? 0 : 1] += taken; else c[2] += taken;
+    c[3] += valid - taken;
+  }
+#pragma unroll
+  for (int k = 0; k < RTC_CENSUS_COUNTS; ++k) {
+    unsigned long long v = c[k];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    if (threadIdx.x == 0 && v != 0) atomicAdd(&counts[k], v);
+  }
+}
+
+// The census of a product that runs without the packed path: every row (with `sel`: every row
+// whose selector is 1) counts under `kind`, the others under [4].
+int launch_plain_census(const int32_t* sel, int kind, int64_t batch, int64_t n, unsigned long long* counts,
+                        hipStream_t stream) {
+  PackAux none = {};
+  const int64_t n_t2 = (n + kPkW - 1) / kPkW;
+  if (batch * n_t2 > 0x7fffffffLL) return RTC_ERR_SHAPE;
+  hipLaunchKernelGGL(census_kernel, dim3((uint32_t)(batch * n_t2)), dim3(64), 0, stream, none, sel, (int)n, (int)batch,
+                     kind, counts);
+  return hip_ok();
+}
+
 // int32 product with the packed fast path.  f32 / g32 are int32 rows (the caller's own,
 // or the narrowed copies of int64 rows); pack_ok / rho were written by the probe and the output
 // is already filled with the identity.  `sel` (optional) restricts both kernels to rows with
@@ -254,7 +296,7 @@ PackLayout pack_layout(int64_t batch, int64_t n) {
 template <typename OutT, int OP>
 int run_packed(const int32_t* f32, int64_t stride_f, const int32_t* g32, int64_t stride_g, OutT* out,
                const OutT* cap, const int32_t* sel, const int64_t* out_base, int64_t batch, int64_t n, char* wsp,
-               const PackLayout& L, hipStream_t stream) {
+               const PackLayout& L, hipStream_t stream, unsigned long long* census) {
   PackAux aux;
   aux.apk = reinterpret_cast<uint32_t*>(wsp + L.off_apk);
   aux.apk_s = reinterpret_cast<uint32_t*>(wsp + L.off_apk_s);
@@ -280,6 +322,13 @@ int run_packed(const int32_t* f32, int64_t stride_f, const int32_t* g32, int64_t
                      const_cast<int32_t*>(aux.bmn), const_cast<int32_t*>(aux.bmx));
   hipLaunchKernelGGL(decide_kernel, dim3((uint32_t)batch), dim3(kDecideThreads), 0, stream, aux, (int)n,
                      const_cast<int32_t*>(aux.pack_ok));
+  if (census != nullptr) {
+    const int64_t n_t2 = (n + kPkW - 1) / kPkW;
+    if (batch * n_t2 > 0x7fffffffLL) return RTC_ERR_SHAPE;
+    hipLaunchKernelGGL(census_kernel, dim3((uint32_t)(batch * n_t2)), dim3(64), 0, stream, aux, sel, (int)n, (int)batch,
+                       3, census);
+    return hip_ok();
+  }
   // short rows: tiles of 1024 outputs halve the candidates wasted on the diagonal
   const bool small_tiles = n <= g_packed_small_n;
   const Plan pk = make_plan(batch, n, small_tiles ? kPkW / 2 : kPkW, kPkChunk);
@@ -319,7 +368,7 @@ bool packed_worthwhile(int64_t batch, int64_t n) {
 template <typename T, int OP>
 int run_typed(const void* f, const void* g, void* out, int64_t batch, int64_t n, int64_t stride_f,
               int64_t stride_g, const void* cap, void* ws, size_t ws_bytes, int32_t* dev_flags,
-              hipStream_t stream) {
+              hipStream_t stream, unsigned long long* census) {
   // convolution: uniform operand f, window g.  deconvolution: uniform g, window f (reversed).
   const T* a = static_cast<const T*>(op_sub(OP) ? g : f);
   const T* b = static_cast<const T*>(op_sub(OP) ? f : g);
@@ -340,13 +389,13 @@ int run_typed(const void* f, const void* g, void* out, int64_t batch, int64_t n,
         launch_period<int32_t>(static_cast<const int32_t*>(f), stride_f, static_cast<const int32_t*>(g), stride_g, sel,
                              reinterpret_cast<int32_t*>(wsp + L.off_period),
                              reinterpret_cast<int32_t*>(wsp + L.off_ok), batch, n, OP, stream);
-      launch_fill<int32_t, OP>(static_cast<int32_t*>(out), batch * n, stream);
+      if (census == nullptr) launch_fill<int32_t, OP>(static_cast<int32_t*>(out), batch * n, stream);
       // general rows (selector 1): packed + 32-bit items; rows of exploitable convexity: structured_kernel
       const int rc = run_packed<int32_t, OP>(static_cast<const int32_t*>(f), stride_f,
                                              static_cast<const int32_t*>(g), stride_g, static_cast<int32_t*>(out),
                                              static_cast<const int32_t*>(cap), sel, nullptr, batch, n, wsp, L,
-                                             stream);
-      if (rc != RTC_OK || !g_structure_paths) return rc;
+                                             stream, census);
+      if (rc != RTC_OK || !g_structure_paths || census != nullptr) return rc;
       return launch_structured<int32_t, OP>(static_cast<const int32_t*>(f), stride_f,
                                             static_cast<const int32_t*>(g), stride_g, static_cast<int32_t*>(out),
                                             static_cast<const int32_t*>(cap), sel,
@@ -355,6 +404,9 @@ int run_typed(const void* f, const void* g, void* out, int64_t batch, int64_t n,
                                             reinterpret_cast<int32_t*>(wsp + L.off_F), batch, n, stream);
     }
   }
+  // no packed path: the 32-bit kernel (counts[3]), or the fp64 kernel (counts[4]), does every row
+  if (census != nullptr)
+    return launch_plain_census(nullptr, std::is_same<T, int32_t>::value ? 3 : 4, batch, n, census, stream);
   if (dev_flags != nullptr && std::numeric_limits<T>::is_integer) {
     hipLaunchKernelGGL(probe_kernel<T>, dim3((uint32_t)batch), dim3(1024), 0, stream,
                        static_cast<const T*>(f), stride_f, static_cast<const T*>(g), stride_g, (int)n,
@@ -381,7 +433,8 @@ size_t narrow_bytes(int64_t batch, int64_t n) {
 
 template <int OP>
 int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, int64_t stride_f,
-            int64_t stride_g, const void* cap, void* ws, int32_t* dev_flags, hipStream_t stream) {
+            int64_t stride_g, const void* cap, void* ws, int32_t* dev_flags, hipStream_t stream,
+            unsigned long long* census) {
   // workspace: [f32: batch*n][g32: batch*n][narrow_ok: batch][out_base: 2*batch int64][probe partials]
   // [block tables of the re-based path][packed-path arrays]
   int32_t* f32 = static_cast<int32_t*>(ws);
@@ -426,11 +479,17 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
   }
   // Several kernels see every row; the selector makes each row run in exactly one family.
   // The output is filled once with the identity, before all of them.
+  if (census != nullptr) {   // rows with selector 1: packed + 32-bit items, or 32-bit items alone; the rest: other kernels
+    if (packed_worthwhile(batch, n))
+      return run_packed<int64_t, OP>(f32, n, g32, n, static_cast<int64_t*>(out), static_cast<const int64_t*>(cap),
+                                     ok, base, batch, n, wsp, L, stream, census);
+    return launch_plain_census(ok, 3, batch, n, census, stream);
+  }
   launch_fill<int64_t, OP>(static_cast<int64_t*>(out), batch * n, stream);
   int rc;
   if (packed_worthwhile(batch, n)) {
     rc = run_packed<int64_t, OP>(f32, n, g32, n, static_cast<int64_t*>(out), static_cast<const int64_t*>(cap),
-                                 ok, base, batch, n, wsp, L, stream);
+                                 ok, base, batch, n, wsp, L, stream, nullptr);
   } else {
     rc = run_product<int32_t, int64_t, OP>(op_sub(OP) ? g32 : f32, n, op_sub(OP) ? f32 : g32, n,
                                            static_cast<int64_t*>(out), static_cast<const int64_t*>(cap), ok, 1,
@@ -548,7 +607,7 @@ int launch_structure_probe(int op, const void* f, const void* g, int32_t* codes,
 
 int launch_tropical(int op, const void* f, const void* g, void* out, int64_t batch, int64_t n,
                     int64_t stride_f, int64_t stride_g, int dt, const void* cap, void* ws,
-                    size_t ws_bytes, int32_t* dev_flags, hipStream_t stream) {
+                    size_t ws_bytes, int32_t* dev_flags, hipStream_t stream, unsigned long long* census) {
   if (dt == RTC_I64 && (ws == nullptr || ws_bytes < tropical_workspace_bytes(batch, n, dt)))
     return RTC_ERR_WORKSPACE;
 #define RTC_BY_OP(CALL)                                  \
@@ -561,11 +620,11 @@ int launch_tropical(int op, const void* f, const void* g, void* out, int64_t bat
   }
   switch (dt) {
     case RTC_I32:
-      RTC_BY_OP((run_typed<int32_t, OP>(f, g, out, batch, n, stride_f, stride_g, cap, ws, ws_bytes, dev_flags, stream)))
+      RTC_BY_OP((run_typed<int32_t, OP>(f, g, out, batch, n, stride_f, stride_g, cap, ws, ws_bytes, dev_flags, stream, census)))
     case RTC_F64:
-      RTC_BY_OP((run_typed<double, OP>(f, g, out, batch, n, stride_f, stride_g, cap, ws, ws_bytes, dev_flags, stream)))
+      RTC_BY_OP((run_typed<double, OP>(f, g, out, batch, n, stride_f, stride_g, cap, ws, ws_bytes, dev_flags, stream, census)))
     case RTC_I64:
-      RTC_BY_OP((run_i64<OP>(f, g, out, batch, n, stride_f, stride_g, cap, ws, dev_flags, stream)))
+      RTC_BY_OP((run_i64<OP>(f, g, out, batch, n, stride_f, stride_g, cap, ws, dev_flags, stream, census)))
     default:
       return RTC_ERR_DTYPE;
   }

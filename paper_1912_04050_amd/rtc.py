@@ -206,6 +206,27 @@ def rtc_product_structure(op: int, f, g, out=None):
     return out
 
 
+_lib.rtc_product_census.argtypes = [_int, _vp, _vp, _i64, _i64, _i64, _i64, _int, _vp, _sz, _vp, _vp]
+_lib.rtc_product_census.restype = _int
+RTC_CENSUS_COUNTS = 5
+
+
+def rtc_product_census(op: int, f, g, ws=None, counts=None):
+    """counts[RTC_CENSUS_COUNTS] (int64, device): units of the product's iteration space per arithmetic
+    flavour (15-bit on chunk base, 15-bit on sub-chunk bases, 16-bit saturating, 32-bit, other kernels)."""
+    f, bf, n, _ = _rows(f)
+    g, bg, ng, _ = _rows(g)
+    if ng != n or f.dtype != g.dtype or (bf != bg and 1 not in (bf, bg)):
+        raise ValueError("operands must have the same length and dtype, batch equal or 1")
+    batch = max(bf, bg)
+    if counts is None:
+        counts = torch.zeros(RTC_CENSUS_COUNTS, dtype=torch.int64, device=f.device)
+    ws, ws_bytes = _workspace(op, batch, n, f.dtype, f.device, ws)
+    _check(_lib.rtc_product_census(op, _ptr(f), _ptr(g), batch, n, _row_stride(f, bf, batch, n),
+                                   _row_stride(g, bg, batch, n), _DT[f.dtype], _ptr(ws), ws_bytes, _ptr(counts), _stream()))
+    return counts
+
+
 _lib.rtc_set_packed_small_n.argtypes = [_i64]
 _lib.rtc_set_packed_small_n.restype = _int
 
@@ -438,6 +459,26 @@ def rtc_max_hdev(alpha, beta, out=None, dev_flags=None):
     _check(_lib.rtc_max_hdev(_ptr(alpha), _ptr(beta), _ptr(out), batch, n, _DT[alpha.dtype],
                              _ptr(dev_flags), _stream()))
     return out
+
+
+_lib.rtc_max_deviations.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _int, _vp, _vp]
+_lib.rtc_max_deviations.restype = _int
+RTC_PROFILE_KIND_TAIL = 64
+
+
+def rtc_max_deviations(alpha, beta, out_h=None, out_v=None, dev_flags=None):
+    """(delay bound, backlog bound) per row from one pass: rtc_max_hdev and rtc_max_vdev together."""
+    alpha, batch, n = _dense(alpha)
+    beta = _dense(beta)[0]
+    if beta.shape != alpha.shape or beta.dtype != alpha.dtype:
+        raise ValueError("alpha and beta must have one shape and dtype")
+    if out_h is None:
+        out_h = torch.empty(batch, dtype=torch.int32, device=alpha.device)
+    if out_v is None:
+        out_v = torch.empty(batch, dtype=alpha.dtype, device=alpha.device)
+    _check(_lib.rtc_max_deviations(_ptr(alpha), _ptr(beta), _ptr(out_h), _ptr(out_v), batch, n, _DT[alpha.dtype],
+                                   _ptr(dev_flags), _stream()))
+    return out_h, out_v
 
 
 def rtc_max_vdev(alpha, beta, out=None):

@@ -210,6 +210,29 @@ def test_chain_bounds_config4_shape(rtc):
     run_chain_bounds(rtc, wl.config4(wl.DEFAULT_SEED, 24, 16, 16384), 24, 16)
 
 
+def test_product_census(rtc):
+    """rtc_product_census: the units it reports add up to the iteration space, rows of the headline
+    kind run in the 15-bit flavour, and a product without the packed path counts as 32-bit items."""
+    n, batch = 6000, 3
+    c = wl.config3(5, batch, n)
+    units = batch * sum((min((t + 1) * 2048, n) + 127) // 128 for t in range((n + 2047) // 2048))
+    for f, g in ((c["f"], c["g"]), (c["f"].astype(np.int32), c["g"].astype(np.int32))):
+        rtc.rtc_set_packed_min_work(0.0)
+        try:
+            counts = host(rtc.rtc_product_census(rtc.RTC_OP_CONV, dev(f), dev(g)))
+        finally:
+            rtc.rtc_set_packed_min_work(rtc.RTC_DEFAULT_PACKED_MIN_WORK)
+        assert counts.sum() == units and counts[0] + counts[1] > 0.9 * units and counts[4] == 0
+    rtc.rtc_set_packed_min_work(1e30)
+    try:
+        counts = host(rtc.rtc_product_census(rtc.RTC_OP_DECONV, dev(c["f"].astype(np.int32)), dev(c["g"].astype(np.int32))))
+        assert counts.tolist() == [0, 0, 0, units, 0]
+        counts = host(rtc.rtc_product_census(rtc.RTC_OP_CONV, dev(c["f"].astype(np.float64)), dev(c["g"].astype(np.float64))))
+        assert counts.tolist() == [0, 0, 0, 0, units]
+    finally:
+        rtc.rtc_set_packed_min_work(rtc.RTC_DEFAULT_PACKED_MIN_WORK)
+
+
 def run_config5(rtc, seed, n):
     c = wl.config5(seed, n)
     f, g, x = c["f"], c["g"], c["x"]

@@ -415,6 +415,48 @@ def test_deviations(rtc, dtype):
         want_h, fl = oracle.max_hdev(alpha, beta)
         assert np.array_equal(h, want_h) and int(host(flags)[0]) == fl
         assert np.array_equal(v, oracle.max_vdev(alpha, beta))
+        # both bounds from one pass
+        flags2 = torch.zeros(1, dtype=torch.int32, device="cuda")
+        h2, v2 = rtc.rtc_max_deviations(dev(alpha), dev(beta), dev_flags=flags2)
+        assert np.array_equal(host(h2), want_h) and int(host(flags2)[0]) == fl
+        assert np.array_equal(host(v2), oracle.max_vdev(alpha, beta))
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_gpc_tail_long_rows_and_scattered_events(rtc, dtype):
+    """The fused tail of the component step (scan + both event-domain images in one kernel): rows
+    long enough for several workgroups per row and several passes each, a workload curve gamma of
+    another length than the rows, steep and flat stretches so that the answers of one pass span
+    more of gamma than the staged window holds (the per-thread search then takes over), queries
+    below gamma[0] and above its end, plateaus in gamma; both sides of the component."""
+    rng = np.random.default_rng(77)
+    for batch, n, ng in ((2, 70001, 50000), (3, 9000, 20000), (5, 300, 64)):
+        alpha = wl.random_monotone(21, n, batch, n, dtype, max_inc=3)
+        beta_u = wl.random_monotone(21, n + 1, batch, n, dtype, max_inc=40, start_max=0)
+        beta_l = (beta_u // 2 if np.dtype(dtype) != np.float64 else beta_u / 2).astype(dtype)
+        beta_l[0, n // 3 :] += 3000                       # a jump: the answers of that pass scatter
+        alpha_l = (alpha // 3 if np.dtype(dtype) != np.float64 else alpha / 3).astype(dtype)
+        inc = rng.integers(0, 7, (batch, ng))             # plateaus (zeros) included
+        inc[:, 0] = 5                                      # some queries (0) lie below gamma[0]
+        gamma = np.cumsum(inc, axis=1).astype(dtype)
+        gamma_l = (gamma // 2 if np.dtype(dtype) != np.float64 else gamma / 2).astype(dtype)
+        say("gpc tail", dtype, batch, n, ng)
+        ev = [torch.empty((batch, n), dtype=torch.int32, device="cuda") for _ in range(4)]
+        au, bl, al, bu = rtc.rtc_gpc_step(dev(alpha), dev(beta_u), dev(beta_l), gamma_u=dev(gamma), events_lower=ev[0],
+                                          events_upper=ev[1], alpha_l=dev(alpha_l), gamma_l=dev(gamma_l),
+                                          events_u_lower=ev[2], events_u_upper=ev[3])
+        want_au, want_bl = oracle.gpc_step(alpha, beta_u, beta_l)
+        want_al, want_bu = oracle.gpc_step_lower(alpha_l, beta_u, beta_l)
+        assert np.array_equal(host(bl), want_bl) and np.array_equal(host(bu), want_bu)
+        assert np.array_equal(host(au), want_au) and np.array_equal(host(al), want_al)
+        assert np.array_equal(host(ev[0]), oracle.pseudo_inverse(gamma, want_bl, 0))
+        assert np.array_equal(host(ev[1]), oracle.pseudo_inverse(gamma, want_bl, 1))
+        assert np.array_equal(host(ev[2]), oracle.pseudo_inverse(gamma_l, want_bu, 0))
+        assert np.array_equal(host(ev[3]), oracle.pseudo_inverse(gamma_l, want_bu, 1))
+        # one inverse only
+        only = torch.empty((batch, n), dtype=torch.int32, device="cuda")
+        rtc.rtc_gpc_step(dev(alpha), dev(beta_u), dev(beta_l), gamma_u=dev(gamma), events_upper=only)
+        assert np.array_equal(host(only), oracle.pseudo_inverse(gamma, want_bl, 1))
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
