@@ -35,7 +35,7 @@ namespace {
 
 constexpr int kProfileKind = 32;   // rtc_profile_read() kind of the convolution kernel
 
-inline int hip_status() { return hipGetLastError() == hipSuccess ? BNN_OK : BNN_ERR_HIP; }
+inline int hip_status() { return rtc::hip_ok() == RTC_OK ? BNN_OK : BNN_ERR_HIP; }   // this thread's own launches only
 
 // ---- channel packing ------------------------------------------------------------------------
 
@@ -684,7 +684,7 @@ __global__ __launch_bounds__(64) void bconv_resident_half_kernel(
 template <int S, int STRIDE, int QC, int TM, int KB>
 void launch_general(const ConvArgs& a, uint32_t blocks, hipStream_t stream) {
   rtc::prof_begin(kProfileKind, stream);
-  hipLaunchKernelGGL((bconv_kernel<S, STRIDE, QC, TM, KB>), dim3(blocks), dim3(64), 0, stream, a.x, a.w, a.xi, a.gamma,
+  RTC_LAUNCH((bconv_kernel<S, STRIDE, QC, TM, KB>), dim3(blocks), dim3(64), 0, stream, a.x, a.w, a.xi, a.gamma,
                      a.out_x1, a.out_x4, a);
   rtc::prof_end(stream);
 }
@@ -707,7 +707,7 @@ bool launch_general_s(const ConvArgs& a, int stride, int qc, int tm, uint32_t bl
 template <int S, int STRIDE, int TM, int KB>
 void launch_lds_one(const ConvArgs& a, uint32_t blocks, size_t lds_bytes, hipStream_t stream) {
   rtc::prof_begin(kProfileKind, stream);
-  hipLaunchKernelGGL((bconv_lds_kernel<S, STRIDE, TM, KB>), dim3(blocks), dim3(256), lds_bytes, stream, a.x, a.w, a.xi,
+  RTC_LAUNCH((bconv_lds_kernel<S, STRIDE, TM, KB>), dim3(blocks), dim3(256), lds_bytes, stream, a.x, a.w, a.xi,
                      a.gamma, a.out_x1, a.out_x4, a);
   rtc::prof_end(stream);
 }
@@ -728,7 +728,7 @@ bool launch_lds_s(const ConvArgs& a, int stride, int tm, int kb, uint32_t blocks
 template <int R, int S, int STRIDE, int CW, int TM>
 void launch_resident_one(const ConvArgs& a, uint32_t blocks, hipStream_t stream) {
   rtc::prof_begin(kProfileKind, stream);
-  hipLaunchKernelGGL((bconv_resident_kernel<R, S, STRIDE, CW, TM>), dim3(blocks), dim3(64), 0, stream, a.x, a.w, a.xi,
+  RTC_LAUNCH((bconv_resident_kernel<R, S, STRIDE, CW, TM>), dim3(blocks), dim3(64), 0, stream, a.x, a.w, a.xi,
                      a.gamma, a.out_x1, a.out_x4, a);
   rtc::prof_end(stream);
 }
@@ -755,7 +755,7 @@ bool launch_resident(const ConvArgs& a, int R, int S, int stride, int tm, uint32
 template <int R, int S, int CW, int TM>
 void launch_resident_half_one(const ConvArgs& a, uint32_t blocks, hipStream_t stream) {
   rtc::prof_begin(kProfileKind, stream);
-  hipLaunchKernelGGL((bconv_resident_half_kernel<R, S, CW, TM>), dim3(blocks), dim3(64), 0, stream, a.x, a.w, a.xi, a.gamma,
+  RTC_LAUNCH((bconv_resident_half_kernel<R, S, CW, TM>), dim3(blocks), dim3(64), 0, stream, a.x, a.w, a.xi, a.gamma,
                      a.out_x1, a.out_x4, a);
   rtc::prof_end(stream);
 }
@@ -812,10 +812,10 @@ int bnn_pack_channels(const void* x, bnn_value_type type, uint32_t* words, int64
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const dim3 grid((uint32_t)(rows * cblocks));
   if (type == BNN_VALUE_INT8)
-    hipLaunchKernelGGL(pack_channels_kernel<int8_t>, grid, dim3(64), 0, stream, static_cast<const int8_t*>(x), words,
+    RTC_LAUNCH(pack_channels_kernel<int8_t>, grid, dim3(64), 0, stream, static_cast<const int8_t*>(x), words,
                        rows, (int)C, (int)Cw, (int)cblocks);
   else
-    hipLaunchKernelGGL(pack_channels_kernel<float>, grid, dim3(64), 0, stream, static_cast<const float*>(x), words,
+    RTC_LAUNCH(pack_channels_kernel<float>, grid, dim3(64), 0, stream, static_cast<const float*>(x), words,
                        rows, (int)C, (int)Cw, (int)cblocks);
   return hip_status();
 }
@@ -836,9 +836,9 @@ int bnn_pack_weights(const int8_t* w, uint32_t* packed, int64_t K, int64_t R, in
   if (!aligned(packed, 4)) return BNN_ERR_ALIGN;
   const int64_t Kp = (K + 63) / 64 * 64, Cw = (C + 31) / 32, taps = R * S;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  hipLaunchKernelGGL(pack_weights_kernel, dim3((uint32_t)((taps * Cw * Kp + 255) / 256)), dim3(256), 0, stream, w,
+  RTC_LAUNCH(pack_weights_kernel, dim3((uint32_t)((taps * Cw * Kp + 255) / 256)), dim3(256), 0, stream, w,
                      packed, (int)K, (int)taps, (int)C, (int)Cw, (int)Kp);
-  hipLaunchKernelGGL(weight_popcount_kernel, dim3((uint32_t)((taps * Kp + 255) / 256)), dim3(256), 0, stream, packed,
+  RTC_LAUNCH(weight_popcount_kernel, dim3((uint32_t)((taps * Kp + 255) / 256)), dim3(256), 0, stream, packed,
                      (int)taps, (int)Cw, (int)Kp);
   return hip_status();
 }

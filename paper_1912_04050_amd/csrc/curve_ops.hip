@@ -586,7 +586,7 @@ int pinv_typed(const void* f, int64_t n, const void* x, int64_t m, int32_t* out,
                hipStream_t stream) {
   const int64_t bpr = (m + kSearchPerBlock - 1) / kSearchPerBlock;
   if (bpr * batch > 0x7fffffffLL) return RTC_ERR_SHAPE;
-  hipLaunchKernelGGL(pinv_kernel<T>, dim3((uint32_t)(bpr * batch)), dim3(256), 0, stream,
+  RTC_LAUNCH(pinv_kernel<T>, dim3((uint32_t)(bpr * batch)), dim3(256), 0, stream,
                      static_cast<const T*>(f), (int)n, static_cast<const T*>(x), (int)m, out, (int)bpr, mode);
   return hip_ok();
 }
@@ -596,7 +596,7 @@ int compose_typed(const void* outer, int64_t n_outer, const int32_t* inner, int6
                   int64_t batch, int32_t* dev_flags, hipStream_t stream) {
   const int64_t bpr = (n + 255) / 256;
   if (bpr * batch > 0x7fffffffLL) return RTC_ERR_SHAPE;
-  hipLaunchKernelGGL(compose_kernel<T>, dim3((uint32_t)(bpr * batch)), dim3(256), 0, stream,
+  RTC_LAUNCH(compose_kernel<T>, dim3((uint32_t)(bpr * batch)), dim3(256), 0, stream,
                      static_cast<const T*>(outer), (int)n_outer, inner, (int)n, static_cast<T*>(out),
                      (int)bpr, dev_flags);
   return hip_ok();
@@ -648,19 +648,19 @@ int launch_residual_service(const void* beta, const void* alpha, void* out, int6
   RTC_DISPATCH(dt, {
     if (events) {
       if (suffix_min)
-        hipLaunchKernelGGL((gpc_tail_kernel<T, true>), dim3((uint32_t)(batch * parts)), dim3(1024), 0, stream,
+        RTC_LAUNCH((gpc_tail_kernel<T, true>), dim3((uint32_t)(batch * parts)), dim3(1024), 0, stream,
                            static_cast<const T*>(beta), static_cast<const T*>(alpha), static_cast<T*>(out), (int)n,
                            (int)parts, (int)seg, static_cast<const T*>(gamma), (int)n_gamma, ev_lo, ev_up);
       else
-        hipLaunchKernelGGL((gpc_tail_kernel<T, false>), dim3((uint32_t)(batch * parts)), dim3(1024), 0, stream,
+        RTC_LAUNCH((gpc_tail_kernel<T, false>), dim3((uint32_t)(batch * parts)), dim3(1024), 0, stream,
                            static_cast<const T*>(beta), static_cast<const T*>(alpha), static_cast<T*>(out), (int)n,
                            (int)parts, (int)seg, static_cast<const T*>(gamma), (int)n_gamma, ev_lo, ev_up);
     } else if (suffix_min) {
-      hipLaunchKernelGGL((residual_service_kernel<T, true>), dim3((uint32_t)(batch * parts)), dim3(1024), 0, stream,
+      RTC_LAUNCH((residual_service_kernel<T, true>), dim3((uint32_t)(batch * parts)), dim3(1024), 0, stream,
                          static_cast<const T*>(beta), static_cast<const T*>(alpha), static_cast<T*>(out), (int)n,
                          (int)parts, (int)seg);
     } else {
-      hipLaunchKernelGGL((residual_service_kernel<T, false>), dim3((uint32_t)(batch * parts)), dim3(1024), 0, stream,
+      RTC_LAUNCH((residual_service_kernel<T, false>), dim3((uint32_t)(batch * parts)), dim3(1024), 0, stream,
                          static_cast<const T*>(beta), static_cast<const T*>(alpha), static_cast<T*>(out), (int)n,
                          (int)parts, (int)seg);
     }
@@ -674,7 +674,7 @@ int launch_closure_init(const void* f, void* out, int64_t batch, int64_t n, int 
   const int64_t bpr = (n + 255) / 256;
   if (bpr * batch > 0x7fffffffLL) return RTC_ERR_SHAPE;
   RTC_DISPATCH(dt, {
-    hipLaunchKernelGGL(closure_init_kernel<T>, dim3((uint32_t)(bpr * batch)), dim3(256), 0, stream,
+    RTC_LAUNCH(closure_init_kernel<T>, dim3((uint32_t)(bpr * batch)), dim3(256), 0, stream,
                        static_cast<const T*>(f), static_cast<T*>(out), (int)n, (int)bpr, super, dev_flags);
     return hip_ok();
   });
@@ -684,7 +684,7 @@ int launch_copy(const void* src, void* dst, int64_t count, int dt, hipStream_t s
   const int64_t want = (count + 2047) / 2048;
   const int blocks = (int)(want < 65535 ? want : 65535);
   RTC_DISPATCH(dt, {
-    hipLaunchKernelGGL(copy_kernel<T>, dim3(blocks), dim3(256), 0, stream, static_cast<const T*>(src),
+    RTC_LAUNCH(copy_kernel<T>, dim3(blocks), dim3(256), 0, stream, static_cast<const T*>(src),
                        static_cast<T*>(dst), count);
     return hip_ok();
   });
@@ -695,10 +695,10 @@ int launch_max_hdev(const void* alpha, const void* beta, int32_t* out, int64_t b
   const int64_t bpr = (n + kDevPerBlock - 1) / kDevPerBlock;
   if (bpr * batch > 0x7fffffffLL) return RTC_ERR_SHAPE;
   RTC_DISPATCH(dt, {
-    hipLaunchKernelGGL(init2_kernel<T>, dim3((uint32_t)((batch + 255) / 256)), dim3(256), 0, stream, out,
+    RTC_LAUNCH(init2_kernel<T>, dim3((uint32_t)((batch + 255) / 256)), dim3(256), 0, stream, out,
                        static_cast<T*>(out_v), (int)batch, std::numeric_limits<T>::has_infinity
                            ? (T)-std::numeric_limits<T>::infinity() : std::numeric_limits<T>::lowest());
-    hipLaunchKernelGGL(hdev_kernel<T>, dim3((uint32_t)(bpr * batch)), dim3(256), 0, stream,
+    RTC_LAUNCH(hdev_kernel<T>, dim3((uint32_t)(bpr * batch)), dim3(256), 0, stream,
                        static_cast<const T*>(alpha), static_cast<const T*>(beta), out, (int)n, (int)bpr,
                        dev_flags, static_cast<T*>(out_v));
     return hip_ok();
@@ -732,7 +732,7 @@ __global__ __launch_bounds__(256) void validate_monotone_kernel(const T* __restr
 int launch_validate_monotone(const void* f, int64_t batch, int64_t n, int64_t stride, int dt, int32_t* first_bad,
                              int32_t* dev_flags, hipStream_t stream) {
   RTC_DISPATCH(dt, {
-    hipLaunchKernelGGL(validate_monotone_kernel<T>, dim3((uint32_t)batch), dim3(256), 0, stream,
+    RTC_LAUNCH(validate_monotone_kernel<T>, dim3((uint32_t)batch), dim3(256), 0, stream,
                        static_cast<const T*>(f), stride, (int)n, first_bad, dev_flags);
     return hip_ok();
   });
@@ -743,10 +743,10 @@ int launch_max_vdev(const void* alpha, const void* beta, void* out, int64_t batc
   const int64_t bpr = (n + kDevPerBlock - 1) / kDevPerBlock;
   if (bpr * batch > 0x7fffffffLL) return RTC_ERR_SHAPE;
   RTC_DISPATCH(dt, {
-    hipLaunchKernelGGL(init_kernel<T>, dim3((uint32_t)((batch + 255) / 256)), dim3(256), 0, stream,
+    RTC_LAUNCH(init_kernel<T>, dim3((uint32_t)((batch + 255) / 256)), dim3(256), 0, stream,
                        static_cast<T*>(out), (int)batch, std::numeric_limits<T>::has_infinity
                            ? (T)-std::numeric_limits<T>::infinity() : std::numeric_limits<T>::lowest());
-    hipLaunchKernelGGL(vdev_kernel<T>, dim3((uint32_t)(bpr * batch)), dim3(256), 0, stream,
+    RTC_LAUNCH(vdev_kernel<T>, dim3((uint32_t)(bpr * batch)), dim3(256), 0, stream,
                        static_cast<const T*>(alpha), static_cast<const T*>(beta), static_cast<T*>(out),
                        (int)n, (int)bpr);
     return hip_ok();

@@ -6,6 +6,9 @@
 #include "rtc_internal.h"
 
 namespace rtc {
+
+thread_local bool t_launch_failed = false;   // see launch_checked
+
 namespace {
 
 constexpr int kRing = 1024;

@@ -5,6 +5,9 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <tuple>
+#include <utility>
+
 #include "rtc.h"
 
 namespace rtc {
@@ -60,6 +63,35 @@ int launch_max_vdev(const void* alpha, const void* beta, void* out, int64_t batc
 void prof_begin(int kind, hipStream_t stream);
 void prof_end(hipStream_t stream);
 
-inline int hip_ok() { return hipGetLastError() == hipSuccess ? RTC_OK : RTC_ERR_HIP; }
+// Kernel launches go through launch_checked, which takes the launch's OWN return code (the
+// thread's sticky "last error" may belong to some other library's earlier call, and reading it
+// would both blame a good launch and swallow that error).  A failed launch is remembered per host
+// thread until hip_ok() reports it.  Arguments are converted to the kernel's parameter types
+// here, as a direct call would convert them.
+extern thread_local bool t_launch_failed;
+
+template <typename... P, typename... A, size_t... I>
+inline hipError_t launch_with_tuple(void (*kernel)(P...), dim3 grid, dim3 block, size_t shmem, hipStream_t stream,
+                                    std::index_sequence<I...>, A&&... a) {
+  std::tuple<P...> params{static_cast<P>(std::forward<A>(a))...};
+  void* ptrs[] = {static_cast<void*>(&std::get<I>(params))...};
+  return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, shmem, stream);
+}
+
+template <typename... P, typename... A>
+inline void launch_checked(void (*kernel)(P...), dim3 grid, dim3 block, size_t shmem, hipStream_t stream, A&&... a) {
+  static_assert(sizeof...(P) == sizeof...(A), "one argument per kernel parameter");
+  if (launch_with_tuple(kernel, grid, block, shmem, stream, std::index_sequence_for<P...>{}, std::forward<A>(a)...) !=
+      hipSuccess)
+    t_launch_failed = true;
+}
+#define RTC_LAUNCH(kernel, grid, block, shmem, stream, ...) ::rtc::launch_checked(kernel, grid, block, shmem, stream, __VA_ARGS__)
+
+// RTC_OK, or RTC_ERR_HIP when a launch of this thread failed since the last call (which clears it).
+inline int hip_ok() {
+  const bool failed = t_launch_failed;
+  t_launch_failed = false;
+  return failed ? RTC_ERR_HIP : RTC_OK;
+}
 
 }  // namespace rtc

@@ -28,7 +28,6 @@ void* scratch_address(int* status) {
   if (g_scratch_ptr[dev] == nullptr) {
     void* ptr = nullptr;
     if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
-      (void)hipGetLastError();
       *status = RTC_ERR_HIP;
       return nullptr;
     }

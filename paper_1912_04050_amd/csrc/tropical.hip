@@ -156,12 +156,20 @@ template <typename T, int R> Plan make_plan(int64_t batch, int64_t n) {
 // sixth of that, although each candidate costs more instructions).
 constexpr int kSmallR = 4;
 
+// Starting value of an output that work items merge into with atomics: the identity of the
+// reduction, or, for a min-type product with a fused cap, the cap itself -- an item whose partial
+// result still equals the identity skips its merge (it saw no candidate), so an output whose
+// every candidate legitimately equals the largest value of the type must already hold
+// min(identity, cap) = cap.  (Under a max-type reduction the skipped value is the smallest of the
+// type, which a min with the cap leaves as it is.)
 template <typename OutT, int OP>
-void launch_fill(OutT* out, int64_t count, hipStream_t stream) {
+void launch_fill(OutT* out, const OutT* cap, int64_t count, hipStream_t stream) {
   const int64_t want = (count + 2047) / 2048;
   const int blocks = (int)(want < 65535 ? want : 65535);
-  hipLaunchKernelGGL(fill_kernel<OutT>, dim3(blocks), dim3(256), 0, stream, out, count,
-                     host_identity<OutT, OP>());
+  if (cap != nullptr && !op_max(OP))
+    RTC_LAUNCH(copy_rows_kernel<OutT>, dim3(blocks), dim3(256), 0, stream, cap, out, count);
+  else
+    RTC_LAUNCH(fill_kernel<OutT>, dim3(blocks), dim3(256), 0, stream, out, count, host_identity<OutT, OP>());
 }
 
 // One launch of the generic kernel.  `force_atomic` is set when several kernels contribute to
@@ -180,22 +188,22 @@ int run_product_r(const T* a, int64_t stride_a, const T* b, int64_t stride_b, Ou
   args.out_base = out_base;
   constexpr int dtype_code = std::is_same<T, int32_t>::value ? RTC_I32 : std::is_same<T, int64_t>::value ? RTC_I64 : RTC_F64;
   if (pl.atomic || force_atomic) {
-    if (!prefilled) launch_fill<OutT, OP>(out, batch * n, stream);
+    if (!prefilled) launch_fill<OutT, OP>(out, cap, batch * n, stream);
     prof_begin(RTC_PROFILE_KIND(dtype_code, 0, OP), stream);
     if (sel != nullptr && sizeof(T) == 8 && pl.items > 8192) {
       const uint32_t items_per_row = (uint32_t)(pl.items / batch);
       uint32_t parts = (uint32_t)(4096 / batch);
       if (parts < 1) parts = 1;
       if (parts > items_per_row) parts = items_per_row;
-      hipLaunchKernelGGL((tropical_rows_kernel<T, OutT, OP, R>), dim3((uint32_t)batch * parts), dim3(64), 0, stream,
+      RTC_LAUNCH((tropical_rows_kernel<T, OutT, OP, R>), dim3((uint32_t)batch * parts), dim3(64), 0, stream,
                          args, items_per_row, parts);
     } else {
-      hipLaunchKernelGGL((tropical_kernel<T, OutT, OP, R, true>), dim3((uint32_t)pl.items), dim3(64), 0,
+      RTC_LAUNCH((tropical_kernel<T, OutT, OP, R, true>), dim3((uint32_t)pl.items), dim3(64), 0,
                          stream, args);
     }
   } else {
     prof_begin(RTC_PROFILE_KIND(dtype_code, 0, OP), stream);
-    hipLaunchKernelGGL((tropical_kernel<T, OutT, OP, R, false>), dim3((uint32_t)pl.items), dim3(64), 0,
+    RTC_LAUNCH((tropical_kernel<T, OutT, OP, R, false>), dim3((uint32_t)pl.items), dim3(64), 0,
                        stream, args);
   }
   prof_end(stream);
@@ -284,7 +292,7 @@ int launch_plain_census(const int32_t* sel, int kind, int64_t batch, int64_t n, 
   PackAux none = {};
   const int64_t n_t2 = (n + kPkW - 1) / kPkW;
   if (batch * n_t2 > 0x7fffffffLL) return RTC_ERR_SHAPE;
-  hipLaunchKernelGGL(census_kernel, dim3((uint32_t)(batch * n_t2)), dim3(64), 0, stream, none, sel, (int)n, (int)batch,
+  RTC_LAUNCH(census_kernel, dim3((uint32_t)(batch * n_t2)), dim3(64), 0, stream, none, sel, (int)n, (int)batch,
                      kind, counts);
   return hip_ok();
 }
@@ -313,19 +321,19 @@ int run_packed(const int32_t* f32, int64_t stride_f, const int32_t* g32, int64_t
   aux.nblk = (int32_t)L.nblk;
   if (batch * L.nchunk > 0x7fffffffLL) return RTC_ERR_SHAPE;
   // uniform operand: f for the convolution, g for the deconvolution; window operand: the other
-  hipLaunchKernelGGL(prep_kernel, dim3((uint32_t)(batch * L.nchunk)), dim3(kPrepThreads), 0, stream,
+  RTC_LAUNCH(prep_kernel, dim3((uint32_t)(batch * L.nchunk)), dim3(kPrepThreads), 0, stream,
                      op_sub(OP) ? g32 : f32, op_sub(OP) ? stride_g : stride_f, op_sub(OP) ? f32 : g32,
                      op_sub(OP) ? stride_f : stride_g, (int)n, op_sub(OP), op_sub(OP) != op_max(OP), (int)L.npad, (int)L.nchunk, (int)L.nblk,
                      aux.rho, aux.pack_ok, const_cast<uint32_t*>(aux.apk), const_cast<uint32_t*>(aux.apk_s),
                      const_cast<int32_t*>(aux.ab_s), const_cast<int32_t*>(aux.ar_s), (int)L.nsub,
                      const_cast<int32_t*>(aux.bd), const_cast<int32_t*>(aux.ab), const_cast<int32_t*>(aux.ar),
                      const_cast<int32_t*>(aux.bmn), const_cast<int32_t*>(aux.bmx));
-  hipLaunchKernelGGL(decide_kernel, dim3((uint32_t)batch), dim3(kDecideThreads), 0, stream, aux, (int)n,
+  RTC_LAUNCH(decide_kernel, dim3((uint32_t)batch), dim3(kDecideThreads), 0, stream, aux, (int)n,
                      const_cast<int32_t*>(aux.pack_ok));
   if (census != nullptr) {
     const int64_t n_t2 = (n + kPkW - 1) / kPkW;
     if (batch * n_t2 > 0x7fffffffLL) return RTC_ERR_SHAPE;
-    hipLaunchKernelGGL(census_kernel, dim3((uint32_t)(batch * n_t2)), dim3(64), 0, stream, aux, sel, (int)n, (int)batch,
+    RTC_LAUNCH(census_kernel, dim3((uint32_t)(batch * n_t2)), dim3(64), 0, stream, aux, sel, (int)n, (int)batch,
                        3, census);
     return hip_ok();
   }
@@ -346,10 +354,10 @@ int run_packed(const int32_t* f32, int64_t stride_f, const int32_t* g32, int64_t
   ag.n_tiles = pg.n_tiles; ag.fold_width = pg.fold_width; ag.seg = pg.seg;
   prof_begin(RTC_PROFILE_KIND(RTC_I32, 1, OP), stream);
   if (small_tiles)
-    hipLaunchKernelGGL((fused_kernel<OutT, OP, kPkR / 2>), dim3((uint32_t)(pk.items + pg.items)), dim3(64), 0,
+    RTC_LAUNCH((fused_kernel<OutT, OP, kPkR / 2>), dim3((uint32_t)(pk.items + pg.items)), dim3(64), 0,
                        stream, ak, ag, (uint32_t)pk.items);
   else
-    hipLaunchKernelGGL((fused_kernel<OutT, OP, kPkR>), dim3((uint32_t)(pk.items + pg.items)), dim3(64), 0,
+    RTC_LAUNCH((fused_kernel<OutT, OP, kPkR>), dim3((uint32_t)(pk.items + pg.items)), dim3(64), 0,
                        stream, ak, ag, (uint32_t)pk.items);
   prof_end(stream);
   return hip_ok();
@@ -380,7 +388,7 @@ int run_typed(const void* f, const void* g, void* out, int64_t batch, int64_t n,
     if (ws != nullptr && ws_bytes >= L.bytes && packed_worthwhile(batch, n)) {
       char* wsp = static_cast<char*>(ws);
       int32_t* sel = reinterpret_cast<int32_t*>(wsp + L.off_sel);
-      hipLaunchKernelGGL(probe_kernel<int32_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,
+      RTC_LAUNCH(probe_kernel<int32_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,
                          static_cast<const int32_t*>(f), stride_f, static_cast<const int32_t*>(g), stride_g,
                          (int)n, g_structure_paths ? OP : OP | kProbeGeneralOnly,
                          reinterpret_cast<int32_t*>(wsp + L.off_ok),
@@ -389,7 +397,8 @@ int run_typed(const void* f, const void* g, void* out, int64_t batch, int64_t n,
         launch_period<int32_t>(static_cast<const int32_t*>(f), stride_f, static_cast<const int32_t*>(g), stride_g, sel,
                              reinterpret_cast<int32_t*>(wsp + L.off_period),
                              reinterpret_cast<int32_t*>(wsp + L.off_ok), batch, n, OP, stream);
-      if (census == nullptr) launch_fill<int32_t, OP>(static_cast<int32_t*>(out), batch * n, stream);
+      if (census == nullptr)
+        launch_fill<int32_t, OP>(static_cast<int32_t*>(out), static_cast<const int32_t*>(cap), batch * n, stream);
       // general rows (selector 1): packed + 32-bit items; rows of exploitable convexity: structured_kernel
       const int rc = run_packed<int32_t, OP>(static_cast<const int32_t*>(f), stride_f,
                                              static_cast<const int32_t*>(g), stride_g, static_cast<int32_t*>(out),
@@ -408,7 +417,7 @@ int run_typed(const void* f, const void* g, void* out, int64_t batch, int64_t n,
   if (census != nullptr)
     return launch_plain_census(nullptr, std::is_same<T, int32_t>::value ? 3 : 4, batch, n, census, stream);
   if (dev_flags != nullptr && std::numeric_limits<T>::is_integer) {
-    hipLaunchKernelGGL(probe_kernel<T>, dim3((uint32_t)batch), dim3(1024), 0, stream,
+    RTC_LAUNCH(probe_kernel<T>, dim3((uint32_t)batch), dim3(1024), 0, stream,
                        static_cast<const T*>(f), stride_f, static_cast<const T*>(g), stride_g, (int)n,
                        OP, (int32_t*)nullptr, (int32_t*)nullptr, (int32_t*)nullptr, dev_flags);
   }
@@ -449,10 +458,10 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
   int64_t* partial = reinterpret_cast<int64_t*>(static_cast<char*>(ws) + narrow_partial_offset(batch, n));
   const bool structure = packed_worthwhile(batch, n) && g_structure_paths;
   if (segs > 1)
-    hipLaunchKernelGGL(probe_partial_kernel, dim3((uint32_t)(batch * segs)), dim3(1024), 0, stream,
+    RTC_LAUNCH(probe_partial_kernel, dim3((uint32_t)(batch * segs)), dim3(1024), 0, stream,
                        static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g, (int)n,
                        structure, segs, partial);
-  hipLaunchKernelGGL(probe_narrow_kernel, dim3((uint32_t)(batch * segs)), dim3(1024), 0, stream,
+  RTC_LAUNCH(probe_narrow_kernel, dim3((uint32_t)(batch * segs)), dim3(1024), 0, stream,
                      static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g,
                      (int)n, OP, structure, f32, g32, ok, base,
                      reinterpret_cast<int32_t*>(wsp + L.off_ok),
@@ -472,7 +481,7 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
   const bool small = make_plan<int64_t, RFor<int64_t>::value>(batch, n).items < (g_small_items < 256 ? g_small_items : 256);
   const bool rebase = g_rebase_wide >= 1 && n > kWideBlock && pw.items <= 0x7fffffffLL && !small;
   if (rebase) {
-    hipLaunchKernelGGL(wide_tables_kernel<OP>, dim3((uint32_t)batch), dim3(kWideThreads), 0, stream,
+    RTC_LAUNCH(wide_tables_kernel<OP>, dim3((uint32_t)batch), dim3(kWideThreads), 0, stream,
                        static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g, ok, tab,
                        tab + (size_t)batch * nb * 4, reinterpret_cast<double*>(wsp + L.off_F),
                        reinterpret_cast<double*>(wsp + L.off_dbl), (int)n, nb, g_rebase_wide >= 2);
@@ -485,7 +494,7 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
                                      ok, base, batch, n, wsp, L, stream, census);
     return launch_plain_census(ok, 3, batch, n, census, stream);
   }
-  launch_fill<int64_t, OP>(static_cast<int64_t*>(out), batch * n, stream);
+  launch_fill<int64_t, OP>(static_cast<int64_t*>(out), static_cast<const int64_t*>(cap), batch * n, stream);
   int rc;
   if (packed_worthwhile(batch, n)) {
     rc = run_packed<int64_t, OP>(f32, n, g32, n, static_cast<int64_t*>(out), static_cast<const int64_t*>(cap),
@@ -514,7 +523,7 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
     if (parts < 1) parts = 1;
     if (parts > items_per_row) parts = items_per_row;
     prof_begin(RTC_PROFILE_KIND(RTC_I64, 0, OP), stream);
-    hipLaunchKernelGGL(rebased_rows_kernel<OP>, dim3((uint32_t)batch * parts), dim3(64), 0, stream, args, tab,
+    RTC_LAUNCH(rebased_rows_kernel<OP>, dim3((uint32_t)batch * parts), dim3(64), 0, stream, args, tab,
                        tab + (size_t)batch * nb * 4, nb, items_per_row, parts);
     prof_end(stream);
     if (int hrc = hip_ok()) return hrc;
@@ -570,7 +579,7 @@ __global__ __launch_bounds__(256) void selftest_half_minmax_kernel(uint32_t* __r
 }  // namespace
 
 int launch_selftest_half_minmax(uint32_t* mismatches, hipStream_t stream) {
-  hipLaunchKernelGGL(selftest_half_minmax_kernel, dim3(0x7C00 / 256), dim3(256), 0, stream, mismatches);
+  RTC_LAUNCH(selftest_half_minmax_kernel, dim3(0x7C00 / 256), dim3(256), 0, stream, mismatches);
   return hip_ok();
 }
 
@@ -583,23 +592,23 @@ int launch_structure_probe(int op, const void* f, const void* g, int32_t* codes,
   const int code_op = op == RTC_OP_CONV ? 0 : op == RTC_OP_DECONV ? 1 : op == RTC_OP_MAXCONV ? 2 : 3;
   if (periods != nullptr) {       // period_kernel writes the rows it accepts only
     const int blocks = (int)((batch + 255) / 256 < 65535 ? (batch + 255) / 256 : 65535);
-    hipLaunchKernelGGL(fill_kernel<int32_t>, dim3(blocks), dim3(256), 0, stream, periods, batch, (int32_t)0);
+    RTC_LAUNCH(fill_kernel<int32_t>, dim3(blocks), dim3(256), 0, stream, periods, batch, (int32_t)0);
   }
   if (dt == RTC_I32) {
-    hipLaunchKernelGGL(probe_kernel<int32_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,
+    RTC_LAUNCH(probe_kernel<int32_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,
                        static_cast<const int32_t*>(f), stride_f, static_cast<const int32_t*>(g), stride_g, (int)n,
                        code_op, (int32_t*)nullptr, (int32_t*)nullptr, codes, (int32_t*)nullptr);
     launch_period<int32_t>(static_cast<const int32_t*>(f), stride_f, static_cast<const int32_t*>(g), stride_g, codes,
                            periods, nullptr, batch, n, code_op, stream);
   } else if (dt == RTC_I64) {
-    hipLaunchKernelGGL(probe_kernel<int64_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,
+    RTC_LAUNCH(probe_kernel<int64_t>, dim3((uint32_t)batch), dim3(1024), 0, stream,
                        static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g, (int)n,
                        code_op, (int32_t*)nullptr, (int32_t*)nullptr, codes, (int32_t*)nullptr);
     launch_period<int64_t>(static_cast<const int64_t*>(f), stride_f, static_cast<const int64_t*>(g), stride_g, codes,
                            periods, nullptr, batch, n, code_op, stream);
   } else {
     const int blocks = (int)((batch + 255) / 256 < 65535 ? (batch + 255) / 256 : 65535);
-    hipLaunchKernelGGL(fill_kernel<int32_t>, dim3(blocks), dim3(256), 0, stream, codes, batch,
+    RTC_LAUNCH(fill_kernel<int32_t>, dim3(blocks), dim3(256), 0, stream, codes, batch,
                        (int32_t)RTC_STRUCTURE_GENERAL);
   }
   return hip_ok();

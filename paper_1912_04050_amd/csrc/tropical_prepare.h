@@ -15,6 +15,13 @@ __global__ __launch_bounds__(256) void fill_kernel(T* __restrict__ dst, int64_t 
   for (; i < count; i += step) dst[i] = value;
 }
 
+template <typename T>
+__global__ __launch_bounds__(256) void copy_rows_kernel(const T* __restrict__ src, T* __restrict__ dst, int64_t count) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t step = (int64_t)gridDim.x * blockDim.x;
+  for (; i < count; i += step) dst[i] = src[i];
+}
+
 // Shape bits of a row pair: bit 0 f convex (second differences >= 0), bit 1 f concave, bit 2 g
 // convex, bit 3 g concave.  second_diff_bits() looks at sample i of one row (1 <= i <= n-2) and
 // returns the bits that survive; differences are taken in int64 (int32 rows: always exact; int64

@@ -529,7 +529,7 @@ template <typename T>
 void launch_period(const T* f, int64_t stride_f, const T* g, int64_t stride_g, int32_t* sel, int32_t* period,
                    int32_t* pack_ok, int64_t batch, int64_t n, int op, hipStream_t stream) {
   if (period_limit(n) < 1) return;
-  hipLaunchKernelGGL(period_kernel<T>, dim3((uint32_t)batch), dim3(kPeriodThreads), 0, stream, f, stride_f, g, stride_g, sel,
+  RTC_LAUNCH(period_kernel<T>, dim3((uint32_t)batch), dim3(kPeriodThreads), 0, stream, f, stride_f, g, stride_g, sel,
                      period, pack_ok, (int)n, op, period_target(batch));
 }
 
@@ -549,12 +549,12 @@ int launch_structured(const T* f, int64_t stride_f, const T* g, int64_t stride_g
   int32_t* jcoarse = jstar + batch * fine;
   const int pblocks = (period_limit(n) + 255) / 256;
   if (batch * (coarse + pblocks) > 0x7fffffffLL) return RTC_ERR_SHAPE;
-  hipLaunchKernelGGL((structured_first_kernel<T, OP>), dim3((uint32_t)(batch * (coarse + pblocks))), dim3(256), 0,
+  RTC_LAUNCH((structured_first_kernel<T, OP>), dim3((uint32_t)(batch * (coarse + pblocks))), dim3(256), 0,
                      stream, f, stride_f, g, stride_g, sel, jcoarse, coarse, (int)(batch * coarse), period, F, (int)n,
                      pblocks);
-  hipLaunchKernelGGL((bracket_fine_kernel<T, OP>), dim3((uint32_t)(batch * ((fine + 3) / 4))), dim3(256), 0, stream,
+  RTC_LAUNCH((bracket_fine_kernel<T, OP>), dim3((uint32_t)(batch * ((fine + 3) / 4))), dim3(256), 0, stream,
                      f, stride_f, g, stride_g, sel, jcoarse, coarse, jstar, (int)n, fine);
-  hipLaunchKernelGGL((structured_kernel<T, OP>), dim3((uint32_t)(batch * bpr)), dim3(256), 0, stream, f, stride_f, g,
+  RTC_LAUNCH((structured_kernel<T, OP>), dim3((uint32_t)(batch * bpr)), dim3(256), 0, stream, f, stride_f, g,
                      stride_g, out, cap, sel, jstar, period, F, (int)n, (int)bpr, (int)batch);
   return hip_ok();
 }

@@ -422,6 +422,25 @@ def test_deviations(rtc, dtype):
         assert np.array_equal(host(v2), oracle.max_vdev(alpha, beta))
 
 
+@pytest.mark.parametrize("dtype", [np.int32, np.int64])
+def test_fused_cap_when_every_candidate_is_the_largest_value_of_the_type(rtc, dtype):
+    """alpha'^l = min((alpha^l (/) beta^u) (x) beta^l, beta^l) on rows for which every candidate of
+    the convolution equals the largest value of the type (a legitimate, overflow-free input): the
+    result is the cap beta^l, whatever the number of work items the product is cut into."""
+    top = int(np.iinfo(dtype).max)
+    for n in (40, 3000, 9000):
+        alpha_l = np.full((2, n), top - 5, dtype)
+        beta_u = np.zeros((2, n), dtype)
+        beta_l = np.full((2, n), 5, dtype)
+        beta_l[1] = 3                      # candidates of row 1: top - 2, the cap still decides
+        alpha_u = np.zeros((2, n), dtype)
+        say("cap against type maximum", dtype, n)
+        au, bl, al, bu = rtc.rtc_gpc_step(dev(alpha_u), dev(beta_u), dev(beta_l), alpha_l=dev(alpha_l))
+        want_al, want_bu = oracle.gpc_step_lower(alpha_l, beta_u, beta_l)
+        assert np.array_equal(want_al, beta_l)
+        assert np.array_equal(host(al), want_al) and np.array_equal(host(bu), want_bu)
+
+
 @pytest.mark.parametrize("dtype", DTYPES)
 def test_gpc_tail_long_rows_and_scattered_events(rtc, dtype):
     """The fused tail of the component step (scan + both event-domain images in one kernel): rows
