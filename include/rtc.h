@@ -15,9 +15,19 @@
  *   - `hip_stream` is a hipStream_t passed as void*.  Every call only enqueues work on
  *     that stream and returns; there is no internal synchronisation.
  *   - Outputs must not alias inputs or the workspace.
- *   - Return value: RTC_OK, or a negative rtc_status.  On a negative status nothing was
- *     launched.  Data-dependent conditions are not errors: they set bits in the optional
- *     caller-provided device word `dev_flags` (never cleared by the library).
+ *   - Return value: RTC_OK, or a negative rtc_status.  Every status but RTC_ERR_HIP is decided on
+ *     the host before the first kernel of the call is enqueued -- argument checks, and a dry run
+ *     of the call's whole launch sequence, which turns a launch the runtime would not accept
+ *     (more than 2^32 - 1 threads in one grid) into RTC_ERR_SHAPE: on such a status nothing was
+ *     launched and no output byte changed.  RTC_ERR_HIP means that the runtime refused a launch
+ *     while enqueueing; kernels of the same call enqueued before it still run.
+ *     Data-dependent conditions are not errors: they set bits in the optional caller-provided
+ *     device word `dev_flags` (never cleared by the library).
+ *   - Host threads: calls from different host threads on different streams are independent
+ *     (the library keeps no per-call state outside the caller's buffers).  The planner knobs
+ *     (rtc_set_*) are process-wide values that every call reads once per launch decision; set
+ *     them while no call is in progress.  rtc_profile_* serialises on a lock of its own and
+ *     describes the calls of all threads together.
  *   - Integer arithmetic must not overflow: the caller guarantees that every candidate
  *     f[s]+g[t-s] (convolution) or f[t+u]-g[u] (deconvolution) fits the element type.
  *     With `dev_flags` non-NULL the library checks max+max / min-min style bounds of
@@ -45,7 +55,7 @@ typedef enum {
 typedef enum {
   RTC_OK = 0,
   RTC_ERR_NULL = -1,      /* a required pointer is NULL */
-  RTC_ERR_SHAPE = -2,     /* batch < 1, n < 1, n > RTC_MAX_N, or the launch would exceed grid limits */
+  RTC_ERR_SHAPE = -2,     /* batch < 1, n < 1, n > RTC_MAX_N, or some launch of the call would exceed the grid limit */
   RTC_ERR_DTYPE = -3,     /* unknown rtc_dtype */
   RTC_ERR_ALIGN = -4,     /* a pointer is not aligned to its element size */
   RTC_ERR_STRIDE = -5,    /* a stride is neither 0 nor >= n */
@@ -276,14 +286,14 @@ int rtc_product_census(int op, const void* f, const void* g, int64_t batch, int6
  * batch * n^2 >= this value (default RTC_DEFAULT_PACKED_MIN_WORK = 2^33, the measured break-even
  * on MI355X: below it the probes and preparation kernels cost more than the faster kernel
  * gains, and the 32-bit kernel alone is quicker).  0 uses it for every size.  Results do not
- * depend on it.  Process-wide, not thread-safe. */
+ * depend on it.  Process-wide. */
 #define RTC_DEFAULT_PACKED_MIN_WORK 8589934592
 int rtc_set_packed_min_work(double batch_times_n_squared);
 
 /* Planner knob: rows of at most this many samples give the packed work items tiles of 1024
  * outputs instead of 2048 (fewer candidates wasted on the half-empty diagonal of a tile, more
  * loop overhead per candidate; default 4096, measured).  0 never does, a value >= RTC_MAX_N always does.  Results do not
- * depend on it.  Process-wide, not thread-safe.  RTC_ERR_SHAPE for a negative value. */
+ * depend on it.  Process-wide.  RTC_ERR_SHAPE for a negative value. */
 int rtc_set_packed_small_n(int64_t n);
 
 /* Planner knob: a product that the general kernel would cut into fewer work items than this
@@ -291,7 +301,7 @@ int rtc_set_packed_small_n(int64_t n);
  * one pair of 4096 samples gives 10, one of 65536 gives 2080) runs with tiles of 256 outputs and
  * chunks of 256 steps instead of 1024 x 1024, which costs more instructions per candidate and
  * finishes sooner because more CUs take part and more wavefronts hide each other's waits.  0 never
- * does.  Results do not depend on it.  Process-wide, not thread-safe.  RTC_ERR_SHAPE for a negative
+ * does.  Results do not depend on it.  Process-wide.  RTC_ERR_SHAPE for a negative
  * value. */
 #define RTC_DEFAULT_SMALL_PROBLEM_ITEMS 8192
 int rtc_set_small_problem_items(int64_t items);
@@ -306,14 +316,13 @@ int rtc_set_small_problem_items(int64_t items);
  * on values re-based per chunk, about 2.5 times as fast as the 64-bit kernel; of the rest, pairs
  * whose values all lie within +-2^51 run in fp64 arithmetic, which is exact on such integers
  * (about 1.8 times as fast), and only the others in the 64-bit integer kernel.  mode 1: without
- * any slope removed; mode 0: the 64-bit integer kernel for every pair that spans 2^30 or more.  Results do not depend on it.  Process-wide, not
- * thread-safe.  RTC_ERR_MODE for other values. */
+ * any slope removed; mode 0: the 64-bit integer kernel for every pair that spans 2^30 or more.  Results do not depend on it.  Process-wide.  RTC_ERR_MODE for other values. */
 int rtc_set_rebase_wide(int mode);
 
 /* Planner knob: 0 sends every row pair of the integer products through the general kernels,
  * whatever its convexity or periodicity (rtc_product_structure still reports what it finds);
  * non-zero (default) lets the structure-exploiting paths take the rows they recognise.  Results
- * do not depend on it.  Process-wide, not thread-safe. */
+ * do not depend on it.  Process-wide. */
 int rtc_set_structure_paths(int enabled);
 
 /* rtc_minplus_conv for callers that cannot allocate device memory: code running under HIP graph
@@ -359,7 +368,7 @@ int rtc_selftest_half_minmax(uint32_t* mismatches, void* hip_stream);
  * in milliseconds) pairs to the HOST arrays kinds / ms; it returns the number written or a
  * negative status.  kind = RTC_PROFILE_KIND(dtype of the arithmetic, packed 16-bit kernel?,
  * product), product = 0 min-plus convolution, 1 max-plus deconvolution, 2 max-plus convolution,
- * 3 min-plus deconvolution.  Not thread-safe. */
+ * 3 min-plus deconvolution.  One record for the whole process, serialised by a lock. */
 #define RTC_PROFILE_KIND(dtype, packed, product) ((dtype) * 8 + (packed) * 4 + (product))
 #define RTC_PROFILE_KIND_TAIL 64   /* the scan (+ event-domain inverses) kernel of rtc_gpc_step */
 int rtc_profile_enable(int on);

@@ -1,13 +1,18 @@
 // Measurement aid: HIP event pairs around the product kernels (rtc_profile_enable / _read).
 // A fixed ring of event pairs, created lazily and kept for the life of the process; recording
-// stops when the ring is full.  Not thread-safe: enable, run, read from one host thread.
+// stops when the ring is full.  One lock serialises every access, so calls from several host
+// threads are safe (their kernels share the one record).
 #include <hip/hip_runtime.h>
+
+#include <mutex>
 
 #include "rtc_internal.h"
 
 namespace rtc {
 
 thread_local bool t_launch_failed = false;   // see launch_checked
+thread_local bool t_dry_run = false;
+thread_local bool t_dry_bad = false;
 
 namespace {
 
@@ -21,10 +26,13 @@ Slot g_ring[kRing];
 int g_count = 0;
 bool g_on = false;
 bool g_open = false;   // a begin without its end
+std::mutex g_lock;
 
 }  // namespace
 
 void prof_begin(int kind, hipStream_t stream) {
+  if (t_dry_run) return;
+  std::lock_guard<std::mutex> lock(g_lock);
   if (!g_on || g_count >= kRing) return;
   Slot& s = g_ring[g_count];
   if (!s.made) {
@@ -36,6 +44,8 @@ void prof_begin(int kind, hipStream_t stream) {
 }
 
 void prof_end(hipStream_t stream) {
+  if (t_dry_run) return;
+  std::lock_guard<std::mutex> lock(g_lock);
   if (!g_on || !g_open) return;
   g_open = false;
   if (hipEventRecord(g_ring[g_count].e1, stream) == hipSuccess) ++g_count;
@@ -46,6 +56,7 @@ void prof_end(hipStream_t stream) {
 extern "C" {
 
 int rtc_profile_enable(int on) {
+  std::lock_guard<std::mutex> lock(rtc::g_lock);
   rtc::g_on = on != 0;
   rtc::g_count = 0;
   rtc::g_open = false;
@@ -54,6 +65,7 @@ int rtc_profile_enable(int on) {
 
 int rtc_profile_read(int max_entries, int* kinds, float* ms) {
   if (kinds == nullptr || ms == nullptr) return RTC_ERR_NULL;
+  std::lock_guard<std::mutex> lock(rtc::g_lock);
   int out = 0;
   for (int i = 0; i < rtc::g_count && out < max_entries; ++i) {
     float t = 0.f;

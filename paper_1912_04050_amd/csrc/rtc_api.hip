@@ -39,32 +39,32 @@ int rtc_minplus_conv(const void* f, const void* g, void* out, int64_t batch, int
                      int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* ws, size_t ws_bytes,
                      int32_t* dev_flags, void* hip_stream) {
   if (int rc = check_product(f, g, out, batch, n, stride_f, stride_g, dt, ws, ws_bytes, dev_flags)) return rc;
-  return launch_tropical(RTC_OP_CONV, f, g, out, batch, n, stride_f, stride_g, dt, nullptr, ws, ws_bytes,
-                         dev_flags, static_cast<hipStream_t>(hip_stream));
+  return validated([&] { return launch_tropical(RTC_OP_CONV, f, g, out, batch, n, stride_f, stride_g, dt, nullptr, ws, ws_bytes,
+                         dev_flags, static_cast<hipStream_t>(hip_stream)); });
 }
 
 int rtc_maxplus_conv(const void* f, const void* g, void* out, int64_t batch, int64_t n,
                      int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* ws, size_t ws_bytes,
                      int32_t* dev_flags, void* hip_stream) {
   if (int rc = check_product(f, g, out, batch, n, stride_f, stride_g, dt, ws, ws_bytes, dev_flags)) return rc;
-  return launch_tropical(RTC_OP_MAXCONV, f, g, out, batch, n, stride_f, stride_g, dt, nullptr, ws, ws_bytes,
-                         dev_flags, static_cast<hipStream_t>(hip_stream));
+  return validated([&] { return launch_tropical(RTC_OP_MAXCONV, f, g, out, batch, n, stride_f, stride_g, dt, nullptr, ws, ws_bytes,
+                         dev_flags, static_cast<hipStream_t>(hip_stream)); });
 }
 
 int rtc_minplus_deconv(const void* f, const void* g, void* out, int64_t batch, int64_t n,
                        int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* ws, size_t ws_bytes,
                        int32_t* dev_flags, void* hip_stream) {
   if (int rc = check_product(f, g, out, batch, n, stride_f, stride_g, dt, ws, ws_bytes, dev_flags)) return rc;
-  return launch_tropical(RTC_OP_MINDECONV, f, g, out, batch, n, stride_f, stride_g, dt, nullptr, ws, ws_bytes,
-                         dev_flags, static_cast<hipStream_t>(hip_stream));
+  return validated([&] { return launch_tropical(RTC_OP_MINDECONV, f, g, out, batch, n, stride_f, stride_g, dt, nullptr, ws, ws_bytes,
+                         dev_flags, static_cast<hipStream_t>(hip_stream)); });
 }
 
 int rtc_maxplus_deconv(const void* f, const void* g, void* out, int64_t batch, int64_t n,
                        int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* ws, size_t ws_bytes,
                        int32_t* dev_flags, void* hip_stream) {
   if (int rc = check_product(f, g, out, batch, n, stride_f, stride_g, dt, ws, ws_bytes, dev_flags)) return rc;
-  return launch_tropical(RTC_OP_DECONV, f, g, out, batch, n, stride_f, stride_g, dt, nullptr, ws, ws_bytes,
-                         dev_flags, static_cast<hipStream_t>(hip_stream));
+  return validated([&] { return launch_tropical(RTC_OP_DECONV, f, g, out, batch, n, stride_f, stride_g, dt, nullptr, ws, ws_bytes,
+                         dev_flags, static_cast<hipStream_t>(hip_stream)); });
 }
 
 int rtc_product_census(int op, const void* f, const void* g, int64_t batch, int64_t n, int64_t stride_f,
@@ -76,8 +76,8 @@ int rtc_product_census(int op, const void* f, const void* g, int64_t batch, int6
   // `counts` stands in for the output in the argument check (non-null, aligned); no output is written
   if (int rc = check_product(f, g, counts, batch, n, stride_f, stride_g, dt, ws, ws_bytes, nullptr)) return rc;
   static_assert(sizeof(unsigned long long) == sizeof(uint64_t), "census words");
-  return launch_tropical(op, f, g, nullptr, batch, n, stride_f, stride_g, dt, nullptr, ws, ws_bytes, nullptr,
-                         static_cast<hipStream_t>(hip_stream), reinterpret_cast<unsigned long long*>(counts));
+  return validated([&] { return launch_tropical(op, f, g, nullptr, batch, n, stride_f, stride_g, dt, nullptr, ws, ws_bytes, nullptr,
+                         static_cast<hipStream_t>(hip_stream), reinterpret_cast<unsigned long long*>(counts)); });
 }
 
 int rtc_product_structure(int op, const void* f, const void* g, int32_t* codes, int64_t batch, int64_t n,
@@ -94,8 +94,8 @@ int rtc_product_periods(int op, const void* f, const void* g, int32_t* codes, in
   if (int rc = check_shape(batch, n)) return rc;
   if ((stride_f != 0 && stride_f < n) || (stride_g != 0 && stride_g < n)) return RTC_ERR_STRIDE;
   if (!aligned(f, es) || !aligned(g, es) || !aligned(codes, 4) || !aligned(periods, 4)) return RTC_ERR_ALIGN;
-  return launch_structure_probe(op, f, g, codes, periods, batch, n, stride_f, stride_g, dt,
-                                static_cast<hipStream_t>(hip_stream));
+  return validated([&] { return launch_structure_probe(op, f, g, codes, periods, batch, n, stride_f, stride_g, dt,
+                                static_cast<hipStream_t>(hip_stream)); });
 }
 
 int rtc_pseudo_inverse(const void* f, int64_t n, const void* x, int64_t m, int32_t* out_idx,
@@ -107,7 +107,7 @@ int rtc_pseudo_inverse(const void* f, int64_t n, const void* x, int64_t m, int32
   if (int rc = check_shape(batch, n)) return rc;
   if (m < 1 || m > RTC_MAX_N) return RTC_ERR_SHAPE;
   if (!aligned(f, es) || !aligned(x, es) || !aligned(out_idx, 4)) return RTC_ERR_ALIGN;
-  return launch_pseudo_inverse(f, n, x, m, out_idx, batch, mode, dt, static_cast<hipStream_t>(hip_stream));
+  return validated([&] { return launch_pseudo_inverse(f, n, x, m, out_idx, batch, mode, dt, static_cast<hipStream_t>(hip_stream)); });
 }
 
 int rtc_compose(const void* outer, int64_t n_outer, const int32_t* inner, int64_t n, void* out,
@@ -119,8 +119,8 @@ int rtc_compose(const void* outer, int64_t n_outer, const int32_t* inner, int64_
   if (n_outer < 1 || n_outer > RTC_MAX_N) return RTC_ERR_SHAPE;
   if (!aligned(outer, es) || !aligned(out, es) || !aligned(inner, 4) || !aligned(dev_flags, 4))
     return RTC_ERR_ALIGN;
-  return launch_compose(outer, n_outer, inner, n, out, batch, dt, dev_flags,
-                        static_cast<hipStream_t>(hip_stream));
+  return validated([&] { return launch_compose(outer, n_outer, inner, n, out, batch, dt, dev_flags,
+                        static_cast<hipStream_t>(hip_stream)); });
 }
 
 int rtc_gpc_step(const rtc_gpc_args* a, void* hip_stream) {
@@ -153,6 +153,8 @@ int rtc_gpc_step(const rtc_gpc_args* a, void* hip_stream) {
   const size_t c_bytes = ((size_t)batch * n * es + 255) / 256 * 256;
   void* sub_ws = c + c_bytes;
   const size_t sub_bytes = a->ws_bytes - c_bytes;
+  // (the whole sequence runs dry first: a launch that would not fit is reported before any is enqueued)
+  return validated([&]() -> int {
   int rc = launch_tropical(RTC_OP_CONV, a->alpha_u, a->beta_u, c, batch, n, n, n, a->dt, nullptr, sub_ws,
                            sub_bytes, a->dev_flags, stream);
   if (rc != RTC_OK) return rc;
@@ -177,6 +179,7 @@ int rtc_gpc_step(const rtc_gpc_args* a, void* hip_stream) {
     if (rc != RTC_OK) return rc;
   }
   return RTC_OK;
+  });
 }
 
 namespace {
@@ -199,16 +202,18 @@ int closure(const void* f, void* out, int64_t batch, int64_t n, int dt, void* ws
   char* buf[2] = {static_cast<char*>(ws), static_cast<char*>(ws) + half};
   void* sub_ws = static_cast<char*>(ws) + 2 * half;
   const size_t sub_bytes = ws_bytes - 2 * half;
-  int rc = launch_closure_init(f, squarings == 0 ? out : buf[0], batch, n, dt, super, dev_flags, stream);
-  if (rc != RTC_OK) return rc;
-  for (int j = 0; j < squarings; ++j) {
-    const void* src = buf[j & 1];
-    void* dst = (j == squarings - 1) ? out : buf[(j + 1) & 1];
-    rc = launch_tropical(super ? RTC_OP_MAXCONV : RTC_OP_CONV, src, src, dst, batch, n, n, n, dt, nullptr, sub_ws,
-                         sub_bytes, dev_flags, stream);
+  return validated([&]() -> int {
+    int rc = launch_closure_init(f, squarings == 0 ? out : buf[0], batch, n, dt, super, dev_flags, stream);
     if (rc != RTC_OK) return rc;
-  }
-  return RTC_OK;
+    for (int j = 0; j < squarings; ++j) {
+      const void* src = buf[j & 1];
+      void* dst = (j == squarings - 1) ? out : buf[(j + 1) & 1];
+      rc = launch_tropical(super ? RTC_OP_MAXCONV : RTC_OP_CONV, src, src, dst, batch, n, n, n, dt, nullptr, sub_ws,
+                           sub_bytes, dev_flags, stream);
+      if (rc != RTC_OK) return rc;
+    }
+    return RTC_OK;
+  });
 }
 
 }  // namespace
@@ -235,20 +240,22 @@ int rtc_conv_chain(const void* curves, int64_t count, void* out, int64_t batch, 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const size_t curve_bytes = (size_t)batch * n * es;
   const char* base = static_cast<const char*>(curves);
-  if (count == 1) return launch_copy(base, out, batch * n, dt, stream);
+  if (count == 1) return validated([&] { return launch_copy(base, out, batch * n, dt, stream); });
   const size_t half = pingpong_bytes(batch, n, es) / 2;
   char* buf[2] = {static_cast<char*>(ws), static_cast<char*>(ws) + half};
   void* sub_ws = static_cast<char*>(ws) + 2 * half;
   const size_t sub_bytes = ws_bytes - 2 * half;
-  const void* acc = base;
-  for (int64_t k = 1; k < count; ++k) {
-    void* dst = (k == count - 1) ? out : buf[k & 1];
-    int rc = launch_tropical(RTC_OP_CONV, acc, base + k * curve_bytes, dst, batch, n, n, n, dt, nullptr, sub_ws,
-                             sub_bytes, dev_flags, stream);
-    if (rc != RTC_OK) return rc;
-    acc = dst;
-  }
-  return RTC_OK;
+  return validated([&]() -> int {
+    const void* acc = base;
+    for (int64_t k = 1; k < count; ++k) {
+      void* dst = (k == count - 1) ? out : buf[k & 1];
+      int rc = launch_tropical(RTC_OP_CONV, acc, base + k * curve_bytes, dst, batch, n, n, n, dt, nullptr, sub_ws,
+                               sub_bytes, dev_flags, stream);
+      if (rc != RTC_OK) return rc;
+      acc = dst;
+    }
+    return RTC_OK;
+  });
 }
 
 int rtc_max_hdev(const void* alpha, const void* beta, int32_t* out, int64_t batch, int64_t n,
@@ -259,7 +266,7 @@ int rtc_max_hdev(const void* alpha, const void* beta, int32_t* out, int64_t batc
   if (int rc = check_shape(batch, n)) return rc;
   if (!aligned(alpha, es) || !aligned(beta, es) || !aligned(out, 4) || !aligned(dev_flags, 4))
     return RTC_ERR_ALIGN;
-  return launch_max_hdev(alpha, beta, out, batch, n, dt, dev_flags, static_cast<hipStream_t>(hip_stream));
+  return validated([&] { return launch_max_hdev(alpha, beta, out, batch, n, dt, dev_flags, static_cast<hipStream_t>(hip_stream)); });
 }
 
 int rtc_max_deviations(const void* alpha, const void* beta, int32_t* out_h, void* out_v, int64_t batch, int64_t n,
@@ -270,7 +277,7 @@ int rtc_max_deviations(const void* alpha, const void* beta, int32_t* out_h, void
   if (int rc = check_shape(batch, n)) return rc;
   if (!aligned(alpha, es) || !aligned(beta, es) || !aligned(out_h, 4) || !aligned(out_v, es) || !aligned(dev_flags, 4))
     return RTC_ERR_ALIGN;
-  return launch_max_hdev(alpha, beta, out_h, batch, n, dt, dev_flags, static_cast<hipStream_t>(hip_stream), out_v);
+  return validated([&] { return launch_max_hdev(alpha, beta, out_h, batch, n, dt, dev_flags, static_cast<hipStream_t>(hip_stream), out_v); });
 }
 
 int rtc_validate_monotone(const void* f, int64_t batch, int64_t n, int64_t stride, rtc_dtype dt,
@@ -281,7 +288,7 @@ int rtc_validate_monotone(const void* f, int64_t batch, int64_t n, int64_t strid
   if (int rc = check_shape(batch, n)) return rc;
   if (stride != 0 && stride < n) return RTC_ERR_STRIDE;
   if (!aligned(f, es) || !aligned(first_bad, 4) || !aligned(dev_flags, 4)) return RTC_ERR_ALIGN;
-  return launch_validate_monotone(f, batch, n, stride, dt, first_bad, dev_flags, static_cast<hipStream_t>(hip_stream));
+  return validated([&] { return launch_validate_monotone(f, batch, n, stride, dt, first_bad, dev_flags, static_cast<hipStream_t>(hip_stream)); });
 }
 
 int rtc_max_vdev(const void* alpha, const void* beta, void* out, int64_t batch, int64_t n,
@@ -291,7 +298,7 @@ int rtc_max_vdev(const void* alpha, const void* beta, void* out, int64_t batch, 
   if (es == 0) return RTC_ERR_DTYPE;
   if (int rc = check_shape(batch, n)) return rc;
   if (!aligned(alpha, es) || !aligned(beta, es) || !aligned(out, es)) return RTC_ERR_ALIGN;
-  return launch_max_vdev(alpha, beta, out, batch, n, dt, static_cast<hipStream_t>(hip_stream));
+  return validated([&] { return launch_max_vdev(alpha, beta, out, batch, n, dt, static_cast<hipStream_t>(hip_stream)); });
 }
 
 size_t rtc_workspace_bytes(int op, int64_t batch, int64_t n, rtc_dtype dt) {
@@ -361,7 +368,7 @@ const char* rtc_strerror(int status) {
 int rtc_selftest_half_minmax(uint32_t* mismatches, void* hip_stream) {
   if (mismatches == nullptr) return RTC_ERR_NULL;
   if (!aligned(mismatches, 4)) return RTC_ERR_ALIGN;
-  return launch_selftest_half_minmax(mismatches, static_cast<hipStream_t>(hip_stream));
+  return validated([&] { return launch_selftest_half_minmax(mismatches, static_cast<hipStream_t>(hip_stream)); });
 }
 
 int rtc_device_info(int* cu_count, int* clock_khz, int* lds_bytes) {

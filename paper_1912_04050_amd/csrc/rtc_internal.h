@@ -5,6 +5,7 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
 #include <tuple>
 #include <utility>
 
@@ -32,11 +33,13 @@ size_t tropical_workspace_bytes(int64_t batch, int64_t n, int dt);
 int launch_structure_probe(int op, const void* f, const void* g, int32_t* codes, int32_t* periods, int64_t batch,
                            int64_t n, int64_t stride_f, int64_t stride_g, int dt, hipStream_t stream);
 int launch_selftest_half_minmax(uint32_t* mismatches, hipStream_t stream);
-extern double g_packed_min_work;  // planner knob, see rtc_set_packed_min_work
-extern int64_t g_packed_small_n;  // planner knob, see rtc_set_packed_small_n
-extern bool g_structure_paths;    // planner knob, see rtc_set_structure_paths
-extern int64_t g_small_items;     // planner knob, see rtc_set_small_problem_items
-extern int g_rebase_wide;         // planner knob, see rtc_set_rebase_wide
+// Planner knobs: process-wide, atomic so that a call in one host thread may read them while
+// another thread sets them (each launch decision reads them once).
+extern std::atomic<double> g_packed_min_work;  // see rtc_set_packed_min_work
+extern std::atomic<int64_t> g_packed_small_n;  // see rtc_set_packed_small_n
+extern std::atomic<bool> g_structure_paths;    // see rtc_set_structure_paths
+extern std::atomic<int64_t> g_small_items;     // see rtc_set_small_problem_items
+extern std::atomic<int> g_rebase_wide;         // see rtc_set_rebase_wide
 
 // HBM-bound curve kernels (curve_ops.hip).
 int launch_pseudo_inverse(const void* f, int64_t n, const void* x, int64_t m, int32_t* out,
@@ -68,7 +71,21 @@ void prof_end(hipStream_t stream);
 // would both blame a good launch and swallow that error).  A failed launch is remembered per host
 // thread until hip_ok() reports it.  Arguments are converted to the kernel's parameter types
 // here, as a direct call would convert them.
+// An entry point first walks its whole launch sequence in a dry run (validated(), below): nothing
+// is launched, every launch's grid is checked against what the runtime accepts, and a grid that
+// does not fit turns into RTC_ERR_SHAPE before the first kernel of the call is enqueued.  HIP
+// takes grid x block as a 32-bit number of threads: a product of 2^32 is refused and a larger one
+// wraps around silently, so the limit is grid * block < 2^32 (67 108 863 workgroups of 64
+// threads, 4 194 303 of 1024).
 extern thread_local bool t_launch_failed;
+extern thread_local bool t_dry_run;
+extern thread_local bool t_dry_bad;
+
+inline bool grid_fits(dim3 grid, dim3 block) {
+  return grid.x >= 1 && grid.y == 1 && grid.z == 1 && (uint64_t)grid.x * block.x * block.y * block.z < (1ull << 32);
+}
+// Guard for host code that computes a grid in 64 bits before narrowing it.
+inline bool blocks_fit(int64_t blocks, int threads) { return blocks >= 1 && blocks * threads < (1ll << 32); }
 
 template <typename... P, typename... A, size_t... I>
 inline hipError_t launch_with_tuple(void (*kernel)(P...), dim3 grid, dim3 block, size_t shmem, hipStream_t stream,
@@ -81,6 +98,11 @@ inline hipError_t launch_with_tuple(void (*kernel)(P...), dim3 grid, dim3 block,
 template <typename... P, typename... A>
 inline void launch_checked(void (*kernel)(P...), dim3 grid, dim3 block, size_t shmem, hipStream_t stream, A&&... a) {
   static_assert(sizeof...(P) == sizeof...(A), "one argument per kernel parameter");
+  if (!grid_fits(grid, block)) {          // never hand the runtime a grid it would wrap around
+    (t_dry_run ? t_dry_bad : t_launch_failed) = true;
+    return;
+  }
+  if (t_dry_run) return;
   if (launch_with_tuple(kernel, grid, block, shmem, stream, std::index_sequence_for<P...>{}, std::forward<A>(a)...) !=
       hipSuccess)
     t_launch_failed = true;
@@ -89,9 +111,24 @@ inline void launch_checked(void (*kernel)(P...), dim3 grid, dim3 block, size_t s
 
 // RTC_OK, or RTC_ERR_HIP when a launch of this thread failed since the last call (which clears it).
 inline int hip_ok() {
+  if (t_dry_run) return RTC_OK;
   const bool failed = t_launch_failed;
   t_launch_failed = false;
   return failed ? RTC_ERR_HIP : RTC_OK;
+}
+
+// Runs `sequence` (a callable that enqueues the kernels of one call and returns a status) twice:
+// dry first, then for real when every grid of the dry run fitted and it returned RTC_OK.
+template <typename F>
+inline int validated(F&& sequence) {
+  t_dry_run = true;
+  t_dry_bad = false;
+  const int rc = sequence();
+  t_dry_run = false;
+  if (rc != RTC_OK) return rc;
+  if (t_dry_bad) return RTC_ERR_SHAPE;
+  t_launch_failed = false;
+  return sequence();
 }
 
 }  // namespace rtc

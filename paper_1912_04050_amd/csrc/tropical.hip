@@ -63,10 +63,10 @@
 
 namespace rtc {
 
-int64_t g_packed_small_n = 4096;   // rows up to this length use the narrower packed tiles
-bool g_structure_paths = true;     // rows of exploitable convexity / periodicity take their own kernels
-int64_t g_small_items = RTC_DEFAULT_SMALL_PROBLEM_ITEMS;       // problems with fewer work items than this get the small tiles, see kSmallR
-int g_rebase_wide = 2;             // int64 rows beyond 32 bits: 0 64-bit kernel, 1 also re-based per chunk, 2 also common slope removed
+std::atomic<int64_t> g_packed_small_n{4096};   // rows up to this length use the narrower packed tiles
+std::atomic<bool> g_structure_paths{true};     // rows of exploitable convexity / periodicity take their own kernels
+std::atomic<int64_t> g_small_items{RTC_DEFAULT_SMALL_PROBLEM_ITEMS};   // problems with fewer work items than this get the small tiles, see kSmallR
+std::atomic<int> g_rebase_wide{2};             // int64 rows beyond 32 bits: 0 64-bit kernel, 1 also re-based per chunk, 2 also common slope removed
 
 namespace {
 
@@ -365,7 +365,7 @@ int run_packed(const int32_t* f32, int64_t stride_f, const int32_t* g32, int64_t
 
 }  // namespace
 
-double g_packed_min_work = (double)RTC_DEFAULT_PACKED_MIN_WORK;   // batch * n^2 from which the packed path is used
+std::atomic<double> g_packed_min_work{(double)RTC_DEFAULT_PACKED_MIN_WORK};   // batch * n^2 from which the packed path is used
 
 namespace {
 
@@ -478,7 +478,8 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
   const Plan pw = make_plan<int32_t, kWideR>(batch, n);
   // (not for problems so small that the launches themselves are the cost: their rows stay with
   // the 64-bit kernel, which the same criterion gives small tiles)
-  const bool small = make_plan<int64_t, RFor<int64_t>::value>(batch, n).items < (g_small_items < 256 ? g_small_items : 256);
+  const int64_t small_items = g_small_items;
+  const bool small = make_plan<int64_t, RFor<int64_t>::value>(batch, n).items < (small_items < 256 ? small_items : 256);
   const bool rebase = g_rebase_wide >= 1 && n > kWideBlock && pw.items <= 0x7fffffffLL && !small;
   if (rebase) {
     RTC_LAUNCH(wide_tables_kernel<OP>, dim3((uint32_t)batch), dim3(kWideThreads), 0, stream,

@@ -233,6 +233,37 @@ def test_product_census(rtc):
         rtc.rtc_set_packed_min_work(rtc.RTC_DEFAULT_PACKED_MIN_WORK)
 
 
+def test_a_refused_call_changes_no_output(rtc):
+    """A component step over 2^22 rows of two samples: its two products would fit, the scan after them
+    would need 2^32 threads in one grid.  The call is refused with RTC_ERR_SHAPE before its first
+    kernel: both outputs still hold what they held.  One row fewer runs, and equals the oracle."""
+    batch, n = 1 << 22, 2
+    rng = np.random.default_rng(8)
+    alpha = np.cumsum(rng.integers(0, 5, (batch, n)), axis=1).astype(np.int32)
+    beta_u = np.cumsum(rng.integers(0, 9, (batch, n)), axis=1).astype(np.int32)
+    beta_l = (beta_u // 2).astype(np.int32)
+    au = torch.full((batch, n), -77, dtype=torch.int32, device="cuda")
+    bl = torch.full((batch, n), -78, dtype=torch.int32, device="cuda")
+    say("refused component step", batch, n)
+    with pytest.raises(rtc.RtcError) as e:
+        rtc.rtc_gpc_step(dev(alpha), dev(beta_u), dev(beta_l), alpha_u_out=au, beta_l_out=bl)
+    assert e.value.status == -2
+    torch.cuda.synchronize()
+    assert int((au != -77).sum().item()) == 0 and int((bl != -78).sum().item()) == 0
+    m = batch - 1
+    got_au, got_bl = rtc.rtc_gpc_step(dev(alpha[:m]), dev(beta_u[:m]), dev(beta_l[:m]))
+    got_au, got_bl = host(got_au), host(got_bl)
+    for rows in (slice(0, 3000), slice(m - 3000, m)):       # (the oracle takes a parallel region per row)
+        want_au, want_bl = oracle.gpc_step(alpha[rows], beta_u[rows], beta_l[rows])
+        assert np.array_equal(got_au[rows], want_au) and np.array_equal(got_bl[rows], want_bl)
+    # every row: two samples have closed forms
+    c0 = alpha[:m, 0] + beta_u[:m, 0]
+    c1 = np.minimum(alpha[:m, 0] + beta_u[:m, 1], alpha[:m, 1] + beta_u[:m, 0])
+    d0 = np.maximum(c0 - beta_l[:m, 0], c1 - beta_l[:m, 1])
+    d1 = c1 - beta_l[:m, 0]
+    assert np.array_equal(got_au, np.minimum(np.stack([d0, d1], 1), beta_u[:m]))
+
+
 def run_config5(rtc, seed, n):
     c = wl.config5(seed, n)
     f, g, x = c["f"], c["g"], c["x"]
