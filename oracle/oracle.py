@@ -18,25 +18,50 @@ _LIB = os.path.join(_HERE, "liboracle.so")
 
 _DT = {np.dtype(np.int32): 0, np.dtype(np.int64): 1, np.dtype(np.float64): 2}
 
-_lib = None
+_LIB_CHECKED = os.path.join(_HERE, "liboracle_checked.so")
+
+_libs = {}
+_checked = False
+
+_FLAGS = ["g++", "-std=c++17", "-O2", "-fno-fast-math", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC"]
 
 
 def build(force: bool = True) -> str:
     """Compile the oracle with g++ (no fast-math, no FMA contraction)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["g++", "-std=c++17", "-O2", "-fno-fast-math", "-ffp-contract=off", "-fopenmp",
-               "-shared", "-fPIC", "-o", _LIB, _SRC]
-        subprocess.run(cmd, check=True)
+        subprocess.run([*_FLAGS, "-o", _LIB, _SRC], check=True)
     return _LIB
 
 
+def build_checked(force: bool = True) -> str:
+    """The debug build: every integer addition / subtraction of two samples is checked for overflow
+    and counted (overflow_count); same loops, same results on inputs that obey the precondition."""
+    if force or not os.path.exists(_LIB_CHECKED) or os.path.getmtime(_LIB_CHECKED) < os.path.getmtime(_SRC):
+        subprocess.run([*_FLAGS, "-DORACLE_CHECK_OVERFLOW", "-o", _LIB_CHECKED, _SRC], check=True)
+    return _LIB_CHECKED
+
+
+def use_checked_build(on: bool) -> None:
+    """Route every call of this module through the overflow-checking debug build (tests only)."""
+    global _checked
+    _checked = bool(on)
+
+
 def lib():
-    global _lib
-    if _lib is None:
-        build(force=False)
-        _lib = ctypes.CDLL(_LIB)
-        _lib.oracle_num_threads.restype = ctypes.c_int
-    return _lib
+    key = "checked" if _checked else "plain"
+    if key not in _libs:
+        path = build_checked(force=False) if _checked else build(force=False)
+        handle = ctypes.CDLL(path)
+        handle.oracle_num_threads.restype = ctypes.c_int
+        handle.oracle_overflow_count.restype = ctypes.c_longlong
+        handle.oracle_overflow_count.argtypes = [ctypes.c_int]
+        _libs[key] = handle
+    return _libs[key]
+
+
+def overflow_count(reset: bool = True) -> int:
+    """Overflowing sample additions / subtractions since the last reset; -1 in the normal build."""
+    return int(lib().oracle_overflow_count(1 if reset else 0))
 
 
 def num_threads() -> int:

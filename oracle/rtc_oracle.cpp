@@ -40,16 +40,53 @@
 #include <cstdint>
 #include <cstddef>
 #include <omp.h>
+#include <type_traits>
 
 namespace {
+
+// Every sum and difference of two samples goes through oadd / osub: plain + and - in the normal
+// build.  Built with -DORACLE_CHECK_OVERFLOW (the debug build that tests/test_oracle_hygiene.py
+// uses) the integer ones are checked with __builtin_add_overflow / __builtin_sub_overflow and
+// counted, which asserts the precondition of the whole algebra -- no candidate leaves the
+// element type -- on the inputs the benchmark configurations generate.
+#ifdef ORACLE_CHECK_OVERFLOW
+long long g_overflows = 0;
+template <typename T> inline T oadd(T a, T b) {
+  if constexpr (std::is_integral<T>::value) {
+    T r;
+    if (__builtin_add_overflow(a, b, &r)) {
+#pragma omp atomic
+      ++g_overflows;
+    }
+    return r;
+  } else {
+    return a + b;
+  }
+}
+template <typename T> inline T osub(T a, T b) {
+  if constexpr (std::is_integral<T>::value) {
+    T r;
+    if (__builtin_sub_overflow(a, b, &r)) {
+#pragma omp atomic
+      ++g_overflows;
+    }
+    return r;
+  } else {
+    return a - b;
+  }
+}
+#else
+template <typename T> inline T oadd(T a, T b) { return a + b; }
+template <typename T> inline T osub(T a, T b) { return a - b; }
+#endif
 
 template <typename T>
 void conv_one(const T* f, const T* g, T* out, int64_t n) {
 #pragma omp parallel for schedule(dynamic, 64)
   for (int64_t t = 0; t < n; ++t) {
-    T m = f[0] + g[t];
+    T m = oadd(f[0], g[t]);
     for (int64_t s = 1; s <= t; ++s) {
-      T v = f[s] + g[t - s];
+      T v = oadd(f[s], g[t - s]);
       if (v < m) m = v;
     }
     out[t] = m;
@@ -60,9 +97,9 @@ template <typename T>
 void deconv_one(const T* f, const T* g, T* out, int64_t n) {
 #pragma omp parallel for schedule(dynamic, 64)
   for (int64_t t = 0; t < n; ++t) {
-    T m = f[t] - g[0];
+    T m = osub(f[t], g[0]);
     for (int64_t u = 1; u <= n - 1 - t; ++u) {
-      T v = f[t + u] - g[u];
+      T v = osub(f[t + u], g[u]);
       if (v > m) m = v;
     }
     out[t] = m;
@@ -73,9 +110,9 @@ template <typename T>
 void maxconv_one(const T* f, const T* g, T* out, int64_t n) {
 #pragma omp parallel for schedule(dynamic, 64)
   for (int64_t t = 0; t < n; ++t) {
-    T m = f[0] + g[t];
+    T m = oadd(f[0], g[t]);
     for (int64_t s = 1; s <= t; ++s) {
-      T v = f[s] + g[t - s];
+      T v = oadd(f[s], g[t - s]);
       if (v > m) m = v;
     }
     out[t] = m;
@@ -86,9 +123,9 @@ template <typename T>
 void mindeconv_one(const T* f, const T* g, T* out, int64_t n) {
 #pragma omp parallel for schedule(dynamic, 64)
   for (int64_t t = 0; t < n; ++t) {
-    T m = f[t] - g[0];
+    T m = osub(f[t], g[0]);
     for (int64_t u = 1; u <= n - 1 - t; ++u) {
-      T v = f[t + u] - g[u];
+      T v = osub(f[t + u], g[u]);
       if (v < m) m = v;
     }
     out[t] = m;
@@ -104,15 +141,15 @@ void product_at(const T* f, const T* g, int64_t n, const int64_t* t_idx, int64_t
     const int64_t t = t_idx[j];
     T r;
     if (!deconv) {
-      r = f[0] + g[t];
+      r = oadd(f[0], g[t]);
       for (int64_t s = 1; s <= t; ++s) {
-        T v = f[s] + g[t - s];
+        T v = oadd(f[s], g[t - s]);
         if (v < r) r = v;
       }
     } else {
-      r = f[t] - g[0];
+      r = osub(f[t], g[0]);
       for (int64_t u = 1; u <= n - 1 - t; ++u) {
-        T v = f[t + u] - g[u];
+        T v = osub(f[t + u], g[u]);
         if (v > r) r = v;
       }
     }
@@ -174,9 +211,9 @@ void gpc_rows(const T* au, const T* bu, const T* bl, T* au_out, T* bl_out, T* tm
     deconv_one(c, l, d, n);
     for (int64_t k = 0; k < n; ++k)
       if (u[k] < d[k]) d[k] = u[k];
-    T run = l[0] - a[0];
+    T run = osub(l[0], a[0]);
     for (int64_t k = 0; k < n; ++k) {
-      T v = l[k] - a[k];
+      T v = osub(l[k], a[k]);
       if (v > run) run = v;
       bl_out[b * n + k] = run > (T)0 ? run : (T)0;
     }
@@ -197,9 +234,9 @@ void gpc_lower_rows(const T* al, const T* bu, const T* bl, T* al_out, T* bu_out,
     conv_one(d, l, c, n);
     for (int64_t k = 0; k < n; ++k)
       if (l[k] < c[k]) c[k] = l[k];
-    T run = u[n - 1] - a[n - 1];
+    T run = osub(u[n - 1], a[n - 1]);
     for (int64_t k = n - 1; k >= 0; --k) {
-      T v = u[k] - a[k];
+      T v = osub(u[k], a[k]);
       if (v < run) run = v;
       bu_out[b * n + k] = run > (T)0 ? run : (T)0;
     }
@@ -262,9 +299,9 @@ void hdev_rows(const T* alpha, const T* beta, int32_t* out, int64_t batch, int64
 template <typename T>
 void vdev_rows(const T* alpha, const T* beta, T* out, int64_t batch, int64_t n) {
   for (int64_t b = 0; b < batch; ++b) {
-    T m = alpha[b * n] - beta[b * n];
+    T m = osub(alpha[b * n], beta[b * n]);
     for (int64_t d = 1; d < n; ++d) {
-      T v = alpha[b * n + d] - beta[b * n + d];
+      T v = osub(alpha[b * n + d], beta[b * n + d]);
       if (v > m) m = v;
     }
     out[b] = m;
@@ -300,6 +337,19 @@ void dual_rows(const void* f, const void* g, void* out, int64_t batch, int64_t n
 extern "C" {
 
 int oracle_num_threads() { return omp_get_max_threads(); }
+
+// Overflowing integer additions / subtractions seen since the last reset: only the debug build
+// counts them (-1: this build does not check).
+long long oracle_overflow_count(int reset) {
+#ifdef ORACLE_CHECK_OVERFLOW
+  const long long c = g_overflows;
+  if (reset) g_overflows = 0;
+  return c;
+#else
+  (void)reset;
+  return -1;
+#endif
+}
 
 int oracle_minplus_conv(const void* f, const void* g, void* out, int64_t batch, int64_t n,
                         int64_t stride_f, int64_t stride_g, int dt) {
