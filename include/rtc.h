@@ -363,7 +363,10 @@ int rtc_selftest_half_minmax(uint32_t* mismatches, void* hip_stream);
 /* Measurement aid (not part of the curve algebra).  While enabled, every product kernel that
  * rtc_minplus_conv / rtc_maxplus_deconv / rtc_gpc_step launch is bracketed by a HIP event pair
  * on the call's stream (up to 1024 kernels; helper kernels such as probes and fills are not
- * recorded).  rtc_profile_enable(1) clears the record and starts, rtc_profile_enable(0) stops.
+ * recorded).  rtc_profile_enable(1) clears the record and starts, rtc_profile_enable(0) stops;
+ * rtc_profile_enable(2) also records the launches that sit behind a per-row selector and may find
+ * no row of their kind (the 64-bit, re-based and fp64-on-integers kernels of an int64 product),
+ * which level 1 leaves out because every recorded launch costs about 10 us of idle stream.
  * rtc_profile_read waits for the recorded kernels and writes up to max_entries (kind, duration
  * in milliseconds) pairs to the HOST arrays kinds / ms; it returns the number written or a
  * negative status.  kind = RTC_PROFILE_KIND(dtype of the arithmetic, packed 16-bit kernel?,

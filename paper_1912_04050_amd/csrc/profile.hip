@@ -25,15 +25,16 @@ struct Slot {
 Slot g_ring[kRing];
 int g_count = 0;
 bool g_on = false;
+bool g_all = false;    // also the launches behind a per-row selector
 bool g_open = false;   // a begin without its end
 std::mutex g_lock;
 
 }  // namespace
 
-void prof_begin(int kind, hipStream_t stream) {
+void prof_begin(int kind, hipStream_t stream, bool gated) {
   if (t_dry_run) return;
   std::lock_guard<std::mutex> lock(g_lock);
-  if (!g_on || g_count >= kRing) return;
+  if (!g_on || (gated && !g_all) || g_count >= kRing) return;
   Slot& s = g_ring[g_count];
   if (!s.made) {
     if (hipEventCreate(&s.e0) != hipSuccess || hipEventCreate(&s.e1) != hipSuccess) { g_on = false; return; }
@@ -58,6 +59,7 @@ extern "C" {
 int rtc_profile_enable(int on) {
   std::lock_guard<std::mutex> lock(rtc::g_lock);
   rtc::g_on = on != 0;
+  rtc::g_all = on >= 2;
   rtc::g_count = 0;
   rtc::g_open = false;
   return RTC_OK;

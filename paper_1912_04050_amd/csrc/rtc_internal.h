@@ -63,7 +63,10 @@ int launch_max_vdev(const void* alpha, const void* beta, void* out, int64_t batc
                     hipStream_t stream);
 
 // Optional kernel timing (profile.hip).  kind = RTC_PROFILE_KIND(dtype, packed, product).
-void prof_begin(int kind, hipStream_t stream);
+// `gated`: the launch sits behind a per-row selector and may find no row of its kind; such
+// launches are recorded only by rtc_profile_enable(2) (the two event records cost about 10 us of
+// idle stream each, which a benchmark step should not pay for kernels that do nothing).
+void prof_begin(int kind, hipStream_t stream, bool gated = false);
 void prof_end(hipStream_t stream);
 
 // Kernel launches go through launch_checked, which takes the launch's OWN return code (the

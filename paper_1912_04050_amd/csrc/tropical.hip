@@ -189,7 +189,7 @@ int run_product_r(const T* a, int64_t stride_a, const T* b, int64_t stride_b, Ou
   constexpr int dtype_code = std::is_same<T, int32_t>::value ? RTC_I32 : std::is_same<T, int64_t>::value ? RTC_I64 : RTC_F64;
   if (pl.atomic || force_atomic) {
     if (!prefilled) launch_fill<OutT, OP>(out, cap, batch * n, stream);
-    prof_begin(RTC_PROFILE_KIND(dtype_code, 0, OP), stream);
+    prof_begin(RTC_PROFILE_KIND(dtype_code, 0, OP), stream, sel != nullptr);
     if (sel != nullptr && sizeof(T) == 8 && pl.items > 8192) {
       const uint32_t items_per_row = (uint32_t)(pl.items / batch);
       uint32_t parts = (uint32_t)(4096 / batch);
@@ -523,7 +523,7 @@ int run_i64(const void* f, const void* g, void* out, int64_t batch, int64_t n, i
     uint32_t parts = (uint32_t)(4096 / batch);
     if (parts < 1) parts = 1;
     if (parts > items_per_row) parts = items_per_row;
-    prof_begin(RTC_PROFILE_KIND(RTC_I64, 0, OP), stream);
+    prof_begin(RTC_PROFILE_KIND(RTC_I64, 0, OP), stream, true);
     RTC_LAUNCH(rebased_rows_kernel<OP>, dim3((uint32_t)batch * parts), dim3(64), 0, stream, args, tab,
                        tab + (size_t)batch * nb * 4, nb, items_per_row, parts);
     prof_end(stream);

@@ -158,8 +158,10 @@ __device__ __forceinline__ int32_t narrow_umax(int32_t br) { return (kPkNarrowBu
 // kPlanWhole when the whole chunk runs on the chunk-level base (else every granted sub-chunk on
 // its own base), kPlanNarrow when the narrow flavour applies.  Evaluated identically
 // (wave-uniform) by packed and 32-bit items.  *gb receives the window base, *br the window range.
-// The choice between a larger wide grant and a smaller narrow one weighs the measured cost of a
-// sub-chunk in the narrow, wide and 32-bit kernels (about 10 : 13 : 24).
+// The choice between a larger wide grant and a smaller narrow one weighs the cost of a sub-chunk
+// in the narrow, wide and 32-bit kernels (0.5, 1 and 1.5 VALU instructions per candidate plus the
+// folds: about 11 : 21 : 30), i.e. what each grant saves against leaving its sub-chunks to the
+// 32-bit items.
 __device__ __forceinline__ int chunk_plan(const PackAux& x, int row, int T2, int c, int n, int32_t* gb,
                                           int32_t* br) {
   if (as_invariant(x.pack_ok)[row] == 0) return 0;
@@ -192,7 +194,7 @@ __device__ __forceinline__ int chunk_plan(const PackAux& x, int row, int T2, int
     if (wr + r <= kPkWideBudget) wide |= 1 << j;
   }
   const int n_narrow = __builtin_popcount(narrow), n_wide = wide_whole ? kPkSubs : __builtin_popcount(wide);
-  if (n_narrow > 0 && 14 * n_narrow >= 11 * n_wide) return kPlanNarrow | narrow;
+  if (n_narrow > 0 && 19 * n_narrow >= 9 * n_wide) return kPlanNarrow | narrow;
   return wide_whole ? (kPlanWhole | 0xFF) : wide;
 }
 

@@ -264,8 +264,9 @@ def rtc_set_structure_paths(enabled: bool):
     _check(_lib.rtc_set_structure_paths(1 if enabled else 0))
 
 
-def rtc_profile_enable(on: bool):
-    _check(_lib.rtc_profile_enable(1 if on else 0))
+def rtc_profile_enable(on):
+    """False / 0 stops; True / 1 records the product kernels; 2 also those behind a per-row selector."""
+    _check(_lib.rtc_profile_enable(int(on)))
 
 
 def rtc_profile_read(max_entries: int = 1024):
