@@ -53,6 +53,10 @@ def parse():
     ap.add_argument("--bnn-batch", type=int, default=256, help="images per step of --bnn")
     ap.add_argument("--bnn-layers", default="", help="profiling aid: restrict the --bnn step to a comma list of "
                     "layer names (conv2..conv8)")
+    ap.add_argument("--case", default="", choices=["", "int32-only", "fp64"],
+                    help="profiling aid: time one other arithmetic path instead of the headline step and print its own "
+                         "JSON line: int32-only = configuration 3 as native int32 rows with the packed path off (the 32-bit "
+                         "kernel alone), fp64 = configuration 5 (one pair of 262144 samples); conv + deconv per step")
     ap.add_argument("--copy-mib", type=int, default=0, help="profiling aid: also run one plain device copy "
                     "of this many MiB, the known-size kernel that FETCH_SIZE / WRITE_SIZE are scaled by")
     return ap.parse_args()
@@ -61,7 +65,7 @@ def parse():
 # HBM traffic of one launch of the dominant kernel on the headline workload, from two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by what the same counters read for a
 # plain 1 GiB device copy; see profiles/.  None for any other workload.
-HEADLINE_TRAFFIC_BYTES = 649751657   # fetched + 532 MiB of atomic-merge writes (profiles/fused_kernel_headline_pmc.md)
+HEADLINE_TRAFFIC_BYTES = 789386329   # 211 MiB fetched + 542 MiB of atomic-merge writes (profiles/fused_kernel_headline_pmc.md)
 HEADLINE_TRAFFIC_SOURCE = ("profiles/fused_kernel_headline_pmc.md: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, "
                            "scaled by a 1 GiB device copy; a stored figure, not measured in this run")
 
@@ -725,6 +729,60 @@ def compact_configs(seed, lane_rate, copy_gbs):
     return rows
 
 
+def case_main(args):
+    """One other arithmetic path, conv + deconv per step, kernel durations from the library's event pairs."""
+    import numpy as np
+    import torch
+
+    from paper_1912_04050_amd import rtc, workloads as wl
+    torch.cuda.set_device(0)
+    seed = wl.DEFAULT_SEED if args.seed is None else args.seed
+    if args.case == "int32-only":
+        c = wl.config3(seed, 64, 65536, np.int32)
+        rtc.rtc_set_packed_min_work(1e30)       # packed path and structure detection off
+        instr, what = 1.5, "config 3 as native int32 rows, packed path off: tropical_kernel<int32> alone"
+    else:
+        c = wl.config5(seed, 262144)
+        instr, what = 2.0, "config 5: one fp64 pair of 262144 samples: tropical_kernel<double>"
+    f, g = torch.from_numpy(c["f"]).cuda(), torch.from_numpy(c["g"]).cuda()
+    B, N = f.shape
+    out_c, out_d = torch.empty_like(f), torch.empty_like(f)
+    ws = torch.empty(max(16, rtc.rtc_workspace_bytes(rtc.RTC_OP_CONV, B, N, f.dtype)), dtype=torch.uint8, device="cuda")
+    if args.copy_mib > 0:
+        src = torch.zeros(args.copy_mib << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    def step():
+        rtc.rtc_minplus_conv(f, g, out=out_c, ws=ws)
+        rtc.rtc_maxplus_deconv(f, g, out=out_d, ws=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    rtc.rtc_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    times = rtc.rtc_profile_read()
+    rtc.rtc_profile_enable(False)
+    conv = [ms for kind, ms in times if kind % 4 == 0]
+    deconv = [ms for kind, ms in times if kind % 4 == 1]
+    info = rtc.rtc_device_info()
+    lane_rate = info["cu_count"] * 64 * info["clock_khz"] * 1e3
+    po = B * N * (N + 1) // 2
+    conv_ms, deconv_ms = sum(conv) / len(conv), sum(deconv) / len(deconv)
+    print(json.dumps({"case": args.case, "workload": what, "batch": B, "n": N, "steps": args.steps, "ms_per_step": round(ms_per_step, 4),
+                      "conv_kernel_ms": round(conv_ms, 4), "deconv_kernel_ms": round(deconv_ms, 4),
+                      "conv_gpair_ops_per_s": round(po / conv_ms / 1e6, 1), "valu_instr_per_pair_op": instr,
+                      "frac_of_issue_ceiling": round(po / (conv_ms * 1e-3) * instr / lane_rate, 4),
+                      "pct_valu_peak_2ops": round(100 * 2 * po / (conv_ms * 1e-3) / lane_rate, 2)}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -733,6 +791,8 @@ def main():
         sys.exit(2)
     if args.bnn:
         return bnn_main(args)
+    if args.case:
+        return case_main(args)
 
     import numpy as np
     import torch

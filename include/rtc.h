@@ -81,8 +81,8 @@ typedef enum {
  *   widened and shifted back on store; other rows take the 64-bit kernel.
  *   For RTC_I32 it is optional: with a workspace of the full size the library also uses its
  *   packed 16-bit kernel on every (tile, chunk of 1024 steps) whose detrended value ranges fit
- *   16 bits (same exact results, up to 1.5x faster); with ws == NULL or a smaller size only the
- *   32-bit kernel runs.  The packed kernel applies to int64 rows narrowed as above, too.
+ *   16 bits (same exact results, up to 2.6x faster where they fit 15); with ws == NULL or a
+ *   smaller size only the 32-bit kernel runs.  The packed kernel applies to int64 rows narrowed as above, too.
  * Exact: there is one correct bit pattern per output (values only, no argmin). */
 int rtc_minplus_conv(const void* f, const void* g, void* out, int64_t batch, int64_t n,
                      int64_t stride_f, int64_t stride_g, rtc_dtype dt, void* ws, size_t ws_bytes,
