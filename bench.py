@@ -51,6 +51,8 @@ def parse():
                     help="measure the binary convolution layer instead (detector trunk conv2..conv8); "
                          "prints its own JSON line")
     ap.add_argument("--bnn-batch", type=int, default=256, help="images per step of --bnn")
+    ap.add_argument("--bnn-matrix", type=int, default=0, choices=[-1, 0, 1],
+                    help="matrix-core kernel of --bnn: 0 = planner's choice, 1 = wherever the shape allows, -1 = never")
     ap.add_argument("--bnn-layers", default="", help="profiling aid: restrict the --bnn step to a comma list of "
                     "layer names (conv2..conv8)")
     ap.add_argument("--case", default="", choices=["", "int32-only", "fp64"],
@@ -111,6 +113,24 @@ def gpu_ms_back_to_back(fn, calls=50, reps=5):
         ts.append(e0.elapsed_time(e1) / calls)
     ts.sort()
     return ts[len(ts) // 2]
+
+
+def graph_replay_ms(fn, reps=5):
+    """Median HIP-event time of replaying fn() captured once in a HIP graph (the library allocates nothing and
+    never synchronises, so its calls can be captured): what the call sequence costs without the host's launch path."""
+    import torch
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):          # warm-up outside the capture
+        fn()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fn()
+    med, _ = gpu_ms(graph.replay, warm=1, reps=reps)
+    del graph
+    return med
 
 
 def per_config_table(seed, peak_ops, with_cpu, configs=(1, 2, 3, 4, 5)):
@@ -420,6 +440,7 @@ def bnn_main(args):
     torch.cuda.set_device(0)
     seed = bw.DEFAULT_SEED if args.seed is None else args.seed
     N = args.bnn_batch
+    bnn.bnn_set_matrix_path(args.bnn_matrix)
     info = rtc.rtc_device_info()
     layers = []
     wanted = set(x for x in args.bnn_layers.split(",") if x)
@@ -639,6 +660,17 @@ def compact_configs(seed, lane_rate, copy_gbs):
     f, g = dev(c["f"]), dev(c["g"])
     product(1, "minplus_conv", rtc.rtc_minplus_conv, rtc.RTC_OP_CONV, f, g, "int32", note="launch-bound")
     product(1, "maxplus_deconv", rtc.rtc_maxplus_deconv, rtc.RTC_OP_DECONV, f, g, "int32", note="launch-bound")
+    o1, o2 = torch.empty_like(f), torch.empty_like(f)
+    ws1 = torch.empty(max(16, rtc.rtc_workspace_bytes(rtc.RTC_OP_CONV, 1, 4096, torch.int32)), dtype=torch.uint8, device="cuda")
+
+    def twenty_pairs():
+        for _ in range(20):
+            rtc.rtc_minplus_conv(f, g, out=o1, ws=ws1)
+            rtc.rtc_maxplus_deconv(f, g, out=o2, ws=ws1)
+
+    rows.append({"config": 1, "op": "conv + deconv, 20 times, replayed as one HIP graph", "dtype": "int32", "batch": 1, "n": 4096,
+                 "gpu_ms_per_product": round(graph_replay_ms(twenty_pairs) / 40, 4),
+                 "note": "per product once the host's launch path is out of the way"})
     # config 2: 1024 pairs of 4096 samples, periodic curves
     c = wl.config2(seed, 1024, 4096)
     a, b = dev(c["alpha_u"]), dev(c["beta_l"])
@@ -694,6 +726,7 @@ def compact_configs(seed, lane_rate, copy_gbs):
         rtc.rtc_set_structure_paths(True)
     rows.append({"config": 4, "op": "16-component GPC chain, 256 chains (32 products + scans + inverses)", "dtype": "int32",
                  "batch": B4, "n": N4, "gpu_ms": round(med, 3), "gpu_ms_min": round(mn, 3),
+                 "graph_replay_ms": round(graph_replay_ms(whole_chain), 3),
                  "equivalent_gpair_ops_per_s": round(16 * po4 / med / 1e6, 1),
                  "general_kernels_gpu_ms": round(med_g, 3),
                  "general_kernels_gpair_ops_per_s": round(16 * po4 / med_g / 1e6, 1),

@@ -42,7 +42,9 @@ int bnn_pack_channels(const void* x, bnn_value_type type, uint32_t* words, int64
 /* Number of 32-bit words of the filter bank in the kernel's own layout (the paper prepares its
  * compressed model format offline; so does this): the packed filters, transposed so that the 64
  * filters of a wavefront sit side by side, followed by one popcount per (tap, filter) that the
- * kernel uses at image borders.  0 on invalid sizes. */
+ * kernel uses at image borders; for layers that the matrix cores can take (3 x 3 filters, C a
+ * multiple of 32 and at least 128, K a multiple of 64) the filters follow once more as int8, in
+ * the order of that instruction's operand.  0 on invalid sizes. */
 size_t bnn_weight_words(int64_t K, int64_t R, int64_t S, int64_t C);
 
 /* w: [K][R][S][C] int8 of +1 / -1  ->  packed: bnn_weight_words(K, R, S, C) words. */
@@ -72,6 +74,11 @@ int bnn_binary_conv2d(const uint32_t* x, const uint32_t* packed, const float* xi
  * (1 or 2; 2 only for pixels of a multiple of 4 words and an even number of blocks).
  * 0 = choose automatically.  A value that does not apply to a shape is ignored for that shape. */
 int bnn_set_planner(int tile_pixels, int filter_blocks);
+
+/* Matrix-core path for 3 x 3, stride 1, pad 1 layers with C a multiple of 32 (>= 128) and K a
+ * multiple of 64 (results do not depend on it; process-wide, not thread-safe): 0 = where the
+ * planner expects it to be faster, 1 = wherever the shape allows, -1 = never. */
+int bnn_set_matrix_path(int mode);
 
 /* Static description of a status code. */
 const char* bnn_strerror(int status);

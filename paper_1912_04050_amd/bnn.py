@@ -31,6 +31,8 @@ _lib.bnn_strerror.restype = ctypes.c_char_p
 
 _lib.bnn_set_planner.argtypes = [_int, _int]
 _lib.bnn_set_planner.restype = _int
+_lib.bnn_set_matrix_path.argtypes = [_int]
+_lib.bnn_set_matrix_path.restype = _int
 
 
 class BnnError(RuntimeError):
@@ -60,6 +62,10 @@ def _dense_cuda(t, name):
 
 def bnn_set_planner(tile_pixels: int = 0, filter_blocks: int = 0):
     _check(_lib.bnn_set_planner(tile_pixels, filter_blocks))
+
+
+def bnn_set_matrix_path(mode: int = 0):
+    _check(_lib.bnn_set_matrix_path(mode))
 
 
 def out_shape(H, W, R, S, stride, pad):

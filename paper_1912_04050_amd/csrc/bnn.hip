@@ -28,6 +28,7 @@
 #include <hip/hip_runtime.h>
 
 #include "bnn.h"
+#include "bnn_internal.h"
 #include "rtc_internal.h"
 
 namespace bnn {
@@ -104,18 +105,6 @@ struct ConvArgs {
 // (and with them occupancy) for nothing.
 __device__ __forceinline__ void popcount_accumulate(uint32_t& acc, uint32_t v) {
   asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc) : "v"(v));
-}
-
-// Thresholds of the integrated layer in the integer domain.  For an integer x1 (exact in fp32
-// while |x1| <= 2^24, which the entry point guarantees) and v = (float)x1:
-//   gamma > 0:  (A xor B) or C = not (v < xi) = not (x1 < ceil(xi))
-//   otherwise:  (A xor B) or C = (v <= xi)    = x1 < floor(xi) + 1
-// so the decision is `(x1 < T) xor (gamma > 0)` with T = ceil(xi) resp. floor(xi) + 1, clamped to
-// +-2^30 (infinite thresholds) and -2^30 for a NaN (every comparison with it is false).
-__device__ __forceinline__ int32_t integer_threshold(float xi, bool positive) {
-  if (xi != xi) return -(1 << 30);
-  const float t = positive ? ceilf(xi) : floorf(xi) + 1.0f;
-  return (int32_t)fminf(fmaxf(t, -1073741824.0f), 1073741824.0f);
 }
 
 // v with lane LANE replaced by the wave-uniform value s (v_writelane_b32: one VALU instruction).
@@ -777,6 +766,7 @@ bool launch_resident_half(const ConvArgs& a, int R, int S, int tm, uint32_t bloc
 // Output pixels per wave: the candidate that leaves the fewest idle slots in an output row of
 // Wo pixels (ties: the wider tile).
 int g_force_tm = 0, g_force_kb = 0;   // planner overrides, see bnn_set_planner
+int g_matrix_path = 0;                // see bnn_set_matrix_path
 
 int pick_tm(int64_t Wo, bool allow13) {
   if (g_force_tm == 7 || g_force_tm == 8 || (g_force_tm == 13 && allow13)) return g_force_tm;
@@ -794,6 +784,8 @@ int pick_tm(int64_t Wo, bool allow13) {
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 constexpr int64_t kMaxDim = 1 << 20;
+// below this many output pixels the matrix-core kernel's 512-pixel workgroups leave the chip idle
+constexpr int64_t kMatrixMinPixels = 4096;
 
 }  // namespace
 }  // namespace bnn
@@ -824,7 +816,8 @@ size_t bnn_weight_words(int64_t K, int64_t R, int64_t S, int64_t C) {
   using namespace bnn;
   if (K < 1 || R < 1 || S < 1 || C < 1 || K > kMaxDim || C > kMaxDim || R > 64 || S > 64) return 0;
   const int64_t Kp = (K + 63) / 64 * 64, Cw = (C + 31) / 32;
-  return (size_t)(R * S * Cw * Kp + R * S * Kp);
+  // (a multiple of 4 words, so the int8 fragments that may follow start on a 16-byte boundary)
+  return (size_t)(R * S * Cw * Kp + R * S * Kp) + mfma_bank_bytes(K, R, S, C) / 4;
 }
 
 int bnn_pack_weights(const int8_t* w, uint32_t* packed, int64_t K, int64_t R, int64_t S, int64_t C,
@@ -840,6 +833,8 @@ int bnn_pack_weights(const int8_t* w, uint32_t* packed, int64_t K, int64_t R, in
                      packed, (int)K, (int)taps, (int)C, (int)Cw, (int)Kp);
   RTC_LAUNCH(weight_popcount_kernel, dim3((uint32_t)((taps * Kp + 255) / 256)), dim3(256), 0, stream, packed,
                      (int)taps, (int)Cw, (int)Kp);
+  if (mfma_shape(K, R, S, C))
+    launch_pack_weights_mfma(w, reinterpret_cast<int8_t*>(packed + taps * Cw * Kp + taps * Kp), K, C, stream);
   return hip_status();
 }
 
@@ -871,6 +866,15 @@ int bnn_binary_conv2d(const uint32_t* x, const uint32_t* packed, const float* xi
   a.kblocks = (int32_t)kblocks;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
+  // many channels and filters, 3 x 3, same-size output: a dense contraction for the matrix cores
+  if (g_matrix_path >= 0 && mfma_shape(K, R, S, C) && stride == 1 && pad == 1 && aligned(packed, 16) &&
+      (g_matrix_path > 0 || N * Ho * Wo >= kMatrixMinPixels)) {
+    MfmaArgs m;
+    m.x = x; m.wbytes = reinterpret_cast<const int8_t*>(packed + R * S * Cw * Kp + R * S * Kp);
+    m.xi = xi; m.gamma = gamma; m.out_x1 = out_x1; m.out_x4 = out_x4;
+    m.N = (int32_t)N; m.H = (int32_t)H; m.W = (int32_t)W; m.Cw = (int32_t)Cw; m.K = (int32_t)K;
+    if (launch_bconv_mfma(m, stream)) return hip_status();
+  }
   // few channels: the filters stay in registers and a wave streams over several tiles, enough
   // of them that a launch has about 32K waves (measured: better than 8K or 16K)
   const bool resident_shape = R == S && Cw <= 4 && (Cw & (Cw - 1)) == 0 && R * S * Cw <= 36;
@@ -937,6 +941,12 @@ int bnn_set_planner(int tile_pixels, int filter_blocks) {
     return BNN_ERR_SHAPE;
   bnn::g_force_tm = tile_pixels;
   bnn::g_force_kb = filter_blocks;
+  return BNN_OK;
+}
+
+int bnn_set_matrix_path(int mode) {
+  if (mode < -1 || mode > 1) return BNN_ERR_SHAPE;
+  bnn::g_matrix_path = mode;
   return BNN_OK;
 }
 

@@ -1,0 +1,262 @@
+// Binary convolution on the matrix cores of gfx950 (the paper's binary convolution operation and
+// layer integration sections; the instruction choice is this machine's, not the paper's).
+//
+// A binary dot product is a dense contraction: with +1 / -1 stored as int8, x1 = sum x w is
+// what v_mfma_i32_32x32x32_i8 accumulates, 32768 multiply-accumulates per instruction against 64
+// per v_xor_b32 + v_bcnt_u32_b32 pair on the vector ALU.  The price is the unpacking of bits to
+// bytes, which is paid once per staged value and amortised over the filters (activations) resp.
+// done when the filter bank is prepared (filters).
+//
+// Mapping.  Output pixels are numbered q = (n H + y) W + x over the whole batch (stride 1 and
+// padding 1 keep the output the size of the input).  A workgroup of 4 waves owns 128 MT
+// consecutive pixels and 64 consecutive filters; wave w owns the pixel tiles
+// [32 (w MT + mt), +32), mt < MT, and both 32-filter tiles: 2 MT accumulator tiles of 16 registers.
+// Per word of channels (32 channels = one K step of the instruction):
+//   * the words of the input pixels that the workgroup's taps touch are unpacked to bytes in LDS,
+//     48 bytes apart (32 of data + 16 of skew: the 16-byte reads of 8 consecutive pixels then
+//     fall on 8 different bank groups).  LDS slots follow the PADDED image: slot
+//     t(n, y, x) = (n (H + 1) + y) (W + 1) + x, so every image row is followed by one slot and
+//     every image by one row of slots that hold zeros.  The tap (dy, dx) of any pixel is then the
+//     slot t + dy (W + 1) + dx, also at the borders, where it is one of the zero slots -- zero
+//     padding: such taps add nothing -- and no lane needs a mask;
+//   * the filter fragments of this channel word (18 KB: 9 taps x 2 tiles of 32 filters) are
+//     copied to LDS as they are;
+//   * for each of the 9 taps a lane reads the 16 bytes of "its" pixel shifted by the tap
+//     (row i = lane % 32 of the A operand, channels 16 (lane / 32) ... + 15) and, once per tap,
+//     the 16 bytes of filter lane % 32 for the same channels (B operand).
+// Both stagings are fetched into registers one channel word ahead, under the matrix instructions
+// of the current one.
+// The contraction sums over (tap, channel) in any order, so only the pairing of A and B bytes
+// matters: both use lane / 32 for the half and the byte index for the channel.
+// Result layout of the instruction (checked on the device): register r of lane l holds row
+// 8 (r / 4) + 4 (l / 32) + r % 4, column l % 32.  Columns are filters, so the 64-lane compare mask
+// of register r IS the packed output word of two pixels (rows ... and ... + 4): the ballot packs.
+#include <hip/hip_runtime.h>
+
+#include "bnn_internal.h"
+#include "rtc_internal.h"
+
+namespace bnn {
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int kProfileKind = 32;    // the convolution kernel's kind in the timing record
+constexpr int kPitch = 48;          // bytes per staged pixel: 32 channels + skew
+constexpr int kMinChannels = 128;   // below that the vector-ALU kernels keep their filters in registers
+
+// 4 bits -> 4 bytes of +1 (bit set) / -1, or 4 zero bytes.  The multiplication puts bit j of the
+// nibble at bit 8 j (the partial products n << 0, 7, 14, 21 do not collide there); the byte
+// permute then looks every byte up in the table {0: 0xFF, 1: 0x01}.  `zero` = 0x0C0C0C0C together
+// with n = 0 makes every selector 12, which yields 0x00; `zero` = 0 changes nothing.
+__device__ __forceinline__ uint32_t nibble_to_signs(uint32_t n, uint32_t zero) {
+  const uint32_t spread = (__umul24(n, 0x204081u) & 0x01010101u) | zero;
+  return __builtin_amdgcn_perm(0x000001FFu, 0x000001FFu, spread);
+}
+
+// ---- filter fragments -------------------------------------------------------------------------
+// bank[((((fg Cw + cw) 9 + tap) 2 + nt) 64 + lane) 16 + j] = w[fg 64 + nt 32 + lane % 32][tap][cw 32 + 16 (lane / 32) + j]
+__global__ __launch_bounds__(256) void pack_weights_mfma_kernel(const int8_t* __restrict__ w, int8_t* __restrict__ bank,
+                                                                int K, int C, int Cw) {
+  const int64_t frag = (int64_t)blockIdx.x * 256 + threadIdx.x;      // one 16-byte fragment per thread
+  const int64_t total = (int64_t)(K / 64) * Cw * 9 * 2 * 64;
+  if (frag >= total) return;
+  const int lane = (int)(frag % 64);
+  const int nt = (int)((frag / 64) % 2);
+  const int tap = (int)((frag / 128) % 9);
+  const int cw = (int)((frag / (128 * 9)) % Cw);
+  const int fg = (int)(frag / ((int64_t)128 * 9 * Cw));
+  const int k = fg * 64 + nt * 32 + lane % 32;
+  const int8_t* src = w + ((int64_t)k * 9 + tap) * C + cw * 32 + 16 * (lane / 32);
+  int8_t* dst = bank + frag * 16;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) dst[j] = src[j] > 0 ? (int8_t)1 : (int8_t)-1;
+}
+
+// ---- convolution ------------------------------------------------------------------------------
+constexpr int kStageRounds = 3;                      // staged slots per thread and channel word
+constexpr int kMaxSlots = 256 * kStageRounds;
+constexpr int kFragBytes = 9 * 2 * 64 * 16;          // filter fragments of one (filter group, channel word)
+constexpr int kFragChunks = kFragBytes / 16;         // in 16-byte pieces: 1152 = 4.5 per thread
+constexpr int kFragRounds = (kFragChunks + 255) / 256;
+
+// slot of pixel q in the padded numbering
+__device__ __forceinline__ int64_t padded_slot(int64_t q, int H, int W) {
+  const int64_t row = q / W;                         // n H + y
+  const int x = (int)(q - row * W);
+  const int64_t n = row / H;
+  const int y = (int)(row - n * H);
+  return (n * (H + 1) + y) * (W + 1) + x;
+}
+
+template <int MT>
+__global__ __launch_bounds__(256, 2) void bconv_mfma_kernel(const MfmaArgs a, int fgroups) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  unsigned char* const ldsB = lds;                     // the filter fragments of the current channel word
+  unsigned char* const ldsA = lds + kFragBytes;        // the unpacked pixels
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int i = lane & 31, h = lane >> 5;
+  const int W = a.W, H = a.H, Cw = a.Cw, PW = W + 1, PH = H + 1;
+  const int64_t total = (int64_t)a.N * H * W;
+  constexpr int kWgPixels = 4 * MT * 32;
+  const int fg = blockIdx.x % fgroups;
+  const int64_t P0 = (int64_t)(blockIdx.x / fgroups) * kWgPixels;
+  const int64_t Plast = P0 + kWgPixels - 1 < total ? P0 + kWgPixels - 1 : total - 1;
+  const int64_t slot0 = padded_slot(P0, H, W) - (PW + 1);
+  const int slots = (int)(padded_slot(Plast, H, W) + (PW + 1) + 1 - slot0);   // <= kMaxSlots (launcher)
+
+  // the lane's pixel of each of the wave's tiles (pixels beyond the last one read the last one's
+  // data; their results are not stored)
+  int lds_pix[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    int64_t q = P0 + (wave * MT + mt) * 32 + i;
+    if (q > Plast) q = Plast;
+    lds_pix[mt] = (int)(padded_slot(q, H, W) - slot0) * kPitch + 16 * h;
+  }
+
+  v16i acc[MT][2];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { acc[mt][0][r] = 0; acc[mt][1][r] = 0; }
+  }
+
+  // what a thread stages per channel word: up to kStageRounds slots and kFragRounds 16-byte pieces
+  // of the filter fragments (in the last round the upper half of the threads repeats the lower
+  // half's pieces)
+  const uint32_t* xsrc[kStageRounds];
+  bool xreal[kStageRounds];
+  int xdst[kStageRounds];
+#pragma unroll
+  for (int j = 0; j < kStageRounds; ++j) {
+    int s = threadIdx.x + 256 * j;
+    if (s > slots - 1) s = slots - 1;
+    const int64_t t = slot0 + s;
+    const int64_t prow = t >= 0 ? t / PW : -1;
+    const int x = (int)(t - prow * PW);
+    const int64_t n = prow >= 0 ? prow / PH : 0;
+    const int y = (int)(prow - n * PH);
+    xreal[j] = prow >= 0 && x < W && y < H && n < a.N;
+    xsrc[j] = a.x + (xreal[j] ? ((n * H + y) * W + x) * Cw : 0);
+    xdst[j] = s * kPitch;
+  }
+  int wchunk[kFragRounds];
+#pragma unroll
+  for (int j = 0; j < kFragRounds; ++j) {
+    const int c = threadIdx.x + 256 * j;
+    wchunk[j] = c < kFragChunks ? c : c - 128;
+  }
+  const v4i* wsrc = reinterpret_cast<const v4i*>(a.wbytes + (int64_t)fg * Cw * kFragBytes);
+  uint32_t xr[kStageRounds];
+  v4i wr[kFragRounds];
+  auto fetch = [&](int cw) {
+#pragma unroll
+    for (int j = 0; j < kStageRounds; ++j) xr[j] = xsrc[j][cw];
+#pragma unroll
+    for (int j = 0; j < kFragRounds; ++j) wr[j] = wsrc[cw * kFragChunks + wchunk[j]];
+  };
+  fetch(0);
+
+  for (int cw = 0; cw < Cw; ++cw) {
+    __syncthreads();                       // the previous word's reads are done
+#pragma unroll
+    for (int j = 0; j < kStageRounds; ++j) {
+      if (256 * j < slots) {               // (uniform) a round that would only repeat the last slot
+        const uint32_t word = xreal[j] ? xr[j] : 0u;            // a padding slot: zeros
+        const uint32_t zero = xreal[j] ? 0u : 0x0C0C0C0Cu;
+        uint4 lo, hi;
+        lo.x = nibble_to_signs(word & 15u, zero);         lo.y = nibble_to_signs((word >> 4) & 15u, zero);
+        lo.z = nibble_to_signs((word >> 8) & 15u, zero);  lo.w = nibble_to_signs((word >> 12) & 15u, zero);
+        hi.x = nibble_to_signs((word >> 16) & 15u, zero); hi.y = nibble_to_signs((word >> 20) & 15u, zero);
+        hi.z = nibble_to_signs((word >> 24) & 15u, zero); hi.w = nibble_to_signs(word >> 28, zero);
+        *reinterpret_cast<uint4*>(ldsA + xdst[j]) = lo;
+        *reinterpret_cast<uint4*>(ldsA + xdst[j] + 16) = hi;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < kFragRounds; ++j) reinterpret_cast<v4i*>(ldsB)[wchunk[j]] = wr[j];
+    __syncthreads();
+    if (cw + 1 < Cw) fetch(cw + 1);
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap) {
+      const v4i b0 = *reinterpret_cast<const v4i*>(ldsB + ((tap * 2 + 0) * 64 + lane) * 16);
+      const v4i b1 = *reinterpret_cast<const v4i*>(ldsB + ((tap * 2 + 1) * 64 + lane) * 16);
+      const int toff = ((tap / 3 - 1) * PW + (tap % 3 - 1)) * kPitch;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const v4i av = *reinterpret_cast<const v4i*>(ldsA + lds_pix[mt] + toff);
+        acc[mt][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av, b0, acc[mt][0], 0, 0, 0);
+        acc[mt][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av, b1, acc[mt][1], 0, 0, 0);
+      }
+    }
+  }
+
+  // epilogue: x1 as it is, and / or the integrated layer's bit, packed by the ballot
+  const int Kw = a.K / 32;
+#pragma unroll
+  for (int nt = 0; nt < 2; ++nt) {
+    const int k = fg * 64 + nt * 32 + i;
+    int32_t T = 0;
+    bool positive = false;
+    if (a.out_x4 != nullptr) {
+      positive = a.gamma[k] > 0.f;
+      T = integer_threshold(a.xi[k], positive);
+    }
+    const unsigned long long posmask = __ballot(positive);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = 8 * (r / 4) + 4 * h + (r % 4);
+        const int64_t q = P0 + (wave * MT + mt) * 32 + row;
+        const int32_t x1 = acc[mt][nt][r];
+        if (a.out_x1 != nullptr && q < total) a.out_x1[q * a.K + k] = x1;
+        if (a.out_x4 != nullptr) {
+          const unsigned long long mask = __ballot(x1 < T) ^ posmask;
+          // lanes 0..31 hold the pixel of row (h = 0), lanes 32..63 the one four rows further
+          if (i == 0 && q < total) a.out_x4[q * Kw + fg * 2 + nt] = (uint32_t)(h ? mask >> 32 : mask);
+        }
+      }
+    }
+  }
+}
+
+}  // namespace
+
+bool mfma_shape(int64_t K, int64_t R, int64_t S, int64_t C) {
+  return R == 3 && S == 3 && C % 32 == 0 && C >= kMinChannels && K % 64 == 0;
+}
+
+size_t mfma_bank_bytes(int64_t K, int64_t R, int64_t S, int64_t C) {
+  return mfma_shape(K, R, S, C) ? (size_t)K * 9 * C : 0;
+}
+
+void launch_pack_weights_mfma(const int8_t* w, int8_t* bank, int64_t K, int64_t C, hipStream_t stream) {
+  const int64_t frags = (K / 64) * (C / 32) * 9 * 2 * 64;
+  RTC_LAUNCH(pack_weights_mfma_kernel, dim3((uint32_t)((frags + 255) / 256)), dim3(256), 0, stream, w, bank, (int)K,
+             (int)C, (int)(C / 32));
+}
+
+bool launch_bconv_mfma(const MfmaArgs& a, hipStream_t stream) {
+  const int64_t total = (int64_t)a.N * a.H * a.W;
+  constexpr int MT = 4;
+  constexpr int kWgPixels = 4 * MT * 32;
+  // upper bound of the padded slots that a workgroup's pixels and their taps span: its pixels, one
+  // slot per image row and one row of slots per image that it can touch, and a padded row + 1 on
+  // either side
+  const int64_t rows_touched = (kWgPixels - 1) / a.W + 2, images_touched = (kWgPixels - 1) / ((int64_t)a.H * a.W) + 2;
+  const int64_t slot_bound = kWgPixels + rows_touched + images_touched * (a.W + 1) + 2 * (a.W + 2) + 1;
+  if (slot_bound > kMaxSlots) return false;                  // long rows or tiny images: another kernel
+  const size_t lds_bytes = (size_t)kFragBytes + (size_t)slot_bound * kPitch;
+  const int64_t fgroups = a.K / 64;
+  const int64_t blocks = (total + kWgPixels - 1) / kWgPixels * fgroups;
+  if (blocks > 0x7fffffffLL) return false;
+  rtc::prof_begin(kProfileKind, stream);
+  RTC_LAUNCH(bconv_mfma_kernel<MT>, dim3((uint32_t)blocks), dim3(256), lds_bytes, stream, a, (int)fgroups);
+  rtc::prof_end(stream);
+  return true;
+}
+
+}  // namespace bnn

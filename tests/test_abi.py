@@ -127,6 +127,9 @@ def test_bnn_entry_points_reject_bad_arguments(lib):
     lib.bnn_weight_words.restype = ctypes.c_size_t
     assert lib.bnn_weight_words(70, 3, 3, 40) == 9 * 2 * 128 + 9 * 128      # K padded to 128, two words per pixel
     assert lib.bnn_weight_words(0, 3, 3, 40) == 0
+    # a matrix-core shape carries the filters once more as int8 (K 9 C bytes)
+    assert lib.bnn_weight_words(64, 3, 3, 128) == 9 * 4 * 64 + 9 * 64 + 64 * 9 * 128 // 4
+    assert lib.bnn_weight_words(64, 3, 3, 96) == 9 * 3 * 64 + 9 * 64
     lib.bnn_pack_weights.argtypes = [ctypes.c_void_p, ctypes.c_void_p, i64, i64, i64, i64, ctypes.c_void_p]
     assert lib.bnn_pack_weights(p, None, 8, 3, 3, 32, None) == -1
     assert lib.bnn_pack_weights(p, p, 8, 3, 0, 32, None) == -2

@@ -13,15 +13,18 @@ pytestmark = pytest.mark.gpu
 SEED = bw.DEFAULT_SEED
 
 
-@pytest.fixture(scope="module", params=[(0, 0), (7, 1), (8, 2), (13, 2)],
-                ids=["automatic", "tiles-of-7", "tiles-of-8-two-blocks", "tiles-of-13-two-blocks"])
+@pytest.fixture(scope="module", params=[(0, 0, 0), (7, 1, -1), (8, 2, -1), (13, 2, -1), (0, 0, 1)],
+                ids=["automatic", "tiles-of-7", "tiles-of-8-two-blocks", "tiles-of-13-two-blocks", "matrix-cores"])
 def bnn(request):
-    """Every test runs under the automatic planner and with the tile width / filter blocks per
-    wave forced to each instantiated value (settings that do not apply to a shape are ignored)."""
+    """Every test runs under the automatic planner, with the tile width / filter blocks per wave
+    forced to each instantiated value, and with the matrix-core kernel forced wherever a shape
+    admits it (settings that do not apply to a shape are ignored)."""
     from paper_1912_04050_amd import bnn as mod
-    mod.bnn_set_planner(*request.param)
+    mod.bnn_set_planner(*request.param[:2])
+    mod.bnn_set_matrix_path(request.param[2])
     yield mod
     mod.bnn_set_planner(0, 0)
+    mod.bnn_set_matrix_path(0)
 
 
 def say(*a):
@@ -172,3 +175,33 @@ def test_classifier_layer_shapes(bnn):
     """The 32 x 32 classifier trunk's layer shapes (maps down to 2 x 2, where every pixel is a border pixel)."""
     for i, (name, hw, C, K) in enumerate(bw.CLASSIFIER_LAYERS):
         check_layer(bnn, 500 + i, 3, hw, hw, C, K, 3, 3, 1, 1)
+
+
+@pytest.mark.parametrize("shape", [
+    # N, H, W, C, K: shapes the matrix-core kernel admits (3 x 3, stride 1, pad 1, C % 32 = 0, C >= 128, K % 64 = 0)
+    (1, 1, 1, 128, 64), (2, 3, 3, 128, 64), (1, 5, 1, 160, 128), (1, 1, 9, 128, 64), (3, 13, 13, 128, 192),
+    (1, 20, 27, 224, 64), (5, 11, 10, 128, 64), (1, 2, 300, 128, 64), (1, 23, 23, 1024, 64), (7, 25, 25, 128, 64)])
+def test_matrix_core_shapes(bnn, shape):
+    """Images smaller than a tile of 32 pixels, tiles that straddle image rows and images, a ragged
+    last workgroup, a row longer than a tile, pixels of 4, 5, 7 and 32 words, 1 to 3 groups of 64
+    filters; the last case is large enough for the automatic planner to pick the kernel."""
+    N, H, W, C, K = shape
+    check_layer(bnn, 600 + H * 7 + W + C, N, H, W, C, K, 3, 3, 1, 1)
+
+
+def test_matrix_core_special_thresholds(bnn):
+    """Infinite, NaN, tied and out-of-range thresholds with 64 filters (the shape the matrix-core
+    kernel takes); every filter beyond the first eight gets one of the special values in turn."""
+    N, H, W, C, K = 2, 7, 6, 128, 64
+    x, w, xi, gamma = bw.layer_inputs(SEED, 306, N, H, W, C, K)
+    special = np.array([np.inf, -np.inf, np.nan, np.nan, 0.5, -0.5, 3e9, -3e9], np.float32)
+    sign = np.array([1, 1, 1, -1, 1, -1, -1, 1], np.float32)
+    xi[8:] = np.tile(special, 7)
+    gamma[8:] = np.tile(sign, 7)
+    _, x4 = bnn.bnn_binary_conv2d(bnn.bnn_pack_channels(dev(x)), bnn.bnn_pack_weights(dev(w)), (N, H, W, C, K, 3, 3),
+                                  dev(xi), dev(gamma), pad=1)
+    x1 = obnn.conv2d(x, w, 1, 1).astype(np.float32)
+    with np.errstate(invalid="ignore"):
+        A, B, Cq = x1 < xi, gamma > 0, x1 == xi
+    want = np.logical_or(np.logical_xor(A, B), Cq)
+    assert np.array_equal(host_words(x4), obnn.pack(want.astype(np.int8)))
