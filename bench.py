@@ -421,6 +421,7 @@ def per_config_table(seed, peak_ops, with_cpu, configs=(1, 2, 3, 4, 5)):
 # HBM traffic of one launch of the dominant kernel of --bnn (conv8 at batch 256), measured like
 # HEADLINE_TRAFFIC_BYTES; see profiles/.  None until measured / for any other batch.
 BNN_TRAFFIC_BYTES = 40876675   # 33.7 MiB fetched + 5.3 MiB written (profiles/bconv_lds_kernel_conv8_pmc.md)
+BNN_MFMA_TRAFFIC_BYTES = 100652980   # 71.3 MiB fetched + 24.7 MiB written (profiles/bconv_mfma_kernel_conv8_pmc.md)
 
 
 def bnn_main(args):
@@ -496,19 +497,37 @@ def bnn_main(args):
         avg = sum(ts) / max(len(ts), 1)
         per_layer.append({"layer": L["name"], "map": L["hw"], "C": L["C"], "K": L["K"], "kernel_ms": round(avg, 4),
                           "tmac_per_s": round(L["macs"] / avg / 1e9, 1) if avg else None})
-    # roofline of the dominant kernel (the last, largest layer): 2 VALU instructions (xor, popcount-accumulate)
-    # per 32 multiply-accumulates and lane; peak = CUs x 64 lanes x clock lane-ops/s
-    peak_ops = info["cu_count"] * 64 * info["clock_khz"] * 1e3
+    # roofline of the dominant kernel (the last, largest layer)
+    info_clock = info["clock_khz"] * 1e3
     dom = layers[-1]
     dom_ms = per_layer[-1]["kernel_ms"]
-    achieved = dom["macs"] / 16 / (dom_ms * 1e-3)
-    roofline = {"bound": "alu", "kernel": f"bconv_lds_kernel ({dom['name']}: {dom['hw']}x{dom['hw']} map, {dom['C']} -> {dom['K']} channels)",
-                "achieved": round(achieved / 1e12, 4), "peak": round(peak_ops / 1e12, 4), "unit": "TOP/s",
-                "frac": round(achieved / peak_ops, 4), "traffic": BNN_TRAFFIC_BYTES if N == 256 and dom["name"] == "conv8" else None,
-                "launch_ms": dom_ms, "macs_per_launch": dom["macs"],
-                "tmac_per_s": round(dom["macs"] / dom_ms / 1e9, 1),
-                "note": "a lane-op is one VALU lane-instruction; the kernel needs v_xor_b32 + v_bcnt_u32_b32 per 32 "
-                        "binary multiply-accumulates, so peak = 16 x 39.32 T = 629 TMAC/s"}
+    on_matrix = bnn.bnn_matrix_path_applies(N, dom["hw"], dom["hw"], dom["C"], dom["K"])
+    shape = f"{dom['name']}: {dom['hw']}x{dom['hw']} map, {dom['C']} -> {dom['K']} channels"
+    if on_matrix:
+        # +1 / -1 as int8 on v_mfma_i32_32x32x32_i8: 2 operations per multiply-accumulate against the published
+        # dense int8 peak
+        achieved = 2.0 * dom["macs"] / (dom_ms * 1e-3)
+        roofline = {"bound": "mfma", "kernel": f"bconv_mfma_kernel ({shape})",
+                    "achieved": round(achieved / 1e12, 1), "peak": 5000.0, "unit": "TOP/s", "frac": round(achieved / 5e15, 4),
+                    "traffic": BNN_MFMA_TRAFFIC_BYTES if N == 256 and dom["name"] == "conv8" else None,
+                    "launch_ms": dom_ms, "macs_per_launch": dom["macs"], "tmac_per_s": round(dom["macs"] / dom_ms / 1e9, 1),
+                    "note": "int8 dense peak 5.0 POP/s = 2500 TMAC/s at 2.4 GHz; a loop of nothing but this instruction on "
+                            "random +-1 operands measured 1770-1980 TMAC/s on this chip (sustained clock 1.75-1.95 GHz); "
+                            "the vector-ALU kernel of the same layer (--bnn-matrix -1) is bounded by 629 TMAC/s"}
+    else:
+        # 2 VALU instructions (xor, popcount-accumulate) per 32 multiply-accumulates and lane; peak = CUs x 64
+        # lanes x clock lane-ops/s
+        peak_ops = info["cu_count"] * 64 * info_clock
+        achieved = dom["macs"] / 16 / (dom_ms * 1e-3)
+        roofline = {"bound": "alu", "kernel": f"bconv_lds_kernel ({shape})",
+                    "achieved": round(achieved / 1e12, 4), "peak": round(peak_ops / 1e12, 4), "unit": "TOP/s",
+                    "frac": round(achieved / peak_ops, 4), "traffic": BNN_TRAFFIC_BYTES if N == 256 and dom["name"] == "conv8" else None,
+                    "launch_ms": dom_ms, "macs_per_launch": dom["macs"],
+                    "tmac_per_s": round(dom["macs"] / dom_ms / 1e9, 1),
+                    "note": "a lane-op is one VALU lane-instruction; the kernel needs v_xor_b32 + v_bcnt_u32_b32 per 32 "
+                            "binary multiply-accumulates, so peak = 16 x 39.32 T = 629 TMAC/s"}
+    for L, row in zip(layers, per_layer):
+        row["kernel"] = "matrix cores" if bnn.bnn_matrix_path_applies(N, L["hw"], L["hw"], L["C"], L["K"]) else "vector ALU"
 
     # sampled parity and CPU baseline: the oracle on a few images of each layer
     cpu_baseline, parity = None, None
@@ -544,7 +563,7 @@ def bnn_main(args):
     line = {"metric": "binary convolution TMAC/s (xor/popcount, integrated threshold + packing), detector trunk",
             "value": round(total_macs / (ms_per_step * 1e-3) / 1e12, 2), "unit": "TMAC/s", "n_gpus": 1,
             "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32 (1-bit values, 32 per word)",
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32 (1-bit values, 32 per word; layers on the matrix cores multiply them as int8, accumulate int32)",
             "data": "synthetic",
             "config": {"workload": f"binary layers conv2..conv8 of a 416x416 single-shot detector trunk, batch {N}, "
                                    "3x3 / stride 1 / padding 1, packed NHWC in and out", "batch": N, "seed": seed},

@@ -80,6 +80,12 @@ int bnn_set_planner(int tile_pixels, int filter_blocks);
  * planner expects it to be faster, 1 = wherever the shape allows, -1 = never. */
 int bnn_set_matrix_path(int mode);
 
+/* 1 if bnn_binary_conv2d would run this layer on the matrix cores under the current setting of
+ * bnn_set_matrix_path (given 16-byte aligned filter bank), else 0 (also for invalid sizes).  For
+ * reports: which kernel a measured time belongs to. */
+int bnn_matrix_path_applies(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
+                            int64_t stride, int64_t pad);
+
 /* Static description of a status code. */
 const char* bnn_strerror(int status);
 

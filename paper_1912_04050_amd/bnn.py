@@ -33,6 +33,8 @@ _lib.bnn_set_planner.argtypes = [_int, _int]
 _lib.bnn_set_planner.restype = _int
 _lib.bnn_set_matrix_path.argtypes = [_int]
 _lib.bnn_set_matrix_path.restype = _int
+_lib.bnn_matrix_path_applies.argtypes = [_i64] * 9
+_lib.bnn_matrix_path_applies.restype = _int
 
 
 class BnnError(RuntimeError):
@@ -66,6 +68,10 @@ def bnn_set_planner(tile_pixels: int = 0, filter_blocks: int = 0):
 
 def bnn_set_matrix_path(mode: int = 0):
     _check(_lib.bnn_set_matrix_path(mode))
+
+
+def bnn_matrix_path_applies(N, H, W, C, K, R=3, S=3, stride=1, pad=1) -> bool:
+    return bool(_lib.bnn_matrix_path_applies(N, H, W, C, K, R, S, stride, pad))
 
 
 def out_shape(H, W, R, S, stride, pad):

@@ -787,6 +787,14 @@ constexpr int64_t kMaxDim = 1 << 20;
 // below this many output pixels the matrix-core kernel's 512-pixel workgroups leave the chip idle
 constexpr int64_t kMatrixMinPixels = 4096;
 
+// The planner's choice for a layer (the launcher can still decline: rows of more than 127 pixels
+// and images of very few pixels need more LDS slots than the kernel stages).
+bool matrix_path_wanted(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S, int64_t stride,
+                        int64_t pad) {
+  return g_matrix_path >= 0 && mfma_shape(K, R, S, C) && stride == 1 && pad == 1 &&
+         (g_matrix_path > 0 || N * H * W >= kMatrixMinPixels);
+}
+
 }  // namespace
 }  // namespace bnn
 
@@ -867,8 +875,7 @@ int bnn_binary_conv2d(const uint32_t* x, const uint32_t* packed, const float* xi
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
   // many channels and filters, 3 x 3, same-size output: a dense contraction for the matrix cores
-  if (g_matrix_path >= 0 && mfma_shape(K, R, S, C) && stride == 1 && pad == 1 && aligned(packed, 16) &&
-      (g_matrix_path > 0 || N * Ho * Wo >= kMatrixMinPixels)) {
+  if (matrix_path_wanted(N, H, W, C, K, R, S, stride, pad) && aligned(packed, 16)) {
     MfmaArgs m;
     m.x = x; m.wbytes = reinterpret_cast<const int8_t*>(packed + R * S * Cw * Kp + R * S * Kp);
     m.xi = xi; m.gamma = gamma; m.out_x1 = out_x1; m.out_x4 = out_x4;
@@ -948,6 +955,13 @@ int bnn_set_matrix_path(int mode) {
   if (mode < -1 || mode > 1) return BNN_ERR_SHAPE;
   bnn::g_matrix_path = mode;
   return BNN_OK;
+}
+
+int bnn_matrix_path_applies(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S, int64_t stride,
+                            int64_t pad) {
+  using namespace bnn;
+  if (N < 1 || H < 1 || W < 1 || C < 1 || K < 1 || R < 1 || S < 1) return 0;
+  return matrix_path_wanted(N, H, W, C, K, R, S, stride, pad) && mfma_slots_fit(H, W) ? 1 : 0;
 }
 
 const char* bnn_strerror(int status) {

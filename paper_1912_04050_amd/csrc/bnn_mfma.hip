@@ -13,8 +13,8 @@
 // [32 (w MT + mt), +32), mt < MT, and both 32-filter tiles: 2 MT accumulator tiles of 16 registers.
 // Per word of channels (32 channels = one K step of the instruction):
 //   * the words of the input pixels that the workgroup's taps touch are unpacked to bytes in LDS,
-//     48 bytes apart (32 of data + 16 of skew: the 16-byte reads of 8 consecutive pixels then
-//     fall on 8 different bank groups).  LDS slots follow the PADDED image: slot
+//     16 bytes per pixel in each of two planes (channels 0..15 and 16..31 of the word), so that
+//     consecutive lanes read consecutive 16-byte pieces.  LDS slots follow the PADDED image: slot
 //     t(n, y, x) = (n (H + 1) + y) (W + 1) + x, so every image row is followed by one slot and
 //     every image by one row of slots that hold zeros.  The tap (dy, dx) of any pixel is then the
 //     slot t + dy (W + 1) + dx, also at the borders, where it is one of the zero slots -- zero
@@ -43,7 +43,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kProfileKind = 32;    // the convolution kernel's kind in the timing record
-constexpr int kPitch = 48;          // bytes per staged pixel: 32 channels + skew
+constexpr int kPitch = 16;          // bytes per staged pixel and half (16 channels)
 constexpr int kMinChannels = 128;   // below that the vector-ALU kernels keep their filters in registers
 
 // 4 bits -> 4 bytes of +1 (bit set) / -1, or 4 zero bytes.  The multiplication puts bit j of the
@@ -75,6 +75,7 @@ __global__ __launch_bounds__(256) void pack_weights_mfma_kernel(const int8_t* __
 }
 
 // ---- convolution ------------------------------------------------------------------------------
+constexpr int kTilesPerWave = 4;                     // MT: pixel tiles of 32 per wave
 constexpr int kStageRounds = 3;                      // staged slots per thread and channel word
 constexpr int kMaxSlots = 256 * kStageRounds;
 constexpr int kFragBytes = 9 * 2 * 64 * 16;          // filter fragments of one (filter group, channel word)
@@ -90,8 +91,12 @@ __device__ __forceinline__ int64_t padded_slot(int64_t q, int H, int W) {
   return (n * (H + 1) + y) * (W + 1) + x;
 }
 
-template <int MT>
-__global__ __launch_bounds__(256, 2) void bconv_mfma_kernel(const MfmaArgs a, int fgroups) {
+// QC: channel words that a thread fetches per staged pixel at a time (4 where a pixel's words
+// allow 16-byte loads: a word-by-word walk would pull every pixel's cache line in again for each
+// word).
+template <int MT, int QC>
+__global__ __launch_bounds__(256, 2) void bconv_mfma_kernel(const MfmaArgs a, int fgroups, int plane) {
+  typedef uint32_t xwords __attribute__((ext_vector_type(QC)));
   extern __shared__ __align__(16) unsigned char lds[];
   unsigned char* const ldsB = lds;                     // the filter fragments of the current channel word
   unsigned char* const ldsA = lds + kFragBytes;        // the unpacked pixels
@@ -113,7 +118,7 @@ __global__ __launch_bounds__(256, 2) void bconv_mfma_kernel(const MfmaArgs a, in
   for (int mt = 0; mt < MT; ++mt) {
     int64_t q = P0 + (wave * MT + mt) * 32 + i;
     if (q > Plast) q = Plast;
-    lds_pix[mt] = (int)(padded_slot(q, H, W) - slot0) * kPitch + 16 * h;
+    lds_pix[mt] = (int)(padded_slot(q, H, W) - slot0 - 1) * kPitch + plane * h;     // the tap (0, -1)
   }
 
   v16i acc[MT][2];
@@ -149,11 +154,13 @@ __global__ __launch_bounds__(256, 2) void bconv_mfma_kernel(const MfmaArgs a, in
     wchunk[j] = c < kFragChunks ? c : c - 128;
   }
   const v4i* wsrc = reinterpret_cast<const v4i*>(a.wbytes + (int64_t)fg * Cw * kFragBytes);
-  uint32_t xr[kStageRounds];
+  xwords xr[kStageRounds];
   v4i wr[kFragRounds];
   auto fetch = [&](int cw) {
+    if (cw % QC == 0) {
 #pragma unroll
-    for (int j = 0; j < kStageRounds; ++j) xr[j] = xsrc[j][cw];
+      for (int j = 0; j < kStageRounds; ++j) xr[j] = *reinterpret_cast<const xwords*>(xsrc[j] + cw);
+    }
 #pragma unroll
     for (int j = 0; j < kFragRounds; ++j) wr[j] = wsrc[cw * kFragChunks + wchunk[j]];
   };
@@ -164,7 +171,14 @@ __global__ __launch_bounds__(256, 2) void bconv_mfma_kernel(const MfmaArgs a, in
 #pragma unroll
     for (int j = 0; j < kStageRounds; ++j) {
       if (256 * j < slots) {               // (uniform) a round that would only repeat the last slot
-        const uint32_t word = xreal[j] ? xr[j] : 0u;            // a padding slot: zeros
+        uint32_t word;
+        if constexpr (QC == 1) {
+          word = xr[j][0];
+        } else {
+          const int sub = cw % QC;
+          word = sub == 0 ? xr[j][0] : sub == 1 ? xr[j][1] : sub == 2 ? xr[j][2] : xr[j][3];
+        }
+        if (!xreal[j]) word = 0u;                               // a padding slot: zeros
         const uint32_t zero = xreal[j] ? 0u : 0x0C0C0C0Cu;
         uint4 lo, hi;
         lo.x = nibble_to_signs(word & 15u, zero);         lo.y = nibble_to_signs((word >> 4) & 15u, zero);
@@ -172,23 +186,32 @@ __global__ __launch_bounds__(256, 2) void bconv_mfma_kernel(const MfmaArgs a, in
         hi.x = nibble_to_signs((word >> 16) & 15u, zero); hi.y = nibble_to_signs((word >> 20) & 15u, zero);
         hi.z = nibble_to_signs((word >> 24) & 15u, zero); hi.w = nibble_to_signs(word >> 28, zero);
         *reinterpret_cast<uint4*>(ldsA + xdst[j]) = lo;
-        *reinterpret_cast<uint4*>(ldsA + xdst[j] + 16) = hi;
+        *reinterpret_cast<uint4*>(ldsA + plane + xdst[j]) = hi;
       }
     }
 #pragma unroll
     for (int j = 0; j < kFragRounds; ++j) reinterpret_cast<v4i*>(ldsB)[wchunk[j]] = wr[j];
     __syncthreads();
     if (cw + 1 < Cw) fetch(cw + 1);
+    // operands of tap t + 1 are requested before the matrix instructions of tap t (the compiler
+    // moves the reads where its register budget allows; forcing the order with scheduling
+    // barriers cost 26 more registers and measured no faster)
+    v4i bq[2][2], aq[2][MT];
+    auto read_tap = [&](int tap, int buf) {
+      bq[buf][0] = *reinterpret_cast<const v4i*>(ldsB + ((tap * 2 + 0) * 64 + lane) * 16);
+      bq[buf][1] = *reinterpret_cast<const v4i*>(ldsB + ((tap * 2 + 1) * 64 + lane) * 16);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+        aq[buf][mt] = *reinterpret_cast<const v4i*>(ldsA + lds_pix[mt] + (tap / 3 - 1) * PW * kPitch + (tap % 3) * kPitch);
+    };
+    read_tap(0, 0);
 #pragma unroll
     for (int tap = 0; tap < 9; ++tap) {
-      const v4i b0 = *reinterpret_cast<const v4i*>(ldsB + ((tap * 2 + 0) * 64 + lane) * 16);
-      const v4i b1 = *reinterpret_cast<const v4i*>(ldsB + ((tap * 2 + 1) * 64 + lane) * 16);
-      const int toff = ((tap / 3 - 1) * PW + (tap % 3 - 1)) * kPitch;
+      if (tap + 1 < 9) read_tap(tap + 1, (tap + 1) & 1);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        const v4i av = *reinterpret_cast<const v4i*>(ldsA + lds_pix[mt] + toff);
-        acc[mt][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av, b0, acc[mt][0], 0, 0, 0);
-        acc[mt][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av, b1, acc[mt][1], 0, 0, 0);
+        acc[mt][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(aq[tap & 1][mt], bq[tap & 1][0], acc[mt][0], 0, 0, 0);
+        acc[mt][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(aq[tap & 1][mt], bq[tap & 1][1], acc[mt][1], 0, 0, 0);
       }
     }
   }
@@ -239,22 +262,36 @@ void launch_pack_weights_mfma(const int8_t* w, int8_t* bank, int64_t K, int64_t 
              (int)C, (int)(C / 32));
 }
 
+// Upper bound of the padded slots that a workgroup's pixels and their taps span: its pixels, one
+// slot per image row and one row of slots per image that it can touch, and a padded row + 1 on
+// either side.
+static int64_t slot_bound(int64_t H, int64_t W) {
+  constexpr int kWgPixels = 4 * kTilesPerWave * 32;
+  const int64_t rows_touched = (kWgPixels - 1) / W + 2, images_touched = (kWgPixels - 1) / (H * W) + 2;
+  return kWgPixels + rows_touched + images_touched * (W + 1) + 2 * (W + 2) + 1;
+}
+
+bool mfma_slots_fit(int64_t H, int64_t W) { return slot_bound(H, W) <= kMaxSlots; }
+
 bool launch_bconv_mfma(const MfmaArgs& a, hipStream_t stream) {
   const int64_t total = (int64_t)a.N * a.H * a.W;
-  constexpr int MT = 4;
+  constexpr int MT = kTilesPerWave;
   constexpr int kWgPixels = 4 * MT * 32;
-  // upper bound of the padded slots that a workgroup's pixels and their taps span: its pixels, one
-  // slot per image row and one row of slots per image that it can touch, and a padded row + 1 on
-  // either side
-  const int64_t rows_touched = (kWgPixels - 1) / a.W + 2, images_touched = (kWgPixels - 1) / ((int64_t)a.H * a.W) + 2;
-  const int64_t slot_bound = kWgPixels + rows_touched + images_touched * (a.W + 1) + 2 * (a.W + 2) + 1;
-  if (slot_bound > kMaxSlots) return false;                  // long rows or tiny images: another kernel
-  const size_t lds_bytes = (size_t)kFragBytes + (size_t)slot_bound * kPitch;
+  if (!mfma_slots_fit(a.H, a.W)) return false;               // long rows or tiny images: another kernel
+  const int64_t slot_bound = bnn::slot_bound(a.H, a.W);
+  // the two halves of the staged pixels (channels 0..15 and 16..31 of the word) lie in two planes
+  // an odd multiple of 128 bytes apart: the 16 lanes that the LDS serves per cycle then hit 16
+  // different bank groups whether they belong to one half or to both
+  const int plane = (int)((slot_bound * kPitch + 255) / 256 * 256 + 128);
+  const size_t lds_bytes = (size_t)kFragBytes + 2 * (size_t)plane;
   const int64_t fgroups = a.K / 64;
   const int64_t blocks = (total + kWgPixels - 1) / kWgPixels * fgroups;
   if (blocks > 0x7fffffffLL) return false;
   rtc::prof_begin(kProfileKind, stream);
-  RTC_LAUNCH(bconv_mfma_kernel<MT>, dim3((uint32_t)blocks), dim3(256), lds_bytes, stream, a, (int)fgroups);
+  if (a.Cw % 4 == 0 && reinterpret_cast<uintptr_t>(a.x) % 16 == 0)
+    RTC_LAUNCH((bconv_mfma_kernel<MT, 4>), dim3((uint32_t)blocks), dim3(256), lds_bytes, stream, a, (int)fgroups, plane);
+  else
+    RTC_LAUNCH((bconv_mfma_kernel<MT, 1>), dim3((uint32_t)blocks), dim3(256), lds_bytes, stream, a, (int)fgroups, plane);
   rtc::prof_end(stream);
   return true;
 }

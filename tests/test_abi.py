@@ -130,6 +130,20 @@ def test_bnn_entry_points_reject_bad_arguments(lib):
     # a matrix-core shape carries the filters once more as int8 (K 9 C bytes)
     assert lib.bnn_weight_words(64, 3, 3, 128) == 9 * 4 * 64 + 9 * 64 + 64 * 9 * 128 // 4
     assert lib.bnn_weight_words(64, 3, 3, 96) == 9 * 3 * 64 + 9 * 64
+    # the planner's choice of the matrix-core kernel: shape rules, the size threshold, the knob
+    lib.bnn_matrix_path_applies.argtypes = [i64] * 9
+    assert lib.bnn_matrix_path_applies(256, 13, 13, 1024, 1024, 3, 3, 1, 1) == 1
+    assert lib.bnn_matrix_path_applies(1, 13, 13, 1024, 1024, 3, 3, 1, 1) == 0        # too few pixels to fill the chip
+    assert lib.bnn_matrix_path_applies(256, 13, 13, 1024, 1000, 3, 3, 1, 1) == 0      # K not a multiple of 64
+    assert lib.bnn_matrix_path_applies(256, 13, 13, 64, 1024, 3, 3, 1, 1) == 0        # too few channels
+    assert lib.bnn_matrix_path_applies(256, 13, 13, 1024, 1024, 3, 3, 2, 1) == 0      # stride 2
+    assert lib.bnn_matrix_path_applies(64, 8, 300, 128, 64, 3, 3, 1, 1) == 0          # rows too long for the staged range
+    assert lib.bnn_set_matrix_path(1) == 0
+    assert lib.bnn_matrix_path_applies(1, 13, 13, 1024, 1024, 3, 3, 1, 1) == 1
+    assert lib.bnn_set_matrix_path(-1) == 0
+    assert lib.bnn_matrix_path_applies(256, 13, 13, 1024, 1024, 3, 3, 1, 1) == 0
+    assert lib.bnn_set_matrix_path(2) < 0
+    assert lib.bnn_set_matrix_path(0) == 0
     lib.bnn_pack_weights.argtypes = [ctypes.c_void_p, ctypes.c_void_p, i64, i64, i64, i64, ctypes.c_void_p]
     assert lib.bnn_pack_weights(p, None, 8, 3, 3, 32, None) == -1
     assert lib.bnn_pack_weights(p, p, 8, 3, 0, 32, None) == -2
