@@ -953,7 +953,7 @@ def main():
                   rtc.RTC_PROFILE_KIND(1, 0, 1): "tropical_kernel<int64, max-plus>",
                   rtc.RTC_PROFILE_KIND(2, 0, 0): "tropical_kernel<fp64, min-plus>",
                   rtc.RTC_PROFILE_KIND(2, 0, 1): "tropical_kernel<fp64, max-plus>",
-                  rtc.RTC_PROFILE_KIND_TAIL: "gpc_tail_kernel"}
+                  rtc.RTC_PROFILE_KIND_TAIL: "residual_service_kernel"}
     per_kind = {}
     for kind, ms in kernel_times:
         per_kind.setdefault(kind_names.get(kind, str(kind)), []).append(ms)
@@ -1020,7 +1020,7 @@ def main():
         hbm["ops"].append(hbm_entry("max_deviations (hdev + vdev in one pass)",
                                     lambda: rtc.rtc_max_deviations(f, g, out_h=hv, out_v=vdev, dev_flags=flags),
                                     B * N * 2 * w + (4 + w) * B, copy_gbs))
-        tail = sorted(per_kind.get("gpc_tail_kernel", []))
+        tail = sorted(per_kind.get("residual_service_kernel", []))
         if tail:
             t_ms, nb = tail[len(tail) // 2], B * N * (4 * w + 8)
             gbs = nb / (t_ms * 1e-3) / 1e9

@@ -765,8 +765,8 @@ bool launch_resident_half(const ConvArgs& a, int R, int S, int tm, uint32_t bloc
 
 // Output pixels per wave: the candidate that leaves the fewest idle slots in an output row of
 // Wo pixels (ties: the wider tile).
-int g_force_tm = 0, g_force_kb = 0;   // planner overrides, see bnn_set_planner
-int g_matrix_path = 0;                // see bnn_set_matrix_path
+std::atomic<int> g_force_tm{0}, g_force_kb{0};   // planner overrides, see bnn_set_planner
+std::atomic<int> g_matrix_path{0};        // see bnn_set_matrix_path
 
 int pick_tm(int64_t Wo, bool allow13) {
   if (g_force_tm == 7 || g_force_tm == 8 || (g_force_tm == 13 && allow13)) return g_force_tm;

@@ -75,114 +75,202 @@ __device__ __forceinline__ int wave_first_true(int n, Pred pred) {
   return lo;
 }
 
-// Number of samples of fr[0, n) not beyond each of the calling workgroup's (256 threads)
-// queries xv[0 .. kSearchPerThread), in cnt[]: for every thread, whether its queries are real
-// or repeats of a real one.  s_win: kSearchWindow values of LDS.
-template <typename T>
-__device__ __forceinline__ void windowed_counts(const T* __restrict__ fr, int n, const T (&xv)[kSearchPerThread],
-                                                bool upper, T* s_win, int (&cnt)[kSearchPerThread]) {
-  __shared__ T s_mm[2][4];
-  __shared__ int s_ab[2];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  T xmin = xv[0], xmax = xv[0];
+// Stages fr[a, a + len) into s_win (len <= WINDOW, uniform) with every load of a thread in flight
+// before the first one is waited for.  A loop of "load, store to LDS" is compiled into one round
+// trip per iteration: the store waits for its own load.  The barrier in the instruction stream
+// between the two phases keeps the compiler from sinking the loads back into the stores' blocks.
+template <typename T, int THREADS, int WINDOW>
+__device__ __forceinline__ void stage_window(const T* __restrict__ fr, int a, int len, T* s_win) {
+  constexpr int K = (WINDOW + THREADS - 1) / THREADS;
+  T tmp[K];
 #pragma unroll
-  for (int e = 1; e < kSearchPerThread; ++e) { xmin = xv[e] < xmin ? xv[e] : xmin; xmax = vmax(xmax, xv[e]); }
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) {
-    const T a = __shfl_xor(xmin, off), b = __shfl_xor(xmax, off);
-    xmin = a < xmin ? a : xmin; xmax = vmax(xmax, b);
-  }
-  if (lane == 0) { s_mm[0][wave] = xmin; s_mm[1][wave] = xmax; }
-  __syncthreads();
-#pragma unroll
-  for (int w = 0; w < 4; ++w) { xmin = s_mm[0][w] < xmin ? s_mm[0][w] : xmin; xmax = vmax(xmax, s_mm[1][w]); }
-  if (wave < 2) {
-    const T q = wave == 0 ? xmin : xmax;
-    const int at = wave_first_true(n, [&](int k) { return beyond(fr[k], q, upper); });
-    if (lane == 0) s_ab[wave] = at;
-  }
-  __syncthreads();
-  const int a = s_ab[0], len = s_ab[1] - a;
-  if (len >= 0 && len <= kSearchWindow) {
-#pragma unroll 4
-    for (int i = threadIdx.x; i < len; i += 256) s_win[i] = fr[a + i];
-    __syncthreads();
-#pragma unroll
-    for (int e = 0; e < kSearchPerThread; ++e) {
-      int lo = 0, hi = len;
-      while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (beyond(s_win[mid], xv[e], upper)) hi = mid; else lo = mid + 1;
-      }
-      cnt[e] = a + lo;
+  for (int k = 0; k < K; ++k) {
+    if (k * THREADS < len) {                   // (uniform)
+      const int i = k * THREADS + (int)threadIdx.x;
+      tmp[k] = fr[a + (i < len ? i : len - 1)];
     }
-  } else {
+  }
+  asm volatile("" ::: "memory");
 #pragma unroll
-    for (int e = 0; e < kSearchPerThread; ++e) cnt[e] = upper ? upper_index(fr, n, xv[e]) + 1 : lower_index(fr, n, xv[e]);
+  for (int k = 0; k < K; ++k) {
+    const int i = k * THREADS + (int)threadIdx.x;
+    if (i < len) s_win[i] = tmp[k];
   }
 }
 
-// Both pseudo-inverses of a workgroup's queries from ONE staged window: with a = the number of
-// samples below the smallest query and b = the number of samples not above the largest one, the
-// stretch fr[a, b) holds every sample that lies inside the queries' range, so for each query
-//   lower count (samples <  x) = a + (samples of the window <  x)
-//   upper count (samples <= x) = a + (samples of the window <= x).
-// THREADS threads (a multiple of 64, at most 1024), PER queries per thread, WINDOW samples of LDS
-// in s_win; a longer stretch falls back to the plain searches per thread.
-template <typename T, int THREADS, int PER, int WINDOW>
-__device__ __forceinline__ void windowed_counts_both(const T* __restrict__ fr, int n, const T (&xv)[PER], T* s_win,
-                                                     int (&cnt_lo)[PER], int (&cnt_up)[PER]) {
-  constexpr int NW = THREADS / 64;
-  __shared__ T s_mm[2][NW];
-  __shared__ int s_ab[2];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  T xmin = xv[0], xmax = xv[0];
+// ---- searching the staged window ---------------------------------------------------------------
+// A binary search per query over the whole window costs log2(len) dependent LDS reads for each
+// kind of count.  The queries of a wavefront are neighbours (consecutive samples of a curve), so
+// their answers lie close together; when both kinds of count are asked for,
+//   * the wavefront brackets them with two 64-ary searches for its smallest and largest query
+//     (each lane probes one position per round: two rounds for up to 4096 samples);
+//   * a thread brackets its own queries inside that, by its smallest and largest one;
+//   * each query is then searched in the thread's bracket, a handful of samples.
+// Nothing here assumes that the queries are sorted: the brackets come from minima and maxima.
+// first index in [lo, hi) whose sample is > x (GT) or >= x; hi if there is none
+template <typename T, bool GT>
+__device__ __forceinline__ int first_beyond(const T* s_win, int lo, int hi, T x) {
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    const T w = s_win[mid];
+    if (GT ? w > x : w >= x) hi = mid; else lo = mid + 1;
+  }
+  return lo;
+}
+
+// the same for a wave-uniform x and a wave-uniform range, by all 64 lanes together
+template <typename T, bool GT>
+__device__ __forceinline__ int wave_first_beyond(const T* s_win, int lo, int hi, T x) {
+  return lo + wave_first_true(hi - lo, [&](int k) { const T w = s_win[lo + k]; return GT ? w > x : w >= x; });
+}
+
+// Counts of the window's samples below (c_lo; MODE 0 and 2) and not above (c_up; MODE 1 and 2)
+// each query; wmin / wmax: smallest and largest query of the calling wavefront (wave-uniform).
+template <typename T, int PER, int MODE>
+__device__ __forceinline__ void search_window(const T* s_win, int len, const T (&xv)[PER], T wmin, T wmax,
+                                              int (&c_lo)[PER], int (&c_up)[PER]) {
+  if constexpr (MODE != 2) {
+    // one kind of count: the brackets cost about what they save (measured on rows of 16384 and
+    // 65536 samples, 4- and 8-byte values); with both kinds they pay
 #pragma unroll
-  for (int e = 1; e < PER; ++e) { xmin = xv[e] < xmin ? xv[e] : xmin; xmax = vmax(xmax, xv[e]); }
+    for (int e = 0; e < PER; ++e) {
+      if (MODE == 0) c_lo[e] = first_beyond<T, false>(s_win, 0, len, xv[e]);
+      else c_up[e] = first_beyond<T, true>(s_win, 0, len, xv[e]);
+    }
+    return;
+  }
+  constexpr bool kLowGT = false;         // the lower end of a bracket counts like the lower count (samples < x),
+  constexpr bool kHighGT = true;         // the upper end like the upper one (samples <= x)
+  const int L = wave_first_beyond<T, kLowGT>(s_win, 0, len, wmin);
+  const int H = wave_first_beyond<T, kHighGT>(s_win, L, len, wmax);
+  T tmin = xv[0], tmax = xv[0];
+#pragma unroll
+  for (int e = 1; e < PER; ++e) { tmin = xv[e] < tmin ? xv[e] : tmin; tmax = vmax(tmax, xv[e]); }
+  const int Lt = first_beyond<T, kLowGT>(s_win, L, H, tmin);
+  const int Ht = first_beyond<T, kHighGT>(s_win, Lt, H, tmax);
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    if (MODE == 0) c_lo[e] = first_beyond<T, false>(s_win, Lt, Ht, xv[e]);
+    if (MODE == 1) c_up[e] = first_beyond<T, true>(s_win, Lt, Ht, xv[e]);
+    if (MODE == 2) {
+      c_lo[e] = first_beyond<T, false>(s_win, Lt, Ht, xv[e]);
+      c_up[e] = first_beyond<T, true>(s_win, c_lo[e], Ht, xv[e]);
+    }
+  }
+}
+
+// Smallest and largest query of the calling wavefront (in all its lanes) and, through s_mm and one
+// barrier, of the workgroup.
+template <typename T, int THREADS, int PER>
+__device__ __forceinline__ void query_range(const T (&xv)[PER], T (*s_mm)[THREADS / 64], T& wmin, T& wmax, T& xmin, T& xmax) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  wmin = xv[0]; wmax = xv[0];
+#pragma unroll
+  for (int e = 1; e < PER; ++e) { wmin = xv[e] < wmin ? xv[e] : wmin; wmax = vmax(wmax, xv[e]); }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) {
-    const T a = __shfl_xor(xmin, off), b = __shfl_xor(xmax, off);
-    xmin = a < xmin ? a : xmin; xmax = vmax(xmax, b);
+    const T a = __shfl_xor(wmin, off), b = __shfl_xor(wmax, off);
+    wmin = a < wmin ? a : wmin; wmax = vmax(wmax, b);
   }
-  if (lane == 0) { s_mm[0][wave] = xmin; s_mm[1][wave] = xmax; }
+  if (lane == 0) { s_mm[0][wave] = wmin; s_mm[1][wave] = wmax; }
   __syncthreads();
+  xmin = wmin; xmax = wmax;
 #pragma unroll
-  for (int w = 0; w < NW; ++w) { xmin = s_mm[0][w] < xmin ? s_mm[0][w] : xmin; xmax = vmax(xmax, s_mm[1][w]); }
+  for (int w = 0; w < THREADS / 64; ++w) { xmin = s_mm[0][w] < xmin ? s_mm[0][w] : xmin; xmax = vmax(xmax, s_mm[1][w]); }
+}
+
+// Counts of the samples of fr[0, n) below (cnt_lo; MODE 0 and 2) and not above (cnt_up; MODE 1 and
+// 2) each of the calling workgroup's queries xv[], for every thread, whether its queries are real
+// or repeats of a real one.  With a = the number of samples below the smallest query (not above
+// it, when only the upper counts are asked for) and b = the number of samples not above the
+// largest one (below it, when only the lower counts are), the stretch fr[a, b) holds every sample
+// the counts depend on: count = a + (count inside the stretch).  Two wavefronts find a and b in
+// three round trips each; a stretch longer than WINDOW (queries that are not clustered) falls back
+// to the plain search per thread.  THREADS threads (a multiple of 64, at least 128), PER queries
+// per thread; s_win: WINDOW values of LDS.  Ends with a barrier: the arrays may be reused at once.
+template <typename T, int THREADS, int PER, int WINDOW, int MODE>
+__device__ __forceinline__ void exact_windowed_counts(const T* __restrict__ fr, int n, const T (&xv)[PER], T* s_win,
+                                                      int (&cnt_lo)[PER], int (&cnt_up)[PER]) {
+  __shared__ T s_mm[2][THREADS / 64];
+  __shared__ int s_ab[2];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  T wmin, wmax, xmin, xmax;
+  query_range<T, THREADS, PER>(xv, s_mm, wmin, wmax, xmin, xmax);
   if (wave < 2) {
     const T q = wave == 0 ? xmin : xmax;
-    const bool upper = wave == 1;
+    const bool upper = wave == 0 ? MODE == 1 : MODE != 0;
     const int at = wave_first_true(n, [&](int k) { return beyond(fr[k], q, upper); });
     if (lane == 0) s_ab[wave] = at;
   }
   __syncthreads();
   const int a = s_ab[0], len = s_ab[1] - a;
-  if (len >= 0 && len <= WINDOW) {
-#pragma unroll 4
-    for (int i = threadIdx.x; i < len; i += THREADS) s_win[i] = fr[a + i];
+  if (len <= WINDOW) {                         // (uniform; len >= 0: the predicates are nested)
+    stage_window<T, THREADS, WINDOW>(fr, a, len, s_win);
     __syncthreads();
+    search_window<T, PER, MODE>(s_win, len, xv, wmin, wmax, cnt_lo, cnt_up);
 #pragma unroll
-    for (int e = 0; e < PER; ++e) {
-      int lo = 0, hi = len;
-      while (lo < hi) {                       // samples < x
-        const int mid = (lo + hi) >> 1;
-        if (s_win[mid] >= xv[e]) hi = mid; else lo = mid + 1;
-      }
-      cnt_lo[e] = a + lo;
-      hi = len;                               // samples <= x: from the first one >= x on
-      while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (s_win[mid] > xv[e]) hi = mid; else lo = mid + 1;
-      }
-      cnt_up[e] = a + lo;
-    }
+    for (int e = 0; e < PER; ++e) { cnt_lo[e] += a; cnt_up[e] += a; }
   } else {
 #pragma unroll
     for (int e = 0; e < PER; ++e) {
-      cnt_lo[e] = lower_index(fr, n, xv[e]);
-      cnt_up[e] = upper_index(fr, n, xv[e]) + 1;
+      if (MODE != 1) cnt_lo[e] = lower_index(fr, n, xv[e]);
+      if (MODE != 0) cnt_up[e] = upper_index(fr, n, xv[e]) + 1;
     }
   }
-  __syncthreads();   // s_win and the small arrays may be reused by the caller's next pass
+  __syncthreads();
+}
+
+// ---- the same, with the window located in ONE round trip ------------------------------------
+// The 64-ary searches above cost three dependent round trips before the window can be staged.
+// Instead every thread fetches one sample of a coarse table of the row, the last sample of each of
+// THREADS granules of G = ceil(n / THREADS) samples -- positions that do not depend on the queries,
+// so the loads travel together with the loads of the queries themselves (and hit in L2: every
+// workgroup of a row asks for the same ones; a caller that has the table as one contiguous piece
+// passes its entry instead).  With glo = the first granule whose last sample is >= the smallest
+// query (> it, for the upper counts alone) and ghi = the first granule whose last sample is > the
+// largest query (>= it, for the lower counts alone), every sample before granule glo lies below
+// all queries and every sample after granule ghi beyond all of them, so the stretch
+// [glo G, (ghi + 1) G) holds all that the counts depend on: at most two granules more than the
+// exact stretch.  A stretch longer than the window falls back to the exact searches.
+template <int THREADS> __device__ __forceinline__ int coarse_granule(int n) { return (n + THREADS - 1) / THREADS; }
+
+// Position in the row of entry e of its coarse table.
+template <int THREADS> __device__ __forceinline__ int coarse_position(int n, int e) {
+  const int64_t at = (int64_t)(e + 1) * coarse_granule<THREADS>(n);
+  return (at < n ? (int)at : n) - 1;
+}
+
+// s_coarse: THREADS values of LDS.  Ends with a barrier.
+template <typename T, int THREADS, int PER, int WINDOW, int MODE>
+__device__ __forceinline__ void coarse_windowed_counts(const T* __restrict__ fr, int n, const T (&xv)[PER], T coarse,
+                                                       T* s_win, T* s_coarse, int (&cnt_lo)[PER], int (&cnt_up)[PER]) {
+  constexpr int NW = THREADS / 64;
+  __shared__ T s_mm[2][NW];
+  const int lane = threadIdx.x & 63;
+  s_coarse[threadIdx.x] = coarse;
+  T wmin, wmax, xmin, xmax;
+  query_range<T, THREADS, PER>(xv, s_mm, wmin, wmax, xmin, xmax);      // (its barrier also covers s_coarse)
+  // the table is nondecreasing: the first granule beyond a query is the number of granules that are not
+  int glo = 0, ghi = 0;
+#pragma unroll
+  for (int e = 0; e < NW; ++e) {
+    const T c = s_coarse[e * 64 + lane];
+    glo += __builtin_popcountll(__ballot(MODE == 1 ? !(c > xmin) : !(c >= xmin)));
+    ghi += __builtin_popcountll(__ballot(MODE == 0 ? !(c >= xmax) : !(c > xmax)));
+  }
+  const int G = coarse_granule<THREADS>(n);
+  const int64_t a64 = (int64_t)glo * G, b64 = (int64_t)(ghi + 1) * G;
+  const int a = a64 < n ? (int)a64 : n, len = (b64 < n ? (int)b64 : n) - a;
+  if (len <= WINDOW) {                         // (uniform; len >= 0 because ghi >= glo)
+    stage_window<T, THREADS, WINDOW>(fr, a, len, s_win);
+    __syncthreads();
+    search_window<T, PER, MODE>(s_win, len, xv, wmin, wmax, cnt_lo, cnt_up);
+#pragma unroll
+    for (int e = 0; e < PER; ++e) { cnt_lo[e] += a; cnt_up[e] += a; }
+    __syncthreads();
+  } else {
+    exact_windowed_counts<T, THREADS, PER, WINDOW, MODE>(fr, n, xv, s_win, cnt_lo, cnt_up);
+  }
 }
 
 template <typename T>
@@ -192,19 +280,19 @@ __global__ __launch_bounds__(256) void pinv_kernel(const T* __restrict__ f, int 
                                                    int mode) {
   __shared__ T s_win[kSearchWindow];
   const int row = blockIdx.x / blocks_per_row;
-  const int base = (blockIdx.x % blocks_per_row) * kSearchPerBlock;
+  const int base = (blockIdx.x % blocks_per_row) * kSearchPerBlock + (int)threadIdx.x;
   const T* fr = f + (int64_t)row * n;
   const bool upper = mode != RTC_INV_LOWER;
   T xv[kSearchPerThread];
 #pragma unroll
   for (int e = 0; e < kSearchPerThread; ++e)      // past the end: the last query again
-    xv[e] = x[(int64_t)row * m + min(base + e * 256 + (int)threadIdx.x, m - 1)];
-  int cnt[kSearchPerThread];
-  windowed_counts(fr, n, xv, upper, s_win, cnt);
+    xv[e] = x[(int64_t)row * m + min(base + e * 256, m - 1)];
+  int cnt[kSearchPerThread], unused[kSearchPerThread];
+  if (upper) exact_windowed_counts<T, 256, kSearchPerThread, kSearchWindow, 1>(fr, n, xv, s_win, unused, cnt);
+  else exact_windowed_counts<T, 256, kSearchPerThread, kSearchWindow, 0>(fr, n, xv, s_win, cnt, unused);
 #pragma unroll
   for (int e = 0; e < kSearchPerThread; ++e) {
-    const int j = base + e * 256 + threadIdx.x;
-    if (j < m) out[(int64_t)row * m + j] = upper ? cnt[e] - 1 : cnt[e];
+    if (base + e * 256 < m) out[(int64_t)row * m + base + e * 256] = upper ? cnt[e] - 1 : cnt[e];
   }
 }
 
@@ -276,17 +364,86 @@ __device__ __forceinline__ T wave_scan(T v) {
 // Remaining service of a greedy processing component:
 //   SUFFIX = false: out[D] = max(0, max_{l<=D} beta[l] - alpha[l])   (beta^l, alpha^u -> beta'^l)
 //   SUFFIX = true : out[D] = max(0, min_{l>=D} beta[l] - alpha[l])   (beta^u, alpha^l -> beta'^u)
-// `parts` workgroups per row (few rows would otherwise leave most CUs idle): each scans one segment
-// of the row in scan order, after reducing everything before its segment itself (maximum and
-// minimum are exact and order-free, so the extra reads cost time only, and no workgroup waits for
-// another).  seg = segment length, a multiple of the 4096 positions one pass covers.
+// and, with EVENTS, the event-domain images of the values while they are still in registers:
+//   ev_lo / ev_up (each optional) = lower / upper pseudo-inverse of gamma at out[D].
+// A row is cut into `parts` segments of seg positions (in scan order; seg a multiple of the
+// kScanPass positions one pass covers), one workgroup each.  What a segment needs from the ones
+// before it is one number, the maximum (minimum) of their differences: segment_extrema_kernel
+// reduces every segment but the last of each row first (a second read of the operands; no
+// workgroup ever waits for another), and a scanning workgroup folds the totals before its own
+// segment into its carry.  The values of a pass are monotone in scan order, so their answers fall
+// into one stretch of gamma, which is staged once for both inverses.
+constexpr int kScanThreads = 256;
+constexpr int kScanPer = 4;                                  // consecutive positions per thread
+constexpr int kScanPass = kScanThreads * kScanPer;           // positions per pass
+constexpr int kExtremaPerThread = 8;
+constexpr int kExtremaTrip = 256 * kExtremaPerThread;
+
+// With gamma, the row's workgroups also gather the coarse table of gamma (see coarse_windowed_counts:
+// kScanThreads samples, fetched here once per row so that the scanning workgroups read them as one
+// contiguous piece) into coarse_tab[row][kScanThreads].
 template <typename T, bool SUFFIX>
-__global__ __launch_bounds__(1024) void residual_service_kernel(const T* __restrict__ beta,
-                                                                const T* __restrict__ alpha,
-                                                                T* __restrict__ out, int n, int parts, int seg) {
+__global__ __launch_bounds__(256) void segment_extrema_kernel(const T* __restrict__ beta, const T* __restrict__ alpha,
+                                                              T* __restrict__ seg_tot, int n, int parts, int seg,
+                                                              const T* __restrict__ gamma, int n_gamma,
+                                                              T* __restrict__ coarse_tab) {
   using S = ScanOp<T, SUFFIX>;
-  constexpr int kPer = 4;
-  __shared__ T wave_tot[16];
+  __shared__ T red[4];
+  const int row = blockIdx.x / (parts - 1), part = blockIdx.x % (parts - 1);
+  if (gamma != nullptr) {
+    const T* gr = gamma + (int64_t)row * n_gamma;
+    for (int e = part * 256 + threadIdx.x; e < kScanThreads; e += (parts - 1) * 256)
+      coarse_tab[(int64_t)row * kScanThreads + e] = gr[coarse_position<kScanThreads>(n_gamma, e)];
+  }
+  const int start = part * seg;                      // < n: the launcher's parts are all non-empty
+  const int last = min(n, start + seg) - 1;
+  const T* bl = beta + (int64_t)row * n;
+  const T* au = alpha + (int64_t)row * n;
+  T acc = S::id();
+  for (int base = start + threadIdx.x; base <= last; base += kExtremaTrip) {
+    T bv[kExtremaPerThread], av[kExtremaPerThread];
+#pragma unroll
+    for (int e = 0; e < kExtremaPerThread; ++e) {    // past the end: the last position again
+      const int p = min(base + e * 256, last);
+      const int i = SUFFIX ? n - 1 - p : p;
+      bv[e] = bl[i];
+      av[e] = au[i];
+    }
+#pragma unroll
+    for (int e = 0; e < kExtremaPerThread; ++e) acc = S::op(acc, (T)(bv[e] - av[e]));
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) acc = S::op(acc, __shfl_xor(acc, off));
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) seg_tot[(int64_t)row * parts + part] = S::op(S::op(red[0], red[1]), S::op(red[2], red[3]));
+}
+
+// Carry into segment `part` of a row: the totals of the segments before it, reduced by every
+// wavefront for itself (no barrier; a handful of values unless the row has millions of samples).
+template <typename T, bool SUFFIX>
+__device__ __forceinline__ T carry_before(const T* __restrict__ seg_tot, int row, int parts, int part) {
+  using S = ScanOp<T, SUFFIX>;
+  T acc = S::id();
+  const T* tot = seg_tot + (int64_t)row * parts;
+  for (int j = threadIdx.x & 63; j < part; j += 64) acc = S::op(acc, tot[j]);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) acc = S::op(acc, __shfl_xor(acc, off));
+  return acc;
+}
+
+template <typename T, bool SUFFIX, bool EVENTS>
+__global__ __launch_bounds__(kScanThreads) void residual_service_kernel(const T* __restrict__ beta, const T* __restrict__ alpha,
+                                                                        T* __restrict__ out, int n, int parts, int seg,
+                                                                        const T* __restrict__ seg_tot,
+                                                                        const T* __restrict__ gamma, int n_gamma,
+                                                                        int32_t* __restrict__ ev_lo, int32_t* __restrict__ ev_up,
+                                                                        const T* __restrict__ coarse_tab) {
+  using S = ScanOp<T, SUFFIX>;
+  constexpr int NW = kScanThreads / 64;
+  __shared__ T s_win[EVENTS ? kSearchWindow : 1];
+  __shared__ T s_coarse[EVENTS ? kScanThreads : 1];
+  __shared__ T wave_tot[NW];
   __shared__ T carry_s;
   const int row = blockIdx.x / parts, part = blockIdx.x % parts;
   const int start = part * seg;
@@ -296,44 +453,46 @@ __global__ __launch_bounds__(1024) void residual_service_kernel(const T* __restr
   const T* au = alpha + (int64_t)row * n;
   T* o = out + (int64_t)row * n;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  T carry = S::id();
-  if (start > 0) {
-    // everything before the segment; the loads of eight passes are independent and in flight together
-    T acc = S::id();
-#pragma unroll 8
-    for (int p = threadIdx.x; p < start; p += 1024) {
+  // The differences of one pass, loaded one pass ahead of their use.  Every load is issued
+  // whatever the position (one past the row's end reads the last sample), so that all loads of
+  // a pass travel together: a load under its own condition is waited for on the spot.
+  auto load = [&](int base, T (&d)[kScanPer]) {
+    T bv[kScanPer], av[kScanPer];
+#pragma unroll
+    for (int e = 0; e < kScanPer; ++e) {
+      const int p = min(base + (int)threadIdx.x * kScanPer + e, n - 1);
       const int i = SUFFIX ? n - 1 - p : p;
-      acc = S::op(acc, (T)(bl[i] - au[i]));
+      bv[e] = bl[i];
+      av[e] = au[i];
     }
-    const T incl = wave_scan<T, SUFFIX>(acc);
-    if (lane == 63) wave_tot[wave] = incl;
-    __syncthreads();
 #pragma unroll
-    for (int w = 0; w < 16; ++w) carry = S::op(carry, wave_tot[w]);
-    __syncthreads();
-  }
-  // the differences of one pass, loaded one pass ahead of their use
-  auto load = [&](int base, T (&d)[kPer]) {
-#pragma unroll
-    for (int e = 0; e < kPer; ++e) {
-      const int p = base + threadIdx.x * kPer + e;
-      const int i = SUFFIX ? n - 1 - p : p;
+    for (int e = 0; e < kScanPer; ++e) {
       // the difference may be negative; inputs obey the no-overflow precondition
-      d[e] = p < n ? (T)(bl[i] - au[i]) : S::id();
+      d[e] = base + (int)threadIdx.x * kScanPer + e < n ? (T)(bv[e] - av[e]) : S::id();
     }
   };
-  T next[kPer];
+  T next[kScanPer];
   load(start, next);
-  for (int base = start; base < end; base += 1024 * kPer) {
-    const int p0 = base + threadIdx.x * kPer;   // position in scan order
-    T v[kPer];
+  // the thread's entry of the row's coarse table of gamma (the same for every pass): from the table
+  // that segment_extrema_kernel has gathered, else from the row itself
+  T coarse = (T)0;
+  const T* gr = nullptr;
+  if constexpr (EVENTS) {
+    gr = gamma + (int64_t)row * n_gamma;
+    coarse = coarse_tab != nullptr ? coarse_tab[(int64_t)row * kScanThreads + threadIdx.x]
+                                   : gr[coarse_position<kScanThreads>(n_gamma, threadIdx.x)];
+  }
+  T carry = part > 0 ? carry_before<T, SUFFIX>(seg_tot, row, parts, part) : S::id();
+  for (int base = start; base < end; base += kScanPass) {
+    const int p0 = base + threadIdx.x * kScanPer;   // position in scan order
+    T v[kScanPer];
     T run = S::id();
 #pragma unroll
-    for (int e = 0; e < kPer; ++e) {
+    for (int e = 0; e < kScanPer; ++e) {
       run = S::op(run, next[e]);
       v[e] = run;
     }
-    if (base + 1024 * kPer < end) load(base + 1024 * kPer, next);
+    if (base + kScanPass < end) load(base + kScanPass, next);
     const T incl = wave_scan<T, SUFFIX>(run);
     if (lane == 63) wave_tot[wave] = incl;
     __syncthreads();
@@ -343,111 +502,32 @@ __global__ __launch_bounds__(1024) void residual_service_kernel(const T* __restr
     T prev = __shfl_up(incl, 1);
     if (lane == 0) prev = S::id();
     before = S::op(before, prev);
-#pragma unroll
-    for (int e = 0; e < kPer; ++e) {
-      const int p = p0 + e;
-      if (p < n) {
-        const T r = S::op(before, v[e]);
-        o[SUFFIX ? n - 1 - p : p] = r > (T)0 ? r : (T)0;
-      }
-    }
-    if (threadIdx.x == 1023) carry_s = S::op(before, run);
-    __syncthreads();
-    carry = carry_s;
-  }
-}
-
-// The tail of a greedy processing component in one kernel: the remaining service as in
-// residual_service_kernel, and the event-domain images of the values while they are still in
-// registers -- ev_lo / ev_up (each optional) = lower / upper pseudo-inverse of gamma at out[D].
-// The values of a pass are monotone in scan order, so their answers fall into one stretch of
-// gamma, which windowed_counts_both stages once for both inverses: gamma and out are read resp.
-// written once instead of twice and three times.
-template <typename T> constexpr int tail_window() { return sizeof(T) == 8 ? 6144 : 8192; }
-
-template <typename T, bool SUFFIX>
-__global__ __launch_bounds__(1024) void gpc_tail_kernel(const T* __restrict__ beta, const T* __restrict__ alpha,
-                                                        T* __restrict__ out, int n, int parts, int seg,
-                                                        const T* __restrict__ gamma, int n_gamma,
-                                                        int32_t* __restrict__ ev_lo, int32_t* __restrict__ ev_up) {
-  using S = ScanOp<T, SUFFIX>;
-  constexpr int kPer = 4;
-  __shared__ T s_win[tail_window<T>()];
-  __shared__ T wave_tot[16];
-  __shared__ T carry_s;
-  const int row = blockIdx.x / parts, part = blockIdx.x % parts;
-  const int start = part * seg;
-  if (start >= n) return;
-  const int end = min(n, start + seg);
-  const T* bl = beta + (int64_t)row * n;
-  const T* au = alpha + (int64_t)row * n;
-  const T* gr = gamma + (int64_t)row * n_gamma;
-  T* o = out + (int64_t)row * n;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  T carry = S::id();
-  if (start > 0) {
-    T acc = S::id();
-#pragma unroll 8
-    for (int p = threadIdx.x; p < start; p += 1024) {
-      const int i = SUFFIX ? n - 1 - p : p;
-      acc = S::op(acc, (T)(bl[i] - au[i]));
-    }
-    const T incl = wave_scan<T, SUFFIX>(acc);
-    if (lane == 63) wave_tot[wave] = incl;
-    __syncthreads();
-#pragma unroll
-    for (int w = 0; w < 16; ++w) carry = S::op(carry, wave_tot[w]);
-    __syncthreads();
-  }
-  auto load = [&](int base, T (&d)[kPer]) {
-#pragma unroll
-    for (int e = 0; e < kPer; ++e) {
-      const int p = base + threadIdx.x * kPer + e;
-      const int i = SUFFIX ? n - 1 - p : p;
-      d[e] = p < n ? (T)(bl[i] - au[i]) : S::id();
-    }
-  };
-  T next[kPer];
-  load(start, next);
-  for (int base = start; base < end; base += 1024 * kPer) {
-    const int p0 = base + threadIdx.x * kPer;   // position in scan order
-    T v[kPer];
-    T run = S::id();
-#pragma unroll
-    for (int e = 0; e < kPer; ++e) {
-      run = S::op(run, next[e]);
-      v[e] = run;
-    }
-    if (base + 1024 * kPer < end) load(base + 1024 * kPer, next);
-    const T incl = wave_scan<T, SUFFIX>(run);
-    if (lane == 63) wave_tot[wave] = incl;
-    __syncthreads();
-    T before = carry;
-    for (int w = 0; w < wave; ++w) before = S::op(before, wave_tot[w]);
-    T prev = __shfl_up(incl, 1);
-    if (lane == 0) prev = S::id();
-    before = S::op(before, prev);
     // a position past the row's end repeats the value before it (its difference is the scan's
     // identity), i.e. a real query, which is what the windowed search asks for
-    T q[kPer];
+    T q[kScanPer];
 #pragma unroll
-    for (int e = 0; e < kPer; ++e) {
+    for (int e = 0; e < kScanPer; ++e) {
       const T r = S::op(before, v[e]);
       q[e] = r > (T)0 ? r : (T)0;
       const int p = p0 + e;
       if (p < n) o[SUFFIX ? n - 1 - p : p] = q[e];
     }
-    if (threadIdx.x == 1023) carry_s = S::op(before, run);
-    int cnt_lo[kPer], cnt_up[kPer];
-    windowed_counts_both<T, 1024, kPer, tail_window<T>()>(gr, n_gamma, q, s_win, cnt_lo, cnt_up);   // (has barriers)
+    if (threadIdx.x == kScanThreads - 1) carry_s = S::op(before, run);
+    if constexpr (EVENTS) {
+      int cnt_lo[kScanPer], cnt_up[kScanPer];
+      coarse_windowed_counts<T, kScanThreads, kScanPer, kSearchWindow, 2>(gr, n_gamma, q, coarse, s_win, s_coarse, cnt_lo,
+                                                                           cnt_up);   // (has barriers)
 #pragma unroll
-    for (int e = 0; e < kPer; ++e) {
-      const int p = p0 + e;
-      if (p < n) {
-        const int64_t at = (int64_t)row * n + (SUFFIX ? n - 1 - p : p);
-        if (ev_lo != nullptr) ev_lo[at] = cnt_lo[e];
-        if (ev_up != nullptr) ev_up[at] = cnt_up[e] - 1;
+      for (int e = 0; e < kScanPer; ++e) {
+        const int p = p0 + e;
+        if (p < n) {
+          const int64_t at = (int64_t)row * n + (SUFFIX ? n - 1 - p : p);
+          if (ev_lo != nullptr) ev_lo[at] = cnt_lo[e];
+          if (ev_up != nullptr) ev_up[at] = cnt_up[e] - 1;
+        }
       }
+    } else {
+      __syncthreads();
     }
     carry = carry_s;
   }
@@ -476,54 +556,63 @@ __global__ __launch_bounds__(256) void init2_kernel(int32_t* __restrict__ h, T* 
 constexpr int kDevPerThread = 4;   // alpha samples per thread in the deviation kernels
 constexpr int kDevPerBlock = 256 * kDevPerThread;
 
-// Maximal horizontal deviation: each thread searches beta for a few alpha[D]; a workgroup
-// covers kDevPerBlock consecutive D of one row and merges into out[row] (pre-set to 0) with
-// an atomic max.
+// Maximal horizontal deviation: each thread searches beta for a few alpha[D]; a workgroup takes
+// `trips` consecutive blocks of kDevPerBlock samples of one row, one after the other, and merges
+// into out[row] (pre-set to 0) with one atomic max at the end (atomics on one address are served
+// one after the other, so a row should not see many more of them than it takes to fill the chip).
 // With out_v (optional; pre-set to the lowest value) the same pass also takes the maximal vertical
 // deviation of its samples, alpha[D] - beta[D]: delay and backlog bound from one read of alpha.
 template <typename T>
 __global__ __launch_bounds__(256) void hdev_kernel(const T* __restrict__ alpha,
                                                    const T* __restrict__ beta, int32_t* __restrict__ out,
-                                                   int n, int blocks_per_row,
+                                                   int n, int parts, int trips,
                                                    int32_t* __restrict__ dev_flags, T* __restrict__ out_v) {
   static_assert(kDevPerThread == kSearchPerThread, "the deviation kernels search kSearchPerThread samples per thread");
   __shared__ T s_win[kSearchWindow];
   __shared__ int32_t red[4];
   __shared__ int32_t unb[4];
   __shared__ T redv[4];
-  const int row = blockIdx.x / blocks_per_row;
-  const int base = (blockIdx.x % blocks_per_row) * kDevPerBlock;
+  const int row = blockIdx.x / parts;
+  const int first = (blockIdx.x % parts) * trips * kDevPerBlock;
+  if (first >= n) return;
   const T* a = alpha + (int64_t)row * n;
   const T* b = beta + (int64_t)row * n;
-  T xv[kSearchPerThread];
-#pragma unroll
-  for (int e = 0; e < kDevPerThread; ++e) xv[e] = a[min(base + e * 256 + (int)threadIdx.x, n - 1)];   // past the end: the last sample again
   T vmaxdev = lowest<T>();
-  if (out_v != nullptr) {
-#pragma unroll
-    for (int e = 0; e < kDevPerThread; ++e)     // (a repeated last sample changes no maximum)
-      vmaxdev = vmax(vmaxdev, (T)(xv[e] - b[min(base + e * 256 + (int)threadIdx.x, n - 1)]));
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) vmaxdev = vmax(vmaxdev, __shfl_xor(vmaxdev, off));
-    if ((threadIdx.x & 63) == 0) redv[threadIdx.x >> 6] = vmaxdev;    // read after the barriers of the search below
-  }
-  int cnt[kSearchPerThread];
-  windowed_counts(b, n, xv, false, s_win, cnt);
   int32_t h = 0;
   bool unbounded = false;
+  for (int trip = 0; trip < trips; ++trip) {
+    const int base = first + trip * kDevPerBlock + (int)threadIdx.x;
+    if (first + trip * kDevPerBlock >= n) break;                                       // (uniform)
+    T xv[kSearchPerThread];
 #pragma unroll
-  for (int e = 0; e < kDevPerThread; ++e) {
-    const int d = base + e * 256 + threadIdx.x;
-    if (d < n) {
-      const int k = cnt[e];
-      unbounded |= (k == n);
-      h = max(h, k - d);
+    for (int e = 0; e < kDevPerThread; ++e) xv[e] = a[min(base + e * 256, n - 1)];   // past the end: the last sample again
+    if (out_v != nullptr) {
+      T bv[kDevPerThread];
+#pragma unroll
+      for (int e = 0; e < kDevPerThread; ++e) bv[e] = b[min(base + e * 256, n - 1)];
+#pragma unroll
+      for (int e = 0; e < kDevPerThread; ++e) vmaxdev = vmax(vmaxdev, (T)(xv[e] - bv[e]));   // (a repeated last sample changes no maximum)
+    }
+    int cnt[kSearchPerThread], unused[kSearchPerThread];
+    exact_windowed_counts<T, 256, kSearchPerThread, kSearchWindow, 0>(b, n, xv, s_win, cnt, unused);   // (ends with a barrier)
+#pragma unroll
+    for (int e = 0; e < kDevPerThread; ++e) {
+      const int d = base + e * 256;
+      if (d < n) {
+        const int k = cnt[e];
+        unbounded |= (k == n);
+        h = max(h, k - d);
+      }
     }
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) h = max(h, __shfl_xor(h, off));
+  if (out_v != nullptr) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) vmaxdev = vmax(vmaxdev, __shfl_xor(vmaxdev, off));
+  }
   const bool any_unb = __any(unbounded);
-  if ((threadIdx.x & 63) == 0) { red[threadIdx.x >> 6] = h; unb[threadIdx.x >> 6] = any_unb; }
+  if ((threadIdx.x & 63) == 0) { red[threadIdx.x >> 6] = h; unb[threadIdx.x >> 6] = any_unb; redv[threadIdx.x >> 6] = vmaxdev; }
   __syncthreads();
   if (threadIdx.x == 0) {
     const int32_t m = max(max(red[0], red[1]), max(red[2], red[3]));
@@ -533,21 +622,36 @@ __global__ __launch_bounds__(256) void hdev_kernel(const T* __restrict__ alpha,
   }
 }
 
-// Maximal vertical deviation; same decomposition, out[row] pre-set to the lowest value.
+// Maximal vertical deviation, out[row] pre-set to the lowest value.  `parts` workgroups per row, each
+// over a segment of seg samples (a multiple of the 2048 one trip covers): as many workgroups as keep
+// every CU busy and no more, because each ends in one atomic on its row's result and atomics on one
+// address are served one after the other.  Eight loads per operand and thread are in flight per trip
+// (a position past the segment's end reads its last sample again, which changes no maximum).
+constexpr int kVdevPerThread = 8;
+constexpr int kVdevTrip = 256 * kVdevPerThread;
+
 template <typename T>
 __global__ __launch_bounds__(256) void vdev_kernel(const T* __restrict__ alpha,
                                                    const T* __restrict__ beta, T* __restrict__ out, int n,
-                                                   int blocks_per_row) {
+                                                   int parts, int seg) {
   __shared__ T red[4];
-  const int row = blockIdx.x / blocks_per_row;
-  const int base = (blockIdx.x % blocks_per_row) * kDevPerBlock;
+  const int row = blockIdx.x / parts;
+  const int start = (blockIdx.x % parts) * seg;
+  if (start >= n) return;
+  const int last = min(n, start + seg) - 1;
   const T* a = alpha + (int64_t)row * n;
   const T* b = beta + (int64_t)row * n;
   T m = lowest<T>();
+  for (int base = start + threadIdx.x; base <= last; base += kVdevTrip) {
+    T av[kVdevPerThread], bv[kVdevPerThread];
 #pragma unroll
-  for (int e = 0; e < kDevPerThread; ++e) {
-    const int d = base + e * 256 + threadIdx.x;
-    if (d < n) m = vmax(m, (T)(a[d] - b[d]));
+    for (int e = 0; e < kVdevPerThread; ++e) {
+      const int d = min(base + e * 256, last);
+      av[e] = a[d];
+      bv[e] = b[d];
+    }
+#pragma unroll
+    for (int e = 0; e < kVdevPerThread; ++e) m = vmax(m, (T)(av[e] - bv[e]));
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) m = vmax(m, __shfl_xor(m, off));
@@ -623,46 +727,50 @@ int launch_compose(const void* outer, int64_t n_outer, const int32_t* inner, int
 }
 
 int launch_residual_service(const void* beta, const void* alpha, void* out, int64_t batch,
-                            int64_t n, int dt, bool suffix_min, hipStream_t stream, const void* gamma,
+                            int64_t n, int dt, bool suffix_min, hipStream_t stream, void* scratch, const void* gamma,
                             int64_t n_gamma, int32_t* ev_lo, int32_t* ev_up) {
-  // Several workgroups per row when the rows alone would not fill the chip.  A workgroup's passes
-  // over its segment are bound by latency (about 3.3 us each, measured), the whole launch by its
-  // traffic: 3 arrays, plus (parts - 1) more for what the workgroups re-read before their segments
-  // (at about 3.5 TB/s).  Take the power of two that minimises the larger of the two.
+  // One workgroup per row, passing over it 1024 positions at a time, moves the fewest bytes; but the
+  // passes of a row are then taken one after the other.  Once the rows alone give every CU its
+  // eight workgroups, that is the better trade; below that every segment of one pass gets its own
+  // workgroup, which costs one more read of both operands (segment_extrema_kernel) and no waiting.
   const bool events = gamma != nullptr && (ev_lo != nullptr || ev_up != nullptr);
-  int64_t parts = 1;
-  {
-    const double array_bytes = (double)batch * (double)n * (dt == RTC_I32 ? 4.0 : 8.0);
-    double best = 1e300;
-    for (int64_t p = 1; p <= 16 && (p == 1 || (batch * p <= 512 && n / p >= 8192)); p *= 2) {
-      // with the event-domain images a pass also searches (two barriers and a staged window more)
-      const double latency_us = (double)((n + p * 4096 - 1) / (p * 4096)) * (events ? 6.0 : 3.3);
-      const double traffic_us = ((events ? 4.0 : 2.0) + (double)p) * array_bytes / 3.5e6;
-      const double t = latency_us > traffic_us ? latency_us : traffic_us;
-      if (t < best) { best = t; parts = p; }
-    }
-  }
-  const int64_t seg = ((n + parts - 1) / parts + 4095) / 4096 * 4096;
+  const int64_t passes = (n + kScanPass - 1) / kScanPass;
+  // (the scratch holds n elements per row; a row's totals and its coarse table of gamma must fit)
+  const int64_t parts = (batch >= 2048 || scratch == nullptr || passes + kScanThreads > n) ? 1 : passes;
+  const int64_t seg = parts == 1 ? passes * kScanPass : kScanPass;
   if (batch * parts > 0x7fffffffLL) return RTC_ERR_SHAPE;
-  prof_begin(RTC_PROFILE_KIND_TAIL, stream);
   RTC_DISPATCH(dt, {
+    T* tot = static_cast<T*>(scratch);              // [batch][parts], then [batch][kScanThreads]
+    T* tab = parts > 1 && events ? tot + batch * parts : nullptr;
+    const T* gam = events ? static_cast<const T*>(gamma) : nullptr;
+    const T* b = static_cast<const T*>(beta);
+    const T* a = static_cast<const T*>(alpha);
+    T* o = static_cast<T*>(out);
+    const dim3 grid((uint32_t)(batch * parts));
+    const dim3 block(kScanThreads);
+    prof_begin(RTC_PROFILE_KIND_TAIL, stream);      // (both launches: the totals belong to the scan)
+    if (parts > 1) {
+      const dim3 grid1((uint32_t)(batch * (parts - 1)));
+      if (suffix_min)
+        RTC_LAUNCH((segment_extrema_kernel<T, true>), grid1, dim3(256), 0, stream, b, a, tot, (int)n, (int)parts, (int)seg,
+                   gam, (int)n_gamma, tab);
+      else
+        RTC_LAUNCH((segment_extrema_kernel<T, false>), grid1, dim3(256), 0, stream, b, a, tot, (int)n, (int)parts, (int)seg,
+                   gam, (int)n_gamma, tab);
+    }
     if (events) {
       if (suffix_min)
-        RTC_LAUNCH((gpc_tail_kernel<T, true>), dim3((uint32_t)(batch * parts)), dim3(1024), 0, stream,
-                           static_cast<const T*>(beta), static_cast<const T*>(alpha), static_cast<T*>(out), (int)n,
-                           (int)parts, (int)seg, static_cast<const T*>(gamma), (int)n_gamma, ev_lo, ev_up);
+        RTC_LAUNCH((residual_service_kernel<T, true, true>), grid, block, 0, stream, b, a, o, (int)n, (int)parts, (int)seg,
+                   tot, gam, (int)n_gamma, ev_lo, ev_up, tab);
       else
-        RTC_LAUNCH((gpc_tail_kernel<T, false>), dim3((uint32_t)(batch * parts)), dim3(1024), 0, stream,
-                           static_cast<const T*>(beta), static_cast<const T*>(alpha), static_cast<T*>(out), (int)n,
-                           (int)parts, (int)seg, static_cast<const T*>(gamma), (int)n_gamma, ev_lo, ev_up);
+        RTC_LAUNCH((residual_service_kernel<T, false, true>), grid, block, 0, stream, b, a, o, (int)n, (int)parts, (int)seg,
+                   tot, gam, (int)n_gamma, ev_lo, ev_up, tab);
     } else if (suffix_min) {
-      RTC_LAUNCH((residual_service_kernel<T, true>), dim3((uint32_t)(batch * parts)), dim3(1024), 0, stream,
-                         static_cast<const T*>(beta), static_cast<const T*>(alpha), static_cast<T*>(out), (int)n,
-                         (int)parts, (int)seg);
+      RTC_LAUNCH((residual_service_kernel<T, true, false>), grid, block, 0, stream, b, a, o, (int)n, (int)parts, (int)seg,
+                 tot, gam, 0, nullptr, nullptr, tab);
     } else {
-      RTC_LAUNCH((residual_service_kernel<T, false>), dim3((uint32_t)(batch * parts)), dim3(1024), 0, stream,
-                         static_cast<const T*>(beta), static_cast<const T*>(alpha), static_cast<T*>(out), (int)n,
-                         (int)parts, (int)seg);
+      RTC_LAUNCH((residual_service_kernel<T, false, false>), grid, block, 0, stream, b, a, o, (int)n, (int)parts, (int)seg,
+                 tot, gam, 0, nullptr, nullptr, tab);
     }
     prof_end(stream);
     return hip_ok();
@@ -692,14 +800,20 @@ int launch_copy(const void* src, void* dst, int64_t count, int dt, hipStream_t s
 
 int launch_max_hdev(const void* alpha, const void* beta, int32_t* out, int64_t batch, int64_t n,
                     int dt, int32_t* dev_flags, hipStream_t stream, void* out_v) {
+  // about 2048 workgroups in all (8 per CU) where the rows are long enough for that
   const int64_t bpr = (n + kDevPerBlock - 1) / kDevPerBlock;
-  if (bpr * batch > 0x7fffffffLL) return RTC_ERR_SHAPE;
+  int64_t parts = (2048 + batch - 1) / batch;
+  if (parts < 32) parts = 32;                    // (up to 32 atomics per row cost nothing measurable)
+  if (parts > bpr) parts = bpr;
+  const int64_t trips = (bpr + parts - 1) / parts;
+  parts = (bpr + trips - 1) / trips;
+  if (parts * batch > 0x7fffffffLL) return RTC_ERR_SHAPE;
   RTC_DISPATCH(dt, {
     RTC_LAUNCH(init2_kernel<T>, dim3((uint32_t)((batch + 255) / 256)), dim3(256), 0, stream, out,
                        static_cast<T*>(out_v), (int)batch, std::numeric_limits<T>::has_infinity
                            ? (T)-std::numeric_limits<T>::infinity() : std::numeric_limits<T>::lowest());
-    RTC_LAUNCH(hdev_kernel<T>, dim3((uint32_t)(bpr * batch)), dim3(256), 0, stream,
-                       static_cast<const T*>(alpha), static_cast<const T*>(beta), out, (int)n, (int)bpr,
+    RTC_LAUNCH(hdev_kernel<T>, dim3((uint32_t)(parts * batch)), dim3(256), 0, stream,
+                       static_cast<const T*>(alpha), static_cast<const T*>(beta), out, (int)n, (int)parts, (int)trips,
                        dev_flags, static_cast<T*>(out_v));
     return hip_ok();
   });
@@ -740,15 +854,20 @@ int launch_validate_monotone(const void* f, int64_t batch, int64_t n, int64_t st
 
 int launch_max_vdev(const void* alpha, const void* beta, void* out, int64_t batch, int64_t n, int dt,
                     hipStream_t stream) {
-  const int64_t bpr = (n + kDevPerBlock - 1) / kDevPerBlock;
-  if (bpr * batch > 0x7fffffffLL) return RTC_ERR_SHAPE;
+  // about 2048 workgroups in all (8 per CU), at least one trip each
+  const int64_t trips = (n + kVdevTrip - 1) / kVdevTrip;
+  int64_t parts = (2048 + batch - 1) / batch;
+  if (parts > trips) parts = trips;
+  const int64_t seg = (trips + parts - 1) / parts * kVdevTrip;
+  parts = (n + seg - 1) / seg;
+  if (parts * batch > 0x7fffffffLL) return RTC_ERR_SHAPE;
   RTC_DISPATCH(dt, {
     RTC_LAUNCH(init_kernel<T>, dim3((uint32_t)((batch + 255) / 256)), dim3(256), 0, stream,
                        static_cast<T*>(out), (int)batch, std::numeric_limits<T>::has_infinity
                            ? (T)-std::numeric_limits<T>::infinity() : std::numeric_limits<T>::lowest());
-    RTC_LAUNCH(vdev_kernel<T>, dim3((uint32_t)(bpr * batch)), dim3(256), 0, stream,
+    RTC_LAUNCH(vdev_kernel<T>, dim3((uint32_t)(parts * batch)), dim3(256), 0, stream,
                        static_cast<const T*>(alpha), static_cast<const T*>(beta), static_cast<T*>(out),
-                       (int)n, (int)bpr);
+                       (int)n, (int)parts, (int)seg);
     return hip_ok();
   });
 }

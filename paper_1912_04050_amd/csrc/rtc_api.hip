@@ -162,7 +162,8 @@ int rtc_gpc_step(const rtc_gpc_args* a, void* hip_stream) {
                        sub_bytes, a->dev_flags, stream);
   if (rc != RTC_OK) return rc;
   // beta'^l and, while its values are in registers, their event-domain images: one kernel
-  rc = launch_residual_service(a->beta_l, a->alpha_u, a->beta_l_out, batch, n, a->dt, false, stream, a->gamma_u,
+  // (c is free again: the segment totals of the scan go there)
+  rc = launch_residual_service(a->beta_l, a->alpha_u, a->beta_l_out, batch, n, a->dt, false, stream, c, a->gamma_u,
                                a->n_gamma, a->events_lower, a->events_upper);
   if (rc != RTC_OK) return rc;
   if (a->alpha_l != nullptr) {
@@ -174,7 +175,7 @@ int rtc_gpc_step(const rtc_gpc_args* a, void* hip_stream) {
     rc = launch_tropical(RTC_OP_CONV, c, a->beta_l, a->alpha_l_out, batch, n, n, n, a->dt, a->beta_l, sub_ws,
                          sub_bytes, a->dev_flags, stream);
     if (rc != RTC_OK) return rc;
-    rc = launch_residual_service(a->beta_u, a->alpha_l, a->beta_u_out, batch, n, a->dt, true, stream, a->gamma_l,
+    rc = launch_residual_service(a->beta_u, a->alpha_l, a->beta_u_out, batch, n, a->dt, true, stream, c, a->gamma_l,
                                  a->n_gamma_l, a->events_u_lower, a->events_u_upper);
     if (rc != RTC_OK) return rc;
   }

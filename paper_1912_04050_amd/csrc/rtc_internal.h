@@ -48,9 +48,12 @@ int launch_compose(const void* outer, int64_t n_outer, const int32_t* inner, int
                    int64_t batch, int dt, int32_t* dev_flags, hipStream_t stream);
 // Remaining service of a component and, with gamma and at least one of ev_lo / ev_up, its
 // event-domain images (lower / upper pseudo-inverse of gamma at the result) in the same kernel.
+// scratch (optional): batch * ceil(n / 4096) elements of dtype dt for the segment totals of rows
+// that are cut over several workgroups; without it every row is one workgroup's.
 int launch_residual_service(const void* beta, const void* alpha, void* out, int64_t batch,
-                            int64_t n, int dt, bool suffix_min, hipStream_t stream, const void* gamma = nullptr,
-                            int64_t n_gamma = 0, int32_t* ev_lo = nullptr, int32_t* ev_up = nullptr);
+                            int64_t n, int dt, bool suffix_min, hipStream_t stream, void* scratch,
+                            const void* gamma = nullptr, int64_t n_gamma = 0, int32_t* ev_lo = nullptr,
+                            int32_t* ev_up = nullptr);
 int launch_closure_init(const void* f, void* out, int64_t batch, int64_t n, int dt, bool super,
                         int32_t* dev_flags, hipStream_t stream);
 int launch_copy(const void* src, void* dst, int64_t count, int dt, hipStream_t stream);

@@ -191,8 +191,8 @@ def test_binding_constants_match_the_headers():
 
 def test_a_launch_that_would_not_fit_is_refused_before_anything_is_enqueued(lib):
     """Every entry point walks its launch sequence in a dry run first.  A component step over
-    2^22 rows of two samples: both products fit (workgroups of 64 threads), the scan that follows
-    them would need 2^22 workgroups of 1024 threads = 2^32 threads, which the runtime does not
+    2^24 rows of two samples: both products fit (workgroups of 64 threads), the scan that follows
+    them would need 2^24 workgroups of 256 threads = 2^32 threads, which the runtime does not
     take.  The call returns RTC_ERR_SHAPE from the dry run, i.e. without a single HIP call (which
     is why this runs without a GPU, on pointers that are never dereferenced); the GPU suite
     repeats it on real buffers and checks that no output byte changed."""
@@ -200,7 +200,7 @@ def test_a_launch_that_would_not_fit_is_refused_before_anything_is_enqueued(lib)
     lib.rtc_gpc_step.argtypes = [ctypes.POINTER(rtc.rtc_gpc_args), ctypes.c_void_p]
     lib.rtc_workspace_bytes.restype = ctypes.c_size_t
     lib.rtc_workspace_bytes.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int]
-    batch, n = 1 << 22, 2
+    batch, n = 1 << 24, 2
     a = rtc.rtc_gpc_args()
     for k, name in enumerate(("alpha_u", "beta_u", "beta_l", "alpha_u_out", "beta_l_out", "ws")):
         setattr(a, name, 0x100000 * (k + 1))

@@ -234,10 +234,10 @@ def test_product_census(rtc):
 
 
 def test_a_refused_call_changes_no_output(rtc):
-    """A component step over 2^22 rows of two samples: its two products would fit, the scan after them
-    would need 2^32 threads in one grid.  The call is refused with RTC_ERR_SHAPE before its first
+    """A component step over 2^24 rows of two samples: its two products would fit, the scan after them
+    (workgroups of 256 threads) would need 2^32 threads in one grid.  The call is refused with RTC_ERR_SHAPE before its first
     kernel: both outputs still hold what they held.  One row fewer runs, and equals the oracle."""
-    batch, n = 1 << 22, 2
+    batch, n = 1 << 24, 2
     rng = np.random.default_rng(8)
     alpha = np.cumsum(rng.integers(0, 5, (batch, n)), axis=1).astype(np.int32)
     beta_u = np.cumsum(rng.integers(0, 9, (batch, n)), axis=1).astype(np.int32)
