@@ -24,8 +24,9 @@
 //   * for each of the 9 taps a lane reads the 16 bytes of "its" pixel shifted by the tap
 //     (row i = lane % 32 of the A operand, channels 16 (lane / 32) ... + 15) and, once per tap,
 //     the 16 bytes of filter lane % 32 for the same channels (B operand).
-// Both stagings are fetched into registers one channel word ahead, under the matrix instructions
-// of the current one.
+// Both stagings go through registers two channel words ahead and through one of two LDS buffers
+// one word ahead: while the matrix instructions of word cw read one buffer, word cw + 1 is
+// unpacked into the other and word cw + 2 is on its way from memory; one barrier per word.
 // The contraction sums over (tap, channel) in any order, so only the pairing of A and B bytes
 // matters: both use lane / 32 for the half and the byte index for the channel.
 // Result layout of the instruction (checked on the device): register r of lane l holds row
@@ -98,8 +99,7 @@ template <int MT, int QC>
 __global__ __launch_bounds__(256, 2) void bconv_mfma_kernel(const MfmaArgs a, int fgroups, int plane) {
   typedef uint32_t xwords __attribute__((ext_vector_type(QC)));
   extern __shared__ __align__(16) unsigned char lds[];
-  unsigned char* const ldsB = lds;                     // the filter fragments of the current channel word
-  unsigned char* const ldsA = lds + kFragBytes;        // the unpacked pixels
+  // two buffers of [filter fragments of a channel word][unpacked pixels: two planes]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int i = lane & 31, h = lane >> 5;
   const int W = a.W, H = a.H, Cw = a.Cw, PW = W + 1, PH = H + 1;
@@ -156,63 +156,81 @@ __global__ __launch_bounds__(256, 2) void bconv_mfma_kernel(const MfmaArgs a, in
   const v4i* wsrc = reinterpret_cast<const v4i*>(a.wbytes + (int64_t)fg * Cw * kFragBytes);
   xwords xr[kStageRounds];
   v4i wr[kFragRounds];
-  auto fetch = [&](int cw) {
-    if (cw % QC == 0) {
+  // Fetches are never conditional (a word index past the end is clamped: the values are then
+  // staged into a buffer that nobody reads), so that the loop body below is one basic block in
+  // which the compiler can place the staging between the matrix instructions.
+  auto fetch_x = [&](int cw) {                 // the QC words from cw on (cw a multiple of QC)
+    const int c = cw < Cw - QC ? cw : Cw - QC;
 #pragma unroll
-      for (int j = 0; j < kStageRounds; ++j) xr[j] = *reinterpret_cast<const xwords*>(xsrc[j] + cw);
-    }
-#pragma unroll
-    for (int j = 0; j < kFragRounds; ++j) wr[j] = wsrc[cw * kFragChunks + wchunk[j]];
+    for (int j = 0; j < kStageRounds; ++j) xr[j] = *reinterpret_cast<const xwords*>(xsrc[j] + c);
   };
-  fetch(0);
+  auto fetch_w = [&](int cw) {
+    const int c = cw < Cw - 1 ? cw : Cw - 1;
+#pragma unroll
+    for (int j = 0; j < kFragRounds; ++j) wr[j] = wsrc[c * kFragChunks + wchunk[j]];
+  };
 
-  for (int cw = 0; cw < Cw; ++cw) {
-    __syncthreads();                       // the previous word's reads are done
+  // Two LDS buffers: while the matrix instructions of channel word cw read one, the word cw + 1
+  // (fetched into registers an iteration earlier) is unpacked into the other, so a wave's own
+  // staging runs under its own matrix instructions and an iteration needs one barrier: the buffer
+  // written in iteration cw was last read in iteration cw - 1, which every wave has left.
+  // (A staging round beyond the workgroup's slots repeats its last slot: same bytes, same place.)
+  const int buf_bytes = kFragBytes + 2 * plane;
+  auto stage = [&](int sub, unsigned char* buf) {       // word `sub` of the fetched QC words
+    unsigned char* const bB = buf;
+    unsigned char* const bA = buf + kFragBytes;
 #pragma unroll
     for (int j = 0; j < kStageRounds; ++j) {
-      if (256 * j < slots) {               // (uniform) a round that would only repeat the last slot
-        uint32_t word;
-        if constexpr (QC == 1) {
-          word = xr[j][0];
-        } else {
-          const int sub = cw % QC;
-          word = sub == 0 ? xr[j][0] : sub == 1 ? xr[j][1] : sub == 2 ? xr[j][2] : xr[j][3];
-        }
-        if (!xreal[j]) word = 0u;                               // a padding slot: zeros
-        const uint32_t zero = xreal[j] ? 0u : 0x0C0C0C0Cu;
-        uint4 lo, hi;
-        lo.x = nibble_to_signs(word & 15u, zero);         lo.y = nibble_to_signs((word >> 4) & 15u, zero);
-        lo.z = nibble_to_signs((word >> 8) & 15u, zero);  lo.w = nibble_to_signs((word >> 12) & 15u, zero);
-        hi.x = nibble_to_signs((word >> 16) & 15u, zero); hi.y = nibble_to_signs((word >> 20) & 15u, zero);
-        hi.z = nibble_to_signs((word >> 24) & 15u, zero); hi.w = nibble_to_signs(word >> 28, zero);
-        *reinterpret_cast<uint4*>(ldsA + xdst[j]) = lo;
-        *reinterpret_cast<uint4*>(ldsA + plane + xdst[j]) = hi;
-      }
+      uint32_t word = xr[j][sub];
+      if (!xreal[j]) word = 0u;                               // a padding slot: zeros
+      const uint32_t zero = xreal[j] ? 0u : 0x0C0C0C0Cu;
+      uint4 lo, hi;
+      lo.x = nibble_to_signs(word & 15u, zero);         lo.y = nibble_to_signs((word >> 4) & 15u, zero);
+      lo.z = nibble_to_signs((word >> 8) & 15u, zero);  lo.w = nibble_to_signs((word >> 12) & 15u, zero);
+      hi.x = nibble_to_signs((word >> 16) & 15u, zero); hi.y = nibble_to_signs((word >> 20) & 15u, zero);
+      hi.z = nibble_to_signs((word >> 24) & 15u, zero); hi.w = nibble_to_signs(word >> 28, zero);
+      *reinterpret_cast<uint4*>(bA + xdst[j]) = lo;
+      *reinterpret_cast<uint4*>(bA + plane + xdst[j]) = hi;
     }
 #pragma unroll
-    for (int j = 0; j < kFragRounds; ++j) reinterpret_cast<v4i*>(ldsB)[wchunk[j]] = wr[j];
-    __syncthreads();
-    if (cw + 1 < Cw) fetch(cw + 1);
-    // operands of tap t + 1 are requested before the matrix instructions of tap t (the compiler
-    // moves the reads where its register budget allows; forcing the order with scheduling
-    // barriers cost 26 more registers and measured no faster)
-    v4i bq[2][2], aq[2][MT];
-    auto read_tap = [&](int tap, int buf) {
-      bq[buf][0] = *reinterpret_cast<const v4i*>(ldsB + ((tap * 2 + 0) * 64 + lane) * 16);
-      bq[buf][1] = *reinterpret_cast<const v4i*>(ldsB + ((tap * 2 + 1) * 64 + lane) * 16);
+    for (int j = 0; j < kFragRounds; ++j) reinterpret_cast<v4i*>(bB)[wchunk[j]] = wr[j];
+  };
+  fetch_x(0);
+  fetch_w(0);
+  stage(0, lds);
+  if constexpr (QC == 1) fetch_x(1);
+  fetch_w(1);
+  __syncthreads();
+
+  for (int cq = 0; cq < Cw; cq += QC) {
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-        aq[buf][mt] = *reinterpret_cast<const v4i*>(ldsA + lds_pix[mt] + (tap / 3 - 1) * PW * kPitch + (tap % 3) * kPitch);
-    };
-    read_tap(0, 0);
+    for (int sub = 0; sub < QC; ++sub) {
+      const int cw = cq + sub;
+      const unsigned char* const curB = lds + (cw & 1) * buf_bytes;
+      const unsigned char* const curA = curB + kFragBytes;
+      stage((sub + 1) % QC, lds + ((cw + 1) & 1) * buf_bytes);
+      if ((sub + 2) % QC == 0) fetch_x(cw + 2);          // (decided at compile time)
+      fetch_w(cw + 2);
+      // operands of tap t + 1 are requested before the matrix instructions of tap t
+      v4i bq[2][2], aq[2][MT];
+      auto read_tap = [&](int tap, int buf) {
+        bq[buf][0] = *reinterpret_cast<const v4i*>(curB + ((tap * 2 + 0) * 64 + lane) * 16);
+        bq[buf][1] = *reinterpret_cast<const v4i*>(curB + ((tap * 2 + 1) * 64 + lane) * 16);
 #pragma unroll
-    for (int tap = 0; tap < 9; ++tap) {
-      if (tap + 1 < 9) read_tap(tap + 1, (tap + 1) & 1);
+        for (int mt = 0; mt < MT; ++mt)
+          aq[buf][mt] = *reinterpret_cast<const v4i*>(curA + lds_pix[mt] + (tap / 3 - 1) * PW * kPitch + (tap % 3) * kPitch);
+      };
+      read_tap(0, 0);
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        acc[mt][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(aq[tap & 1][mt], bq[tap & 1][0], acc[mt][0], 0, 0, 0);
-        acc[mt][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(aq[tap & 1][mt], bq[tap & 1][1], acc[mt][1], 0, 0, 0);
+      for (int tap = 0; tap < 9; ++tap) {
+        if (tap + 1 < 9) read_tap(tap + 1, (tap + 1) & 1);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          acc[mt][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(aq[tap & 1][mt], bq[tap & 1][0], acc[mt][0], 0, 0, 0);
+          acc[mt][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(aq[tap & 1][mt], bq[tap & 1][1], acc[mt][1], 0, 0, 0);
+        }
       }
+      __syncthreads();                       // reads of this word done, the next word's buffer complete
     }
   }
 
@@ -283,10 +301,23 @@ bool launch_bconv_mfma(const MfmaArgs& a, hipStream_t stream) {
   // an odd multiple of 128 bytes apart: the 16 lanes that the LDS serves per cycle then hit 16
   // different bank groups whether they belong to one half or to both
   const int plane = (int)((slot_bound * kPitch + 255) / 256 * 256 + 128);
-  const size_t lds_bytes = (size_t)kFragBytes + 2 * (size_t)plane;
+  const size_t lds_bytes = 2 * ((size_t)kFragBytes + 2 * (size_t)plane);       // two buffers
   const int64_t fgroups = a.K / 64;
   const int64_t blocks = (total + kWgPixels - 1) / kWgPixels * fgroups;
   if (blocks > 0x7fffffffLL) return false;
+  // more dynamic LDS than the default limit of a kernel: ask for it once per process
+  static const bool lds_ok = [] {
+    constexpr int kMaxLds = 2 * (kFragBytes + 2 * ((kMaxSlots * kPitch + 255) / 256 * 256 + 128));
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&bconv_mfma_kernel<MT, 4>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds) == hipSuccess &&
+           hipFuncSetAttribute(reinterpret_cast<const void*>(&bconv_mfma_kernel<MT, 1>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds) == hipSuccess;
+  }();
+  if (!lds_ok) return false;
+  // (Cutting the pixels into whole rounds of these workgroups plus a second launch of smaller ones
+  // for the rest, so that no partly filled last round costs a full one, was measured: conv8 3 %
+  // quicker, conv5 and conv6 4 to 6 % slower -- workgroups do not run in lockstep rounds, and the
+  // second launch waits for the first to drain.  Not kept.)
   rtc::prof_begin(kProfileKind, stream);
   if (a.Cw % 4 == 0 && reinterpret_cast<uintptr_t>(a.x) % 16 == 0)
     RTC_LAUNCH((bconv_mfma_kernel<MT, 4>), dim3((uint32_t)blocks), dim3(256), lds_bytes, stream, a, (int)fgroups, plane);

@@ -189,6 +189,14 @@ def test_matrix_core_shapes(bnn, shape):
     check_layer(bnn, 600 + H * 7 + W + C, N, H, W, C, K, 3, 3, 1, 1)
 
 
+@pytest.mark.parametrize("shape", [(1100, 64), (600, 192)])
+def test_matrix_core_more_workgroups_than_slots(bnn, shape):
+    """More workgroups than a chip of 256 CUs holds at once (two per CU), a ragged last one, one and
+    three groups of 64 filters."""
+    N, K = shape
+    check_layer(bnn, 700 + N, N, 16, 16, 128, K, 3, 3, 1, 1)
+
+
 def test_matrix_core_special_thresholds(bnn):
     """Infinite, NaN, tied and out-of-range thresholds with 64 filters (the shape the matrix-core
     kernel takes); every filter beyond the first eight gets one of the special values in turn."""
