@@ -403,6 +403,33 @@ def test_component_step_long_rows_few_pairs(rtc, dtype):
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
+def test_component_step_many_rows_several_passes(rtc, dtype):
+    """From 2048 rows on the scan takes one workgroup per row, pass after pass, with the carry and
+    the prefetched pass of the loop, and its coarse table of gamma read by the workgroup itself
+    (below that every pass is its own workgroup): both sides with the event-domain images, rows of
+    2.2 passes, against the oracle."""
+    batch, n = 2048, 2300
+    au = wl.random_monotone(31, 1, batch, n, dtype, max_inc=6)
+    al = np.minimum(au, wl.random_monotone(31, 2, batch, n, dtype, max_inc=4, start_max=0))
+    bu = wl.random_monotone(31, 3, batch, n, dtype, max_inc=12, start_max=0)
+    bl = np.minimum(bu, wl.random_monotone(31, 4, batch, n, dtype, max_inc=8, start_max=0))
+    gu = wl.random_monotone(31, 5, batch, n + 7, dtype, max_inc=9, start_max=0)
+    gl = wl.random_monotone(31, 6, batch, n + 3, dtype, max_inc=7, start_max=0)
+    ev = [torch.empty((batch, n), dtype=torch.int32, device="cuda") for _ in range(4)]
+    say("component step, many rows", dtype, batch, n)
+    ao, blo, alo, buo = rtc.rtc_gpc_step(dev(au), dev(bu), dev(bl), gamma_u=dev(gu), events_lower=ev[0], events_upper=ev[1],
+                                         alpha_l=dev(al), gamma_l=dev(gl), events_u_lower=ev[2], events_u_upper=ev[3])
+    want_a, want_b = oracle.gpc_step(au, bu, bl)
+    want_al, want_bu = oracle.gpc_step_lower(al, bu, bl)
+    assert np.array_equal(host(ao), want_a) and np.array_equal(host(blo), want_b)
+    assert np.array_equal(host(alo), want_al) and np.array_equal(host(buo), want_bu)
+    assert np.array_equal(host(ev[0]), oracle.pseudo_inverse(gu, want_b, 0))
+    assert np.array_equal(host(ev[1]), oracle.pseudo_inverse(gu, want_b, 1))
+    assert np.array_equal(host(ev[2]), oracle.pseudo_inverse(gl, want_bu, 0))
+    assert np.array_equal(host(ev[3]), oracle.pseudo_inverse(gl, want_bu, 1))
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
 def test_deviations(rtc, dtype):
     for n in (1, 77, 5000):
         alpha = wl.random_monotone(14, n, 4, n, dtype, max_inc=5)
@@ -420,6 +447,29 @@ def test_deviations(rtc, dtype):
         h2, v2 = rtc.rtc_max_deviations(dev(alpha), dev(beta), dev_flags=flags2)
         assert np.array_equal(host(h2), want_h) and int(host(flags2)[0]) == fl
         assert np.array_equal(host(v2), oracle.max_vdev(alpha, beta))
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_deviations_long_rows_and_many_rows(rtc, dtype):
+    """Rows of more than 32 blocks of 1024 samples: a workgroup of the horizontal deviation then
+    takes several blocks in turn (one atomic per workgroup, at most 32 per row).  Thousands of rows:
+    a workgroup of the vertical deviation takes its whole row in several trips."""
+    batch, n = 2, 70001
+    alpha = wl.random_monotone(33, 1, batch, n, dtype, max_inc=5)
+    beta = wl.random_monotone(33, 2, batch, n, dtype, max_inc=9, start_max=0)
+    beta[1, 20000:] = beta[1, 20000]          # row 1: the service stops growing, the delay is unbounded
+    say("deviations, long rows", dtype, batch, n)
+    flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+    h, v = rtc.rtc_max_deviations(dev(alpha), dev(beta), dev_flags=flags)
+    want_h, fl = oracle.max_hdev(alpha, beta)
+    assert np.array_equal(host(h), want_h) and int(host(flags)[0]) == fl
+    assert np.array_equal(host(v), oracle.max_vdev(alpha, beta))
+    assert np.array_equal(host(rtc.rtc_max_hdev(dev(alpha), dev(beta))), want_h)
+    batch, n = 2500, 5000
+    alpha = wl.random_monotone(33, 3, batch, n, dtype, max_inc=5)
+    beta = wl.random_monotone(33, 4, batch, n, dtype, max_inc=9, start_max=0)
+    say("vertical deviation, many rows", dtype, batch, n)
+    assert np.array_equal(host(rtc.rtc_max_vdev(dev(alpha), dev(beta))), oracle.max_vdev(alpha, beta))
 
 
 @pytest.mark.parametrize("dtype", [np.int32, np.int64])
