@@ -77,7 +77,8 @@ int bnn_set_planner(int tile_pixels, int filter_blocks);
 
 /* Matrix-core path for 3 x 3, stride 1, pad 1 layers with C a multiple of 32 (>= 128) and K a
  * multiple of 64 (results do not depend on it; process-wide, not thread-safe): 0 = where the
- * planner expects it to be faster, 1 = wherever the shape allows, -1 = never. */
+ * planner expects it to be faster, 1 = wherever the shape allows, -1 = never; 3 or 4 = as 1, with
+ * that many tiles of 32 pixels per wave instead of the planner's choice between the two (tests). */
 int bnn_set_matrix_path(int mode);
 
 /* 1 if bnn_binary_conv2d would run this layer on the matrix cores under the current setting of

@@ -880,7 +880,8 @@ int bnn_binary_conv2d(const uint32_t* x, const uint32_t* packed, const float* xi
     m.x = x; m.wbytes = reinterpret_cast<const int8_t*>(packed + R * S * Cw * Kp + R * S * Kp);
     m.xi = xi; m.gamma = gamma; m.out_x1 = out_x1; m.out_x4 = out_x4;
     m.N = (int32_t)N; m.H = (int32_t)H; m.W = (int32_t)W; m.Cw = (int32_t)Cw; m.K = (int32_t)K;
-    if (launch_bconv_mfma(m, stream)) return hip_status();
+    const int mode = g_matrix_path;
+    if (launch_bconv_mfma(m, stream, mode == 3 || mode == 4 ? mode : 0)) return hip_status();
   }
   // few channels: the filters stay in registers and a wave streams over several tiles, enough
   // of them that a launch has about 32K waves (measured: better than 8K or 16K)
@@ -952,7 +953,7 @@ int bnn_set_planner(int tile_pixels, int filter_blocks) {
 }
 
 int bnn_set_matrix_path(int mode) {
-  if (mode < -1 || mode > 1) return BNN_ERR_SHAPE;
+  if (mode < -1 || mode == 2 || mode > 4) return BNN_ERR_SHAPE;
   bnn::g_matrix_path = mode;
   return BNN_OK;
 }

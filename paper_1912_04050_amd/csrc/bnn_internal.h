@@ -41,6 +41,7 @@ size_t mfma_bank_bytes(int64_t K, int64_t R, int64_t S, int64_t C);      // 0 wh
 bool mfma_slots_fit(int64_t H, int64_t W);                               // the staged pixel range fits the kernel
 void launch_pack_weights_mfma(const int8_t* w, int8_t* bank, int64_t K, int64_t C, hipStream_t stream);
 // false when the shape does not fit the kernel (the caller then takes another one)
-bool launch_bconv_mfma(const MfmaArgs& a, hipStream_t stream);
+// tiles: 3 or 4 pixel tiles of 32 per wave, 0 = the launcher chooses
+bool launch_bconv_mfma(const MfmaArgs& a, hipStream_t stream, int tiles = 0);
 
 }  // namespace bnn

@@ -291,18 +291,11 @@ static int64_t slot_bound(int64_t H, int64_t W) {
 
 bool mfma_slots_fit(int64_t H, int64_t W) { return slot_bound(H, W) <= kMaxSlots; }
 
-bool launch_bconv_mfma(const MfmaArgs& a, hipStream_t stream) {
-  const int64_t total = (int64_t)a.N * a.H * a.W;
-  constexpr int MT = kTilesPerWave;
+namespace {
+
+template <int MT>
+bool launch_tiles(const MfmaArgs& a, int64_t total, int64_t fgroups, size_t lds_bytes, int plane, hipStream_t stream) {
   constexpr int kWgPixels = 4 * MT * 32;
-  if (!mfma_slots_fit(a.H, a.W)) return false;               // long rows or tiny images: another kernel
-  const int64_t slot_bound = bnn::slot_bound(a.H, a.W);
-  // the two halves of the staged pixels (channels 0..15 and 16..31 of the word) lie in two planes
-  // an odd multiple of 128 bytes apart: the 16 lanes that the LDS serves per cycle then hit 16
-  // different bank groups whether they belong to one half or to both
-  const int plane = (int)((slot_bound * kPitch + 255) / 256 * 256 + 128);
-  const size_t lds_bytes = 2 * ((size_t)kFragBytes + 2 * (size_t)plane);       // two buffers
-  const int64_t fgroups = a.K / 64;
   const int64_t blocks = (total + kWgPixels - 1) / kWgPixels * fgroups;
   if (blocks > 0x7fffffffLL) return false;
   // more dynamic LDS than the default limit of a kernel: ask for it once per process
@@ -314,10 +307,6 @@ bool launch_bconv_mfma(const MfmaArgs& a, hipStream_t stream) {
                                hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds) == hipSuccess;
   }();
   if (!lds_ok) return false;
-  // (Cutting the pixels into whole rounds of these workgroups plus a second launch of smaller ones
-  // for the rest, so that no partly filled last round costs a full one, was measured: conv8 3 %
-  // quicker, conv5 and conv6 4 to 6 % slower -- workgroups do not run in lockstep rounds, and the
-  // second launch waits for the first to drain.  Not kept.)
   rtc::prof_begin(kProfileKind, stream);
   if (a.Cw % 4 == 0 && reinterpret_cast<uintptr_t>(a.x) % 16 == 0)
     RTC_LAUNCH((bconv_mfma_kernel<MT, 4>), dim3((uint32_t)blocks), dim3(256), lds_bytes, stream, a, (int)fgroups, plane);
@@ -325,6 +314,43 @@ bool launch_bconv_mfma(const MfmaArgs& a, hipStream_t stream) {
     RTC_LAUNCH((bconv_mfma_kernel<MT, 1>), dim3((uint32_t)blocks), dim3(256), lds_bytes, stream, a, (int)fgroups, plane);
   rtc::prof_end(stream);
   return true;
+}
+
+}  // namespace
+
+bool launch_bconv_mfma(const MfmaArgs& a, hipStream_t stream, int tiles) {
+  const int64_t total = (int64_t)a.N * a.H * a.W;
+  if (!mfma_slots_fit(a.H, a.W)) return false;               // long rows or tiny images: another kernel
+  const int64_t slot_bound = bnn::slot_bound(a.H, a.W);
+  // the two halves of the staged pixels (channels 0..15 and 16..31 of the word) lie in two planes
+  // an odd multiple of 128 bytes apart: the 16 lanes that the LDS serves per cycle then hit 16
+  // different bank groups whether they belong to one half or to both
+  const int plane = (int)((slot_bound * kPitch + 255) / 256 * 256 + 128);
+  const size_t lds_bytes = 2 * ((size_t)kFragBytes + 2 * (size_t)plane);       // two buffers
+  const int64_t fgroups = a.K / 64;
+  // Workgroups of one size run in rounds of one per slot (two slots per CU), and a partly filled
+  // last round costs about as much as a full one.  Three tiles per wave instead of four (a round
+  // then costs about 3.3 / 4.3 of a full-size one: prologue, epilogue and the filter fragments do
+  // not shrink) win where they save a round's worth: conv6 of the detector trunk at batch 256,
+  // 680 workgroups of four tiles = 2 rounds against 904 of three = 2 cheaper ones (74 -> 69 us);
+  // conv5, conv7 and conv8 stay with four (measured 0 to 3 % slower with three).  Cutting a layer
+  // into whole rounds of full-size workgroups plus a second launch of smaller ones for the rest was
+  // measured too and not kept (conv8 3 % quicker, conv5 and conv6 4 to 6 % slower: the second
+  // launch waits for the first to drain).
+  static const int cus = [] {                                 // (the devices of a process are alike)
+    int device = 0, count = 0;
+    if (hipGetDevice(&device) != hipSuccess ||
+        hipDeviceGetAttribute(&count, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess)
+      return 0;
+    return count;
+  }();
+  const int64_t slots = 2 * (int64_t)(cus > 0 ? cus : 256);
+  auto cost = [&](int mt) {
+    const int64_t wgs = (total + 128 * mt - 1) / (128 * mt) * fgroups;
+    return (double)((wgs + slots - 1) / slots) * (mt + 0.3);
+  };
+  if (tiles == 3 || (tiles != 4 && cost(3) < cost(4))) return launch_tiles<3>(a, total, fgroups, lds_bytes, plane, stream);
+  return launch_tiles<4>(a, total, fgroups, lds_bytes, plane, stream);
 }
 
 }  // namespace bnn

@@ -142,7 +142,8 @@ def test_bnn_entry_points_reject_bad_arguments(lib):
     assert lib.bnn_matrix_path_applies(1, 13, 13, 1024, 1024, 3, 3, 1, 1) == 1
     assert lib.bnn_set_matrix_path(-1) == 0
     assert lib.bnn_matrix_path_applies(256, 13, 13, 1024, 1024, 3, 3, 1, 1) == 0
-    assert lib.bnn_set_matrix_path(2) < 0
+    assert lib.bnn_set_matrix_path(2) < 0 and lib.bnn_set_matrix_path(5) < 0
+    assert lib.bnn_set_matrix_path(3) == 0 and lib.bnn_set_matrix_path(4) == 0
     assert lib.bnn_set_matrix_path(0) == 0
     lib.bnn_pack_weights.argtypes = [ctypes.c_void_p, ctypes.c_void_p, i64, i64, i64, i64, ctypes.c_void_p]
     assert lib.bnn_pack_weights(p, None, 8, 3, 3, 32, None) == -1

@@ -13,12 +13,13 @@ pytestmark = pytest.mark.gpu
 SEED = bw.DEFAULT_SEED
 
 
-@pytest.fixture(scope="module", params=[(0, 0, 0), (7, 1, -1), (8, 2, -1), (13, 2, -1), (0, 0, 1)],
-                ids=["automatic", "tiles-of-7", "tiles-of-8-two-blocks", "tiles-of-13-two-blocks", "matrix-cores"])
+@pytest.fixture(scope="module", params=[(0, 0, 0), (7, 1, -1), (8, 2, -1), (13, 2, -1), (0, 0, 3), (0, 0, 4)],
+                ids=["automatic", "tiles-of-7", "tiles-of-8-two-blocks", "tiles-of-13-two-blocks", "matrix-cores-3-tiles",
+                     "matrix-cores-4-tiles"])
 def bnn(request):
     """Every test runs under the automatic planner, with the tile width / filter blocks per wave
     forced to each instantiated value, and with the matrix-core kernel forced wherever a shape
-    admits it (settings that do not apply to a shape are ignored)."""
+    admits it, in both of its workgroup sizes (settings that do not apply to a shape are ignored)."""
     from paper_1912_04050_amd import bnn as mod
     mod.bnn_set_planner(*request.param[:2])
     mod.bnn_set_matrix_path(request.param[2])
