@@ -175,8 +175,10 @@ int rtc_gpc_step(const rtc_gpc_args* a, void* hip_stream);
  * row is treated as if f[0] were 0).  Computed by ceil(log2(n-1)) squarings g <- g (x) g starting
  * from g = f with g[0] = 0.  rtc_superadditive_closure is the max-plus dual
  * (max instead of min, rtc_maxplus_conv, needs f[0] <= 0).
- * Integer dtypes only (RTC_ERR_DTYPE for RTC_F64): the k-fold sums of a closure have no unique
- * floating-point value, because floating-point addition does not associate.
+ * RTC_F64: a k-fold sum depends on the order of its additions, so the powers are formed as the
+ * definition writes them, one factor at a time from the left (h <- h (x) g, n - 2 products: cubic
+ * in n, meant for short rows); since g[0] = 0 every power lies at or below the one before it, and
+ * the last one is the closure.  Bit for bit the minimum over the powers so formed.
  * f, out: dense [batch][n]; ws needs rtc_workspace_bytes(RTC_OP_CLOSURE, ...). */
 int rtc_subadditive_closure(const void* f, void* out, int64_t batch, int64_t n, rtc_dtype dt, void* ws,
                             size_t ws_bytes, int32_t* dev_flags, void* hip_stream);

@@ -192,11 +192,34 @@ int closure(const void* f, void* out, int64_t batch, int64_t n, int dt, void* ws
             int32_t* dev_flags, hipStream_t stream, bool super) {
   if (f == nullptr || out == nullptr) return RTC_ERR_NULL;
   const size_t es = elem_size(dt);
-  // integer curves only: a k-fold sum has no unique floating-point value (addition does not associate)
-  if (es == 0 || dt == RTC_F64) return RTC_ERR_DTYPE;
+  if (es == 0) return RTC_ERR_DTYPE;
   if (int rc = check_shape(batch, n)) return rc;
   if (!aligned(f, es) || !aligned(out, es) || !aligned(dev_flags, 4) || !aligned(ws, 16)) return RTC_ERR_ALIGN;
   if (ws == nullptr || ws_bytes < rtc_workspace_bytes(RTC_OP_CLOSURE, batch, n, (rtc_dtype)dt)) return RTC_ERR_WORKSPACE;
+  if (dt == RTC_F64) {
+    // Floating point: a k-fold sum depends on the order of its additions, so the powers are formed
+    // as the definition writes them, one factor at a time from the left: h <- h (x) g, n - 2 times,
+    // with g = f, g[0] = 0.  Because g[0] = 0, the candidate s = t of (h (x) g)[t] is h[t] itself:
+    // every power lies below (above, for the max-plus dual) the one before it at every sample, and
+    // the minimum (maximum) over all powers is the last one.  Workspace: g and two curves in turn.
+    const size_t one = ((size_t)batch * n * es + 255) / 256 * 256;
+    char* g = static_cast<char*>(ws);
+    char* buf[2] = {g + one, g + 2 * one};
+    const int64_t products = n > 2 ? n - 2 : 0;
+    return validated([&]() -> int {
+      int rc = launch_closure_init(f, products == 0 ? out : g, batch, n, dt, super, dev_flags, stream);
+      if (rc != RTC_OK) return rc;
+      const void* h = g;
+      for (int64_t j = 0; j < products; ++j) {
+        void* dst = (j == products - 1) ? out : buf[j & 1];
+        rc = launch_tropical(super ? RTC_OP_MAXCONV : RTC_OP_CONV, h, g, dst, batch, n, n, n, dt, nullptr, nullptr, 0,
+                             dev_flags, stream);
+        if (rc != RTC_OK) return rc;
+        h = dst;
+      }
+      return RTC_OK;
+    });
+  }
   int squarings = 0;   // after j squarings every k-fold term with k <= 2^j is covered; k <= n-1 suffices
   while (((int64_t)1 << squarings) < n - 1) ++squarings;
   const size_t half = pingpong_bytes(batch, n, es) / 2;
@@ -315,6 +338,8 @@ size_t rtc_workspace_bytes(int op, int64_t batch, int64_t n, rtc_dtype dt) {
     case RTC_OP_GPC:
       return ((size_t)batch * n * es + 255) / 256 * 256 + prod;
     case RTC_OP_CLOSURE:
+      if (dt == RTC_F64) return 3 * (((size_t)batch * n * es + 255) / 256 * 256);   // g and two powers in turn
+      return 2 * (((size_t)batch * n * es + 255) / 256 * 256) + prod;
     case RTC_OP_CHAIN:
       return 2 * (((size_t)batch * n * es + 255) / 256 * 256) + prod;
     default:

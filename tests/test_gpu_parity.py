@@ -983,11 +983,23 @@ def test_many_tiny_rows(rtc):
 # closures and concatenation
 # ---------------------------------------------------------------------------
 
-def test_closure_rejects_floating_point(rtc):
-    f = torch.zeros((1, 8), dtype=torch.float64, device="cuda")
-    with pytest.raises(rtc.RtcError) as e:
-        rtc.rtc_subadditive_closure(f)
-    assert e.value.status == -3
+def test_closures_fp64_by_definition(rtc):
+    """Floating point: the powers one factor at a time from the left, as the oracle forms them
+    (a squaring schedule would round other sums); tolerance 0."""
+    rng = np.random.default_rng(43)
+    for n in (1, 2, 3, 4, 17, 130, 300):
+        f = np.abs(wl.random_monotone(43, n, 3, n, np.float64, max_inc=9)) + rng.random((3, n))
+        f[1] = rng.permutation(f[1])                       # not monotone
+        f[2, 0] = -3.5                                     # wrong sign at 0: flagged, read as 0
+        flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+        say("closure fp64", n)
+        got = host(rtc.rtc_subadditive_closure(dev(f), dev_flags=flags))
+        want, fl = oracle.closure(f)
+        assert np.array_equal(got, want) and int(host(flags)[0]) == fl == rtc.RTC_FLAG_DOMAIN
+        flags.zero_()
+        got = host(rtc.rtc_superadditive_closure(dev(-f), dev_flags=flags))
+        want, fl = oracle.closure(-f, super_additive=True)
+        assert np.array_equal(got, want) and int(host(flags)[0]) == fl
 
 
 @pytest.mark.parametrize("dtype", [np.int32, np.int64])

@@ -583,6 +583,27 @@ def test_closure_closed_forms(dtype):
     assert fl == 2 and np.array_equal(out[0], want)            # flagged, computed as if f[0] were 0
 
 
+def test_closure_fp64_powers_fall_and_the_last_one_is_the_closure():
+    """Floating point: with g[0] = 0 the candidate s = t of (h (x) g)[t] is h[t] itself, so each
+    power formed from the left lies at or below the one before it at every sample, and the minimum
+    over all powers -- the oracle's result -- is the last power.  (What the GPU path relies on when
+    it returns the (n - 2)-nd iterated product.)"""
+    rng = np.random.default_rng(93)
+    n = 40
+    f = np.cumsum(rng.random(n) * 3)
+    f[5:9] = rng.random(4) * 20                 # not monotone
+    g = f.copy()
+    g[0] = 0.0
+    h = g.copy()
+    for _ in range(n - 2):
+        nxt = oracle.minplus_conv(h[None, :], g[None, :])[0]
+        assert np.all(nxt <= h)
+        h = nxt
+    assert np.array_equal(oracle.closure(f)[0][0], h)
+    # and the max-plus dual on the negated row
+    assert np.array_equal(oracle.closure(-f, super_additive=True)[0][0], -h)
+
+
 def test_superadditive_closure_is_negated_dual():
     rng = np.random.default_rng(92)
     f = -rng.integers(0, 60, 50).astype(np.int64)
