@@ -147,15 +147,8 @@ __global__ __launch_bounds__(256, 2) void bconv_mfma_kernel(const MfmaArgs a, in
     xsrc[j] = a.x + (xreal[j] ? ((n * H + y) * W + x) * Cw : 0);
     xdst[j] = s * kPitch;
   }
-  int wchunk[kFragRounds];
-#pragma unroll
-  for (int j = 0; j < kFragRounds; ++j) {
-    const int c = threadIdx.x + 256 * j;
-    wchunk[j] = c < kFragChunks ? c : c - 128;
-  }
   const v4i* wsrc = reinterpret_cast<const v4i*>(a.wbytes + (int64_t)fg * Cw * kFragBytes);
   xwords xr[kStageRounds];
-  v4i wr[kFragRounds];
   // Fetches are never conditional (a word index past the end is clamped: the values are then
   // staged into a buffer that nobody reads), so that the loop body below is one basic block in
   // which the compiler can place the staging between the matrix instructions.
@@ -164,10 +157,19 @@ __global__ __launch_bounds__(256, 2) void bconv_mfma_kernel(const MfmaArgs a, in
 #pragma unroll
     for (int j = 0; j < kStageRounds; ++j) xr[j] = *reinterpret_cast<const xwords*>(xsrc[j] + c);
   };
-  auto fetch_w = [&](int cw) {
+  // The filter fragments need no unpacking: they go from memory straight into LDS
+  // (global_load_lds_dwordx4: lane l of a wave writes 16 bytes at the wave's LDS base + 16 l), one
+  // wave per run of 64 pieces; the copy is complete for everybody after the copying wave's
+  // s_waitcnt vmcnt(0) and the workgroup's barrier.
+  auto stage_w = [&](int cw, unsigned char* buf) {
     const int c = cw < Cw - 1 ? cw : Cw - 1;
 #pragma unroll
-    for (int j = 0; j < kFragRounds; ++j) wr[j] = wsrc[c * kFragChunks + wchunk[j]];
+    for (int j = 0; j < kFragRounds; ++j) {
+      const int piece0 = 256 * j + 64 * wave;            // (wave-uniform)
+      if (piece0 < kFragChunks)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(wsrc + c * kFragChunks + piece0 + lane),
+                                         (__attribute__((address_space(3))) void*)(buf + piece0 * 16), 16, 0, 0);
+    }
   };
 
   // Two LDS buffers: while the matrix instructions of channel word cw read one, the word cw + 1
@@ -177,7 +179,6 @@ __global__ __launch_bounds__(256, 2) void bconv_mfma_kernel(const MfmaArgs a, in
   // (A staging round beyond the workgroup's slots repeats its last slot: same bytes, same place.)
   const int buf_bytes = kFragBytes + 2 * plane;
   auto stage = [&](int sub, unsigned char* buf) {       // word `sub` of the fetched QC words
-    unsigned char* const bB = buf;
     unsigned char* const bA = buf + kFragBytes;
 #pragma unroll
     for (int j = 0; j < kStageRounds; ++j) {
@@ -192,14 +193,12 @@ __global__ __launch_bounds__(256, 2) void bconv_mfma_kernel(const MfmaArgs a, in
       *reinterpret_cast<uint4*>(bA + xdst[j]) = lo;
       *reinterpret_cast<uint4*>(bA + plane + xdst[j]) = hi;
     }
-#pragma unroll
-    for (int j = 0; j < kFragRounds; ++j) reinterpret_cast<v4i*>(bB)[wchunk[j]] = wr[j];
   };
+  stage_w(0, lds);
   fetch_x(0);
-  fetch_w(0);
   stage(0, lds);
   if constexpr (QC == 1) fetch_x(1);
-  fetch_w(1);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
   for (int cq = 0; cq < Cw; cq += QC) {
@@ -208,9 +207,9 @@ __global__ __launch_bounds__(256, 2) void bconv_mfma_kernel(const MfmaArgs a, in
       const int cw = cq + sub;
       const unsigned char* const curB = lds + (cw & 1) * buf_bytes;
       const unsigned char* const curA = curB + kFragBytes;
+      stage_w(cw + 1, lds + ((cw + 1) & 1) * buf_bytes);
       stage((sub + 1) % QC, lds + ((cw + 1) & 1) * buf_bytes);
       if ((sub + 2) % QC == 0) fetch_x(cw + 2);          // (decided at compile time)
-      fetch_w(cw + 2);
       // operands of tap t + 1 are requested before the matrix instructions of tap t
       v4i bq[2][2], aq[2][MT];
       auto read_tap = [&](int tap, int buf) {
@@ -230,6 +229,7 @@ __global__ __launch_bounds__(256, 2) void bconv_mfma_kernel(const MfmaArgs a, in
           acc[mt][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(aq[tap & 1][mt], bq[tap & 1][1], acc[mt][1], 0, 0, 0);
         }
       }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's share of the next word's fragments has landed
       __syncthreads();                       // reads of this word done, the next word's buffer complete
     }
   }
