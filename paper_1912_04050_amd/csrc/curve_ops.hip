@@ -99,26 +99,17 @@ __device__ __forceinline__ void stage_window(const T* __restrict__ fr, int a, in
 }
 
 // ---- searching the staged window ---------------------------------------------------------------
-// A binary search per query over the whole window costs log2(len) dependent LDS reads for each
-// kind of count.  The queries of a wavefront are neighbours (consecutive samples of a curve), so
-// their answers lie close together; when both kinds of count are asked for,
-//   * the wavefront brackets them with two 64-ary searches for its smallest and largest query
-//     (each lane probes one position per round: two rounds for up to 4096 samples);
-//   * a thread brackets its own queries inside that, by its smallest and largest one;
-//   * each query is then searched in the thread's bracket, a handful of samples.
-// Nothing here assumes that the queries are sorted: the brackets come from minima and maxima.
-// first index in [lo, hi) whose sample is > x (GT) or >= x; hi if there is none
-template <typename T, bool GT>
-__device__ __forceinline__ int first_beyond(const T* s_win, int lo, int hi, T x) {
-  while (lo < hi) {
-    const int mid = (lo + hi) >> 1;
-    const T w = s_win[mid];
-    if (GT ? w > x : w >= x) hi = mid; else lo = mid + 1;
-  }
-  return lo;
-}
+// A binary search per query over the whole window is a chain of log2(len) dependent LDS reads,
+// one query after the other.  Instead the searches of a thread's queries run side by side and
+// without branches (the range is the same for all lanes, so all searches take the same steps),
+// and when both kinds of count are asked for the wavefront first brackets its queries -- they are
+// neighbours, consecutive samples of a curve, so their answers lie close together -- with two
+// 64-ary searches for its smallest and largest one (each lane probes one position per round: two
+// rounds for up to 4096 samples).  Nothing here assumes that the queries are sorted: the bracket
+// comes from a minimum and a maximum.
 
-// the same for a wave-uniform x and a wave-uniform range, by all 64 lanes together
+// first index in [lo, hi) whose sample is > x (GT) or >= x, hi if there is none, for a wave-uniform x
+// and a wave-uniform range, by all 64 lanes together
 template <typename T, bool GT>
 __device__ __forceinline__ int wave_first_beyond(const T* s_win, int lo, int hi, T x) {
   return lo + wave_first_true(hi - lo, [&](int k) { const T w = s_win[lo + k]; return GT ? w > x : w >= x; });
@@ -130,33 +121,48 @@ template <typename T, int PER, int MODE>
 __device__ __forceinline__ void search_window(const T* s_win, int len, const T (&xv)[PER], T wmin, T wmax,
                                               int (&c_lo)[PER], int (&c_up)[PER]) {
   if constexpr (MODE != 2) {
-    // one kind of count: the brackets cost about what they save (measured on rows of 16384 and
-    // 65536 samples, 4- and 8-byte values); with both kinds they pay
+    // One kind of count (the brackets cost about what they save there: measured on rows of 16384
+    // and 65536 samples, 4- and 8-byte values).  The searches of a thread's queries run side by
+    // side, without branches: the window's length is the same for all, so every search takes the
+    // same steps -- largest count `at` with sample at - 1 not beyond the query, found one bit
+    // of `at` at a time from the top -- and the LDS reads of the PER queries are in flight together.
+    int at[PER];
+#pragma unroll
+    for (int e = 0; e < PER; ++e) at[e] = 0;
+    for (int step = len > 0 ? 1 << (31 - __builtin_clz(len)) : 0; step > 0; step >>= 1) {   // (uniform)
+#pragma unroll
+      for (int e = 0; e < PER; ++e) {
+        const int probe = at[e] + step;
+        const T w = s_win[min(probe, len) - 1];
+        const bool below = MODE == 0 ? w < xv[e] : !(w > xv[e]);
+        at[e] = probe <= len && below ? probe : at[e];
+      }
+    }
 #pragma unroll
     for (int e = 0; e < PER; ++e) {
-      if (MODE == 0) c_lo[e] = first_beyond<T, false>(s_win, 0, len, xv[e]);
-      else c_up[e] = first_beyond<T, true>(s_win, 0, len, xv[e]);
+      if (MODE == 0) c_lo[e] = at[e]; else c_up[e] = at[e];
     }
     return;
   }
-  constexpr bool kLowGT = false;         // the lower end of a bracket counts like the lower count (samples < x),
-  constexpr bool kHighGT = true;         // the upper end like the upper one (samples <= x)
-  const int L = wave_first_beyond<T, kLowGT>(s_win, 0, len, wmin);
-  const int H = wave_first_beyond<T, kHighGT>(s_win, L, len, wmax);
-  T tmin = xv[0], tmax = xv[0];
+  // both kinds: the wavefront's bracket first, then all 2 PER searches of a thread side by side
+  // inside it, as above
+  const int L = wave_first_beyond<T, false>(s_win, 0, len, wmin);     // samples below every query of the wave
+  const int H = wave_first_beyond<T, true>(s_win, L, len, wmax);      // samples not above its largest query
+  const int span = H - L;
+  int lo[PER], up[PER];
 #pragma unroll
-  for (int e = 1; e < PER; ++e) { tmin = xv[e] < tmin ? xv[e] : tmin; tmax = vmax(tmax, xv[e]); }
-  const int Lt = first_beyond<T, kLowGT>(s_win, L, H, tmin);
-  const int Ht = first_beyond<T, kHighGT>(s_win, Lt, H, tmax);
+  for (int e = 0; e < PER; ++e) { lo[e] = 0; up[e] = 0; }
+  for (int step = span > 0 ? 1 << (31 - __builtin_clz(span)) : 0; step > 0; step >>= 1) {   // (wave-uniform)
 #pragma unroll
-  for (int e = 0; e < PER; ++e) {
-    if (MODE == 0) c_lo[e] = first_beyond<T, false>(s_win, Lt, Ht, xv[e]);
-    if (MODE == 1) c_up[e] = first_beyond<T, true>(s_win, Lt, Ht, xv[e]);
-    if (MODE == 2) {
-      c_lo[e] = first_beyond<T, false>(s_win, Lt, Ht, xv[e]);
-      c_up[e] = first_beyond<T, true>(s_win, c_lo[e], Ht, xv[e]);
+    for (int e = 0; e < PER; ++e) {
+      const int pl = lo[e] + step, pu = up[e] + step;
+      const T wl = s_win[L + min(pl, span) - 1], wu = s_win[L + min(pu, span) - 1];
+      lo[e] = pl <= span && wl < xv[e] ? pl : lo[e];
+      up[e] = pu <= span && !(wu > xv[e]) ? pu : up[e];
     }
   }
+#pragma unroll
+  for (int e = 0; e < PER; ++e) { c_lo[e] = L + lo[e]; c_up[e] = L + up[e]; }
 }
 
 // Smallest and largest query of the calling wavefront (in all its lanes) and, through s_mm and one
