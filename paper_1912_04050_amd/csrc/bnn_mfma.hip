@@ -45,7 +45,7 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kProfileKind = 32;    // the convolution kernel's kind in the timing record
 constexpr int kPitch = 16;          // bytes per staged pixel and half (16 channels)
-constexpr int kMinChannels = 128;   // below that the vector-ALU kernels keep their filters in registers
+constexpr int kMinChannels = 128;  // below that the vector-ALU kernels keep their filters in registers
 
 // 4 bits -> 4 bytes of +1 (bit set) / -1, or 4 zero bytes.  The multiplication puts bit j of the
 // nibble at bit 8 j (the partial products n << 0, 7, 14, 21 do not collide there); the byte
@@ -281,12 +281,13 @@ void launch_pack_weights_mfma(const int8_t* w, int8_t* bank, int64_t K, int64_t 
 }
 
 // Upper bound of the padded slots that a workgroup's pixels and their taps span: its pixels, one
-// slot per image row and one row of slots per image that it can touch, and a padded row + 1 on
-// either side.
+// slot per end of an image row and one row of slots per end of an image that lie between its
+// first and last pixel, and a padded row + 1 on either side.  (It sizes the LDS buffers: two
+// workgroups per CU need it tight.)
 static int64_t slot_bound(int64_t H, int64_t W) {
   constexpr int kWgPixels = 4 * kTilesPerWave * 32;
-  const int64_t rows_touched = (kWgPixels - 1) / W + 2, images_touched = (kWgPixels - 1) / (H * W) + 2;
-  return kWgPixels + rows_touched + images_touched * (W + 1) + 2 * (W + 2) + 1;
+  const int64_t row_ends = (kWgPixels - 1) / W + 1, image_ends = (kWgPixels - 1) / (H * W) + 1;
+  return kWgPixels + row_ends + image_ends * (W + 1) + 2 * (W + 2) + 1;
 }
 
 bool mfma_slots_fit(int64_t H, int64_t W) { return slot_bound(H, W) <= kMaxSlots; }
