@@ -45,7 +45,8 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kProfileKind = 32;    // the convolution kernel's kind in the timing record
 constexpr int kPitch = 16;          // bytes per staged pixel and half (16 channels)
-constexpr int kMinChannels = 128;  // below that the vector-ALU kernels keep their filters in registers
+constexpr int kMinChannels = 128;   // below that the vector-ALU kernels keep their filters in registers (64 channels on
+                                    // a 52 x 52 map, 128 filters, batch 256: 0.132 ms here against 0.107 ms there)
 
 // 4 bits -> 4 bytes of +1 (bit set) / -1, or 4 zero bytes.  The multiplication puts bit j of the
 // nibble at bit 8 j (the partial products n << 0, 7, 14, 21 do not collide there); the byte
