@@ -67,7 +67,7 @@ def parse():
 # HBM traffic of one launch of the dominant kernel on the headline workload, from two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by what the same counters read for a
 # plain 1 GiB device copy; see profiles/.  None for any other workload.
-HEADLINE_TRAFFIC_BYTES = 789443170   # 211 MiB fetched + 542 MiB of atomic-merge writes (profiles/fused_kernel_headline_pmc.md)
+HEADLINE_TRAFFIC_BYTES = 789538436   # 211 MiB fetched + 542 MiB of atomic-merge writes (profiles/fused_kernel_headline_pmc.md)
 HEADLINE_TRAFFIC_SOURCE = ("profiles/fused_kernel_headline_pmc.md: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, "
                            "scaled by a 1 GiB device copy; a stored figure, not measured in this run")
 
@@ -421,7 +421,7 @@ def per_config_table(seed, peak_ops, with_cpu, configs=(1, 2, 3, 4, 5)):
 # HBM traffic of one launch of the dominant kernel of --bnn (conv8 at batch 256), measured like
 # HEADLINE_TRAFFIC_BYTES; see profiles/.  None until measured / for any other batch.
 BNN_TRAFFIC_BYTES = 40876675   # 33.7 MiB fetched + 5.3 MiB written (profiles/bconv_lds_kernel_conv8_pmc.md)
-BNN_MFMA_TRAFFIC_BYTES = 102717097   # fetched + written (profiles/bconv_mfma_kernel_conv8_pmc.md)
+BNN_MFMA_TRAFFIC_BYTES = 102725445   # fetched + written (profiles/bconv_mfma_kernel_conv8_pmc.md)
 
 
 def bnn_main(args):
