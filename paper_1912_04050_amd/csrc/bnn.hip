@@ -508,7 +508,12 @@ __global__ __launch_bounds__(64) void bconv_resident_kernel(
 // j then holds tile A's packed word in its low half and tile B's in its high half.  No filter
 // row is skipped (the halves may sit in different output rows): rows and columns outside the
 // image are read as zero words and corrected alike.  Stride 1, WORDS = PS * CW <= 32.
-template <int R, int S, int CW, int TM>
+// PAIR (one word per pixel of at most 16 channels, S = 3): the upper half of every activation and
+// filter word is padding, zero in both, so the taps (r, 0) and (r, 1) share one xor + popcount:
+// the strip is staged a second time with each word's right neighbour in its upper half, the
+// filters pair their taps the same way, and a filter row costs two instruction pairs per pixel
+// instead of three.
+template <int R, int S, int CW, int TM, bool PAIR>
 __global__ __launch_bounds__(64) void bconv_resident_half_kernel(
     const uint32_t* __restrict__ x, const uint32_t* __restrict__ w, const float* __restrict__ xi,
     const float* __restrict__ gamma, int32_t* __restrict__ out_x1, uint32_t* __restrict__ out_x4, const ConvArgs dims) {
@@ -519,7 +524,9 @@ __global__ __launch_bounds__(64) void bconv_resident_half_kernel(
   constexpr int QUADS = (WORDS + 3) / 4;
   if (WORDS > 32) return;                        // the host never launches such a shape
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  static_assert(!PAIR || (CW == 1 && S == 3), "pairing is for one half-filled word per pixel and three taps per row");
   __shared__ __align__(16) uint32_t line[R][64];
+  __shared__ __align__(16) uint32_t linep[PAIR ? R : 1][64];   // word i | word i + 1 << 16
   const int lane = threadIdx.x, half = lane >> 5, l32 = lane & 31;
   const int chunk = blockIdx.x % p.waves_per_image;
   const int n = blockIdx.x / p.waves_per_image;
@@ -534,6 +541,9 @@ __global__ __launch_bounds__(64) void bconv_resident_half_kernel(
     for (int s = 0; s < S; ++s)
 #pragma unroll
       for (int q = 0; q < CW; ++q) wreg[r][s][q] = (p.w + (uint32_t)((r * S + s) * CW + q) * (uint32_t)p.Kp)[k];
+  uint32_t wpair[R];                             // PAIR: taps (r, 0) and (r, 1) in one word
+#pragma unroll
+  for (int r = 0; r < R; ++r) wpair[r] = PAIR ? wreg[r][0][0] | (wreg[r][S > 1 ? 1 : 0][0] << 16) : 0u;
   const Decision d = make_decision(p, k, S);
   uint32_t popv[R][S];                           // popcount of each tap of this lane's filter (border corrections)
 #pragma unroll
@@ -576,7 +586,11 @@ __global__ __launch_bounds__(64) void bconv_resident_half_kernel(
     if (t + 2 < t_end) fetch(nxt, half ? hoB2 : hoA2, half ? wtB2 : wtA2, half == 0 || t + 3 < t_end);
 
 #pragma unroll
-    for (int r = 0; r < R; ++r) line[r][lane] = cur[r];
+    for (int r = 0; r < R; ++r) {
+      line[r][lane] = cur[r];
+      // (the neighbour of a half's last lane belongs to the other tile: no pixel of a tile reads that far)
+      if constexpr (PAIR) linep[r][lane] = cur[r] | ((uint32_t)__shfl_down((int)cur[r], 1) << 16);
+    }
     __syncthreads();                             // one wave: orders the LDS writes before the reads
     uint32_t acc[TM];
 #pragma unroll
@@ -586,15 +600,26 @@ __global__ __launch_bounds__(64) void bconv_resident_half_kernel(
       u32x4 a[QUADS];                            // the same value in every lane of a half
 #pragma unroll
       for (int v = 0; v < QUADS; ++v) a[v] = reinterpret_cast<const u32x4*>(&line[r][half * 32])[v];
+      if constexpr (PAIR) {
+        u32x4 ap[QUADS];
 #pragma unroll
-      for (int s = 0; s < S; ++s)
+        for (int v = 0; v < QUADS; ++v) ap[v] = reinterpret_cast<const u32x4*>(&linep[r][half * 32])[v];
 #pragma unroll
-        for (int j = 0; j < TM; ++j)
+        for (int j = 0; j < TM; ++j) {
+          popcount_accumulate(acc[j], ap[j / 4][j % 4] ^ wpair[r]);
+          popcount_accumulate(acc[j], a[(j + 2) / 4][(j + 2) % 4] ^ wreg[r][2][0]);
+        }
+      } else {
 #pragma unroll
-          for (int q = 0; q < CW; ++q) {
-            const int word = (j + s) * CW + q;
-            popcount_accumulate(acc[j], a[word / 4][word % 4] ^ wreg[r][s][q]);
-          }
+        for (int s = 0; s < S; ++s)
+#pragma unroll
+          for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int q = 0; q < CW; ++q) {
+              const int word = (j + s) * CW + q;
+              popcount_accumulate(acc[j], a[word / 4][word % 4] ^ wreg[r][s][q]);
+            }
+      }
     }
     __syncthreads();                             // reads done before the next pair's writes
 
@@ -744,7 +769,15 @@ bool launch_resident(const ConvArgs& a, int R, int S, int stride, int tm, uint32
 template <int R, int S, int CW, int TM>
 void launch_resident_half_one(const ConvArgs& a, uint32_t blocks, hipStream_t stream) {
   rtc::prof_begin(kProfileKind, stream);
-  RTC_LAUNCH((bconv_resident_half_kernel<R, S, CW, TM>), dim3(blocks), dim3(64), 0, stream, a.x, a.w, a.xi, a.gamma,
+  if constexpr (CW == 1 && S == 3) {
+    if (a.C <= 16) {                              // half-filled words: two taps per instruction pair
+      RTC_LAUNCH((bconv_resident_half_kernel<R, S, CW, TM, true>), dim3(blocks), dim3(64), 0, stream, a.x, a.w, a.xi,
+                 a.gamma, a.out_x1, a.out_x4, a);
+      rtc::prof_end(stream);
+      return;
+    }
+  }
+  RTC_LAUNCH((bconv_resident_half_kernel<R, S, CW, TM, false>), dim3(blocks), dim3(64), 0, stream, a.x, a.w, a.xi, a.gamma,
                      a.out_x1, a.out_x4, a);
   rtc::prof_end(stream);
 }

@@ -73,6 +73,14 @@ def test_channel_counts(bnn, C):
     assert 0.1 < ones < 0.9
 
 
+@pytest.mark.parametrize("shape", [(16, 32), (16, 7), (5, 32), (11, 20), (1, 3)])
+def test_few_channels_few_filters(bnn, shape):
+    """At most 16 channels and 32 filters: the two-tiles-per-wave kernel pairs two taps per word
+    (the upper half of every word is padding); rows wide enough for interior and border tiles."""
+    C, K = shape
+    check_layer(bnn, 150 + C + K, 2, 9, 31, C, K, 3, 3, 1, 1)
+
+
 @pytest.mark.parametrize("K", [1, 8, 31, 32, 33, 64, 65, 96, 130, 512])
 def test_filter_counts(bnn, K):
     """Filters below, at and above the 64 lanes of a wave; ragged output words."""
