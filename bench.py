@@ -421,7 +421,7 @@ def per_config_table(seed, peak_ops, with_cpu, configs=(1, 2, 3, 4, 5)):
 # HBM traffic of one launch of the dominant kernel of --bnn (conv8 at batch 256), measured like
 # HEADLINE_TRAFFIC_BYTES; see profiles/.  None until measured / for any other batch.
 BNN_TRAFFIC_BYTES = 40876675   # 33.7 MiB fetched + 5.3 MiB written (profiles/bconv_lds_kernel_conv8_pmc.md)
-BNN_MFMA_TRAFFIC_BYTES = 102725445   # fetched + written (profiles/bconv_mfma_kernel_conv8_pmc.md)
+BNN_MFMA_TRAFFIC_BYTES = 102649480   # fetched + written (profiles/bconv_mfma_kernel_conv8_pmc.md)
 
 
 def bnn_main(args):
