@@ -96,6 +96,45 @@ def gpu_ms(fn, warm=3, reps=10):
     return ts[len(ts) // 2], ts[0]
 
 
+def measured_sclk_mhz(fn, seconds=0.6):
+    """Average shader clock while fn() runs back to back for about `seconds`: the driver's current-clock
+    line of pp_dpm_sclk (the one marked '*'), sampled from a host thread every few milliseconds.  None
+    where the file is not readable."""
+    import glob
+    import threading
+    import time
+    import torch
+    paths = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
+    if not paths:
+        return None
+    samples, stop = [], threading.Event()
+
+    def sample():
+        while not stop.is_set():
+            try:
+                with open(paths[0]) as fh:
+                    for ln in fh:
+                        if "*" in ln:
+                            samples.append(float(ln.split(":")[1].lower().split("mhz")[0]))
+            except (OSError, ValueError, IndexError):
+                return
+            time.sleep(0.003)
+
+    fn()
+    torch.cuda.synchronize()
+    th = threading.Thread(target=sample, daemon=True)
+    t0 = time.time()
+    th.start()
+    while time.time() - t0 < seconds:
+        for _ in range(8):
+            fn()
+        torch.cuda.synchronize()
+    stop.set()
+    th.join(timeout=1.0)
+    busy = samples[len(samples) // 5:]          # the first samples may still show the idle clock
+    return sum(busy) / len(busy) if busy else None
+
+
 def gpu_ms_back_to_back(fn, calls=50, reps=5):
     """Per-call time of `calls` invocations enqueued without a host wait in between (median over
     reps): what a call costs once the host's submission overlaps the device's work."""
@@ -971,6 +1010,9 @@ def main():
         instr, ceiling_pair_ops = 1.5, lane_rate / 1.5
     peak = 2.0 * ceiling_pair_ops
     units = max(1, sum(census[:4]))
+    # secondary figure: the same fraction against the clock the chip actually ran at during the product
+    conv_out = torch.empty_like(f)
+    sclk = None if args.only else measured_sclk_mhz(lambda: rtc.rtc_minplus_conv(f, g, out=conv_out, ws=ws))
     roofline = {
         "bound": "alu", "kernel": "fused_kernel<out int64, min-plus> (packed 16-bit work items + 32-bit work items in one launch)",
         "achieved": round(achieved / 1e12, 4), "peak": round(peak / 1e12, 4), "unit": "TOP/s",
@@ -980,6 +1022,8 @@ def main():
         "pair_ops_per_launch": B * pair_ops_one,
         "gpair_ops_per_s": round(B * pair_ops_one / (conv_ms * 1e-3) / 1e9, 2),
         "valu_instr_per_pair_op": round(instr, 4),
+        "measured_clock_mhz": round(sclk, 1) if sclk else None,
+        "frac_at_measured_clock": round(achieved / peak * (info["clock_khz"] / 1e3) / sclk, 4) if sclk else None,
         "arithmetic_shares": {"packed 15-bit, chunk base (0.5 instr/pair-op)": round(census[0] / units, 4),
                               "packed 15-bit, sub-chunk bases (0.5)": round(census[1] / units, 4),
                               "packed 16-bit saturating (1.0)": round(census[2] / units, 4),
