@@ -542,6 +542,7 @@ def bnn_main(args):
     dom_ms = per_layer[-1]["kernel_ms"]
     on_matrix = bnn.bnn_matrix_path_applies(N, dom["hw"], dom["hw"], dom["C"], dom["K"])
     shape = f"{dom['name']}: {dom['hw']}x{dom['hw']} map, {dom['C']} -> {dom['K']} channels"
+    sclk = measured_sclk_mhz(lambda: run_layer(dom))     # the shader clock while this layer runs back to back
     if on_matrix:
         # +1 / -1 as int8 on v_mfma_i32_32x32x32_i8: 2 operations per multiply-accumulate against the published
         # dense int8 peak
@@ -550,6 +551,8 @@ def bnn_main(args):
                     "achieved": round(achieved / 1e12, 1), "peak": 5000.0, "unit": "TOP/s", "frac": round(achieved / 5e15, 4),
                     "traffic": BNN_MFMA_TRAFFIC_BYTES if N == 256 and dom["name"] == "conv8" else None,
                     "launch_ms": dom_ms, "macs_per_launch": dom["macs"], "tmac_per_s": round(dom["macs"] / dom_ms / 1e9, 1),
+                    "measured_clock_mhz": round(sclk, 1) if sclk else None,
+                    "frac_at_measured_clock": round(achieved / 5e15 * (info["clock_khz"] / 1e3) / sclk, 4) if sclk else None,
                     "note": "int8 dense peak 5.0 POP/s = 2500 TMAC/s at 2.4 GHz; a loop of nothing but this instruction on "
                             "random +-1 operands measured 1770-1980 TMAC/s on this chip (sustained clock 1.75-1.95 GHz); "
                             "the vector-ALU kernel of the same layer (--bnn-matrix -1) is bounded by 629 TMAC/s"}
