@@ -463,7 +463,7 @@ BNN_TRAFFIC_BYTES = 40876675   # 33.7 MiB fetched + 5.3 MiB written (profiles/bc
 BNN_MFMA_TRAFFIC_BYTES = 102649480   # fetched + written (profiles/bconv_mfma_kernel_conv8_pmc.md)
 
 
-def bnn_main(args):
+def bnn_line(args):
     """One step = the seven binary layers of the detector trunk (3x3, stride 1, padding 1) on a
     batch of synthetic images: xor / popcount convolution with the integrated threshold,
     binarisation and packing, packed activations in, packed activations out.  Layers are timed on
@@ -610,7 +610,11 @@ def bnn_main(args):
             "config": {"workload": f"binary layers conv2..conv8 of a 416x416 single-shot detector trunk, batch {N}, "
                                    "3x3 / stride 1 / padding 1, packed NHWC in and out", "batch": N, "seed": seed},
             "per_layer": per_layer, "roofline": roofline, "cpu_baseline": cpu_baseline, "parity": parity}
-    print(json.dumps(line))
+    return line
+
+
+def bnn_main(args):
+    print(json.dumps(bnn_line(args)))
 
 
 def copy_rate_gbs(mib=1024):
@@ -1048,6 +1052,7 @@ def main():
     # ---- HBM-bound operators against a device copy measured in the same run -----------------
     hbm = None
     per_config = None
+    binary_layer = None
     if not args.only:
         w = 8
         copy_gbs = copy_rate_gbs()
@@ -1078,6 +1083,20 @@ def main():
                                        "beta^l, alpha^u and gamma^u read once, beta'^l and two int32 index rows written once"})
         if not args.no_configs:
             per_config = compact_configs(seed, lane_rate, copy_gbs)
+            # the paper's binary convolution layer (bench.py --bnn has the full line): the detector trunk at batch
+            # 256, a few steps, the oracle on a short sample
+            import copy
+            b_args = copy.copy(args)
+            b_args.steps, b_args.warmup, b_args.bnn_batch, b_args.bnn_layers = 5, 2, 256, ""
+            b_args.cpu_seconds = min(args.cpu_seconds, 3.0)
+            bl = bnn_line(b_args)
+            binary_layer = {"metric": bl["metric"], "value": bl["value"], "unit": bl["unit"], "ms_per_step": bl["ms_per_step"],
+                            "workload": bl["config"]["workload"], "dtype": bl["dtype"],
+                            "per_layer": [{k: r[k] for k in ("layer", "kernel", "kernel_ms", "tmac_per_s")} for r in bl["per_layer"]],
+                            "roofline": {k: bl["roofline"][k] for k in ("bound", "kernel", "achieved", "peak", "unit", "frac",
+                                                                        "traffic", "launch_ms", "measured_clock_mhz",
+                                                                        "frac_at_measured_clock") if k in bl["roofline"]},
+                            "cpu_baseline": bl["cpu_baseline"], "parity": bl["parity"]}
 
     # ---- sampled parity + CPU baseline (the oracle as it stands, on this machine's host cores) --
     parity = None
@@ -1125,7 +1144,8 @@ def main():
                        "convolution alone is roofline.gpair_ops_per_s (kernel) and pair_ops_per_launch / call_ms (call)",
         "conv_call_gpair_ops_per_s": round(B * pair_ops_one / (conv_call_ms * 1e-3) / 1e9, 2),
         "pct_valu_peak": round(100.0 * achieved / lane_rate, 2),
-        "roofline": roofline, "hbm": hbm, "per_config": per_config, "cpu_baseline": cpu_baseline, "parity": parity,
+        "roofline": roofline, "hbm": hbm, "per_config": per_config, "binary_layer": binary_layer,
+        "cpu_baseline": cpu_baseline, "parity": parity,
     }
     if args.all_configs:
         wanted = tuple(int(k) for k in args.configs.split(",")) if args.configs else (1, 2, 3, 4, 5)
