@@ -302,20 +302,35 @@ __global__ __launch_bounds__(256) void pinv_kernel(const T* __restrict__ f, int 
   }
 }
 
+// Four elements per thread, a block of 256 apart: the index loads of all four travel together,
+// then the four gathers.
+constexpr int kComposePerThread = 4;
+constexpr int kComposePerBlock = 256 * kComposePerThread;
+
 template <typename T>
 __global__ __launch_bounds__(256) void compose_kernel(const T* __restrict__ outer, int n_outer,
                                                       const int32_t* __restrict__ inner, int n,
                                                       T* __restrict__ out, int blocks_per_row,
                                                       int32_t* __restrict__ dev_flags) {
   const int row = blockIdx.x / blocks_per_row;
-  const int d = (blockIdx.x % blocks_per_row) * 256 + threadIdx.x;
+  const int d0 = (blockIdx.x % blocks_per_row) * kComposePerBlock + threadIdx.x;
+  const int32_t* in = inner + (int64_t)row * n;
+  const T* o = outer + (int64_t)row * n_outer;
+  int k[kComposePerThread];
+#pragma unroll
+  for (int e = 0; e < kComposePerThread; ++e) k[e] = in[min(d0 + e * 256, n - 1)];   // past the end: the last index again
   bool clamped = false;
-  if (d < n) {
-    int k = inner[(int64_t)row * n + d];
-    if (k < 0) { k = 0; clamped = true; }
-    if (k > n_outer - 1) { k = n_outer - 1; clamped = true; }
-    out[(int64_t)row * n + d] = outer[(int64_t)row * n_outer + k];
+  T v[kComposePerThread];
+#pragma unroll
+  for (int e = 0; e < kComposePerThread; ++e) {
+    const bool real = d0 + e * 256 < n;
+    if (k[e] < 0) { k[e] = 0; clamped |= real; }
+    if (k[e] > n_outer - 1) { k[e] = n_outer - 1; clamped |= real; }
+    v[e] = o[k[e]];
   }
+#pragma unroll
+  for (int e = 0; e < kComposePerThread; ++e)
+    if (d0 + e * 256 < n) out[(int64_t)row * n + d0 + e * 256] = v[e];
   if (dev_flags != nullptr && __any(clamped)) {
     if ((threadIdx.x & 63) == 0) atomicOr(dev_flags, RTC_FLAG_DOMAIN);
   }
@@ -704,7 +719,7 @@ int pinv_typed(const void* f, int64_t n, const void* x, int64_t m, int32_t* out,
 template <typename T>
 int compose_typed(const void* outer, int64_t n_outer, const int32_t* inner, int64_t n, void* out,
                   int64_t batch, int32_t* dev_flags, hipStream_t stream) {
-  const int64_t bpr = (n + 255) / 256;
+  const int64_t bpr = (n + kComposePerBlock - 1) / kComposePerBlock;
   if (bpr * batch > 0x7fffffffLL) return RTC_ERR_SHAPE;
   RTC_LAUNCH(compose_kernel<T>, dim3((uint32_t)(bpr * batch)), dim3(256), 0, stream,
                      static_cast<const T*>(outer), (int)n_outer, inner, (int)n, static_cast<T*>(out),
