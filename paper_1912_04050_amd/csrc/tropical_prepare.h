@@ -194,6 +194,50 @@ __device__ __forceinline__ int64_t detrended(int64_t v, int64_t v0, int64_t slop
   return wrap_sub(wrap_sub(v, v0), (int64_t)((uint64_t)slope * (uint64_t)i));
 }
 
+// Extrema (plain and, with `lines`, with the common slope removed) and shape bits of the samples
+// [i_begin, i_end) of one int64 row pair, for the calling thread's share: four strides of the
+// workgroup per trip, their loads in flight together (one stride per trip is one round trip to
+// memory per trip).  A stride past the end repeats the segment's last sample, which changes
+// neither an extremum nor a shape bit.
+__device__ __forceinline__ void probe_samples(const int64_t* __restrict__ fr, const int64_t* __restrict__ gr, int i_begin,
+                                              int i_end, int n, bool lines, int64_t f0, int64_t g0, int64_t slope,
+                                              int64_t& fmin, int64_t& fmax, int64_t& gmin, int64_t& gmax,
+                                              int64_t& dfmin, int64_t& dfmax, int64_t& dgmin, int64_t& dgmax, int& bits) {
+  constexpr int kTrip = 4;
+  for (int i0 = i_begin + (int)threadIdx.x; i0 < i_end; i0 += kTrip * (int)blockDim.x) {
+    int64_t fv[kTrip], gv[kTrip];
+#pragma unroll
+    for (int k = 0; k < kTrip; ++k) {
+      const int i = min(i0 + k * (int)blockDim.x, i_end - 1);
+      fv[k] = fr[i]; gv[k] = gr[i];
+    }
+#pragma unroll
+    for (int k = 0; k < kTrip; ++k) {
+      fmin = sel_min(fmin, fv[k]); fmax = sel_max(fmax, fv[k]);
+      gmin = sel_min(gmin, gv[k]); gmax = sel_max(gmax, gv[k]);
+    }
+    if (lines) {
+#pragma unroll
+      for (int k = 0; k < kTrip; ++k) {
+        const int i = min(i0 + k * (int)blockDim.x, i_end - 1);
+        const int64_t fd = detrended(fv[k], f0, slope, i), gd = detrended(gv[k], g0, slope, i);
+        dfmin = sel_min(dfmin, fd); dfmax = sel_max(dfmax, fd);
+        dgmin = sel_min(dgmin, gd); dgmax = sel_max(dgmax, gd);
+      }
+    }
+    if (bits != 0 && n >= 3) {
+      int b[kTrip];
+#pragma unroll
+      for (int k = 0; k < kTrip; ++k) {
+        const int i = min(max(min(i0 + k * (int)blockDim.x, i_end - 1), 1), n - 2);   // interior samples only
+        b[k] = second_diff_bits(fr, i) | (second_diff_bits(gr, i) << 2);
+      }
+#pragma unroll
+      for (int k = 0; k < kTrip; ++k) bits &= b[k];
+    }
+  }
+}
+
 // First half of the range probe of long int64 rows: extrema and shape bits of one segment of
 // one row pair, [fmin, fmax, gmin, gmax, bits] at partial[(row * segs + seg) * 5].
 __global__ __launch_bounds__(1024) void probe_partial_kernel(const int64_t* __restrict__ f, int64_t stride_f,
@@ -212,17 +256,7 @@ __global__ __launch_bounds__(1024) void probe_partial_kernel(const int64_t* __re
   const bool lines = worth_detrending(fr, gr, n);
   const int64_t f0 = fr[0], g0 = gr[0], slope = lines ? common_slope(fr, gr, n) : 0;   // (64-bit divisions: not for nothing)
   int bits = structure ? 15 : 0;
-  for (int i = i_begin + threadIdx.x; i < i_end; i += blockDim.x) {
-    const int64_t fv = fr[i], gv = gr[i];
-    fmin = sel_min(fmin, fv); fmax = sel_max(fmax, fv);
-    gmin = sel_min(gmin, gv); gmax = sel_max(gmax, gv);
-    if (lines) {
-      const int64_t fd = detrended(fv, f0, slope, i), gd = detrended(gv, g0, slope, i);
-      dfmin = sel_min(dfmin, fd); dfmax = sel_max(dfmax, fd);
-      dgmin = sel_min(dgmin, gd); dgmax = sel_max(dgmax, gd);
-    }
-    if (bits != 0 && i >= 1 && i <= n - 2) bits &= second_diff_bits(fr, i) | (second_diff_bits(gr, i) << 2);
-  }
+  probe_samples(fr, gr, i_begin, i_end, n, lines, f0, g0, slope, fmin, fmax, gmin, gmax, dfmin, dfmax, dgmin, dgmax, bits);
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) {
     fmin = sel_min(fmin, __shfl_xor(fmin, off)); fmax = sel_max(fmax, __shfl_xor(fmax, off));
@@ -308,17 +342,8 @@ __global__ __launch_bounds__(1024) void probe_narrow_kernel(const int64_t* __res
       dgmin = sel_min(dgmin, q[7]); dgmax = sel_max(dgmax, q[8]);
     }
   }
-  for (int i = threadIdx.x; partial == nullptr && i < n; i += blockDim.x) {
-    const int64_t fv = fr[i], gv = gr[i];
-    fmin = sel_min(fmin, fv); fmax = sel_max(fmax, fv);
-    gmin = sel_min(gmin, gv); gmax = sel_max(gmax, gv);
-    if (lines) {
-      const int64_t fd = detrended(fv, f0, slope, i), gd = detrended(gv, g0, slope, i);
-      dfmin = sel_min(dfmin, fd); dfmax = sel_max(dfmax, fd);
-      dgmin = sel_min(dgmin, gd); dgmax = sel_max(dgmax, gd);
-    }
-    if (bits != 0 && i >= 1 && i <= n - 2) bits &= second_diff_bits(fr, i) | (second_diff_bits(gr, i) << 2);
-  }
+  if (partial == nullptr)
+    probe_samples(fr, gr, 0, n, n, lines, f0, g0, slope, fmin, fmax, gmin, gmax, dfmin, dfmax, dgmin, dgmax, bits);
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) {
     fmin = sel_min(fmin, __shfl_xor(fmin, off)); fmax = sel_max(fmax, __shfl_xor(fmax, off));
@@ -395,15 +420,22 @@ __global__ __launch_bounds__(1024) void probe_narrow_kernel(const int64_t* __res
   if (s_narrow) {
     const int64_t fb = s_base[0], gb = s_base[1];
     const uint64_t rho_row = (uint64_t)s_base[2];
-    if (rho_row == 0) {
-      for (int i = i_begin + threadIdx.x; i < i_end; i += blockDim.x) {
-        f32[(int64_t)row * n + i] = (int32_t)(fr[i] - fb);
-        g32[(int64_t)row * n + i] = (int32_t)(gr[i] - gb);
+    // (rho_row = 0 when the rows are narrow as they are.)  Four strides per trip, loads first.
+    constexpr int kTrip = 4;
+    for (int i0 = i_begin + (int)threadIdx.x; i0 < i_end; i0 += kTrip * (int)blockDim.x) {
+      int64_t fv[kTrip], gv[kTrip];
+#pragma unroll
+      for (int k = 0; k < kTrip; ++k) {
+        const int i = min(i0 + k * (int)blockDim.x, i_end - 1);
+        fv[k] = fr[i]; gv[k] = gr[i];
       }
-    } else {
-      for (int i = i_begin + threadIdx.x; i < i_end; i += blockDim.x) {
-        f32[(int64_t)row * n + i] = (int32_t)(uint32_t)((uint64_t)fr[i] - (uint64_t)fb - rho_row * (uint64_t)i);
-        g32[(int64_t)row * n + i] = (int32_t)(uint32_t)((uint64_t)gr[i] - (uint64_t)gb - rho_row * (uint64_t)i);
+#pragma unroll
+      for (int k = 0; k < kTrip; ++k) {
+        const int i = i0 + k * (int)blockDim.x;
+        if (i < i_end) {
+          f32[(int64_t)row * n + i] = (int32_t)(uint32_t)((uint64_t)fv[k] - (uint64_t)fb - rho_row * (uint64_t)i);
+          g32[(int64_t)row * n + i] = (int32_t)(uint32_t)((uint64_t)gv[k] - (uint64_t)gb - rho_row * (uint64_t)i);
+        }
       }
     }
   }
@@ -447,15 +479,21 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(const int32_t* __res
   int32_t adv[kPer], bdv[kPer];
 #pragma unroll
   for (int k = 0; k < kPer; ++k) {
+    // all eight loads are issued before the first is used (a load under its own bounds check is
+    // waited for on the spot): positions beyond the row's end read its last sample and drop it
+    const int ic = min(c * kPkChunk + k * kPrepThreads + (int)threadIdx.x, n - 1);
+    adv[k] = a[(int64_t)row * stride_a + ic];
+    bdv[k] = b[(int64_t)row * stride_b + (deconv ? n - 1 - ic : ic)];
+  }
+#pragma unroll
+  for (int k = 0; k < kPer; ++k) {
     const int i = c * kPkChunk + k * kPrepThreads + threadIdx.x;
     const bool valid = i < n;
-    adv[k] = valid ? wrap_sub(a[(int64_t)row * stride_a + i], r * i) : 0;
+    adv[k] = valid ? wrap_sub(adv[k], r * i) : 0;
     if (neg) adv[k] = wrap_sub(0, adv[k]);   // max-plus convolution / min-plus deconvolution: see packed_body
     // positions beyond the row's end are packed as 0: every window position that meets them is
     // poison, which decides the outcome whatever the uniform value
-    bdv[k] = 0;
-    if (valid) bdv[k] = deconv ? wrap_add(b[(int64_t)row * stride_b + (n - 1 - i)], r * i)
-                               : wrap_sub(b[(int64_t)row * stride_b + i], r * i);
+    bdv[k] = !valid ? 0 : deconv ? wrap_add(bdv[k], r * i) : wrap_sub(bdv[k], r * i);
   }
 #pragma unroll
   for (int k = 0; k < kPer; ++k) {
