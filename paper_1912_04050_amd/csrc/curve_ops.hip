@@ -18,6 +18,11 @@ template <typename T> __device__ __forceinline__ T lowest() {
 }
 
 // Lower pseudo-inverse: first index with f[k] >= x (n if none).  f nondecreasing.
+template <typename T> __device__ __forceinline__ T highest() {
+  if constexpr (std::numeric_limits<T>::has_infinity) return __builtin_huge_val();
+  else return std::numeric_limits<T>::max();
+}
+
 template <typename T>
 __device__ __forceinline__ int lower_index(const T* __restrict__ f, int n, T x) {
   int lo = 0, hi = n;
@@ -79,8 +84,9 @@ __device__ __forceinline__ int wave_first_true(int n, Pred pred) {
 // before the first one is waited for.  A loop of "load, store to LDS" is compiled into one round
 // trip per iteration: the store waits for its own load.  The barrier in the instruction stream
 // between the two phases keeps the compiler from sinking the loads back into the stores' blocks.
+// Entries [len, padded) of s_win (padded <= WINDOW, uniform) are set to the largest value of the type.
 template <typename T, int THREADS, int WINDOW>
-__device__ __forceinline__ void stage_window(const T* __restrict__ fr, int a, int len, T* s_win) {
+__device__ __forceinline__ void stage_window(const T* __restrict__ fr, int a, int len, T* s_win, int padded = 0) {
   constexpr int K = (WINDOW + THREADS - 1) / THREADS;
   T tmp[K];
 #pragma unroll
@@ -95,8 +101,15 @@ __device__ __forceinline__ void stage_window(const T* __restrict__ fr, int a, in
   for (int k = 0; k < K; ++k) {
     const int i = k * THREADS + (int)threadIdx.x;
     if (i < len) s_win[i] = tmp[k];
+    else if (i < padded) s_win[i] = highest<T>();
   }
 }
+
+// The search of one kind of count (search_window, MODE 0 and 1) wants the window padded with the
+// largest value up to one entry short of the power of two above its length: then no probe needs
+// a bounds check.  padded_length(len) is that length; it fits the window for len < WINDOW.
+__device__ __forceinline__ int pow2_above(int len) { return len > 0 ? 2 << (31 - __builtin_clz(len)) : 1; }
+__device__ __forceinline__ int padded_length(int len) { return pow2_above(len) - 1; }
 
 // ---- searching the staged window ---------------------------------------------------------------
 // A binary search per query over the whole window is a chain of log2(len) dependent LDS reads,
@@ -126,21 +139,26 @@ __device__ __forceinline__ void search_window(const T* s_win, int len, const T (
     // side, without branches: the window's length is the same for all, so every search takes the
     // same steps -- largest count `at` with sample at - 1 not beyond the query, found one bit
     // of `at` at a time from the top -- and the LDS reads of the PER queries are in flight together.
+    // The window is padded (padded_length) with the largest value, which is beyond every query
+    // (or equal to it and counted, for a query that is that value: hence the min at the end), so
+    // a step is an add, a read, a compare and a select; counts are kept as byte offsets.
+    constexpr int kBytes = (int)sizeof(T);
     int at[PER];
 #pragma unroll
     for (int e = 0; e < PER; ++e) at[e] = 0;
-    for (int step = len > 0 ? 1 << (31 - __builtin_clz(len)) : 0; step > 0; step >>= 1) {   // (uniform)
+    for (int step = pow2_above(len) * (kBytes / 2); step >= kBytes; step >>= 1) {   // (uniform)
 #pragma unroll
       for (int e = 0; e < PER; ++e) {
         const int probe = at[e] + step;
-        const T w = s_win[min(probe, len) - 1];
+        const T w = *reinterpret_cast<const T*>(reinterpret_cast<const char*>(s_win) + probe - kBytes);
         const bool below = MODE == 0 ? w < xv[e] : !(w > xv[e]);
-        at[e] = probe <= len && below ? probe : at[e];
+        at[e] = below ? probe : at[e];
       }
     }
 #pragma unroll
     for (int e = 0; e < PER; ++e) {
-      if (MODE == 0) c_lo[e] = at[e]; else c_up[e] = at[e];
+      const int c = min((int)((unsigned)at[e] / (unsigned)kBytes), len);
+      if (MODE == 0) c_lo[e] = c; else c_up[e] = c;
     }
     return;
   }
@@ -194,14 +212,17 @@ __device__ __forceinline__ void query_range(const T (&xv)[PER], T (*s_mm)[THREAD
 // three round trips each; a stretch longer than WINDOW (queries that are not clustered) falls back
 // to the plain search per thread.  THREADS threads (a multiple of 64, at least 128), PER queries
 // per thread; s_win: WINDOW values of LDS.  Ends with a barrier: the arrays may be reused at once.
+// (a_out, b_out, xmax_out: a, b and the largest query, for callers that go on from there.)
 template <typename T, int THREADS, int PER, int WINDOW, int MODE>
 __device__ __forceinline__ void exact_windowed_counts(const T* __restrict__ fr, int n, const T (&xv)[PER], T* s_win,
-                                                      int (&cnt_lo)[PER], int (&cnt_up)[PER]) {
+                                                      int (&cnt_lo)[PER], int (&cnt_up)[PER], int& a_out, int& b_out,
+                                                      T& xmax_out) {
   __shared__ T s_mm[2][THREADS / 64];
   __shared__ int s_ab[2];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   T wmin, wmax, xmin, xmax;
   query_range<T, THREADS, PER>(xv, s_mm, wmin, wmax, xmin, xmax);
+  xmax_out = xmax;
   if (wave < 2) {
     const T q = wave == 0 ? xmin : xmax;
     const bool upper = wave == 0 ? MODE == 1 : MODE != 0;
@@ -210,8 +231,9 @@ __device__ __forceinline__ void exact_windowed_counts(const T* __restrict__ fr, 
   }
   __syncthreads();
   const int a = s_ab[0], len = s_ab[1] - a;
-  if (len <= WINDOW) {                         // (uniform; len >= 0: the predicates are nested)
-    stage_window<T, THREADS, WINDOW>(fr, a, len, s_win);
+  a_out = a; b_out = s_ab[1];
+  if (MODE == 2 ? len <= WINDOW : len < WINDOW) {   // (uniform; len >= 0: the predicates are nested)
+    stage_window<T, THREADS, WINDOW>(fr, a, len, s_win, MODE == 2 ? 0 : padded_length(len));
     __syncthreads();
     search_window<T, PER, MODE>(s_win, len, xv, wmin, wmax, cnt_lo, cnt_up);
 #pragma unroll
@@ -224,6 +246,62 @@ __device__ __forceinline__ void exact_windowed_counts(const T* __restrict__ fr, 
     }
   }
   __syncthreads();
+}
+
+template <typename T, int THREADS, int PER, int WINDOW, int MODE>
+__device__ __forceinline__ void exact_windowed_counts(const T* __restrict__ fr, int n, const T (&xv)[PER], T* s_win,
+                                                      int (&cnt_lo)[PER], int (&cnt_up)[PER]) {
+  int a, b;
+  T xmax;
+  exact_windowed_counts<T, THREADS, PER, WINDOW, MODE>(fr, n, xv, s_win, cnt_lo, cnt_up, a, b, xmax);
+}
+
+// ---- a workgroup that takes one block of queries after the other -------------------------------
+// Lower counts (samples of fr below each query) for a workgroup whose blocks of queries follow
+// each other along a curve.  The block before left b = the number of samples below its largest
+// query.  If no query of this block is smaller than that one, every sample before b lies below all of
+// them, so the window may start at b without any search; how far it must reach is guessed from the
+// length of the last one, and the guess is checked against the window's own last sample (nothing
+// beyond a sample that is >= the largest query is counted by any of them).  The window's loads
+// then travel together with the loads of the queries: one round trip per block instead of the
+// three of the 64-ary searches and the one of the staging after them.  A block that does not fit
+// (a smaller query, a window too short) takes the exact path, as does the first.
+template <typename T> struct ChainState {
+  int b = -1;        // samples below the largest query of the block before; < 0: nothing known yet
+  int len = 0;       // length of its stretch
+  T xmax = T();      // its largest query
+};
+
+template <typename T, int THREADS, int PER, int WINDOW>
+__device__ __forceinline__ void chained_lower_counts(const T* __restrict__ fr, int n, const T (&xv)[PER], T* s_win,
+                                                     int (&cnt)[PER], ChainState<T>& st) {
+  __shared__ T s_mm[2][THREADS / 64];
+  __shared__ int s_b;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int unused[PER];
+  if (st.b >= 0) {                                                   // (uniform, as all of st)
+    const int a = st.b;
+    const int len = min(min(WINDOW - 1, n - a), max(THREADS, st.len + (st.len >> 1)));
+    stage_window<T, THREADS, WINDOW>(fr, a, len, s_win, padded_length(len));
+    T wmin, wmax, xmin, xmax;
+    query_range<T, THREADS, PER>(xv, s_mm, wmin, wmax, xmin, xmax);   // (its barrier also puts the window's writes before the reads below)
+    const bool fits = !(xmin < st.xmax) && (a + len >= n || !(s_win[len - 1] < xmax));
+    if (fits) {
+      search_window<T, PER, 0>(s_win, len, xv, wmin, wmax, cnt, unused);
+#pragma unroll
+      for (int e = 0; e < PER; ++e) cnt[e] += a;
+      if (wave == 0) {
+        const int b = a + wave_first_beyond<T, false>(s_win, 0, len, xmax);
+        if (lane == 0) s_b = b;
+      }
+      __syncthreads();
+      st.len = s_b - a; st.b = s_b; st.xmax = xmax;
+      return;      // (s_b is written again only behind the next block's barrier)
+    }
+    __syncthreads();                                                 // the window is staged again below
+  }
+  exact_windowed_counts<T, THREADS, PER, WINDOW, 0>(fr, n, xv, s_win, cnt, unused, st.len, st.b, st.xmax);
+  st.len = st.b - st.len;                                            // (a came back in st.len)
 }
 
 // ---- the same, with the window located in ONE round trip ------------------------------------
@@ -267,8 +345,8 @@ __device__ __forceinline__ void coarse_windowed_counts(const T* __restrict__ fr,
   const int G = coarse_granule<THREADS>(n);
   const int64_t a64 = (int64_t)glo * G, b64 = (int64_t)(ghi + 1) * G;
   const int a = a64 < n ? (int)a64 : n, len = (b64 < n ? (int)b64 : n) - a;
-  if (len <= WINDOW) {                         // (uniform; len >= 0 because ghi >= glo)
-    stage_window<T, THREADS, WINDOW>(fr, a, len, s_win);
+  if (MODE == 2 ? len <= WINDOW : len < WINDOW) {   // (uniform; len >= 0 because ghi >= glo)
+    stage_window<T, THREADS, WINDOW>(fr, a, len, s_win, MODE == 2 ? 0 : padded_length(len));
     __syncthreads();
     search_window<T, PER, MODE>(s_win, len, xv, wmin, wmax, cnt_lo, cnt_up);
 #pragma unroll
@@ -284,7 +362,8 @@ __global__ __launch_bounds__(256) void pinv_kernel(const T* __restrict__ f, int 
                                                    const T* __restrict__ x, int m,
                                                    int32_t* __restrict__ out, int blocks_per_row,
                                                    int mode) {
-  __shared__ T s_win[kSearchWindow];
+  __shared__ T s_buf[kSearchWindow + 1];       // (one entry in front: the search reads entry `count - 1` at a non-negative offset)
+  T* s_win = s_buf + 1;
   const int row = blockIdx.x / blocks_per_row;
   const int base = (blockIdx.x % blocks_per_row) * kSearchPerBlock + (int)threadIdx.x;
   const T* fr = f + (int64_t)row * n;
@@ -355,10 +434,6 @@ __device__ __forceinline__ double dpp_move(double identity, double v) {
 
 template <typename T> __device__ __forceinline__ T vmin(T a, T b) { return b < a ? b : a; }
 
-template <typename T> __device__ __forceinline__ T highest() {
-  if constexpr (std::numeric_limits<T>::has_infinity) return __builtin_huge_val();
-  else return std::numeric_limits<T>::max();
-}
 
 // The two scans of a greedy processing component share one kernel:
 //   MIN = false: running maximum over increasing index (identity: lowest)
@@ -589,7 +664,8 @@ __global__ __launch_bounds__(256) void hdev_kernel(const T* __restrict__ alpha,
                                                    int n, int parts, int trips,
                                                    int32_t* __restrict__ dev_flags, T* __restrict__ out_v) {
   static_assert(kDevPerThread == kSearchPerThread, "the deviation kernels search kSearchPerThread samples per thread");
-  __shared__ T s_win[kSearchWindow];
+  __shared__ T s_buf[kSearchWindow + 1];       // (one entry in front: the search reads entry `count - 1` at a non-negative offset)
+  T* s_win = s_buf + 1;
   __shared__ int32_t red[4];
   __shared__ int32_t unb[4];
   __shared__ T redv[4];
@@ -601,6 +677,7 @@ __global__ __launch_bounds__(256) void hdev_kernel(const T* __restrict__ alpha,
   T vmaxdev = lowest<T>();
   int32_t h = 0;
   bool unbounded = false;
+  ChainState<T> chain;
   for (int trip = 0; trip < trips; ++trip) {
     const int base = first + trip * kDevPerBlock + (int)threadIdx.x;
     if (first + trip * kDevPerBlock >= n) break;                                       // (uniform)
@@ -614,8 +691,8 @@ __global__ __launch_bounds__(256) void hdev_kernel(const T* __restrict__ alpha,
 #pragma unroll
       for (int e = 0; e < kDevPerThread; ++e) vmaxdev = vmax(vmaxdev, (T)(xv[e] - bv[e]));   // (a repeated last sample changes no maximum)
     }
-    int cnt[kSearchPerThread], unused[kSearchPerThread];
-    exact_windowed_counts<T, 256, kSearchPerThread, kSearchWindow, 0>(b, n, xv, s_win, cnt, unused);   // (ends with a barrier)
+    int cnt[kSearchPerThread];
+    chained_lower_counts<T, 256, kSearchPerThread, kSearchWindow>(b, n, xv, s_win, cnt, chain);   // (ends with a barrier)
 #pragma unroll
     for (int e = 0; e < kDevPerThread; ++e) {
       const int d = base + e * 256;

@@ -472,6 +472,45 @@ def test_deviations_long_rows_and_many_rows(rtc, dtype):
     assert np.array_equal(host(rtc.rtc_max_vdev(dev(alpha), dev(beta))), oracle.max_vdev(alpha, beta))
 
 
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_horizontal_deviation_uneven_service(rtc, dtype):
+    """With 64 rows or more of more than 32 blocks of 1024 samples, a workgroup of the horizontal
+    deviation goes from one block of alpha to the next and starts the next stretch of beta where
+    the last one ended, with a length guessed from the last one.  Service curves whose density
+    changes abruptly (plateaus, slow climbs, steep stretches: stretches of a few hundred to more
+    than ten thousand samples per block, so that the guess is too short, or the stretch too long
+    for the window) and an arrival curve that steps back for a while (outside what the bound is
+    used for, but the definition still has a value: a block with smaller queries than the one
+    before it) must all come out as the plain search per sample gives them."""
+    rng = np.random.default_rng(71)
+    distinct, n = 6, 66000
+    inc = np.zeros((distinct, n), np.int64)
+    for b in range(distinct):
+        at = 0
+        while at < n:
+            kind, run = int(rng.integers(0, 4)), int(rng.integers(200, 6000))
+            inc[b, at:at + run] = 0 if kind == 0 else rng.integers(0, (1, 3, 40, 400)[kind], min(run, n - at))
+            at += run
+    beta = np.cumsum(inc, axis=1)
+    beta[:, 0] = 0
+    alpha = np.cumsum(rng.integers(0, 100, (distinct, n)), axis=1)
+    alpha[0] = np.minimum(alpha[0], beta[0, -1])                 # row 0 stays bounded
+    alpha[2, 9000:9500] -= alpha[2, 9000] // 2                   # row 2 steps back for a while
+    alpha[3] = beta[3]                                           # row 3: no delay at all
+    alpha[4] = np.minimum(alpha[4] // 3, beta[4, -1])            # row 4: arrivals far below the service
+    alpha, beta = alpha.astype(dtype), beta.astype(dtype)
+    want_h, fl = oracle.max_hdev(alpha, beta)
+    want_v = oracle.max_vdev(alpha, beta)
+    reps = 11                                                    # 66 rows: 32 workgroups per row, three blocks each
+    alpha, beta = np.tile(alpha, (reps, 1)), np.tile(beta, (reps, 1))
+    say("horizontal deviation, uneven service", dtype, alpha.shape)
+    flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+    assert np.array_equal(host(rtc.rtc_max_hdev(dev(alpha), dev(beta), dev_flags=flags)), np.tile(want_h, reps))
+    assert int(host(flags)[0]) == fl
+    h, v = rtc.rtc_max_deviations(dev(alpha), dev(beta))
+    assert np.array_equal(host(h), np.tile(want_h, reps)) and np.array_equal(host(v), np.tile(want_v, reps))
+
+
 @pytest.mark.parametrize("dtype", [np.int32, np.int64])
 def test_fused_cap_when_every_candidate_is_the_largest_value_of_the_type(rtc, dtype):
     """alpha'^l = min((alpha^l (/) beta^u) (x) beta^l, beta^l) on rows for which every candidate of
