@@ -324,6 +324,37 @@ def test_pseudo_inverse(rtc, dtype):
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
+def test_pseudo_inverse_stretch_lengths(rtc, dtype):
+    """The inverse stages the stretch of f between the answers of a block's smallest and largest
+    query, pads it to one entry short of a power of two and searches it without bounds checks;
+    a stretch as long as the window takes the plain search instead.  Blocks of 1024 queries whose
+    stretch has exactly 0, 1, 2, 3 ... 2046, 2047, 2048, 2049 ... samples (f strictly increasing, the
+    queries spread over [a, a + L]), in both modes, with ties, and with the largest value of the
+    type as a query (it equals the padding)."""
+    n, m = 9000, 1024
+    rng = np.random.default_rng(19)
+    top = np.inf if np.dtype(dtype) == np.float64 else np.iinfo(dtype).max
+    for L in (0, 1, 2, 3, 4, 7, 8, 1022, 1023, 1024, 1025, 2045, 2046, 2047, 2048, 2049, 4000):
+        f = (3 * np.arange(n, dtype=np.int64))[None, :].repeat(2, axis=0)
+        f[1, 5000:] = f[1, 5000]                              # row 1 ends in a plateau
+        a = int(rng.integers(1, n - L - 2))
+        x = np.empty((2, m), np.int64)
+        for b in range(2):
+            q = rng.integers(3 * a, 3 * (a + L) + 1, m)       # values between and on the samples: ties in both modes
+            q[0], q[-1] = 3 * a, 3 * (a + L)
+            x[b] = np.sort(q) if b == 0 else q
+        f, x = f.astype(dtype), x.astype(dtype)
+        for mode in (0, 1):
+            say("pinv stretch", dtype, L, mode)
+            assert np.array_equal(host(rtc.rtc_pseudo_inverse(dev(f), dev(x), mode)), oracle.pseudo_inverse(f, x, mode))
+        x[0, -1] = top                                         # beyond every sample; equal to the padding
+        if np.dtype(dtype) != np.float64:
+            f[0, -1] = top                                     # ... and to the row's last sample
+        for mode in (0, 1):
+            assert np.array_equal(host(rtc.rtc_pseudo_inverse(dev(f), dev(x), mode)), oracle.pseudo_inverse(f, x, mode))
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
 def test_compose(rtc, dtype):
     rng = np.random.default_rng(12)
     for k, n in ((1, 9), (300, 1000), (5000, 70000)):
