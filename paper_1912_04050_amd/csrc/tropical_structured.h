@@ -146,11 +146,25 @@ __global__ __launch_bounds__(kPeriodThreads) void period_kernel(const T* __restr
     (&s_seen[0][0])[k] = 0;
   }
   const int staged = min(run + 2 * pmax, n - 1);      // w[1 .. staged]
-  // (both rows in one unrolled loop: all loads of a thread in flight together)
-#pragma unroll 6
-  for (int k = threadIdx.x; k < nrows * staged; k += kPeriodThreads) {
-    const int which = k >= staged, at = k - which * staged;
-    s_w[which][at] = rows[which][1 + at];
+  {
+    // both rows, every load of a thread issued before the first is stored (a loop of "load, store
+    // to LDS" waits for each load on the spot); an index past the end repeats the last one
+    constexpr int kLoads = (2 * (kPeriodRun + 2 * kPeriodMax) + kPeriodThreads - 1) / kPeriodThreads;
+    const T* const w0 = g + (int64_t)row * stride_g;
+    const T* const w1 = f + (int64_t)row * stride_f;
+    const int count = nrows * staged;
+    T head[kLoads];
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+      const int at = min(k * kPeriodThreads + (int)threadIdx.x, count - 1);
+      head[k] = at >= staged ? w1[1 + at - staged] : w0[1 + at];
+    }
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+      const int at = k * kPeriodThreads + (int)threadIdx.x;
+      if (at < count) (&s_w[0][0])[at >= staged ? (kPeriodRun + 2 * kPeriodMax) + at - staged : at] = head[k];
+    }
   }
   __syncthreads();
   // Screening, one thread per (row, period), from the staged head of the row alone: eight
@@ -175,6 +189,10 @@ __global__ __launch_bounds__(kPeriodThreads) void period_kernel(const T* __restr
     if ((lane & 31) == 0) s_seen[which][(item % pmax64) >> 5] = (lane & 32) ? (uint32_t)(pass >> 32) : (uint32_t)pass;
   }
   __syncthreads();
+  // (The common case, rows without a period: nothing passed -- both rows' sets are 64 words, one
+  // per lane -- and every wavefront leaves here instead of walking empty sets word by word.)
+  static_assert(2 * (kPeriodMax / 32) == 64, "one word of the two rows' sets per lane");
+  if (__ballot((&s_seen[0][0])[lane] != 0u) == 0) return;
   // First test of what passed, in ascending order, one wavefront per period and kWaves at a
   // time: a run of consecutive positions (staircases agree with many wrong periods at scattered
   // ones), three positions spread over the row and the far ends of two residue classes over
@@ -239,6 +257,7 @@ __global__ __launch_bounds__(kPeriodThreads) void period_kernel(const T* __restr
     }
   }
   __syncthreads();
+  if (__ballot((&s_cand[0][0])[lane] != 0u) == 0) return;   // (no survivor: as above)
   // full test of the survivors in ascending order; the first full pass also takes the extrema of
   // both rows over the indices >= 1
   // (target = period_target(batch): periods below it are multiplied up anyway)
